@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Benchmark of the SSD pre-speculation hot path on one MI355X.
+
+One "step" = one whole SSD round on the draft side: the pre-speculation round (glue extend, top-F fan-out,
+K batched branch-decode steps writing the speculation cache) on one HIP stream, the lossless verification
+kernel on a second stream at the same time, then the cache lookup of the realised outcome.  The workload is
+the Llama-3.2-1B-shaped bf16 draft with a 1024-token shared prefix, K=5, F=4 (24 branch rows), greedy, on
+seeded synthetic weights / prefix KV / logits already resident in HBM.
+
+Prints ONE JSON line: whole-job pre-speculated branch-tokens/s, ms per round, the HBM roofline of the dominant
+kernel (the batched branch-decode step) measured with HIP events on its own stream, and the CPU oracle timed on a
+bounded sample of the same workload (a reported baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+WORKLOAD = "1b_p1024_f4"
+WEIGHT_SEED = 2025
+
+
+def algorithmic_bytes_per_decode_step(shape, rnd):
+    """Bytes one batched branch-decode step must move: every weight once, the shared trunk KV once per
+    sequence (not once per branch), the fp32 logits it has to keep, and the branch-private suffix KV."""
+    d, f, V, L = shape.d_model, shape.d_ffn, shape.vocab, shape.n_layers
+    qd, kvd = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    weights = (L * ((qd + 2 * kvd) * d + d * qd + 3 * d * f) + V * d) * 2
+    trunk = rnd.batch * L * (rnd.prefix + rnd.K + 1) * 2 * kvd * 2
+    logits = rnd.rows * V * 4
+    suffix = rnd.rows * L * rnd.K * 2 * kvd * 2
+    return weights + trunk + logits + suffix
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import ssd_inputs as I
+    from paper_2603_03251_amd import binding as B
+
+    wl = I.WORKLOADS[WORKLOAD]
+    shape, r = wl.draft, wl.round
+    K, F, P, nb, V = r.K, r.F, r.prefix, r.batch, shape.vocab
+    dev = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+
+    w = I.make_weights(shape, WEIGHT_SEED)
+    model = B.ssd_model_create(shape, w)
+    ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2)
+    k, v = I.make_prefix_kv(shape, nb, P, wl.seed)
+    to_bf16 = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    B.ssd_ctx_load_trunk(ctx, to_bf16(k), to_bf16(v), P)
+    pending = dev(I.make_pending(shape, nb, K, wl.seed), np.int32)
+    temps = dev(np.full(nb, r.temperature), np.float32)
+    pending_spec = pending[:, 1:].contiguous()            # s_1..s_K, what the verifier checks
+    # the verifier's inputs: target logits over the K+1 positions and the draft logits of the pending speculation
+    zt = dev(I.make_logits(nb * (K + 1), V, wl.seed + 1).reshape(nb, K + 1, V), np.float32)
+    zd = dev(I.make_logits(nb * K, V, wl.seed + 2).reshape(nb, K, V), np.float32)
+    k_out = torch.zeros(nb, dtype=torch.int32, device="cuda")
+    t_out = torch.zeros(nb, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.ssd_verify_workspace_bytes(nb, K), dtype=torch.uint8, device="cuda")
+    hit = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+    branch = torch.zeros(nb, dtype=torch.int32, device="cuda")
+    spec = torch.zeros((nb, K), dtype=torch.int32, device="cuda")
+    s_draft, s_verify = torch.cuda.Stream(), torch.cuda.Stream()
+    verified = torch.cuda.Event()
+    torch.cuda.synchronize()
+
+    def one_round(seed):
+        B.ssd_verify(zt, zd, pending_spec, temps, seed, k_out, t_out, ws, stream=s_verify)
+        verified.record(s_verify)
+        B.ssd_prespeculate(ctx, pending, temps, seed, stream=s_draft)
+        s_draft.wait_event(verified)
+        B.ssd_cache_lookup(ctx, k_out, t_out, hit, branch, spec, stream=s_draft)
+
+    B.ssd_ctx_enable_timing(ctx, True)
+    for i in range(args.warmup):
+        one_round(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_round(1000 + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    # per-segment HIP-event times of the last round + a few extra rounds (the events are per-context)
+    seg = []
+    for i in range(min(args.steps, 10)):
+        one_round(2000 + i)
+        seg.append(B.ssd_ctx_read_timing(ctx, K))
+    torch.cuda.synchronize()
+    seg = np.array(seg)                                   # [rounds][K+2] ms: glue, fan-out, K steps
+    step_ms = float(seg[:, 2:].mean())
+    bytes_step = algorithmic_bytes_per_decode_step(shape, r)
+    achieved = bytes_step / (step_ms * 1e-3) / 1e9
+
+    tokens_per_round = nb * (K + 1) * F * K
+    ms_per_step = elapsed / args.steps * 1e3
+    out = {
+        "metric": "prespeculated_branch_tokens_per_s",
+        "value": tokens_per_round / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "us_per_ssd_round": ms_per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{WORKLOAD}: Llama-3.2-1B-shaped bf16 draft, B={nb}, prefix {P}, K={K}, F={F} "
+                               f"({r.rows} branch rows), lookahead {K}, greedy; verify on a second stream; lookup",
+                   "branch_rows": r.rows, "tokens_per_round": tokens_per_round},
+        "segments_ms": {"glue_extend": float(seg[:, 0].mean()), "fan_out": float(seg[:, 1].mean()),
+                        "branch_decode_step": step_ms, "decode_steps_total": float(seg[:, 2:].sum(axis=1).mean())},
+        "decode_only_branch_tokens_per_s": tokens_per_round / (float(seg[:, 2:].sum(axis=1).mean()) * 1e-3),
+        "roofline": {"kernel": "batched branch-decode step", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": bytes_step, "avg_ms": step_ms},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import ssd_oracle as O
+        om = O.Model.from_weights(shape, w)
+        trunk = O.KV([k[l, 0].astype(np.float64) for l in range(shape.n_layers)],
+                     [v[l, 0].astype(np.float64) for l in range(shape.n_layers)])
+        pend = pending.cpu().numpy()[0]
+        _, _, trunk_glue = O.glue_extend(om, trunk, pend)
+        n_branches = r.rows                        # every branch of one round, one at a time
+        t0 = time.perf_counter()
+        for j in range(n_branches):
+            O.decode_branch(om, trunk_glue, P, j // F, 17 + j, K, 0.0, 0, j)
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        out["cpu_baseline"] = {"value": n_branches * K / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"{n_branches} of {r.rows} branches x {K} tokens, one branch at a time "
+                                         f"(float64 numpy oracle, same weights and prefix), {dt:.1f} s"}
+    print(json.dumps(out))
+    B.ssd_ctx_destroy(ctx)
+    B.ssd_model_destroy(model)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,214 @@
+/* ssd.h -- C ABI of the MI355X (gfx950) library for the draft side of speculative
+ * speculative decoding (SSD / Saguaro).
+ *
+ * What the calls compute is fixed by the paper: Alg. 1 (speculator loop:
+ * predict_verify_outcomes, speculate_for_outcomes, cache lookup), Sec. 2.1
+ * (verification: sequential acceptance, residual distribution, bonus token),
+ * Sec. 4.1.1 (outcome prediction: top-F of the draft logits at each accept length,
+ * without the token sent for verification), the definitions of speculation,
+ * verification outcome and speculation cache (Sec. 2.1, Sec. 3.1), App. B (all
+ * (K+1)F branches decoded together, each seeing the verified trunk and its own
+ * path; the "glue" extend before each round; the once-per-round payload fields)
+ * and App. C (token and cache-element counts).
+ *
+ * General conventions
+ *   - Every function returns SSD_OK (0) or a negative ssd_status.  Nothing throws or
+ *     aborts.  ssd_last_error() returns a thread-local message for the last failure.
+ *   - Pointers named d_* are DEVICE memory, h_* are HOST memory.  Unless a comment says
+ *     otherwise the caller owns them and must keep them alive until `stream` has reached
+ *     the call.  Buffers inside ssd_model / ssd_ctx are owned by the library.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work; none synchronises the host unless stated.
+ *   - Branch row order (part of the contract): row = b (K+1) F + k F + j, with b the
+ *     sequence, k the accept length 0..K and j the candidate rank 0..F-1.
+ *   - Ordering of tokens wherever a maximum or a top-F is taken: larger score first,
+ *     equal scores by smaller token id; NaN ranks below every number.
+ *   - The library allocates device memory only in *_create; the hot calls
+ *     (ssd_prespeculate, ssd_cache_lookup, ssd_ctx_commit, ssd_verify, ssd_top_f,
+ *     ssd_sample) allocate nothing.
+ */
+#ifndef SSD_H_
+#define SSD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SSD_OK = 0,
+  SSD_EINVAL = -1,  /* null pointer, size out of range, shape the kernels do not support */
+  SSD_ESTATE = -2,  /* call order: lookup before any pre-speculation, trunk not loaded, ... */
+  SSD_EHIP = -3,    /* a HIP runtime call failed; message holds hipGetErrorString */
+  SSD_ENOMEM = -4   /* device allocation failed */
+} ssd_status;
+
+enum { SSD_F32 = 0, SSD_BF16 = 1 };
+
+/* Limits of this build. */
+enum { SSD_MAX_F = 16, SSD_MAX_K = 15 };
+
+typedef struct ssd_model ssd_model; /* decoder weights, library-owned device copies */
+typedef struct ssd_ctx ssd_ctx;     /* per-batch state: trunk KV, branch KV, speculation cache */
+
+/* A Llama-style decoder (RMSNorm, rotary embedding pairing (i, i + head_dim/2), grouped-query
+ * attention, SwiGLU), the family of the paper's draft and target models (Sec. 4 "Setup"). */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int32_t dtype;          /* SSD_F32 or SSD_BF16: storage type of weights and KV.  Arithmetic
+                             accumulates in fp32 either way; logits are always fp32. */
+  float rope_theta, rms_eps;
+  int32_t tie_embeddings; /* 1: the LM head is the embedding matrix */
+} ssd_model_config;
+
+/* Weights as the linear layers apply them, row-major [out_features][in_features], elements of
+ * config.dtype (bf16 = the upper 16 bits of the fp32 pattern).  All pointers are DEVICE memory;
+ * the per-layer members are HOST arrays of n_layers device pointers.  ssd_model_create copies
+ * (and re-tiles) everything on `stream`; the caller may free its buffers once that stream has
+ * been synchronised. */
+typedef struct {
+  const void* d_embed;      /* [vocab][d_model] */
+  const void* d_lm_head;    /* [vocab][d_model], NULL when tie_embeddings */
+  const void* d_final_norm; /* [d_model] */
+  const void* const* h_attn_norm; /* [d_model] each */
+  const void* const* h_wq;        /* [n_q_heads*head_dim][d_model] */
+  const void* const* h_wk;        /* [n_kv_heads*head_dim][d_model] */
+  const void* const* h_wv;        /* [n_kv_heads*head_dim][d_model] */
+  const void* const* h_wo;        /* [d_model][n_q_heads*head_dim] */
+  const void* const* h_mlp_norm;  /* [d_model] */
+  const void* const* h_w_gate;    /* [d_ffn][d_model] */
+  const void* const* h_w_up;      /* [d_ffn][d_model] */
+  const void* const* h_w_down;    /* [d_model][d_ffn] */
+} ssd_model_weights;
+
+/* Shape of the pre-speculation round: speculative lookahead K and uniform fan-out F
+ * (Sec. 2.1 Def. "speculation"; Sec. 4.1.1 Def. "fan-out"). */
+typedef struct {
+  int32_t batch;     /* B >= 1 sequences */
+  int32_t K;         /* 1..SSD_MAX_K drafted tokens per speculation = decode steps per branch */
+  int32_t F;         /* 1..SSD_MAX_F bonus-token candidates per accept length */
+  int32_t max_trunk; /* capacity of the trunk KV in positions, per sequence */
+} ssd_round_config;
+
+/* Read-only device views of the context's state, for tests and for the verifier's payload. */
+typedef struct {
+  const int32_t* d_trunk_len;  /* [B] positions currently in the trunk */
+  const int32_t* d_keys;       /* [B][K+1][F] cached bonus tokens (cache keys) */
+  const int32_t* d_tokens;     /* [B][K+1][F][K] speculation per cached outcome */
+  const float* d_logits;       /* [B][K+1][F][K][V] logits each of those tokens was drawn from */
+  const float* d_hidden;       /* [B][K+1][F][K][d_model] final-norm hidden states */
+  const float* d_glue_logits;  /* [B][K+1][V] logits of the glue extend */
+  const float* d_glue_hidden;  /* [B][K+1][d_model] */
+  const void* const* h_trunk_k; /* host array [n_layers] of device [B][max_trunk][Hkv][D] (model dtype) */
+  const void* const* h_trunk_v;
+  int32_t batch, K, F, vocab, d_model, max_trunk;
+} ssd_views;
+
+const char* ssd_last_error(void);
+
+/* ---- set-up (not on the hot path; these allocate) ------------------------------------------ */
+
+int ssd_model_create(const ssd_model_config* cfg, const ssd_model_weights* w, void* stream, ssd_model** out);
+int ssd_model_destroy(ssd_model* m);
+
+/* The context keeps a pointer to `model`; destroy the context first. */
+int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx** out);
+int ssd_ctx_destroy(ssd_ctx* ctx);
+
+/* Trunk := KV of d_tokens[b][0 .. h_lens[b]-1] (row stride `stride` tokens), computed with the same
+ * extend kernels in chunks.  EINVAL if a length exceeds max_trunk - (2K+2). */
+int ssd_ctx_prefill(ssd_ctx* ctx, const int32_t* d_tokens, int32_t stride, const int32_t* h_lens, void* stream);
+/* Trunk := given KV (a synthetic prefix standing in for a prefill).  d_k, d_v:
+ * [n_layers][B][len][n_kv_heads][head_dim] in the model dtype; every sequence gets length `len`. */
+int ssd_ctx_load_trunk(ssd_ctx* ctx, const void* d_k, const void* d_v, int32_t len, void* stream);
+
+/* ---- hot path --------------------------------------------------------------------------------- */
+
+/* One pre-speculation round (Alg. 1: predict_verify_outcomes + speculate_for_outcomes; App. B).
+ *   d_pending      int32 [B][K+1] = {last verified token, s_1..s_K}: the speculation now being verified.
+ *   d_temperature  float [B]; 0 = greedy.  T > 0: each branch token is argmax(logit/T + Gumbel) with
+ *                  noise from the counter-based generator keyed (round_seed, stream 2, row, step, token).
+ * Steps enqueued on `stream`: glue extend of the pending block onto the trunk (KV slots
+ * trunk_len .. trunk_len+K, logits z_1..z_{K+1}); fan-out keys[b][k][:] = top-F of z_{k+1} without
+ * s_{k+1} (nothing excluded at k = K); K batched decode steps over all B(K+1)F rows, row (b,k,j)
+ * starting from keys[b][k][j] at position trunk_len+1+k and seeing trunk[0 .. trunk_len+k] plus its own
+ * tokens; tokens and logits of every step go straight into the speculation cache.
+ * trunk_len itself is not changed (see ssd_ctx_commit).  ESTATE if the trunk is empty or the host's
+ * upper bound of trunk_len + 2K+2 exceeds max_trunk. */
+int ssd_prespeculate(ssd_ctx* ctx, const int32_t* d_pending, const float* d_temperature, uint64_t round_seed,
+                     void* stream);
+
+/* Teacher forcing for parity tests: when set, branch row inputs are taken from the caller instead of
+ * the library's own selection/sampling (outputs are still written as usual).  d_keys [B][K+1][F] feeds
+ * step 0, d_tokens [B][K+1][F][K] entry i-1 feeds step i.  Either may be NULL (not forced). */
+int ssd_ctx_set_forced(ssd_ctx* ctx, const int32_t* d_keys, const int32_t* d_tokens);
+
+/* Look the realised verification outcome up (Alg. 1; payload fields of App. B).
+ *   in : d_accept_len int32 [B] (k in 0..K), d_bonus int32 [B] (t*)
+ *   out: d_hit uint8 [B] (1 = cache hit), d_branch int32 [B] (rank j of the hit, -1 on a miss),
+ *        d_spec_tokens int32 [B][K] (the cached speculation; -1 on a miss),
+ *        d_logits_ptr (optional) const float* [B]: device address of the hit's [K][V] logits, NULL on a miss.
+ * An accept length outside 0..K counts as a miss.  ESTATE before the first ssd_prespeculate. */
+int ssd_cache_lookup(ssd_ctx* ctx, const int32_t* d_accept_len, const int32_t* d_bonus, uint8_t* d_hit,
+                     int32_t* d_branch, int32_t* d_spec_tokens, const float** d_logits_ptr, void* stream);
+
+/* After the outcome (k, t*): trunk_len[b] += k+1 (keeps the glue positions of the last verified token
+ * and the k accepted ones, drops the rest).  Values of d_accept_len are clamped to 0..K. */
+int ssd_ctx_commit(ssd_ctx* ctx, const int32_t* d_accept_len, void* stream);
+
+/* Lossless verification (Sec. 2.1), stateless, meant for a stream of its own.
+ *   d_target_logits float [B][K+1][V]: row i = target distribution of the token after s_1..s_i.
+ *   d_draft_logits  float [B][K][V]:   row i = distribution s_{i+1} was drawn from (may be NULL if every
+ *                                      temperature is 0).
+ *   d_spec_tokens int32 [B][K];  d_temperature float [B] (0 = greedy).
+ * T = 0: accept while argmax(target row i) == s_{i+1}; bonus = argmax of the first mismatching row (row K
+ * if none).  T > 0: p = softmax(target/T), q = softmax(draft/T) in fp64; accept s_{i+1} iff u_i q(s) < p(s)
+ * with u_i from generator stream 0 keyed (seed, b, i, 0); bonus = argmax_t log(max(p_t - q_t, 0)) + g_t at
+ * the first rejected row (residual distribution), or argmax_t log p_t + g_t at row K, g from stream 1 keyed
+ * (seed, b, k, t).  A residual without mass falls back to p.
+ *   out: d_accept_len int32 [B], d_bonus int32 [B].
+ *   d_workspace: device scratch of ssd_verify_workspace_bytes(B, K) bytes.
+ * EINVAL for B < 1, K < 1 or K > SSD_MAX_K, V < 2, null pointers. */
+int ssd_verify(const float* d_target_logits, const float* d_draft_logits, const int32_t* d_spec_tokens,
+               const float* d_temperature, int32_t B, int32_t K, int32_t V, uint64_t seed,
+               int32_t* d_accept_len, int32_t* d_bonus, void* d_workspace, void* stream);
+size_t ssd_verify_workspace_bytes(int32_t B, int32_t K);
+
+/* The selection kernel on caller-provided logits (Sec. 4.1.1).  d_logits float [rows][V] with row stride
+ * `ld` elements; d_exclude int32 [rows] token to skip per row, or -1 (d_exclude may be NULL);
+ * out d_ids int32 [rows][F].  EINVAL if F > SSD_MAX_F or F + 1 > V. */
+int ssd_top_f(const float* d_logits, int64_t ld, const int32_t* d_exclude, int32_t rows, int32_t V, int32_t F,
+              int32_t* d_ids, void* stream);
+
+/* The branch sampler on caller-provided logits: d_out[r] = argmax_t logits[r][t] (T[r] == 0) or
+ * argmax_t logits[r][t]/T[r] + g(seed, stream 2, row_base + r, step, t) in fp64.  d_temperature float [rows]. */
+int ssd_sample(const float* d_logits, int64_t ld, const float* d_temperature, int32_t rows, int32_t V,
+               uint64_t seed, int32_t row_base, int32_t step, int32_t* d_out, void* stream);
+
+/* ---- generic extend (the glue step on its own; also how a target model is run) ------------------ */
+
+/* Forward T tokens per sequence at positions trunk_len+offset .. +T-1 (causal among themselves, seeing
+ * trunk[0 .. trunk_len+offset-1]); writes their KV into those trunk slots and, if d_logits is not NULL,
+ * their logits to d_logits [B][T][V].  trunk_len is unchanged.  T <= K+1. */
+int ssd_ctx_extend(ssd_ctx* ctx, const int32_t* d_tokens, int32_t T, int32_t offset, float* d_logits, void* stream);
+
+/* The host keeps only an upper bound of trunk_len (it grows by K+1 per commit, since accept lengths live on the
+ * device).  This call SYNCHRONISES `stream`, reads the true lengths back and tightens the bound; use it between
+ * rounds of a long generation, never inside the hot path. */
+int ssd_ctx_refresh_bounds(ssd_ctx* ctx, void* stream);
+
+/* Measurement aid.  With timing on, ssd_prespeculate records HIP events on its stream around the glue extend,
+ * the fan-out and each of the K branch-decode steps.  ssd_ctx_read_timing waits for the last event of the most
+ * recent round and returns h_ms[K+2] = {glue, fan-out, step 0 .. step K-1} in milliseconds.  Enabling creates
+ * the events (set-up, not hot path). */
+int ssd_ctx_enable_timing(ssd_ctx* ctx, int32_t on);
+int ssd_ctx_read_timing(ssd_ctx* ctx, float* h_ms, int32_t n);
+
+int ssd_ctx_views(const ssd_ctx* ctx, ssd_views* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSD_H_ */

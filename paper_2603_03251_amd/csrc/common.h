@@ -1,0 +1,137 @@
+// Shared declarations of the HIP library: error plumbing, element types, row descriptors and
+// the launchers each kernel file exports to the round driver.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ssd.h"
+
+namespace ssd {
+
+void set_error(const char* fmt, ...);
+
+#define SSD_HIP(expr)                                                                 \
+  do {                                                                                \
+    hipError_t e_ = (expr);                                                           \
+    if (e_ != hipSuccess) {                                                           \
+      ::ssd::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      return SSD_EHIP;                                                                \
+    }                                                                                 \
+  } while (0)
+
+#define SSD_TRY(expr)            \
+  do {                           \
+    int s_ = (expr);             \
+    if (s_ != SSD_OK) return s_; \
+  } while (0)
+
+#define SSD_CHECK_ARG(cond, ...)      \
+  do {                                \
+    if (!(cond)) {                    \
+      ::ssd::set_error(__VA_ARGS__);  \
+      return SSD_EINVAL;              \
+    }                                 \
+  } while (0)
+
+typedef uint16_t bf16_t;  // bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even; NaN stays NaN
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// One row of a batched forward pass (a branch at some depth, or one token of an extend).
+struct RowDesc {
+  int32_t seq;        // sequence b
+  int32_t pos;        // absolute position of the row's token (rotary angle)
+  int32_t vis;        // number of trunk positions the row sees (for extend rows this includes itself)
+  int32_t suffix_len; // number of private suffix positions the row sees (includes itself); 0 for extend rows
+  int32_t kv_slot;    // where the row's own K/V goes: trunk position (extend) or suffix depth (branch)
+  int32_t is_branch;  // 1: KV goes to the row's private suffix, 0: to the trunk
+};
+
+// Shapes every kernel launcher needs.
+struct Dims {
+  int n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int dtype;
+  float rope_theta, rms_eps;
+  int q_dim() const { return n_q_heads * head_dim; }
+  int kv_dim() const { return n_kv_heads * head_dim; }
+  int qkv_dim() const { return q_dim() + 2 * kv_dim(); }
+};
+
+// ---------------------------------------------------------------- kernels_misc.hip
+// Row descriptors + rotary tables for a branch step / an extend, from device-side trunk lengths.
+int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int K, int F, int step,
+                             int half_dim, float theta, hipStream_t s);
+int launch_setup_extend_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int T, int offset,
+                             int half_dim, float theta, hipStream_t s);
+int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* h, int M, int d, int vocab, hipStream_t s);
+int launch_rmsnorm(int dtype, const float* h, const void* gain, float* xn, float* copy_out, int64_t copy_ld, int M, int d,
+                   float eps, hipStream_t s);
+// Rotary embedding of q and k (fp32 [M][qkv_dim]) + write of q (activation dtype) and of the row's K/V
+// into the trunk or its private suffix.
+int launch_rope_append(int dtype, const float* qkv, const RowDesc* rows, const float* cos_sin, float* q_out,
+                       void* trunk_k, void* trunk_v, void* suffix_k, void* suffix_v, int M, int n_q_heads,
+                       int n_kv_heads, int head_dim, int max_trunk, int suffix_cap, hipStream_t s);
+int launch_gather_step_tokens(int32_t* out, const int32_t* keys, const int32_t* cache_tokens,
+                              const int32_t* forced_keys, const int32_t* forced_tokens, int M, int K, int step,
+                              hipStream_t s);
+int launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
+int launch_commit(int32_t* trunk_len, const int32_t* accept_len, int B, int K, hipStream_t s);
+int launch_lookup(const int32_t* keys, const int32_t* cache_tokens, const float* cache_logits, const int32_t* accept_len,
+                  const int32_t* bonus, uint8_t* hit, int32_t* branch, int32_t* spec, const float** logits_ptr, int B,
+                  int K, int F, int V, hipStream_t s);
+int launch_pending_exclude(int32_t* exclude, const int32_t* pending, int B, int K, hipStream_t s);
+int launch_copy_kv_in(int dtype, void* trunk, const void* src, int B, int len, int max_trunk, int row_elems, hipStream_t s);
+
+// ---------------------------------------------------------------- kernels_gemm.hip
+enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL_ADD = 1, EPI_SWIGLU = 2 };
+// Tiled copy of a [N][Kd] bf16 matrix into the MFMA-operand order the bf16 GEMM streams (see kernels_gemm.hip).
+int launch_tile_weights_bf16(const bf16_t* src, bf16_t* dst, int N, int Kd, hipStream_t s);
+// y[m][n] (+)= sum_k x[m][k] w[n][k].  x: fp32 [M][Kd]; out fp32 (ld elements); for EPI_SWIGLU
+// out[m][n] = silu(x.w^T) * (x.w2^T).
+int launch_gemm(int dtype, int epi, const void* x, const void* w, const void* w2, void* out, int64_t ld, int M, int N,
+                int Kd, hipStream_t s);
+
+// ---------------------------------------------------------------- kernels_attn.hip
+struct AttnArgs {
+  const float* q;        // fp32 [M][Hq][D]
+  const void* trunk_k;   // model dtype [B][max_trunk][Hkv][D]
+  const void* trunk_v;
+  const void* suffix_k;  // model dtype [M][suffix_cap][Hkv][D]
+  const void* suffix_v;
+  float* out;            // fp32 [M][Hq][D]
+  const RowDesc* rows;
+  float* partial;        // scratch for split-KV partial results
+  int M, n_q_heads, n_kv_heads, head_dim, max_trunk, suffix_cap;
+  int rows_per_seq;      // rows of one sequence are consecutive
+  int max_vis;           // host upper bound of any row's visible trunk length (grid sizing only)
+};
+int launch_attention(int dtype, const AttnArgs& a, hipStream_t s);
+size_t attention_partial_bytes(int M, int n_q_heads, int head_dim, int max_trunk);
+
+// ---------------------------------------------------------------- kernels_select.hip
+int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int32_t* ids,
+                 hipStream_t s);
+int launch_sample(const float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int V,
+                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, hipStream_t s);
+int launch_verify(const float* zt, const float* zd, const int32_t* spec, const float* temperature, int B, int K, int V,
+                  uint64_t seed, int32_t* accept_len, int32_t* bonus, void* workspace, hipStream_t s);
+size_t verify_workspace_bytes(int B, int K);
+
+}  // namespace ssd

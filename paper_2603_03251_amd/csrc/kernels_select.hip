@@ -1,0 +1,273 @@
+// Selection kernels: top-F bonus-token candidates per accept length (Sec. 4.1.1), the branch sampler
+// (argmax / Gumbel-max), and lossless verification (Sec. 2.1).  All orderings are (score descending,
+// token id ascending); NaN ranks below every number.
+#include "common.h"
+#include "rng.h"
+
+namespace ssd {
+
+namespace {
+
+constexpr int kSelBlock = 1024;
+constexpr int kSelWaves = kSelBlock / 64;
+
+// 64-bit sort key of (fp32 logit, token id): larger key = better candidate.
+__device__ __forceinline__ uint64_t make_key(float f, int id) {
+  uint32_t hi;
+  if (f != f) hi = 0u;                              // NaN: below -inf
+  else {
+    if (f == 0.f) f = 0.f;                          // -0 and +0 tie
+    uint32_t u = __float_as_uint(f);
+    hi = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  }
+  return ((uint64_t)hi << 32) | (uint32_t)(~(uint32_t)id);
+}
+__device__ __forceinline__ int key_id(uint64_t k) { return (int)(~(uint32_t)k); }
+
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+  for (int o = 32; o > 0; o >>= 1) {
+    uint64_t t = __shfl_xor((unsigned long long)v, o);
+    v = t > v ? t : v;
+  }
+  return v;
+}
+
+// One block per row.  Every thread keeps the best FMAX keys of its strided share in sorted registers; then F
+// rounds of a block-wide maximum over the threads' current heads pick the row's top F in order.
+template <int FMAX>
+__global__ __launch_bounds__(kSelBlock) void top_f_kernel(const float* __restrict__ logits, int64_t ld,
+                                                          const int32_t* __restrict__ exclude, int V, int F,
+                                                          int32_t* __restrict__ ids) {
+  __shared__ uint64_t wave_best[kSelWaves];
+  __shared__ uint64_t round_best;
+  const int row = blockIdx.x;
+  const float* z = logits + (int64_t)row * ld;
+  const int ex = exclude ? exclude[row] : -1;
+  uint64_t best[FMAX];
+#pragma unroll
+  for (int i = 0; i < FMAX; ++i) best[i] = 0ull;    // 0 is below every real key (ids < 2^32-1)
+  for (int t = threadIdx.x; t < V; t += kSelBlock) {
+    if (t == ex) continue;
+    uint64_t k = make_key(z[t], t);
+    if (k > best[FMAX - 1]) {
+      best[FMAX - 1] = k;
+#pragma unroll
+      for (int i = FMAX - 1; i > 0; --i) {
+        if (best[i] > best[i - 1]) { uint64_t tmp = best[i]; best[i] = best[i - 1]; best[i - 1] = tmp; }
+      }
+    }
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int f = 0; f < F; ++f) {
+    uint64_t w = wave_max_u64(best[0]);
+    if (lane == 0) wave_best[wave] = w;
+    __syncthreads();
+    if (wave == 0) {
+      uint64_t v = lane < kSelWaves ? wave_best[lane] : 0ull;
+      v = wave_max_u64(v);
+      if (lane == 0) { round_best = v; ids[(int64_t)row * F + f] = key_id(v); }
+    }
+    __syncthreads();
+    if (best[0] == round_best) {                    // keys are unique: exactly one thread pops
+#pragma unroll
+      for (int i = 0; i < FMAX - 1; ++i) best[i] = best[i + 1];
+      best[FMAX - 1] = 0ull;
+    }
+  }
+}
+
+struct ScoreId {
+  double s;
+  int id;
+};
+__device__ __forceinline__ bool better(const ScoreId& a, const ScoreId& b) {
+  return a.s > b.s || (a.s == b.s && a.id < b.id);
+}
+__device__ __forceinline__ ScoreId block_argmax(ScoreId v, ScoreId* smem) {
+  for (int o = 32; o > 0; o >>= 1) {
+    ScoreId t;
+    t.s = __shfl_xor(v.s, o);
+    t.id = __shfl_xor(v.id, o);
+    if (better(t, v)) v = t;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) smem[wave] = v;
+  __syncthreads();
+  ScoreId r = smem[0];
+  for (int i = 1; i < kSelWaves; ++i)
+    if (better(smem[i], r)) r = smem[i];
+  __syncthreads();
+  return r;
+}
+__device__ __forceinline__ double block_sum_f64(double v, double* smem) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) smem[wave] = v;
+  __syncthreads();
+  double r = 0.0;
+  for (int i = 0; i < kSelWaves; ++i) r += smem[i];
+  __syncthreads();
+  return r;
+}
+__device__ __forceinline__ double score_of(float z) { return z != z ? -INFINITY : (double)z; }
+
+// Branch sampler: greedy argmax or Gumbel-max sample of softmax(z / T), one block per row.
+__global__ __launch_bounds__(kSelBlock) void sample_kernel(const float* __restrict__ logits, int64_t ld,
+                                                           const float* __restrict__ temperature, int rows_per_seq,
+                                                           int V, uint64_t seed, int row_base, int step,
+                                                           int32_t* __restrict__ out, int64_t out_stride) {
+  __shared__ ScoreId smem[kSelWaves];
+  const int row = blockIdx.x;
+  const float* z = logits + (int64_t)row * ld;
+  const double T = (double)temperature[row / rows_per_seq];
+  const uint64_t prefix = draw_prefix(seed, STREAM_DRAFT, (uint64_t)(row_base + row), (uint64_t)step);
+  ScoreId best = {-INFINITY, 0x7fffffff};
+  for (int t = threadIdx.x; t < V; t += kSelBlock) {
+    ScoreId c;
+    c.id = t;
+    c.s = score_of(z[t]);
+    if (T > 0.0) c.s = c.s / T + gumbel_from_u(draw_u(prefix, (uint64_t)t));
+    if (better(c, best)) best = c;
+  }
+  best = block_argmax(best, smem);
+  if (threadIdx.x == 0) out[(int64_t)row * out_stride] = best.id;
+}
+
+struct RowStats {
+  double max;     // max of the row's logits
+  double sum;     // sum exp((z - max)/T), T > 0 only
+  int32_t argmax;
+  int32_t pad;
+};
+
+// Pass 1 of verification: per logit row (K+1 target rows, K draft rows per sequence) the argmax / max and the
+// softmax denominator at the sequence's temperature.
+__global__ __launch_bounds__(kSelBlock) void verify_stats_kernel(const float* __restrict__ zt, const float* __restrict__ zd,
+                                                                 const float* __restrict__ temperature, int K, int V,
+                                                                 RowStats* __restrict__ stats) {
+  __shared__ ScoreId smem[kSelWaves];
+  __shared__ double dsm[kSelWaves];
+  const int b = blockIdx.x / (2 * K + 1), r = blockIdx.x % (2 * K + 1);
+  const double T = zd ? (double)temperature[b] : 0.0;   // without draft logits every sequence is greedy
+  const float* z;
+  if (r <= K) z = zt + ((int64_t)b * (K + 1) + r) * V;
+  else {
+    if (T <= 0.0) return;
+    z = zd + ((int64_t)b * K + (r - K - 1)) * V;
+  }
+  ScoreId best = {-INFINITY, 0x7fffffff};
+  for (int t = threadIdx.x; t < V; t += kSelBlock) {
+    ScoreId c = {score_of(z[t]), t};
+    if (better(c, best)) best = c;
+  }
+  best = block_argmax(best, smem);
+  double sum = 0.0;
+  if (T > 0.0) {
+    for (int t = threadIdx.x; t < V; t += kSelBlock) sum += exp((score_of(z[t]) - best.s) / T);
+    sum = block_sum_f64(sum, dsm);
+  }
+  if (threadIdx.x == 0) {
+    RowStats st;
+    st.max = best.s; st.sum = sum; st.argmax = best.id; st.pad = 0;
+    stats[blockIdx.x] = st;
+  }
+}
+
+// Pass 2: one block per sequence: sequential acceptance (thread 0), then the bonus token at row k.
+__global__ __launch_bounds__(kSelBlock) void verify_decide_kernel(const float* __restrict__ zt, const float* __restrict__ zd,
+                                                                  const int32_t* __restrict__ spec,
+                                                                  const float* __restrict__ temperature, int K, int V,
+                                                                  uint64_t seed, const RowStats* __restrict__ stats,
+                                                                  int32_t* __restrict__ accept_len,
+                                                                  int32_t* __restrict__ bonus) {
+  __shared__ ScoreId smem[kSelWaves];
+  __shared__ double dsm[kSelWaves];
+  __shared__ int k_s;
+  const int b = blockIdx.x;
+  const double T = zd ? (double)temperature[b] : 0.0;
+  const RowStats* st = stats + (int64_t)b * (2 * K + 1);
+  if (threadIdx.x == 0) {
+    int k = K;
+    for (int i = 0; i < K; ++i) {
+      int s = spec[(int64_t)b * K + i];
+      bool ok;
+      if (T <= 0.0) ok = st[i].argmax == s;
+      else if (s < 0 || s >= V) ok = false;
+      else {
+        double p = exp((score_of(zt[((int64_t)b * (K + 1) + i) * V + s]) - st[i].max) / T) / st[i].sum;
+        double q = exp((score_of(zd[((int64_t)b * K + i) * V + s]) - st[K + 1 + i].max) / T) / st[K + 1 + i].sum;
+        double u = draw_u(draw_prefix(seed, STREAM_ACCEPT, (uint64_t)b, (uint64_t)i), 0ull);
+        ok = u * q < p;
+      }
+      if (!ok) { k = i; break; }
+    }
+    k_s = k;
+  }
+  __syncthreads();
+  const int k = k_s;
+  if (T <= 0.0) {
+    if (threadIdx.x == 0) { accept_len[b] = k; bonus[b] = st[k].argmax; }
+    return;
+  }
+  const float* zp = zt + ((int64_t)b * (K + 1) + k) * V;
+  const float* zq = k < K ? zd + ((int64_t)b * K + k) * V : nullptr;
+  const double pmax = st[k].max, psum = st[k].sum;
+  const double qmax = k < K ? st[K + 1 + k].max : 0.0, qsum = k < K ? st[K + 1 + k].sum : 1.0;
+  bool use_residual = false;
+  if (zq) {
+    double mass = 0.0;
+    for (int t = threadIdx.x; t < V; t += kSelBlock) {
+      double p = exp((score_of(zp[t]) - pmax) / T) / psum;
+      double q = exp((score_of(zq[t]) - qmax) / T) / qsum;
+      mass += fmax(p - q, 0.0);
+    }
+    use_residual = block_sum_f64(mass, dsm) > 0.0;
+  }
+  const uint64_t prefix = draw_prefix(seed, STREAM_BONUS, (uint64_t)b, (uint64_t)k);
+  ScoreId best = {-INFINITY, 0x7fffffff};
+  for (int t = threadIdx.x; t < V; t += kSelBlock) {
+    double r = exp((score_of(zp[t]) - pmax) / T) / psum;
+    if (use_residual) r = fmax(r - exp((score_of(zq[t]) - qmax) / T) / qsum, 0.0);
+    ScoreId c;
+    c.id = t;
+    c.s = r > 0.0 ? log(r) + gumbel_from_u(draw_u(prefix, (uint64_t)t)) : -INFINITY;
+    if (better(c, best)) best = c;
+  }
+  best = block_argmax(best, smem);
+  if (threadIdx.x == 0) { accept_len[b] = k; bonus[b] = best.id; }
+}
+
+}  // namespace
+
+int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int32_t* ids,
+                 hipStream_t s) {
+  if (rows <= 0) return SSD_OK;
+  if (F <= 4) top_f_kernel<4><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, ids);
+  else if (F <= 8) top_f_kernel<8><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, ids);
+  else top_f_kernel<16><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, ids);
+  SSD_HIP(hipGetLastError());
+  return SSD_OK;
+}
+
+int launch_sample(const float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int V,
+                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, hipStream_t s) {
+  if (rows <= 0) return SSD_OK;
+  sample_kernel<<<rows, kSelBlock, 0, s>>>(logits, ld, temperature, rows_per_seq, V, seed, row_base, step, out,
+                                           out_stride);
+  SSD_HIP(hipGetLastError());
+  return SSD_OK;
+}
+
+size_t verify_workspace_bytes(int B, int K) { return (size_t)B * (2 * K + 1) * sizeof(RowStats); }
+
+int launch_verify(const float* zt, const float* zd, const int32_t* spec, const float* temperature, int B, int K, int V,
+                  uint64_t seed, int32_t* accept_len, int32_t* bonus, void* workspace, hipStream_t s) {
+  RowStats* stats = (RowStats*)workspace;
+  verify_stats_kernel<<<B * (2 * K + 1), kSelBlock, 0, s>>>(zt, zd, temperature, K, V, stats);
+  SSD_HIP(hipGetLastError());
+  verify_decide_kernel<<<B, kSelBlock, 0, s>>>(zt, zd, spec, temperature, K, V, seed, stats, accept_len, bonus);
+  SSD_HIP(hipGetLastError());
+  return SSD_OK;
+}
+
+}  // namespace ssd

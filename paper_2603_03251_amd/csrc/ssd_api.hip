@@ -1,0 +1,493 @@
+// C ABI and round driver: owns device buffers, validates arguments, enqueues the kernels of one
+// pre-speculation round (glue extend -> fan-out -> K branch-decode steps writing the speculation cache in place).
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+namespace ssd {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
+size_t elem_size(int dtype) { return dtype == SSD_BF16 ? 2 : 4; }
+
+// Device allocations of one object, freed together.
+struct Arena {
+  std::vector<void*> ptrs;
+  int alloc(void** out, size_t bytes) {
+    *out = nullptr;
+    if (bytes == 0) bytes = 16;
+    hipError_t e = hipMalloc(out, bytes);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      set_error("hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+      return SSD_ENOMEM;
+    }
+    ptrs.push_back(*out);
+    return SSD_OK;
+  }
+  void release() {
+    for (void* p : ptrs) (void)hipFree(p);
+    ptrs.clear();
+  }
+};
+
+__global__ void gather_chunk_tokens_kernel(int32_t* out, const int32_t* tokens, int stride, int B, int T, int start) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= B * T) return;
+  int b = idx / T, t = idx % T;
+  int src = start + t;
+  out[idx] = src < stride ? tokens[(int64_t)b * stride + src] : 0;
+}
+
+}  // namespace
+}  // namespace ssd
+
+using namespace ssd;
+
+struct ssd_model {
+  Dims dims;
+  int tie;
+  Arena arena;
+  void* embed = nullptr;       // row-major [V][d]
+  void* lm_head = nullptr;     // GEMM layout (bf16: tile order)
+  void* final_norm = nullptr;
+  struct Layer {
+    void *attn_norm, *wqkv, *wo, *mlp_norm, *w_gate, *w_up, *w_down;
+  };
+  std::vector<Layer> layers;
+};
+
+struct ssd_ctx {
+  const ssd_model* model;
+  int B, K, F, max_trunk;
+  int M;        // branch rows B (K+1) F
+  int max_rows; // rows of the largest batched pass
+  Arena arena;
+  int trunk_ub = 0;   // host upper bound of every trunk_len[b]; 0 = trunk not loaded
+  bool have_cache = false;
+  // state
+  int32_t* trunk_len;
+  std::vector<void*> trunk_k, trunk_v;   // per layer [B][max_trunk][Hkv][D]
+  std::vector<void*> suffix_k, suffix_v; // per layer [M][K][Hkv][D]
+  // speculation cache
+  int32_t* keys;
+  int32_t* tokens;
+  float* logits;
+  float* hidden;
+  float* glue_logits;
+  float* glue_hidden;
+  // scratch of a batched pass
+  RowDesc* rows;
+  float* cos_sin;
+  int32_t* step_tokens;
+  int32_t* exclude;
+  float* h;          // residual stream
+  float* xn;         // all activations between kernels are fp32
+  float* qkv;
+  float* q;
+  float* attn_out;
+  float* act;
+  float* attn_partial;
+  const int32_t* forced_keys = nullptr;
+  const int32_t* forced_tokens = nullptr;
+  // optional per-segment timing of a round: K+3 events (start, glue, fan-out, K steps)
+  std::vector<hipEvent_t> events;
+  bool timing = false;
+};
+
+namespace {
+
+// Weight of a linear layer into the layout the GEMM streams: bf16 -> tile order, fp32 -> row-major copy.
+int put_linear(int dtype, const void* src, void* dst, int N, int Kd, hipStream_t s) {
+  if (dtype == SSD_BF16) return launch_tile_weights_bf16((const bf16_t*)src, (bf16_t*)dst, N, Kd, s);
+  SSD_HIP(hipMemcpyAsync(dst, src, (size_t)N * Kd * 4, hipMemcpyDeviceToDevice, s));
+  return SSD_OK;
+}
+
+int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
+  const Dims& d = m->dims;
+  const size_t es = elem_size(d.dtype);
+  const int qd = d.q_dim(), kvd = d.kv_dim();
+  SSD_TRY(m->arena.alloc(&m->embed, (size_t)d.vocab * d.d_model * es));
+  SSD_HIP(hipMemcpyAsync(m->embed, w->d_embed, (size_t)d.vocab * d.d_model * es, hipMemcpyDeviceToDevice, s));
+  SSD_TRY(m->arena.alloc(&m->final_norm, (size_t)d.d_model * es));
+  SSD_HIP(hipMemcpyAsync(m->final_norm, w->d_final_norm, (size_t)d.d_model * es, hipMemcpyDeviceToDevice, s));
+  const void* head_src = m->tie ? w->d_embed : w->d_lm_head;
+  if (d.dtype == SSD_F32 && m->tie) m->lm_head = m->embed;
+  else {
+    SSD_TRY(m->arena.alloc(&m->lm_head, (size_t)d.vocab * d.d_model * es));
+    SSD_TRY(put_linear(d.dtype, head_src, m->lm_head, d.vocab, d.d_model, s));
+  }
+  m->layers.resize(d.n_layers);
+  for (int l = 0; l < d.n_layers; ++l) {
+    ssd_model::Layer& L = m->layers[l];
+    SSD_TRY(m->arena.alloc(&L.attn_norm, (size_t)d.d_model * es));
+    SSD_TRY(m->arena.alloc(&L.mlp_norm, (size_t)d.d_model * es));
+    SSD_HIP(hipMemcpyAsync(L.attn_norm, w->h_attn_norm[l], (size_t)d.d_model * es, hipMemcpyDeviceToDevice, s));
+    SSD_HIP(hipMemcpyAsync(L.mlp_norm, w->h_mlp_norm[l], (size_t)d.d_model * es, hipMemcpyDeviceToDevice, s));
+    SSD_TRY(m->arena.alloc(&L.wqkv, (size_t)d.qkv_dim() * d.d_model * es));
+    char* qkv = (char*)L.wqkv;
+    SSD_TRY(put_linear(d.dtype, w->h_wq[l], qkv, qd, d.d_model, s));
+    SSD_TRY(put_linear(d.dtype, w->h_wk[l], qkv + (size_t)qd * d.d_model * es, kvd, d.d_model, s));
+    SSD_TRY(put_linear(d.dtype, w->h_wv[l], qkv + (size_t)(qd + kvd) * d.d_model * es, kvd, d.d_model, s));
+    SSD_TRY(m->arena.alloc(&L.wo, (size_t)d.d_model * qd * es));
+    SSD_TRY(put_linear(d.dtype, w->h_wo[l], L.wo, d.d_model, qd, s));
+    SSD_TRY(m->arena.alloc(&L.w_gate, (size_t)d.d_ffn * d.d_model * es));
+    SSD_TRY(put_linear(d.dtype, w->h_w_gate[l], L.w_gate, d.d_ffn, d.d_model, s));
+    SSD_TRY(m->arena.alloc(&L.w_up, (size_t)d.d_ffn * d.d_model * es));
+    SSD_TRY(put_linear(d.dtype, w->h_w_up[l], L.w_up, d.d_ffn, d.d_model, s));
+    SSD_TRY(m->arena.alloc(&L.w_down, (size_t)d.d_model * d.d_ffn * es));
+    SSD_TRY(put_linear(d.dtype, w->h_w_down[l], L.w_down, d.d_model, d.d_ffn, s));
+  }
+  return SSD_OK;
+}
+
+// One batched pass of the decoder over `M` rows whose descriptors and rotary tables are already in ctx->rows /
+// ctx->cos_sin.  Logits (fp32, row stride logits_ld) and final-norm hidden states are optional.
+int forward_rows(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int max_vis, float* logits,
+                 int64_t logits_ld, float* hidden, int64_t hidden_ld, hipStream_t s) {
+  const ssd_model* m = c->model;
+  const Dims& d = m->dims;
+  const int dt = d.dtype;
+  SSD_TRY(launch_embed(dt, m->embed, tokens, c->h, M, d.d_model, d.vocab, s));
+  for (int l = 0; l < d.n_layers; ++l) {
+    const ssd_model::Layer& L = m->layers[l];
+    SSD_TRY(launch_rmsnorm(dt, c->h, L.attn_norm, c->xn, nullptr, 0, M, d.d_model, d.rms_eps, s));
+    SSD_TRY(launch_gemm(dt, EPI_STORE_F32, c->xn, L.wqkv, nullptr, c->qkv, d.qkv_dim(), M, d.qkv_dim(), d.d_model, s));
+    SSD_TRY(launch_rope_append(dt, c->qkv, c->rows, c->cos_sin, c->q, c->trunk_k[l], c->trunk_v[l], c->suffix_k[l],
+                               c->suffix_v[l], M, d.n_q_heads, d.n_kv_heads, d.head_dim, c->max_trunk, c->K, s));
+    AttnArgs a;
+    a.q = c->q; a.trunk_k = c->trunk_k[l]; a.trunk_v = c->trunk_v[l]; a.suffix_k = c->suffix_k[l];
+    a.suffix_v = c->suffix_v[l]; a.out = c->attn_out; a.rows = c->rows; a.partial = c->attn_partial; a.M = M;
+    a.n_q_heads = d.n_q_heads; a.n_kv_heads = d.n_kv_heads; a.head_dim = d.head_dim; a.max_trunk = c->max_trunk;
+    a.suffix_cap = c->K; a.rows_per_seq = rows_per_seq; a.max_vis = max_vis;
+    SSD_TRY(launch_attention(dt, a, s));
+    SSD_TRY(launch_gemm(dt, EPI_RESIDUAL_ADD, c->attn_out, L.wo, nullptr, c->h, d.d_model, M, d.d_model, d.q_dim(), s));
+    SSD_TRY(launch_rmsnorm(dt, c->h, L.mlp_norm, c->xn, nullptr, 0, M, d.d_model, d.rms_eps, s));
+    SSD_TRY(launch_gemm(dt, EPI_SWIGLU, c->xn, L.w_gate, L.w_up, c->act, d.d_ffn, M, d.d_ffn, d.d_model, s));
+    SSD_TRY(launch_gemm(dt, EPI_RESIDUAL_ADD, c->act, L.w_down, nullptr, c->h, d.d_model, M, d.d_model, d.d_ffn, s));
+  }
+  if (logits || hidden) {
+    SSD_TRY(launch_rmsnorm(dt, c->h, m->final_norm, c->xn, hidden, hidden_ld, M, d.d_model, d.rms_eps, s));
+    if (logits) SSD_TRY(launch_gemm(dt, EPI_STORE_F32, c->xn, m->lm_head, nullptr, logits, logits_ld, M, d.vocab,
+                                    d.d_model, s));
+  }
+  return SSD_OK;
+}
+
+int extend_rows(ssd_ctx* c, const int32_t* tokens, int T, int offset, float* logits, float* hidden, hipStream_t s) {
+  const Dims& d = c->model->dims;
+  SSD_TRY(launch_setup_extend_rows(c->rows, c->cos_sin, c->trunk_len, c->B, T, offset, d.head_dim / 2, d.rope_theta, s));
+  return forward_rows(c, c->B * T, tokens, T, c->trunk_ub + offset + T, logits, d.vocab, hidden, d.d_model, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ssd_last_error(void) { return g_error; }
+
+int ssd_model_create(const ssd_model_config* cfg, const ssd_model_weights* w, void* stream, ssd_model** out) {
+  SSD_CHECK_ARG(cfg && w && out, "ssd_model_create: null argument");
+  *out = nullptr;
+  SSD_CHECK_ARG(cfg->dtype == SSD_F32 || cfg->dtype == SSD_BF16, "dtype %d unknown", cfg->dtype);
+  SSD_CHECK_ARG(cfg->n_layers >= 1 && cfg->d_model >= 1 && cfg->n_q_heads >= 1 && cfg->n_kv_heads >= 1 &&
+                    cfg->d_ffn >= 1 && cfg->vocab >= 2,
+                "model sizes must be positive (vocab >= 2)");
+  SSD_CHECK_ARG(cfg->head_dim == 64 || cfg->head_dim == 128, "head_dim %d not supported (64 or 128)", cfg->head_dim);
+  SSD_CHECK_ARG(cfg->n_q_heads % cfg->n_kv_heads == 0, "n_q_heads must be a multiple of n_kv_heads");
+  SSD_CHECK_ARG(cfg->d_model % 4 == 0 && cfg->d_ffn % 4 == 0, "d_model and d_ffn must be multiples of 4");
+  SSD_CHECK_ARG(w->d_embed && w->d_final_norm && (cfg->tie_embeddings || w->d_lm_head), "null weight pointer");
+  SSD_CHECK_ARG(w->h_attn_norm && w->h_wq && w->h_wk && w->h_wv && w->h_wo && w->h_mlp_norm && w->h_w_gate &&
+                    w->h_w_up && w->h_w_down,
+                "null per-layer pointer table");
+  for (int l = 0; l < cfg->n_layers; ++l)
+    SSD_CHECK_ARG(w->h_attn_norm[l] && w->h_wq[l] && w->h_wk[l] && w->h_wv[l] && w->h_wo[l] && w->h_mlp_norm[l] &&
+                      w->h_w_gate[l] && w->h_w_up[l] && w->h_w_down[l],
+                  "null weight pointer in layer %d", l);
+  ssd_model* m = new (std::nothrow) ssd_model();
+  if (!m) { set_error("out of host memory"); return SSD_ENOMEM; }
+  m->dims.n_layers = cfg->n_layers; m->dims.d_model = cfg->d_model; m->dims.n_q_heads = cfg->n_q_heads;
+  m->dims.n_kv_heads = cfg->n_kv_heads; m->dims.head_dim = cfg->head_dim; m->dims.d_ffn = cfg->d_ffn;
+  m->dims.vocab = cfg->vocab; m->dims.dtype = cfg->dtype; m->dims.rope_theta = cfg->rope_theta;
+  m->dims.rms_eps = cfg->rms_eps;
+  m->tie = cfg->tie_embeddings ? 1 : 0;
+  int st = build_model(m, w, (hipStream_t)stream);
+  if (st != SSD_OK) { m->arena.release(); delete m; return st; }
+  *out = m;
+  return SSD_OK;
+}
+
+int ssd_model_destroy(ssd_model* m) {
+  if (!m) return SSD_OK;
+  m->arena.release();
+  delete m;
+  return SSD_OK;
+}
+
+int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx** out) {
+  SSD_CHECK_ARG(model && cfg && out, "ssd_ctx_create: null argument");
+  *out = nullptr;
+  SSD_CHECK_ARG(cfg->batch >= 1, "batch must be >= 1");
+  SSD_CHECK_ARG(cfg->K >= 1 && cfg->K <= SSD_MAX_K, "K must be in 1..%d", SSD_MAX_K);
+  SSD_CHECK_ARG(cfg->F >= 1 && cfg->F <= SSD_MAX_F, "F must be in 1..%d", SSD_MAX_F);
+  SSD_CHECK_ARG(cfg->F + 1 <= model->dims.vocab, "F + 1 must not exceed the vocabulary");
+  SSD_CHECK_ARG(cfg->max_trunk >= 2 * cfg->K + 3, "max_trunk must be at least 2K+3");
+  SSD_CHECK_ARG((int64_t)cfg->batch * (cfg->K + 1) * cfg->F <= (1 << 20), "too many branch rows");
+  ssd_ctx* c = new (std::nothrow) ssd_ctx();
+  if (!c) { set_error("out of host memory"); return SSD_ENOMEM; }
+  const Dims& d = model->dims;
+  c->model = model; c->B = cfg->batch; c->K = cfg->K; c->F = cfg->F; c->max_trunk = cfg->max_trunk;
+  c->M = c->B * (c->K + 1) * c->F;
+  c->max_rows = c->M > c->B * (c->K + 1) ? c->M : c->B * (c->K + 1);
+  const size_t es = elem_size(d.dtype);
+  const size_t kvd = (size_t)d.kv_dim();
+  const int R = c->max_rows;
+  int st = SSD_OK;
+  auto A = [&](void** p, size_t bytes) { if (st == SSD_OK) st = c->arena.alloc(p, bytes); };
+  A((void**)&c->trunk_len, sizeof(int32_t) * c->B);
+  c->trunk_k.resize(d.n_layers); c->trunk_v.resize(d.n_layers);
+  c->suffix_k.resize(d.n_layers); c->suffix_v.resize(d.n_layers);
+  for (int l = 0; l < d.n_layers; ++l) {
+    A(&c->trunk_k[l], (size_t)c->B * c->max_trunk * kvd * es);
+    A(&c->trunk_v[l], (size_t)c->B * c->max_trunk * kvd * es);
+    A(&c->suffix_k[l], (size_t)c->M * c->K * kvd * es);
+    A(&c->suffix_v[l], (size_t)c->M * c->K * kvd * es);
+  }
+  A((void**)&c->keys, sizeof(int32_t) * c->M);
+  A((void**)&c->tokens, sizeof(int32_t) * c->M * c->K);
+  A((void**)&c->logits, sizeof(float) * (size_t)c->M * c->K * d.vocab);
+  A((void**)&c->hidden, sizeof(float) * (size_t)c->M * c->K * d.d_model);
+  A((void**)&c->glue_logits, sizeof(float) * (size_t)c->B * (c->K + 1) * d.vocab);
+  A((void**)&c->glue_hidden, sizeof(float) * (size_t)c->B * (c->K + 1) * d.d_model);
+  A((void**)&c->rows, sizeof(RowDesc) * R);
+  A((void**)&c->cos_sin, sizeof(float) * (size_t)R * d.head_dim);
+  A((void**)&c->step_tokens, sizeof(int32_t) * R);
+  A((void**)&c->exclude, sizeof(int32_t) * c->B * (c->K + 1));
+  A((void**)&c->h, sizeof(float) * (size_t)R * d.d_model);
+  A((void**)&c->xn, sizeof(float) * (size_t)R * d.d_model);
+  A((void**)&c->qkv, sizeof(float) * (size_t)R * d.qkv_dim());
+  A((void**)&c->q, sizeof(float) * (size_t)R * d.q_dim());
+  A((void**)&c->attn_out, sizeof(float) * (size_t)R * d.q_dim());
+  A((void**)&c->act, sizeof(float) * (size_t)R * d.d_ffn);
+  A((void**)&c->attn_partial, attention_partial_bytes(R, d.n_q_heads, d.head_dim, c->max_trunk));
+  if (st == SSD_OK) {
+    hipError_t e = hipMemset(c->trunk_len, 0, sizeof(int32_t) * c->B);
+    if (e != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(e)); st = SSD_EHIP; }
+  }
+  if (st != SSD_OK) { c->arena.release(); delete c; return st; }
+  *out = c;
+  return SSD_OK;
+}
+
+int ssd_ctx_destroy(ssd_ctx* c) {
+  if (!c) return SSD_OK;
+  for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+  c->arena.release();
+  delete c;
+  return SSD_OK;
+}
+
+int ssd_ctx_prefill(ssd_ctx* c, const int32_t* d_tokens, int32_t stride, const int32_t* h_lens, void* stream) {
+  SSD_CHECK_ARG(c && d_tokens && h_lens, "ssd_ctx_prefill: null argument");
+  hipStream_t s = (hipStream_t)stream;
+  int max_len = 0;
+  for (int b = 0; b < c->B; ++b) {
+    SSD_CHECK_ARG(h_lens[b] >= 1 && h_lens[b] <= stride, "prefill length %d of sequence %d out of range", h_lens[b], b);
+    max_len = h_lens[b] > max_len ? h_lens[b] : max_len;
+  }
+  SSD_CHECK_ARG(max_len + 2 * c->K + 2 <= c->max_trunk, "prefill of %d tokens does not leave room for a round (max_trunk %d)",
+                max_len, c->max_trunk);
+  SSD_TRY(launch_fill_i32(c->trunk_len, 0, c->B, s));
+  const int T = c->K + 1;
+  c->trunk_ub = 0;
+  for (int start = 0; start < max_len; start += T) {
+    int n = c->B * T;
+    gather_chunk_tokens_kernel<<<(n + 255) / 256, 256, 0, s>>>(c->step_tokens, d_tokens, stride, c->B, T, start);
+    SSD_HIP(hipGetLastError());
+    SSD_TRY(extend_rows(c, c->step_tokens, T, start, nullptr, nullptr, s));
+  }
+  SSD_HIP(hipMemcpyAsync(c->trunk_len, h_lens, sizeof(int32_t) * c->B, hipMemcpyHostToDevice, s));
+  SSD_HIP(hipStreamSynchronize(s));   // h_lens is caller-owned pageable memory
+  c->trunk_ub = max_len;
+  c->have_cache = false;
+  return SSD_OK;
+}
+
+int ssd_ctx_load_trunk(ssd_ctx* c, const void* d_k, const void* d_v, int32_t len, void* stream) {
+  SSD_CHECK_ARG(c && d_k && d_v, "ssd_ctx_load_trunk: null argument");
+  SSD_CHECK_ARG(len >= 1 && len + 2 * c->K + 2 <= c->max_trunk, "trunk length %d does not fit max_trunk %d with room for a round",
+                len, c->max_trunk);
+  hipStream_t s = (hipStream_t)stream;
+  const Dims& d = c->model->dims;
+  const size_t es = elem_size(d.dtype);
+  const size_t per_layer = (size_t)c->B * len * d.kv_dim() * es;
+  for (int l = 0; l < d.n_layers; ++l) {
+    SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_k[l], (const char*)d_k + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
+    SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_v[l], (const char*)d_v + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
+  }
+  SSD_TRY(launch_fill_i32(c->trunk_len, len, c->B, s));
+  c->trunk_ub = len;
+  c->have_cache = false;
+  return SSD_OK;
+}
+
+int ssd_ctx_set_forced(ssd_ctx* c, const int32_t* d_keys, const int32_t* d_tokens) {
+  SSD_CHECK_ARG(c, "ssd_ctx_set_forced: null context");
+  c->forced_keys = d_keys;
+  c->forced_tokens = d_tokens;
+  return SSD_OK;
+}
+
+int ssd_ctx_extend(ssd_ctx* c, const int32_t* d_tokens, int32_t T, int32_t offset, float* d_logits, void* stream) {
+  SSD_CHECK_ARG(c && d_tokens, "ssd_ctx_extend: null argument");
+  SSD_CHECK_ARG(T >= 1 && T <= c->K + 1, "extend of %d tokens: must be in 1..K+1", T);
+  SSD_CHECK_ARG(offset >= 0, "negative offset");
+  if (c->trunk_ub + offset + T > c->max_trunk) {
+    set_error("extend would pass max_trunk (%d + %d + %d > %d)", c->trunk_ub, offset, T, c->max_trunk);
+    return SSD_ESTATE;
+  }
+  return extend_rows(c, d_tokens, T, offset, d_logits, nullptr, (hipStream_t)stream);
+}
+
+int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temperature, uint64_t round_seed, void* stream) {
+  SSD_CHECK_ARG(c && d_pending && d_temperature, "ssd_prespeculate: null argument");
+  if (c->trunk_ub < 1) { set_error("ssd_prespeculate: the trunk is empty (prefill or load it first)"); return SSD_ESTATE; }
+  if (c->trunk_ub + 2 * c->K + 2 > c->max_trunk) {
+    set_error("ssd_prespeculate: trunk bound %d + 2K+2 exceeds max_trunk %d", c->trunk_ub, c->max_trunk);
+    return SSD_ESTATE;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  const Dims& d = c->model->dims;
+  const int K = c->K, F = c->F, B = c->B, M = c->M, V = d.vocab;
+  int ev = 0;
+  auto mark = [&]() -> int {
+    if (c->timing) SSD_HIP(hipEventRecord(c->events[ev++], s));
+    return SSD_OK;
+  };
+  SSD_TRY(mark());
+  // a0: glue extend of {last verified token, s_1..s_K}
+  SSD_TRY(extend_rows(c, d_pending, K + 1, 0, c->glue_logits, c->glue_hidden, s));
+  SSD_TRY(mark());
+  // a1: fan-out
+  SSD_TRY(launch_pending_exclude(c->exclude, d_pending, B, K, s));
+  SSD_TRY(launch_top_f(c->glue_logits, V, c->exclude, B * (K + 1), V, F, c->keys, s));
+  SSD_TRY(mark());
+  // a2/a3: K batched branch-decode steps; logits and tokens land in the cache directly
+  for (int i = 0; i < K; ++i) {
+    SSD_TRY(launch_gather_step_tokens(c->step_tokens, c->keys, c->tokens, c->forced_keys, c->forced_tokens, M, K, i, s));
+    SSD_TRY(launch_setup_branch_rows(c->rows, c->cos_sin, c->trunk_len, B, K, F, i, d.head_dim / 2, d.rope_theta, s));
+    SSD_TRY(forward_rows(c, M, c->step_tokens, (K + 1) * F, c->trunk_ub + K + 1, c->logits + (size_t)i * V, (int64_t)K * V,
+                         c->hidden + (size_t)i * d.d_model, (int64_t)K * d.d_model, s));
+    SSD_TRY(launch_sample(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, (K + 1) * F, M, V, round_seed, 0, i,
+                          c->tokens + i, K, s));
+    SSD_TRY(mark());
+  }
+  c->have_cache = true;
+  return SSD_OK;
+}
+
+int ssd_cache_lookup(ssd_ctx* c, const int32_t* d_accept_len, const int32_t* d_bonus, uint8_t* d_hit, int32_t* d_branch,
+                     int32_t* d_spec_tokens, const float** d_logits_ptr, void* stream) {
+  SSD_CHECK_ARG(c && d_accept_len && d_bonus && d_hit && d_branch && d_spec_tokens, "ssd_cache_lookup: null argument");
+  if (!c->have_cache) { set_error("ssd_cache_lookup before any ssd_prespeculate"); return SSD_ESTATE; }
+  return launch_lookup(c->keys, c->tokens, c->logits, d_accept_len, d_bonus, d_hit, d_branch, d_spec_tokens, d_logits_ptr,
+                       c->B, c->K, c->F, c->model->dims.vocab, (hipStream_t)stream);
+}
+
+int ssd_ctx_commit(ssd_ctx* c, const int32_t* d_accept_len, void* stream) {
+  SSD_CHECK_ARG(c && d_accept_len, "ssd_ctx_commit: null argument");
+  if (c->trunk_ub < 1) { set_error("ssd_ctx_commit: the trunk is empty"); return SSD_ESTATE; }
+  SSD_TRY(launch_commit(c->trunk_len, d_accept_len, c->B, c->K, (hipStream_t)stream));
+  c->trunk_ub += c->K + 1;
+  return SSD_OK;
+}
+
+int ssd_ctx_refresh_bounds(ssd_ctx* c, void* stream) {
+  SSD_CHECK_ARG(c, "ssd_ctx_refresh_bounds: null context");
+  std::vector<int32_t> lens(c->B);
+  SSD_HIP(hipMemcpyAsync(lens.data(), c->trunk_len, sizeof(int32_t) * c->B, hipMemcpyDeviceToHost, (hipStream_t)stream));
+  SSD_HIP(hipStreamSynchronize((hipStream_t)stream));
+  int ub = 0;
+  for (int v : lens) ub = v > ub ? v : ub;
+  c->trunk_ub = ub;
+  return SSD_OK;
+}
+
+int ssd_ctx_enable_timing(ssd_ctx* c, int32_t on) {
+  SSD_CHECK_ARG(c, "ssd_ctx_enable_timing: null context");
+  if (on && c->events.empty()) {
+    for (int i = 0; i < c->K + 3; ++i) {
+      hipEvent_t e;
+      SSD_HIP(hipEventCreate(&e));
+      c->events.push_back(e);
+    }
+  }
+  c->timing = on != 0;
+  return SSD_OK;
+}
+
+int ssd_ctx_read_timing(ssd_ctx* c, float* h_ms, int32_t n) {
+  SSD_CHECK_ARG(c && h_ms, "ssd_ctx_read_timing: null argument");
+  SSD_CHECK_ARG(n == c->K + 2, "ssd_ctx_read_timing: n must be K+2");
+  if (!c->timing || !c->have_cache) { set_error("ssd_ctx_read_timing: no timed round has run"); return SSD_ESTATE; }
+  SSD_HIP(hipEventSynchronize(c->events[c->K + 2]));
+  for (int i = 0; i < n; ++i) SSD_HIP(hipEventElapsedTime(&h_ms[i], c->events[i], c->events[i + 1]));
+  return SSD_OK;
+}
+
+size_t ssd_verify_workspace_bytes(int32_t B, int32_t K) {
+  if (B < 1 || K < 1) return 0;
+  return verify_workspace_bytes(B, K);
+}
+
+int ssd_verify(const float* d_target_logits, const float* d_draft_logits, const int32_t* d_spec_tokens,
+               const float* d_temperature, int32_t B, int32_t K, int32_t V, uint64_t seed, int32_t* d_accept_len,
+               int32_t* d_bonus, void* d_workspace, void* stream) {
+  SSD_CHECK_ARG(d_target_logits && d_spec_tokens && d_temperature && d_accept_len && d_bonus && d_workspace,
+                "ssd_verify: null argument");
+  SSD_CHECK_ARG(B >= 1 && K >= 1 && K <= SSD_MAX_K && V >= 2, "ssd_verify: B >= 1, 1 <= K <= %d, V >= 2 required", SSD_MAX_K);
+  return launch_verify(d_target_logits, d_draft_logits, d_spec_tokens, d_temperature, B, K, V, seed, d_accept_len, d_bonus,
+                       d_workspace, (hipStream_t)stream);
+}
+
+int ssd_top_f(const float* d_logits, int64_t ld, const int32_t* d_exclude, int32_t rows, int32_t V, int32_t F,
+              int32_t* d_ids, void* stream) {
+  SSD_CHECK_ARG(d_logits && d_ids, "ssd_top_f: null argument");
+  SSD_CHECK_ARG(rows >= 0 && V >= 2 && ld >= V, "ssd_top_f: rows >= 0, V >= 2, ld >= V required");
+  SSD_CHECK_ARG(F >= 1 && F <= SSD_MAX_F && F + 1 <= V, "ssd_top_f: F must be in 1..%d and F + 1 <= V", SSD_MAX_F);
+  return launch_top_f(d_logits, ld, d_exclude, rows, V, F, d_ids, (hipStream_t)stream);
+}
+
+int ssd_sample(const float* d_logits, int64_t ld, const float* d_temperature, int32_t rows, int32_t V, uint64_t seed,
+               int32_t row_base, int32_t step, int32_t* d_out, void* stream) {
+  SSD_CHECK_ARG(d_logits && d_temperature && d_out, "ssd_sample: null argument");
+  SSD_CHECK_ARG(rows >= 0 && V >= 2 && ld >= V, "ssd_sample: rows >= 0, V >= 2, ld >= V required");
+  return launch_sample(d_logits, ld, d_temperature, 1, rows, V, seed, row_base, step, d_out, 1, (hipStream_t)stream);
+}
+
+int ssd_ctx_views(const ssd_ctx* c, ssd_views* out) {
+  SSD_CHECK_ARG(c && out, "ssd_ctx_views: null argument");
+  out->d_trunk_len = c->trunk_len; out->d_keys = c->keys; out->d_tokens = c->tokens; out->d_logits = c->logits;
+  out->d_hidden = c->hidden; out->d_glue_logits = c->glue_logits; out->d_glue_hidden = c->glue_hidden;
+  out->h_trunk_k = (const void* const*)c->trunk_k.data(); out->h_trunk_v = (const void* const*)c->trunk_v.data();
+  out->batch = c->B; out->K = c->K; out->F = c->F; out->vocab = c->model->dims.vocab; out->d_model = c->model->dims.d_model;
+  out->max_trunk = c->max_trunk;
+  return SSD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,118 @@
+"""Parity at the full sizes of the 1B-shaped workloads, in the launch configuration bench.py times.
+
+The oracle cannot decode every branch of these rounds in seconds, so it computes the glue extend of a sample
+of sequences and a sample of branches (one at a time, as always); the GPU runs the whole round, teacher-forced
+on the sampled branches, and is compared on exactly those outputs.  Selection is compared bit-exactly on the
+oracle's logits."""
+import numpy as np
+import pytest
+import torch
+
+import ssd_inputs as I
+from oracle import ssd_oracle as O
+from tests.gpu_util import TOL, dev_f32, dev_i32, kv_to_device, oracle_trunk_from_arrays, row_rel_err
+
+pytestmark = pytest.mark.gpu
+
+WEIGHT_SEED = 2025
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_03251_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def draft_1b(B):
+    shape = I.LLAMA_1B
+    w = I.make_weights(shape, WEIGHT_SEED)
+    model = B.ssd_model_create(shape, w)
+    om = O.Model.from_weights(shape, w)
+    del w
+    yield shape, model, om
+    B.ssd_model_destroy(model)
+
+
+@pytest.mark.parametrize("name,seqs,rows", [
+    ("1b_p1024_f4", [0], [0, 9, 23]),            # (k=0,j=0), (k=2,j=1), (k=5,j=3)
+    ("1b_p8192_f8_t1", [0], [5, 47]),            # temperature 1.0: Gumbel sampling inside the round
+    ("1b_b16_p2048_f4", [0, 11], [2, 21]),       # 384 branch rows; two of the 16 sequences sampled
+])
+def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows):
+    shape, model, om = draft_1b
+    wl = I.WORKLOADS[name]
+    r = wl.round
+    K, F, P, nb, T = r.K, r.F, r.prefix, r.batch, r.temperature
+    tol = TOL["bf16"]
+    print(f"[case] {name}: B={nb} P={P} K={K} F={F} T={T} sampled seqs {seqs} rows {rows}", flush=True)
+    k, v = I.make_prefix_kv(shape, nb, P, wl.seed)
+    ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2)
+    try:
+        B.ssd_ctx_load_trunk(ctx, kv_to_device(k, "bf16"), kv_to_device(v, "bf16"), P)
+        pending = I.make_pending(shape, nb, K, wl.seed)
+        caches = {}
+        for b in seqs:
+            trunk = oracle_trunk_from_arrays(om, k, v, b)
+            spec, _ = O.speculate(om, trunk, pending[b, 0], K, 0.0, 0)     # a greedy draft's speculation
+            pending[b, 1:] = spec
+            caches[b] = O.prespeculate(om, trunk, pending[b], F, T, seed=wl.seed, row_base=b * (K + 1) * F,
+                                       only_rows=rows)
+            print(f"[oracle] sequence {b} done", flush=True)
+        temps = dev_f32(np.full(nb, T, np.float32))
+        M1 = (K + 1) * F
+        f_keys = np.zeros((nb, K + 1, F), np.int32)
+        f_toks = np.zeros((nb, K + 1, F, K), np.int32)
+        for b in seqs:
+            f_keys[b] = caches[b].keys
+            f_toks[b] = caches[b].tokens
+        d_keys, d_toks, d_pending = dev_i32(f_keys), dev_i32(f_toks), dev_i32(pending)   # kept alive over the call
+        B.ssd_ctx_set_forced(ctx, d_keys, d_toks)
+        B.ssd_prespeculate(ctx, d_pending, temps, wl.seed)
+        B.ssd_ctx_set_forced(ctx, None, None)
+        torch.cuda.synchronize()
+        view = B.ssd_ctx_views(ctx)
+        V, d = shape.vocab, shape.d_model
+        keys = B.device_copy(view.d_keys, (nb, K + 1, F), torch.int32).cpu().numpy()
+        glue = B.device_copy(view.d_glue_logits, (nb, K + 1, V), torch.float32).cpu().numpy()
+        toks = B.device_copy(view.d_tokens, (nb, K + 1, F, K), torch.int32).cpu().numpy()
+        for b in seqs:
+            c = caches[b]
+            e = row_rel_err(glue[b], c.glue_logits)
+            print(f"[glue] seq {b}: rel err {e:.3e}", flush=True)
+            assert e < tol
+            # selection, bit-exact on the oracle's logits (as fp32, the type the kernel consumes)
+            z32 = c.glue_logits.astype(np.float32)
+            ex = np.array([pending[b, kk + 1] if kk < K else -1 for kk in range(K + 1)], np.int32)
+            ids = torch.zeros((K + 1, F), dtype=torch.int32, device="cuda")
+            B.ssd_top_f(dev_f32(z32), dev_i32(ex), F, ids)
+            want = np.stack([O.top_f_ids(z32[kk], F, exclude=None if ex[kk] < 0 else int(ex[kk])) for kk in range(K + 1)])
+            assert np.array_equal(ids.cpu().numpy(), want)
+            # the round's own keys: equal wherever the GPU's logit error cannot flip the order
+            for kk in range(K + 1):
+                err = np.abs(glue[b, kk] - c.glue_logits[kk]).max()
+                zz = c.glue_logits[kk].copy()
+                if ex[kk] >= 0:
+                    zz[ex[kk]] = -np.inf
+                top = np.sort(zz)[::-1][:F + 1]
+                if (-np.diff(top)).min() > 2 * err:
+                    assert np.array_equal(keys[b, kk], c.keys[kk]), (b, kk)
+                if ex[kk] >= 0:
+                    assert ex[kk] not in keys[b, kk]
+            for row in rows:
+                kk, j = divmod(row, F)
+                m = b * M1 + row
+                lg = B.device_copy(view.d_logits + m * K * V * 4, (K, V), torch.float32).cpu().numpy()
+                hd = B.device_copy(view.d_hidden + m * K * d * 4, (K, d), torch.float32).cpu().numpy()
+                e_l, e_h = row_rel_err(lg, c.logits[kk, j]), row_rel_err(hd, c.hidden[kk, j])
+                print(f"[branch] seq {b} row {row}: logits rel err {e_l:.3e}, hidden rel err {e_h:.3e}", flush=True)
+                assert e_l < tol and e_h < tol
+                if T == 0:
+                    err = np.abs(lg - c.logits[kk, j]).max(axis=-1)
+                    ok = c.margins[kk, j] > 2 * err
+                    assert np.array_equal(toks[b, kk, j][ok], c.tokens[kk, j][ok])
+        # App. C: the round decoded B K (K+1) F branch tokens and every one is a valid token id
+        assert toks.size == nb * K * (K + 1) * F
+        assert toks.min() >= 0 and toks.max() < V
+    finally:
+        B.ssd_ctx_destroy(ctx)

@@ -1,0 +1,218 @@
+"""GPU parity of the pre-speculation round against the float64 oracle, through the C ABI.
+
+Protocol: (i) selection is compared on the oracle's logits (test_gpu_select.py) and, inside the round,
+wherever the oracle's margin is not a near-tie; (ii) numerics are teacher-forced: the GPU runs every step on
+the oracle's input tokens, so logits and hidden states must agree within the benchmark spec's tolerance
+(rel 2e-2 in bf16, 1e-4 in fp32, relative to each row's largest magnitude); (iii) the fp32 tiny workload also
+runs free and must reproduce the oracle's tokens wherever the oracle's top-2 margin exceeds 1e-4."""
+import numpy as np
+import pytest
+import torch
+
+import ssd_inputs as I
+from oracle import ssd_oracle as O
+from tests.gpu_util import (MARGIN, TOL, dev_f32, dev_i32, kv_to_device, oracle_trunk_from_arrays, rms_rel_err,
+                            row_rel_err)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_03251_amd import binding
+    return binding
+
+
+SMALL_BF16 = I.ModelShape(n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ffn=1024,
+                          vocab=4112, dtype="bf16", rope_theta=500000.0, tie_embeddings=True)
+SMALL_BF16_D128 = I.ModelShape(n_layers=1, d_model=512, n_q_heads=8, n_kv_heads=1, head_dim=128, d_ffn=512,
+                               vocab=2064, dtype="bf16", rope_theta=500000.0, tie_embeddings=False)
+
+
+def _key_margin(z, keys_row, exclude):
+    """Gap between the F-th selected logit and the best one left out (a near-tie makes the key set ambiguous)."""
+    zz = np.array(z, dtype=np.float64)
+    if exclude is not None:
+        zz[exclude] = -np.inf
+    sel = zz[keys_row]
+    zz[keys_row] = -np.inf
+    gaps = np.concatenate([-np.diff(sel), [sel[-1] - zz.max()]])
+    return float(gaps.min())
+
+
+def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=0.0):
+    tol = TOL[shape.dtype]
+    w = I.make_weights(shape, seed)
+    om = O.Model.from_weights(shape, w)
+    model = B.ssd_model_create(shape, w)
+    ctx = B.ssd_ctx_create(model, batch, K, F, P + 4 * K + 8)
+    try:
+        if synthetic_kv:
+            k, v = I.make_prefix_kv(shape, batch, P, seed)
+            B.ssd_ctx_load_trunk(ctx, kv_to_device(k, shape.dtype), kv_to_device(v, shape.dtype), P)
+            trunks = [oracle_trunk_from_arrays(om, k, v, b) for b in range(batch)]
+        else:
+            prompt = I.make_prompt(shape, batch, P, seed)
+            B.ssd_ctx_prefill(ctx, dev_i32(prompt), [P] * batch)
+            trunks = [O.prefill(om, prompt[b])[1] for b in range(batch)]
+        pending = I.make_pending(shape, batch, K, seed)
+        # make the pending tokens what a greedy draft would have proposed, so that exclusion bites
+        for b in range(batch):
+            spec, _ = O.speculate(om, trunks[b], pending[b, 0], K, 0.0, 0)
+            pending[b, 1:] = spec
+        caches = [O.prespeculate(om, trunks[b], pending[b], F, temperature, seed=seed, row_base=b * (K + 1) * F)
+                  for b in range(batch)]
+        temps = dev_f32(np.full(batch, temperature, np.float32))
+
+        # ---- free run: selection and sampling on the GPU's own logits
+        B.ssd_prespeculate(ctx, dev_i32(pending), temps, seed)
+        free = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx).items()}
+        assert (free["trunk_len"] == P).all()
+        n_keys_checked = 0
+        for b in range(batch):
+            assert row_rel_err(free["glue_logits"][b], caches[b].glue_logits) < tol
+            for k in range(K + 1):
+                ex = int(pending[b, k + 1]) if k < K else None
+                err = np.abs(free["glue_logits"][b, k] - caches[b].glue_logits[k]).max()
+                # an ordering gap wider than twice the largest logit error cannot be flipped by it
+                if _key_margin(caches[b].glue_logits[k], caches[b].keys[k], ex) > 2 * err + 1e-12:
+                    assert np.array_equal(free["keys"][b, k], caches[b].keys[k]), (b, k)
+                    n_keys_checked += 1
+                if k < K:
+                    assert pending[b, k + 1] not in free["keys"][b, k]
+        assert n_keys_checked > 0
+
+        # ---- teacher-forced run: every row consumes the oracle's tokens
+        f_keys = dev_i32(np.stack([c.keys for c in caches]))
+        f_toks = dev_i32(np.stack([c.tokens for c in caches]))
+        B.ssd_ctx_set_forced(ctx, f_keys, f_toks)
+        B.ssd_prespeculate(ctx, dev_i32(pending), temps, seed)
+        B.ssd_ctx_set_forced(ctx, None, None)
+        forced = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx).items()}
+        worst = 0.0
+        for b in range(batch):
+            e_l = row_rel_err(forced["logits"][b], caches[b].logits)
+            e_h = row_rel_err(forced["hidden"][b], caches[b].hidden)
+            worst = max(worst, e_l, e_h)
+            assert e_l < tol and e_h < tol, (b, e_l, e_h)
+            assert rms_rel_err(forced["logits"][b], caches[b].logits) < tol
+            # sampled tokens agree wherever the decision is not a near-tie at this precision
+            if temperature == 0:
+                err = np.abs(forced["logits"][b] - caches[b].logits).max(axis=-1)
+                decided = caches[b].margins > 2 * err + 1e-12
+                assert decided.any()
+                assert np.array_equal(forced["tokens"][b][decided], caches[b].tokens[decided])
+        return free, forced, caches, worst
+    finally:
+        B.ssd_ctx_destroy(ctx)
+        B.ssd_model_destroy(model)
+
+
+def test_tiny_f32_workload_teacher_forced_and_free_running(B):
+    wl = I.WORKLOADS["tiny_f32"]
+    r = wl.round
+    free, forced, caches, worst = _run_round_parity(B, wl.draft, r.batch, r.prefix - 1, r.K, r.F, wl.seed,
+                                                     synthetic_kv=False)
+    assert worst < 1e-4
+    # free-running fp32: tokens equal the oracle's unless an earlier decision of that branch was a near-tie
+    c = caches[0]
+    n_equal = 0
+    for k in range(r.K + 1):
+        for j in range(r.F):
+            if free["keys"][0, k, j] != c.keys[k, j]:
+                continue
+            for i in range(r.K):
+                if c.margins[k, j, i] < MARGIN:
+                    break
+                assert free["tokens"][0, k, j, i] == c.tokens[k, j, i]
+                n_equal += 1
+    assert n_equal >= r.K * (r.K + 1) * r.F - 4
+
+
+def test_small_bf16_ragged_rows_synthetic_prefix(B):
+    # M = 2 * 4 * 3 = 24 rows, prefix 203 (not a multiple of anything), GQA group 4
+    _run_round_parity(B, SMALL_BF16, batch=2, P=203, K=3, F=3, seed=7, synthetic_kv=True)
+
+
+def test_small_bf16_many_rows_and_real_prefill(B):
+    # M = 3 * 5 * 5 = 75 rows: more than one 64-row GEMM pass, last 16-row tile ragged
+    _run_round_parity(B, SMALL_BF16, batch=3, P=37, K=4, F=5, seed=8, synthetic_kv=False)
+
+
+def test_small_bf16_head_dim_128_untied(B):
+    _run_round_parity(B, SMALL_BF16_D128, batch=1, P=70, K=2, F=2, seed=9, synthetic_kv=True)
+
+
+def test_lookup_and_commit(B):
+    shape = I.WORKLOADS["tiny_f32"].draft
+    w = I.make_weights(shape, 3)
+    model = B.ssd_model_create(shape, w)
+    K, F, nb, P = 4, 2, 3, 20
+    ctx = B.ssd_ctx_create(model, nb, K, F, 128)
+    try:
+        acc = dev_i32([0, 1, 2])
+        bonus = dev_i32([1, 2, 3])
+        hit = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+        branch = torch.zeros(nb, dtype=torch.int32, device="cuda")
+        spec = torch.zeros((nb, K), dtype=torch.int32, device="cuda")
+        with pytest.raises(B.SsdError) as e:
+            B.ssd_cache_lookup(ctx, acc, bonus, hit, branch, spec)
+        assert e.value.status == B.SSD_ESTATE                     # lookup before any pre-speculation
+        with pytest.raises(B.SsdError) as e:
+            B.ssd_prespeculate(ctx, dev_i32(np.zeros((nb, K + 1))), dev_f32(np.zeros(nb)), 0)
+        assert e.value.status == B.SSD_ESTATE                     # empty trunk
+        prompt = I.make_prompt(shape, nb, P, 5)
+        B.ssd_ctx_prefill(ctx, dev_i32(prompt), [P, P - 3, P - 7])    # ragged lengths
+        pending = I.make_pending(shape, nb, K, 5)
+        B.ssd_prespeculate(ctx, dev_i32(pending), dev_f32(np.zeros(nb)), 0)
+        cache = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx, with_logits=False).items()}
+        assert list(cache["trunk_len"]) == [P, P - 3, P - 7]
+        keys, toks = cache["keys"], cache["tokens"]
+        # every (k, token) outcome of sequence 1: hit iff the oracle's linear search finds it
+        ptrs = torch.zeros(nb, dtype=torch.int64, device="cuda")
+        v = B.ssd_ctx_views(ctx)
+        for k in range(K + 1):
+            probe = [int(keys[0, k, F - 1]), int((keys[1, k].max() + 1) % shape.vocab), int(keys[2, k, 0])]
+            B.ssd_cache_lookup(ctx, dev_i32([k] * nb), dev_i32(probe), hit, branch, spec, ptrs)
+            torch.cuda.synchronize()
+            want = [O.cache_lookup(keys[b], k, probe[b]) for b in range(nb)]
+            assert list(branch.cpu().numpy()) == want
+            assert list(hit.cpu().numpy()) == [1 if j >= 0 else 0 for j in want]
+            sp = spec.cpu().numpy()
+            for b in range(nb):
+                if want[b] >= 0:
+                    assert np.array_equal(sp[b], toks[b, k, want[b]])
+                    row = (b * (K + 1) + k) * F + want[b]
+                    assert int(ptrs[b]) == v.d_logits + row * K * shape.vocab * 4
+                else:
+                    assert (sp[b] == -1).all() and int(ptrs[b]) == 0
+        # an accept length outside 0..K is a miss
+        B.ssd_cache_lookup(ctx, dev_i32([K + 1, -1, 0]), dev_i32([int(keys[0, 0, 0])] * nb), hit, branch, spec)
+        torch.cuda.synchronize()
+        assert list(hit.cpu().numpy())[:2] == [0, 0]
+        # commit: trunk grows by k + 1 (clamped)
+        B.ssd_ctx_commit(ctx, dev_i32([0, K, K + 5]))
+        torch.cuda.synchronize()
+        tl = B.read_cache(ctx, with_logits=False)["trunk_len"].cpu().numpy()
+        assert list(tl) == [P + 1, P - 3 + K + 1, P - 7 + K + 1]
+        B.ssd_ctx_refresh_bounds(ctx)
+    finally:
+        B.ssd_ctx_destroy(ctx)
+        B.ssd_model_destroy(model)
+
+
+def test_argument_validation(B):
+    shape = I.WORKLOADS["tiny_f32"].draft
+    model = B.ssd_model_create(shape, I.make_weights(shape, 3))
+    try:
+        for bad in [(0, 4, 2, 128), (1, 0, 2, 128), (1, 16, 2, 128), (1, 4, 17, 128), (1, 4, 2, 5)]:
+            with pytest.raises(B.SsdError) as e:
+                B.ssd_ctx_create(model, *bad)
+            assert e.value.status == B.SSD_EINVAL
+        ctx = B.ssd_ctx_create(model, 1, 4, 2, 40)
+        with pytest.raises(B.SsdError) as e:      # prompt does not leave room for a round
+            B.ssd_ctx_prefill(ctx, dev_i32(np.zeros((1, 35))), [35])
+        assert e.value.status == B.SSD_EINVAL
+        B.ssd_ctx_destroy(ctx)
+    finally:
+        B.ssd_model_destroy(model)
