@@ -54,6 +54,24 @@ template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
+// Activations between kernels.  fp32 models: plain fp32 [rows][cols].  bf16 models: two bf16 planes of the same
+// shape, `plane` elements apart: head = bf16(x) and remainder = bf16(x - head), so that x = head + remainder to
+// about 2^-17 relative and each plane is directly an MFMA operand.
+template <typename T> struct Act;
+template <> struct Act<float> {
+  static __device__ __forceinline__ void store(void* base, int64_t plane, int64_t idx, float v) {
+    (void)plane;
+    ((float*)base)[idx] = v;
+  }
+};
+template <> struct Act<bf16_t> {
+  static __device__ __forceinline__ void store(void* base, int64_t plane, int64_t idx, float v) {
+    bf16_t h = f32_to_bf16(v);
+    ((bf16_t*)base)[idx] = h;
+    ((bf16_t*)base)[plane + idx] = f32_to_bf16(v - bf16_to_f32(h));
+  }
+};
+
 // One row of a batched forward pass (a branch at some depth, or one token of an extend).
 struct RowDesc {
   int32_t seq;        // sequence b
@@ -81,8 +99,8 @@ int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk
 int launch_setup_extend_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int T, int offset,
                              int half_dim, float theta, hipStream_t s);
 int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* h, int M, int d, int vocab, hipStream_t s);
-int launch_rmsnorm(int dtype, const float* h, const void* gain, float* xn, float* copy_out, int64_t copy_ld, int M, int d,
-                   float eps, hipStream_t s);
+int launch_rmsnorm(int dtype, const float* h, const void* gain, void* xn, int64_t xn_plane, float* copy_out,
+                   int64_t copy_ld, int M, int d, float eps, hipStream_t s);
 // Rotary embedding of q and k (fp32 [M][qkv_dim]) + write of q (activation dtype) and of the row's K/V
 // into the trunk or its private suffix.
 int launch_rope_append(int dtype, const float* qkv, const RowDesc* rows, const float* cos_sin, float* q_out,
@@ -103,10 +121,10 @@ int launch_copy_kv_in(int dtype, void* trunk, const void* src, int B, int len, i
 enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL_ADD = 1, EPI_SWIGLU = 2 };
 // Tiled copy of a [N][Kd] bf16 matrix into the MFMA-operand order the bf16 GEMM streams (see kernels_gemm.hip).
 int launch_tile_weights_bf16(const bf16_t* src, bf16_t* dst, int N, int Kd, hipStream_t s);
-// y[m][n] (+)= sum_k x[m][k] w[n][k].  x: fp32 [M][Kd]; out fp32 (ld elements); for EPI_SWIGLU
-// out[m][n] = silu(x.w^T) * (x.w2^T).
-int launch_gemm(int dtype, int epi, const void* x, const void* w, const void* w2, void* out, int64_t ld, int M, int N,
-                int Kd, hipStream_t s);
+// y[m][n] (+)= sum_k x[m][k] w[n][k].  x: activation [M][Kd] (planes `x_plane` apart for bf16 models); out fp32
+// (ld elements); for EPI_SWIGLU out is an activation [M][N] = silu(x.w^T) * (x.w2^T) (planes `out_plane` apart).
+int launch_gemm(int dtype, int epi, const void* x, int64_t x_plane, const void* w, const void* w2, void* out, int64_t ld,
+                int64_t out_plane, int M, int N, int Kd, hipStream_t s);
 
 // ---------------------------------------------------------------- kernels_attn.hip
 struct AttnArgs {
@@ -115,7 +133,8 @@ struct AttnArgs {
   const void* trunk_v;
   const void* suffix_k;  // model dtype [M][suffix_cap][Hkv][D]
   const void* suffix_v;
-  float* out;            // fp32 [M][Hq][D]
+  void* out;             // activation [M][Hq][D]
+  int64_t out_plane;
   const RowDesc* rows;
   float* partial;        // scratch for split-KV partial results
   int M, n_q_heads, n_kv_heads, head_dim, max_trunk, suffix_cap;

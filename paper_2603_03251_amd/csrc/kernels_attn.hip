@@ -34,7 +34,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void attention_rowwise_kernel(const float* __restrict__ q, const T* __restrict__ trunk_k,
                                                                  const T* __restrict__ trunk_v,
                                                                  const T* __restrict__ suffix_k,
-                                                                 const T* __restrict__ suffix_v, float* __restrict__ out,
+                                                                 const T* __restrict__ suffix_v, void* __restrict__ out,
+                                                                 int64_t out_plane,
                                                                  const RowDesc* __restrict__ rows, int n_q_heads,
                                                                  int n_kv_heads, int max_trunk, int suffix_cap) {
   __shared__ float q_s[4][D];
@@ -94,12 +95,12 @@ __global__ __launch_bounds__(256) void attention_rowwise_kernel(const float* __r
     float l_all = l_run * w;
     for (int o = 32; o > 0; o >>= 1) l_all += __shfl_xor(l_all, o);
     float inv = 1.0f / l_all;
-    float* op = out + ((int64_t)m * n_q_heads + hq) * D;
+    const int64_t obase = ((int64_t)m * n_q_heads + hq) * D;
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       float v = acc[d] * w;
       for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-      if (lane == (d & 63)) op[d] = v * inv;
+      if (lane == (d & 63)) Act<T>::store(out, out_plane, obase + d, v * inv);
     }
     __builtin_amdgcn_wave_barrier();
   }
@@ -110,11 +111,11 @@ int launch_rowwise(const AttnArgs& a, hipStream_t s) {
   dim3 grid(a.M, a.n_kv_heads);
   if (a.head_dim == 64)
     attention_rowwise_kernel<T, 64><<<grid, 256, 0, s>>>(a.q, (const T*)a.trunk_k, (const T*)a.trunk_v,
-                                                         (const T*)a.suffix_k, (const T*)a.suffix_v, a.out, a.rows,
+                                                         (const T*)a.suffix_k, (const T*)a.suffix_v, a.out, a.out_plane, a.rows,
                                                          a.n_q_heads, a.n_kv_heads, a.max_trunk, a.suffix_cap);
   else if (a.head_dim == 128)
     attention_rowwise_kernel<T, 128><<<grid, 256, 0, s>>>(a.q, (const T*)a.trunk_k, (const T*)a.trunk_v,
-                                                          (const T*)a.suffix_k, (const T*)a.suffix_v, a.out, a.rows,
+                                                          (const T*)a.suffix_k, (const T*)a.suffix_v, a.out, a.out_plane, a.rows,
                                                           a.n_q_heads, a.n_kv_heads, a.max_trunk, a.suffix_cap);
   else {
     set_error("head_dim %d not supported (64 or 128)", a.head_dim);

@@ -6,9 +6,9 @@
 // order": tile (nt, kt) = 16 features x 32 inputs is 1 KiB, laid out exactly as the 64 lanes hold it (lane l:
 // feature nt*16 + l%16, inputs kt*32 + (l/16)*8 .. +7), tiles of one nt consecutive over kt.  A wavefront
 // therefore streams its share of a feature tile with fully coalesced 16-byte-per-lane loads.
-// Activations stay fp32 in memory; each is split on the fly into a bf16 head and a bf16 remainder (x = hi + lo,
-// two MFMAs per weight tile), so the only bf16 rounding left in a layer is that of the weights themselves and of
-// the KV cache.  With a handful of rows the extra MFMAs are free: the kernel is bound by the weight stream.
+// Activations arrive as two bf16 planes, head and remainder (x = hi + lo, written by the producing kernel), and
+// take two MFMAs per weight tile, so the only bf16 rounding left in a layer is that of the weights themselves
+// and of the KV cache.  With a handful of rows the extra MFMAs are free: the kernel is bound by the weight stream.
 // fp32 models (the small correctness configuration): plain FMA dot products, one wavefront per output feature.
 #include "common.h"
 
@@ -38,29 +38,13 @@ __global__ void tile_weights_kernel(const bf16_t* __restrict__ src, bf16_t* __re
 
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
 
-typedef __attribute__((ext_vector_type(8))) uint16_t u16x8;
-
-// 8 consecutive fp32 activations -> bf16 head and bf16 remainder (x = hi + lo up to 2^-17 relative).
-__device__ __forceinline__ void split_hi_lo(const float* p, bf16x8& hi, bf16x8& lo) {
-  f32x4 a = *(const f32x4*)p, b = *(const f32x4*)(p + 4);
-  float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-  u16x8 h, l;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    bf16_t hb = f32_to_bf16(v[i]);
-    h[i] = hb;
-    l[i] = f32_to_bf16(v[i] - bf16_to_f32(hb));
-  }
-  hi = __builtin_bit_cast(bf16x8, h);
-  lo = __builtin_bit_cast(bf16x8, l);
-}
-
 // grid.x = N/16 feature tiles, grid.y = passes of 64 rows.  Each of the 4 wavefronts reduces a quarter of Kd;
 // partial tiles meet in LDS; wavefront w finishes activation tile w.
 template <int EPI, int MT>
-__global__ __launch_bounds__(kWaves * 64) void gemm_bf16_kernel(const float* __restrict__ x, const bf16_t* __restrict__ w,
+__global__ __launch_bounds__(kWaves * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ x, int64_t x_plane,
+                                                                 const bf16_t* __restrict__ w,
                                                                  const bf16_t* __restrict__ w2, void* __restrict__ out,
-                                                                 int64_t ld, int M, int N, int Kd) {
+                                                                 int64_t ld, int64_t out_plane, int M, int N, int Kd) {
   __shared__ f32x4 red[(EPI == EPI_SWIGLU ? 2 : 1) * kWaves * MT * 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nt = blockIdx.x;
@@ -77,7 +61,7 @@ __global__ __launch_bounds__(kWaves * 64) void gemm_bf16_kernel(const float* __r
   const bf16x8* wp = (const bf16x8*)(w + ((int64_t)nt * KT + kt0) * 512) + lane;
   const bf16x8* wp2 = EPI == EPI_SWIGLU ? (const bf16x8*)(w2 + ((int64_t)nt * KT + kt0) * 512) + lane : nullptr;
   // activation operand: row (clamped to M-1; those columns are never stored), 8 inputs at (lane/16)*8
-  const float* xrow[MT];
+  const bf16_t* xrow[MT];
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
     int m = m0 + t * 16 + (lane & 15);
@@ -97,8 +81,8 @@ __global__ __launch_bounds__(kWaves * 64) void gemm_bf16_kernel(const float* __r
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
-        bf16x8 hi, lo;
-        split_hi_lo(xrow[t] + (kt + u) * 32, hi, lo);
+        bf16x8 hi = *(const bf16x8*)(xrow[t] + (kt + u) * 32);
+        bf16x8 lo = *(const bf16x8*)(xrow[t] + x_plane + (kt + u) * 32);
         acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wr[u], hi, acc[t], 0, 0, 0);
         acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wr[u], lo, acc[t], 0, 0, 0);
         if (EPI == EPI_SWIGLU) {
@@ -131,8 +115,8 @@ __global__ __launch_bounds__(kWaves * 64) void gemm_bf16_kernel(const float* __r
       f32x4 up = red[kWaves * MT * 64 + t * 64 + lane];
 #pragma unroll
       for (int v = 1; v < kWaves; ++v) up += red[kWaves * MT * 64 + (v * MT + t) * 64 + lane];
-      f32x4 r = {silu(sum[0]) * up[0], silu(sum[1]) * up[1], silu(sum[2]) * up[2], silu(sum[3]) * up[3]};
-      *(f32x4*)((float*)out + (int64_t)m * ld + n) = r;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) Act<bf16_t>::store(out, out_plane, (int64_t)m * ld + n + r, silu(sum[r]) * up[r]);
     }
   }
 }
@@ -181,17 +165,17 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 }
 
 template <int EPI>
-int launch_bf16(const void* x, const void* w, const void* w2, void* out, int64_t ld, int M, int N, int Kd, hipStream_t s) {
+int launch_bf16(const void* x, int64_t x_plane, const void* w, const void* w2, void* out, int64_t ld, int64_t out_plane,
+                int M, int N, int Kd, hipStream_t s) {
   dim3 grid(N / 16, (M + kMaxMT * 16 - 1) / (kMaxMT * 16));
   int rows_in_pass = M < kMaxMT * 16 ? M : kMaxMT * 16;
   int mt = (rows_in_pass + 15) / 16;
-  const float* xb = (const float*)x;
-  const bf16_t *wb = (const bf16_t*)w, *w2b = (const bf16_t*)w2;
+  const bf16_t *xb = (const bf16_t*)x, *wb = (const bf16_t*)w, *w2b = (const bf16_t*)w2;
   switch (mt) {
-    case 1: gemm_bf16_kernel<EPI, 1><<<grid, kWaves * 64, 0, s>>>(xb, wb, w2b, out, ld, M, N, Kd); break;
-    case 2: gemm_bf16_kernel<EPI, 2><<<grid, kWaves * 64, 0, s>>>(xb, wb, w2b, out, ld, M, N, Kd); break;
-    case 3: gemm_bf16_kernel<EPI, 3><<<grid, kWaves * 64, 0, s>>>(xb, wb, w2b, out, ld, M, N, Kd); break;
-    default: gemm_bf16_kernel<EPI, 4><<<grid, kWaves * 64, 0, s>>>(xb, wb, w2b, out, ld, M, N, Kd); break;
+    case 1: gemm_bf16_kernel<EPI, 1><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd); break;
+    case 2: gemm_bf16_kernel<EPI, 2><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd); break;
+    case 3: gemm_bf16_kernel<EPI, 3><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd); break;
+    default: gemm_bf16_kernel<EPI, 4><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd); break;
   }
   SSD_HIP(hipGetLastError());
   return SSD_OK;
@@ -216,14 +200,14 @@ int launch_tile_weights_bf16(const bf16_t* src, bf16_t* dst, int N, int Kd, hipS
   return SSD_OK;
 }
 
-int launch_gemm(int dtype, int epi, const void* x, const void* w, const void* w2, void* out, int64_t ld, int M, int N,
-                int Kd, hipStream_t s) {
+int launch_gemm(int dtype, int epi, const void* x, int64_t x_plane, const void* w, const void* w2, void* out, int64_t ld,
+                int64_t out_plane, int M, int N, int Kd, hipStream_t s) {
   if (M <= 0) return SSD_OK;
   if (dtype == SSD_BF16) {
     switch (epi) {
-      case EPI_STORE_F32: return launch_bf16<EPI_STORE_F32>(x, w, w2, out, ld, M, N, Kd, s);
-      case EPI_RESIDUAL_ADD: return launch_bf16<EPI_RESIDUAL_ADD>(x, w, w2, out, ld, M, N, Kd, s);
-      default: return launch_bf16<EPI_SWIGLU>(x, w, w2, out, ld, M, N, Kd, s);
+      case EPI_STORE_F32: return launch_bf16<EPI_STORE_F32>(x, x_plane, w, w2, out, ld, out_plane, M, N, Kd, s);
+      case EPI_RESIDUAL_ADD: return launch_bf16<EPI_RESIDUAL_ADD>(x, x_plane, w, w2, out, ld, out_plane, M, N, Kd, s);
+      default: return launch_bf16<EPI_SWIGLU>(x, x_plane, w, w2, out, ld, out_plane, M, N, Kd, s);
     }
   }
   switch (epi) {

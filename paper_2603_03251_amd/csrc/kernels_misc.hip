@@ -73,7 +73,8 @@ __device__ __forceinline__ float block_sum(float v, float* smem) {
 
 // x / sqrt(mean(x^2) + eps) * gain, one block per row.
 template <typename T>
-__global__ void rmsnorm_kernel(const float* h, const T* gain, float* xn, float* copy_out, int64_t copy_ld, int d, float eps) {
+__global__ void rmsnorm_kernel(const float* h, const T* gain, void* xn, int64_t xn_plane, float* copy_out, int64_t copy_ld,
+                               int d, float eps) {
   __shared__ float smem[kBlock / 64];
   int m = blockIdx.x;
   const float* row = h + (int64_t)m * d;
@@ -83,7 +84,7 @@ __global__ void rmsnorm_kernel(const float* h, const T* gain, float* xn, float* 
   float scale = 1.0f / sqrtf(ss / (float)d + eps);
   for (int c = threadIdx.x; c < d; c += blockDim.x) {
     float v = row[c] * scale * Elem<T>::load(gain + c);
-    xn[(int64_t)m * d + c] = v;
+    Act<T>::store(xn, xn_plane, (int64_t)m * d + c, v);
     if (copy_out) copy_out[(int64_t)m * copy_ld + c] = v;
   }
 }
@@ -210,12 +211,12 @@ int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* h, 
   return SSD_OK;
 }
 
-int launch_rmsnorm(int dtype, const float* h, const void* gain, float* xn, float* copy_out, int64_t copy_ld, int M, int d,
-                   float eps, hipStream_t s) {
+int launch_rmsnorm(int dtype, const float* h, const void* gain, void* xn, int64_t xn_plane, float* copy_out,
+                   int64_t copy_ld, int M, int d, float eps, hipStream_t s) {
   if (dtype == SSD_BF16)
-    rmsnorm_kernel<bf16_t><<<M, kBlock, 0, s>>>(h, (const bf16_t*)gain, xn, copy_out, copy_ld, d, eps);
+    rmsnorm_kernel<bf16_t><<<M, kBlock, 0, s>>>(h, (const bf16_t*)gain, xn, xn_plane, copy_out, copy_ld, d, eps);
   else
-    rmsnorm_kernel<float><<<M, kBlock, 0, s>>>(h, (const float*)gain, xn, copy_out, copy_ld, d, eps);
+    rmsnorm_kernel<float><<<M, kBlock, 0, s>>>(h, (const float*)gain, xn, xn_plane, copy_out, copy_ld, d, eps);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }

@@ -95,12 +95,13 @@ struct ssd_ctx {
   float* cos_sin;
   int32_t* step_tokens;
   int32_t* exclude;
-  float* h;          // residual stream
-  float* xn;         // all activations between kernels are fp32
-  float* qkv;
-  float* q;
-  float* attn_out;
-  float* act;
+  float* h;          // residual stream, fp32
+  float* qkv;        // fp32
+  float* q;          // fp32
+  // activations that feed a GEMM: fp32 (fp32 models) or bf16 head/remainder planes (bf16 models), 4 bytes/element
+  void* xn;
+  void* attn_out;
+  void* act;
   float* attn_partial;
   const int32_t* forced_keys = nullptr;
   const int32_t* forced_tokens = nullptr;
@@ -163,28 +164,33 @@ int forward_rows(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int
   const ssd_model* m = c->model;
   const Dims& d = m->dims;
   const int dt = d.dtype;
+  const int64_t R = c->max_rows;     // plane stride of an activation buffer = R * columns
   SSD_TRY(launch_embed(dt, m->embed, tokens, c->h, M, d.d_model, d.vocab, s));
   for (int l = 0; l < d.n_layers; ++l) {
     const ssd_model::Layer& L = m->layers[l];
-    SSD_TRY(launch_rmsnorm(dt, c->h, L.attn_norm, c->xn, nullptr, 0, M, d.d_model, d.rms_eps, s));
-    SSD_TRY(launch_gemm(dt, EPI_STORE_F32, c->xn, L.wqkv, nullptr, c->qkv, d.qkv_dim(), M, d.qkv_dim(), d.d_model, s));
+    SSD_TRY(launch_rmsnorm(dt, c->h, L.attn_norm, c->xn, R * d.d_model, nullptr, 0, M, d.d_model, d.rms_eps, s));
+    SSD_TRY(launch_gemm(dt, EPI_STORE_F32, c->xn, R * d.d_model, L.wqkv, nullptr, c->qkv, d.qkv_dim(), 0, M, d.qkv_dim(),
+                        d.d_model, s));
     SSD_TRY(launch_rope_append(dt, c->qkv, c->rows, c->cos_sin, c->q, c->trunk_k[l], c->trunk_v[l], c->suffix_k[l],
                                c->suffix_v[l], M, d.n_q_heads, d.n_kv_heads, d.head_dim, c->max_trunk, c->K, s));
     AttnArgs a;
     a.q = c->q; a.trunk_k = c->trunk_k[l]; a.trunk_v = c->trunk_v[l]; a.suffix_k = c->suffix_k[l];
-    a.suffix_v = c->suffix_v[l]; a.out = c->attn_out; a.rows = c->rows; a.partial = c->attn_partial; a.M = M;
+    a.suffix_v = c->suffix_v[l]; a.out = c->attn_out; a.out_plane = R * d.q_dim(); a.rows = c->rows; a.partial = c->attn_partial; a.M = M;
     a.n_q_heads = d.n_q_heads; a.n_kv_heads = d.n_kv_heads; a.head_dim = d.head_dim; a.max_trunk = c->max_trunk;
     a.suffix_cap = c->K; a.rows_per_seq = rows_per_seq; a.max_vis = max_vis;
     SSD_TRY(launch_attention(dt, a, s));
-    SSD_TRY(launch_gemm(dt, EPI_RESIDUAL_ADD, c->attn_out, L.wo, nullptr, c->h, d.d_model, M, d.d_model, d.q_dim(), s));
-    SSD_TRY(launch_rmsnorm(dt, c->h, L.mlp_norm, c->xn, nullptr, 0, M, d.d_model, d.rms_eps, s));
-    SSD_TRY(launch_gemm(dt, EPI_SWIGLU, c->xn, L.w_gate, L.w_up, c->act, d.d_ffn, M, d.d_ffn, d.d_model, s));
-    SSD_TRY(launch_gemm(dt, EPI_RESIDUAL_ADD, c->act, L.w_down, nullptr, c->h, d.d_model, M, d.d_model, d.d_ffn, s));
+    SSD_TRY(launch_gemm(dt, EPI_RESIDUAL_ADD, c->attn_out, R * d.q_dim(), L.wo, nullptr, c->h, d.d_model, 0, M, d.d_model,
+                        d.q_dim(), s));
+    SSD_TRY(launch_rmsnorm(dt, c->h, L.mlp_norm, c->xn, R * d.d_model, nullptr, 0, M, d.d_model, d.rms_eps, s));
+    SSD_TRY(launch_gemm(dt, EPI_SWIGLU, c->xn, R * d.d_model, L.w_gate, L.w_up, c->act, d.d_ffn, R * d.d_ffn, M, d.d_ffn,
+                        d.d_model, s));
+    SSD_TRY(launch_gemm(dt, EPI_RESIDUAL_ADD, c->act, R * d.d_ffn, L.w_down, nullptr, c->h, d.d_model, 0, M, d.d_model,
+                        d.d_ffn, s));
   }
   if (logits || hidden) {
-    SSD_TRY(launch_rmsnorm(dt, c->h, m->final_norm, c->xn, hidden, hidden_ld, M, d.d_model, d.rms_eps, s));
-    if (logits) SSD_TRY(launch_gemm(dt, EPI_STORE_F32, c->xn, m->lm_head, nullptr, logits, logits_ld, M, d.vocab,
-                                    d.d_model, s));
+    SSD_TRY(launch_rmsnorm(dt, c->h, m->final_norm, c->xn, R * d.d_model, hidden, hidden_ld, M, d.d_model, d.rms_eps, s));
+    if (logits) SSD_TRY(launch_gemm(dt, EPI_STORE_F32, c->xn, R * d.d_model, m->lm_head, nullptr, logits, logits_ld, 0, M,
+                                    d.vocab, d.d_model, s));
   }
   return SSD_OK;
 }
@@ -279,11 +285,11 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   A((void**)&c->step_tokens, sizeof(int32_t) * R);
   A((void**)&c->exclude, sizeof(int32_t) * c->B * (c->K + 1));
   A((void**)&c->h, sizeof(float) * (size_t)R * d.d_model);
-  A((void**)&c->xn, sizeof(float) * (size_t)R * d.d_model);
+  A(&c->xn, sizeof(float) * (size_t)R * d.d_model);
   A((void**)&c->qkv, sizeof(float) * (size_t)R * d.qkv_dim());
   A((void**)&c->q, sizeof(float) * (size_t)R * d.q_dim());
-  A((void**)&c->attn_out, sizeof(float) * (size_t)R * d.q_dim());
-  A((void**)&c->act, sizeof(float) * (size_t)R * d.d_ffn);
+  A(&c->attn_out, sizeof(float) * (size_t)R * d.q_dim());
+  A(&c->act, sizeof(float) * (size_t)R * d.d_ffn);
   A((void**)&c->attn_partial, attention_partial_bytes(R, d.n_q_heads, d.head_dim, c->max_trunk));
   if (st == SSD_OK) {
     hipError_t e = hipMemset(c->trunk_len, 0, sizeof(int32_t) * c->B);
