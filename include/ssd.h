@@ -102,7 +102,8 @@ typedef struct {
   const float* d_glue_logits;  /* [B][K+1][V] logits of the glue extend */
   const float* d_glue_hidden;  /* [B][K+1][d_model] */
   const void* const* h_trunk_k; /* host array [n_layers] of device [B][max_trunk][Hkv][D] (model dtype) */
-  const void* const* h_trunk_v;
+  const void* const* h_trunk_v; /* same layout; contexts served by the fused decode pass (bf16, head_dim 64, at most
+                                   48 rows per pass) keep values transposed: [B][Hkv][D][max_trunk rounded up to 64] */
   int32_t batch, K, F, vocab, d_model, max_trunk;
 } ssd_views;
 
@@ -205,6 +206,15 @@ int ssd_ctx_refresh_bounds(ssd_ctx* ctx, void* stream);
  * the events (set-up, not hot path). */
 int ssd_ctx_enable_timing(ssd_ctx* ctx, int32_t on);
 int ssd_ctx_read_timing(ssd_ctx* ctx, float* h_ms, int32_t n);
+
+/* Measurement aid for contexts served by the fused decode pass (bf16 model, at most 48 rows per pass): with phase
+ * clocks on, every workgroup of the persistent kernel records the device's 100 MHz real-time counter at the entry of
+ * each phase, after the grid barrier in front of it and at the end of its work.  ssd_ctx_read_phase_clocks
+ * SYNCHRONISES the device and copies the clocks of the most recent pass to h_ticks[phase][3][workgroup]
+ * (n = capacity in entries; *n_phases and *n_workgroups receive the extents; phases: 0 embedding, then per layer
+ * {qkv, attention partials, attention merge, o-proj, gate/up, down}, last the LM head).  ESTATE in other contexts. */
+int ssd_ctx_enable_phase_clocks(ssd_ctx* ctx, int32_t on);
+int ssd_ctx_read_phase_clocks(ssd_ctx* ctx, uint64_t* h_ticks, int64_t n, int32_t* n_phases, int32_t* n_workgroups);
 
 int ssd_ctx_views(const ssd_ctx* ctx, ssd_views* out);
 

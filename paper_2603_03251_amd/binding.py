@@ -74,6 +74,9 @@ EXPORTS = {
     "ssd_ctx_enable_timing": (C.c_int, [C.c_void_p, C.c_int32]),
     "ssd_ctx_read_timing": (C.c_int, [C.c_void_p, C.POINTER(C.c_float), C.c_int32]),
     "ssd_ctx_views": (C.c_int, [C.c_void_p, C.POINTER(ssd_views)]),
+    "ssd_ctx_enable_phase_clocks": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ssd_ctx_read_phase_clocks": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_int32),
+                                            C.POINTER(C.c_int32)]),
 }
 
 
@@ -242,6 +245,19 @@ def ssd_ctx_read_timing(ctx: int, K: int):
     buf = (C.c_float * (K + 2))()
     _check(lib.ssd_ctx_read_timing(ctx, buf, K + 2))
     return list(buf)
+
+
+def ssd_ctx_enable_phase_clocks(ctx: int, on: bool) -> None:
+    _check(lib.ssd_ctx_enable_phase_clocks(ctx, 1 if on else 0))
+
+
+def ssd_ctx_read_phase_clocks(ctx: int) -> np.ndarray:
+    """uint64 [phases][3][workgroups] ticks (100 MHz) of the most recent fused pass; synchronises the device."""
+    cap = 1 << 20
+    buf = np.zeros(cap, dtype=np.uint64)
+    n_ph, n_wg = C.c_int32(), C.c_int32()
+    _check(lib.ssd_ctx_read_phase_clocks(ctx, buf.ctypes.data_as(C.c_void_p), cap, C.byref(n_ph), C.byref(n_wg)))
+    return buf[: n_ph.value * 3 * n_wg.value].reshape(n_ph.value, 3, n_wg.value)
 
 
 def ssd_ctx_views(ctx: int) -> ssd_views:

@@ -1,0 +1,95 @@
+// The fused decode pass for bf16 models with few rows (M <= 48): one batched forward of the draft decoder
+// (embedding, every layer, LM head) as ONE persistent kernel of one workgroup per compute unit.  Phases are
+// separated by a grid barrier; workgroups exchange activations through memory that is written once per launch
+// (write-through stores, plain loads), and each workgroup issues the weight loads of its next phase before it
+// waits at the barrier, so the weight stream keeps running across phase boundaries.
+// Shared between the round driver (ssd_api.hip) and kernels_fused.hip.
+#pragma once
+
+#include "common.h"
+
+namespace ssd {
+
+constexpr int kFusedThreads = 512;  // 8 wavefronts; they split the reduction dimension of a weight block
+constexpr int kFusedWaves = 8;
+constexpr int kFusedMaxRows = 48;   // rows of one pass (three 16-row MFMA tiles)
+constexpr int kFusedActPlanes = 2;  // bf16 planes of the SwiGLU output (1 = rounded to bf16, 2 = head + remainder)
+
+// A linear layer in "stream order".  The [N][Kd] matrix is cut into 1 KiB MFMA tiles (16 features x 32 inputs,
+// stored as the 64 lanes of an MFMA 16x16x32 A operand hold them).  A unit is AT feature tiles over the whole
+// reduction dimension; inside a unit wavefront w owns the k-tiles w*KTW .. w*KTW+KTW-1.  Tiles are stored
+// [unit][wavefront][k-tile of the wavefront][feature tile of the unit], so each wavefront streams one contiguous
+// run of memory per unit.  Workgroup g takes units g, g + grid, ...
+struct FusedGemm {
+  const bf16_t* w;
+  int KTW;      // k-tiles per wavefront = Kd / 32 / 8
+  int n_units;  // ceil(NT / AT)
+  int NT;       // real feature tiles (the last unit may hold zero padding)
+};
+
+struct FusedLayer {
+  FusedGemm qkv, o, gu, down;              // gu: unit p = gate tiles 2p, 2p+1 then up tiles 2p, 2p+1
+  const bf16_t *attn_norm, *mlp_norm;      // gains [d]
+  bf16_t *trunk_k;                         // [B][max_trunk][Hkv][64]
+  bf16_t *trunk_vt;                        // [B][Hkv][64][vt_stride]   (values transposed: keys contiguous)
+  bf16_t *suffix_k, *suffix_v;             // [M][suffix_cap][Hkv][64]
+};
+
+struct FusedParams {
+  // model
+  int L, d, qd, kvd, qkvd, ffn, V, Hq, Hkv, G;
+  float eps;
+  const FusedLayer* layers;                // device array [L]
+  const bf16_t *embed, *final_norm;
+  FusedGemm lm;
+  // this pass
+  int M, B, R;                             // rows, sequences, rows per sequence (rows of a sequence are consecutive)
+  const RowDesc* rows;
+  const float* cos_sin;                    // [M][32][2]
+  const int32_t* tokens;
+  int max_trunk, vt_stride, suffix_cap;
+  // attention work split: trunk units (b, kv head, q-tile group, key split) then fresh units (8 (row, head) pairs)
+  int KPU;                                 // trunk keys per unit (multiple of 32)
+  int NS;                                  // key splits; partial NS is the fresh-key partial
+  int QT, QG;                              // 16-row q tiles per (b, kv head), groups of 8 tiles
+  int n_trunk_units, n_pair_units;
+  // workspace, every address written at most once per launch
+  float* h;        // [2L+1][48][d]    residual stream after embed / each o-proj / each down-proj
+  bf16_t* xn;      // [2L+1][2][48*d]  (h * gain of the next norm) as head/remainder planes in B-operand order
+  float* ssq;      // [2L+1][d/16][48] per-feature-tile partial sums of h^2
+  float* qkv;      // [L][48][qkvd]    raw projections (before the norm's row scale and the rotary embedding)
+  bf16_t* att;     // [L][2][48*qd]    attention output planes, B-operand order
+  bf16_t* act;     // [L][planes][48*ffn]
+  float* part_o;   // [L][B][Hkv][NS+1][QG*128][64]
+  float* part_ml;  // [L][B][Hkv][NS+1][QG*128][2]
+  int64_t part_layer_stride;               // in (q-row) entries
+  float* logits;   int64_t logits_ld;      // may be null
+  float* hidden;   int64_t hidden_ld;      // may be null
+  unsigned* bar;                           // grid-barrier words, zeroed before a persistent launch
+  unsigned* err;                           // set to 1 if a bounded wait expired
+  unsigned long long* prof;                // optional [phases][3][nwg] real-time-counter ticks, or null
+  int nwg;
+};
+
+// Phase ids: 0 embed; 1 + 6 l + {0 qkv, 1 attention partials, 2 attention combine, 3 o-proj, 4 gate/up, 5 down};
+// 1 + 6 L LM head.
+__host__ __device__ inline int fused_last_phase(int L) { return 1 + 6 * L; }
+
+// Retile row-major bf16 matrices into stream order.  `mode` 0: rows of src0, src1, src2 concatenated along the
+// feature dimension (rows0, rows1, rows2 features); mode 1: gate/up interleave (src0 = gate, src1 = up, AT = 4).
+int launch_retile_stream(const bf16_t* src0, int rows0, const bf16_t* src1, int rows1, const bf16_t* src2, int rows2,
+                         int mode, int AT, int Kd, bf16_t* dst, hipStream_t s);
+int64_t stream_order_elems(int N, int Kd, int AT);
+// [B][len][Hkv][64] values -> transposed trunk layout
+int launch_copy_v_transposed(bf16_t* trunk_vt, const bf16_t* src, int B, int len, int Hkv, int vt_stride, hipStream_t s);
+
+// feature tiles per unit of each linear layer
+constexpr int kAtQkv = 1, kAtO = 1, kAtGu = 4, kAtDown = 1, kAtLm = 4;
+
+bool fused_supported(const Dims& d, int max_rows);
+// Runs phases [first, last].  persistent = 1: one launch with grid barriers between phases (p.bar must be zero);
+// persistent = 0: one launch per phase (a debugging aid that needs no co-residency).
+int launch_fused(const FusedParams& p, int first, int last, int persistent, hipStream_t s);
+int fused_grid_size(int* out);
+
+}  // namespace ssd

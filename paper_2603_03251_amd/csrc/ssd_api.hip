@@ -7,7 +7,10 @@
 #include <new>
 #include <vector>
 
+#include <stdlib.h>
+
 #include "common.h"
+#include "fused.h"
 
 namespace ssd {
 
@@ -69,6 +72,13 @@ struct ssd_model {
     void *attn_norm, *wqkv, *wo, *mlp_norm, *w_gate, *w_up, *w_down;
   };
   std::vector<Layer> layers;
+  // stream-order copies for the fused pass (bf16 models whose shape it supports)
+  bool fused_ok = false;
+  struct FusedW {
+    FusedGemm qkv, o, gu, down;
+  };
+  std::vector<FusedW> fused_layers;
+  FusedGemm fused_lm{};
 };
 
 struct ssd_ctx {
@@ -103,6 +113,15 @@ struct ssd_ctx {
   void* attn_out;
   void* act;
   float* attn_partial;
+  // fused pass (see fused.h): 0 = per-operator kernels, 1 = one launch per phase, 2 = one persistent launch
+  int fused_mode = 0;
+  int vt_stride = 0;
+  FusedParams fp{};            // everything that does not change between passes
+  FusedLayer* fused_layers_dev = nullptr;
+  unsigned* fused_bar = nullptr;
+  unsigned* fused_err = nullptr;
+  int64_t part_entries = 0;    // per-layer capacity of the attention partial buffers, in query rows
+  unsigned long long* phase_clocks = nullptr;
   const int32_t* forced_keys = nullptr;
   const int32_t* forced_tokens = nullptr;
   // optional per-segment timing of a round: K+3 events (start, glue, fan-out, K steps)
@@ -154,7 +173,63 @@ int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
     SSD_TRY(m->arena.alloc(&L.w_down, (size_t)d.d_model * d.d_ffn * es));
     SSD_TRY(put_linear(d.dtype, w->h_w_down[l], L.w_down, d.d_model, d.d_ffn, s));
   }
+  m->fused_ok = fused_supported(d, 1);
+  if (m->fused_ok) {
+    auto make = [&](FusedGemm* g, const void* s0, int r0, const void* s1, int r1, const void* s2, int r2, int mode, int at,
+                    int Kd) -> int {
+      int N = mode == 0 ? r0 + r1 + r2 : 2 * r0;
+      void* dst = nullptr;
+      SSD_TRY(m->arena.alloc(&dst, (size_t)stream_order_elems(N, Kd, at) * 2));
+      SSD_TRY(launch_retile_stream((const bf16_t*)s0, r0, (const bf16_t*)s1, r1, (const bf16_t*)s2, r2, mode, at, Kd,
+                                   (bf16_t*)dst, s));
+      g->w = (const bf16_t*)dst;
+      g->KTW = Kd / 32 / kFusedWaves;
+      g->NT = (N + 15) / 16;
+      g->n_units = (g->NT + at - 1) / at;
+      return SSD_OK;
+    };
+    m->fused_layers.resize(d.n_layers);
+    for (int l = 0; l < d.n_layers; ++l) {
+      ssd_model::FusedW& F = m->fused_layers[l];
+      SSD_TRY(make(&F.qkv, w->h_wq[l], qd, w->h_wk[l], kvd, w->h_wv[l], kvd, 0, kAtQkv, d.d_model));
+      SSD_TRY(make(&F.o, w->h_wo[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtO, qd));
+      SSD_TRY(make(&F.gu, w->h_w_gate[l], d.d_ffn, w->h_w_up[l], d.d_ffn, nullptr, 0, 1, kAtGu, d.d_model));
+      SSD_TRY(make(&F.down, w->h_w_down[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtDown, d.d_ffn));
+    }
+    SSD_TRY(make(&m->fused_lm, head_src, d.vocab, nullptr, 0, nullptr, 0, 0, kAtLm, d.d_model));
+  }
   return SSD_OK;
+}
+
+// The same pass through the fused kernel: attention work split for this pass's shape, then one launch.
+int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int max_vis, float* logits, int64_t logits_ld,
+                  float* hidden, int64_t hidden_ld, hipStream_t s) {
+  FusedParams p = c->fp;
+  p.M = M;
+  p.R = rows_per_seq;
+  p.tokens = tokens;
+  const int RG = p.R * p.G;
+  p.QT = (RG + 15) / 16;
+  p.QG = (p.QT + 7) / 8;
+  const int per_split = p.B * p.Hkv * p.QG;
+  const int ns_target = p.nwg / per_split > 1 ? p.nwg / per_split : 1;
+  const int p_ub = max_vis > 1 ? max_vis : 1;
+  int kpu = 64 * ((p_ub + 64 * ns_target - 1) / (64 * ns_target));
+  p.KPU = kpu < 64 ? 64 : kpu;
+  p.NS = (p_ub + p.KPU - 1) / p.KPU;
+  p.n_trunk_units = per_split * p.NS;
+  p.n_pair_units = (M * p.Hq + kFusedWaves - 1) / kFusedWaves;
+  if ((int64_t)p.B * p.Hkv * (p.NS + 1) * p.QG * 128 > c->part_entries) {
+    set_error("fused pass: attention partial buffer too small (%d splits, %d q groups)", p.NS, p.QG);
+    return SSD_ESTATE;
+  }
+  p.logits = logits;
+  p.logits_ld = logits_ld;
+  p.hidden = hidden;
+  p.hidden_ld = hidden_ld;
+  const int last = (logits || hidden) ? fused_last_phase(p.L) : fused_last_phase(p.L) - 1;
+  if (c->fused_mode == 2) SSD_TRY(launch_fill_i32((int32_t*)c->fused_bar, 0, 1024, s));
+  return launch_fused(p, 0, last, c->fused_mode == 2, s);
 }
 
 // One batched pass of the decoder over `M` rows whose descriptors and rotary tables are already in ctx->rows /
@@ -163,6 +238,7 @@ int forward_rows(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int
                  int64_t logits_ld, float* hidden, int64_t hidden_ld, hipStream_t s) {
   const ssd_model* m = c->model;
   const Dims& d = m->dims;
+  if (c->fused_mode) return fused_forward(c, M, tokens, rows_per_seq, max_vis, logits, logits_ld, hidden, hidden_ld, s);
   const int dt = d.dtype;
   const int64_t R = c->max_rows;     // plane stride of an activation buffer = R * columns
   SSD_TRY(launch_embed(dt, m->embed, tokens, c->h, M, d.d_model, d.vocab, s));
@@ -199,6 +275,66 @@ int extend_rows(ssd_ctx* c, const int32_t* tokens, int T, int offset, float* log
   const Dims& d = c->model->dims;
   SSD_TRY(launch_setup_extend_rows(c->rows, c->cos_sin, c->trunk_len, c->B, T, offset, d.head_dim / 2, d.rope_theta, s));
   return forward_rows(c, c->B * T, tokens, T, c->trunk_ub + offset + T, logits, d.vocab, hidden, d.d_model, s);
+}
+
+// Workspace and constant parameters of the fused pass.
+int fused_setup(ssd_ctx* c) {
+  const ssd_model* m = c->model;
+  const Dims& d = m->dims;
+  const int L = d.n_layers;
+  FusedParams& p = c->fp;
+  SSD_TRY(fused_grid_size(&p.nwg));
+  p.L = L; p.d = d.d_model; p.qd = d.q_dim(); p.kvd = d.kv_dim(); p.qkvd = d.qkv_dim(); p.ffn = d.d_ffn; p.V = d.vocab;
+  p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.G = d.n_q_heads / d.n_kv_heads; p.eps = d.rms_eps;
+  p.embed = (const bf16_t*)m->embed;
+  p.final_norm = (const bf16_t*)m->final_norm;
+  p.lm = m->fused_lm;
+  p.B = c->B;
+  p.rows = c->rows;
+  p.cos_sin = c->cos_sin;
+  p.max_trunk = c->max_trunk;
+  p.vt_stride = c->vt_stride;
+  p.suffix_cap = c->K;
+  const size_t MPr = kFusedMaxRows;
+  const size_t nv = 2 * (size_t)L + 1;
+  int st = SSD_OK;
+  auto A = [&](void** q, size_t bytes) { if (st == SSD_OK) st = c->arena.alloc(q, bytes); };
+  A((void**)&p.h, nv * MPr * p.d * 4);
+  A((void**)&p.xn, nv * 2 * MPr * p.d * 2);
+  A((void**)&p.ssq, nv * (p.d / 16) * MPr * 4);
+  A((void**)&p.qkv, (size_t)L * MPr * p.qkvd * 4);
+  A((void**)&p.att, (size_t)L * 2 * MPr * p.qd * 2);
+  A((void**)&p.act, (size_t)L * kFusedActPlanes * MPr * p.ffn * 2);
+  // attention partials: at most nwg / (B Hkv QG) key splits plus the fresh-key partial, QG * 128 query rows each
+  const int r_max = (c->K + 1) * c->F > c->K + 1 ? (c->K + 1) * c->F : c->K + 1;
+  const int qg_max = ((r_max * p.G + 15) / 16 + 7) / 8;
+  c->part_entries = (int64_t)128 * (p.nwg + (int64_t)2 * p.B * p.Hkv * qg_max);
+  p.part_layer_stride = c->part_entries;
+  A((void**)&p.part_o, (size_t)L * c->part_entries * 64 * 4);
+  A((void**)&p.part_ml, (size_t)L * c->part_entries * 2 * 4);
+  A((void**)&c->fused_bar, 4096 + 256);
+  A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L);
+  SSD_TRY(st);
+  c->fused_err = c->fused_bar + 1024;
+  p.bar = c->fused_bar;
+  p.err = c->fused_err;
+  SSD_HIP(hipMemset(c->fused_bar, 0, 4096 + 256));
+  std::vector<FusedLayer> host(L);
+  const size_t kvd = (size_t)d.kv_dim();
+  for (int l = 0; l < L; ++l) {
+    FusedLayer& F = host[l];
+    F.qkv = m->fused_layers[l].qkv; F.o = m->fused_layers[l].o; F.gu = m->fused_layers[l].gu; F.down = m->fused_layers[l].down;
+    F.attn_norm = (const bf16_t*)m->layers[l].attn_norm;
+    F.mlp_norm = (const bf16_t*)m->layers[l].mlp_norm;
+    F.trunk_k = (bf16_t*)c->trunk_k[l]; F.trunk_vt = (bf16_t*)c->trunk_v[l];
+    F.suffix_k = (bf16_t*)c->suffix_k[l]; F.suffix_v = (bf16_t*)c->suffix_v[l];
+    // masked keys still feed the value MFMA with weight 0: everything there must be finite
+    SSD_HIP(hipMemset(c->trunk_k[l], 0, (size_t)c->B * c->max_trunk * kvd * 2));
+    SSD_HIP(hipMemset(c->trunk_v[l], 0, (size_t)c->B * kvd * c->vt_stride * 2));
+  }
+  SSD_HIP(hipMemcpy(c->fused_layers_dev, host.data(), sizeof(FusedLayer) * L, hipMemcpyHostToDevice));
+  p.layers = c->fused_layers_dev;
+  return SSD_OK;
 }
 
 }  // namespace
@@ -268,9 +404,17 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   A((void**)&c->trunk_len, sizeof(int32_t) * c->B);
   c->trunk_k.resize(d.n_layers); c->trunk_v.resize(d.n_layers);
   c->suffix_k.resize(d.n_layers); c->suffix_v.resize(d.n_layers);
+  // the fused pass serves every pass of a context it fits (SSD_FUSED=off|phases|persistent overrides, a debugging aid)
+  c->fused_mode = model->fused_ok && fused_supported(d, c->max_rows) ? 2 : 0;
+  if (const char* env = getenv("SSD_FUSED")) {
+    if (!strcmp(env, "off")) c->fused_mode = 0;
+    else if (!strcmp(env, "phases") && c->fused_mode) c->fused_mode = 1;
+  }
+  c->vt_stride = (c->max_trunk + 63) / 64 * 64;
   for (int l = 0; l < d.n_layers; ++l) {
     A(&c->trunk_k[l], (size_t)c->B * c->max_trunk * kvd * es);
-    A(&c->trunk_v[l], (size_t)c->B * c->max_trunk * kvd * es);
+    // fused contexts keep the values transposed: [B][Hkv][D][vt_stride]
+    A(&c->trunk_v[l], c->fused_mode ? (size_t)c->B * kvd * c->vt_stride * es : (size_t)c->B * c->max_trunk * kvd * es);
     A(&c->suffix_k[l], (size_t)c->M * c->K * kvd * es);
     A(&c->suffix_v[l], (size_t)c->M * c->K * kvd * es);
   }
@@ -291,6 +435,7 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   A(&c->attn_out, sizeof(float) * (size_t)R * d.q_dim());
   A(&c->act, sizeof(float) * (size_t)R * d.d_ffn);
   A((void**)&c->attn_partial, attention_partial_bytes(R, d.n_q_heads, d.head_dim, c->max_trunk));
+  if (st == SSD_OK && c->fused_mode) st = fused_setup(c);
   if (st == SSD_OK) {
     hipError_t e = hipMemset(c->trunk_len, 0, sizeof(int32_t) * c->B);
     if (e != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(e)); st = SSD_EHIP; }
@@ -344,7 +489,11 @@ int ssd_ctx_load_trunk(ssd_ctx* c, const void* d_k, const void* d_v, int32_t len
   const size_t per_layer = (size_t)c->B * len * d.kv_dim() * es;
   for (int l = 0; l < d.n_layers; ++l) {
     SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_k[l], (const char*)d_k + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
-    SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_v[l], (const char*)d_v + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
+    if (c->fused_mode)
+      SSD_TRY(launch_copy_v_transposed((bf16_t*)c->trunk_v[l], (const bf16_t*)((const char*)d_v + l * per_layer), c->B, len,
+                                       d.n_kv_heads, c->vt_stride, s));
+    else
+      SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_v[l], (const char*)d_v + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
   }
   SSD_TRY(launch_fill_i32(c->trunk_len, len, c->B, s));
   c->trunk_ub = len;
@@ -431,6 +580,14 @@ int ssd_ctx_refresh_bounds(ssd_ctx* c, void* stream) {
   int ub = 0;
   for (int v : lens) ub = v > ub ? v : ub;
   c->trunk_ub = ub;
+  if (c->fused_mode) {
+    unsigned e = 0;
+    SSD_HIP(hipMemcpy(&e, c->fused_err, sizeof(e), hipMemcpyDeviceToHost));
+    if (e) {
+      set_error("a grid barrier of the fused pass timed out");
+      return SSD_EHIP;
+    }
+  }
   return SSD_OK;
 }
 
@@ -444,6 +601,30 @@ int ssd_ctx_enable_timing(ssd_ctx* c, int32_t on) {
     }
   }
   c->timing = on != 0;
+  return SSD_OK;
+}
+
+int ssd_ctx_enable_phase_clocks(ssd_ctx* c, int32_t on) {
+  SSD_CHECK_ARG(c, "ssd_ctx_enable_phase_clocks: null context");
+  if (!c->fused_mode) { set_error("phase clocks exist only in contexts served by the fused pass"); return SSD_ESTATE; }
+  if (on && !c->phase_clocks) {
+    const size_t n = (size_t)(fused_last_phase(c->fp.L) + 1) * 3 * c->fp.nwg;
+    SSD_TRY(c->arena.alloc((void**)&c->phase_clocks, n * sizeof(unsigned long long)));
+    SSD_HIP(hipMemset(c->phase_clocks, 0, n * sizeof(unsigned long long)));
+  }
+  c->fp.prof = on ? c->phase_clocks : nullptr;
+  return SSD_OK;
+}
+
+int ssd_ctx_read_phase_clocks(ssd_ctx* c, uint64_t* h_ticks, int64_t n, int32_t* n_phases, int32_t* n_workgroups) {
+  SSD_CHECK_ARG(c && h_ticks && n_phases && n_workgroups, "ssd_ctx_read_phase_clocks: null argument");
+  if (!c->phase_clocks) { set_error("phase clocks are not enabled"); return SSD_ESTATE; }
+  *n_phases = fused_last_phase(c->fp.L) + 1;
+  *n_workgroups = c->fp.nwg;
+  const int64_t need = (int64_t)*n_phases * 3 * c->fp.nwg;
+  SSD_CHECK_ARG(n >= need, "ssd_ctx_read_phase_clocks: buffer of %lld entries, %lld needed", (long long)n, (long long)need);
+  SSD_HIP(hipDeviceSynchronize());
+  SSD_HIP(hipMemcpy(h_ticks, c->phase_clocks, (size_t)need * sizeof(uint64_t), hipMemcpyDeviceToHost));
   return SSD_OK;
 }
 
