@@ -102,8 +102,9 @@ typedef struct {
   const float* d_glue_logits;  /* [B][K+1][V] logits of the glue extend */
   const float* d_glue_hidden;  /* [B][K+1][d_model] */
   const void* const* h_trunk_k; /* host array [n_layers] of device [B][max_trunk][Hkv][D] (model dtype) */
-  const void* const* h_trunk_v; /* same layout; contexts served by the fused decode pass (bf16, head_dim 64, at most
-                                   48 rows per pass) keep values transposed: [B][Hkv][D][max_trunk rounded up to 64] */
+  const void* const* h_trunk_v; /* same layout.  Contexts served by the fused decode pass (bf16, head_dim 64, at most 48
+                                   rows per pass) keep both head-major with T = max_trunk rounded up to 64: keys
+                                   [B][Hkv][T][D], values transposed per 32-position block [B][Hkv][T/32][D][32] */
   int32_t batch, K, F, vocab, d_model, max_trunk;
 } ssd_views;
 
@@ -209,8 +210,9 @@ int ssd_ctx_read_timing(ssd_ctx* ctx, float* h_ms, int32_t n);
 
 /* Measurement aid for contexts served by the fused decode pass (bf16 model, at most 48 rows per pass): with phase
  * clocks on, every workgroup of the persistent kernel records the device's 100 MHz real-time counter at the entry of
- * each phase, after the grid barrier in front of it and at the end of its work.  ssd_ctx_read_phase_clocks
- * SYNCHRONISES the device and copies the clocks of the most recent pass to h_ticks[phase][3][workgroup]
+ * each phase (slot 0), after the grid barrier in front of it (1) and at the end of its work (2); slots 3..7 are
+ * probes inside some phases (unused slots keep their last value).  ssd_ctx_read_phase_clocks
+ * SYNCHRONISES the device and copies the clocks of the most recent pass to h_ticks[phase][8][workgroup]
  * (n = capacity in entries; *n_phases and *n_workgroups receive the extents; phases: 0 embedding, then per layer
  * {qkv, attention partials, attention merge, o-proj, gate/up, down}, last the LM head).  ESTATE in other contexts. */
 int ssd_ctx_enable_phase_clocks(ssd_ctx* ctx, int32_t on);

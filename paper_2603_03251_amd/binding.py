@@ -252,12 +252,12 @@ def ssd_ctx_enable_phase_clocks(ctx: int, on: bool) -> None:
 
 
 def ssd_ctx_read_phase_clocks(ctx: int) -> np.ndarray:
-    """uint64 [phases][3][workgroups] ticks (100 MHz) of the most recent fused pass; synchronises the device."""
+    """uint64 [phases][8][workgroups] ticks (100 MHz) of the most recent fused pass; synchronises the device."""
     cap = 1 << 20
     buf = np.zeros(cap, dtype=np.uint64)
     n_ph, n_wg = C.c_int32(), C.c_int32()
     _check(lib.ssd_ctx_read_phase_clocks(ctx, buf.ctypes.data_as(C.c_void_p), cap, C.byref(n_ph), C.byref(n_wg)))
-    return buf[: n_ph.value * 3 * n_wg.value].reshape(n_ph.value, 3, n_wg.value)
+    return buf[: n_ph.value * 8 * n_wg.value].reshape(n_ph.value, 8, n_wg.value)
 
 
 def ssd_ctx_views(ctx: int) -> ssd_views:

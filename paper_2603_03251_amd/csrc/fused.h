@@ -13,7 +13,8 @@ namespace ssd {
 constexpr int kFusedThreads = 512;  // 8 wavefronts; they split the reduction dimension of a weight block
 constexpr int kFusedWaves = 8;
 constexpr int kFusedMaxRows = 48;   // rows of one pass (three 16-row MFMA tiles)
-constexpr int kFusedActPlanes = 2;  // bf16 planes of the SwiGLU output (1 = rounded to bf16, 2 = head + remainder)
+constexpr int kFusedActPlanes = 2;
+constexpr int kFusedClockSlots = 8;  // clock probes per phase and workgroup (see stamp())  // bf16 planes of the SwiGLU output (1 = rounded to bf16, 2 = head + remainder)
 
 // A linear layer in "stream order".  The [N][Kd] matrix is cut into 1 KiB MFMA tiles (16 features x 32 inputs,
 // stored as the 64 lanes of an MFMA 16x16x32 A operand hold them).  A unit is AT feature tiles over the whole
@@ -22,16 +23,18 @@ constexpr int kFusedActPlanes = 2;  // bf16 planes of the SwiGLU output (1 = rou
 // run of memory per unit.  Workgroup g takes units g, g + grid, ...
 struct FusedGemm {
   const bf16_t* w;
-  int KTW;      // k-tiles per wavefront = Kd / 32 / 8
-  int n_units;  // ceil(NT / AT)
+  int KTW;      // k-tiles per wavefront and unit = Kd / 32 / 8 / KS
+  int n_units;  // ceil(NT / AT) * KS
   int NT;       // real feature tiles (the last unit may hold zero padding)
+  int KS;       // k-slices: with KS > 1 unit u = (tile group u / KS, slice u % KS) covers 1/KS of the reduction dimension
+                // and slice 0 adds the others' partial tiles in order; needs n_units <= grid (one unit per workgroup)
 };
 
 struct FusedLayer {
   FusedGemm qkv, o, gu, down;              // gu: unit p = gate tiles 2p, 2p+1 then up tiles 2p, 2p+1
   const bf16_t *attn_norm, *mlp_norm;      // gains [d]
-  bf16_t *trunk_k;                         // [B][max_trunk][Hkv][64]
-  bf16_t *trunk_vt;                        // [B][Hkv][64][vt_stride]   (values transposed: keys contiguous)
+  bf16_t *trunk_k;                         // [B][Hkv][vt_stride][64]              (head-major)
+  bf16_t *trunk_vt;                        // [B][Hkv][vt_stride / 32][64][32]     (values transposed per 32-key block)
   bf16_t *suffix_k, *suffix_v;             // [M][suffix_cap][Hkv][64]
 };
 
@@ -48,11 +51,15 @@ struct FusedParams {
   const float* cos_sin;                    // [M][32][2]
   const int32_t* tokens;
   int max_trunk, vt_stride, suffix_cap;
-  // attention work split: trunk units (b, kv head, q-tile group, key split) then fresh units (8 (row, head) pairs)
-  int KPU;                                 // trunk keys per unit (multiple of 32)
-  int NS;                                  // key splits; partial NS is the fresh-key partial
-  int QT, QG;                              // 16-row q tiles per (b, kv head), groups of 8 tiles
-  int n_trunk_units, n_pair_units;
+  // attention work split: unit = (sequence, KV head, 16-row query tile, key split)
+  int KPU;                                 // stored trunk keys per split (multiple of 32)
+  int NS;                                  // key splits; 1 = the attention phase writes the final output
+  int QT;                                  // query tiles per (sequence, KV head) = ceil(R G / 16)
+  int SL;                                  // fresh-key slots per branch row (8 or 16)
+  int is_branch;                           // 1: branch rows (private suffix), 0: extend rows (causal among themselves)
+  int suffix_len;                          // branch rows: private positions a row sees, its own token included
+  int tv_ub;                               // host bound of the stored trunk keys any row sees (loop counts only)
+  int n_attn_units, n_pair_units;          // B Hkv QT NS attention units; ceil(M Hq / 8) merge units
   // workspace, every address written at most once per launch
   float* h;        // [2L+1][48][d]    residual stream after embed / each o-proj / each down-proj
   bf16_t* xn;      // [2L+1][2][48*d]  (h * gain of the next norm) as head/remainder planes in B-operand order
@@ -60,28 +67,33 @@ struct FusedParams {
   float* qkv;      // [L][48][qkvd]    raw projections (before the norm's row scale and the rotary embedding)
   bf16_t* att;     // [L][2][48*qd]    attention output planes, B-operand order
   bf16_t* act;     // [L][planes][48*ffn]
-  float* part_o;   // [L][B][Hkv][NS+1][QG*128][64]
-  float* part_ml;  // [L][B][Hkv][NS+1][QG*128][2]
+  float* fix_buf;  // [L][3][fix_stride]  partial tiles of K-split linear layers (qkv, o, down)
+  unsigned* fix_cnt;  // [L][3][fix_cnt_stride] published slices per tile group, zeroed before every launch
+  int64_t fix_stride, fix_cnt_stride;
+  float* part_o;   // [L][B][Hkv][NS][QT*16][64]  partial softmaxes of the key splits (NS > 1 only)
+  float* part_ml;  // [L][B][Hkv][NS][QT*16][2]
   int64_t part_layer_stride;               // in (q-row) entries
   float* logits;   int64_t logits_ld;      // may be null
   float* hidden;   int64_t hidden_ld;      // may be null
   unsigned* bar;                           // grid-barrier words, zeroed before a persistent launch
   unsigned* err;                           // set to 1 if a bounded wait expired
-  unsigned long long* prof;                // optional [phases][3][nwg] real-time-counter ticks, or null
+  unsigned long long* prof;                // optional [phases][kFusedClockSlots][nwg] real-time-counter ticks, or null
   int nwg;
+  int deep;                                // 1: every linear layer has a multiple of 4 k-tiles per wavefront and unit
 };
 
-// Phase ids: 0 embed; 1 + 6 l + {0 qkv, 1 attention partials, 2 attention combine, 3 o-proj, 4 gate/up, 5 down};
+// Phase ids: 0 embed; 1 + 6 l + {0 qkv, 1 attention, 2 merge of key splits (NS > 1 only), 3 o-proj, 4 gate/up, 5 down};
 // 1 + 6 L LM head.
 __host__ __device__ inline int fused_last_phase(int L) { return 1 + 6 * L; }
 
 // Retile row-major bf16 matrices into stream order.  `mode` 0: rows of src0, src1, src2 concatenated along the
 // feature dimension (rows0, rows1, rows2 features); mode 1: gate/up interleave (src0 = gate, src1 = up, AT = 4).
 int launch_retile_stream(const bf16_t* src0, int rows0, const bf16_t* src1, int rows1, const bf16_t* src2, int rows2,
-                         int mode, int AT, int Kd, bf16_t* dst, hipStream_t s);
+                         int mode, int AT, int KS, int Kd, bf16_t* dst, hipStream_t s);
 int64_t stream_order_elems(int N, int Kd, int AT);
-// [B][len][Hkv][64] values -> transposed trunk layout
-int launch_copy_v_transposed(bf16_t* trunk_vt, const bf16_t* src, int B, int len, int Hkv, int vt_stride, hipStream_t s);
+// [B][len][Hkv][64] keys and values -> the trunk layouts of FusedLayer
+int launch_copy_kv_fused(bf16_t* trunk_k, bf16_t* trunk_vt, const bf16_t* src_k, const bf16_t* src_v, int B, int len, int Hkv,
+                         int vt_stride, hipStream_t s);
 
 // feature tiles per unit of each linear layer
 constexpr int kAtQkv = 1, kAtO = 1, kAtGu = 4, kAtDown = 1, kAtLm = 4;

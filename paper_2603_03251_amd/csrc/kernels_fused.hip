@@ -40,6 +40,7 @@ typedef __attribute__((address_space(1))) bf16_t gbf16;
 
 constexpr int MP = kFusedMaxRows;
 constexpr int NPA = kFusedActPlanes;
+static_assert(kFusedActPlanes == 2, "the down-projection shares the two-plane streaming loop");
 constexpr unsigned kSpinLimit = 4000000u;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -65,10 +66,10 @@ __device__ __forceinline__ uint64_t pack_bf16x4(bf16_t a, bf16_t b, bf16_t c, bf
 }
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Optional phase clocks (a measurement aid): [phase][3][workgroup] ticks of the 100 MHz real-time counter at
-// phase entry, after the grid barrier, and at the end of the phase's work.
+// Optional phase clocks (a measurement aid): [phase][slot][workgroup] ticks of the 100 MHz real-time counter; slot 0
+// phase entry, 1 after the grid barrier, 2 end of the phase's work, 3.. probes inside a phase.
 __device__ __forceinline__ void stamp(const FusedParams& p, int ph, int which) {
-  if (p.prof && threadIdx.x == 0) p.prof[((int64_t)ph * 3 + which) * p.nwg + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
+  if (p.prof && threadIdx.x == 0) p.prof[((int64_t)ph * kFusedClockSlots + which) * p.nwg + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
 }
 
 // Offset of element (row m, input k) in a B-operand-ordered activation plane with MT row tiles:
@@ -121,6 +122,7 @@ __device__ __forceinline__ bool grid_wait(Grid& g) {
         *g.dead = 1;
         break;
       }
+      __builtin_amdgcn_s_sleep(20);   // idle workgroups must not flood the memory fabric with polls
     }
   }
   wg_barrier();
@@ -131,9 +133,19 @@ __device__ __forceinline__ bool grid_wait(Grid& g) {
 __device__ __forceinline__ void compute_row_scales(const FusedParams& p, const float* ssq, float* r_s) {
   const int n_tiles = p.d >> 4;
   const int m = threadIdx.x >> 3, part = threadIdx.x & 7;
+  const gfloat* src = (const gfloat*)ssq + (m < p.M ? m : 0);
   float s = 0.f;
-  if (m < p.M)
-    for (int j = part; j < n_tiles; j += 8) s += ((const gfloat*)ssq)[j * MP + m];
+  // 16 independent loads at a time: a chain of dependent loads would cost a memory latency each
+  for (int j0 = part; j0 < n_tiles; j0 += 128) {
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int j = j0 + 8 * i;
+      v[i] = src[(j < n_tiles ? j : j0) * MP];
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += j0 + 8 * i < n_tiles ? v[i] : 0.f;
+  }
   s += __shfl_xor(s, 1);
   s += __shfl_xor(s, 2);
   s += __shfl_xor(s, 4);
@@ -183,6 +195,8 @@ struct EpiArgs {
   bf16_t* xn_out;
   float* ssq_out;
   bf16_t* act_out;     // SWIGLU
+  float* fix_buf;      // K-split: [tile group][slice][tile][64 lanes][4] partial tiles of this phase instance
+  unsigned* fix_cnt;   // K-split: [tile group] slices that have published, zero at launch
 };
 
 template <int AT, int MT, int NP>
@@ -193,9 +207,12 @@ struct Chunk {
 
 // One linear layer over the workgroup's units.  bsrc: activation planes in B-operand order, `bplane` elements apart.
 // ssq_in: if not null, row scales are computed into r_s after the barrier (SWIGLU and LOGITS need them).
-template <int AT, int MT, int NP, int D, int EPI>
+// AT = 1 serves the qkv, o and down projections (epilogue EPI_QKV / EPI_RESID), AT = 4 the gate/up projection and the
+// LM head (EPI_SWIGLU / EPI_LOGITS).  The epilogue kind is a run-time argument so that each of the two streaming loops
+// exists once in the kernel: its code has to stay resident in the instruction cache across the layers.
+template <int AT, int MT, int NP, int D>
 __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm g, const bf16_t* bsrc, int64_t bplane,
-                                           const EpiArgs& e, Grid& grid, bool do_wait, f32x4* red, float* r_s,
+                                           const int EPI, const EpiArgs& e, Grid& grid, bool do_wait, f32x4* red, float* r_s,
                                            const float* ssq_in, int ph) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int KTW = g.KTW;
@@ -213,7 +230,9 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
     a_next += AT * 64;
     if (++a_i == KTW) { a_i = 0; a_next += a_unit_jump; }
   };
-  const gbf16x8* b_first = (const gbf16x8*)(bsrc + ((int64_t)(wave * KTW) * MT * 64 + lane) * 8);
+  // K-split (g.KS > 1, at most one unit per workgroup): unit u = (feature-tile group u / KS, k-slice u % KS)
+  const int KS = g.KS, ks = KS > 1 ? (int)blockIdx.x % KS : 0;
+  const gbf16x8* b_first = (const gbf16x8*)(bsrc + ((int64_t)((ks * kFusedWaves + wave) * KTW) * MT * 64 + lane) * 8);
   const int64_t bplane_v = bplane / 8;
   int b_i = 0;
   auto load_b = [&](Chunk<AT, MT, NP>& ck) {
@@ -264,24 +283,58 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
         acc[j][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
       }
     wg_barrier();
-    constexpr int NOUT = EPI == EPI_SWIGLU ? 2 * MT : AT * MT;
+    const int NOUT = EPI == EPI_SWIGLU ? 2 * MT : AT * MT;
+    const int tg = KS > 1 ? unit / KS : unit;     // feature-tile group of the unit
+    if (KS > 1) {
+      // Ordered fix-up of the K-split: slices 1.. publish their reduced tiles and count themselves in; slice 0 waits
+      // for the count, adds the partials in slice order (the result does not depend on timing) and runs the epilogue.
+      float* fix = e.fix_buf + ((int64_t)tg * KS) * (AT * MT) * 256;
+      if (ks > 0) {
+        for (int idx = wave; idx < AT * MT; idx += kFusedWaves) {
+          f32x4 v = red[idx * 64 + lane];
+#pragma unroll
+          for (int w = 1; w < kFusedWaves; ++w) v += red[(w * (AT * MT) + idx) * 64 + lane];
+          st_f32x4(fix + ((int64_t)ks * (AT * MT) + idx) * 256 + lane * 4, v);
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        wg_barrier();
+        if (threadIdx.x == 0) __hip_atomic_fetch_add(e.fix_cnt + tg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+      }
+      if (threadIdx.x == 0) {
+        unsigned spins = 0;
+        while (__hip_atomic_load(e.fix_cnt + tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (unsigned)(KS - 1)) {
+          if (++spins > kSpinLimit) {
+            __hip_atomic_store(grid.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *grid.dead = 1;
+            break;
+          }
+          __builtin_amdgcn_s_sleep(1);
+        }
+      }
+      wg_barrier();
+    }
     for (int idx = wave; idx < NOUT; idx += kFusedWaves) {
       const int j = idx / MT, t = idx - j * MT;
       f32x4 v = red[(j * MT + t) * 64 + lane];
 #pragma unroll
       for (int w = 1; w < kFusedWaves; ++w) v += red[(w * (AT * MT) + j * MT + t) * 64 + lane];
+      if (KS > 1) {
+        const float* fix = e.fix_buf + ((int64_t)tg * KS) * (AT * MT) * 256;
+        for (int q = 1; q < KS; ++q) v += *(const gf32x4*)(fix + ((int64_t)q * (AT * MT) + idx) * 256 + lane * 4);
+      }
       const int m = t * 16 + (lane & 15);
       const int f4 = (lane >> 4) * 4;
-      if (EPI == EPI_QKV) {
-        const int n = (unit * AT + j) * 16 + f4;
+      if (AT == 1 && EPI == EPI_QKV) {
+        const int n = (tg * AT + j) * 16 + f4;
         if (m < p.M) st_f32x4(e.out + (int64_t)m * e.ld + n, v);
-      } else if (EPI == EPI_RESID) {
-        const int tile = unit * AT + j;
+      } else if (AT == 1 && EPI == EPI_RESID) {
+        const int tile = tg * AT + j;
         const int n = tile * 16 + f4;
         f32x4 ho = (f32x4){0.f, 0.f, 0.f, 0.f};
         if (m < p.M) ho = *(const gf32x4*)(e.h_in + (int64_t)m * p.d + n);
         resid_store<MT>(p, ho + v, m, n, lane, e.gain, e.h_out, e.xn_out, e.ssq_out, tile);
-      } else if (EPI == EPI_SWIGLU) {
+      } else if (AT == 4 && EPI == EPI_SWIGLU) {
         // tiles 0,1 of the unit are gate, 2,3 the matching up tiles; idx = (gate tile j, row tile t)
         f32x4 u = red[((j + 2) * MT + t) * 64 + lane];
 #pragma unroll
@@ -301,7 +354,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
           st_u64(e.act_out + off, pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
           if (NPA == 2) st_u64(e.act_out + (int64_t)MP * p.ffn + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
         }
-      } else {
+      } else if (AT == 4) {
         const int tile = unit * AT + j;
         const int n = tile * 16 + f4;
         if (m < p.M && tile < g.NT) {
@@ -350,51 +403,191 @@ __device__ __forceinline__ int trunk_visible(const RowDesc& r, int m, int R) {
   return r.is_branch ? r.vis : r.vis - 1 - (m % R);
 }
 
-// Rotary embedding of element d (0..63) of a head, given the element and its partner (d ^ 32).
-__device__ __forceinline__ float rope_elem(float own, float partner, float c, float s, int d) {
-  return d < 32 ? own * c - partner * s : own * c + partner * s;
+struct OnlineSoftmax {
+  float m_run, l_run;   // running maximum (base-2 exponent) and this lane's share of the running sum
+  f32x4 acc[4];         // O^T: dims dt*16 + (lane>>4)*4 + r of query row lane & 15
+};
+
+// One 32-key block: scores S[tile][r] of this lane's query row against keys (lane>>4)*8 + tile*4 + r of the block,
+// `vis` = visibility of those 8 keys, vt[dt] = V^T operands of the block.
+template <int NPP>
+__device__ __forceinline__ void softmax_block(OnlineSoftmax& st, const f32x4 S[2], const bool vis[8], const bf16x8 vt[4]) {
+  float sv[8];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float x = i < 4 ? S[0][i] : S[1][i - 4];
+    sv[i] = vis[i] ? x : -INFINITY;
+    mx = fmaxf(mx, sv[i]);
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(st.m_run, mx);
+  const float m_use = m_new == -INFINITY ? 0.f : m_new;
+  const float corr = exp2_fast(st.m_run - m_use);
+  Bf8 ph, pl;
+  float psum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float pe = exp2_fast(sv[i] - m_use);
+    psum += pe;
+    ph.u[i] = f32_to_bf16(pe);
+    pl.u[i] = f32_to_bf16(pe - bf16_to_f32(ph.u[i]));
+  }
+  st.l_run = st.l_run * corr + psum;
+  st.m_run = m_new;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) {
+    st.acc[dt] = st.acc[dt] * corr;
+    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[dt], ph.v, st.acc[dt], 0, 0, 0);
+    if (NPP == 2) st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[dt], pl.v, st.acc[dt], 0, 0, 0);
+  }
 }
 
-// Trunk unit: all query rows of (sequence b, KV head hk) in q tiles qg*8 .. qg*8+7 (one per wavefront) against the
-// stored trunk keys [s KPU, (s+1) KPU).
-template <int NPQ, int NPP>
-__device__ __forceinline__ void attn_trunk_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
-                                                const float* r_s, float* part_o, float* part_ml) {
+template <int NPQ>
+__device__ __forceinline__ f32x4 score_tile(bf16x8 k0, bf16x8 k1, const Bf8 qh[2], const Bf8 ql[2]) {
+  f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
+  s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qh[0].v, s, 0, 0, 0);
+  s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qh[1].v, s, 0, 0, 0);
+  if (NPQ == 2) {
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[0].v, s, 0, 0, 0);
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[1].v, s, 0, 0, 0);
+  }
+  return s;
+}
+
+// Attention unit = (sequence b, KV head hk, 16-row query tile qt, key split s).  A query tile holds 16 / G whole
+// rows with all G query heads of the group.  The 8 wavefronts take the 32-key blocks of the unit round-robin:
+// first the stored trunk keys of the split, then (split 0 only) the blocks of "fresh" keys: keys that exist only in
+// this pass or only for one row.  Branch rows: fresh key f = (row of the tile f / SL, slot f % SL), the row's
+// stored private suffix followed by its own token, visible to that row alone.  Extend rows: fresh key f = token f
+// of this pass, visible to rows f and later.  All 512 threads stage the fresh K rows and V^T columns in LDS (and
+// append the new K/V to the suffix or the trunk).  A dependent global load costs more than a microsecond here, so
+// every load whose address is pure index arithmetic (row descriptors, the query tile, the first trunk blocks, the
+// fresh-key sources) is issued up front; loop counts come from the host's bound on the visible trunk, the true
+// visibility only masks.  The 8 partial softmaxes meet in LDS; with one split the result goes straight to the
+// o-projection's operand planes, otherwise to the partial buffers of the merge phase.
+template <int MT, int NPQ, int NPP>
+__device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
+                                          const float* r_s, f32x4* lds, bf16_t* att_out, float* part_o, float* part_ml, int ph) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int per = p.B * p.Hkv * p.NS;
-  const int qg = unit / per;
-  int rem = unit - qg * per;
-  const int hk = rem % p.Hkv;
-  rem /= p.Hkv;
+  const int li = lane & 15, g4 = lane >> 4;
+  const int hk = unit % p.Hkv;
+  int rem = unit / p.Hkv;
+  const int qt = rem % p.QT;
+  rem /= p.QT;
   const int s = rem % p.NS, b = rem / p.NS;
-  const int qt = qg * 8 + wave;
-  if (qt >= p.QT) return;
-  const int RG = p.R * p.G;
-  const int qr = qt * 16 + (lane & 15);
+  const int g_log = 31 - __builtin_clz(p.G), sl_log = p.SL == 8 ? 3 : 4;   // G and SL are powers of two
+  const int RG = p.R << g_log;
+  const int qr = qt * 16 + li;
   const bool vq = qr < RG;
   const int qrc = vq ? qr : RG - 1;
-  const int m = b * p.R + qrc / p.G;
-  const int hq = hk * p.G + qrc % p.G;
-  const int g4 = lane >> 4;
-  const RowDesc rd = p.rows[m];
-  const int tv = vq ? trunk_visible(rd, m, p.R) : 0;
-  int tvmax = tv;
-  for (int o = 32; o > 0; o >>= 1) tvmax = max(tvmax, __shfl_xor(tvmax, o));
-  const int kb0 = s * p.KPU;
-  const int kend = min(kb0 + p.KPU, tvmax);
+  const int rloc = qrc >> g_log;           // row of the sequence
+  const int m = b * p.R + rloc;
+  const int hq = hk * p.G + (qrc & (p.G - 1));
+  const bool is_branch = p.is_branch != 0;
+  const gfloat* gq = (const gfloat*)qkv;
+  const gfloat* gcs = (const gfloat*)p.cos_sin;
 
-  // Q operand: dims g4*8..+7 (k-step 0) and 32+g4*8..+7 (k-step 1) of this lane's query row, rotated and scaled
+  // ---- issue: row descriptor, raw query tile
+  const RowDesc rd = p.rows[m];
+  const gfloat* qp = gq + (int64_t)m * p.qkvd + hq * 64 + g4 * 8;
+  const f32x4 qa0 = *(const gf32x4*)qp, qa1 = *(const gf32x4*)(qp + 4);
+  const f32x4 qb0 = *(const gf32x4*)(qp + 32), qb1 = *(const gf32x4*)(qp + 36);
+  const gfloat* qcs = gcs + ((int64_t)m * 32 + g4 * 8) * 2;
+  const f32x4 qc0 = *(const gf32x4*)qcs, qc1 = *(const gf32x4*)(qcs + 4), qc2 = *(const gf32x4*)(qcs + 8), qc3 = *(const gf32x4*)(qcs + 12);
+
+  // ---- issue: the first trunk blocks of this wavefront (block counts from the host's bound)
+  const int kb0 = s * p.KPU;
+  const int kend_ub = min(kb0 + p.KPU, p.tv_ub);
+  const int n_tb = kend_ub > kb0 ? (kend_ub - kb0 + 31) >> 5 : 0;
+  const int n_mine = n_tb > wave ? (n_tb - wave + kFusedWaves - 1) / kFusedWaves : 0;
+  const int rpt = 16 >> g_log;                                // rows per query tile
+  const int n_fresh_keys = is_branch ? rpt << sl_log : p.R;
+  const int n_fb = s == 0 ? (n_fresh_keys + 31) >> 5 : 0;
+  const int krow = (li >> 2) * 8 + (li & 3);                  // key of this lane's A-operand row in a block (tile 0)
+  // trunk K [B][Hkv][vt_stride][64]; trunk V^T [B][Hkv][vt_stride / 32][64 dims][32 keys]: a 32-key block of one head is
+  // 4 KiB of contiguous memory in both, so every operand load covers whole cache lines
+  const gbf16* kbase = (const gbf16*)L.trunk_k + ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64 + g4 * 8;
+  const gbf16* vbase = (const gbf16*)L.trunk_vt + ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64 + li * 32 + g4 * 8;
+  struct TrunkBlock {
+    bf16x8 k[2][2];
+    bf16x8 vt[4];
+  };
+  constexpr int RING = 2;
+  TrunkBlock ring[RING];
+  auto load_trunk = [&](TrunkBlock& tb, int i) {   // i-th block of this wavefront, clamped to its last one
+    const int blk = wave + kFusedWaves * max(min(i, n_mine - 1), 0);
+    const int kb = min(kb0 + blk * 32, p.vt_stride - 32);
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+      const gbf16* kp = kbase + (int64_t)(kb + krow + tile * 4) * 64;
+      tb.k[tile][0] = *(const gbf16x8*)kp;
+      tb.k[tile][1] = *(const gbf16x8*)(kp + 32);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) tb.vt[dt] = *(const gbf16x8*)(vbase + (int64_t)kb * 64 + dt * 16 * 32);
+  };
+#pragma unroll
+  for (int i = 0; i < RING; ++i) load_trunk(ring[i], i);   // unconditional (a wavefront without blocks re-reads block 0)
+
+  // ---- issue: sources of the fresh key this thread stages (item = key f, rotary quad / 8-dim group q8)
+  struct Fresh {
+    int f, q8, m_o;
+    bool valid, stored;
+    u32x2 k_lo, k_hi;      // stored: 4 + 4 key elements
+    bf16x8 v;              // stored: 8 value elements
+    f32x4 a, bb, c0, c1, v0, v1;   // computed: raw projections and rotary table
+  };
+  Fresh fr[1];
+  const int nf8 = n_fb * 32 * 8;   // at most 512: one item per thread
+#pragma unroll
+  for (int t = 0; t < 1; ++t) {
+    Fresh& x = fr[t];
+    const int it = threadIdx.x + t * kFusedThreads;
+    x.f = it >> 3;
+    x.q8 = it & 7;
+    x.valid = false;
+    x.stored = false;
+    x.m_o = b * p.R;
+    if (it < nf8) {
+      if (is_branch) {
+        const int rt = qt * rpt + (x.f >> sl_log), j = x.f & (p.SL - 1);
+        x.m_o = b * p.R + min(rt, p.R - 1);
+        x.valid = rt < p.R && j < p.suffix_len;
+        x.stored = j < p.suffix_len - 1;
+        if (x.valid && x.stored) {
+          const int64_t row = (((int64_t)x.m_o * p.suffix_cap + j) * p.Hkv + hk) * 64;
+          x.k_lo = *(const gu32x2*)(L.suffix_k + row + x.q8 * 4);
+          x.k_hi = *(const gu32x2*)(L.suffix_k + row + 32 + x.q8 * 4);
+          x.v = *(const gbf16x8*)(L.suffix_v + row + x.q8 * 8);
+        }
+      } else {
+        x.m_o = b * p.R + min(x.f, p.R - 1);
+        x.valid = x.f < p.R;
+      }
+      if (x.valid && !x.stored) {
+        const gfloat* kp = gq + (int64_t)x.m_o * p.qkvd + p.qd + hk * 64 + x.q8 * 4;
+        x.a = *(const gf32x4*)kp;
+        x.bb = *(const gf32x4*)(kp + 32);
+        const gfloat* cs = gcs + ((int64_t)x.m_o * 32 + x.q8 * 4) * 2;
+        x.c0 = *(const gf32x4*)cs;
+        x.c1 = *(const gf32x4*)(cs + 4);
+        const gfloat* vp = gq + (int64_t)x.m_o * p.qkvd + p.qd + p.kvd + hk * 64 + x.q8 * 8;
+        x.v0 = *(const gf32x4*)vp;
+        x.v1 = *(const gf32x4*)(vp + 4);
+      }
+    }
+  }
+
+  // ---- Q operand: dims g4*8..+7 (k-step 0) and 32+g4*8..+7 (k-step 1) of this lane's query row, rotated, scaled
+  const int tv = vq ? trunk_visible(rd, m, p.R) : 0;
   Bf8 qh[2], ql[2];
   {
-    const float* qp = qkv + (int64_t)m * p.qkvd + hq * 64 + g4 * 8;
-    f32x4 a0 = *(const gf32x4*)qp, a1 = *(const gf32x4*)(qp + 4);
-    f32x4 b0 = *(const gf32x4*)(qp + 32), b1 = *(const gf32x4*)(qp + 36);
-    const float* cs = p.cos_sin + ((int64_t)m * 32 + g4 * 8) * 2;
-    f32x4 c0 = *(const gf32x4*)cs, c1 = *(const gf32x4*)(cs + 4), c2 = *(const gf32x4*)(cs + 8), c3 = *(const gf32x4*)(cs + 12);
-    float a[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-    float bb[8] = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
-    float cc[16] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3],
-                    c2[0], c2[1], c2[2], c2[3], c3[0], c3[1], c3[2], c3[3]};
+    float a[8] = {qa0[0], qa0[1], qa0[2], qa0[3], qa1[0], qa1[1], qa1[2], qa1[3]};
+    float bb[8] = {qb0[0], qb0[1], qb0[2], qb0[3], qb1[0], qb1[1], qb1[2], qb1[3]};
+    float cc[16] = {qc0[0], qc0[1], qc0[2], qc0[3], qc1[0], qc1[1], qc1[2], qc1[3],
+                    qc2[0], qc2[1], qc2[2], qc2[3], qc3[0], qc3[1], qc3[2], qc3[3]};
     const float scale = r_s[m] * 0.125f * kLog2e;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -406,175 +599,191 @@ __device__ __forceinline__ void attn_trunk_unit(const FusedParams& p, const Fuse
       ql[1].u[i] = f32_to_bf16(x1 - bf16_to_f32(qh[1].u[i]));
     }
   }
+  stamp(p, ph, 4);
 
-  f32x4 acc[4];
+  // ---- stage the fresh keys in LDS: K rows [64][72] (row padding against bank conflicts), V^T columns [64][72]
+  bf16_t* kf_s = (bf16_t*)(lds + kFusedWaves * 4 * 64 + 64);
+  bf16_t* vf_s = kf_s + 64 * 72;
+  if (n_fb > 0) {
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt) acc[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
-  const bf16_t* kbase = L.trunk_k + ((int64_t)b * p.max_trunk * p.Hkv + hk) * 64 + g4 * 8;
-  const bf16_t* vbase = L.trunk_vt + (((int64_t)b * p.Hkv + hk) * 64 + (lane & 15)) * p.vt_stride + g4 * 8;
-  const int krow = ((lane & 15) >> 2) * 8 + (lane & 3);   // key row of this lane inside a 32-key block (tile 0)
+    for (int t = 0; t < 1; ++t) {
+      Fresh& x = fr[t];
+      if (threadIdx.x + t * kFusedThreads < nf8) {
+        u32x2 k_lo = (u32x2){0u, 0u}, k_hi = (u32x2){0u, 0u};
+        Bf8 vv;
+        vv.w = (u32x4){0u, 0u, 0u, 0u};
+        if (x.valid && x.stored) {
+          k_lo = x.k_lo;
+          k_hi = x.k_hi;
+          vv.v = x.v;
+        } else if (x.valid) {
+          const float rs = r_s[x.m_o];
+          float cc[8] = {x.c0[0], x.c0[1], x.c0[2], x.c0[3], x.c1[0], x.c1[1], x.c1[2], x.c1[3]};
+          bf16_t x0[4], x1[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float c = cc[2 * e], sn = cc[2 * e + 1];
+            x0[e] = f32_to_bf16((x.a[e] * c - x.bb[e] * sn) * rs);
+            x1[e] = f32_to_bf16((x.bb[e] * c + x.a[e] * sn) * rs);
+          }
+          uint64_t p0 = pack_bf16x4(x0[0], x0[1], x0[2], x0[3]), p1 = pack_bf16x4(x1[0], x1[1], x1[2], x1[3]);
+          k_lo = (u32x2){(uint32_t)p0, (uint32_t)(p0 >> 32)};
+          k_hi = (u32x2){(uint32_t)p1, (uint32_t)(p1 >> 32)};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            vv.u[e] = f32_to_bf16(x.v0[e] * rs);
+            vv.u[4 + e] = f32_to_bf16(x.v1[e] * rs);
+          }
+          // append for later passes: the row's private suffix slot (branch) or its trunk position (extend)
+          if (is_branch) {
+            const int64_t row = (((int64_t)x.m_o * p.suffix_cap + (p.suffix_len - 1)) * p.Hkv + hk) * 64;
+            *(gu32x2*)(L.suffix_k + row + x.q8 * 4) = k_lo;
+            *(gu32x2*)(L.suffix_k + row + 32 + x.q8 * 4) = k_hi;
+            *(gbf16x8*)(L.suffix_v + row + x.q8 * 8) = vv.v;
+          } else {
+            const int slot = p.rows[x.m_o].kv_slot;
+            const int64_t head = (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64;
+            const int64_t row = head + (int64_t)slot * 64;
+            *(gu32x2*)(L.trunk_k + row + x.q8 * 4) = k_lo;
+            *(gu32x2*)(L.trunk_k + row + 32 + x.q8 * 4) = k_hi;
+            gbf16* vcol = (gbf16*)L.trunk_vt + head + (int64_t)(slot >> 5) * 2048 + (x.q8 * 8) * 32 + (slot & 31);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) vcol[e * 32] = vv.u[e];
+          }
+        }
+        *(u32x2*)(kf_s + x.f * 72 + x.q8 * 4) = k_lo;
+        *(u32x2*)(kf_s + x.f * 72 + 32 + x.q8 * 4) = k_hi;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vf_s[(x.q8 * 8 + e) * 72 + x.f] = vv.u[e];
+      }
+    }
+    wg_barrier();
+  }
+  stamp(p, ph, 5);
 
-  for (int kb = kb0; kb < kend; kb += 32) {
+  OnlineSoftmax st;
+  st.m_run = -INFINITY;
+  st.l_run = 0.f;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) st.acc[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  // ---- stored trunk keys: RING blocks in flight; every iteration computes and reloads unconditionally (blocks past
+  // the wavefront's last one are clamped duplicates with every key masked), so the load counting stays exact
+  for (int i0 = 0; i0 < n_mine; i0 += RING) {
+#pragma unroll
+    for (int r = 0; r < RING; ++r) {
+      const int i = i0 + r;
+      const int kb = kb0 + (wave + kFusedWaves * i) * 32;
+      f32x4 S[2];
+      bool vis[8];
+#pragma unroll
+      for (int tile = 0; tile < 2; ++tile) S[tile] = score_tile<NPQ>(ring[r].k[tile][0], ring[r].k[tile][1], qh, ql);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vis[e] = i < n_mine && kb + g4 * 8 + e < tv;
+      softmax_block<NPP>(st, S, vis, ring[r].vt);
+      load_trunk(ring[r], i + RING);
+    }
+  }
+  stamp(p, ph, 6);
+  // ---- fresh blocks continue the round-robin after the trunk blocks
+  for (int blk = n_tb + ((wave - n_tb) & (kFusedWaves - 1)); blk < n_tb + n_fb; blk += kFusedWaves) {
+    const int f0 = (blk - n_tb) * 32;
     f32x4 S[2];
+    bool vis[8];
+    bf16x8 vt[4];
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
-      int key = min(kb + krow + tile * 4, p.max_trunk - 1);
-      const bf16_t* kp = kbase + (int64_t)key * p.Hkv * 64;
-      bf16x8 k0 = *(const gbf16x8*)kp, k1 = *(const gbf16x8*)(kp + 32);
-      f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
-      sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qh[0].v, sacc, 0, 0, 0);
-      sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qh[1].v, sacc, 0, 0, 0);
-      if (NPQ == 2) {
-        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[0].v, sacc, 0, 0, 0);
-        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[1].v, sacc, 0, 0, 0);
+      const bf16_t* kp = kf_s + (f0 + krow + tile * 4) * 72 + g4 * 8;
+      S[tile] = score_tile<NPQ>(*(const bf16x8*)kp, *(const bf16x8*)(kp + 32), qh, ql);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) vt[dt] = *(const bf16x8*)(vf_s + (dt * 16 + li) * 72 + f0 + g4 * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int f = f0 + g4 * 8 + e;
+      vis[e] = vq && (is_branch ? ((f >> sl_log) == (li >> g_log) && (f & (p.SL - 1)) < p.suffix_len) : f <= rloc);
+    }
+    softmax_block<NPP>(st, S, vis, vt);
+  }
+  st.l_run += __shfl_xor(st.l_run, 16);
+  st.l_run += __shfl_xor(st.l_run, 32);
+  stamp(p, ph, 7);
+
+  // ---- the 8 wavefronts' partial softmaxes meet in LDS: acc [wave][dt][lane], (m, l) [wave][16]
+  float* ml = (float*)(lds + kFusedWaves * 4 * 64);
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) lds[(wave * 4 + dt) * 64 + lane] = st.acc[dt];
+  if (g4 == 0) {
+    ml[(wave * 16 + li) * 2] = st.m_run;
+    ml[(wave * 16 + li) * 2 + 1] = st.l_run;
+  }
+  wg_barrier();
+  if (threadIdx.x < 256) {
+    const int q = threadIdx.x & 15, dq = threadIdx.x >> 4;       // query row of the tile, dims 4 dq .. 4 dq + 3
+    float mmax = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kFusedWaves; ++w) mmax = fmaxf(mmax, ml[(w * 16 + q) * 2]);
+    const float m_use = mmax == -INFINITY ? 0.f : mmax;
+    float lsum = 0.f;
+    f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < kFusedWaves; ++w) {
+      const float wgt = exp2_fast(ml[(w * 16 + q) * 2] - m_use);
+      lsum += wgt * ml[(w * 16 + q) * 2 + 1];
+      o += lds[(w * 4 + (dq >> 2)) * 64 + q + 16 * (dq & 3)] * wgt;
+    }
+    const int qrow = qt * 16 + q;
+    if (qrow < RG) {
+      if (p.NS == 1) {
+        const int mm = b * p.R + qrow / p.G;
+        const int k = (hk * p.G + qrow % p.G) * 64 + dq * 4;
+        const float inv = 1.0f / lsum;
+        bf16_t hi[4], lo[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float x = o[i] * inv;
+          hi[i] = f32_to_bf16(x);
+          lo[i] = f32_to_bf16(x - bf16_to_f32(hi[i]));
+        }
+        const int64_t off = b_off<MT>(k, mm);
+        st_u64(att_out + off, pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
+        st_u64(att_out + (int64_t)MP * p.qd + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
+      } else {
+        const int64_t pb = ((int64_t)(b * p.Hkv + hk) * p.NS + s) * (p.QT * 16) + qrow;
+        if (dq == 0) st_u64(part_ml + pb * 2, pack_f32x2(mmax, lsum));
+        st_f32x4(part_o + pb * 64 + dq * 4, o);
       }
-      S[tile] = sacc;
-    }
-    // this lane: query row lane & 15, keys kb + g4*8 + {0..3} (tile 0) and + {4..7} (tile 1)
-    float sv[8];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int key = kb + g4 * 8 + i;
-      float x = i < 4 ? S[0][i] : S[1][i - 4];
-      sv[i] = key < tv ? x : -INFINITY;
-      mx = fmaxf(mx, sv[i]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float corr = exp2_fast(m_run - m_use);
-    Bf8 ph, pl;
-    float psum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float pe = exp2_fast(sv[i] - m_use);
-      psum += pe;
-      ph.u[i] = f32_to_bf16(pe);
-      pl.u[i] = f32_to_bf16(pe - bf16_to_f32(ph.u[i]));
-    }
-    l_run = l_run * corr + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      bf16x8 vt = *(const gbf16x8*)(vbase + (int64_t)dt * 16 * p.vt_stride + kb);
-      acc[dt] = acc[dt] * corr;
-      acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, ph.v, acc[dt], 0, 0, 0);
-      if (NPP == 2) acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pl.v, acc[dt], 0, 0, 0);
     }
   }
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-  if (vq) {
-    const int64_t pb = ((int64_t)(b * p.Hkv + hk) * (p.NS + 1) + s) * (p.QG * 128) + qr;
-    if (g4 == 0) st_u64(part_ml + pb * 2, pack_f32x2(m_run, l_run));
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) st_f32x4(part_o + pb * 64 + dt * 16 + g4 * 4, acc[dt]);
-  }
+  wg_barrier();
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-
-// Pair unit: one wavefront per (row, query head), lane = head dimension.  Keys that exist only in this pass or
-// only for this row: the row's own token, its stored private suffix (branch rows), the earlier tokens of the same
-// extend (extend rows).  Also appends the row's K/V to its suffix slot or trunk position (first head of a group).
-__device__ __forceinline__ void attn_pair_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
-                                               const float* r_s, float* part_o, float* part_ml) {
-  const int d = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int pair = unit * kFusedWaves + wave;
-  if (pair >= p.M * p.Hq) return;
-  const int m = pair / p.Hq, hq = pair - m * p.Hq;
-  const int hk = hq / p.G, gq = hq - hk * p.G;
-  const RowDesc rd = p.rows[m];
-  const int b = rd.seq;
-  const int t_self = m - b * p.R;
-  const int i = d & 31;
-
-  auto rotated = [&](int row, int col0) -> float {   // rotary embedding at `row`'s position of head columns col0..+63
-    const gfloat* src = (const gfloat*)qkv + (int64_t)row * p.qkvd + col0;
-    const gfloat* cs = (const gfloat*)p.cos_sin + ((int64_t)row * 32 + i) * 2;
-    return rope_elem(src[d], src[d ^ 32], cs[0], cs[1], d) * r_s[row];
-  };
-  const float q = rotated(m, hq * 64) * (0.125f * kLog2e);
-  // this row's own key and value, rounded to the KV storage type like every other key
-  const bf16_t k_self = f32_to_bf16(rotated(m, p.qd + hk * 64));
-  const bf16_t v_self = f32_to_bf16(((const gfloat*)qkv)[(int64_t)m * p.qkvd + p.qd + p.kvd + hk * 64 + d] * r_s[m]);
-
-  const int nk = rd.is_branch ? rd.suffix_len : t_self + 1;
-  float m_run = -INFINITY, l_run = 0.f, o = 0.f;
-  for (int j = 0; j < nk; ++j) {
-    float kj, vj;
-    if (j == nk - 1) {
-      kj = bf16_to_f32(k_self);
-      vj = bf16_to_f32(v_self);
-    } else if (rd.is_branch) {
-      int64_t off = (((int64_t)m * p.suffix_cap + j) * p.Hkv + hk) * 64 + d;
-      kj = bf16_to_f32(((const gbf16*)L.suffix_k)[off]);
-      vj = bf16_to_f32(((const gbf16*)L.suffix_v)[off]);
-    } else {
-      int row = b * p.R + j;
-      kj = bf16_to_f32(f32_to_bf16(rotated(row, p.qd + hk * 64)));
-      vj = bf16_to_f32(f32_to_bf16(((const gfloat*)qkv)[(int64_t)row * p.qkvd + p.qd + p.kvd + hk * 64 + d] * r_s[row]));
-    }
-    const float sc = wave_sum(q * kj);
-    const float m_new = fmaxf(m_run, sc);
-    const float corr = exp2_fast(m_run - m_new);
-    const float pe = exp2_fast(sc - m_new);
-    l_run = l_run * corr + pe;
-    o = o * corr + pe * vj;
-    m_run = m_new;
-  }
-  const int qr = t_self * p.G + gq;
-  const int64_t pb = ((int64_t)(b * p.Hkv + hk) * (p.NS + 1) + p.NS) * (p.QG * 128) + qr;
-  st_f32(part_o + pb * 64 + d, o);
-  if (d == 0) st_u64(part_ml + pb * 2, pack_f32x2(m_run, l_run));
-  if (gq == 0) {
-    if (rd.is_branch) {
-      int64_t off = (((int64_t)m * p.suffix_cap + rd.kv_slot) * p.Hkv + hk) * 64 + d;
-      ((gbf16*)L.suffix_k)[off] = k_self;
-      ((gbf16*)L.suffix_v)[off] = v_self;
-    } else {
-      ((gbf16*)L.trunk_k)[(((int64_t)b * p.max_trunk + rd.kv_slot) * p.Hkv + hk) * 64 + d] = k_self;
-      ((gbf16*)L.trunk_vt)[(((int64_t)b * p.Hkv + hk) * 64 + d) * p.vt_stride + rd.kv_slot] = v_self;
-    }
-  }
-}
-
-// Combine unit: one wavefront per (row, query head) merges the partial softmaxes of the key splits the row sees
-// and of its fresh keys, and writes the attention output as head/remainder planes for the o-projection.
+// Merge unit (only when the trunk is split over several units): one wavefront per (row, query head), lane = head
+// dimension, merges the NS partial softmaxes and writes the attention output planes.
 template <int MT>
-__device__ __forceinline__ void attn_combine_unit(const FusedParams& p, int unit, const float* part_o,
-                                                  const float* part_ml, bf16_t* att_out) {
+__device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, const float* part_o, const float* part_ml,
+                                                bf16_t* att_out) {
   const int d = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int pair = unit * kFusedWaves + wave;
   if (pair >= p.M * p.Hq) return;
   const int m = pair / p.Hq, hq = pair - m * p.Hq;
   const int hk = hq / p.G, gq = hq - hk * p.G;
-  const RowDesc rd = p.rows[m];
-  const int b = rd.seq;
-  const int qr = (m - b * p.R) * p.G + gq;
-  const int tv = trunk_visible(rd, m, p.R);
-  const int nsv = min(p.NS, (tv + p.KPU - 1) / p.KPU);
-  const int64_t pb0 = ((int64_t)(b * p.Hkv + hk) * (p.NS + 1)) * (p.QG * 128) + qr;
-  float m_run = -INFINITY, l_run = 0.f, o = 0.f;
-  for (int j = 0; j <= nsv; ++j) {
-    const int s = j < nsv ? j : p.NS;
-    const int64_t pb = pb0 + (int64_t)s * (p.QG * 128);
-    const float ms = ((const gfloat*)part_ml)[pb * 2], ls = ((const gfloat*)part_ml)[pb * 2 + 1];
-    const float os = ((const gfloat*)part_o)[pb * 64 + d];
-    const float m_new = fmaxf(m_run, ms);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float c1 = exp2_fast(m_run - m_use), c2 = exp2_fast(ms - m_use);
-    l_run = l_run * c1 + ls * c2;
-    o = o * c1 + os * c2;
-    m_run = m_new;
+  const int b = m / p.R;
+  const int qrow = (m - b * p.R) * p.G + gq;
+  const int64_t pb0 = ((int64_t)(b * p.Hkv + hk) * p.NS) * (p.QT * 16) + qrow;
+  const gfloat* gml = (const gfloat*)part_ml;
+  const gfloat* go = (const gfloat*)part_o;
+  float mmax = -INFINITY;
+  for (int s = 0; s < p.NS; ++s) mmax = fmaxf(mmax, gml[(pb0 + (int64_t)s * (p.QT * 16)) * 2]);
+  const float m_use = mmax == -INFINITY ? 0.f : mmax;
+  float lsum = 0.f, o = 0.f;
+  for (int s = 0; s < p.NS; ++s) {
+    const int64_t pb = pb0 + (int64_t)s * (p.QT * 16);
+    const float wgt = exp2_fast(gml[pb * 2] - m_use);
+    lsum += wgt * gml[pb * 2 + 1];
+    o += wgt * go[pb * 64 + d];
   }
-  const float x = o / l_run;
+  const float x = o / lsum;
   const bf16_t hi = f32_to_bf16(x);
   const bf16_t lo = f32_to_bf16(x - bf16_to_f32(hi));
   // lanes d, d+1, d+2, d+3 -> one 8-byte store per plane from lane d (d % 4 == 0)
@@ -589,11 +798,32 @@ __device__ __forceinline__ void attn_combine_unit(const FusedParams& p, int unit
   }
 }
 
+// A compute unit pulls only ~30 GB/s out of HBM (latency x its limited number of misses in flight) but over 100 GB/s
+// out of its L2.  The 48-odd attention units of a layer cannot afford to fetch the trunk K/V of their head from HBM
+// themselves, so during the qkv phase EVERY workgroup touches a 1/32nd slice of "its" head's K/V (workgroup g serves
+// KV head g % Hkv: workgroups are dealt round-robin to the 8 XCDs, whose L2s are private, and attention unit u of
+// head hk = u % Hkv runs as workgroup u).  Purely a performance hint: nothing depends on where a line ends up.
+__device__ __forceinline__ unsigned prefetch_trunk_kv(const FusedParams& p, const FusedLayer& L) {
+  const int hk = blockIdx.x % p.Hkv, rank = blockIdx.x / p.Hkv, n_rank = (p.nwg + p.Hkv - 1) / p.Hkv;
+  const int lines = p.tv_ub;   // one 128-byte line per stored key in K, and as many in V^T
+  unsigned acc = 0;
+  for (int b = 0; b < p.B; ++b) {
+    const int64_t head = (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64;
+    const __attribute__((address_space(1))) unsigned* k = (const __attribute__((address_space(1))) unsigned*)(L.trunk_k + head);
+    const __attribute__((address_space(1))) unsigned* v = (const __attribute__((address_space(1))) unsigned*)(L.trunk_vt + head);
+    for (int i = rank * kFusedThreads + threadIdx.x; i < lines; i += n_rank * kFusedThreads) {
+      acc ^= k[(int64_t)i * 32];
+      acc ^= v[(int64_t)i * 32];
+    }
+  }
+  return acc;
+}
+
 // ---------------------------------------------------------------------------------------------- the kernel
 // Register chunks in flight per wavefront.  DEEP needs the k-tiles per wavefront of every linear layer to be a
 // multiple of 8 (one feature tile per unit) / 4 (four per unit); the shallow set needs multiples of 2.
 template <int MT, bool DEEP> struct Depth {
-  static constexpr int a1 = !DEEP ? 2 : (MT == 3 ? 4 : 8);   // one feature tile per unit
+  static constexpr int a1 = !DEEP ? 2 : 4;                    // one feature tile per unit
   static constexpr int a4 = !DEEP ? 2 : (MT == 3 ? 2 : 4);   // four feature tiles per unit
 };
 
@@ -609,13 +839,60 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
   const int64_t h_stride = (int64_t)MP * p.d;
   const int64_t ssq_stride = (int64_t)(p.d >> 4) * MP;
   const int lm_phase = fused_last_phase(p.L);
+  unsigned sink = 0;   // keeps prefetch loads alive
 
   for (int ph = first; ph <= last; ++ph) {
+    if (p.NS == 1 && ph > 0 && ph < lm_phase && (ph - 1) % 6 == 2) continue;
     const bool do_wait = persistent && ph > first;
     stamp(p, ph, 0);
-    if (ph == 0) {
+    const int l = ph == 0 ? 0 : (ph == lm_phase ? p.L - 1 : (ph - 1) / 6);
+    const int sub = ph == 0 ? -1 : (ph == lm_phase ? 6 : (ph - 1) % 6);
+    const FusedLayer L = p.layers[l];
+    float* qkv = p.qkv + (int64_t)l * MP * p.qkvd;
+    bf16_t* att = p.att + (int64_t)l * 2 * MP * p.qd;
+    bf16_t* act = p.act + (int64_t)l * NPA * MP * p.ffn;
+
+    // ---- what a linear-layer phase streams, reads and writes
+    FusedGemm g{};
+    const bf16_t* bsrc = nullptr;
+    int64_t bplane = 0;
+    int epi = 0;
+    EpiArgs e{};
+    const float* ssq_in = nullptr;
+    // K-split scratch of this phase instance (sub 0, 3, 5 -> slot 0, 1, 2)
+    const int fix_slot = l * 3 + (sub == 0 ? 0 : (sub == 3 ? 1 : 2));
+    e.fix_buf = p.fix_buf + (int64_t)fix_slot * p.fix_stride;
+    e.fix_cnt = p.fix_cnt + (int64_t)fix_slot * p.fix_cnt_stride;
+    if (sub == 0) {
+      g = L.qkv; bsrc = p.xn + (int64_t)(2 * l) * 2 * h_stride; bplane = h_stride; epi = EPI_QKV;
+      e.out = qkv; e.ld = p.qkvd;
+      ssq_in = p.ssq + (int64_t)(2 * l) * ssq_stride;   // the attention phase finds this layer's row scales in LDS
+    } else if (sub == 3 || sub == 5) {
+      const int v = sub == 3 ? 2 * l + 1 : 2 * l + 2;
+      g = sub == 3 ? L.o : L.down;
+      bsrc = sub == 3 ? att : act;
+      bplane = sub == 3 ? (int64_t)MP * p.qd : (int64_t)MP * p.ffn;
+      epi = EPI_RESID;
+      e.h_in = p.h + (int64_t)(v - 1) * h_stride;
+      e.h_out = p.h + (int64_t)v * h_stride;
+      e.gain = sub == 3 ? L.mlp_norm : (l + 1 < p.L ? p.layers[l + 1].attn_norm : p.final_norm);
+      e.xn_out = p.xn + (int64_t)v * 2 * h_stride;
+      e.ssq_out = p.ssq + (int64_t)v * ssq_stride;
+    } else if (sub == 4) {
+      const int v = 2 * l + 1;
+      g = L.gu; bsrc = p.xn + (int64_t)v * 2 * h_stride; bplane = h_stride; epi = EPI_SWIGLU;
+      e.act_out = act;
+      ssq_in = p.ssq + (int64_t)v * ssq_stride;
+    } else if (sub == 6) {
+      const int v = 2 * p.L;
+      g = p.lm; bsrc = p.xn + (int64_t)v * 2 * h_stride; bplane = h_stride; epi = EPI_LOGITS;
+      e.out = p.logits; e.ld = p.logits_ld;
+      ssq_in = p.ssq + (int64_t)v * ssq_stride;
+      if (!p.logits) g.n_units = 0;   // hidden states only
+    }
+
+    if (sub == -1) {
       // ---- embedding gather: residual stream version 0
-      const FusedLayer L0 = p.layers[0];
       for (int u = blockIdx.x; u < (p.d >> 4); u += p.nwg) {
         if (wave < MT) {
           const int m = wave * 16 + (lane & 15);
@@ -625,97 +902,51 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
           u32x2 eb = *(const gu32x2*)(p.embed + (int64_t)tok * p.d + n);
           f32x4 hn = (f32x4){__uint_as_float(eb.x << 16), __uint_as_float(eb.x & 0xffff0000u),
                              __uint_as_float(eb.y << 16), __uint_as_float(eb.y & 0xffff0000u)};
-          resid_store<MT>(p, hn, m, n, lane, L0.attn_norm, p.h, p.xn, p.ssq, u);
+          resid_store<MT>(p, hn, m, n, lane, L.attn_norm, p.h, p.xn, p.ssq, u);
         }
       }
-    } else if (ph == lm_phase) {
-      const int v = 2 * p.L;
-      EpiArgs e{};
-      e.out = p.logits;
-      e.ld = p.logits_ld;
-      // final-norm hidden states go out first: they need only the row scales
-      if (do_wait && !grid_wait(grid)) return;
-      stamp(p, ph, 1);
-      compute_row_scales(p, p.ssq + v * ssq_stride, r_s);
-      if (p.hidden) {
-        const float* hv = p.h + v * h_stride;
+    } else if (sub == 0 || sub == 3 || sub == 5) {
+      if (!gemm_phase<1, MT, 2, Depth<MT, DEEP>::a1>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph)) return;
+      if (sub == 0) sink ^= prefetch_trunk_kv(p, L);
+    } else if (sub == 4 || sub == 6) {
+      if (!gemm_phase<4, MT, 2, Depth<MT, DEEP>::a4>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph)) return;
+      if (sub == 6 && p.hidden) {
+        // final-norm hidden states (the row scales are in LDS)
+        const gfloat* hv = (const gfloat*)(p.h + (int64_t)(2 * p.L) * h_stride);
         for (int m = blockIdx.x; m < p.M; m += p.nwg)
           for (int c = threadIdx.x; c < p.d; c += kFusedThreads)
             p.hidden[(int64_t)m * p.hidden_ld + c] = hv[(int64_t)m * p.d + c] * bf16_to_f32(p.final_norm[c]) * r_s[m];
       }
-      if (p.logits &&
-          !gemm_phase<kAtLm, MT, 2, Depth<MT, DEEP>::a4, EPI_LOGITS>(p, p.lm, p.xn + v * 2 * h_stride, h_stride, e, grid, false,
-                                                              red, r_s, nullptr, ph))
-        return;
-    } else {
-      const int l = (ph - 1) / 6, sub = (ph - 1) % 6;
-      const FusedLayer L = p.layers[l];
-      float* qkv = p.qkv + (int64_t)l * MP * p.qkvd;
-      bf16_t* att = p.att + (int64_t)l * 2 * MP * p.qd;
-      bf16_t* act = p.act + (int64_t)l * NPA * MP * p.ffn;
+    } else if (sub == 1) {
       float* part_o = p.part_o + (int64_t)l * p.part_layer_stride * 64;
       float* part_ml = p.part_ml + (int64_t)l * p.part_layer_stride * 2;
-      if (sub == 0) {
-        EpiArgs e{};
-        e.out = qkv;
-        e.ld = p.qkvd;
-        if (!gemm_phase<kAtQkv, MT, 2, Depth<MT, DEEP>::a1, EPI_QKV>(p, L.qkv, p.xn + (int64_t)(2 * l) * 2 * h_stride, h_stride, e,
-                                                              grid, do_wait, red, r_s, nullptr, ph))
-          return;
-      } else if (sub == 1) {
-        if (do_wait && !grid_wait(grid)) return;
-        stamp(p, ph, 1);
-        compute_row_scales(p, p.ssq + (int64_t)(2 * l) * ssq_stride, r_s);
-        const int n_units = p.n_trunk_units + p.n_pair_units;
-        for (int u = blockIdx.x; u < n_units; u += p.nwg) {
-          if (u < p.n_trunk_units) attn_trunk_unit<2, 2>(p, L, qkv, u, r_s, part_o, part_ml);
-          else attn_pair_unit(p, L, qkv, u - p.n_trunk_units, r_s, part_o, part_ml);
-        }
-      } else if (sub == 2) {
-        if (do_wait && !grid_wait(grid)) return;
-        stamp(p, ph, 1);
-        for (int u = blockIdx.x; u < p.n_pair_units; u += p.nwg) attn_combine_unit<MT>(p, u, part_o, part_ml, att);
-      } else if (sub == 3) {
-        const int v = 2 * l + 1;
-        EpiArgs e{};
-        e.h_in = p.h + (int64_t)(v - 1) * h_stride;
-        e.h_out = p.h + (int64_t)v * h_stride;
-        e.gain = L.mlp_norm;
-        e.xn_out = p.xn + (int64_t)v * 2 * h_stride;
-        e.ssq_out = p.ssq + (int64_t)v * ssq_stride;
-        if (!gemm_phase<kAtO, MT, 2, Depth<MT, DEEP>::a1, EPI_RESID>(p, L.o, att, (int64_t)MP * p.qd, e, grid, do_wait, red, r_s,
-                                                              nullptr, ph))
-          return;
-      } else if (sub == 4) {
-        const int v = 2 * l + 1;
-        EpiArgs e{};
-        e.act_out = act;
-        if (!gemm_phase<kAtGu, MT, 2, Depth<MT, DEEP>::a4, EPI_SWIGLU>(p, L.gu, p.xn + (int64_t)v * 2 * h_stride, h_stride, e, grid,
-                                                                do_wait, red, r_s, p.ssq + (int64_t)v * ssq_stride, ph))
-          return;
-      } else {
-        const int v = 2 * l + 2;
-        EpiArgs e{};
-        e.h_in = p.h + (int64_t)(v - 1) * h_stride;
-        e.h_out = p.h + (int64_t)v * h_stride;
-        e.gain = l + 1 < p.L ? p.layers[l + 1].attn_norm : p.final_norm;
-        e.xn_out = p.xn + (int64_t)v * 2 * h_stride;
-        e.ssq_out = p.ssq + (int64_t)v * ssq_stride;
-        if (!gemm_phase<kAtDown, MT, NPA, Depth<MT, DEEP>::a1, EPI_RESID>(p, L.down, act, (int64_t)MP * p.ffn, e, grid, do_wait,
-                                                                     red, r_s, nullptr, ph))
-          return;
-      }
+      if (do_wait && !grid_wait(grid)) return;
+      stamp(p, ph, 1);
+      // the qkv phase left this layer's row scales in LDS; a launch that starts here computes them itself
+      if (ph == first) compute_row_scales(p, p.ssq + (int64_t)(2 * l) * ssq_stride, r_s);
+      stamp(p, ph, 3);
+      for (int u = blockIdx.x; u < p.n_attn_units; u += p.nwg)
+        attn_unit<MT, 2, 2>(p, L, qkv, u, r_s, red, att, part_o, part_ml, ph);
+    } else {
+      // merge of the key splits; with a single split the attention units wrote the final output and this phase
+      // (and its barrier) does not exist
+      float* part_o = p.part_o + (int64_t)l * p.part_layer_stride * 64;
+      float* part_ml = p.part_ml + (int64_t)l * p.part_layer_stride * 2;
+      if (do_wait && !grid_wait(grid)) return;
+      stamp(p, ph, 1);
+      for (int u = blockIdx.x; u < p.n_pair_units; u += p.nwg) attn_merge_unit<MT>(p, u, part_o, part_ml, att);
     }
     stamp(p, ph, 2);
     if (ph < last) grid_arrive(grid);
   }
+  if (sink == 0x9e3779b9u && p.err) *p.err = 2;   // never true in practice; the prefetched words must count as used
 }
 
 // ---------------------------------------------------------------------------------------------- set-up kernels
 __global__ void retile_stream_kernel(const bf16_t* __restrict__ src0, int rows0, const bf16_t* __restrict__ src1, int rows1,
-                                     const bf16_t* __restrict__ src2, int rows2, int mode, int AT, int Kd, int n_units,
+                                     const bf16_t* __restrict__ src2, int rows2, int mode, int AT, int KS, int Kd, int n_units,
                                      bf16_t* __restrict__ dst) {
-  const int KTW = Kd / 32 / kFusedWaves;
+  const int KTW = Kd / 32 / kFusedWaves / KS;
   const int64_t total = (int64_t)n_units * kFusedWaves * KTW * AT * 64;
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
@@ -726,8 +957,10 @@ __global__ void retile_stream_kernel(const bf16_t* __restrict__ src0, int rows0,
   const int i = (int)(tile % KTW);
   tile /= KTW;
   const int w = (int)(tile % kFusedWaves);
-  const int64_t u = tile / kFusedWaves;
-  const int kt = w * KTW + i;
+  const int64_t unit = tile / kFusedWaves;
+  const int64_t u = unit / KS;            // feature-tile group
+  const int ks = (int)(unit % KS);        // k-slice
+  const int kt = (ks * kFusedWaves + w) * KTW + i;
   const bf16_t* src = nullptr;
   int64_t row = 0;
   if (mode == 0) {
@@ -744,7 +977,9 @@ __global__ void retile_stream_kernel(const bf16_t* __restrict__ src0, int rows0,
   *(u32x4*)(dst + idx * 8) = v;
 }
 
-__global__ void copy_v_transposed_kernel(bf16_t* trunk_vt, const bf16_t* src, int len, int Hkv, int vt_stride, int64_t total) {
+// [B][len][Hkv][64] keys and values -> the head-major trunk layouts of the fused pass
+__global__ void copy_kv_fused_kernel(bf16_t* trunk_k, bf16_t* trunk_vt, const bf16_t* src_k, const bf16_t* src_v, int len,
+                                     int Hkv, int vt_stride, int64_t total) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // over [B][len][Hkv][64]
   if (idx >= total) return;
   int d = (int)(idx & 63);
@@ -753,7 +988,9 @@ __global__ void copy_v_transposed_kernel(bf16_t* trunk_vt, const bf16_t* src, in
   r /= Hkv;
   int pos = (int)(r % len);
   int64_t b = r / len;
-  trunk_vt[((b * Hkv + hk) * 64 + d) * vt_stride + pos] = src[idx];
+  const int64_t head = (b * Hkv + hk) * (int64_t)vt_stride * 64;
+  trunk_k[head + (int64_t)pos * 64 + d] = src_k[idx];
+  trunk_vt[head + (int64_t)(pos >> 5) * 2048 + d * 32 + (pos & 31)] = src_v[idx];
 }
 
 template <int MT, bool DEEP>
@@ -785,22 +1022,23 @@ int64_t stream_order_elems(int N, int Kd, int AT) {
 }
 
 int launch_retile_stream(const bf16_t* src0, int rows0, const bf16_t* src1, int rows1, const bf16_t* src2, int rows2,
-                         int mode, int AT, int Kd, bf16_t* dst, hipStream_t s) {
-  SSD_CHECK_ARG(Kd % 256 == 0, "fused path: reduction dimension %d must be a multiple of 256", Kd);
+                         int mode, int AT, int KS, int Kd, bf16_t* dst, hipStream_t s) {
+  SSD_CHECK_ARG(KS >= 1 && Kd % (256 * KS) == 0, "fused path: reduction dimension %d must be a multiple of %d", Kd, 256 * KS);
   SSD_CHECK_ARG(mode == 0 || (AT == 4 && rows0 == rows1 && rows0 % 32 == 0), "gate/up interleave needs AT = 4 and equal heights");
   int64_t nt = mode == 0 ? ((int64_t)rows0 + rows1 + rows2 + 15) / 16 : (int64_t)2 * (rows0 / 16);
-  int n_units = (int)((nt + AT - 1) / AT);
-  int64_t total = (int64_t)n_units * AT * (Kd / 32) * 64;
-  retile_stream_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(src0, rows0, src1, rows1, src2, rows2, mode, AT, Kd,
+  int n_units = (int)((nt + AT - 1) / AT) * KS;
+  int64_t total = (int64_t)(n_units / KS) * AT * (Kd / 32) * 64;
+  retile_stream_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(src0, rows0, src1, rows1, src2, rows2, mode, AT, KS, Kd,
                                                                        n_units, dst);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }
 
-int launch_copy_v_transposed(bf16_t* trunk_vt, const bf16_t* src, int B, int len, int Hkv, int vt_stride, hipStream_t s) {
+int launch_copy_kv_fused(bf16_t* trunk_k, bf16_t* trunk_vt, const bf16_t* src_k, const bf16_t* src_v, int B, int len, int Hkv,
+                         int vt_stride, hipStream_t s) {
   int64_t total = (int64_t)B * len * Hkv * 64;
   if (total == 0) return SSD_OK;
-  copy_v_transposed_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(trunk_vt, src, len, Hkv, vt_stride, total);
+  copy_kv_fused_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(trunk_k, trunk_vt, src_k, src_v, len, Hkv, vt_stride, total);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }
@@ -808,7 +1046,7 @@ int launch_copy_v_transposed(bf16_t* trunk_vt, const bf16_t* src, int B, int len
 bool fused_supported(const Dims& d, int max_rows) {
   return d.dtype == SSD_BF16 && d.head_dim == 64 && max_rows <= kFusedMaxRows && d.d_model % 512 == 0 &&
          d.q_dim() % 512 == 0 && d.d_ffn % 512 == 0 && d.kv_dim() % 16 == 0 && d.vocab % 16 == 0 &&
-         d.n_q_heads % d.n_kv_heads == 0;
+         d.n_q_heads % d.n_kv_heads == 0 && 16 % (d.n_q_heads / d.n_kv_heads) == 0;
 }
 
 int fused_grid_size(int* out) {
@@ -828,12 +1066,12 @@ int fused_grid_size(int* out) {
 int launch_fused(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
   SSD_CHECK_ARG(p.M >= 1 && p.M <= kFusedMaxRows, "fused pass of %d rows (1..%d supported)", p.M, kFusedMaxRows);
   SSD_CHECK_ARG(p.nwg >= 8 && p.nwg % 8 == 0, "fused grid of %d workgroups must be a multiple of 8", p.nwg);
-  SSD_CHECK_ARG(p.KPU >= 32 && p.KPU % 32 == 0 && p.NS >= 1 && p.QG >= 1 && p.QT <= p.QG * 8, "bad attention split");
+  SSD_CHECK_ARG(p.KPU >= 32 && p.KPU % 32 == 0 && p.NS >= 1 && p.QT >= 1 && (p.SL == 8 || p.SL == 16) && 16 % p.G == 0 &&
+                    (16 / p.G) * p.SL <= 64,
+                "bad attention split");
   SSD_CHECK_ARG(first >= 0 && last <= fused_last_phase(p.L) && first <= last, "bad phase range");
   const int mt = (p.M + 15) / 16;
-  const int k_d = p.d / 256, k_q = p.qd / 256, k_f = p.ffn / 256;
-  SSD_CHECK_ARG(k_d % 2 == 0 && k_q % 2 == 0 && k_f % 2 == 0, "fused pass: d_model, q_dim and d_ffn must be multiples of 512");
-  const bool deep = k_d % 8 == 0 && k_q % 8 == 0 && k_f % 8 == 0;
+  const bool deep = p.deep != 0;
   if (deep) {
     if (mt == 1) return launch_mt<1, true>(p, first, last, persistent, s);
     if (mt == 2) return launch_mt<2, true>(p, first, last, persistent, s);

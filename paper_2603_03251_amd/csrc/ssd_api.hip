@@ -120,6 +120,7 @@ struct ssd_ctx {
   FusedLayer* fused_layers_dev = nullptr;
   unsigned* fused_bar = nullptr;
   unsigned* fused_err = nullptr;
+  int64_t fused_sync_words = 0; // barrier words + K-split counters, zeroed before every persistent launch
   int64_t part_entries = 0;    // per-layer capacity of the attention partial buffers, in query rows
   unsigned long long* phase_clocks = nullptr;
   const int32_t* forced_keys = nullptr;
@@ -175,52 +176,61 @@ int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
   }
   m->fused_ok = fused_supported(d, 1);
   if (m->fused_ok) {
+    int grid = 0;
+    SSD_TRY(fused_grid_size(&grid));
+    // ks_wanted > 1: split the reduction dimension so that every workgroup of the grid gets a unit, if the shape allows
     auto make = [&](FusedGemm* g, const void* s0, int r0, const void* s1, int r1, const void* s2, int r2, int mode, int at,
-                    int Kd) -> int {
+                    int ks_wanted, int Kd) -> int {
       int N = mode == 0 ? r0 + r1 + r2 : 2 * r0;
+      const int NT = (N + 15) / 16, groups = (NT + at - 1) / at;
+      int ks = 1;
+      if (ks_wanted > 1 && groups * ks_wanted <= grid && (Kd / 256) % (4 * ks_wanted) == 0) ks = ks_wanted;
       void* dst = nullptr;
       SSD_TRY(m->arena.alloc(&dst, (size_t)stream_order_elems(N, Kd, at) * 2));
-      SSD_TRY(launch_retile_stream((const bf16_t*)s0, r0, (const bf16_t*)s1, r1, (const bf16_t*)s2, r2, mode, at, Kd,
+      SSD_TRY(launch_retile_stream((const bf16_t*)s0, r0, (const bf16_t*)s1, r1, (const bf16_t*)s2, r2, mode, at, ks, Kd,
                                    (bf16_t*)dst, s));
       g->w = (const bf16_t*)dst;
-      g->KTW = Kd / 32 / kFusedWaves;
-      g->NT = (N + 15) / 16;
-      g->n_units = (g->NT + at - 1) / at;
+      g->KS = ks;
+      g->KTW = Kd / 32 / kFusedWaves / ks;
+      g->NT = NT;
+      g->n_units = groups * ks;
       return SSD_OK;
     };
     m->fused_layers.resize(d.n_layers);
     for (int l = 0; l < d.n_layers; ++l) {
       ssd_model::FusedW& F = m->fused_layers[l];
-      SSD_TRY(make(&F.qkv, w->h_wq[l], qd, w->h_wk[l], kvd, w->h_wv[l], kvd, 0, kAtQkv, d.d_model));
-      SSD_TRY(make(&F.o, w->h_wo[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtO, qd));
-      SSD_TRY(make(&F.gu, w->h_w_gate[l], d.d_ffn, w->h_w_up[l], d.d_ffn, nullptr, 0, 1, kAtGu, d.d_model));
-      SSD_TRY(make(&F.down, w->h_w_down[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtDown, d.d_ffn));
+      SSD_TRY(make(&F.qkv, w->h_wq[l], qd, w->h_wk[l], kvd, w->h_wv[l], kvd, 0, kAtQkv, 1, d.d_model));
+      SSD_TRY(make(&F.o, w->h_wo[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtO, 2, qd));
+      SSD_TRY(make(&F.gu, w->h_w_gate[l], d.d_ffn, w->h_w_up[l], d.d_ffn, nullptr, 0, 1, kAtGu, 1, d.d_model));
+      SSD_TRY(make(&F.down, w->h_w_down[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtDown, 2, d.d_ffn));
     }
-    SSD_TRY(make(&m->fused_lm, head_src, d.vocab, nullptr, 0, nullptr, 0, 0, kAtLm, d.d_model));
+    SSD_TRY(make(&m->fused_lm, head_src, d.vocab, nullptr, 0, nullptr, 0, 0, kAtLm, 1, d.d_model));
   }
   return SSD_OK;
 }
 
 // The same pass through the fused kernel: attention work split for this pass's shape, then one launch.
-int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int max_vis, float* logits, int64_t logits_ld,
-                  float* hidden, int64_t hidden_ld, hipStream_t s) {
+int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int max_vis, int branch_depth, float* logits,
+                  int64_t logits_ld, float* hidden, int64_t hidden_ld, hipStream_t s) {
   FusedParams p = c->fp;
   p.M = M;
   p.R = rows_per_seq;
   p.tokens = tokens;
+  p.is_branch = branch_depth >= 0;
+  p.suffix_len = branch_depth >= 0 ? branch_depth + 1 : 0;
+  p.tv_ub = max_vis > 0 ? max_vis : 0;
   const int RG = p.R * p.G;
   p.QT = (RG + 15) / 16;
-  p.QG = (p.QT + 7) / 8;
-  const int per_split = p.B * p.Hkv * p.QG;
-  const int ns_target = p.nwg / per_split > 1 ? p.nwg / per_split : 1;
+  p.SL = c->K + 1 <= 8 ? 8 : 16;
+  // stored trunk keys are split over several units only when one unit's share would pass 2048 keys
   const int p_ub = max_vis > 1 ? max_vis : 1;
-  int kpu = 64 * ((p_ub + 64 * ns_target - 1) / (64 * ns_target));
-  p.KPU = kpu < 64 ? 64 : kpu;
+  int ns = (p_ub + 2047) / 2048;
+  p.KPU = ((p_ub + ns - 1) / ns + 31) / 32 * 32;
   p.NS = (p_ub + p.KPU - 1) / p.KPU;
-  p.n_trunk_units = per_split * p.NS;
+  p.n_attn_units = p.B * p.Hkv * p.QT * p.NS;
   p.n_pair_units = (M * p.Hq + kFusedWaves - 1) / kFusedWaves;
-  if ((int64_t)p.B * p.Hkv * (p.NS + 1) * p.QG * 128 > c->part_entries) {
-    set_error("fused pass: attention partial buffer too small (%d splits, %d q groups)", p.NS, p.QG);
+  if (p.NS > 1 && (int64_t)p.B * p.Hkv * p.NS * p.QT * 16 > c->part_entries) {
+    set_error("fused pass: attention partial buffer too small (%d splits, %d query tiles)", p.NS, p.QT);
     return SSD_ESTATE;
   }
   p.logits = logits;
@@ -228,17 +238,18 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
   p.hidden = hidden;
   p.hidden_ld = hidden_ld;
   const int last = (logits || hidden) ? fused_last_phase(p.L) : fused_last_phase(p.L) - 1;
-  if (c->fused_mode == 2) SSD_TRY(launch_fill_i32((int32_t*)c->fused_bar, 0, 1024, s));
+  SSD_TRY(launch_fill_i32((int32_t*)c->fused_bar, 0, c->fused_sync_words, s));
   return launch_fused(p, 0, last, c->fused_mode == 2, s);
 }
 
 // One batched pass of the decoder over `M` rows whose descriptors and rotary tables are already in ctx->rows /
 // ctx->cos_sin.  Logits (fp32, row stride logits_ld) and final-norm hidden states are optional.
-int forward_rows(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int max_vis, float* logits,
+// max_vis: host bound of the stored trunk positions any row sees; branch_depth: decode step of branch rows, -1 for an extend.
+int forward_rows(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int max_vis, int branch_depth, float* logits,
                  int64_t logits_ld, float* hidden, int64_t hidden_ld, hipStream_t s) {
   const ssd_model* m = c->model;
   const Dims& d = m->dims;
-  if (c->fused_mode) return fused_forward(c, M, tokens, rows_per_seq, max_vis, logits, logits_ld, hidden, hidden_ld, s);
+  if (c->fused_mode) return fused_forward(c, M, tokens, rows_per_seq, max_vis, branch_depth, logits, logits_ld, hidden, hidden_ld, s);
   const int dt = d.dtype;
   const int64_t R = c->max_rows;     // plane stride of an activation buffer = R * columns
   SSD_TRY(launch_embed(dt, m->embed, tokens, c->h, M, d.d_model, d.vocab, s));
@@ -274,7 +285,7 @@ int forward_rows(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int
 int extend_rows(ssd_ctx* c, const int32_t* tokens, int T, int offset, float* logits, float* hidden, hipStream_t s) {
   const Dims& d = c->model->dims;
   SSD_TRY(launch_setup_extend_rows(c->rows, c->cos_sin, c->trunk_len, c->B, T, offset, d.head_dim / 2, d.rope_theta, s));
-  return forward_rows(c, c->B * T, tokens, T, c->trunk_ub + offset + T, logits, d.vocab, hidden, d.d_model, s);
+  return forward_rows(c, c->B * T, tokens, T, c->trunk_ub + offset, -1, logits, d.vocab, hidden, d.d_model, s);
 }
 
 // Workspace and constant parameters of the fused pass.
@@ -305,20 +316,37 @@ int fused_setup(ssd_ctx* c) {
   A((void**)&p.qkv, (size_t)L * MPr * p.qkvd * 4);
   A((void**)&p.att, (size_t)L * 2 * MPr * p.qd * 2);
   A((void**)&p.act, (size_t)L * kFusedActPlanes * MPr * p.ffn * 2);
-  // attention partials: at most nwg / (B Hkv QG) key splits plus the fresh-key partial, QG * 128 query rows each
+  // attention partials (used only when the trunk is split over several units: more than 2048 visible keys)
   const int r_max = (c->K + 1) * c->F > c->K + 1 ? (c->K + 1) * c->F : c->K + 1;
-  const int qg_max = ((r_max * p.G + 15) / 16 + 7) / 8;
-  c->part_entries = (int64_t)128 * (p.nwg + (int64_t)2 * p.B * p.Hkv * qg_max);
+  const int qt_max = (r_max * p.G + 15) / 16;
+  const int ns_max = (c->max_trunk + 2047) / 2048 + 1;
+  c->part_entries = (int64_t)p.B * p.Hkv * ns_max * qt_max * 16;
   p.part_layer_stride = c->part_entries;
   A((void**)&p.part_o, (size_t)L * c->part_entries * 64 * 4);
   A((void**)&p.part_ml, (size_t)L * c->part_entries * 2 * 4);
-  A((void**)&c->fused_bar, 4096 + 256);
+  // K-split scratch: per (layer, qkv / o / down) partial tiles and their arrival counters (after the barrier words,
+  // so that one fill zeroes both before a launch)
+  int tg_max = 1;
+  for (int l = 0; l < L; ++l)
+    for (const FusedGemm* g : {&m->fused_layers[l].qkv, &m->fused_layers[l].o, &m->fused_layers[l].down})
+      tg_max = g->NT > tg_max ? g->NT : tg_max;
+  p.fix_cnt_stride = (tg_max + 63) / 64 * 64;
+  p.fix_stride = (int64_t)tg_max * 2 * 3 * 256;
+  c->fused_sync_words = 1024 + (int64_t)L * 3 * p.fix_cnt_stride;
+  A((void**)&p.fix_buf, (size_t)L * 3 * p.fix_stride * 4);
+  A((void**)&c->fused_bar, (size_t)(c->fused_sync_words + 64) * 4);
   A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L);
   SSD_TRY(st);
-  c->fused_err = c->fused_bar + 1024;
+  c->fused_err = c->fused_bar + c->fused_sync_words;
   p.bar = c->fused_bar;
+  p.fix_cnt = c->fused_bar + 1024;
   p.err = c->fused_err;
-  SSD_HIP(hipMemset(c->fused_bar, 0, 4096 + 256));
+  SSD_HIP(hipMemset(c->fused_bar, 0, (size_t)(c->fused_sync_words + 64) * 4));
+  p.deep = 1;
+  for (int l = 0; l < L; ++l)
+    for (const FusedGemm* g : {&m->fused_layers[l].qkv, &m->fused_layers[l].o, &m->fused_layers[l].gu, &m->fused_layers[l].down})
+      if (g->KTW % 4) p.deep = 0;
+  if (m->fused_lm.KTW % 4) p.deep = 0;
   std::vector<FusedLayer> host(L);
   const size_t kvd = (size_t)d.kv_dim();
   for (int l = 0; l < L; ++l) {
@@ -329,7 +357,7 @@ int fused_setup(ssd_ctx* c) {
     F.trunk_k = (bf16_t*)c->trunk_k[l]; F.trunk_vt = (bf16_t*)c->trunk_v[l];
     F.suffix_k = (bf16_t*)c->suffix_k[l]; F.suffix_v = (bf16_t*)c->suffix_v[l];
     // masked keys still feed the value MFMA with weight 0: everything there must be finite
-    SSD_HIP(hipMemset(c->trunk_k[l], 0, (size_t)c->B * c->max_trunk * kvd * 2));
+    SSD_HIP(hipMemset(c->trunk_k[l], 0, (size_t)c->B * kvd * c->vt_stride * 2));
     SSD_HIP(hipMemset(c->trunk_v[l], 0, (size_t)c->B * kvd * c->vt_stride * 2));
   }
   SSD_HIP(hipMemcpy(c->fused_layers_dev, host.data(), sizeof(FusedLayer) * L, hipMemcpyHostToDevice));
@@ -406,15 +434,17 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   c->suffix_k.resize(d.n_layers); c->suffix_v.resize(d.n_layers);
   // the fused pass serves every pass of a context it fits (SSD_FUSED=off|phases|persistent overrides, a debugging aid)
   c->fused_mode = model->fused_ok && fused_supported(d, c->max_rows) ? 2 : 0;
+  if (c->fused_mode && (16 / (d.n_q_heads / d.n_kv_heads)) * (c->K + 1 <= 8 ? 8 : 16) > 64) c->fused_mode = 0;
   if (const char* env = getenv("SSD_FUSED")) {
     if (!strcmp(env, "off")) c->fused_mode = 0;
     else if (!strcmp(env, "phases") && c->fused_mode) c->fused_mode = 1;
   }
   c->vt_stride = (c->max_trunk + 63) / 64 * 64;
   for (int l = 0; l < d.n_layers; ++l) {
-    A(&c->trunk_k[l], (size_t)c->B * c->max_trunk * kvd * es);
-    // fused contexts keep the values transposed: [B][Hkv][D][vt_stride]
-    A(&c->trunk_v[l], c->fused_mode ? (size_t)c->B * kvd * c->vt_stride * es : (size_t)c->B * c->max_trunk * kvd * es);
+    // fused contexts keep the trunk head-major, with max_trunk rounded up to 64 positions (layouts in fused.h)
+    const size_t trunk_pos = c->fused_mode ? (size_t)c->vt_stride : (size_t)c->max_trunk;
+    A(&c->trunk_k[l], (size_t)c->B * trunk_pos * kvd * es);
+    A(&c->trunk_v[l], (size_t)c->B * trunk_pos * kvd * es);
     A(&c->suffix_k[l], (size_t)c->M * c->K * kvd * es);
     A(&c->suffix_v[l], (size_t)c->M * c->K * kvd * es);
   }
@@ -488,12 +518,13 @@ int ssd_ctx_load_trunk(ssd_ctx* c, const void* d_k, const void* d_v, int32_t len
   const size_t es = elem_size(d.dtype);
   const size_t per_layer = (size_t)c->B * len * d.kv_dim() * es;
   for (int l = 0; l < d.n_layers; ++l) {
-    SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_k[l], (const char*)d_k + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
-    if (c->fused_mode)
-      SSD_TRY(launch_copy_v_transposed((bf16_t*)c->trunk_v[l], (const bf16_t*)((const char*)d_v + l * per_layer), c->B, len,
-                                       d.n_kv_heads, c->vt_stride, s));
-    else
+    if (c->fused_mode) {
+      SSD_TRY(launch_copy_kv_fused((bf16_t*)c->trunk_k[l], (bf16_t*)c->trunk_v[l], (const bf16_t*)((const char*)d_k + l * per_layer),
+                                   (const bf16_t*)((const char*)d_v + l * per_layer), c->B, len, d.n_kv_heads, c->vt_stride, s));
+    } else {
+      SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_k[l], (const char*)d_k + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
       SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_v[l], (const char*)d_v + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
+    }
   }
   SSD_TRY(launch_fill_i32(c->trunk_len, len, c->B, s));
   c->trunk_ub = len;
@@ -546,7 +577,7 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
   for (int i = 0; i < K; ++i) {
     SSD_TRY(launch_gather_step_tokens(c->step_tokens, c->keys, c->tokens, c->forced_keys, c->forced_tokens, M, K, i, s));
     SSD_TRY(launch_setup_branch_rows(c->rows, c->cos_sin, c->trunk_len, B, K, F, i, d.head_dim / 2, d.rope_theta, s));
-    SSD_TRY(forward_rows(c, M, c->step_tokens, (K + 1) * F, c->trunk_ub + K + 1, c->logits + (size_t)i * V, (int64_t)K * V,
+    SSD_TRY(forward_rows(c, M, c->step_tokens, (K + 1) * F, c->trunk_ub + K + 1, i, c->logits + (size_t)i * V, (int64_t)K * V,
                          c->hidden + (size_t)i * d.d_model, (int64_t)K * d.d_model, s));
     SSD_TRY(launch_sample(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, (K + 1) * F, M, V, round_seed, 0, i,
                           c->tokens + i, K, s));
@@ -608,7 +639,7 @@ int ssd_ctx_enable_phase_clocks(ssd_ctx* c, int32_t on) {
   SSD_CHECK_ARG(c, "ssd_ctx_enable_phase_clocks: null context");
   if (!c->fused_mode) { set_error("phase clocks exist only in contexts served by the fused pass"); return SSD_ESTATE; }
   if (on && !c->phase_clocks) {
-    const size_t n = (size_t)(fused_last_phase(c->fp.L) + 1) * 3 * c->fp.nwg;
+    const size_t n = (size_t)(fused_last_phase(c->fp.L) + 1) * kFusedClockSlots * c->fp.nwg;
     SSD_TRY(c->arena.alloc((void**)&c->phase_clocks, n * sizeof(unsigned long long)));
     SSD_HIP(hipMemset(c->phase_clocks, 0, n * sizeof(unsigned long long)));
   }
@@ -621,7 +652,7 @@ int ssd_ctx_read_phase_clocks(ssd_ctx* c, uint64_t* h_ticks, int64_t n, int32_t*
   if (!c->phase_clocks) { set_error("phase clocks are not enabled"); return SSD_ESTATE; }
   *n_phases = fused_last_phase(c->fp.L) + 1;
   *n_workgroups = c->fp.nwg;
-  const int64_t need = (int64_t)*n_phases * 3 * c->fp.nwg;
+  const int64_t need = (int64_t)*n_phases * kFusedClockSlots * c->fp.nwg;
   SSD_CHECK_ARG(n >= need, "ssd_ctx_read_phase_clocks: buffer of %lld entries, %lld needed", (long long)n, (long long)need);
   SSD_HIP(hipDeviceSynchronize());
   SSD_HIP(hipMemcpy(h_ticks, c->phase_clocks, (size_t)need * sizeof(uint64_t), hipMemcpyDeviceToHost));
