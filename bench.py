@@ -22,6 +22,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the fused decode kernel from the rocprofv3 counter runs summarised in
+# profiles/fused_decode_kernel_1b_p1024_f4_hbm_traffic.txt (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy); None until measured
+MEASURED_TRAFFIC_BYTES = None
 WORKLOAD = "1b_p1024_f4"
 WEIGHT_SEED = 2025
 
@@ -38,12 +41,43 @@ def algorithmic_bytes_per_decode_step(shape, rnd):
     return weights + trunk + logits + suffix
 
 
+def print_phase_clocks(B, ctx, one_round, shape):
+    """Per-phase wall times inside the persistent kernel (last branch-decode step of one more round), from the
+    100 MHz clocks every workgroup records at phase entry / after the grid barrier / at the end of its work."""
+    import numpy as np
+    B.ssd_ctx_enable_phase_clocks(ctx, True)
+    one_round(3000)
+    t = B.ssd_ctx_read_phase_clocks(ctx).astype(np.int64)
+    B.ssd_ctx_enable_phase_clocks(ctx, False)
+    us = (t - t[0, 0].min()) / 100.0
+    entry, after, end = us[:, 0], us[:, 1], us[:, 2]
+    L = shape.n_layers
+    names = ["qkv", "attention", "merge (unused: 1 key split)", "o-proj", "gate/up", "down"]
+    done = end.max(axis=1)
+    w = sys.stderr.write
+    w("phase clocks of one fused decode kernel (us; mean over layers; per workgroup: wait = barrier wait, body = work)\n")
+    w(f"kernel span {end[-1].max() - entry[0].min():.1f}; embedding {done[0] - entry[0].min():.1f}; "
+      f"per layer {(done[6 * L] - done[0]) / L:.2f}; LM head {done[-1] - done[6 * L]:.1f}\n")
+    for s_ in range(6):
+        ph = [1 + 6 * l + s_ for l in range(L)]
+        if (t[ph, 2] == 0).all():                         # the merge phase does not exist with one key split
+            continue
+        wait = np.mean([(after[p_] - entry[p_]).mean() for p_ in ph])
+        body_mean = np.mean([(end[p_] - after[p_]).mean() for p_ in ph])
+        body_max = np.mean([(end[p_] - after[p_]).max() for p_ in ph])
+        w(f"  {names[s_]:10s} wait {wait:6.2f}  body mean {body_mean:6.2f}  body max {body_max:6.2f}\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--phase-clocks", action="store_true",
+                    help="also print (stderr) the per-phase times inside the fused decode kernel of the last branch step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device copy: the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -51,6 +85,15 @@ def main():
 
     import numpy as np
     import torch
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "5 device copies of 1073741824 bytes (elementwise copy kernel)"}))
+        return
 
     import ssd_inputs as I
     from paper_2603_03251_amd import binding as B
@@ -100,14 +143,23 @@ def main():
     elapsed = time.perf_counter() - t0
     # per-segment HIP-event times of the last round + a few extra rounds (the events are per-context)
     seg = []
+    fused = True
     for i in range(min(args.steps, 10)):
         one_round(2000 + i)
-        seg.append(B.ssd_ctx_read_timing(ctx, K))
+        try:
+            seg.append(B.ssd_ctx_read_timing(ctx, K, with_kernels=fused))
+        except B.SsdError:                                # per-operator kernels (SSD_FUSED=off): step times only
+            fused = False
+            seg.append(B.ssd_ctx_read_timing(ctx, K))
     torch.cuda.synchronize()
-    seg = np.array(seg)                                   # [rounds][K+2] ms: glue, fan-out, K steps
-    step_ms = float(seg[:, 2:].mean())
+    seg = np.array(seg)                                   # [rounds][2K+2] ms: glue, fan-out, K steps, K fused kernels
+    step_ms = float(seg[:, 2:K + 2].mean())
+    # the fused decode kernel alone, HIP events on its stream (the whole step if the per-operator kernels ran)
+    kernel_ms = float(seg[:, K + 2:].mean()) if fused else step_ms
+    if args.phase_clocks and fused:
+        print_phase_clocks(B, ctx, one_round, shape)
     bytes_step = algorithmic_bytes_per_decode_step(shape, r)
-    achieved = bytes_step / (step_ms * 1e-3) / 1e9
+    achieved = bytes_step / (kernel_ms * 1e-3) / 1e9
 
     tokens_per_round = nb * (K + 1) * F * K
     ms_per_step = elapsed / args.steps * 1e3
@@ -124,11 +176,12 @@ def main():
                                f"({r.rows} branch rows), lookahead {K}, greedy; verify on a second stream; lookup",
                    "branch_rows": r.rows, "tokens_per_round": tokens_per_round},
         "segments_ms": {"glue_extend": float(seg[:, 0].mean()), "fan_out": float(seg[:, 1].mean()),
-                        "branch_decode_step": step_ms, "decode_steps_total": float(seg[:, 2:].sum(axis=1).mean())},
-        "decode_only_branch_tokens_per_s": tokens_per_round / (float(seg[:, 2:].sum(axis=1).mean()) * 1e-3),
-        "roofline": {"kernel": "batched branch-decode step", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "bytes_per_launch": bytes_step, "avg_ms": step_ms},
+                        "branch_decode_step": step_ms, "decode_steps_total": float(seg[:, 2:K + 2].sum(axis=1).mean())},
+        "decode_only_branch_tokens_per_s": tokens_per_round / (float(seg[:, 2:K + 2].sum(axis=1).mean()) * 1e-3),
+        "roofline": {"kernel": "fused_kernel<2, true>: one batched branch-decode step (24 rows) in one persistent launch",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "bytes_per_launch": bytes_step, "avg_ms": kernel_ms},
     }
 
     if not args.no_cpu_baseline:

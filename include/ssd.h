@@ -203,8 +203,10 @@ int ssd_ctx_refresh_bounds(ssd_ctx* ctx, void* stream);
 
 /* Measurement aid.  With timing on, ssd_prespeculate records HIP events on its stream around the glue extend,
  * the fan-out and each of the K branch-decode steps.  ssd_ctx_read_timing waits for the last event of the most
- * recent round and returns h_ms[K+2] = {glue, fan-out, step 0 .. step K-1} in milliseconds.  Enabling creates
- * the events (set-up, not hot path). */
+ * recent round and returns h_ms[K+2] = {glue, fan-out, step 0 .. step K-1} in milliseconds.  In a context served by
+ * the fused decode pass n may also be 2K+2: the last K entries are then the durations of the fused kernel alone in
+ * each step (events recorded on `stream` right around its launch).  Enabling creates the events (set-up, not hot
+ * path). */
 int ssd_ctx_enable_timing(ssd_ctx* ctx, int32_t on);
 int ssd_ctx_read_timing(ssd_ctx* ctx, float* h_ms, int32_t n);
 

@@ -240,10 +240,12 @@ def ssd_ctx_enable_timing(ctx: int, on: bool) -> None:
     _check(lib.ssd_ctx_enable_timing(ctx, 1 if on else 0))
 
 
-def ssd_ctx_read_timing(ctx: int, K: int):
-    """[glue, fan-out, step 0 .. step K-1] of the last timed round, in milliseconds."""
-    buf = (C.c_float * (K + 2))()
-    _check(lib.ssd_ctx_read_timing(ctx, buf, K + 2))
+def ssd_ctx_read_timing(ctx: int, K: int, with_kernels: bool = False):
+    """[glue, fan-out, step 0 .. step K-1] of the last timed round, in milliseconds; with_kernels (contexts served by
+    the fused pass) appends the K durations of the fused kernel alone."""
+    n = 2 * K + 2 if with_kernels else K + 2
+    buf = (C.c_float * n)()
+    _check(lib.ssd_ctx_read_timing(ctx, buf, n))
     return list(buf)
 
 

@@ -127,6 +127,7 @@ struct ssd_ctx {
   const int32_t* forced_tokens = nullptr;
   // optional per-segment timing of a round: K+3 events (start, glue, fan-out, K steps)
   std::vector<hipEvent_t> events;
+  std::vector<hipEvent_t> kernel_events;   // fused contexts: start/end of the fused kernel of each branch-decode step
   bool timing = false;
 };
 
@@ -239,7 +240,11 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
   p.hidden_ld = hidden_ld;
   const int last = (logits || hidden) ? fused_last_phase(p.L) : fused_last_phase(p.L) - 1;
   SSD_TRY(launch_fill_i32((int32_t*)c->fused_bar, 0, c->fused_sync_words, s));
-  return launch_fused(p, 0, last, c->fused_mode == 2, s);
+  const bool timed = c->timing && branch_depth >= 0 && 2 * branch_depth + 1 < (int)c->kernel_events.size();
+  if (timed) SSD_HIP(hipEventRecord(c->kernel_events[2 * branch_depth], s));
+  SSD_TRY(launch_fused(p, 0, last, c->fused_mode == 2, s));
+  if (timed) SSD_HIP(hipEventRecord(c->kernel_events[2 * branch_depth + 1], s));
+  return SSD_OK;
 }
 
 // One batched pass of the decoder over `M` rows whose descriptors and rotary tables are already in ctx->rows /
@@ -478,6 +483,7 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
 int ssd_ctx_destroy(ssd_ctx* c) {
   if (!c) return SSD_OK;
   for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->kernel_events) (void)hipEventDestroy(e);
   c->arena.release();
   delete c;
   return SSD_OK;
@@ -630,6 +636,11 @@ int ssd_ctx_enable_timing(ssd_ctx* c, int32_t on) {
       SSD_HIP(hipEventCreate(&e));
       c->events.push_back(e);
     }
+    for (int i = 0; c->fused_mode && i < 2 * c->K; ++i) {
+      hipEvent_t e;
+      SSD_HIP(hipEventCreate(&e));
+      c->kernel_events.push_back(e);
+    }
   }
   c->timing = on != 0;
   return SSD_OK;
@@ -661,10 +672,13 @@ int ssd_ctx_read_phase_clocks(ssd_ctx* c, uint64_t* h_ticks, int64_t n, int32_t*
 
 int ssd_ctx_read_timing(ssd_ctx* c, float* h_ms, int32_t n) {
   SSD_CHECK_ARG(c && h_ms, "ssd_ctx_read_timing: null argument");
-  SSD_CHECK_ARG(n == c->K + 2, "ssd_ctx_read_timing: n must be K+2");
+  const bool with_kernels = n == 2 * c->K + 2 && !c->kernel_events.empty();
+  SSD_CHECK_ARG(n == c->K + 2 || with_kernels, "ssd_ctx_read_timing: n must be K+2 (or 2K+2 in a context served by the fused pass)");
   if (!c->timing || !c->have_cache) { set_error("ssd_ctx_read_timing: no timed round has run"); return SSD_ESTATE; }
   SSD_HIP(hipEventSynchronize(c->events[c->K + 2]));
-  for (int i = 0; i < n; ++i) SSD_HIP(hipEventElapsedTime(&h_ms[i], c->events[i], c->events[i + 1]));
+  for (int i = 0; i < c->K + 2; ++i) SSD_HIP(hipEventElapsedTime(&h_ms[i], c->events[i], c->events[i + 1]));
+  for (int i = 0; with_kernels && i < c->K; ++i)
+    SSD_HIP(hipEventElapsedTime(&h_ms[c->K + 2 + i], c->kernel_events[2 * i], c->kernel_events[2 * i + 1]));
   return SSD_OK;
 }
 

@@ -139,6 +139,51 @@ def test_small_bf16_many_rows_and_real_prefill(B):
     _run_round_parity(B, SMALL_BF16, batch=3, P=37, K=4, F=5, seed=8, synthetic_kv=False)
 
 
+def test_small_bf16_fused_pass_with_real_prefill(B):
+    # M = 2 * 4 * 2 = 16 rows: the context is served by the fused pass, so the prefill chunks, the glue extend (causal
+    # rows whose keys exist only in the pass) and the branch steps all run through its attention and K/V append
+    _run_round_parity(B, SMALL_BF16, batch=2, P=37, K=3, F=2, seed=11, synthetic_kv=False)
+
+
+def test_small_bf16_fused_pass_group_of_two_and_long_lookahead(B):
+    # GQA group 2 (8 rows per query tile) and K + 1 = 9 > 8: sixteen fresh-key slots per row, two fresh blocks
+    shape = I.ModelShape(n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=4, head_dim=64, d_ffn=1024,
+                         vocab=4112, dtype="bf16", rope_theta=500000.0, tie_embeddings=True)
+    _run_round_parity(B, shape, batch=1, P=70, K=3, F=3, seed=12, synthetic_kv=True)
+    _run_round_parity(B, SMALL_BF16, batch=1, P=45, K=8, F=2, seed=13, synthetic_kv=False)
+
+
+def test_fused_pass_phase_by_phase_equals_persistent(B, monkeypatch):
+    # the same pass as one launch per phase (no grid barrier) and as one persistent launch: identical bits, since
+    # every sum is taken in a fixed order
+    shape, seed, nb, P, K, F = SMALL_BF16, 21, 2, 50, 3, 3
+    w = I.make_weights(shape, seed)
+    k, v = I.make_prefix_kv(shape, nb, P, seed)
+    pending = dev_i32(I.make_pending(shape, nb, K, seed))
+    temps = dev_f32(np.zeros(nb, np.float32))
+    outs = []
+    for mode in ("phases", "persistent"):
+        monkeypatch.setenv("SSD_FUSED", mode)
+        model = B.ssd_model_create(shape, w)
+        ctx = B.ssd_ctx_create(model, nb, K, F, P + 4 * K + 8)
+        try:
+            B.ssd_ctx_load_trunk(ctx, kv_to_device(k, "bf16"), kv_to_device(v, "bf16"), P)
+            B.ssd_prespeculate(ctx, pending, temps, seed)
+            if mode == "persistent":
+                B.ssd_ctx_enable_phase_clocks(ctx, True)
+                B.ssd_prespeculate(ctx, pending, temps, seed)
+                clocks = B.ssd_ctx_read_phase_clocks(ctx)
+                assert clocks.shape[0] == 2 + 6 * shape.n_layers and clocks.shape[1] == 8
+                assert (clocks[0, 2] >= clocks[0, 0]).all() and (clocks[-1, 2] > clocks[0, 0]).all()
+            outs.append({k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx).items()})
+            B.ssd_ctx_refresh_bounds(ctx)            # would report a grid-barrier time-out
+        finally:
+            B.ssd_ctx_destroy(ctx)
+            B.ssd_model_destroy(model)
+    for name in ("keys", "tokens", "logits", "hidden", "glue_logits"):
+        assert np.array_equal(outs[0][name], outs[1][name]), name
+
+
 def test_small_bf16_head_dim_128_untied(B):
     _run_round_parity(B, SMALL_BF16_D128, batch=1, P=70, K=2, F=2, seed=9, synthetic_kv=True)
 
