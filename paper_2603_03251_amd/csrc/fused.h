@@ -96,7 +96,7 @@ int launch_copy_kv_fused(bf16_t* trunk_k, bf16_t* trunk_vt, const bf16_t* src_k,
                          int vt_stride, hipStream_t s);
 
 // feature tiles per unit of each linear layer
-constexpr int kAtQkv = 1, kAtO = 1, kAtGu = 4, kAtDown = 1, kAtLm = 4;
+constexpr int kAtQkv = 2, kAtO = 2, kAtGu = 4, kAtDown = 2, kAtLm = 4;
 
 bool fused_supported(const Dims& d, int max_rows);
 // Runs phases [first, last].  persistent = 1: one launch with grid barriers between phases (p.bar must be zero);

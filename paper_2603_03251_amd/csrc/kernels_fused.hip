@@ -21,6 +21,8 @@
 // stored transposed in the trunk.  Keys that are private to a row (its own token, its earlier branch tokens, the
 // other tokens of an extend) are a handful and go through one wavefront per (row, head).  A second phase merges
 // the partial softmaxes.  No mask is ever materialised: a row is (visible trunk length, private suffix length).
+#include <type_traits>
+
 #include "fused.h"
 
 namespace ssd {
@@ -65,6 +67,9 @@ __device__ __forceinline__ uint64_t pack_bf16x4(bf16_t a, bf16_t b, bf16_t c, bf
   return (uint64_t)a | ((uint64_t)b << 16) | ((uint64_t)c << 32) | ((uint64_t)d << 48);
 }
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+// fp32 -> bf16, round to nearest even, on the conversion unit gfx950 has for it (v_cvt_pk_bf16_f32): the softmax and the
+// head/remainder splits convert thousands of values per phase, and the integer sequence costs ~8 VALU instructions each
+__device__ __forceinline__ bf16_t to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
 
 // Optional phase clocks (a measurement aid): [phase][slot][workgroup] ticks of the 100 MHz real-time counter; slot 0
 // phase entry, 1 after the grid barrier, 2 end of the phase's work, 3.. probes inside a phase.
@@ -122,7 +127,7 @@ __device__ __forceinline__ bool grid_wait(Grid& g) {
         *g.dead = 1;
         break;
       }
-      __builtin_amdgcn_s_sleep(20);   // idle workgroups must not flood the memory fabric with polls
+      __builtin_amdgcn_s_sleep(1);   // idle workgroups must not flood the memory fabric with polls
     }
   }
   wg_barrier();
@@ -157,21 +162,20 @@ __device__ __forceinline__ void compute_row_scales(const FusedParams& p, const f
 // (4 consecutive features n..n+3 of row m per lane), (h * gain) as head/remainder planes for the next linear
 // layer, and this feature tile's sum of squares per row.
 template <int MT>
-__device__ __forceinline__ void resid_store(const FusedParams& p, f32x4 hn, int m, int n, int lane, const bf16_t* gain,
+__device__ __forceinline__ void resid_store(const FusedParams& p, f32x4 hn, int m, int n, int lane, u32x2 gb,
                                             float* h_out, bf16_t* xn_out, float* ssq_out, int tile) {
   const bool ok = m < p.M;
   float s = 0.f;
   if (ok) {
     st_f32x4(h_out + (int64_t)m * p.d + n, hn);
-    u32x2 gb = *(const gu32x2*)(gain + n);
     float g[4] = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
                   __uint_as_float(gb.y & 0xffff0000u)};
     bf16_t hi[4], lo[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float x = hn[i] * g[i];
-      hi[i] = f32_to_bf16(x);
-      lo[i] = f32_to_bf16(x - bf16_to_f32(hi[i]));
+      hi[i] = to_bf16(x);
+      lo[i] = to_bf16(x - bf16_to_f32(hi[i]));
       s += hn[i] * hn[i];
     }
     int64_t off = b_off<MT>(n, m);
@@ -210,52 +214,16 @@ struct Chunk {
 // AT = 1 serves the qkv, o and down projections (epilogue EPI_QKV / EPI_RESID), AT = 4 the gate/up projection and the
 // LM head (EPI_SWIGLU / EPI_LOGITS).  The epilogue kind is a run-time argument so that each of the two streaming loops
 // exists once in the kernel: its code has to stay resident in the instruction cache across the layers.
-template <int AT, int MT, int NP, int D>
+template <int AT, int MT, int NP, int D, bool PRE>
 __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm g, const bf16_t* bsrc, int64_t bplane,
                                            const int EPI, const EpiArgs& e, Grid& grid, bool do_wait, f32x4* red, float* r_s,
                                            const float* ssq_in, int ph) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int KTW = g.KTW;
-  const int n_my = (int)blockIdx.x < g.n_units ? (g.n_units - 1 - (int)blockIdx.x) / p.nwg + 1 : 0;
-  const int n_chunks = n_my * KTW;
-  Chunk<AT, MT, NP> ring[D];
-
-  // chunk c = (unit blockIdx.x + n * grid, k-tile i of this wavefront); the load cursors advance one chunk at a time
-  const gbf16x8* a_next = (const gbf16x8*)(g.w + (((int64_t)blockIdx.x * kFusedWaves + wave) * KTW * AT) * 512 + lane * 8);
-  const int64_t a_unit_jump = ((int64_t)p.nwg * kFusedWaves - 1) * KTW * AT * 64;   // in 16-byte vectors, added at a unit's end
-  int a_i = 0;
-  auto load_a = [&](Chunk<AT, MT, NP>& ck) {
-#pragma unroll
-    for (int j = 0; j < AT; ++j) ck.a[j] = __builtin_nontemporal_load(a_next + j * 64);
-    a_next += AT * 64;
-    if (++a_i == KTW) { a_i = 0; a_next += a_unit_jump; }
-  };
   // K-split (g.KS > 1, at most one unit per workgroup): unit u = (feature-tile group u / KS, k-slice u % KS)
   const int KS = g.KS, ks = KS > 1 ? (int)blockIdx.x % KS : 0;
   const gbf16x8* b_first = (const gbf16x8*)(bsrc + ((int64_t)((ks * kFusedWaves + wave) * KTW) * MT * 64 + lane) * 8);
   const int64_t bplane_v = bplane / 8;
-  int b_i = 0;
-  auto load_b = [&](Chunk<AT, MT, NP>& ck) {
-    const gbf16x8* bp = b_first + (int64_t)b_i * MT * 64;
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-      for (int pl = 0; pl < NP; ++pl) ck.b[t * NP + pl] = bp[pl * bplane_v + t * 64];
-    if (++b_i == KTW) b_i = 0;
-  };
-
-  // weights of the first chunks go out before the barrier: they depend on nothing
-  if (n_chunks > 0) {
-#pragma unroll
-    for (int s = 0; s < D - 1; ++s) load_a(ring[s]);
-  }
-  if (do_wait && !grid_wait(grid)) return false;
-  stamp(p, ph, 1);
-  if (n_chunks > 0) {
-#pragma unroll
-    for (int s = 0; s < D - 1; ++s) load_b(ring[s]);
-  }
-  if (ssq_in) compute_row_scales(p, ssq_in, r_s);
 
   f32x4 acc[AT][MT];
 #pragma unroll
@@ -263,18 +231,19 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
 #pragma unroll
     for (int t = 0; t < MT; ++t) acc[j][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  auto mfma_chunk = [&](const Chunk<AT, MT, NP>& ck) {
-#pragma unroll
-    for (int j = 0; j < AT; ++j)
-#pragma unroll
-      for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int pl = 0; pl < NP; ++pl)
-          acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ck.a[j], ck.b[t * NP + pl], acc[j][t], 0, 0, 0);
-  };
-
   // End of a unit: sum the 8 wavefronts' partial tiles in LDS and run the epilogue.
   auto finish_unit = [&](int unit) {
+    // the residual-stream tile and the gains this wavefront's epilogue will want: requested now, so that they arrive
+    // under the LDS reduction and the K-split fix-up instead of costing a memory latency at the very end
+    f32x4 h_pre = (f32x4){0.f, 0.f, 0.f, 0.f};
+    u32x2 gain_pre = (u32x2){0u, 0u};
+    if (AT <= 2 && EPI == EPI_RESID && wave < AT * MT && ks == 0) {
+      const int j = wave / MT, t = wave - j * MT;
+      const int tile = (KS > 1 ? unit / KS : unit) * AT + j;
+      const int m = t * 16 + (lane & 15), n = tile * 16 + (lane >> 4) * 4;
+      if (m < p.M) h_pre = *(const gf32x4*)(e.h_in + (int64_t)m * p.d + n);
+      gain_pre = *(const gu32x2*)(e.gain + n);
+    }
 #pragma unroll
     for (int j = 0; j < AT; ++j)
 #pragma unroll
@@ -325,15 +294,13 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
       }
       const int m = t * 16 + (lane & 15);
       const int f4 = (lane >> 4) * 4;
-      if (AT == 1 && EPI == EPI_QKV) {
+      if (AT <= 2 && EPI == EPI_QKV) {
         const int n = (tg * AT + j) * 16 + f4;
         if (m < p.M) st_f32x4(e.out + (int64_t)m * e.ld + n, v);
-      } else if (AT == 1 && EPI == EPI_RESID) {
+      } else if (AT <= 2 && EPI == EPI_RESID) {
         const int tile = tg * AT + j;
         const int n = tile * 16 + f4;
-        f32x4 ho = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if (m < p.M) ho = *(const gf32x4*)(e.h_in + (int64_t)m * p.d + n);
-        resid_store<MT>(p, ho + v, m, n, lane, e.gain, e.h_out, e.xn_out, e.ssq_out, tile);
+        resid_store<MT>(p, h_pre + v, m, n, lane, gain_pre, e.h_out, e.xn_out, e.ssq_out, tile);   // idx == wave here
       } else if (AT == 4 && EPI == EPI_SWIGLU) {
         // tiles 0,1 of the unit are gate, 2,3 the matching up tiles; idx = (gate tile j, row tile t)
         f32x4 u = red[((j + 2) * MT + t) * 64 + lane];
@@ -346,8 +313,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
           for (int i = 0; i < 4; ++i) {
             float gg = v[i] * rs, uu = u[i] * rs;
             float a = gg / (1.0f + __expf(-gg)) * uu;
-            hi[i] = f32_to_bf16(a);
-            lo[i] = f32_to_bf16(a - bf16_to_f32(hi[i]));
+            hi[i] = to_bf16(a);
+            lo[i] = to_bf16(a - bf16_to_f32(hi[i]));
           }
           const int k = unit * 32 + j * 16 + f4;    // input index of the down-projection
           int64_t off = b_off<MT>(k, m);
@@ -369,32 +336,149 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
     wg_barrier();
   };
 
-  // The host guarantees KTW % D == 0: a unit ends only at the end of a group of D chunks, and every load inside
-  // the steady loop is unconditional (the compiler then counts outstanding loads exactly).
-  const int n_outer = n_chunks / D;
-  int c_i = 0, c_unit = blockIdx.x;
-  for (int q = 0; q + 1 < n_outer; ++q) {
-#pragma unroll
-    for (int s = 0; s < D; ++s) {
-      load_a(ring[(s + D - 1) % D]);
-      load_b(ring[(s + D - 1) % D]);
-      mfma_chunk(ring[s]);
+
+  if constexpr (PRE) {
+    // ---- at most one unit per workgroup (the host checks n_units <= grid): ALL of the wavefront's weight tiles are
+    // requested before the workgroup waits at the barrier, so the weight stream of the phase runs under the barrier
+    // latency, the activation fetch and the row scales; after the barrier only the activation tiles (L2) are loaded,
+    // through a short ring.  KTW is a run-time value: one fully unrolled instance per supported value, so that every
+    // register index is static and the compiler counts outstanding loads exactly.
+    if ((int)blockIdx.x >= g.n_units) {
+      if (do_wait && !grid_wait(grid)) return false;
+      stamp(p, ph, 1);
+      if (ssq_in) compute_row_scales(p, ssq_in, r_s);
+      return true;
     }
-    c_i += D;
-    if (c_i == KTW) {
-      c_i = 0;
+    constexpr int KMAX = 16 / AT;   // most k-tiles per wavefront and unit (the host checks)
+    const gbf16x8* a_base = (const gbf16x8*)(g.w + (((int64_t)blockIdx.x * kFusedWaves + wave) * KTW * AT) * 512 + lane * 8);
+    bf16x8 a[KMAX][AT];
+#pragma unroll
+    for (int i = 0; i < KMAX; ++i)
+      if (i < KTW) {
+#pragma unroll
+        for (int j = 0; j < AT; ++j) a[i][j] = __builtin_nontemporal_load(a_base + (i * AT + j) * 64);
+      }
+    if (do_wait && !grid_wait(grid)) return false;
+    stamp(p, ph, 1);
+    // Activation tiles.  Every workgroup reads the whole activation matrix of its k-range, and all of them the same
+    // lines at the same time: this L2-to-CU traffic, not the weight stream, is what limits these phases, so rows
+    // beyond M (the padding of the last 16-row tile) are not fetched at all.
+    // (their lanes re-read row 0 of their k-group, a line that is fetched anyway; an unconditional load keeps the
+    // compiler's count of outstanding loads exact, and those rows' results are never stored)
+    int row_fix[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) row_fix[t] = t * 16 + (lane & 15) < p.M ? 0 : -(lane & 15);
+    auto load_b = [&](bf16x8* dst, int c) {
+      const gbf16x8* bp = b_first + (int64_t)c * MT * 64;
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl) dst[t * NP + pl] = bp[pl * bplane_v + t * 64 + row_fix[t]];
+    };
+    // the activation tiles of KC chunks through a ring of DB, straight-line code with static register indices
+    auto run = [&](auto kc_tag) {
+      constexpr int KC = decltype(kc_tag)::value;
+      constexpr int DB = KC < 4 ? KC : 4;
+      bf16x8 b[DB][MT * NP];
+#pragma unroll
+      for (int c = 0; c < DB - 1; ++c) load_b(b[c], c);
+#pragma unroll
+      for (int c = 0; c < KC; ++c) {
+        if (c + DB - 1 < KC) load_b(b[(c + DB - 1) % DB], c + DB - 1);
+#pragma unroll
+        for (int j = 0; j < AT; ++j)
+#pragma unroll
+          for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl)
+              acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[c][j], b[c % DB][t * NP + pl], acc[j][t], 0, 0, 0);
+      }
+    };
+    if (KTW == 2) run(std::integral_constant<int, 2>());
+    else if (KTW == 4) run(std::integral_constant<int, 4>());
+    else run(std::integral_constant<int, 8>());
+    stamp(p, ph, 3);
+    if (ssq_in) compute_row_scales(p, ssq_in, r_s);   // for the next phase (qkv -> attention)
+    stamp(p, ph, 4);
+    finish_unit((int)blockIdx.x);
+    stamp(p, ph, 5);
+    return true;
+  } else {
+    // ---- any number of units per workgroup (the LM head): weights and activations travel together through a ring
+    // of D register chunks
+    const int n_my = (int)blockIdx.x < g.n_units ? (g.n_units - 1 - (int)blockIdx.x) / p.nwg + 1 : 0;
+    const int n_chunks = n_my * KTW;
+    Chunk<AT, MT, NP> ring[D];
+    // chunk c = (unit blockIdx.x + n * grid, k-tile i of this wavefront); the load cursors advance one chunk at a time
+    const gbf16x8* a_next = (const gbf16x8*)(g.w + (((int64_t)blockIdx.x * kFusedWaves + wave) * KTW * AT) * 512 + lane * 8);
+    const int64_t a_unit_jump = ((int64_t)p.nwg * kFusedWaves - 1) * KTW * AT * 64;   // in 16-byte vectors, at a unit's end
+    int a_i = 0;
+    auto load_a = [&](Chunk<AT, MT, NP>& ck) {
+#pragma unroll
+      for (int j = 0; j < AT; ++j) ck.a[j] = __builtin_nontemporal_load(a_next + j * 64);
+      a_next += AT * 64;
+      if (++a_i == KTW) { a_i = 0; a_next += a_unit_jump; }
+    };
+    int b_i = 0;
+    int row_fix[MT];   // rows beyond M (padding of the last row tile) are not fetched: their lanes re-read row 0
+#pragma unroll
+    for (int t = 0; t < MT; ++t) row_fix[t] = t * 16 + (lane & 15) < p.M ? 0 : -(lane & 15);
+    auto load_b = [&](Chunk<AT, MT, NP>& ck) {
+      const gbf16x8* bp = b_first + (int64_t)b_i * MT * 64;
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl) ck.b[t * NP + pl] = bp[pl * bplane_v + t * 64 + row_fix[t]];
+      if (++b_i == KTW) b_i = 0;
+    };
+    auto mfma_chunk = [&](const Chunk<AT, MT, NP>& ck) {
+#pragma unroll
+      for (int j = 0; j < AT; ++j)
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+          for (int pl = 0; pl < NP; ++pl)
+            acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ck.a[j], ck.b[t * NP + pl], acc[j][t], 0, 0, 0);
+    };
+    // weights of the first chunks go out before the barrier: they depend on nothing
+    if (n_chunks > 0) {
+#pragma unroll
+      for (int s = 0; s < D - 1; ++s) load_a(ring[s]);
+    }
+    if (do_wait && !grid_wait(grid)) return false;
+    stamp(p, ph, 1);
+    if (n_chunks > 0) {
+#pragma unroll
+      for (int s = 0; s < D - 1; ++s) load_b(ring[s]);
+    }
+    if (ssq_in) compute_row_scales(p, ssq_in, r_s);
+    // The host guarantees KTW % D == 0: a unit ends only at the end of a group of D chunks, and every load inside
+    // the steady loop is unconditional (the compiler then counts outstanding loads exactly).
+    const int n_outer = n_chunks / D;
+    int c_i = 0, c_unit = blockIdx.x;
+    for (int q = 0; q + 1 < n_outer; ++q) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) {
+        load_a(ring[(s + D - 1) % D]);
+        load_b(ring[(s + D - 1) % D]);
+        mfma_chunk(ring[s]);
+      }
+      c_i += D;
+      if (c_i == KTW) {
+        c_i = 0;
+        finish_unit(c_unit);
+        c_unit += p.nwg;
+      }
+    }
+    if (n_outer > 0) {
+      load_a(ring[D - 1]);
+      load_b(ring[D - 1]);
+#pragma unroll
+      for (int s = 0; s < D; ++s) mfma_chunk(ring[s]);
       finish_unit(c_unit);
-      c_unit += p.nwg;
     }
+    return true;
   }
-  if (n_outer > 0) {
-    load_a(ring[D - 1]);
-    load_b(ring[D - 1]);
-#pragma unroll
-    for (int s = 0; s < D; ++s) mfma_chunk(ring[s]);
-    finish_unit(c_unit);
-  }
-  return true;
 }
 
 // ---------------------------------------------------------------------------------------------- attention
@@ -431,8 +515,8 @@ __device__ __forceinline__ void softmax_block(OnlineSoftmax& st, const f32x4 S[2
   for (int i = 0; i < 8; ++i) {
     float pe = exp2_fast(sv[i] - m_use);
     psum += pe;
-    ph.u[i] = f32_to_bf16(pe);
-    pl.u[i] = f32_to_bf16(pe - bf16_to_f32(ph.u[i]));
+    ph.u[i] = to_bf16(pe);
+    pl.u[i] = to_bf16(pe - bf16_to_f32(ph.u[i]));
   }
   st.l_run = st.l_run * corr + psum;
   st.m_run = m_new;
@@ -593,10 +677,10 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
     for (int i = 0; i < 8; ++i) {
       float c = cc[2 * i], sn = cc[2 * i + 1];
       float x0 = (a[i] * c - bb[i] * sn) * scale, x1 = (bb[i] * c + a[i] * sn) * scale;
-      qh[0].u[i] = f32_to_bf16(x0);
-      qh[1].u[i] = f32_to_bf16(x1);
-      ql[0].u[i] = f32_to_bf16(x0 - bf16_to_f32(qh[0].u[i]));
-      ql[1].u[i] = f32_to_bf16(x1 - bf16_to_f32(qh[1].u[i]));
+      qh[0].u[i] = to_bf16(x0);
+      qh[1].u[i] = to_bf16(x1);
+      ql[0].u[i] = to_bf16(x0 - bf16_to_f32(qh[0].u[i]));
+      ql[1].u[i] = to_bf16(x1 - bf16_to_f32(qh[1].u[i]));
     }
   }
   stamp(p, ph, 4);
@@ -623,16 +707,16 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             float c = cc[2 * e], sn = cc[2 * e + 1];
-            x0[e] = f32_to_bf16((x.a[e] * c - x.bb[e] * sn) * rs);
-            x1[e] = f32_to_bf16((x.bb[e] * c + x.a[e] * sn) * rs);
+            x0[e] = to_bf16((x.a[e] * c - x.bb[e] * sn) * rs);
+            x1[e] = to_bf16((x.bb[e] * c + x.a[e] * sn) * rs);
           }
           uint64_t p0 = pack_bf16x4(x0[0], x0[1], x0[2], x0[3]), p1 = pack_bf16x4(x1[0], x1[1], x1[2], x1[3]);
           k_lo = (u32x2){(uint32_t)p0, (uint32_t)(p0 >> 32)};
           k_hi = (u32x2){(uint32_t)p1, (uint32_t)(p1 >> 32)};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            vv.u[e] = f32_to_bf16(x.v0[e] * rs);
-            vv.u[4 + e] = f32_to_bf16(x.v1[e] * rs);
+            vv.u[e] = to_bf16(x.v0[e] * rs);
+            vv.u[4 + e] = to_bf16(x.v1[e] * rs);
           }
           // append for later passes: the row's private suffix slot (branch) or its trunk position (extend)
           if (is_branch) {
@@ -742,8 +826,8 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           float x = o[i] * inv;
-          hi[i] = f32_to_bf16(x);
-          lo[i] = f32_to_bf16(x - bf16_to_f32(hi[i]));
+          hi[i] = to_bf16(x);
+          lo[i] = to_bf16(x - bf16_to_f32(hi[i]));
         }
         const int64_t off = b_off<MT>(k, mm);
         st_u64(att_out + off, pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
@@ -784,8 +868,8 @@ __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, 
     o += wgt * go[pb * 64 + d];
   }
   const float x = o / lsum;
-  const bf16_t hi = f32_to_bf16(x);
-  const bf16_t lo = f32_to_bf16(x - bf16_to_f32(hi));
+  const bf16_t hi = to_bf16(x);
+  const bf16_t lo = to_bf16(x - bf16_to_f32(hi));
   // lanes d, d+1, d+2, d+3 -> one 8-byte store per plane from lane d (d % 4 == 0)
   uint32_t w = (uint32_t)hi | ((uint32_t)lo << 16);
   uint32_t w1 = __shfl_down(w, 1), w2 = __shfl_down(w, 2), w3 = __shfl_down(w, 3);
@@ -796,27 +880,6 @@ __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, 
     st_u64(att_out + (int64_t)MP * p.qd + off,
            pack_bf16x4((bf16_t)(w >> 16), (bf16_t)(w1 >> 16), (bf16_t)(w2 >> 16), (bf16_t)(w3 >> 16)));
   }
-}
-
-// A compute unit pulls only ~30 GB/s out of HBM (latency x its limited number of misses in flight) but over 100 GB/s
-// out of its L2.  The 48-odd attention units of a layer cannot afford to fetch the trunk K/V of their head from HBM
-// themselves, so during the qkv phase EVERY workgroup touches a 1/32nd slice of "its" head's K/V (workgroup g serves
-// KV head g % Hkv: workgroups are dealt round-robin to the 8 XCDs, whose L2s are private, and attention unit u of
-// head hk = u % Hkv runs as workgroup u).  Purely a performance hint: nothing depends on where a line ends up.
-__device__ __forceinline__ unsigned prefetch_trunk_kv(const FusedParams& p, const FusedLayer& L) {
-  const int hk = blockIdx.x % p.Hkv, rank = blockIdx.x / p.Hkv, n_rank = (p.nwg + p.Hkv - 1) / p.Hkv;
-  const int lines = p.tv_ub;   // one 128-byte line per stored key in K, and as many in V^T
-  unsigned acc = 0;
-  for (int b = 0; b < p.B; ++b) {
-    const int64_t head = (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64;
-    const __attribute__((address_space(1))) unsigned* k = (const __attribute__((address_space(1))) unsigned*)(L.trunk_k + head);
-    const __attribute__((address_space(1))) unsigned* v = (const __attribute__((address_space(1))) unsigned*)(L.trunk_vt + head);
-    for (int i = rank * kFusedThreads + threadIdx.x; i < lines; i += n_rank * kFusedThreads) {
-      acc ^= k[(int64_t)i * 32];
-      acc ^= v[(int64_t)i * 32];
-    }
-  }
-  return acc;
 }
 
 // ---------------------------------------------------------------------------------------------- the kernel
@@ -839,12 +902,16 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
   const int64_t h_stride = (int64_t)MP * p.d;
   const int64_t ssq_stride = (int64_t)(p.d >> 4) * MP;
   const int lm_phase = fused_last_phase(p.L);
-  unsigned sink = 0;   // keeps prefetch loads alive
 
   for (int ph = first; ph <= last; ++ph) {
     if (p.NS == 1 && ph > 0 && ph < lm_phase && (ph - 1) % 6 == 2) continue;
     const bool do_wait = persistent && ph > first;
     stamp(p, ph, 0);
+    if (ph == 0 && p.prof && threadIdx.x == 0) {
+      unsigned xcc;
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+      p.prof[(int64_t)7 * p.nwg + blockIdx.x] = xcc;   // phase 0, slot 7: the XCD this workgroup runs on
+    }
     const int l = ph == 0 ? 0 : (ph == lm_phase ? p.L - 1 : (ph - 1) / 6);
     const int sub = ph == 0 ? -1 : (ph == lm_phase ? 6 : (ph - 1) % 6);
     const FusedLayer L = p.layers[l];
@@ -902,14 +969,14 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
           u32x2 eb = *(const gu32x2*)(p.embed + (int64_t)tok * p.d + n);
           f32x4 hn = (f32x4){__uint_as_float(eb.x << 16), __uint_as_float(eb.x & 0xffff0000u),
                              __uint_as_float(eb.y << 16), __uint_as_float(eb.y & 0xffff0000u)};
-          resid_store<MT>(p, hn, m, n, lane, L.attn_norm, p.h, p.xn, p.ssq, u);
+          resid_store<MT>(p, hn, m, n, lane, *(const gu32x2*)(L.attn_norm + n), p.h, p.xn, p.ssq, u);
         }
       }
     } else if (sub == 0 || sub == 3 || sub == 5) {
-      if (!gemm_phase<1, MT, 2, Depth<MT, DEEP>::a1>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph)) return;
-      if (sub == 0) sink ^= prefetch_trunk_kv(p, L);
+      if (!gemm_phase<kAtQkv, MT, 2, 2, true>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph)) return;
     } else if (sub == 4 || sub == 6) {
-      if (!gemm_phase<4, MT, 2, Depth<MT, DEEP>::a4>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph)) return;
+      const bool ok = gemm_phase<4, MT, 2, Depth<MT, DEEP>::a4, false>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
+      if (!ok) return;
       if (sub == 6 && p.hidden) {
         // final-norm hidden states (the row scales are in LDS)
         const gfloat* hv = (const gfloat*)(p.h + (int64_t)(2 * p.L) * h_stride);
@@ -939,7 +1006,6 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
     stamp(p, ph, 2);
     if (ph < last) grid_arrive(grid);
   }
-  if (sink == 0x9e3779b9u && p.err) *p.err = 2;   // never true in practice; the prefetched words must count as used
 }
 
 // ---------------------------------------------------------------------------------------------- set-up kernels

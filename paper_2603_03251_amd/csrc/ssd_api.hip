@@ -185,7 +185,8 @@ int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
       int N = mode == 0 ? r0 + r1 + r2 : 2 * r0;
       const int NT = (N + 15) / 16, groups = (NT + at - 1) / at;
       int ks = 1;
-      if (ks_wanted > 1 && groups * ks_wanted <= grid && (Kd / 256) % (4 * ks_wanted) == 0) ks = ks_wanted;
+      for (int k = ks_wanted; k > 1; k /= 2)
+        if (groups * k <= grid && (Kd / 256) % (2 * k) == 0) { ks = k; break; }
       void* dst = nullptr;
       SSD_TRY(m->arena.alloc(&dst, (size_t)stream_order_elems(N, Kd, at) * 2));
       SSD_TRY(launch_retile_stream((const bf16_t*)s0, r0, (const bf16_t*)s1, r1, (const bf16_t*)s2, r2, mode, at, ks, Kd,
@@ -203,9 +204,15 @@ int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
       SSD_TRY(make(&F.qkv, w->h_wq[l], qd, w->h_wk[l], kvd, w->h_wv[l], kvd, 0, kAtQkv, 1, d.d_model));
       SSD_TRY(make(&F.o, w->h_wo[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtO, 2, qd));
       SSD_TRY(make(&F.gu, w->h_w_gate[l], d.d_ffn, w->h_w_up[l], d.d_ffn, nullptr, 0, 1, kAtGu, 1, d.d_model));
-      SSD_TRY(make(&F.down, w->h_w_down[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtDown, 2, d.d_ffn));
+      SSD_TRY(make(&F.down, w->h_w_down[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtDown, 4, d.d_ffn));
     }
     SSD_TRY(make(&m->fused_lm, head_src, d.vocab, nullptr, 0, nullptr, 0, 0, kAtLm, 1, d.d_model));
+    // the layer phases give every workgroup at most one unit and unroll over the k-tiles of a wavefront
+    auto fits = [&](const FusedGemm& g, int max_ktw) {
+      return g.n_units <= grid && (g.KTW == 2 || g.KTW == 4 || g.KTW == 8) && g.KTW <= max_ktw;
+    };
+    for (const ssd_model::FusedW& F : m->fused_layers)
+      if (!fits(F.qkv, 8) || !fits(F.o, 8) || !fits(F.down, 8)) m->fused_ok = false;
   }
   return SSD_OK;
 }
@@ -336,7 +343,7 @@ int fused_setup(ssd_ctx* c) {
     for (const FusedGemm* g : {&m->fused_layers[l].qkv, &m->fused_layers[l].o, &m->fused_layers[l].down})
       tg_max = g->NT > tg_max ? g->NT : tg_max;
   p.fix_cnt_stride = (tg_max + 63) / 64 * 64;
-  p.fix_stride = (int64_t)tg_max * 2 * 3 * 256;
+  p.fix_stride = (int64_t)tg_max * 4 * 3 * 256;   // tile groups x slices (<= 4) x row tiles (<= 3) x 256 floats, AT folded into tg_max
   c->fused_sync_words = 1024 + (int64_t)L * 3 * p.fix_cnt_stride;
   A((void**)&p.fix_buf, (size_t)L * 3 * p.fix_stride * 4);
   A((void**)&c->fused_bar, (size_t)(c->fused_sync_words + 64) * 4);
@@ -347,10 +354,9 @@ int fused_setup(ssd_ctx* c) {
   p.fix_cnt = c->fused_bar + 1024;
   p.err = c->fused_err;
   SSD_HIP(hipMemset(c->fused_bar, 0, (size_t)(c->fused_sync_words + 64) * 4));
-  p.deep = 1;
+  p.deep = 1;   // ring depth of the gate/up and LM-head streaming loops
   for (int l = 0; l < L; ++l)
-    for (const FusedGemm* g : {&m->fused_layers[l].qkv, &m->fused_layers[l].o, &m->fused_layers[l].gu, &m->fused_layers[l].down})
-      if (g->KTW % 4) p.deep = 0;
+    if (m->fused_layers[l].gu.KTW % 4) p.deep = 0;
   if (m->fused_lm.KTW % 4) p.deep = 0;
   std::vector<FusedLayer> host(L);
   const size_t kvd = (size_t)d.kv_dim();
