@@ -13,8 +13,9 @@ namespace ssd {
 constexpr int kFusedThreads = 512;  // 8 wavefronts; they split the reduction dimension of a weight block
 constexpr int kFusedWaves = 8;
 constexpr int kFusedMaxRows = 48;   // rows of one pass (three 16-row MFMA tiles)
-constexpr int kFusedActPlanes = 2;
-constexpr int kFusedClockSlots = 8;  // clock probes per phase and workgroup (see stamp())  // bf16 planes of the SwiGLU output (1 = rounded to bf16, 2 = head + remainder)
+constexpr int kFusedActPlanes = 2;   // bf16 planes of the SwiGLU output (1 = rounded to bf16, 2 = head + remainder)
+constexpr int kFusedClockSlots = 8;  // clock probes per phase and workgroup (see stamp())
+constexpr int kFusedMaxSlices = 4;   // most k-slices of a linear layer
 
 // A linear layer in "stream order".  The [N][Kd] matrix is cut into 1 KiB MFMA tiles (16 features x 32 inputs,
 // stored as the 64 lanes of an MFMA 16x16x32 A operand hold them).  A unit is AT feature tiles over the whole
@@ -26,8 +27,8 @@ struct FusedGemm {
   int KTW;      // k-tiles per wavefront and unit = Kd / 32 / 8 / KS
   int n_units;  // ceil(NT / AT) * KS
   int NT;       // real feature tiles (the last unit may hold zero padding)
-  int KS;       // k-slices: with KS > 1 unit u = (tile group u / KS, slice u % KS) covers 1/KS of the reduction dimension
-                // and slice 0 adds the others' partial tiles in order; needs n_units <= grid (one unit per workgroup)
+  int KS;       // k-slices (<= kFusedMaxSlices): with KS > 1 unit u = (tile group u / KS, slice u % KS) covers 1/KS of the
+                // reduction dimension and slice 0 adds the others' partial tiles in order; needs n_units <= grid
 };
 
 struct FusedLayer {
@@ -67,9 +68,9 @@ struct FusedParams {
   float* qkv;      // [L][48][qkvd]    raw projections (before the norm's row scale and the rotary embedding)
   bf16_t* att;     // [L][2][48*qd]    attention output planes, B-operand order
   bf16_t* act;     // [L][planes][48*ffn]
-  float* fix_buf;  // [L][3][fix_stride]  partial tiles of K-split linear layers (qkv, o, down)
-  unsigned* fix_cnt;  // [L][3][fix_cnt_stride] published slices per tile group, zeroed before every launch
-  int64_t fix_stride, fix_cnt_stride;
+  float* fix_buf;  // [L][3][fix_stride]  partial tiles of K-split linear layers (qkv, o, down); every word holds
+                   // 0xffffffff ("not written yet") between launches: the reader of a tile puts that value back
+  int64_t fix_stride;
   float* part_o;   // [L][B][Hkv][NS][QT*16][64]  partial softmaxes of the key splits (NS > 1 only)
   float* part_ml;  // [L][B][Hkv][NS][QT*16][2]
   int64_t part_layer_stride;               // in (q-row) entries

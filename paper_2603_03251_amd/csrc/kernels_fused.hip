@@ -63,6 +63,24 @@ __device__ __forceinline__ void st_f32x4(float* p, f32x4 v) {
   st_u64(p, pack_f32x2(v[0], v[1]));
   st_u64(p + 2, pack_f32x2(v[2], v[3]));
 }
+// Partial tiles of a K-split are their own "ready" flag: a word that holds kFixEmpty (a NaN pattern no sum of
+// products produces) has not been written in this launch.  The reader takes the tile with loads that are served by
+// the L2 (agent scope) and writes kFixEmpty back.
+constexpr unsigned kFixEmpty = 0xffffffffu;
+__device__ __forceinline__ f32x4 ld_f32x4_coherent(const float* p) {
+  const uint64_t a = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint64_t b = __hip_atomic_load((const uint64_t*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return (f32x4){__uint_as_float((unsigned)a), __uint_as_float((unsigned)(a >> 32)), __uint_as_float((unsigned)b),
+                 __uint_as_float((unsigned)(b >> 32))};
+}
+__device__ __forceinline__ bool fix_ready(f32x4 v) {
+  return __float_as_uint(v[0]) != kFixEmpty && __float_as_uint(v[1]) != kFixEmpty && __float_as_uint(v[2]) != kFixEmpty &&
+         __float_as_uint(v[3]) != kFixEmpty;
+}
+__device__ __forceinline__ f32x4 fix_empty() {
+  const float e = __uint_as_float(kFixEmpty);
+  return (f32x4){e, e, e, e};
+}
 __device__ __forceinline__ uint64_t pack_bf16x4(bf16_t a, bf16_t b, bf16_t c, bf16_t d) {
   return (uint64_t)a | ((uint64_t)b << 16) | ((uint64_t)c << 32) | ((uint64_t)d << 48);
 }
@@ -200,7 +218,6 @@ struct EpiArgs {
   float* ssq_out;
   bf16_t* act_out;     // SWIGLU
   float* fix_buf;      // K-split: [tile group][slice][tile][64 lanes][4] partial tiles of this phase instance
-  unsigned* fix_cnt;   // K-split: [tile group] slices that have published, zero at launch
 };
 
 template <int AT, int MT, int NP>
@@ -254,34 +271,19 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
     wg_barrier();
     const int NOUT = EPI == EPI_SWIGLU ? 2 * MT : AT * MT;
     const int tg = KS > 1 ? unit / KS : unit;     // feature-tile group of the unit
-    if (KS > 1) {
-      // Ordered fix-up of the K-split: slices 1.. publish their reduced tiles and count themselves in; slice 0 waits
-      // for the count, adds the partials in slice order (the result does not depend on timing) and runs the epilogue.
+    if (KS > 1 && ks > 0) {
+      // K-split, slices 1..: publish the reduced tiles.  The partial-tile buffer holds kFixEmpty words between
+      // launches, so the data are their own "ready" flag and no counter or extra round trip is needed.
       float* fix = e.fix_buf + ((int64_t)tg * KS) * (AT * MT) * 256;
-      if (ks > 0) {
-        for (int idx = wave; idx < AT * MT; idx += kFusedWaves) {
-          f32x4 v = red[idx * 64 + lane];
+      for (int idx = wave; idx < AT * MT; idx += kFusedWaves) {
+        f32x4 v = red[idx * 64 + lane];
 #pragma unroll
-          for (int w = 1; w < kFusedWaves; ++w) v += red[(w * (AT * MT) + idx) * 64 + lane];
-          st_f32x4(fix + ((int64_t)ks * (AT * MT) + idx) * 256 + lane * 4, v);
-        }
-        __builtin_amdgcn_s_waitcnt(0);
-        wg_barrier();
-        if (threadIdx.x == 0) __hip_atomic_fetch_add(e.fix_cnt + tg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return;
+        for (int w = 1; w < kFusedWaves; ++w) v += red[(w * (AT * MT) + idx) * 64 + lane];
+        st_f32x4(fix + ((int64_t)ks * (AT * MT) + idx) * 256 + lane * 4, v);
       }
-      if (threadIdx.x == 0) {
-        unsigned spins = 0;
-        while (__hip_atomic_load(e.fix_cnt + tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (unsigned)(KS - 1)) {
-          if (++spins > kSpinLimit) {
-            __hip_atomic_store(grid.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            *grid.dead = 1;
-            break;
-          }
-          __builtin_amdgcn_s_sleep(1);
-        }
-      }
+      __builtin_amdgcn_s_waitcnt(0);
       wg_barrier();
+      return;
     }
     for (int idx = wave; idx < NOUT; idx += kFusedWaves) {
       const int j = idx / MT, t = idx - j * MT;
@@ -289,8 +291,30 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
 #pragma unroll
       for (int w = 1; w < kFusedWaves; ++w) v += red[(w * (AT * MT) + j * MT + t) * 64 + lane];
       if (KS > 1) {
-        const float* fix = e.fix_buf + ((int64_t)tg * KS) * (AT * MT) * 256;
-        for (int q = 1; q < KS; ++q) v += *(const gf32x4*)(fix + ((int64_t)q * (AT * MT) + idx) * 256 + lane * 4);
+        // Ordered fix-up: slice 0 polls the other slices' tiles until no word is kFixEmpty, adds them in slice order
+        // (the result does not depend on timing) and puts kFixEmpty back for the next launch.
+        float* fix = e.fix_buf + ((int64_t)tg * KS) * (AT * MT) * 256 + (int64_t)idx * 256 + lane * 4;
+        f32x4 pv[kFusedMaxSlices - 1];
+        unsigned pending = (1u << (KS - 1)) - 1u, spins = 0;
+        while (pending) {
+#pragma unroll
+          for (int q = 0; q < kFusedMaxSlices - 1; ++q)
+            if (pending >> q & 1u) pv[q] = ld_f32x4_coherent(fix + (int64_t)(q + 1) * (AT * MT) * 256);
+#pragma unroll
+          for (int q = 0; q < kFusedMaxSlices - 1; ++q)
+            if ((pending >> q & 1u) && fix_ready(pv[q])) pending &= ~(1u << q);
+          if (pending && ++spins > kSpinLimit) {
+            __hip_atomic_store(grid.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *grid.dead = 1;
+            break;
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < kFusedMaxSlices - 1; ++q)
+          if (q + 1 < KS) {
+            v += pv[q];
+            st_f32x4(fix + (int64_t)(q + 1) * (AT * MT) * 256, fix_empty());
+          }
       }
       const int m = t * 16 + (lane & 15);
       const int f4 = (lane >> 4) * 4;
@@ -929,11 +953,12 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
     // K-split scratch of this phase instance (sub 0, 3, 5 -> slot 0, 1, 2)
     const int fix_slot = l * 3 + (sub == 0 ? 0 : (sub == 3 ? 1 : 2));
     e.fix_buf = p.fix_buf + (int64_t)fix_slot * p.fix_stride;
-    e.fix_cnt = p.fix_cnt + (int64_t)fix_slot * p.fix_cnt_stride;
     if (sub == 0) {
       g = L.qkv; bsrc = p.xn + (int64_t)(2 * l) * 2 * h_stride; bplane = h_stride; epi = EPI_QKV;
       e.out = qkv; e.ld = p.qkvd;
-      ssq_in = p.ssq + (int64_t)(2 * l) * ssq_stride;   // the attention phase finds this layer's row scales in LDS
+      // the attention phase finds this layer's row scales in LDS; attention units are dealt out from the far end of
+      // the grid, so (few rows) the workgroups that compute them here are not the ones that hold a qkv unit
+      if (p.nwg - 1 - (int)blockIdx.x < p.n_attn_units) ssq_in = p.ssq + (int64_t)(2 * l) * ssq_stride;
     } else if (sub == 3 || sub == 5) {
       const int v = sub == 3 ? 2 * l + 1 : 2 * l + 2;
       g = sub == 3 ? L.o : L.down;
@@ -992,7 +1017,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       // the qkv phase left this layer's row scales in LDS; a launch that starts here computes them itself
       if (ph == first) compute_row_scales(p, p.ssq + (int64_t)(2 * l) * ssq_stride, r_s);
       stamp(p, ph, 3);
-      for (int u = blockIdx.x; u < p.n_attn_units; u += p.nwg)
+      for (int u = p.nwg - 1 - (int)blockIdx.x; u < p.n_attn_units; u += p.nwg)
         attn_unit<MT, 2, 2>(p, L, qkv, u, r_s, red, att, part_o, part_ml, ph);
     } else {
       // merge of the key splits; with a single split the attention units wrote the final output and this phase

@@ -120,7 +120,7 @@ struct ssd_ctx {
   FusedLayer* fused_layers_dev = nullptr;
   unsigned* fused_bar = nullptr;
   unsigned* fused_err = nullptr;
-  int64_t fused_sync_words = 0; // barrier words + K-split counters, zeroed before every persistent launch
+  int64_t fused_sync_words = 0; // barrier words, zeroed before every persistent launch
   int64_t part_entries = 0;    // per-layer capacity of the attention partial buffers, in query rows
   unsigned long long* phase_clocks = nullptr;
   const int32_t* forced_keys = nullptr;
@@ -336,24 +336,23 @@ int fused_setup(ssd_ctx* c) {
   p.part_layer_stride = c->part_entries;
   A((void**)&p.part_o, (size_t)L * c->part_entries * 64 * 4);
   A((void**)&p.part_ml, (size_t)L * c->part_entries * 2 * 4);
-  // K-split scratch: per (layer, qkv / o / down) partial tiles and their arrival counters (after the barrier words,
-  // so that one fill zeroes both before a launch)
+  // K-split scratch: per (layer, qkv / o / down) partial tiles.  A word of 0xffffffff means "not written in this
+  // launch": filled once here, and the kernel's reader restores it after taking a tile.
   int tg_max = 1;
   for (int l = 0; l < L; ++l)
     for (const FusedGemm* g : {&m->fused_layers[l].qkv, &m->fused_layers[l].o, &m->fused_layers[l].down})
       tg_max = g->NT > tg_max ? g->NT : tg_max;
-  p.fix_cnt_stride = (tg_max + 63) / 64 * 64;
-  p.fix_stride = (int64_t)tg_max * 4 * 3 * 256;   // tile groups x slices (<= 4) x row tiles (<= 3) x 256 floats, AT folded into tg_max
-  c->fused_sync_words = 1024 + (int64_t)L * 3 * p.fix_cnt_stride;
+  p.fix_stride = (int64_t)tg_max * kFusedMaxSlices * 3 * 256;   // tile groups x slices x row tiles (<= 3) x 256 floats, AT folded into tg_max
+  c->fused_sync_words = 1024;
   A((void**)&p.fix_buf, (size_t)L * 3 * p.fix_stride * 4);
   A((void**)&c->fused_bar, (size_t)(c->fused_sync_words + 64) * 4);
   A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L);
   SSD_TRY(st);
   c->fused_err = c->fused_bar + c->fused_sync_words;
   p.bar = c->fused_bar;
-  p.fix_cnt = c->fused_bar + 1024;
   p.err = c->fused_err;
   SSD_HIP(hipMemset(c->fused_bar, 0, (size_t)(c->fused_sync_words + 64) * 4));
+  SSD_HIP(hipMemset(p.fix_buf, 0xff, (size_t)L * 3 * p.fix_stride * 4));
   p.deep = 1;   // ring depth of the gate/up and LM-head streaming loops
   for (int l = 0; l < L; ++l)
     if (m->fused_layers[l].gu.KTW % 4) p.deep = 0;
