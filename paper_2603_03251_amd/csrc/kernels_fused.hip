@@ -647,6 +647,7 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
     bf16x8 v;              // stored: 8 value elements
     f32x4 a, bb, c0, c1, v0, v1;   // computed: raw projections and rotary table
   };
+  int fresh_slot = 0;    // extend rows: trunk position the fresh key is appended at
   Fresh fr[1];
   const int nf8 = n_fb * 32 * 8;   // at most 512: one item per thread
 #pragma unroll
@@ -673,6 +674,7 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
       } else {
         x.m_o = b * p.R + min(x.f, p.R - 1);
         x.valid = x.f < p.R;
+        fresh_slot = p.rows[x.m_o].kv_slot;
       }
       if (x.valid && !x.stored) {
         const gfloat* kp = gq + (int64_t)x.m_o * p.qkvd + p.qd + hk * 64 + x.q8 * 4;
@@ -742,22 +744,6 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
             vv.u[e] = to_bf16(x.v0[e] * rs);
             vv.u[4 + e] = to_bf16(x.v1[e] * rs);
           }
-          // append for later passes: the row's private suffix slot (branch) or its trunk position (extend)
-          if (is_branch) {
-            const int64_t row = (((int64_t)x.m_o * p.suffix_cap + (p.suffix_len - 1)) * p.Hkv + hk) * 64;
-            *(gu32x2*)(L.suffix_k + row + x.q8 * 4) = k_lo;
-            *(gu32x2*)(L.suffix_k + row + 32 + x.q8 * 4) = k_hi;
-            *(gbf16x8*)(L.suffix_v + row + x.q8 * 8) = vv.v;
-          } else {
-            const int slot = p.rows[x.m_o].kv_slot;
-            const int64_t head = (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64;
-            const int64_t row = head + (int64_t)slot * 64;
-            *(gu32x2*)(L.trunk_k + row + x.q8 * 4) = k_lo;
-            *(gu32x2*)(L.trunk_k + row + 32 + x.q8 * 4) = k_hi;
-            gbf16* vcol = (gbf16*)L.trunk_vt + head + (int64_t)(slot >> 5) * 2048 + (x.q8 * 8) * 32 + (slot & 31);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) vcol[e * 32] = vv.u[e];
-          }
         }
         *(u32x2*)(kf_s + x.f * 72 + x.q8 * 4) = k_lo;
         *(u32x2*)(kf_s + x.f * 72 + 32 + x.q8 * 4) = k_hi;
@@ -775,22 +761,30 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt) st.acc[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // ---- stored trunk keys: RING blocks in flight; every iteration computes and reloads unconditionally (blocks past
-  // the wavefront's last one are clamped duplicates with every key masked), so the load counting stays exact
-  for (int i0 = 0; i0 < n_mine; i0 += RING) {
+  // ---- stored trunk keys: RING blocks in flight.  Steady groups compute and reload unconditionally, the last group
+  // only computes (blocks past the wavefront's last one are clamped duplicates with every key masked), so the load
+  // counting stays exact and nothing is fetched twice.
+  auto trunk_block = [&](const TrunkBlock& tb, int i) {
+    const int kb = kb0 + (wave + kFusedWaves * i) * 32;
+    f32x4 S[2];
+    bool vis[8];
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) S[tile] = score_tile<NPQ>(tb.k[tile][0], tb.k[tile][1], qh, ql);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vis[e] = i < n_mine && kb + g4 * 8 + e < tv;
+    softmax_block<NPP>(st, S, vis, tb.vt);
+  };
+  int i0 = 0;
+  for (; i0 + RING < n_mine; i0 += RING) {
 #pragma unroll
     for (int r = 0; r < RING; ++r) {
-      const int i = i0 + r;
-      const int kb = kb0 + (wave + kFusedWaves * i) * 32;
-      f32x4 S[2];
-      bool vis[8];
-#pragma unroll
-      for (int tile = 0; tile < 2; ++tile) S[tile] = score_tile<NPQ>(ring[r].k[tile][0], ring[r].k[tile][1], qh, ql);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) vis[e] = i < n_mine && kb + g4 * 8 + e < tv;
-      softmax_block<NPP>(st, S, vis, ring[r].vt);
-      load_trunk(ring[r], i + RING);
+      trunk_block(ring[r], i0 + r);
+      load_trunk(ring[r], i0 + r + RING);
     }
+  }
+  if (n_mine > 0) {
+#pragma unroll
+    for (int r = 0; r < RING; ++r) trunk_block(ring[r], i0 + r);
   }
   stamp(p, ph, 6);
   // ---- fresh blocks continue the round-robin after the trunk blocks
@@ -860,6 +854,31 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
         const int64_t pb = ((int64_t)(b * p.Hkv + hk) * p.NS + s) * (p.QT * 16) + qrow;
         if (dq == 0) st_u64(part_ml + pb * 2, pack_f32x2(mmax, lsum));
         st_f32x4(part_o + pb * 64 + dq * 4, o);
+      }
+    }
+  }
+  // ---- append the keys and values computed in this pass for later passes, from their LDS copies: the row's private
+  // suffix slot (branch) or its trunk position (extend).  Last, so that the stores are not in the way of any load.
+  {
+    const Fresh& x = fr[0];
+    if (n_fb > 0 && (int)threadIdx.x < nf8 && x.valid && !x.stored) {
+      const u32x2 k_lo = *(const u32x2*)(kf_s + x.f * 72 + x.q8 * 4), k_hi = *(const u32x2*)(kf_s + x.f * 72 + 32 + x.q8 * 4);
+      Bf8 vv;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vv.u[e] = vf_s[(x.q8 * 8 + e) * 72 + x.f];
+      if (is_branch) {
+        const int64_t row = (((int64_t)x.m_o * p.suffix_cap + (p.suffix_len - 1)) * p.Hkv + hk) * 64;
+        *(gu32x2*)(L.suffix_k + row + x.q8 * 4) = k_lo;
+        *(gu32x2*)(L.suffix_k + row + 32 + x.q8 * 4) = k_hi;
+        *(gbf16x8*)(L.suffix_v + row + x.q8 * 8) = vv.v;
+      } else {
+        const int64_t head = (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64;
+        const int64_t row = head + (int64_t)fresh_slot * 64;
+        *(gu32x2*)(L.trunk_k + row + x.q8 * 4) = k_lo;
+        *(gu32x2*)(L.trunk_k + row + 32 + x.q8 * 4) = k_hi;
+        gbf16* vcol = (gbf16*)L.trunk_vt + head + (int64_t)(fresh_slot >> 5) * 2048 + (x.q8 * 8) * 32 + (fresh_slot & 31);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vcol[e * 32] = vv.u[e];
       }
     }
   }
