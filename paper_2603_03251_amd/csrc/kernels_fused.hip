@@ -552,6 +552,7 @@ __device__ __forceinline__ void softmax_block(OnlineSoftmax& st, const f32x4 S[2
   }
 }
 
+constexpr int kAttnQPlanes = 2, kAttnPPlanes = 2;
 template <int NPQ>
 __device__ __forceinline__ f32x4 score_tile(bf16x8 k0, bf16x8 k1, const Bf8 qh[2], const Bf8 ql[2]) {
   f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -576,8 +577,9 @@ __device__ __forceinline__ f32x4 score_tile(bf16x8 k0, bf16x8 k1, const Bf8 qh[2
 // visibility only masks.  The 8 partial softmaxes meet in LDS; with one split the result goes straight to the
 // o-projection's operand planes, otherwise to the partial buffers of the merge phase.
 template <int MT, int NPQ, int NPP>
-__device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
-                                          const float* r_s, f32x4* lds, bf16_t* att_out, float* part_o, float* part_ml, int ph) {
+__device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
+                                          const float* r_s, f32x4* lds, bf16_t* att_out, float* part_o, float* part_ml, int ph,
+                                          Grid* wait_on) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int li = lane & 15, g4 = lane >> 4;
   const int hk = unit % p.Hkv;
@@ -596,14 +598,6 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
   const bool is_branch = p.is_branch != 0;
   const gfloat* gq = (const gfloat*)qkv;
   const gfloat* gcs = (const gfloat*)p.cos_sin;
-
-  // ---- issue: row descriptor, raw query tile
-  const RowDesc rd = p.rows[m];
-  const gfloat* qp = gq + (int64_t)m * p.qkvd + hq * 64 + g4 * 8;
-  const f32x4 qa0 = *(const gf32x4*)qp, qa1 = *(const gf32x4*)(qp + 4);
-  const f32x4 qb0 = *(const gf32x4*)(qp + 32), qb1 = *(const gf32x4*)(qp + 36);
-  const gfloat* qcs = gcs + ((int64_t)m * 32 + g4 * 8) * 2;
-  const f32x4 qc0 = *(const gf32x4*)qcs, qc1 = *(const gf32x4*)(qcs + 4), qc2 = *(const gf32x4*)(qcs + 8), qc3 = *(const gf32x4*)(qcs + 12);
 
   // ---- issue: the first trunk blocks of this wavefront (block counts from the host's bound)
   const int kb0 = s * p.KPU;
@@ -638,6 +632,21 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
   };
 #pragma unroll
   for (int i = 0; i < RING; ++i) load_trunk(ring[i], i);   // unconditional (a wavefront without blocks re-reads block 0)
+  // The stored keys do not depend on the phase before: the first unit of a workgroup requests its ring ahead of the
+  // grid barrier.
+  if (wait_on) {
+    if (!grid_wait(*wait_on)) return false;
+    stamp(p, ph, 1);
+  }
+  stamp(p, ph, 3);
+
+  // ---- issue: row descriptor, raw query tile
+  const RowDesc rd = p.rows[m];
+  const gfloat* qp = gq + (int64_t)m * p.qkvd + hq * 64 + g4 * 8;
+  const f32x4 qa0 = *(const gf32x4*)qp, qa1 = *(const gf32x4*)(qp + 4);
+  const f32x4 qb0 = *(const gf32x4*)(qp + 32), qb1 = *(const gf32x4*)(qp + 36);
+  const gfloat* qcs = gcs + ((int64_t)m * 32 + g4 * 8) * 2;
+  const f32x4 qc0 = *(const gf32x4*)qcs, qc1 = *(const gf32x4*)(qcs + 4), qc2 = *(const gf32x4*)(qcs + 8), qc3 = *(const gf32x4*)(qcs + 12);
 
   // ---- issue: sources of the fresh key this thread stages (item = key f, rotary quad / 8-dim group q8)
   struct Fresh {
@@ -883,6 +892,7 @@ __device__ __forceinline__ void attn_unit(const FusedParams& p, const FusedLayer
     }
   }
   wg_barrier();
+  return true;
 }
 
 // Merge unit (only when the trunk is split over several units): one wavefront per (row, query head), lane = head
@@ -1031,13 +1041,18 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
     } else if (sub == 1) {
       float* part_o = p.part_o + (int64_t)l * p.part_layer_stride * 64;
       float* part_ml = p.part_ml + (int64_t)l * p.part_layer_stride * 2;
-      if (do_wait && !grid_wait(grid)) return;
-      stamp(p, ph, 1);
       // the qkv phase left this layer's row scales in LDS; a launch that starts here computes them itself
       if (ph == first) compute_row_scales(p, p.ssq + (int64_t)(2 * l) * ssq_stride, r_s);
-      stamp(p, ph, 3);
-      for (int u = p.nwg - 1 - (int)blockIdx.x; u < p.n_attn_units; u += p.nwg)
-        attn_unit<MT, 2, 2>(p, L, qkv, u, r_s, red, att, part_o, part_ml, ph);
+      // a workgroup with a unit waits for the grid inside its first unit, after requesting that unit's stored keys
+      bool waited = !do_wait;
+      for (int u = p.nwg - 1 - (int)blockIdx.x; u < p.n_attn_units; u += p.nwg) {
+        if (!attn_unit<MT, kAttnQPlanes, kAttnPPlanes>(p, L, qkv, u, r_s, red, att, part_o, part_ml, ph, waited ? nullptr : &grid)) return;
+        waited = true;
+      }
+      if (!waited) {
+        if (!grid_wait(grid)) return;
+        stamp(p, ph, 1);
+      }
     } else {
       // merge of the key splits; with a single split the attention units wrote the final output and this phase
       // (and its barrier) does not exist
