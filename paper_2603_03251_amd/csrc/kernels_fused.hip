@@ -476,6 +476,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
       for (int s = 0; s < D - 1; ++s) load_b(ring[s]);
     }
     if (ssq_in) compute_row_scales(p, ssq_in, r_s);
+    stamp(p, ph, 3);
     // The host guarantees KTW % D == 0: a unit ends only at the end of a group of D chunks, and every load inside
     // the steady loop is unconditional (the compiler then counts outstanding loads exactly).
     const int n_outer = n_chunks / D;
@@ -495,10 +496,12 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
       }
     }
     if (n_outer > 0) {
+      stamp(p, ph, 4);
       load_a(ring[D - 1]);
       load_b(ring[D - 1]);
 #pragma unroll
       for (int s = 0; s < D; ++s) mfma_chunk(ring[s]);
+      stamp(p, ph, 5);
       finish_unit(c_unit);
     }
     return true;
