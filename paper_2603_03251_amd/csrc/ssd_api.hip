@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <new>
+#include <utility>
 #include <vector>
 
 #include <stdlib.h>
@@ -338,11 +339,12 @@ int fused_setup(ssd_ctx* c) {
   A((void**)&p.part_ml, (size_t)L * c->part_entries * 2 * 4);
   // K-split scratch: per (layer, qkv / o / down) partial tiles.  A word of 0xffffffff means "not written in this
   // launch": filled once here, and the kernel's reader restores it after taking a tile.
-  int tg_max = 1;
+  int64_t fix_tiles = 1;   // most (feature tile, slice) pairs of a K-split layer, padding tiles of the last unit included
   for (int l = 0; l < L; ++l)
-    for (const FusedGemm* g : {&m->fused_layers[l].qkv, &m->fused_layers[l].o, &m->fused_layers[l].down})
-      tg_max = g->NT > tg_max ? g->NT : tg_max;
-  p.fix_stride = (int64_t)tg_max * kFusedMaxSlices * 3 * 256;   // tile groups x slices x row tiles (<= 3) x 256 floats, AT folded into tg_max
+    for (const auto& ga : {std::make_pair(&m->fused_layers[l].qkv, kAtQkv), std::make_pair(&m->fused_layers[l].o, kAtO),
+                           std::make_pair(&m->fused_layers[l].down, kAtDown)})
+      if (ga.first->KS > 1 && (int64_t)ga.first->n_units * ga.second > fix_tiles) fix_tiles = (int64_t)ga.first->n_units * ga.second;
+  p.fix_stride = fix_tiles * (kFusedMaxRows / 16) * 256;   // x row tiles x 256 floats
   c->fused_sync_words = 1024;
   A((void**)&p.fix_buf, (size_t)L * 3 * p.fix_stride * 4);
   A((void**)&c->fused_bar, (size_t)(c->fused_sync_words + 64) * 4);
