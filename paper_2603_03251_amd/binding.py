@@ -146,8 +146,12 @@ def ssd_model_create(shape, weights: Dict[str, np.ndarray], stream=None) -> int:
     keep = {}
 
     def dev(name):
-        keep[name] = to_device_weight(weights[name], shape.dtype)
-        return keep[name].data_ptr()
+        # one upload per distinct array: a caller may give several layers the same weights (a deep model for timing
+        # whose host copy stays small)
+        a = weights[name]
+        if id(a) not in keep:
+            keep[id(a)] = to_device_weight(a, shape.dtype)
+        return keep[id(a)].data_ptr()
 
     w = ssd_model_weights()
     w.d_embed = dev("embed")
