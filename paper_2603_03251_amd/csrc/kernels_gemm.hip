@@ -40,7 +40,9 @@ __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g));
 
 // grid.x = N/16 feature tiles, grid.y = passes of 64 rows.  Each of the 4 wavefronts reduces a quarter of Kd;
 // partial tiles meet in LDS; wavefront w finishes activation tile w.
-template <int EPI, int MT>
+// U = weight tiles a wavefront keeps in flight per stream (gate/up has two streams): 4 KiB did not cover the memory
+// latency for the single-stream layers of large models, so they take 8 when the reduction dimension allows.
+template <int EPI, int MT, int U>
 __global__ __launch_bounds__(kWaves * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ x, int64_t x_plane,
                                                                  const bf16_t* __restrict__ w,
                                                                  const bf16_t* __restrict__ w2, void* __restrict__ out,
@@ -69,7 +71,6 @@ __global__ __launch_bounds__(kWaves * 64) void gemm_bf16_kernel(const bf16_t* __
     xrow[t] = x + (int64_t)m * Kd + (int64_t)kt0 * 32 + (lane >> 4) * 8;
   }
 
-  constexpr int U = 4;
   for (int kt = 0; kt < kt_per_wave; kt += U) {
     bf16x8 wr[U], wr2[U];
 #pragma unroll
@@ -171,12 +172,19 @@ int launch_bf16(const void* x, int64_t x_plane, const void* w, const void* w2, v
   int rows_in_pass = M < kMaxMT * 16 ? M : kMaxMT * 16;
   int mt = (rows_in_pass + 15) / 16;
   const bf16_t *xb = (const bf16_t*)x, *wb = (const bf16_t*)w, *w2b = (const bf16_t*)w2;
+  const bool deep = EPI != EPI_SWIGLU && (Kd / 32 / kWaves) % 8 == 0;
+#define SSD_GEMM_LAUNCH(MTV)                                                                                             \
+  do {                                                                                                                   \
+    if (deep) gemm_bf16_kernel<EPI, MTV, 8><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd); \
+    else gemm_bf16_kernel<EPI, MTV, 4><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd);      \
+  } while (0)
   switch (mt) {
-    case 1: gemm_bf16_kernel<EPI, 1><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd); break;
-    case 2: gemm_bf16_kernel<EPI, 2><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd); break;
-    case 3: gemm_bf16_kernel<EPI, 3><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd); break;
-    default: gemm_bf16_kernel<EPI, 4><<<grid, kWaves * 64, 0, s>>>(xb, x_plane, wb, w2b, out, ld, out_plane, M, N, Kd); break;
+    case 1: SSD_GEMM_LAUNCH(1); break;
+    case 2: SSD_GEMM_LAUNCH(2); break;
+    case 3: SSD_GEMM_LAUNCH(3); break;
+    default: SSD_GEMM_LAUNCH(4); break;
   }
+#undef SSD_GEMM_LAUNCH
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }

@@ -71,21 +71,52 @@ __device__ __forceinline__ float block_sum(float v, float* smem) {
   return t;
 }
 
-// x / sqrt(mean(x^2) + eps) * gain, one block per row.
+// x / sqrt(mean(x^2) + eps) * gain, one block per row.  The row is read once, four elements per thread and step,
+// with the loads of up to 8 steps issued together (a row of 8192 is then one memory latency, not 32).
 template <typename T>
-__global__ void rmsnorm_kernel(const float* h, const T* gain, void* xn, int64_t xn_plane, float* copy_out, int64_t copy_ld,
-                               int d, float eps) {
+__global__ void rmsnorm_kernel(const float* __restrict__ h, const T* __restrict__ gain, void* __restrict__ xn, int64_t xn_plane,
+                               float* __restrict__ copy_out, int64_t copy_ld, int d, float eps) {
   __shared__ float smem[kBlock / 64];
-  int m = blockIdx.x;
+  const int m = blockIdx.x;
   const float* row = h + (int64_t)m * d;
+  constexpr int kHeld = 8;                      // float4 per thread kept in registers
+  const int step = blockDim.x * 4;
+  float4 held[kHeld];
   float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) { float v = row[c]; ss += v * v; }
+  const bool vec = (d & 3) == 0;
+  if (vec) {
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i) {
+      const int c = threadIdx.x * 4 + i * step;
+      held[i] = c < d ? *(const float4*)(row + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i) ss += held[i].x * held[i].x + held[i].y * held[i].y + held[i].z * held[i].z + held[i].w * held[i].w;
+    for (int c = threadIdx.x + kHeld * step; c < d; c += blockDim.x) { float v = row[c]; ss += v * v; }
+  } else {
+    for (int c = threadIdx.x; c < d; c += blockDim.x) { float v = row[c]; ss += v * v; }
+  }
   ss = block_sum(ss, smem);
-  float scale = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float v = row[c] * scale * Elem<T>::load(gain + c);
+  const float scale = 1.0f / sqrtf(ss / (float)d + eps);
+  auto put = [&](int c, float x) {
+    const float v = x * scale * Elem<T>::load(gain + c);
     Act<T>::store(xn, xn_plane, (int64_t)m * d + c, v);
     if (copy_out) copy_out[(int64_t)m * copy_ld + c] = v;
+  };
+  if (vec) {
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i) {
+      const int c = threadIdx.x * 4 + i * step;
+      if (c < d) {
+        put(c, held[i].x);
+        put(c + 1, held[i].y);
+        put(c + 2, held[i].z);
+        put(c + 3, held[i].w);
+      }
+    }
+    for (int c = threadIdx.x + kHeld * step; c < d; c += blockDim.x) put(c, row[c]);
+  } else {
+    for (int c = threadIdx.x; c < d; c += blockDim.x) put(c, row[c]);
   }
 }
 
