@@ -190,8 +190,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--phase-clocks", action="store_true",
                     help="also print (stderr) the per-phase times inside the fused decode kernel of the last branch step")
-    ap.add_argument("--workload", default=WORKLOAD, choices=[WORKLOAD, "70b_verify_1b_draft"],
-                    help="70b_verify_1b_draft: the target's verification forward beside the draft round (its own JSON line)")
+    ap.add_argument("--workload", default=WORKLOAD,
+                    choices=[WORKLOAD, "1b_p8192_f8_t1", "1b_b16_p2048_f4", "70b_verify_1b_draft"],
+                    help="default: the workload the headline metric is quoted on; the others print the same kind of line for "
+                         "their shape (no CPU baseline, no counter traffic); 70b_verify_1b_draft: the target's verification "
+                         "forward beside the draft round")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy: the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
@@ -218,7 +221,8 @@ def main():
     import ssd_inputs as I
     from paper_2603_03251_amd import binding as B
 
-    wl = I.WORKLOADS[WORKLOAD]
+    headline = args.workload == WORKLOAD
+    wl = I.WORKLOADS[args.workload]
     shape, r = wl.draft, wl.round
     K, F, P, nb, V = r.K, r.F, r.prefix, r.batch, shape.vocab
     dev = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
@@ -292,19 +296,27 @@ def main():
         "us_per_ssd_round": ms_per_step * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{WORKLOAD}: Llama-3.2-1B-shaped bf16 draft, B={nb}, prefix {P}, K={K}, F={F} "
-                               f"({r.rows} branch rows), lookahead {K}, greedy; verify on a second stream; lookup",
+        "config": {"workload": f"{args.workload}: Llama-3.2-1B-shaped bf16 draft, B={nb}, prefix {P}, K={K}, F={F} "
+                               f"({r.rows} branch rows), lookahead {K}, {'greedy' if r.temperature == 0 else 'temperature %g' % r.temperature}"
+                               f"; verify on a second stream; lookup",
                    "branch_rows": r.rows, "tokens_per_round": tokens_per_round},
         "segments_ms": {"glue_extend": float(seg[:, 0].mean()), "fan_out": float(seg[:, 1].mean()),
                         "branch_decode_step": step_ms, "decode_steps_total": float(seg[:, 2:K + 2].sum(axis=1).mean())},
         "decode_only_branch_tokens_per_s": tokens_per_round / (float(seg[:, 2:K + 2].sum(axis=1).mean()) * 1e-3),
-        "roofline": {"kernel": "fused_kernel<2, true>: one batched branch-decode step (24 rows) in one persistent launch",
+        "roofline": {"kernel": (f"fused_kernel: one batched branch-decode step ({r.rows} rows) in one persistent launch" if fused
+                                else f"one batched branch-decode step ({r.rows} rows), one kernel per operator"),
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES if headline and fused else None,
                      "bytes_per_launch": bytes_step, "avg_ms": kernel_ms},
     }
+    # with hundreds of rows the linear layers approach the MFMA ridge: report their share of the dense bf16 peak too
+    d_, f_, L_ = shape.d_model, shape.d_ffn, shape.n_layers
+    qd_, kvd_ = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    gemm_flops = 2.0 * r.rows * (L_ * ((qd_ + 2 * kvd_) * d_ + d_ * qd_ + 3 * d_ * f_) + V * d_)
+    out["mfma"] = {"gemm_flops_per_step": gemm_flops, "achieved_tflops": gemm_flops / (kernel_ms * 1e-3) / 1e12,
+                   "peak_tflops": 2500.0, "frac": gemm_flops / (kernel_ms * 1e-3) / 2.5e15}
 
-    if not args.no_cpu_baseline:
+    if headline and not args.no_cpu_baseline:
         from oracle import ssd_oracle as O
         om = O.Model.from_weights(shape, w)
         trunk = O.KV([k[l, 0].astype(np.float64) for l in range(shape.n_layers)],

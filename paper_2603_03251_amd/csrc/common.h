@@ -136,13 +136,14 @@ struct AttnArgs {
   void* out;             // activation [M][Hq][D]
   int64_t out_plane;
   const RowDesc* rows;
-  float* partial;        // scratch for split-KV partial results
+  float* partial;        // scratch for the partial softmaxes of key splits
+  int64_t partial_floats;
   int M, n_q_heads, n_kv_heads, head_dim, max_trunk, suffix_cap;
   int rows_per_seq;      // rows of one sequence are consecutive
   int max_vis;           // host upper bound of any row's visible trunk length (grid sizing only)
 };
 int launch_attention(int dtype, const AttnArgs& a, hipStream_t s);
-size_t attention_partial_bytes(int M, int n_q_heads, int head_dim, int max_trunk);
+int64_t attention_partial_floats(int M, int n_q_heads, int head_dim, int max_keys);
 
 // ---------------------------------------------------------------- kernels_select.hip
 int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int32_t* ids,

@@ -109,8 +109,7 @@ __global__ __launch_bounds__(256) void attention_rowwise_kernel(const float* __r
 
 constexpr int kMaxSplits = 64;          // key splits of a row
 constexpr int kSplitKeys = 256;         // most keys of a split: one per thread
-constexpr int kSplitBelowBlocks = 512;  // (row, KV head) pairs below which the keys are split
-constexpr int kSplitMaxRows = 64;       // ... and the most rows the partial-softmax scratch is sized for
+constexpr int kSplitMaxRows = 64;       // rows up to which the scratch allows the most splits
 constexpr int kSplitMaxGroup = 8;       // query heads per KV head the split kernel holds
 
 template <typename T, int NE> struct LoadElems;
@@ -264,19 +263,20 @@ __global__ __launch_bounds__(D) void attention_merge_kernel(const float* __restr
   Act<T>::store(out, out_plane, pair * D + d, o / l);
 }
 
-// Splits of at most kSplitKeys keys, and enough of them for about 1024 blocks (none shorter than 64 keys); 1 (the
-// row-wise kernel) when the rows alone fill the chip or the shape is outside what the split kernel holds.
+// Splits of at most kSplitKeys keys, and with few rows enough of them for about 1024 blocks (none shorter than 64
+// keys); 1 (the row-wise kernel) when the shape is outside what the split kernel holds or the scratch is too small.
 int choose_splits(const AttnArgs& a, int* keys_per_split) {
   const int pairs = a.M * a.n_kv_heads;
   const int max_keys = (a.max_vis > 0 ? a.max_vis : 0) + a.suffix_cap;
   *keys_per_split = 0;
-  if (pairs >= kSplitBelowBlocks || a.M > kSplitMaxRows || !a.partial || a.n_q_heads / a.n_kv_heads > kSplitMaxGroup) return 1;
+  if (!a.partial || a.n_q_heads / a.n_kv_heads > kSplitMaxGroup) return 1;
   int n = (max_keys + kSplitKeys - 1) / kSplitKeys;
   int fill = (1024 + pairs - 1) / pairs;
   const int by_len = (max_keys + 63) / 64;
   fill = fill < by_len ? fill : by_len;
   n = n > fill ? n : fill;
-  if (n <= 1 || n > kMaxSplits) return 1;
+  if (n < 1) n = 1;
+  if (n > kMaxSplits || (int64_t)a.M * a.n_q_heads * n * (a.head_dim + 2) > a.partial_floats) return 1;
   *keys_per_split = ((max_keys + n - 1) / n + 63) / 64 * 64;
   return n;
 }
@@ -285,7 +285,7 @@ template <typename T, int D>
 int launch_rowwise_d(const AttnArgs& a, hipStream_t s) {
   int keys_per_split = 0;
   const int n_splits = choose_splits(a, &keys_per_split);
-  if (n_splits == 1) {
+  if (keys_per_split == 0) {
     dim3 grid(a.M, a.n_kv_heads);
     attention_rowwise_kernel<T, D><<<grid, 256, 0, s>>>(a.q, (const T*)a.trunk_k, (const T*)a.trunk_v, (const T*)a.suffix_k,
                                                         (const T*)a.suffix_v, a.out, a.out_plane, a.rows, a.n_q_heads,
@@ -312,10 +312,12 @@ int launch_rowwise(const AttnArgs& a, hipStream_t s) {
 
 }  // namespace
 
-size_t attention_partial_bytes(int M, int n_q_heads, int head_dim, int max_trunk) {
-  (void)max_trunk;
-  const int rows = M < kSplitMaxRows ? M : kSplitMaxRows;
-  return (size_t)rows * n_q_heads * kMaxSplits * (head_dim + 2) * sizeof(float) + 256;
+// Floats of split-softmax scratch for contexts of up to M rows: few rows x many splits, or M rows x the splits that
+// max_keys keys need.
+int64_t attention_partial_floats(int M, int n_q_heads, int head_dim, int max_keys) {
+  const int64_t few = (int64_t)(M < kSplitMaxRows ? M : kSplitMaxRows) * kMaxSplits;
+  const int64_t many = (int64_t)M * ((max_keys + kSplitKeys - 1) / kSplitKeys + 1);
+  return (few > many ? few : many) * n_q_heads * (head_dim + 2);
 }
 
 int launch_attention(int dtype, const AttnArgs& a, hipStream_t s) {

@@ -114,6 +114,7 @@ struct ssd_ctx {
   void* attn_out;
   void* act;
   float* attn_partial;
+  int64_t attn_partial_floats = 0;
   // fused pass (see fused.h): 0 = per-operator kernels, 1 = one launch per phase, 2 = one persistent launch
   int fused_mode = 0;
   int vt_stride = 0;
@@ -275,9 +276,11 @@ int forward_rows(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int
                                c->suffix_v[l], M, d.n_q_heads, d.n_kv_heads, d.head_dim, c->max_trunk, c->K, s));
     AttnArgs a;
     a.q = c->q; a.trunk_k = c->trunk_k[l]; a.trunk_v = c->trunk_v[l]; a.suffix_k = c->suffix_k[l];
-    a.suffix_v = c->suffix_v[l]; a.out = c->attn_out; a.out_plane = R * d.q_dim(); a.rows = c->rows; a.partial = c->attn_partial; a.M = M;
+    a.suffix_v = c->suffix_v[l]; a.out = c->attn_out; a.out_plane = R * d.q_dim(); a.rows = c->rows; a.partial = c->attn_partial; a.partial_floats = c->attn_partial_floats; a.M = M;
     a.n_q_heads = d.n_q_heads; a.n_kv_heads = d.n_kv_heads; a.head_dim = d.head_dim; a.max_trunk = c->max_trunk;
-    a.suffix_cap = c->K; a.rows_per_seq = rows_per_seq; a.max_vis = max_vis;
+    a.suffix_cap = c->K; a.rows_per_seq = rows_per_seq;
+    // here the tokens of an extend are trunk positions too (they are appended before the attention runs)
+    a.max_vis = max_vis + (branch_depth < 0 ? rows_per_seq : 0);
     SSD_TRY(launch_attention(dt, a, s));
     SSD_TRY(launch_gemm(dt, EPI_RESIDUAL_ADD, c->attn_out, R * d.q_dim(), L.wo, nullptr, c->h, d.d_model, 0, M, d.d_model,
                         d.q_dim(), s));
@@ -476,7 +479,8 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   A((void**)&c->q, sizeof(float) * (size_t)R * d.q_dim());
   A(&c->attn_out, sizeof(float) * (size_t)R * d.q_dim());
   A(&c->act, sizeof(float) * (size_t)R * d.d_ffn);
-  A((void**)&c->attn_partial, attention_partial_bytes(R, d.n_q_heads, d.head_dim, c->max_trunk));
+  c->attn_partial_floats = attention_partial_floats(R, d.n_q_heads, d.head_dim, c->max_trunk + c->K);
+  A((void**)&c->attn_partial, (size_t)c->attn_partial_floats * sizeof(float));
   if (st == SSD_OK && c->fused_mode) st = fused_setup(c);
   if (st == SSD_OK) {
     hipError_t e = hipMemset(c->trunk_len, 0, sizeof(int32_t) * c->B);
