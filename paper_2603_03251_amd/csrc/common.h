@@ -149,7 +149,8 @@ int64_t attention_partial_floats(int M, int n_q_heads, int head_dim, int max_key
 int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int32_t* ids,
                  hipStream_t s);
 int launch_sample(const float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int V,
-                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, hipStream_t s);
+                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, void* scratch, hipStream_t s);
+size_t sample_scratch_bytes(int rows);
 int launch_verify(const float* zt, const float* zd, const int32_t* spec, const float* temperature, int B, int K, int V,
                   uint64_t seed, int32_t* accept_len, int32_t* bonus, void* workspace, hipStream_t s);
 size_t verify_workspace_bytes(int B, int K);

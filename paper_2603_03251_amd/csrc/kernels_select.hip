@@ -80,6 +80,7 @@ struct ScoreId {
   double s;
   int id;
 };
+constexpr int kSampleMaxParts = 64;   // blocks that share one row of the sampler
 __device__ __forceinline__ bool better(const ScoreId& a, const ScoreId& b) {
   return a.s > b.s || (a.s == b.s && a.id < b.id);
 }
@@ -111,34 +112,41 @@ __device__ __forceinline__ double block_sum_f64(double v, double* smem) {
 }
 __device__ __forceinline__ double score_of(float z) { return z != z ? -INFINITY : (double)z; }
 
-// Branch sampler: greedy argmax or Gumbel-max sample of softmax(z / T), one block per row.
+// Branch sampler: greedy argmax or Gumbel-max sample of softmax(z / T).  grid = (rows, parts): a block scans one
+// part of its row's vocabulary; with one part it writes the token, otherwise its best (score, id) goes to `scratch`
+// [row][part] and sample_merge_kernel picks the row's winner (the order `better` defines is total, so any grouping
+// gives the same token).
 __global__ __launch_bounds__(kSelBlock) void sample_kernel(const float* __restrict__ logits, int64_t ld,
                                                            const float* __restrict__ temperature, int rows_per_seq,
                                                            int V, uint64_t seed, int row_base, int step,
-                                                           int32_t* __restrict__ out, int64_t out_stride) {
+                                                           int32_t* __restrict__ out, int64_t out_stride,
+                                                           ScoreId* __restrict__ scratch) {
   __shared__ ScoreId smem[kSelWaves];
-  const int row = blockIdx.x;
+  const int row = blockIdx.x, part = blockIdx.y, parts = gridDim.y;
   const float* z = logits + (int64_t)row * ld;
   const double T = (double)temperature[row / rows_per_seq];
   const uint64_t prefix = draw_prefix(seed, STREAM_DRAFT, (uint64_t)(row_base + row), (uint64_t)step);
+  // this block's share of the vocabulary, in groups of 4 tokens
+  const int n4_all = (V + 3) >> 2;
+  const int per = (n4_all + parts - 1) / parts;
+  const int q_begin = part * per, q_end = min(n4_all, q_begin + per);
   ScoreId best = {-INFINITY, 0x7fffffff};
   if (T <= 0.0 && (V & 3) == 0 && (ld & 3) == 0 && ((uintptr_t)logits & 15) == 0) {
     // greedy rows: 16-byte loads, eight of them in flight per thread (one dependent 4-byte load per iteration
-    // would cost a memory latency each: 500 of them for a 128k vocabulary)
+    // would cost a memory latency each)
     typedef __attribute__((ext_vector_type(4))) float f4;
     const f4* z4 = (const f4*)z;
-    const int n4 = V >> 2;
-    for (int t0 = threadIdx.x; t0 < n4; t0 += kSelBlock * 8) {
+    for (int t0 = q_begin + threadIdx.x; t0 < q_end; t0 += kSelBlock * 8) {
       f4 v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         int t = t0 + u * kSelBlock;
-        v[u] = z4[t < n4 ? t : t0];
+        v[u] = z4[t < q_end ? t : t0];
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         int t = t0 + u * kSelBlock;
-        if (t < n4) {
+        if (t < q_end) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             ScoreId c = {score_of(v[u][e]), t * 4 + e};
@@ -148,7 +156,8 @@ __global__ __launch_bounds__(kSelBlock) void sample_kernel(const float* __restri
       }
     }
   } else {
-    for (int t = threadIdx.x; t < V; t += kSelBlock) {
+    const int t_end = min(V, q_end * 4);
+    for (int t = q_begin * 4 + threadIdx.x; t < t_end; t += kSelBlock) {
       ScoreId c;
       c.id = t;
       c.s = score_of(z[t]);
@@ -157,6 +166,26 @@ __global__ __launch_bounds__(kSelBlock) void sample_kernel(const float* __restri
     }
   }
   best = block_argmax(best, smem);
+  if (threadIdx.x == 0) {
+    if (parts == 1) out[(int64_t)row * out_stride] = best.id;
+    else scratch[(int64_t)row * parts + part] = best;
+  }
+}
+
+__global__ __launch_bounds__(64) void sample_merge_kernel(const ScoreId* __restrict__ scratch, int parts,
+                                                          int32_t* __restrict__ out, int64_t out_stride) {
+  const int row = blockIdx.x;
+  ScoreId best = {-INFINITY, 0x7fffffff};
+  for (int i = threadIdx.x; i < parts; i += 64) {
+    const ScoreId c = scratch[(int64_t)row * parts + i];
+    if (better(c, best)) best = c;
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    ScoreId t;
+    t.s = __shfl_xor(best.s, o);
+    t.id = __shfl_xor(best.id, o);
+    if (better(t, best)) best = t;
+  }
   if (threadIdx.x == 0) out[(int64_t)row * out_stride] = best.id;
 }
 
@@ -276,12 +305,27 @@ int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int ro
   return SSD_OK;
 }
 
+size_t sample_scratch_bytes(int rows) { return (size_t)rows * kSampleMaxParts * sizeof(ScoreId); }
+
+// scratch: sample_scratch_bytes(rows) of device memory, or null (then every row is one block)
 int launch_sample(const float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int V,
-                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, hipStream_t s) {
+                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, void* scratch, hipStream_t s) {
   if (rows <= 0) return SSD_OK;
-  sample_kernel<<<rows, kSelBlock, 0, s>>>(logits, ld, temperature, rows_per_seq, V, seed, row_base, step, out,
-                                           out_stride);
+  int parts = 1;
+  if (scratch) {
+    parts = (2048 + rows - 1) / rows;                                   // about 2048 blocks
+    const int by_len = (V + kSelBlock * 4 - 1) / (kSelBlock * 4);       // at least 4 tokens per thread
+    parts = parts < by_len ? parts : by_len;
+    parts = parts < kSampleMaxParts ? parts : kSampleMaxParts;
+    parts = parts < 1 ? 1 : parts;
+  }
+  sample_kernel<<<dim3(rows, parts), kSelBlock, 0, s>>>(logits, ld, temperature, rows_per_seq, V, seed, row_base, step, out,
+                                                        out_stride, (ScoreId*)scratch);
   SSD_HIP(hipGetLastError());
+  if (parts > 1) {
+    sample_merge_kernel<<<rows, 64, 0, s>>>((const ScoreId*)scratch, parts, out, out_stride);
+    SSD_HIP(hipGetLastError());
+  }
   return SSD_OK;
 }
 

@@ -114,6 +114,7 @@ struct ssd_ctx {
   void* attn_out;
   void* act;
   float* attn_partial;
+  void* sample_scratch = nullptr;   // per-row partial winners of the multi-block sampler
   int64_t attn_partial_floats = 0;
   // fused pass (see fused.h): 0 = per-operator kernels, 1 = one launch per phase, 2 = one persistent launch
   int fused_mode = 0;
@@ -481,6 +482,7 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   A(&c->act, sizeof(float) * (size_t)R * d.d_ffn);
   c->attn_partial_floats = attention_partial_floats(R, d.n_q_heads, d.head_dim, c->max_trunk + c->K);
   A((void**)&c->attn_partial, (size_t)c->attn_partial_floats * sizeof(float));
+  A(&c->sample_scratch, sample_scratch_bytes(c->M));
   if (st == SSD_OK && c->fused_mode) st = fused_setup(c);
   if (st == SSD_OK) {
     hipError_t e = hipMemset(c->trunk_len, 0, sizeof(int32_t) * c->B);
@@ -597,7 +599,7 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
     SSD_TRY(forward_rows(c, M, c->step_tokens, (K + 1) * F, c->trunk_ub + K + 1, i, c->logits + (size_t)i * V, (int64_t)K * V,
                          c->hidden + (size_t)i * d.d_model, (int64_t)K * d.d_model, s));
     SSD_TRY(launch_sample(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, (K + 1) * F, M, V, round_seed, 0, i,
-                          c->tokens + i, K, s));
+                          c->tokens + i, K, c->sample_scratch, s));
     SSD_TRY(mark());
   }
   c->have_cache = true;
@@ -720,7 +722,7 @@ int ssd_sample(const float* d_logits, int64_t ld, const float* d_temperature, in
                int32_t row_base, int32_t step, int32_t* d_out, void* stream) {
   SSD_CHECK_ARG(d_logits && d_temperature && d_out, "ssd_sample: null argument");
   SSD_CHECK_ARG(rows >= 0 && V >= 2 && ld >= V, "ssd_sample: rows >= 0, V >= 2, ld >= V required");
-  return launch_sample(d_logits, ld, d_temperature, 1, rows, V, seed, row_base, step, d_out, 1, (hipStream_t)stream);
+  return launch_sample(d_logits, ld, d_temperature, 1, rows, V, seed, row_base, step, d_out, 1, nullptr, (hipStream_t)stream);
 }
 
 int ssd_ctx_views(const ssd_ctx* c, ssd_views* out) {
