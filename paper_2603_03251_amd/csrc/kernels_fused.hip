@@ -81,6 +81,19 @@ __device__ __forceinline__ f32x4 fix_empty() {
   const float e = __uint_as_float(kFixEmpty);
   return (f32x4){e, e, e, e};
 }
+// A plain 16-byte store the compiler does not see as a memory operation.  With a store pending, the compiler's waits
+// for loads degrade to "wait for everything", which would empty the weight pipeline at every unit of the LM head.
+// Hidden, the store only makes a later counted wait err on the safe side: loads complete in order among themselves,
+// so "at most N operations outstanding" still implies that every load older than the N youngest has arrived.
+__device__ __forceinline__ void st_f32x4_uncounted(float* p, f32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(p), "v"(v));
+}
+// The lane index, recomputed where it is called (the compiler can neither hoist nor remember the result).
+__device__ __forceinline__ int fresh_lane_id() {
+  int l;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+  return l;
+}
 __device__ __forceinline__ uint64_t pack_bf16x4(bf16_t a, bf16_t b, bf16_t c, bf16_t d) {
   return (uint64_t)a | ((uint64_t)b << 16) | ((uint64_t)c << 32) | ((uint64_t)d << 48);
 }
@@ -250,6 +263,10 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
 
   // End of a unit: sum the 8 wavefronts' partial tiles in LDS and run the epilogue.
   auto finish_unit = [&](int unit) {
+    // The lane index of the epilogue is read afresh here: addresses derived from the function-wide `lane` would be
+    // kept across the streaming loop, where registers are short, spilled, and their reloads (memory loads like any
+    // other) would make the compiler wait for the whole weight pipeline at every unit.
+    const int lane = fresh_lane_id();
     // the residual-stream tile and the gains this wavefront's epilogue will want: requested now, so that they arrive
     // under the LDS reduction and the K-split fix-up instead of costing a memory latency at the very end
     f32x4 h_pre = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -350,13 +367,15 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
         const int n = tile * 16 + f4;
         if (m < p.M && tile < g.NT) {
           const float rs = r_s[m];
-          *(gf32x4*)(e.out + (int64_t)m * e.ld + n) = v * rs;
+          st_f32x4_uncounted(e.out + (int64_t)m * e.ld + n, v * rs);
         }
       }
     }
     // Loads and stores share one counter and may complete out of order with respect to each other: drain it here,
-    // once per unit, so that the chunk waits in the streaming loop stay exact.
-    __builtin_amdgcn_s_waitcnt(0);
+    // once per unit, so that the chunk waits in the streaming loop stay exact.  The LM head, the one phase with several
+    // units per workgroup, must not drain (the next unit's weights are already in flight): its stores are not counted
+    // (see st_f32x4_uncounted) and complete under the next unit; the drain before the grid barrier covers them.
+    if (EPI != EPI_LOGITS) __builtin_amdgcn_s_waitcnt(0);
     wg_barrier();
   };
 
