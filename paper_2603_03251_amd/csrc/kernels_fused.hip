@@ -88,6 +88,15 @@ __device__ __forceinline__ f32x4 fix_empty() {
 __device__ __forceinline__ void st_f32x4_uncounted(float* p, f32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(p), "v"(v));
 }
+// Thread coordinates read afresh where they are called: everything derived from them (row and tile indices, LDS and
+// global addresses) is then local to the phase that computes it.  Derived from the kernel-wide threadIdx they would be
+// hoisted out of the phase loop, stay live through every phase and be spilled where registers are short.
+struct ThreadIds { int tid, lane, wave; };
+__device__ __forceinline__ ThreadIds fresh_thread_ids() {
+  int t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return ThreadIds{t, t & 63, __builtin_amdgcn_readfirstlane(t >> 6)};
+}
 // The lane index, recomputed where it is called (the compiler can neither hoist nor remember the result).
 __device__ __forceinline__ int fresh_lane_id() {
   int l;
@@ -602,7 +611,8 @@ template <int MT, int NPQ, int NPP>
 __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
                                           const float* r_s, f32x4* lds, bf16_t* att_out, float* part_o, float* part_ml, int ph,
                                           Grid* wait_on) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const ThreadIds ids = fresh_thread_ids();
+  const int lane = ids.lane, wave = ids.wave;
   const int li = lane & 15, g4 = lane >> 4;
   const int hk = unit % p.Hkv;
   int rem = unit / p.Hkv;
