@@ -1,0 +1,147 @@
+"""Alg. 1 run for many rounds through the C-ABI on the tiny fp32 pair: every round verifies the pending speculation
+with the target, pre-speculates with the draft, looks the realised outcome up, commits, and on a miss falls back to
+just-in-time drafting with the same draft (Sec. 4.1: backup speculator = primary).  Only the loop is Python; every
+step runs in the library's kernels.
+
+What is fixed independently of any implementation (Sec. 2.1, lossless verification): with greedy decoding the
+generated text equals the target's own greedy autoregressive text, whatever the draft proposes, and a draft that
+equals the target has every speculation accepted in full and (F >= 1) every outcome in the cache."""
+import numpy as np
+import pytest
+import torch
+
+import ssd_inputs as I
+from oracle import ssd_oracle as O
+from tests.gpu_util import dev_f32, dev_i32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_03251_amd import binding
+    return binding
+
+
+class Side:
+    """One model with its context: trunk KV of the verified text, extend / commit."""
+
+    def __init__(self, B, shape, weights, K, F, max_trunk):
+        self.B, self.shape, self.K = B, shape, K
+        self.model = B.ssd_model_create(shape, weights)
+        self.ctx = B.ssd_ctx_create(self.model, 1, K, F, max_trunk)
+
+    def close(self):
+        self.B.ssd_ctx_destroy(self.ctx)
+        self.B.ssd_model_destroy(self.model)
+
+    def extend(self, tokens, offset=0):
+        t = dev_i32(np.asarray(tokens, np.int32)[None, :])
+        z = torch.empty((1, len(tokens), self.shape.vocab), dtype=torch.float32, device="cuda")
+        self.B.ssd_ctx_extend(self.ctx, t, offset, z)
+        return z
+
+    def commit(self, k_dev):
+        self.B.ssd_ctx_commit(self.ctx, k_dev)
+        self.B.ssd_ctx_refresh_bounds(self.ctx)
+
+
+def jit_speculate(B, draft, last, K, temps):
+    """Ordinary drafting: K tokens after `last`, one forward each, greedy."""
+    toks, tok = [], int(last)
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for i in range(K):
+        z = draft.extend([tok], offset=i)
+        B.ssd_sample(z[0], temps, 0, 0, i, out)
+        tok = int(out[0])
+        toks.append(tok)
+    return toks
+
+
+def gpu_ssd_generate(B, target, draft, prompt, n_new, K, F):
+    V = target.shape.vocab
+    temps = dev_f32(np.zeros(1, np.float32))
+    X = [int(t) for t in prompt]
+    n0 = len(X)
+    for side in (target, draft):
+        B.ssd_ctx_prefill(side.ctx, dev_i32(np.asarray(X[:-1], np.int32)[None, :]), [n0 - 1])
+    spec = jit_speculate(B, draft, X[-1], K, temps)
+    acc = torch.zeros(1, dtype=torch.int32, device="cuda")
+    bonus = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hit = torch.zeros(1, dtype=torch.uint8, device="cuda")
+    branch = torch.zeros(1, dtype=torch.int32, device="cuda")
+    nxt = torch.zeros((1, K), dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.ssd_verify_workspace_bytes(1, K), dtype=torch.uint8, device="cuda")
+    s_draft, s_target = torch.cuda.Stream(), torch.cuda.Stream()
+    rounds = hits = accepted = 0
+    accept_lens = []
+    while len(X) - n0 < n_new:
+        rounds += 1
+        pending = dev_i32(np.asarray([X[-1]] + spec, np.int32)[None, :])
+        torch.cuda.synchronize()
+        # the target verifies on one stream while the draft pre-speculates on the other
+        zt = torch.empty((1, K + 1, V), dtype=torch.float32, device="cuda")
+        B.ssd_ctx_extend(target.ctx, pending, 0, zt, stream=s_target)
+        B.ssd_verify(zt, None, pending[:, 1:].contiguous(), temps, rounds, acc, bonus, ws, stream=s_target)
+        B.ssd_prespeculate(draft.ctx, pending, temps, rounds, stream=s_draft)
+        torch.cuda.synchronize()
+        B.ssd_cache_lookup(draft.ctx, acc, bonus, hit, branch, nxt)
+        torch.cuda.synchronize()
+        k, t = int(acc[0]), int(bonus[0])
+        X += spec[:k] + [t]
+        accepted += k
+        accept_lens.append(k)
+        target.commit(acc)
+        draft.commit(acc)
+        if int(hit[0]):
+            hits += 1
+            spec = [int(x) for x in nxt[0].cpu().numpy()]
+        else:
+            spec = jit_speculate(B, draft, t, K, temps)
+    return X[n0:n0 + n_new], dict(rounds=rounds, hits=hits, accepted=accepted, accept_lens=accept_lens)
+
+
+def test_greedy_ssd_text_equals_the_targets_autoregressive_text(B):
+    wl = I.WORKLOADS["tiny_f32"]
+    shape, K, F = wl.draft, wl.round.K, wl.round.F
+    n_new, P = 40, 24
+    wt = I.make_weights(shape, 11)
+    wd = I.make_weights(shape, 12, perturb_of=wt, perturb_std=0.002)     # a draft close to, not equal to, its target
+    prompt = I.make_prompt(shape, 1, P, 21)[0]
+    ot, od = O.Model.from_weights(shape, wt), O.Model.from_weights(shape, wd)
+    want = O.ar_generate(ot, prompt, n_new)
+    want_ssd, st = O.ssd_generate(ot, od, prompt, n_new, K, F)
+    assert want_ssd == want                                              # the oracle's own invariant
+    target = Side(B, shape, wt, K, 1, P + n_new + 4 * K + 8)
+    draft = Side(B, shape, wd, K, F, P + n_new + 4 * K + 8)
+    try:
+        got, gs = gpu_ssd_generate(B, target, draft, prompt, n_new, K, F)
+        print(f"[gpu] rounds {gs['rounds']} hits {gs['hits']} accept lengths {gs['accept_lens']}", flush=True)
+        print(f"[oracle] rounds {st.rounds} hits {st.hits} accept lengths {st.accept_lens}", flush=True)
+        assert got == want
+        # the same decisions round by round (fp32 logits against float64: no near-tie in this seeded run)
+        assert gs["accept_lens"] == st.accept_lens and gs["hits"] == st.hits
+        assert len(set(gs["accept_lens"])) >= 4 and 0 < gs["hits"] < gs["rounds"]      # accept lengths 0..K, hits and misses
+    finally:
+        target.close()
+        draft.close()
+
+
+def test_identical_draft_has_everything_accepted_and_every_outcome_cached(B):
+    wl = I.WORKLOADS["tiny_f32"]
+    shape, K, F = wl.draft, wl.round.K, wl.round.F
+    n_new, P = 30, 17
+    w = I.make_weights(shape, 31)
+    prompt = I.make_prompt(shape, 1, P, 22)[0]
+    want = O.ar_generate(O.Model.from_weights(shape, w), prompt, n_new)
+    target = Side(B, shape, w, K, 1, P + n_new + 4 * K + 8)
+    draft = Side(B, shape, w, K, F, P + n_new + 4 * K + 8)
+    try:
+        got, gs = gpu_ssd_generate(B, target, draft, prompt, n_new, K, F)
+        assert got == want
+        assert all(k == K for k in gs["accept_lens"])
+        assert gs["hits"] == gs["rounds"]                                   # the bonus token is the draft's own top choice
+        assert gs["rounds"] == -(-n_new // (K + 1))
+    finally:
+        target.close()
+        draft.close()
