@@ -368,10 +368,15 @@ class SpecCache:
 
 
 def decode_branch(m: Model, trunk_glue: KV, P: int, k: int, first: int, steps: int, T: float,
-                  seed: int, row: int, forced: Optional[Sequence[int]] = None):
+                  seed: int, row: int, forced: Optional[Sequence[int]] = None,
+                  sigma: Optional[Tuple[int, float]] = None):
     """One branch on its own: feed `first` at position P+1+k on top of trunk[0 .. P+k],
     then its own continuation.  With `forced` (teacher forcing) step i > 0 feeds
-    forced[i-1] instead of its own sample.  Returns (tokens, logits, hidden, margins)."""
+    forced[i-1] instead of its own sample.  Returns (tokens, logits, hidden, margins).
+
+    `sigma` = (F, C) drafts with the Saguaro sampling scheme sigma_{F,C} (Sec. 4.3): at T > 0
+    every token is drawn from the model's logits with the top-F entries downweighted by C, and
+    those are the logits returned (the distribution a verifier has to be given)."""
     past = trunk_glue.slice(P + k + 1)
     tok = int(first)
     toks, logs, hids, margs = [], [], [], []
@@ -380,9 +385,10 @@ def decode_branch(m: Model, trunk_glue: KV, P: int, k: int, first: int, steps: i
         logits, hid, kv = forward(m, [tok], [P + 1 + k + i], past, np.ones((1, S + 1), dtype=bool))
         past = past.concat(kv)
         noise = gumbel(seed, STREAM_DRAFT, row, i, m.vocab) if T > 0 else None
-        nxt, margin = sample_token(logits[0], T, noise)
+        z = logits[0] if sigma is None or T == 0.0 else sigma_FC_logits(logits[0], sigma[0], sigma[1], T)
+        nxt, margin = sample_token(z, T, noise)
         toks.append(nxt)
-        logs.append(logits[0])
+        logs.append(z)
         hids.append(hid[0])
         margs.append(margin)
         tok = nxt if forced is None else int(forced[i])
@@ -392,14 +398,16 @@ def decode_branch(m: Model, trunk_glue: KV, P: int, k: int, first: int, steps: i
 def prespeculate(m: Model, trunk: KV, pending: Sequence[int], F: int, T: float, seed: int,
                  row_base: int = 0,
                  only_rows: Optional[Sequence[int]] = None,
-                 forced_tokens: Optional[np.ndarray] = None) -> SpecCache:
+                 forced_tokens: Optional[np.ndarray] = None,
+                 C: float = 1.0) -> SpecCache:
     """One pre-speculation round for one sequence: glue extend, fan-out, then every branch
     (k, j) decoded for K tokens, one branch at a time, each with KV of its own.
 
     `row_base` is the global row index of branch (0,0) (rows of a batch are numbered
     b (K+1) F + k F + j; the index keys the draft Gumbel stream).  `only_rows` restricts
     the decode to a sample of branches (the others are left zero).  `forced_tokens`
-    [K+1][F][K] teacher-forces every branch's inputs."""
+    [K+1][F][K] teacher-forces every branch's inputs.  C < 1 decodes the branches with the
+    sampling scheme sigma_{F,C} (Sec. 4.3); the fan-out itself always ranks the model's own logits."""
     K = len(pending) - 1
     P = trunk.length
     glue_logits, _, trunk_glue = glue_extend(m, trunk, pending)
@@ -414,7 +422,8 @@ def prespeculate(m: Model, trunk: KV, pending: Sequence[int], F: int, T: float, 
             if only_rows is not None and r not in only_rows:
                 continue
             forced = None if forced_tokens is None else forced_tokens[k, j]
-            t, l, h, g = decode_branch(m, trunk_glue, P, k, keys[k, j], K, T, seed, row_base + r, forced)
+            t, l, h, g = decode_branch(m, trunk_glue, P, k, keys[k, j], K, T, seed, row_base + r, forced,
+                                       sigma=(F, C) if C < 1.0 else None)
             tokens[k, j], logits[k, j], hidden[k, j], margins[k, j] = t, l, h, g
     return SpecCache(keys, tokens, logits, hidden, margins, glue_logits, trunk_glue)
 

@@ -273,3 +273,43 @@ def test_draft_equal_to_target_accepts_all_and_always_hits():
     assert got == O.ar_generate(target, prompt, 40)
     assert all(k == 4 for k in stats.accept_lens)
     assert stats.hits == stats.rounds                            # outcome (K, top-1) is always cached
+
+
+def test_saguaro_sampling_inside_the_round():
+    """Sec. 4.3: branches decoded with sigma_{F,C}.  Pinned by consequences of the definition rather than by the
+    formula: C = 1 changes nothing; under teacher forcing the returned logits differ from the model's own by exactly
+    T log C on the model's top-F tokens and by nothing elsewhere; with C = 0 a top-F token is never drawn; and the
+    fan-out keys (ranked on the model's own logits) do not depend on C."""
+    shape, m = _tiny(7)
+    wl = I.WORKLOADS["tiny_f32"].round
+    K, F, T = wl.K, wl.F, 1.0
+    prompt = I.make_prompt(shape, 1, 30, 4)[0]
+    _, trunk = O.prefill(m, prompt[:-1])
+    spec, _ = O.speculate(m, trunk, prompt[-1], K, T, 5)
+    pending = [int(prompt[-1])] + spec
+    base = O.prespeculate(m, trunk, pending, F, T, seed=9)
+    same = O.prespeculate(m, trunk, pending, F, T, seed=9, C=1.0)
+    assert np.array_equal(base.tokens, same.tokens) and np.array_equal(base.logits, same.logits)
+    Cw = 0.25
+    forced = O.prespeculate(m, trunk, pending, F, T, seed=9, C=Cw, forced_tokens=base.tokens)
+    raw = O.prespeculate(m, trunk, pending, F, T, seed=9, forced_tokens=base.tokens)
+    assert np.array_equal(forced.keys, base.keys)
+    diff = forced.logits - raw.logits
+    for k in range(K + 1):
+        for j in range(F):
+            for i in range(K):
+                top = set(int(t) for t in O.top_f_ids(raw.logits[k, j, i], F))
+                moved = set(int(t) for t in np.nonzero(diff[k, j, i])[0])
+                assert moved == top
+                np.testing.assert_allclose(diff[k, j, i][sorted(top)], T * math.log(Cw), rtol=0, atol=1e-12)
+    # greedy rows are untouched by the scheme (its shift is T log C)
+    g0 = O.prespeculate(m, trunk, pending, F, 0.0, seed=9)
+    g1 = O.prespeculate(m, trunk, pending, F, 0.0, seed=9, C=Cw)
+    assert np.array_equal(g0.tokens, g1.tokens) and np.array_equal(g0.logits, g1.logits)
+    # C = 0: no drafted token is one of the F tokens the model itself ranks first at that step
+    zero = O.prespeculate(m, trunk, pending, F, T, seed=9, C=0.0)
+    raw0 = O.prespeculate(m, trunk, pending, F, T, seed=9, forced_tokens=zero.tokens)
+    for k in range(K + 1):
+        for j in range(F):
+            for i in range(K):
+                assert int(zero.tokens[k, j, i]) not in set(int(t) for t in O.top_f_ids(raw0.logits[k, j, i], F))
