@@ -147,6 +147,13 @@ int ssd_prespeculate(ssd_ctx* ctx, const int32_t* d_pending, const float* d_temp
  * step 0, d_tokens [B][K+1][F][K] entry i-1 feeds step i.  Either may be NULL (not forced). */
 int ssd_ctx_set_forced(ssd_ctx* ctx, const int32_t* d_keys, const int32_t* d_tokens);
 
+/* Saguaro sampling scheme sigma_{F,C} (Sec. 4.3): with C < 1 every later ssd_prespeculate draws the branch tokens of
+ * sampled sequences (temperature > 0) from the step's logits with its own top-F entries lowered by T log(1/C), and the
+ * cache holds those lowered logits (the distribution a verifier must be given).  The fan-out keys always rank the
+ * model's own logits; greedy sequences are unaffected.  C in [0, 1]; 1 (the default) switches the scheme off.
+ * Host-only call, takes effect from the next round. */
+int ssd_ctx_set_saguaro(ssd_ctx* ctx, float C);
+
 /* Look the realised verification outcome up (Alg. 1; payload fields of App. B).
  *   in : d_accept_len int32 [B] (k in 0..K), d_bonus int32 [B] (t*)
  *   out: d_hit uint8 [B] (1 = cache hit), d_branch int32 [B] (rank j of the hit, -1 on a miss),

@@ -61,6 +61,7 @@ EXPORTS = {
     "ssd_ctx_load_trunk": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "ssd_prespeculate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "ssd_ctx_set_forced": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ssd_ctx_set_saguaro": (C.c_int, [C.c_void_p, C.c_float]),
     "ssd_cache_lookup": (C.c_int, [C.c_void_p] * 8),
     "ssd_ctx_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ssd_verify": (C.c_int, [C.c_void_p] * 4 + [C.c_int32] * 3 + [C.c_uint64] + [C.c_void_p] * 4),
@@ -199,6 +200,10 @@ def ssd_prespeculate(ctx: int, pending: torch.Tensor, temperature: torch.Tensor,
 
 def ssd_ctx_set_forced(ctx: int, keys: Optional[torch.Tensor], tokens: Optional[torch.Tensor]) -> None:
     _check(lib.ssd_ctx_set_forced(ctx, _ptr(keys), _ptr(tokens)))
+
+
+def ssd_ctx_set_saguaro(ctx: int, C_: float) -> None:
+    _check(lib.ssd_ctx_set_saguaro(ctx, float(C_)))
 
 
 def ssd_cache_lookup(ctx: int, accept_len, bonus, hit, branch, spec_tokens, logits_ptr=None, stream=None) -> None:

@@ -305,6 +305,25 @@ int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int ro
   return SSD_OK;
 }
 
+// Saguaro sampling scheme sigma_{F,C} (Sec. 4.3) on rows of logits, in place: the F tokens in ids[row] (the row's own
+// top-F) get T log C added, which multiplies their weight exp(z/T) by C.  Greedy rows (T == 0) are left alone.
+__global__ void sigma_shift_kernel(float* __restrict__ logits, int64_t ld, const float* __restrict__ temperature,
+                                   int rows_per_seq, int rows, int F, const int32_t* __restrict__ ids, float log_c) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * F) return;
+  const int row = i / F;
+  const float T = temperature[row / rows_per_seq];
+  if (T > 0.f) logits[(int64_t)row * ld + ids[i]] += T * log_c;
+}
+
+int launch_sigma_shift(float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int F,
+                       const int32_t* ids, float log_c, hipStream_t s) {
+  if (rows <= 0) return SSD_OK;
+  sigma_shift_kernel<<<(rows * F + 255) / 256, 256, 0, s>>>(logits, ld, temperature, rows_per_seq, rows, F, ids, log_c);
+  SSD_HIP(hipGetLastError());
+  return SSD_OK;
+}
+
 size_t sample_scratch_bytes(int rows) { return (size_t)rows * kSampleMaxParts * sizeof(ScoreId); }
 
 // scratch: sample_scratch_bytes(rows) of device memory, or null (then every row is one block)

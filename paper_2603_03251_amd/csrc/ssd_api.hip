@@ -1,5 +1,6 @@
 // C ABI and round driver: owns device buffers, validates arguments, enqueues the kernels of one
 // pre-speculation round (glue extend -> fan-out -> K branch-decode steps writing the speculation cache in place).
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -115,6 +116,8 @@ struct ssd_ctx {
   void* act;
   float* attn_partial;
   void* sample_scratch = nullptr;   // per-row partial winners of the multi-block sampler
+  float saguaro_c = 1.0f;           // downweighting constant of the sampling scheme sigma_{F,C}; 1 = off
+  int32_t* sigma_ids = nullptr;     // [M][F] top-F of the current step's logits (saguaro_c < 1 only)
   int64_t attn_partial_floats = 0;
   // fused pass (see fused.h): 0 = per-operator kernels, 1 = one launch per phase, 2 = one persistent launch
   int fused_mode = 0;
@@ -483,6 +486,7 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   c->attn_partial_floats = attention_partial_floats(R, d.n_q_heads, d.head_dim, c->max_trunk + c->K);
   A((void**)&c->attn_partial, (size_t)c->attn_partial_floats * sizeof(float));
   A(&c->sample_scratch, sample_scratch_bytes(c->M));
+  A((void**)&c->sigma_ids, sizeof(int32_t) * (size_t)c->M * c->F);
   if (st == SSD_OK && c->fused_mode) st = fused_setup(c);
   if (st == SSD_OK) {
     hipError_t e = hipMemset(c->trunk_len, 0, sizeof(int32_t) * c->B);
@@ -598,6 +602,13 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
     SSD_TRY(launch_setup_branch_rows(c->rows, c->cos_sin, c->trunk_len, B, K, F, i, d.head_dim / 2, d.rope_theta, s));
     SSD_TRY(forward_rows(c, M, c->step_tokens, (K + 1) * F, c->trunk_ub + K + 1, i, c->logits + (size_t)i * V, (int64_t)K * V,
                          c->hidden + (size_t)i * d.d_model, (int64_t)K * d.d_model, s));
+    if (c->saguaro_c < 1.0f) {
+      // sigma_{F,C}: lower the step's own top-F logits before the draw; the cache keeps the lowered logits, the
+      // distribution the tokens are drawn from
+      SSD_TRY(launch_top_f(c->logits + (size_t)i * V, (int64_t)K * V, nullptr, M, V, F, c->sigma_ids, s));
+      SSD_TRY(launch_sigma_shift(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, (K + 1) * F, M, F, c->sigma_ids,
+                                 c->saguaro_c > 0.f ? logf(c->saguaro_c) : -INFINITY, s));
+    }
     SSD_TRY(launch_sample(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, (K + 1) * F, M, V, round_seed, 0, i,
                           c->tokens + i, K, c->sample_scratch, s));
     SSD_TRY(mark());
@@ -619,6 +630,13 @@ int ssd_ctx_commit(ssd_ctx* c, const int32_t* d_accept_len, void* stream) {
   if (c->trunk_ub < 1) { set_error("ssd_ctx_commit: the trunk is empty"); return SSD_ESTATE; }
   SSD_TRY(launch_commit(c->trunk_len, d_accept_len, c->B, c->K, (hipStream_t)stream));
   c->trunk_ub += c->K + 1;
+  return SSD_OK;
+}
+
+int ssd_ctx_set_saguaro(ssd_ctx* c, float C) {
+  SSD_CHECK_ARG(c, "ssd_ctx_set_saguaro: null context");
+  SSD_CHECK_ARG(C >= 0.f && C <= 1.f, "the downweighting constant must be in [0, 1]");
+  c->saguaro_c = C;
   return SSD_OK;
 }
 
