@@ -537,6 +537,23 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
 }
 
 // ---------------------------------------------------------------------------------------------- attention
+// Reductions over the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48 hold values of one query row) with
+// the row-swap instructions of gfx950: a swap of a register with itself leaves "mine" in one result and "my
+// partner's" in the other, a few cycles instead of a trip through the LDS crossbar.
+__device__ __forceinline__ float max_over_rows(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned v = __float_as_uint(fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1])));
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float sum_over_rows(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned v = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
 __device__ __forceinline__ int trunk_visible(const RowDesc& r, int m, int R) {
   // stored trunk keys the row sees; the tokens of this very pass are handled as fresh keys
   return r.is_branch ? r.vis : r.vis - 1 - (m % R);
@@ -546,6 +563,39 @@ struct OnlineSoftmax {
   float m_run, l_run;   // running maximum (base-2 exponent) and this lane's share of the running sum
   f32x4 acc[4];         // O^T: dims dt*16 + (lane>>4)*4 + r of query row lane & 15
 };
+
+// Online-softmax update with the block's masked scores sv (this lane's 8 keys) and their maximum mx.  The running
+// accumulators are rescaled only when some row's maximum moved (a wavefront-uniform test): after the first blocks it
+// rarely does.
+template <int NPP>
+__device__ __forceinline__ void softmax_update(OnlineSoftmax& st, const float sv[8], float mx, const bf16x8 vt[4]) {
+  mx = max_over_rows(mx);
+  const float m_new = fmaxf(st.m_run, mx);
+  const float m_use = m_new == -INFINITY ? 0.f : m_new;
+  if (__any(m_new != st.m_run)) {
+    const float corr = exp2_fast(st.m_run - m_use);
+    st.l_run *= corr;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) st.acc[dt] = st.acc[dt] * corr;
+    st.m_run = m_new;
+  }
+  Bf8 ph, pl;
+  float psum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float pe = exp2_fast(sv[i] - m_use);
+    psum += pe;
+    ph.u[i] = to_bf16(pe);
+    pl.u[i] = to_bf16(pe - bf16_to_f32(ph.u[i]));
+  }
+  st.l_run += psum;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) {
+    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[dt], ph.v, st.acc[dt], 0, 0, 0);
+    if (NPP == 2) st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[dt], pl.v, st.acc[dt], 0, 0, 0);
+  }
+}
+
 
 // One 32-key block: scores S[tile][r] of this lane's query row against keys (lane>>4)*8 + tile*4 + r of the block,
 // `vis` = visibility of those 8 keys, vt[dt] = V^T operands of the block.
@@ -559,28 +609,7 @@ __device__ __forceinline__ void softmax_block(OnlineSoftmax& st, const f32x4 S[2
     sv[i] = vis[i] ? x : -INFINITY;
     mx = fmaxf(mx, sv[i]);
   }
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(st.m_run, mx);
-  const float m_use = m_new == -INFINITY ? 0.f : m_new;
-  const float corr = exp2_fast(st.m_run - m_use);
-  Bf8 ph, pl;
-  float psum = 0.f;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    float pe = exp2_fast(sv[i] - m_use);
-    psum += pe;
-    ph.u[i] = to_bf16(pe);
-    pl.u[i] = to_bf16(pe - bf16_to_f32(ph.u[i]));
-  }
-  st.l_run = st.l_run * corr + psum;
-  st.m_run = m_new;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt) {
-    st.acc[dt] = st.acc[dt] * corr;
-    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[dt], ph.v, st.acc[dt], 0, 0, 0);
-    if (NPP == 2) st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[dt], pl.v, st.acc[dt], 0, 0, 0);
-  }
+  softmax_update<NPP>(st, sv, mx, vt);
 }
 
 constexpr int kAttnQPlanes = 2, kAttnPPlanes = 2;
@@ -848,8 +877,7 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
     }
     softmax_block<NPP>(st, S, vis, vt);
   }
-  st.l_run += __shfl_xor(st.l_run, 16);
-  st.l_run += __shfl_xor(st.l_run, 32);
+  st.l_run = sum_over_rows(st.l_run);
   stamp(p, ph, 7);
 
   // ---- the 8 wavefronts' partial softmaxes meet in LDS: acc [wave][dt][lane], (m, l) [wave][16]
