@@ -223,13 +223,13 @@ int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
   return SSD_OK;
 }
 
-// The same pass through the fused kernel: attention work split for this pass's shape, then one launch.
+// The same pass through the fused kernel: attention work split for this pass's shape, then one launch per group of
+// whole sequences that fits kFusedMaxRows rows (one launch for the few-row workloads the kernel is built for; a batch
+// with more rows streams the weights once per group).
 int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int max_vis, int branch_depth, float* logits,
                   int64_t logits_ld, float* hidden, int64_t hidden_ld, hipStream_t s) {
   FusedParams p = c->fp;
-  p.M = M;
   p.R = rows_per_seq;
-  p.tokens = tokens;
   p.is_branch = branch_depth >= 0;
   p.suffix_len = branch_depth >= 0 ? branch_depth + 1 : 0;
   p.tv_ub = max_vis > 0 ? max_vis : 0;
@@ -241,21 +241,37 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
   int ns = (p_ub + 2047) / 2048;
   p.KPU = ((p_ub + ns - 1) / ns + 31) / 32 * 32;
   p.NS = (p_ub + p.KPU - 1) / p.KPU;
-  p.n_attn_units = p.B * p.Hkv * p.QT * p.NS;
-  p.n_pair_units = (M * p.Hq + kFusedWaves - 1) / kFusedWaves;
-  if (p.NS > 1 && (int64_t)p.B * p.Hkv * p.NS * p.QT * 16 > c->part_entries) {
-    set_error("fused pass: attention partial buffer too small (%d splits, %d query tiles)", p.NS, p.QT);
+  const int n_seq = M / rows_per_seq;
+  const int per_pass = kFusedMaxRows / rows_per_seq;
+  if (per_pass < 1 || n_seq * rows_per_seq != M) {
+    set_error("fused pass: %d rows of %d per sequence do not fit passes of %d rows", M, rows_per_seq, kFusedMaxRows);
     return SSD_ESTATE;
   }
-  p.logits = logits;
-  p.logits_ld = logits_ld;
-  p.hidden = hidden;
-  p.hidden_ld = hidden_ld;
   const int last = (logits || hidden) ? fused_last_phase(p.L) : fused_last_phase(p.L) - 1;
-  SSD_TRY(launch_fill_i32((int32_t*)c->fused_bar, 0, c->fused_sync_words, s));
   const bool timed = c->timing && branch_depth >= 0 && 2 * branch_depth + 1 < (int)c->kernel_events.size();
   if (timed) SSD_HIP(hipEventRecord(c->kernel_events[2 * branch_depth], s));
-  SSD_TRY(launch_fused(p, 0, last, c->fused_mode == 2, s));
+  for (int s0 = 0; s0 < n_seq; s0 += per_pass) {
+    const int nb = n_seq - s0 < per_pass ? n_seq - s0 : per_pass;
+    const int64_t row0 = (int64_t)s0 * rows_per_seq;
+    p.B = nb;
+    p.M = nb * rows_per_seq;
+    p.layers = c->fused_layers_dev + (size_t)s0 * p.L;
+    p.rows = c->rows + row0;
+    p.cos_sin = c->cos_sin + row0 * (c->model->dims.head_dim / 2) * 2;
+    p.tokens = tokens + row0;
+    p.logits = logits ? logits + row0 * logits_ld : nullptr;
+    p.logits_ld = logits_ld;
+    p.hidden = hidden ? hidden + row0 * hidden_ld : nullptr;
+    p.hidden_ld = hidden_ld;
+    p.n_attn_units = p.B * p.Hkv * p.QT * p.NS;
+    p.n_pair_units = (p.M * p.Hq + kFusedWaves - 1) / kFusedWaves;
+    if (p.NS > 1 && (int64_t)p.B * p.Hkv * p.NS * p.QT * 16 > c->part_entries) {
+      set_error("fused pass: attention partial buffer too small (%d splits, %d query tiles)", p.NS, p.QT);
+      return SSD_ESTATE;
+    }
+    SSD_TRY(launch_fill_i32((int32_t*)c->fused_bar, 0, c->fused_sync_words, s));
+    SSD_TRY(launch_fused(p, 0, last, c->fused_mode == 2, s));
+  }
   if (timed) SSD_HIP(hipEventRecord(c->kernel_events[2 * branch_depth + 1], s));
   return SSD_OK;
 }
@@ -355,7 +371,7 @@ int fused_setup(ssd_ctx* c) {
   c->fused_sync_words = 1024;
   A((void**)&p.fix_buf, (size_t)L * 3 * p.fix_stride * 4);
   A((void**)&c->fused_bar, (size_t)(c->fused_sync_words + 64) * 4);
-  A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L);
+  A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L * c->B);
   SSD_TRY(st);
   c->fused_err = c->fused_bar + c->fused_sync_words;
   p.bar = c->fused_bar;
@@ -366,20 +382,28 @@ int fused_setup(ssd_ctx* c) {
   for (int l = 0; l < L; ++l)
     if (m->fused_layers[l].gu.KTW % 4) p.deep = 0;
   if (m->fused_lm.KTW % 4) p.deep = 0;
-  std::vector<FusedLayer> host(L);
+  // Layer tables, one per first sequence of a pass: a pass takes as many whole sequences as fit kFusedMaxRows rows, and
+  // the kernel numbers sequences and rows from 0, so the KV pointers of table s start at sequence s (and at its first
+  // branch row).
+  std::vector<FusedLayer> host((size_t)L * c->B);
   const size_t kvd = (size_t)d.kv_dim();
+  const size_t branch_rows = (size_t)(c->K + 1) * c->F;
   for (int l = 0; l < L; ++l) {
-    FusedLayer& F = host[l];
-    F.qkv = m->fused_layers[l].qkv; F.o = m->fused_layers[l].o; F.gu = m->fused_layers[l].gu; F.down = m->fused_layers[l].down;
-    F.attn_norm = (const bf16_t*)m->layers[l].attn_norm;
-    F.mlp_norm = (const bf16_t*)m->layers[l].mlp_norm;
-    F.trunk_k = (bf16_t*)c->trunk_k[l]; F.trunk_vt = (bf16_t*)c->trunk_v[l];
-    F.suffix_k = (bf16_t*)c->suffix_k[l]; F.suffix_v = (bf16_t*)c->suffix_v[l];
     // masked keys still feed the value MFMA with weight 0: everything there must be finite
     SSD_HIP(hipMemset(c->trunk_k[l], 0, (size_t)c->B * kvd * c->vt_stride * 2));
     SSD_HIP(hipMemset(c->trunk_v[l], 0, (size_t)c->B * kvd * c->vt_stride * 2));
+    for (int sq = 0; sq < c->B; ++sq) {
+      FusedLayer& F = host[(size_t)sq * L + l];
+      F.qkv = m->fused_layers[l].qkv; F.o = m->fused_layers[l].o; F.gu = m->fused_layers[l].gu; F.down = m->fused_layers[l].down;
+      F.attn_norm = (const bf16_t*)m->layers[l].attn_norm;
+      F.mlp_norm = (const bf16_t*)m->layers[l].mlp_norm;
+      F.trunk_k = (bf16_t*)c->trunk_k[l] + (size_t)sq * kvd * c->vt_stride;
+      F.trunk_vt = (bf16_t*)c->trunk_v[l] + (size_t)sq * kvd * c->vt_stride;
+      F.suffix_k = (bf16_t*)c->suffix_k[l] + (size_t)sq * branch_rows * c->K * kvd;
+      F.suffix_v = (bf16_t*)c->suffix_v[l] + (size_t)sq * branch_rows * c->K * kvd;
+    }
   }
-  SSD_HIP(hipMemcpy(c->fused_layers_dev, host.data(), sizeof(FusedLayer) * L, hipMemcpyHostToDevice));
+  SSD_HIP(hipMemcpy(c->fused_layers_dev, host.data(), sizeof(FusedLayer) * host.size(), hipMemcpyHostToDevice));
   p.layers = c->fused_layers_dev;
   return SSD_OK;
 }
@@ -452,7 +476,7 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   c->trunk_k.resize(d.n_layers); c->trunk_v.resize(d.n_layers);
   c->suffix_k.resize(d.n_layers); c->suffix_v.resize(d.n_layers);
   // the fused pass serves every pass of a context it fits (SSD_FUSED=off|phases|persistent overrides, a debugging aid)
-  c->fused_mode = model->fused_ok && fused_supported(d, c->max_rows) ? 2 : 0;
+  c->fused_mode = model->fused_ok && fused_supported(d, (c->K + 1) * c->F) ? 2 : 0;   // rows of one sequence per pass
   if (c->fused_mode && (16 / (d.n_q_heads / d.n_kv_heads)) * (c->K + 1 <= 8 ? 8 : 16) > 64) c->fused_mode = 0;
   if (const char* env = getenv("SSD_FUSED")) {
     if (!strcmp(env, "off")) c->fused_mode = 0;
