@@ -93,9 +93,12 @@ struct Dims {
 };
 
 // ---------------------------------------------------------------- kernels_misc.hip
-// Row descriptors + rotary tables for a branch step / an extend, from device-side trunk lengths.
+// Row descriptors + rotary tables for a branch step / an extend, from device-side trunk lengths.  The branch version
+// also gathers the token every row feeds at this step into step_tokens (null: skipped).
 int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int K, int F, int step,
-                             int half_dim, float theta, hipStream_t s);
+                             int half_dim, float theta, int32_t* step_tokens, const int32_t* keys,
+                             const int32_t* cache_tokens, const int32_t* forced_keys, const int32_t* forced_tokens,
+                             hipStream_t s);
 int launch_setup_extend_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int T, int offset,
                              int half_dim, float theta, hipStream_t s);
 int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* h, int M, int d, int vocab, hipStream_t s);
@@ -106,9 +109,6 @@ int launch_rmsnorm(int dtype, const float* h, const void* gain, void* xn, int64_
 int launch_rope_append(int dtype, const float* qkv, const RowDesc* rows, const float* cos_sin, float* q_out,
                        void* trunk_k, void* trunk_v, void* suffix_k, void* suffix_v, int M, int n_q_heads,
                        int n_kv_heads, int head_dim, int max_trunk, int suffix_cap, hipStream_t s);
-int launch_gather_step_tokens(int32_t* out, const int32_t* keys, const int32_t* cache_tokens,
-                              const int32_t* forced_keys, const int32_t* forced_tokens, int M, int K, int step,
-                              hipStream_t s);
 int launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 int launch_commit(int32_t* trunk_len, const int32_t* accept_len, int B, int K, hipStream_t s);
 int launch_lookup(const int32_t* keys, const int32_t* cache_tokens, const float* cache_logits, const int32_t* accept_len,

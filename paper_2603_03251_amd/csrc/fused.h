@@ -76,7 +76,7 @@ struct FusedParams {
   int64_t part_layer_stride;               // in (q-row) entries
   float* logits;   int64_t logits_ld;      // may be null
   float* hidden;   int64_t hidden_ld;      // may be null
-  unsigned* bar;                           // grid-barrier words, zeroed before a persistent launch
+  unsigned* bar;                           // 1024 grid-barrier words, zeroed once; epochs carry over between launches
   unsigned* err;                           // set to 1 if a bounded wait expired
   unsigned long long* prof;                // optional [phases][kFusedClockSlots][nwg] real-time-counter ticks, or null
   int nwg;
@@ -100,7 +100,7 @@ int launch_copy_kv_fused(bf16_t* trunk_k, bf16_t* trunk_vt, const bf16_t* src_k,
 constexpr int kAtQkv = 2, kAtO = 2, kAtGu = 4, kAtDown = 2, kAtLm = 4;
 
 bool fused_supported(const Dims& d, int max_rows);
-// Runs phases [first, last].  persistent = 1: one launch with grid barriers between phases (p.bar must be zero);
+// Runs phases [first, last].  persistent = 1: one launch with grid barriers between phases;
 // persistent = 0: one launch per phase (a debugging aid that needs no co-residency).
 int launch_fused(const FusedParams& p, int first, int last, int persistent, hipStream_t s);
 int fused_grid_size(int* out);

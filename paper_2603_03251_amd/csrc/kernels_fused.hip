@@ -135,6 +135,7 @@ union Bf8 {
 // epoch in that group's flag, every workgroup polls the 8 flags.  Relaxed agent-scope atomics only: data written
 // before the arrival went out with write-through stores and s_waitcnt 0.  Every wait is bounded; on expiry the
 // error word is set and the workgroup leaves the kernel.
+constexpr int kBarEpochWord = 600;   // barrier words: 8 group counters at 64 g, 8 flags at 512 + g, the epoch here
 struct Grid {
   unsigned* bar;
   unsigned* err;
@@ -1010,7 +1011,9 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
   __shared__ int dead;
   if (threadIdx.x == 0) dead = 0;
   wg_barrier();
-  Grid grid{p.bar, p.err, 0u, persistent, p.nwg, &dead};
+  // The barrier counts on from where the previous launch stopped (its last epoch is kept in a word of its own), so
+  // the barrier words never have to be cleared between launches.
+  Grid grid{p.bar, p.err, persistent ? p.bar[kBarEpochWord] : 0u, persistent, p.nwg, &dead};
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t h_stride = (int64_t)MP * p.d;
   const int64_t ssq_stride = (int64_t)(p.d >> 4) * MP;
@@ -1125,6 +1128,8 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
     stamp(p, ph, 2);
     if (ph < last) grid_arrive(grid);
   }
+  // every workgroup read the word before the first barrier of this launch, which workgroup 0 has passed by now
+  if (persistent && blockIdx.x == 0 && threadIdx.x == 0) p.bar[kBarEpochWord] = grid.epoch;
 }
 
 // ---------------------------------------------------------------------------------------------- set-up kernels

@@ -18,8 +18,13 @@ __device__ __forceinline__ void write_cos_sin(float* cos_sin, int row, int half_
 
 // Branch rows at depth `step` (App. B): row (b,k,j) sits at position trunk_len+1+k+step, sees the trunk up to
 // the glue position of accept length k, and its own step+1 private positions.
+// Everything a branch-decode step needs before its forward pass, in one launch: the row descriptors and rotary tables
+// of step `step`, and the token every row feeds (its cache key at step 0, afterwards the token it drew one step
+// earlier; the forced arrays replace both under teacher forcing).
 __global__ void setup_branch_rows_kernel(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int M, int K, int F,
-                                         int step, int half_dim, float theta) {
+                                         int step, int half_dim, float theta, int32_t* step_tokens, const int32_t* keys,
+                                         const int32_t* cache_tokens, const int32_t* forced_keys,
+                                         const int32_t* forced_tokens) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= M * half_dim) return;
   int m = idx / half_dim, i = idx % half_dim;
@@ -31,6 +36,10 @@ __global__ void setup_branch_rows_kernel(RowDesc* rows, float* cos_sin, const in
     RowDesc r;
     r.seq = b; r.pos = pos; r.vis = tl + k + 1; r.suffix_len = step + 1; r.kv_slot = step; r.is_branch = 1;
     rows[m] = r;
+    if (step_tokens) {
+      if (step == 0) step_tokens[m] = forced_keys ? forced_keys[m] : keys[m];
+      else step_tokens[m] = forced_tokens ? forced_tokens[(int64_t)m * K + step - 1] : cache_tokens[(int64_t)m * K + step - 1];
+    }
   }
   write_cos_sin(cos_sin, m, half_dim, i, pos, theta);
 }
@@ -156,15 +165,6 @@ __global__ void rope_append_kernel(const float* qkv, const RowDesc* rows, const 
 }
 
 // Input token of every branch row at depth `step`: the cache key (step 0) or the previous step's token.
-__global__ void gather_step_tokens_kernel(int32_t* out, const int32_t* keys, const int32_t* cache_tokens,
-                                          const int32_t* forced_keys, const int32_t* forced_tokens, int M, int K,
-                                          int step) {
-  int m = blockIdx.x * blockDim.x + threadIdx.x;
-  if (m >= M) return;
-  if (step == 0) out[m] = forced_keys ? forced_keys[m] : keys[m];
-  else out[m] = forced_tokens ? forced_tokens[(int64_t)m * K + step - 1] : cache_tokens[(int64_t)m * K + step - 1];
-}
-
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -219,10 +219,13 @@ inline int grid_for(int64_t n) { return (int)((n + kBlock - 1) / kBlock); }
 }  // namespace
 
 int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int K, int F, int step,
-                             int half_dim, float theta, hipStream_t s) {
-  int M = B * (K + 1) * F;
+                             int half_dim, float theta, int32_t* step_tokens, const int32_t* keys,
+                             const int32_t* cache_tokens, const int32_t* forced_keys, const int32_t* forced_tokens,
+                             hipStream_t s) {
+  const int M = B * (K + 1) * F;
   setup_branch_rows_kernel<<<grid_for((int64_t)M * half_dim), kBlock, 0, s>>>(rows, cos_sin, trunk_len, M, K, F, step,
-                                                                             half_dim, theta);
+                                                                             half_dim, theta, step_tokens, keys,
+                                                                             cache_tokens, forced_keys, forced_tokens);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }
@@ -263,15 +266,6 @@ int launch_rope_append(int dtype, const float* qkv, const RowDesc* rows, const f
     rope_append_kernel<float><<<M, kBlock, 0, s>>>(qkv, rows, cos_sin, q_out, (float*)trunk_k, (float*)trunk_v,
                                                    (float*)suffix_k, (float*)suffix_v, n_q_heads, n_kv_heads, head_dim,
                                                    max_trunk, suffix_cap);
-  SSD_HIP(hipGetLastError());
-  return SSD_OK;
-}
-
-int launch_gather_step_tokens(int32_t* out, const int32_t* keys, const int32_t* cache_tokens,
-                              const int32_t* forced_keys, const int32_t* forced_tokens, int M, int K, int step,
-                              hipStream_t s) {
-  gather_step_tokens_kernel<<<grid_for(M), kBlock, 0, s>>>(out, keys, cache_tokens, forced_keys, forced_tokens, M, K,
-                                                           step);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }

@@ -126,7 +126,7 @@ struct ssd_ctx {
   FusedLayer* fused_layers_dev = nullptr;
   unsigned* fused_bar = nullptr;
   unsigned* fused_err = nullptr;
-  int64_t fused_sync_words = 0; // barrier words, zeroed before every persistent launch
+  int64_t fused_sync_words = 0; // barrier words, zeroed once (the barrier's epoch carries over from launch to launch)
   int64_t part_entries = 0;    // per-layer capacity of the attention partial buffers, in query rows
   unsigned long long* phase_clocks = nullptr;
   const int32_t* forced_keys = nullptr;
@@ -269,7 +269,6 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
       set_error("fused pass: attention partial buffer too small (%d splits, %d query tiles)", p.NS, p.QT);
       return SSD_ESTATE;
     }
-    SSD_TRY(launch_fill_i32((int32_t*)c->fused_bar, 0, c->fused_sync_words, s));
     SSD_TRY(launch_fused(p, 0, last, c->fused_mode == 2, s));
   }
   if (timed) SSD_HIP(hipEventRecord(c->kernel_events[2 * branch_depth + 1], s));
@@ -622,8 +621,8 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
   SSD_TRY(mark());
   // a2/a3: K batched branch-decode steps; logits and tokens land in the cache directly
   for (int i = 0; i < K; ++i) {
-    SSD_TRY(launch_gather_step_tokens(c->step_tokens, c->keys, c->tokens, c->forced_keys, c->forced_tokens, M, K, i, s));
-    SSD_TRY(launch_setup_branch_rows(c->rows, c->cos_sin, c->trunk_len, B, K, F, i, d.head_dim / 2, d.rope_theta, s));
+    SSD_TRY(launch_setup_branch_rows(c->rows, c->cos_sin, c->trunk_len, B, K, F, i, d.head_dim / 2, d.rope_theta, c->step_tokens,
+                                     c->keys, c->tokens, c->forced_keys, c->forced_tokens, s));
     SSD_TRY(forward_rows(c, M, c->step_tokens, (K + 1) * F, c->trunk_ub + K + 1, i, c->logits + (size_t)i * V, (int64_t)K * V,
                          c->hidden + (size_t)i * d.d_model, (int64_t)K * d.d_model, s));
     if (c->saguaro_c < 1.0f) {
