@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the fused decode kernel from the rocprofv3 counter runs summarised in
 # profiles/fused_decode_kernel_1b_p1024_f4_hbm_traffic.txt (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)
-MEASURED_TRAFFIC_BYTES = 2863934978
+MEASURED_TRAFFIC_BYTES = 2781659285
 WORKLOAD = "1b_p1024_f4"
 WEIGHT_SEED = 2025
 
