@@ -236,13 +236,28 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
   const int RG = p.R * p.G;
   p.QT = (RG + 15) / 16;
   p.SL = c->K + 1 <= 8 ? 8 : 16;
-  // stored trunk keys are split over several units only when one unit's share would pass 2048 keys
   const int p_ub = max_vis > 1 ? max_vis : 1;
-  int ns = (p_ub + 2047) / 2048;
-  p.KPU = ((p_ub + ns - 1) / ns + 31) / 32 * 32;
-  p.NS = (p_ub + p.KPU - 1) / p.KPU;
   const int n_seq = M / rows_per_seq;
   const int per_pass = kFusedMaxRows / rows_per_seq;
+  // Key splits of the stored trunk: the attention phase lasts (rounds of units over the grid) x (a unit's 32-key blocks
+  // per wavefront + its fixed part), and more than one split adds a merge phase.  Costs in microseconds as measured
+  // on the 1B shape; the choice only affects speed.
+  {
+    const int seqs = n_seq < per_pass ? n_seq : (per_pass > 0 ? per_pass : 1);
+    const int pairs = seqs * p.Hkv * p.QT;
+    int best = 1;
+    float best_cost = 0.f;
+    const int ns_cap = (c->max_trunk + 2047) / 2048 + 1;   // what the partial-softmax buffers were sized for
+    for (int ns = 1; ns <= ns_cap && ns <= 16; ++ns) {
+      const int keys = (p_ub + ns - 1) / ns;
+      const int blocks = ((keys + 31) / 32 + kFusedWaves - 1) / kFusedWaves;
+      const int rounds = (pairs * ns + p.nwg - 1) / p.nwg;
+      const float cost = rounds * (0.9f * blocks + 3.0f) + (ns > 1 ? 5.0f : 0.f);
+      if (ns == 1 || cost < best_cost) { best = ns; best_cost = cost; }
+    }
+    p.KPU = ((p_ub + best - 1) / best + 31) / 32 * 32;
+    p.NS = (p_ub + p.KPU - 1) / p.KPU;
+  }
   if (per_pass < 1 || n_seq * rows_per_seq != M) {
     set_error("fused pass: %d rows of %d per sequence do not fit passes of %d rows", M, rows_per_seq, kFusedMaxRows);
     return SSD_ESTATE;
