@@ -144,7 +144,9 @@ int ssd_prespeculate(ssd_ctx* ctx, const int32_t* d_pending, const float* d_temp
 
 /* Teacher forcing for parity tests: when set, branch row inputs are taken from the caller instead of
  * the library's own selection/sampling (outputs are still written as usual).  d_keys [B][K+1][F] feeds
- * step 0, d_tokens [B][K+1][F][K] entry i-1 feeds step i.  Either may be NULL (not forced). */
+ * step 0, d_tokens [B][K+1][F][K] entry i-1 feeds step i.  Either may be NULL (not forced).  The context keeps the
+ * POINTERS, not copies: both arrays stay caller-owned and must remain valid until they are replaced or cleared and every
+ * ssd_prespeculate enqueued meanwhile has run. */
 int ssd_ctx_set_forced(ssd_ctx* ctx, const int32_t* d_keys, const int32_t* d_tokens);
 
 /* Saguaro sampling scheme sigma_{F,C} (Sec. 4.3): with C < 1 every later ssd_prespeculate draws the branch tokens of

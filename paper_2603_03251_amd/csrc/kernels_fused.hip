@@ -1000,7 +1000,6 @@ __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, 
 // Register chunks in flight per wavefront.  DEEP needs the k-tiles per wavefront of every linear layer to be a
 // multiple of 8 (one feature tile per unit) / 4 (four per unit); the shallow set needs multiples of 2.
 template <int MT, bool DEEP> struct Depth {
-  static constexpr int a1 = !DEEP ? 2 : 4;                    // one feature tile per unit
   static constexpr int a4 = !DEEP ? 2 : (MT == 3 ? 2 : 4);   // four feature tiles per unit
 };
 
