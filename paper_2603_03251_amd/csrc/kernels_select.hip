@@ -46,15 +46,30 @@ __global__ __launch_bounds__(kSelBlock) void top_f_kernel(const float* __restric
   uint64_t best[FMAX];
 #pragma unroll
   for (int i = 0; i < FMAX; ++i) best[i] = 0ull;    // 0 is below every real key (ids < 2^32-1)
-  for (int t = threadIdx.x; t < V; t += kSelBlock) {
-    if (t == ex) continue;
-    uint64_t k = make_key(z[t], t);
+  auto offer = [&](float v, int t) {
+    if (t == ex) return;
+    uint64_t k = make_key(v, t);
     if (k > best[FMAX - 1]) {
       best[FMAX - 1] = k;
 #pragma unroll
       for (int i = FMAX - 1; i > 0; --i) {
         if (best[i] > best[i - 1]) { uint64_t tmp = best[i]; best[i] = best[i - 1]; best[i - 1] = tmp; }
       }
+    }
+  };
+  // eight loads in flight per thread: one dependent load per iteration would cost a memory latency each
+  constexpr int U = 8;
+  for (int t0 = threadIdx.x; t0 < V; t0 += kSelBlock * U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * kSelBlock;
+      v[u] = z[t < V ? t : t0];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * kSelBlock;
+      if (t < V) offer(v[u], t);
     }
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
