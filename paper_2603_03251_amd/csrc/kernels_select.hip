@@ -227,14 +227,36 @@ __global__ __launch_bounds__(kSelBlock) void verify_stats_kernel(const float* __
     z = zd + ((int64_t)b * K + (r - K - 1)) * V;
   }
   ScoreId best = {-INFINITY, 0x7fffffff};
-  for (int t = threadIdx.x; t < V; t += kSelBlock) {
-    ScoreId c = {score_of(z[t]), t};
-    if (better(c, best)) best = c;
+  // eight loads in flight per thread in both scans (same visiting order as a plain strided loop)
+  constexpr int U = 8;
+  for (int t0 = threadIdx.x; t0 < V; t0 += kSelBlock * U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * kSelBlock;
+      v[u] = z[t < V ? t : t0];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * kSelBlock;
+      ScoreId c = {score_of(v[u]), t};
+      if (t < V && better(c, best)) best = c;
+    }
   }
   best = block_argmax(best, smem);
   double sum = 0.0;
   if (T > 0.0) {
-    for (int t = threadIdx.x; t < V; t += kSelBlock) sum += exp((score_of(z[t]) - best.s) / T);
+    for (int t0 = threadIdx.x; t0 < V; t0 += kSelBlock * U) {
+      float v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int t = t0 + u * kSelBlock;
+        v[u] = z[t < V ? t : t0];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (t0 + u * kSelBlock < V) sum += exp((score_of(v[u]) - best.s) / T);
+    }
     sum = block_sum_f64(sum, dsm);
   }
   if (threadIdx.x == 0) {
