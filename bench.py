@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MEASURED_STREAM_READ_GBS = 7100.0     # register-ring streaming read of 2 GiB, 256 workgroups x 8 wavefronts
 # HBM bytes per launch of the fused decode kernel from the rocprofv3 counter runs summarised in
 # profiles/fused_decode_kernel_1b_p1024_f4_hbm_traffic.txt (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)
 MEASURED_TRAFFIC_BYTES = 2781659285
@@ -268,7 +269,7 @@ def main():
     # per-segment HIP-event times of the last round + a few extra rounds (the events are per-context)
     seg = []
     fused = True
-    for i in range(min(args.steps, 10)):
+    for i in range(min(max(args.steps, 1), 50)):
         one_round(2000 + i)
         try:
             seg.append(B.ssd_ctx_read_timing(ctx, K, with_kernels=fused))
@@ -303,11 +304,16 @@ def main():
         "segments_ms": {"glue_extend": float(seg[:, 0].mean()), "fan_out": float(seg[:, 1].mean()),
                         "branch_decode_step": step_ms, "decode_steps_total": float(seg[:, 2:K + 2].sum(axis=1).mean())},
         "decode_only_branch_tokens_per_s": tokens_per_round / (float(seg[:, 2:K + 2].sum(axis=1).mean()) * 1e-3),
+        # the draft stream's own time per round (HIP events: glue extend + fan-out + K steps), over the segment-timing rounds
+        "round_ms_percentiles": dict(zip(("p10", "p50", "p90"),
+                                         (float(x) for x in np.percentile(seg[:, :K + 2].sum(axis=1), [10, 50, 90])))),
         "roofline": {"kernel": (f"fused_kernel: one batched branch-decode step ({r.rows} rows) in one persistent launch" if fused
                                 else f"one batched branch-decode step ({r.rows} rows), one kernel per operator"),
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES if headline and fused else None,
-                     "bytes_per_launch": bytes_step, "avg_ms": kernel_ms},
+                     "bytes_per_launch": bytes_step, "avg_ms": kernel_ms,
+                     # against what a plain streaming read reaches on this machine (profiles/microbenchmarks_mi355x.txt)
+                     "frac_of_measured_stream_read": achieved / MEASURED_STREAM_READ_GBS},
     }
     # with hundreds of rows the linear layers approach the MFMA ridge: report their share of the dense bf16 peak too
     d_, f_, L_ = shape.d_model, shape.d_ffn, shape.n_layers
