@@ -21,6 +21,10 @@ What each function follows (section / equation / algorithm of the paper):
   prespeculate                 Alg. 1, predict_verify_outcomes + speculate_for_outcomes;
                                Def. "speculation cache"; App. C (token / element counts)
   cache_lookup                 Alg. 1 (lookup of the realised outcome), App. B payload
+  cache_hit_rate, geometric_fan_out_real, geometric_fan_out
+                               Sec. 4.2.2, Def. "r power-law cache hit rate" and Theorem
+                               "Saguaro Cache Shape: Geometric Fan-Out"; closed form of
+                               F_0 from its proof in the theory appendix
   ssd_generate                 Alg. 1 (whole loop, backup speculator = primary, just in time)
   ar_generate                  ordinary autoregressive decoding (the losslessness reference)
 
@@ -345,26 +349,103 @@ def glue_extend(m: Model, trunk: KV, pending: Sequence[int]) -> Tuple[np.ndarray
     return logits, hid, trunk.concat(kv)
 
 
-def fan_out(glue_logits: np.ndarray, pending: Sequence[int], F: int) -> np.ndarray:
-    """keys[k][j], k = 0..K: the F most likely bonus tokens if exactly k drafted tokens
-    are accepted: top-F of the logits s_{k+1} was drawn from, without s_{k+1} itself
-    (a rejected token has zero residual mass); for k = K, top-F of the logits after s_K."""
+def fan_of(F, K: int) -> np.ndarray:
+    """Fan-out per accept length: F_k, k = 0..K.  A plain integer is the uniform cache shape."""
+    fan = np.full(K + 1, F, np.int64) if np.ndim(F) == 0 else np.asarray(F, np.int64)
+    assert fan.shape == (K + 1,) and (fan >= 1).all()
+    return fan
+
+
+def fan_out(glue_logits: np.ndarray, pending: Sequence[int], F) -> np.ndarray:
+    """keys[k][j], k = 0..K: the F_k most likely bonus tokens if exactly k drafted tokens
+    are accepted: top-F_k of the logits s_{k+1} was drawn from, without s_{k+1} itself
+    (a rejected token has zero residual mass); for k = K, top-F_K of the logits after s_K.
+    With a fan-out that differs per accept length (Sec. 4.2.2) the array is max F_k wide and
+    the unused entries hold -1, which no token equals."""
     K = len(pending) - 1
-    keys = np.empty((K + 1, F), dtype=np.int32)
+    fan = fan_of(F, K)
+    keys = np.full((K + 1, int(fan.max())), -1, dtype=np.int32)
     for k in range(K + 1):
-        keys[k] = top_f_ids(glue_logits[k], F, exclude=int(pending[k + 1]) if k < K else None)
+        keys[k, :fan[k]] = top_f_ids(glue_logits[k], int(fan[k]), exclude=int(pending[k + 1]) if k < K else None)
     return keys
+
+
+# --------------------------------------------------------------------------- cache shape (Sec. 4.2.2)
+
+def cache_hit_rate(fan: Sequence[float], a: float, r: float) -> float:
+    """Chance that the verification outcome of a speculation is in the cache, for a speculator
+    with acceptance rate a whose miss rate at fan-out F is F^-r: exactly k < K tokens are
+    accepted with probability a^k (1 - a), all K with probability a^K, and the outcome at
+    accept length k is among the F_k cached ones with probability 1 - F_k^-r."""
+    K = len(fan) - 1
+    p = a ** K * (1.0 - float(fan[K]) ** -r)
+    for k in range(K):
+        p += a ** k * (1.0 - a) * (1.0 - float(fan[k]) ** -r)
+    return p
+
+
+def geometric_fan_out_real(budget: float, K: int, a: float, r: float) -> np.ndarray:
+    """The real-valued F_0..F_K that maximise `cache_hit_rate` under sum F_k = budget
+    (Theorem "Geometric Fan-Out"): F_k = F_0 a^(k/(1+r)) below K, the last one larger by
+    (1-a)^(-1/(1+r)), F_0 from the budget."""
+    assert 0.0 < a < 1.0 and r > 0.0 and K >= 0
+    q = a ** (1.0 / (1.0 + r))
+    last = q ** K * (1.0 - a) ** (-1.0 / (1.0 + r))
+    f0 = budget / (last + (1.0 - q ** K) / (1.0 - q))
+    return np.array([f0 * q ** k for k in range(K)] + [f0 * last], F64)
+
+
+def geometric_fan_out(budget: int, K: int, a: float, r: float, f_max: Optional[int] = None) -> np.ndarray:
+    """Integer cache shape from the theorem's real-valued one.  The paper does not say how the
+    F_k become integers; the reading taken here: every accept length keeps at least one
+    candidate, none more than f_max; an F_k the real solution puts outside [1, f_max] is fixed
+    at that bound and the rest of the budget is shared among the others in the theorem's
+    proportions (the stationarity conditions of the bounded problem); the shares are rounded
+    down and the units left over go to the largest fractional parts, lower k first on ties,
+    so that sum F_k = budget exactly."""
+    cap = budget if f_max is None else f_max
+    assert K + 1 <= budget <= (K + 1) * cap
+    w = geometric_fan_out_real(1.0, K, a, r)            # proportions
+    lo = np.zeros(K + 1, bool)
+    hi = np.zeros(K + 1, bool)
+    while True:
+        free = ~(lo | hi)
+        left = budget - int(lo.sum()) - cap * int(hi.sum())
+        x = np.where(lo, 1.0, np.where(hi, float(cap), 0.0))
+        if free.any():
+            x[free] = left * w[free] / w[free].sum()
+        over = free & (x > cap)
+        under = free & (x < 1.0)
+        if over.any():                                  # bind one kind at a time, the upper bound first
+            hi |= over
+        elif under.any():
+            lo |= under
+        else:
+            break
+    fan = np.floor(x + 1e-9).astype(np.int64)
+    frac = x - fan
+    order = sorted(range(K + 1), key=lambda k: (-frac[k], k))
+    spare = budget - int(fan.sum())
+    i = 0
+    while spare > 0:
+        k = order[i % (K + 1)]
+        if fan[k] < cap:
+            fan[k] += 1
+            spare -= 1
+        i += 1
+    return fan
 
 
 @dataclass
 class SpecCache:
-    keys: np.ndarray        # int32 [K+1][F]
+    keys: np.ndarray        # int32 [K+1][F]           (F = max F_k; entries j >= F_k are -1 / zero)
     tokens: np.ndarray      # int32 [K+1][F][K]
     logits: np.ndarray      # float64 [K+1][F][K][V]
     hidden: np.ndarray      # float64 [K+1][F][K][d]   (final-norm hidden states, for parity)
     margins: np.ndarray     # float64 [K+1][F][K]      (sampling margin of every decoded token)
     glue_logits: np.ndarray # float64 [K+1][V]
     trunk: KV               # trunk + glue KV after the extend
+    fan: Optional[np.ndarray] = None   # int64 [K+1]: F_k
 
 
 def decode_branch(m: Model, trunk_glue: KV, P: int, k: int, first: int, steps: int, T: float,
@@ -376,7 +457,8 @@ def decode_branch(m: Model, trunk_glue: KV, P: int, k: int, first: int, steps: i
 
     `sigma` = (F, C) drafts with the Saguaro sampling scheme sigma_{F,C} (Sec. 4.3): at T > 0
     every token is drawn from the model's logits with the top-F entries downweighted by C, and
-    those are the logits returned (the distribution a verifier has to be given)."""
+    those are the logits returned (the distribution a verifier has to be given).  F is one
+    number, or one per step."""
     past = trunk_glue.slice(P + k + 1)
     tok = int(first)
     toks, logs, hids, margs = [], [], [], []
@@ -385,7 +467,9 @@ def decode_branch(m: Model, trunk_glue: KV, P: int, k: int, first: int, steps: i
         logits, hid, kv = forward(m, [tok], [P + 1 + k + i], past, np.ones((1, S + 1), dtype=bool))
         past = past.concat(kv)
         noise = gumbel(seed, STREAM_DRAFT, row, i, m.vocab) if T > 0 else None
-        z = logits[0] if sigma is None or T == 0.0 else sigma_FC_logits(logits[0], sigma[0], sigma[1], T)
+        z = logits[0]
+        if sigma is not None and T > 0.0:
+            z = sigma_FC_logits(z, int(sigma[0]) if np.ndim(sigma[0]) == 0 else int(sigma[0][i]), sigma[1], T)
         nxt, margin = sample_token(z, T, noise)
         toks.append(nxt)
         logs.append(z)
@@ -395,7 +479,7 @@ def decode_branch(m: Model, trunk_glue: KV, P: int, k: int, first: int, steps: i
     return np.array(toks, np.int32), np.array(logs), np.array(hids), np.array(margs)
 
 
-def prespeculate(m: Model, trunk: KV, pending: Sequence[int], F: int, T: float, seed: int,
+def prespeculate(m: Model, trunk: KV, pending: Sequence[int], F, T: float, seed: int,
                  row_base: int = 0,
                  only_rows: Optional[Sequence[int]] = None,
                  forced_tokens: Optional[np.ndarray] = None,
@@ -403,29 +487,36 @@ def prespeculate(m: Model, trunk: KV, pending: Sequence[int], F: int, T: float, 
     """One pre-speculation round for one sequence: glue extend, fan-out, then every branch
     (k, j) decoded for K tokens, one branch at a time, each with KV of its own.
 
-    `row_base` is the global row index of branch (0,0) (rows of a batch are numbered
-    b (K+1) F + k F + j; the index keys the draft Gumbel stream).  `only_rows` restricts
-    the decode to a sample of branches (the others are left zero).  `forced_tokens`
-    [K+1][F][K] teacher-forces every branch's inputs.  C < 1 decodes the branches with the
-    sampling scheme sigma_{F,C} (Sec. 4.3); the fan-out itself always ranks the model's own logits."""
+    F is the uniform fan-out, or F_0..F_K (Sec. 4.2.2).  Branches are numbered accept length
+    by accept length, r = F_0 + .. + F_{k-1} + j (k F + j when uniform); `row_base` is the
+    global row index of branch (0,0) (a batch numbers its rows sequence after sequence; the
+    index keys the draft Gumbel stream).  `only_rows` restricts the decode to a sample of
+    branches (the others are left zero).  `forced_tokens` [K+1][max F_k][K] teacher-forces
+    every branch's inputs.  C < 1 decodes the branches with the sampling scheme sigma_{F,C}
+    (Sec. 4.3); the fan-out itself always ranks the model's own logits.  The token drafted at
+    depth i is the one whose rejection ends the next round at accept length i, where the
+    cache will hold F_i candidates: that is the F its logits are downweighted with."""
     K = len(pending) - 1
     P = trunk.length
+    fan = fan_of(F, K)
+    Fm = int(fan.max())
+    off = np.concatenate([[0], np.cumsum(fan)])
     glue_logits, _, trunk_glue = glue_extend(m, trunk, pending)
-    keys = fan_out(glue_logits, pending, F)
-    tokens = np.zeros((K + 1, F, K), np.int32)
-    logits = np.zeros((K + 1, F, K, m.vocab), F64)
-    hidden = np.zeros((K + 1, F, K, m.d_model), F64)
-    margins = np.full((K + 1, F, K), np.inf, F64)
+    keys = fan_out(glue_logits, pending, fan)
+    tokens = np.zeros((K + 1, Fm, K), np.int32)
+    logits = np.zeros((K + 1, Fm, K, m.vocab), F64)
+    hidden = np.zeros((K + 1, Fm, K, m.d_model), F64)
+    margins = np.full((K + 1, Fm, K), np.inf, F64)
     for k in range(K + 1):
-        for j in range(F):
-            r = k * F + j
+        for j in range(int(fan[k])):
+            r = int(off[k]) + j
             if only_rows is not None and r not in only_rows:
                 continue
             forced = None if forced_tokens is None else forced_tokens[k, j]
             t, l, h, g = decode_branch(m, trunk_glue, P, k, keys[k, j], K, T, seed, row_base + r, forced,
-                                       sigma=(F, C) if C < 1.0 else None)
+                                       sigma=(fan[:K], C) if C < 1.0 else None)
             tokens[k, j], logits[k, j], hidden[k, j], margins[k, j] = t, l, h, g
-    return SpecCache(keys, tokens, logits, hidden, margins, glue_logits, trunk_glue)
+    return SpecCache(keys, tokens, logits, hidden, margins, glue_logits, trunk_glue, fan)
 
 
 def cache_lookup(keys: np.ndarray, accept_len: int, bonus: int) -> int:
