@@ -20,7 +20,11 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work; none synchronises the host unless stated.
  *   - Branch row order (part of the contract): row = b (K+1) F + k F + j, with b the
- *     sequence, k the accept length 0..K and j the candidate rank 0..F-1.
+ *     sequence, k the accept length 0..K and j the candidate rank 0..F-1.  With a fan-out
+ *     F_0..F_K that differs per accept length (Sec. 4.2.2; ssd_ctx_create_fanout) rows run
+ *     accept length by accept length: row = b R + (F_0 + .. + F_{k-1}) + j, j < F_k,
+ *     R = F_0 + .. + F_K rows per sequence; wherever a layout below says [K+1][F], such a
+ *     context holds [R] in that order (no padding).
  *   - Ordering of tokens wherever a maximum or a top-F is taken: larger score first,
  *     equal scores by smaller token id; NaN ranks below every number.
  *   - The library allocates device memory only in *_create; the hot calls
@@ -118,6 +122,22 @@ int ssd_model_destroy(ssd_model* m);
 /* The context keeps a pointer to `model`; destroy the context first. */
 int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx** out);
 int ssd_ctx_destroy(ssd_ctx* ctx);
+
+/* Cache shape (Sec. 4.2.2, Theorem "Geometric Fan-Out"): a context whose fan-out differs per accept length.
+ * h_fanout: host int32 [K+1], F_k in 1..SSD_MAX_F (read during the call only); cfg->F is ignored.  Everything else
+ * is as for ssd_ctx_create; ssd_views.F reports the largest F_k.  ssd_ctx_fanout copies F_0..F_K of any context
+ * to h_fanout [K+1]. */
+int ssd_ctx_create_fanout(const ssd_model* model, const ssd_round_config* cfg, const int32_t* h_fanout, ssd_ctx** out);
+int ssd_ctx_fanout(const ssd_ctx* ctx, int32_t* h_fanout);
+
+/* The theorem's shape as integers (host only, no GPU work): for a speculator with acceptance rate a in (0,1) whose
+ * cache-miss rate at fan-out F is F^-r (r > 0), F_k proportional to a^(k/(1+r)) below K and the last one larger by
+ * (1-a)^(-1/(1+r)), scaled so that F_0 + .. + F_K = budget (the closed form of F_0 in the theorem's proof).
+ * The paper leaves the step to integers open; here every F_k is kept within 1..f_max (a bound that binds holds that
+ * F_k, the others share the rest in the same proportions), shares are rounded down and the units left over go to
+ * the largest fractional parts, lower k first on ties.  out h_fanout int32 [K+1].
+ * EINVAL unless K+1 <= budget <= (K+1) f_max. */
+int ssd_geometric_fanout(int32_t budget, int32_t K, double a, double r, int32_t f_max, int32_t* h_fanout);
 
 /* Trunk := KV of d_tokens[b][0 .. h_lens[b]-1] (row stride `stride` tokens), computed with the same
  * extend kernels in chunks.  EINVAL if a length exceeds max_trunk - (2K+2). */

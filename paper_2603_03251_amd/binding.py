@@ -7,7 +7,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import Dict, Optional, Sequence
+from typing import Dict, List, Optional, Sequence
 
 import numpy as np
 import torch  # imported before the library so that both share one HIP runtime
@@ -62,6 +62,10 @@ EXPORTS = {
     "ssd_prespeculate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "ssd_ctx_set_forced": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ssd_ctx_set_saguaro": (C.c_int, [C.c_void_p, C.c_float]),
+    "ssd_ctx_create_fanout": (C.c_int, [C.c_void_p, C.POINTER(ssd_round_config), C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_void_p)]),
+    "ssd_ctx_fanout": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32)]),
+    "ssd_geometric_fanout": (C.c_int, [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_int32, C.POINTER(C.c_int32)]),
     "ssd_cache_lookup": (C.c_int, [C.c_void_p] * 8),
     "ssd_ctx_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ssd_verify": (C.c_int, [C.c_void_p] * 4 + [C.c_int32] * 3 + [C.c_uint64] + [C.c_void_p] * 4),
@@ -181,6 +185,28 @@ def ssd_ctx_create(model: int, batch: int, K: int, F: int, max_trunk: int) -> in
     return out.value
 
 
+def ssd_ctx_create_fanout(model: int, batch: int, K: int, fanout: Sequence[int], max_trunk: int) -> int:
+    assert len(fanout) == K + 1
+    cfg = ssd_round_config(batch, K, 0, max_trunk)
+    fan = (C.c_int32 * (K + 1))(*[int(f) for f in fanout])
+    out = C.c_void_p()
+    _check(lib.ssd_ctx_create_fanout(model, C.byref(cfg), fan, C.byref(out)))
+    return out.value
+
+
+def ssd_ctx_fanout(ctx: int) -> List[int]:
+    K = ssd_ctx_views(ctx).K
+    fan = (C.c_int32 * (K + 1))()
+    _check(lib.ssd_ctx_fanout(ctx, fan))
+    return list(fan)
+
+
+def ssd_geometric_fanout(budget: int, K: int, a: float, r: float, f_max: int = SSD_MAX_F) -> List[int]:
+    fan = (C.c_int32 * (K + 1))()
+    _check(lib.ssd_geometric_fanout(budget, K, a, r, f_max, fan))
+    return list(fan)
+
+
 def ssd_ctx_destroy(ctx: int) -> None:
     _check(lib.ssd_ctx_destroy(ctx))
 
@@ -277,10 +303,43 @@ def ssd_ctx_views(ctx: int) -> ssd_views:
     return v
 
 
+def _read_ragged_cache(v: ssd_views, fan: List[int], with_logits: bool) -> Dict[str, torch.Tensor]:
+    """Cache of a context whose fan-out differs per accept length, spread out to [B][K+1][max F_k] (unused
+    entries: key -1, everything else zero)."""
+    B, K, F, V, d = v.batch, v.K, v.F, v.vocab, v.d_model
+    R = sum(fan)
+    flat = {
+        "keys": device_copy(v.d_keys, (B, R), torch.int32),
+        "tokens": device_copy(v.d_tokens, (B, R, K), torch.int32),
+        "hidden": device_copy(v.d_hidden, (B, R, K, d), torch.float32),
+    }
+    if with_logits:
+        flat["logits"] = device_copy(v.d_logits, (B, R, K, V), torch.float32)
+    out = {
+        "trunk_len": device_copy(v.d_trunk_len, (B,), torch.int32),
+        "glue_hidden": device_copy(v.d_glue_hidden, (B, K + 1, d), torch.float32),
+        "glue_logits": device_copy(v.d_glue_logits, (B, K + 1, V), torch.float32),
+    }
+    for name, t in flat.items():
+        wide = torch.zeros((B, K + 1, F) + tuple(t.shape[2:]), dtype=t.dtype, device=t.device)
+        if name == "keys":
+            wide.fill_(-1)
+        off = 0
+        for k, f in enumerate(fan):
+            wide[:, k, :f] = t[:, off:off + f]
+            off += f
+        out[name] = wide
+    torch.cuda.synchronize()
+    return out
+
+
 def read_cache(ctx: int, with_logits: bool = True) -> Dict[str, torch.Tensor]:
     """Copies of the speculation cache and glue outputs as tensors (test/read-out helper)."""
     v = ssd_ctx_views(ctx)
     B, K, F, V, d = v.batch, v.K, v.F, v.vocab, v.d_model
+    fan = ssd_ctx_fanout(ctx)
+    if len(set(fan)) > 1:
+        return _read_ragged_cache(v, fan, with_logits)
     out = {
         "trunk_len": device_copy(v.d_trunk_len, (B,), torch.int32),
         "keys": device_copy(v.d_keys, (B, K + 1, F), torch.int32),

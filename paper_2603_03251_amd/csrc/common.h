@@ -92,10 +92,17 @@ struct Dims {
   int qkv_dim() const { return q_dim() + 2 * kv_dim(); }
 };
 
+// Cache shape (Sec. 4.2.2): fan-out per accept length as running offsets.  Accept length k owns the F_k =
+// off[k+1] - off[k] consecutive branch rows off[k] .. off[k+1]-1 of its sequence; off[K+1] is the rows per sequence.
+// The uniform shape is off[k] = k F.  Passed to kernels by value.
+struct FanTable {
+  int32_t off[SSD_MAX_K + 2];
+};
+
 // ---------------------------------------------------------------- kernels_misc.hip
 // Row descriptors + rotary tables for a branch step / an extend, from device-side trunk lengths.  The branch version
 // also gathers the token every row feeds at this step into step_tokens (null: skipped).
-int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int K, int F, int step,
+int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int K, const FanTable& fan, int step,
                              int half_dim, float theta, int32_t* step_tokens, const int32_t* keys,
                              const int32_t* cache_tokens, const int32_t* forced_keys, const int32_t* forced_tokens,
                              hipStream_t s);
@@ -113,7 +120,7 @@ int launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 int launch_commit(int32_t* trunk_len, const int32_t* accept_len, int B, int K, hipStream_t s);
 int launch_lookup(const int32_t* keys, const int32_t* cache_tokens, const float* cache_logits, const int32_t* accept_len,
                   const int32_t* bonus, uint8_t* hit, int32_t* branch, int32_t* spec, const float** logits_ptr, int B,
-                  int K, int F, int V, hipStream_t s);
+                  int K, const FanTable& fan, int V, hipStream_t s);
 int launch_pending_exclude(int32_t* exclude, const int32_t* pending, int B, int K, hipStream_t s);
 int launch_copy_kv_in(int dtype, void* trunk, const void* src, int B, int len, int max_trunk, int row_elems, hipStream_t s);
 
@@ -148,6 +155,9 @@ int64_t attention_partial_floats(int M, int n_q_heads, int head_dim, int max_key
 // ---------------------------------------------------------------- kernels_select.hip
 int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int32_t* ids,
                  hipStream_t s);
+// The fan-out of a round: row (b, k) of logits [B (K+1)] gives its top F_k to ids[b][off[k] ..].
+int launch_top_f_fan(const float* logits, int64_t ld, const int32_t* exclude, int B, int K, const FanTable& fan, int V,
+                     int32_t* ids, hipStream_t s);
 int launch_sample(const float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int V,
                   uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, void* scratch, hipStream_t s);
 size_t sample_scratch_bytes(int rows);

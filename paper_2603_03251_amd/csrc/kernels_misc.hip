@@ -21,15 +21,17 @@ __device__ __forceinline__ void write_cos_sin(float* cos_sin, int row, int half_
 // Everything a branch-decode step needs before its forward pass, in one launch: the row descriptors and rotary tables
 // of step `step`, and the token every row feeds (its cache key at step 0, afterwards the token it drew one step
 // earlier; the forced arrays replace both under teacher forcing).
-__global__ void setup_branch_rows_kernel(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int M, int K, int F,
-                                         int step, int half_dim, float theta, int32_t* step_tokens, const int32_t* keys,
+__global__ void setup_branch_rows_kernel(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int M, int K,
+                                         FanTable fan, int step, int half_dim, float theta, int32_t* step_tokens, const int32_t* keys,
                                          const int32_t* cache_tokens, const int32_t* forced_keys,
                                          const int32_t* forced_tokens) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= M * half_dim) return;
   int m = idx / half_dim, i = idx % half_dim;
-  int b = m / ((K + 1) * F);
-  int k = (m / F) % (K + 1);
+  const int per_seq = fan.off[K + 1];
+  int b = m / per_seq, within = m - b * per_seq;
+  int k = 0;
+  while (k < K && within >= fan.off[k + 1]) ++k;
   int tl = trunk_len[b];
   int pos = tl + 1 + k + step;
   if (i == 0) {
@@ -178,21 +180,23 @@ __global__ void commit_kernel(int32_t* trunk_len, const int32_t* accept_len, int
   trunk_len[b] += k + 1;
 }
 
-// One thread per sequence: linear scan of the F keys cached for accept length k.
+// One thread per sequence: linear scan of the F_k keys cached for accept length k.
 __global__ void lookup_kernel(const int32_t* keys, const int32_t* cache_tokens, const float* cache_logits,
                               const int32_t* accept_len, const int32_t* bonus, uint8_t* hit, int32_t* branch,
-                              int32_t* spec, const float** logits_ptr, int B, int K, int F, int V) {
+                              int32_t* spec, const float** logits_ptr, int B, int K, FanTable fan, int V) {
   int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
   int k = accept_len[b], t = bonus[b], found = -1;
+  int64_t first = 0;
   if (k >= 0 && k <= K) {
-    const int32_t* row = keys + ((int64_t)b * (K + 1) + k) * F;
+    first = (int64_t)b * fan.off[K + 1] + fan.off[k];
+    const int F = fan.off[k + 1] - fan.off[k];
     for (int j = 0; j < F; ++j)
-      if (row[j] == t) { found = j; break; }
+      if (keys[first + j] == t) { found = j; break; }
   }
   hit[b] = found >= 0 ? 1 : 0;
   branch[b] = found;
-  int64_t m = ((int64_t)b * (K + 1) + k) * F + found;
+  int64_t m = first + found;
   for (int i = 0; i < K; ++i) spec[(int64_t)b * K + i] = found >= 0 ? cache_tokens[m * K + i] : -1;
   if (logits_ptr) logits_ptr[b] = found >= 0 ? cache_logits + m * (int64_t)K * V : nullptr;
 }
@@ -218,12 +222,12 @@ inline int grid_for(int64_t n) { return (int)((n + kBlock - 1) / kBlock); }
 
 }  // namespace
 
-int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int K, int F, int step,
+int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int K, const FanTable& fan, int step,
                              int half_dim, float theta, int32_t* step_tokens, const int32_t* keys,
                              const int32_t* cache_tokens, const int32_t* forced_keys, const int32_t* forced_tokens,
                              hipStream_t s) {
-  const int M = B * (K + 1) * F;
-  setup_branch_rows_kernel<<<grid_for((int64_t)M * half_dim), kBlock, 0, s>>>(rows, cos_sin, trunk_len, M, K, F, step,
+  const int M = B * fan.off[K + 1];
+  setup_branch_rows_kernel<<<grid_for((int64_t)M * half_dim), kBlock, 0, s>>>(rows, cos_sin, trunk_len, M, K, fan, step,
                                                                              half_dim, theta, step_tokens, keys,
                                                                              cache_tokens, forced_keys, forced_tokens);
   SSD_HIP(hipGetLastError());
@@ -285,9 +289,9 @@ int launch_commit(int32_t* trunk_len, const int32_t* accept_len, int B, int K, h
 
 int launch_lookup(const int32_t* keys, const int32_t* cache_tokens, const float* cache_logits, const int32_t* accept_len,
                   const int32_t* bonus, uint8_t* hit, int32_t* branch, int32_t* spec, const float** logits_ptr, int B,
-                  int K, int F, int V, hipStream_t s) {
+                  int K, const FanTable& fan, int V, hipStream_t s) {
   lookup_kernel<<<grid_for(B), kBlock, 0, s>>>(keys, cache_tokens, cache_logits, accept_len, bonus, hit, branch, spec,
-                                               logits_ptr, B, K, F, V);
+                                               logits_ptr, B, K, fan, V);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }

@@ -34,13 +34,21 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
 
 // One block per row.  Every thread keeps the best FMAX keys of its strided share in sorted registers; then F
 // rounds of a block-wide maximum over the threads' current heads pick the row's top F in order.
+// groups == 0: every row takes F ids, stored at ids[row][F].  groups == K+1 (the fan-out of a round, Sec. 4.1.1 with
+// the cache shape of Sec. 4.2.2): row (b, k) takes F_k ids, stored at ids[b][off[k] ..].
 template <int FMAX>
 __global__ __launch_bounds__(kSelBlock) void top_f_kernel(const float* __restrict__ logits, int64_t ld,
-                                                          const int32_t* __restrict__ exclude, int V, int F,
-                                                          int32_t* __restrict__ ids) {
+                                                          const int32_t* __restrict__ exclude, int V, int F, int groups,
+                                                          FanTable fan, int32_t* __restrict__ ids) {
   __shared__ uint64_t wave_best[kSelWaves];
   __shared__ uint64_t round_best;
   const int row = blockIdx.x;
+  int32_t* out = ids + (int64_t)row * F;
+  if (groups > 0) {
+    const int b = row / groups, k = row - b * groups;
+    F = fan.off[k + 1] - fan.off[k];
+    out = ids + (int64_t)b * fan.off[groups] + fan.off[k];
+  }
   const float* z = logits + (int64_t)row * ld;
   const int ex = exclude ? exclude[row] : -1;
   uint64_t best[FMAX];
@@ -80,7 +88,7 @@ __global__ __launch_bounds__(kSelBlock) void top_f_kernel(const float* __restric
     if (wave == 0) {
       uint64_t v = lane < kSelWaves ? wave_best[lane] : 0ull;
       v = wave_max_u64(v);
-      if (lane == 0) { round_best = v; ids[(int64_t)row * F + f] = key_id(v); }
+      if (lane == 0) { round_best = v; out[f] = key_id(v); }
     }
     __syncthreads();
     if (best[0] == round_best) {                    // keys are unique: exactly one thread pops
@@ -335,9 +343,23 @@ __global__ __launch_bounds__(kSelBlock) void verify_decide_kernel(const float* _
 int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int32_t* ids,
                  hipStream_t s) {
   if (rows <= 0) return SSD_OK;
-  if (F <= 4) top_f_kernel<4><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, ids);
-  else if (F <= 8) top_f_kernel<8><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, ids);
-  else top_f_kernel<16><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, ids);
+  const FanTable none = {};
+  if (F <= 4) top_f_kernel<4><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, 0, none, ids);
+  else if (F <= 8) top_f_kernel<8><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, 0, none, ids);
+  else top_f_kernel<16><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, 0, none, ids);
+  SSD_HIP(hipGetLastError());
+  return SSD_OK;
+}
+
+int launch_top_f_fan(const float* logits, int64_t ld, const int32_t* exclude, int B, int K, const FanTable& fan, int V,
+                     int32_t* ids, hipStream_t s) {
+  const int rows = B * (K + 1);
+  if (rows <= 0) return SSD_OK;
+  int f_max = 0;
+  for (int k = 0; k <= K; ++k) f_max = fan.off[k + 1] - fan.off[k] > f_max ? fan.off[k + 1] - fan.off[k] : f_max;
+  if (f_max <= 4) top_f_kernel<4><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, 0, K + 1, fan, ids);
+  else if (f_max <= 8) top_f_kernel<8><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, 0, K + 1, fan, ids);
+  else top_f_kernel<16><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, 0, K + 1, fan, ids);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }

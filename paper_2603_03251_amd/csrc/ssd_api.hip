@@ -85,7 +85,9 @@ struct ssd_model {
 
 struct ssd_ctx {
   const ssd_model* model;
-  int B, K, F, max_trunk;
+  int B, K, F, max_trunk;          // F: the largest fan-out of any accept length
+  FanTable fan;                    // cache shape: accept length k owns rows fan.off[k] .. fan.off[k+1]-1 of a sequence
+  int rows_per_seq;                // fan.off[K+1]
   int M;        // branch rows B (K+1) F
   int max_rows; // rows of the largest batched pass
   Arena arena;
@@ -367,7 +369,7 @@ int fused_setup(ssd_ctx* c) {
   A((void**)&p.att, (size_t)L * 2 * MPr * p.qd * 2);
   A((void**)&p.act, (size_t)L * kFusedActPlanes * MPr * p.ffn * 2);
   // attention partials (used only when the trunk is split over several units: more than 2048 visible keys)
-  const int r_max = (c->K + 1) * c->F > c->K + 1 ? (c->K + 1) * c->F : c->K + 1;
+  const int r_max = c->rows_per_seq > c->K + 1 ? c->rows_per_seq : c->K + 1;
   const int qt_max = (r_max * p.G + 15) / 16;
   const int ns_max = (c->max_trunk + 2047) / 2048 + 1;
   c->part_entries = (int64_t)p.B * p.Hkv * ns_max * qt_max * 16;
@@ -401,7 +403,7 @@ int fused_setup(ssd_ctx* c) {
   // branch row).
   std::vector<FusedLayer> host((size_t)L * c->B);
   const size_t kvd = (size_t)d.kv_dim();
-  const size_t branch_rows = (size_t)(c->K + 1) * c->F;
+  const size_t branch_rows = (size_t)c->rows_per_seq;
   for (int l = 0; l < L; ++l) {
     // masked keys still feed the value MFMA with weight 0: everything there must be finite
     SSD_HIP(hipMemset(c->trunk_k[l], 0, (size_t)c->B * kvd * c->vt_stride * 2));
@@ -466,20 +468,31 @@ int ssd_model_destroy(ssd_model* m) {
   return SSD_OK;
 }
 
-int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx** out) {
+}  // extern "C"
+
+// One context for both cache shapes: h_fanout == nullptr is the uniform F of the configuration.
+static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const int32_t* h_fanout, ssd_ctx** out) {
   SSD_CHECK_ARG(model && cfg && out, "ssd_ctx_create: null argument");
   *out = nullptr;
   SSD_CHECK_ARG(cfg->batch >= 1, "batch must be >= 1");
   SSD_CHECK_ARG(cfg->K >= 1 && cfg->K <= SSD_MAX_K, "K must be in 1..%d", SSD_MAX_K);
-  SSD_CHECK_ARG(cfg->F >= 1 && cfg->F <= SSD_MAX_F, "F must be in 1..%d", SSD_MAX_F);
-  SSD_CHECK_ARG(cfg->F + 1 <= model->dims.vocab, "F + 1 must not exceed the vocabulary");
   SSD_CHECK_ARG(cfg->max_trunk >= 2 * cfg->K + 3, "max_trunk must be at least 2K+3");
-  SSD_CHECK_ARG((int64_t)cfg->batch * (cfg->K + 1) * cfg->F <= (1 << 20), "too many branch rows");
+  FanTable fan = {};
+  int f_max = 0;
+  for (int k = 0; k <= cfg->K; ++k) {
+    const int f = h_fanout ? h_fanout[k] : cfg->F;
+    SSD_CHECK_ARG(f >= 1 && f <= SSD_MAX_F, "fan-out %d at accept length %d: must be in 1..%d", f, k, SSD_MAX_F);
+    fan.off[k + 1] = fan.off[k] + f;
+    f_max = f > f_max ? f : f_max;
+  }
+  SSD_CHECK_ARG(f_max + 1 <= model->dims.vocab, "F + 1 must not exceed the vocabulary");
+  SSD_CHECK_ARG((int64_t)cfg->batch * fan.off[cfg->K + 1] <= (1 << 20), "too many branch rows");
   ssd_ctx* c = new (std::nothrow) ssd_ctx();
   if (!c) { set_error("out of host memory"); return SSD_ENOMEM; }
   const Dims& d = model->dims;
-  c->model = model; c->B = cfg->batch; c->K = cfg->K; c->F = cfg->F; c->max_trunk = cfg->max_trunk;
-  c->M = c->B * (c->K + 1) * c->F;
+  c->model = model; c->B = cfg->batch; c->K = cfg->K; c->F = f_max; c->max_trunk = cfg->max_trunk;
+  c->fan = fan; c->rows_per_seq = fan.off[c->K + 1];
+  c->M = c->B * c->rows_per_seq;
   c->max_rows = c->M > c->B * (c->K + 1) ? c->M : c->B * (c->K + 1);
   const size_t es = elem_size(d.dtype);
   const size_t kvd = (size_t)d.kv_dim();
@@ -490,7 +503,7 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   c->trunk_k.resize(d.n_layers); c->trunk_v.resize(d.n_layers);
   c->suffix_k.resize(d.n_layers); c->suffix_v.resize(d.n_layers);
   // the fused pass serves every pass of a context it fits (SSD_FUSED=off|phases|persistent overrides, a debugging aid)
-  c->fused_mode = model->fused_ok && fused_supported(d, (c->K + 1) * c->F) ? 2 : 0;   // rows of one sequence per pass
+  c->fused_mode = model->fused_ok && fused_supported(d, c->rows_per_seq) ? 2 : 0;   // rows of one sequence per pass
   if (c->fused_mode && (16 / (d.n_q_heads / d.n_kv_heads)) * (c->K + 1 <= 8 ? 8 : 16) > 64) c->fused_mode = 0;
   if (const char* env = getenv("SSD_FUSED")) {
     if (!strcmp(env, "off")) c->fused_mode = 0;
@@ -532,6 +545,72 @@ int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx*
   }
   if (st != SSD_OK) { c->arena.release(); delete c; return st; }
   *out = c;
+  return SSD_OK;
+}
+
+extern "C" {
+
+int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx** out) {
+  return ctx_create(model, cfg, nullptr, out);
+}
+
+int ssd_ctx_create_fanout(const ssd_model* model, const ssd_round_config* cfg, const int32_t* h_fanout, ssd_ctx** out) {
+  SSD_CHECK_ARG(h_fanout, "ssd_ctx_create_fanout: null fan-out");
+  return ctx_create(model, cfg, h_fanout, out);
+}
+
+int ssd_ctx_fanout(const ssd_ctx* c, int32_t* h_fanout) {
+  SSD_CHECK_ARG(c && h_fanout, "ssd_ctx_fanout: null argument");
+  for (int k = 0; k <= c->K; ++k) h_fanout[k] = c->fan.off[k + 1] - c->fan.off[k];
+  return SSD_OK;
+}
+
+int ssd_geometric_fanout(int32_t budget, int32_t K, double a, double r, int32_t f_max, int32_t* h_fanout) {
+  SSD_CHECK_ARG(h_fanout, "ssd_geometric_fanout: null output");
+  SSD_CHECK_ARG(K >= 0 && K <= SSD_MAX_K, "K must be in 0..%d", SSD_MAX_K);
+  SSD_CHECK_ARG(a > 0.0 && a < 1.0 && r > 0.0, "acceptance rate in (0,1) and power-law exponent > 0 required");
+  SSD_CHECK_ARG(f_max >= 1 && budget >= K + 1 && (int64_t)budget <= (int64_t)(K + 1) * f_max,
+                "budget %d must lie between K+1 and (K+1) f_max", budget);
+  const int n = K + 1;
+  // the theorem's proportions: a^(k/(1+r)), the last one larger by (1-a)^(-1/(1+r))
+  double w[SSD_MAX_K + 1], x[SSD_MAX_K + 1];
+  const double q = pow(a, 1.0 / (1.0 + r));
+  for (int k = 0; k < n; ++k) w[k] = pow(q, (double)k);
+  w[K] *= pow(1.0 - a, -1.0 / (1.0 + r));
+  // bounds 1..f_max: an accept length the proportions put outside is held at the bound and the others share the rest
+  int state[SSD_MAX_K + 1] = {};   // 0 free, 1 at the lower bound, 2 at the upper
+  for (;;) {
+    double left = budget, wsum = 0.0;
+    for (int k = 0; k < n; ++k) {
+      if (state[k] == 1) left -= 1.0;
+      else if (state[k] == 2) left -= f_max;
+      else wsum += w[k];
+    }
+    bool over = false, under = false;
+    for (int k = 0; k < n; ++k) {
+      x[k] = state[k] == 1 ? 1.0 : state[k] == 2 ? (double)f_max : left * w[k] / wsum;
+      over |= state[k] == 0 && x[k] > f_max;
+      under |= state[k] == 0 && x[k] < 1.0;
+    }
+    if (over) { for (int k = 0; k < n; ++k) if (state[k] == 0 && x[k] > f_max) state[k] = 2; }
+    else if (under) { for (int k = 0; k < n; ++k) if (state[k] == 0 && x[k] < 1.0) state[k] = 1; }
+    else break;
+  }
+  // largest remainders take the units the floors leave over (lower accept length first on ties)
+  int total = 0;
+  double frac[SSD_MAX_K + 1];
+  for (int k = 0; k < n; ++k) {
+    h_fanout[k] = (int32_t)floor(x[k] + 1e-9);
+    frac[k] = x[k] - h_fanout[k];
+    total += h_fanout[k];
+  }
+  for (int spare = budget - total; spare > 0; --spare) {
+    int best = -1;
+    for (int k = 0; k < n; ++k)
+      if (h_fanout[k] < f_max && (best < 0 || frac[k] > frac[best])) best = k;
+    h_fanout[best] += 1;
+    frac[best] = -1.0;
+  }
   return SSD_OK;
 }
 
@@ -620,7 +699,7 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
   }
   hipStream_t s = (hipStream_t)stream;
   const Dims& d = c->model->dims;
-  const int K = c->K, F = c->F, B = c->B, M = c->M, V = d.vocab;
+  const int K = c->K, B = c->B, M = c->M, V = d.vocab, RB = c->rows_per_seq;
   int ev = 0;
   auto mark = [&]() -> int {
     if (c->timing) SSD_HIP(hipEventRecord(c->events[ev++], s));
@@ -632,22 +711,24 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
   SSD_TRY(mark());
   // a1: fan-out
   SSD_TRY(launch_pending_exclude(c->exclude, d_pending, B, K, s));
-  SSD_TRY(launch_top_f(c->glue_logits, V, c->exclude, B * (K + 1), V, F, c->keys, s));
+  SSD_TRY(launch_top_f_fan(c->glue_logits, V, c->exclude, B, K, c->fan, V, c->keys, s));
   SSD_TRY(mark());
   // a2/a3: K batched branch-decode steps; logits and tokens land in the cache directly
   for (int i = 0; i < K; ++i) {
-    SSD_TRY(launch_setup_branch_rows(c->rows, c->cos_sin, c->trunk_len, B, K, F, i, d.head_dim / 2, d.rope_theta, c->step_tokens,
+    SSD_TRY(launch_setup_branch_rows(c->rows, c->cos_sin, c->trunk_len, B, K, c->fan, i, d.head_dim / 2, d.rope_theta, c->step_tokens,
                                      c->keys, c->tokens, c->forced_keys, c->forced_tokens, s));
-    SSD_TRY(forward_rows(c, M, c->step_tokens, (K + 1) * F, c->trunk_ub + K + 1, i, c->logits + (size_t)i * V, (int64_t)K * V,
+    SSD_TRY(forward_rows(c, M, c->step_tokens, RB, c->trunk_ub + K + 1, i, c->logits + (size_t)i * V, (int64_t)K * V,
                          c->hidden + (size_t)i * d.d_model, (int64_t)K * d.d_model, s));
     if (c->saguaro_c < 1.0f) {
       // sigma_{F,C}: lower the step's own top-F logits before the draw; the cache keeps the lowered logits, the
-      // distribution the tokens are drawn from
+      // distribution the tokens are drawn from.  The token of depth i is the one whose rejection ends the next round
+      // at accept length i, where the cache holds F_i candidates.
+      const int F = c->fan.off[i + 1] - c->fan.off[i];
       SSD_TRY(launch_top_f(c->logits + (size_t)i * V, (int64_t)K * V, nullptr, M, V, F, c->sigma_ids, s));
-      SSD_TRY(launch_sigma_shift(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, (K + 1) * F, M, F, c->sigma_ids,
+      SSD_TRY(launch_sigma_shift(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, RB, M, F, c->sigma_ids,
                                  c->saguaro_c > 0.f ? logf(c->saguaro_c) : -INFINITY, s));
     }
-    SSD_TRY(launch_sample(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, (K + 1) * F, M, V, round_seed, 0, i,
+    SSD_TRY(launch_sample(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, RB, M, V, round_seed, 0, i,
                           c->tokens + i, K, c->sample_scratch, s));
     SSD_TRY(mark());
   }
@@ -660,7 +741,7 @@ int ssd_cache_lookup(ssd_ctx* c, const int32_t* d_accept_len, const int32_t* d_b
   SSD_CHECK_ARG(c && d_accept_len && d_bonus && d_hit && d_branch && d_spec_tokens, "ssd_cache_lookup: null argument");
   if (!c->have_cache) { set_error("ssd_cache_lookup before any ssd_prespeculate"); return SSD_ESTATE; }
   return launch_lookup(c->keys, c->tokens, c->logits, d_accept_len, d_bonus, d_hit, d_branch, d_spec_tokens, d_logits_ptr,
-                       c->B, c->K, c->F, c->model->dims.vocab, (hipStream_t)stream);
+                       c->B, c->K, c->fan, c->model->dims.vocab, (hipStream_t)stream);
 }
 
 int ssd_ctx_commit(ssd_ctx* c, const int32_t* d_accept_len, void* stream) {

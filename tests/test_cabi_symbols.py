@@ -34,3 +34,26 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert b.lib.ssd_ctx_create(None, None, None) == b.SSD_EINVAL
     assert b.lib.ssd_verify_workspace_bytes(0, 3) == 0
     assert b.lib.ssd_verify_workspace_bytes(2, 5) > 0
+
+
+def test_geometric_cache_shape_equals_the_oracles_integer_shape():
+    """Sec. 4.2.2 theorem: the library's host-side calculator against the oracle over a grid, and its argument checks."""
+    from oracle import ssd_oracle as O
+    from paper_2603_03251_amd import binding as b
+    n = 0
+    for K in (1, 3, 5, 7):
+        for a in (0.3, 0.5, 0.7, 0.8, 0.9):
+            for r in (0.3, 0.5, 1.0):
+                for budget in (K + 1, 2 * (K + 1) + 1, 4 * (K + 1), 6 * (K + 1) - 1, 8 * (K + 1)):
+                    for f_max in (8, 16):
+                        if budget > (K + 1) * f_max:
+                            continue
+                        got = b.ssd_geometric_fanout(budget, K, a, r, f_max)
+                        assert got == O.geometric_fan_out(budget, K, a, r, f_max).tolist(), (K, a, r, budget, f_max)
+                        n += 1
+    assert n > 400
+    import pytest
+    for bad in [(3, 5, 0.8, 0.5, 16), (200, 5, 0.8, 0.5, 16), (24, 5, 1.0, 0.5, 16), (24, 5, 0.8, 0.0, 16)]:
+        with pytest.raises(b.SsdError) as e:
+            b.ssd_geometric_fanout(*bad)
+        assert e.value.status == b.SSD_EINVAL

@@ -116,3 +116,64 @@ def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows):
         assert toks.min() >= 0 and toks.max() < V
     finally:
         B.ssd_ctx_destroy(ctx)
+
+
+def test_full_size_round_with_the_geometric_cache_shape(B, draft_1b):
+    """The headline workload's 24 branch rows spread over the accept lengths by the theorem of Sec. 4.2.2 (acceptance
+    rate 0.8, power-law exponent 0.5) instead of 4 each: same launch configuration, ragged row order."""
+    shape, model, om = draft_1b
+    wl = I.WORKLOADS["1b_p1024_f4"]
+    r = wl.round
+    K, P, T = r.K, r.prefix, 0.0
+    fan = B.ssd_geometric_fanout((K + 1) * r.F, K, 0.8, 0.5, 16)
+    assert fan == O.geometric_fan_out((K + 1) * r.F, K, 0.8, 0.5, 16).tolist() and sum(fan) == 24 and len(set(fan)) > 2
+    off = np.concatenate([[0], np.cumsum(fan)])
+    rows = [0, int(off[1]) + fan[1] - 1, int(off[K]) + fan[K] - 1]          # first row, last of k=1, last of k=K
+    tol = TOL["bf16"]
+    print(f"[case] 1b_p1024 geometric fan-out {fan}, sampled rows {rows}", flush=True)
+    k, v = I.make_prefix_kv(shape, 1, P, wl.seed)
+    ctx = B.ssd_ctx_create_fanout(model, 1, K, fan, P + 2 * K + 2)
+    try:
+        B.ssd_ctx_load_trunk(ctx, kv_to_device(k, "bf16"), kv_to_device(v, "bf16"), P)
+        pending = I.make_pending(shape, 1, K, wl.seed)
+        trunk = oracle_trunk_from_arrays(om, k, v, 0)
+        spec, _ = O.speculate(om, trunk, pending[0, 0], K, 0.0, 0)
+        pending[0, 1:] = spec
+        c = O.prespeculate(om, trunk, pending[0], fan, T, seed=wl.seed, only_rows=rows)
+        print("[oracle] done", flush=True)
+        f_keys = np.concatenate([c.keys[kk, :f] for kk, f in enumerate(fan)])[None]
+        f_toks = np.concatenate([c.tokens[kk, :f] for kk, f in enumerate(fan)])[None]
+        d_keys, d_toks, d_pending = dev_i32(f_keys), dev_i32(f_toks), dev_i32(pending)   # kept alive over the call
+        B.ssd_ctx_set_forced(ctx, d_keys, d_toks)
+        B.ssd_prespeculate(ctx, d_pending, dev_f32(np.zeros(1, np.float32)), wl.seed)
+        B.ssd_ctx_set_forced(ctx, None, None)
+        torch.cuda.synchronize()
+        view = B.ssd_ctx_views(ctx)
+        V, d = shape.vocab, shape.d_model
+        keys = B.device_copy(view.d_keys, (sum(fan),), torch.int32).cpu().numpy()
+        glue = B.device_copy(view.d_glue_logits, (K + 1, V), torch.float32).cpu().numpy()
+        toks = B.device_copy(view.d_tokens, (sum(fan), K), torch.int32).cpu().numpy()
+        assert row_rel_err(glue, c.glue_logits) < tol
+        for kk in range(K + 1):
+            err = np.abs(glue[kk] - c.glue_logits[kk]).max()
+            zz = c.glue_logits[kk].copy()
+            if kk < K:
+                zz[pending[0, kk + 1]] = -np.inf
+                assert pending[0, kk + 1] not in keys[off[kk]:off[kk + 1]]
+            top = np.sort(zz)[::-1][:fan[kk] + 1]
+            if (-np.diff(top)).min() > 2 * err:
+                assert np.array_equal(keys[off[kk]:off[kk + 1]], c.keys[kk, :fan[kk]]), kk
+        for row in rows:
+            kk = int(np.searchsorted(off, row, side="right")) - 1
+            j = row - int(off[kk])
+            lg = B.device_copy(view.d_logits + row * K * V * 4, (K, V), torch.float32).cpu().numpy()
+            hd = B.device_copy(view.d_hidden + row * K * d * 4, (K, d), torch.float32).cpu().numpy()
+            e_l, e_h = row_rel_err(lg, c.logits[kk, j]), row_rel_err(hd, c.hidden[kk, j])
+            print(f"[branch] row {row} = (k {kk}, j {j}): logits rel err {e_l:.3e}, hidden rel err {e_h:.3e}", flush=True)
+            assert e_l < tol and e_h < tol
+            err = np.abs(lg - c.logits[kk, j]).max(axis=-1)
+            ok = c.margins[kk, j] > 2 * err
+            assert np.array_equal(toks[row][ok], c.tokens[kk, j][ok])
+        assert toks.min() >= 0 and toks.max() < V
+    finally:
+        B.ssd_ctx_destroy(ctx)

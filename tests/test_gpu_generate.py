@@ -29,7 +29,10 @@ class Side:
     def __init__(self, B, shape, weights, K, F, max_trunk):
         self.B, self.shape, self.K = B, shape, K
         self.model = B.ssd_model_create(shape, weights)
-        self.ctx = B.ssd_ctx_create(self.model, 1, K, F, max_trunk)
+        if np.ndim(F) == 0:
+            self.ctx = B.ssd_ctx_create(self.model, 1, K, F, max_trunk)
+        else:
+            self.ctx = B.ssd_ctx_create_fanout(self.model, 1, K, [int(f) for f in F], max_trunk)
 
     def close(self):
         self.B.ssd_ctx_destroy(self.ctx)
@@ -142,6 +145,31 @@ def test_identical_draft_has_everything_accepted_and_every_outcome_cached(B):
         assert all(k == K for k in gs["accept_lens"])
         assert gs["hits"] == gs["rounds"]                                   # the bonus token is the draft's own top choice
         assert gs["rounds"] == -(-n_new // (K + 1))
+    finally:
+        target.close()
+        draft.close()
+
+
+def test_greedy_ssd_with_a_geometric_cache_is_lossless_and_decides_like_the_oracle(B):
+    """Sec. 4.2.2: the cache shape changes which outcomes hit, never the text."""
+    wl = I.WORKLOADS["tiny_f32"]
+    shape, K = wl.draft, wl.round.K
+    fan = B.ssd_geometric_fanout((K + 1) * wl.round.F, K, 0.6, 0.5, 8)
+    assert len(set(fan)) > 1
+    n_new, P = 40, 24
+    wt = I.make_weights(shape, 11)
+    wd = I.make_weights(shape, 12, perturb_of=wt, perturb_std=0.002)
+    prompt = I.make_prompt(shape, 1, P, 21)[0]
+    ot, od = O.Model.from_weights(shape, wt), O.Model.from_weights(shape, wd)
+    want = O.ar_generate(ot, prompt, n_new)
+    _, st = O.ssd_generate(ot, od, prompt, n_new, K, fan)
+    target = Side(B, shape, wt, K, 1, P + n_new + 4 * K + 8)
+    draft = Side(B, shape, wd, K, fan, P + n_new + 4 * K + 8)
+    try:
+        got, gs = gpu_ssd_generate(B, target, draft, prompt, n_new, K, fan)
+        print(f"[gpu] fan-out {fan}: rounds {gs['rounds']} hits {gs['hits']} accept lengths {gs['accept_lens']}", flush=True)
+        assert got == want
+        assert gs["accept_lens"] == st.accept_lens and gs["hits"] == st.hits
     finally:
         target.close()
         draft.close()

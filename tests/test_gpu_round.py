@@ -40,12 +40,23 @@ def _key_margin(z, keys_row, exclude):
     return float(gaps.min())
 
 
+def _in_row_order(a, fan):
+    """Oracle cache array [K+1][max F_k]... -> the library's row order [sum F_k]... (accept length by accept length)."""
+    return np.concatenate([a[k, :f] for k, f in enumerate(fan)])
+
+
 def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=0.0):
+    """F: the uniform fan-out, or F_0..F_K (Sec. 4.2.2)."""
     tol = TOL[shape.dtype]
     w = I.make_weights(shape, seed)
     om = O.Model.from_weights(shape, w)
     model = B.ssd_model_create(shape, w)
-    ctx = B.ssd_ctx_create(model, batch, K, F, P + 4 * K + 8)
+    fan = [F] * (K + 1) if np.ndim(F) == 0 else [int(f) for f in F]
+    if np.ndim(F) == 0:
+        ctx = B.ssd_ctx_create(model, batch, K, F, P + 4 * K + 8)
+    else:
+        ctx = B.ssd_ctx_create_fanout(model, batch, K, fan, P + 4 * K + 8)
+    assert B.ssd_ctx_fanout(ctx) == fan
     try:
         if synthetic_kv:
             k, v = I.make_prefix_kv(shape, batch, P, seed)
@@ -60,7 +71,7 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
         for b in range(batch):
             spec, _ = O.speculate(om, trunks[b], pending[b, 0], K, 0.0, 0)
             pending[b, 1:] = spec
-        caches = [O.prespeculate(om, trunks[b], pending[b], F, temperature, seed=seed, row_base=b * (K + 1) * F)
+        caches = [O.prespeculate(om, trunks[b], pending[b], F, temperature, seed=seed, row_base=b * sum(fan))
                   for b in range(batch)]
         temps = dev_f32(np.full(batch, temperature, np.float32))
 
@@ -75,7 +86,7 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
                 ex = int(pending[b, k + 1]) if k < K else None
                 err = np.abs(free["glue_logits"][b, k] - caches[b].glue_logits[k]).max()
                 # an ordering gap wider than twice the largest logit error cannot be flipped by it
-                if _key_margin(caches[b].glue_logits[k], caches[b].keys[k], ex) > 2 * err + 1e-12:
+                if _key_margin(caches[b].glue_logits[k], caches[b].keys[k, :fan[k]], ex) > 2 * err + 1e-12:
                     assert np.array_equal(free["keys"][b, k], caches[b].keys[k]), (b, k)
                     n_keys_checked += 1
                 if k < K:
@@ -83,8 +94,8 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
         assert n_keys_checked > 0
 
         # ---- teacher-forced run: every row consumes the oracle's tokens
-        f_keys = dev_i32(np.stack([c.keys for c in caches]))
-        f_toks = dev_i32(np.stack([c.tokens for c in caches]))
+        f_keys = dev_i32(np.stack([_in_row_order(c.keys, fan) for c in caches]))
+        f_toks = dev_i32(np.stack([_in_row_order(c.tokens, fan) for c in caches]))
         B.ssd_ctx_set_forced(ctx, f_keys, f_toks)
         B.ssd_prespeculate(ctx, dev_i32(pending), temps, seed)
         B.ssd_ctx_set_forced(ctx, None, None)
@@ -96,12 +107,12 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
             worst = max(worst, e_l, e_h)
             assert e_l < tol and e_h < tol, (b, e_l, e_h)
             assert rms_rel_err(forced["logits"][b], caches[b].logits) < tol
-            # sampled tokens agree wherever the decision is not a near-tie at this precision
-            if temperature == 0:
-                err = np.abs(forced["logits"][b] - caches[b].logits).max(axis=-1)
-                decided = caches[b].margins > 2 * err + 1e-12
-                assert decided.any()
-                assert np.array_equal(forced["tokens"][b][decided], caches[b].tokens[decided])
+            # sampled tokens agree wherever the decision is not a near-tie at this precision (at T > 0 the scores are
+            # logits / T + Gumbel noise keyed by the branch's row number)
+            err = np.abs(forced["logits"][b] - caches[b].logits).max(axis=-1)
+            decided = caches[b].margins > 2 * err / (temperature if temperature > 0 else 1.0) + 1e-12
+            assert decided.any()
+            assert np.array_equal(forced["tokens"][b][decided], caches[b].tokens[decided])
         return free, forced, caches, worst
     finally:
         B.ssd_ctx_destroy(ctx)
@@ -186,6 +197,70 @@ def test_fused_pass_phase_by_phase_equals_persistent(B, monkeypatch):
 
 def test_small_bf16_head_dim_128_untied(B):
     _run_round_parity(B, SMALL_BF16_D128, batch=1, P=70, K=2, F=2, seed=9, synthetic_kv=True)
+
+
+def test_small_bf16_geometric_cache_shape(B):
+    """Sec. 4.2.2: a round whose fan-out follows the theorem's geometric shape; the library's integer shape equals the
+    oracle's, the rows run accept length by accept length, and the fused pass serves the 13 rows per sequence."""
+    K = 3
+    fan = B.ssd_geometric_fanout(13, K, 0.7, 0.5, 8)
+    assert fan == O.geometric_fan_out(13, K, 0.7, 0.5, 8).tolist() and len(set(fan)) > 2
+    free, forced, caches, _ = _run_round_parity(B, SMALL_BF16, batch=2, P=203, K=K, F=fan, seed=7, synthetic_kv=True)
+    for k in range(K + 1):
+        assert (free["keys"][:, k, fan[k]:] == -1).all() and (free["keys"][:, k, :fan[k]] >= 0).all()
+
+
+def test_small_bf16_geometric_cache_shape_sampled_per_operator_path(B, monkeypatch):
+    # temperature > 0: the Gumbel noise of a branch is keyed by its row number in the ragged order; kernels launched
+    # one by one instead of the fused pass
+    monkeypatch.setenv("SSD_FUSED", "off")
+    _run_round_parity(B, SMALL_BF16, batch=3, P=77, K=4, F=[6, 1, 3, 2, 9], seed=23, synthetic_kv=False, temperature=0.8)
+
+
+def test_tiny_f32_geometric_cache_shape_lookup(B):
+    """Every cached outcome of a ragged cache is found at its rank and returns its own speculation and logits
+    pointer; the keys a wider cache would have held at that accept length miss."""
+    shape = I.WORKLOADS["tiny_f32"].draft
+    w = I.make_weights(shape, 3)
+    model = B.ssd_model_create(shape, w)
+    K, fan, nb, P = 4, [3, 1, 4, 2, 1], 2, 20
+    R, off = sum(fan), np.concatenate([[0], np.cumsum(fan)])
+    ctx = B.ssd_ctx_create_fanout(model, nb, K, fan, 128)
+    wide = B.ssd_ctx_create(model, nb, K, max(fan), 128)
+    try:
+        prompt = I.make_prompt(shape, nb, P, 5)
+        pending = I.make_pending(shape, nb, K, 5)
+        for c in (ctx, wide):
+            B.ssd_ctx_prefill(c, dev_i32(prompt), [P, P - 3])
+            B.ssd_prespeculate(c, dev_i32(pending), dev_f32(np.zeros(nb)), 0)
+        got = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx, with_logits=False).items()}
+        ref = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(wide, with_logits=False).items()}
+        v = B.ssd_ctx_views(ctx)
+        hit = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+        branch = torch.zeros(nb, dtype=torch.int32, device="cuda")
+        spec = torch.zeros((nb, K), dtype=torch.int32, device="cuda")
+        ptrs = torch.zeros(nb, dtype=torch.int64, device="cuda")
+        for k in range(K + 1):
+            # greedy branches do not depend on their row number: the ragged cache is a sub-cache of the wide one
+            assert np.array_equal(got["keys"][:, k, :fan[k]], ref["keys"][:, k, :fan[k]])
+            assert np.array_equal(got["tokens"][:, k, :fan[k]], ref["tokens"][:, k, :fan[k]])
+            for j in range(max(fan)):
+                probe = [int(ref["keys"][b, k, j]) for b in range(nb)]
+                B.ssd_cache_lookup(ctx, dev_i32([k] * nb), dev_i32(probe), hit, branch, spec, ptrs)
+                torch.cuda.synchronize()
+                want = [O.cache_lookup(got["keys"][b], k, probe[b]) for b in range(nb)]
+                assert want == [j if j < fan[k] else -1] * nb
+                assert list(branch.cpu().numpy()) == want
+                for b in range(nb):
+                    if want[b] >= 0:
+                        assert np.array_equal(spec.cpu().numpy()[b], got["tokens"][b, k, j])
+                        assert int(ptrs[b]) == v.d_logits + (b * R + off[k] + j) * K * shape.vocab * 4
+                    else:
+                        assert int(hit[b]) == 0 and int(ptrs[b]) == 0
+    finally:
+        B.ssd_ctx_destroy(ctx)
+        B.ssd_ctx_destroy(wide)
+        B.ssd_model_destroy(model)
 
 
 def test_lookup_and_commit(B):
