@@ -25,7 +25,9 @@ What each function follows (section / equation / algorithm of the paper):
                                Sec. 4.2.2, Def. "r power-law cache hit rate" and Theorem
                                "Saguaro Cache Shape: Geometric Fan-Out"; closed form of
                                F_0 from its proof in the theory appendix
-  ssd_generate                 Alg. 1 (whole loop, backup speculator = primary, just in time)
+  ssd_generate                 Alg. 1 (whole loop; backup speculator = primary, just in time, or
+                               random tokens: the two ends of the fallback strategy of Sec. 4.4)
+  random_speculation           Sec. 4.4, the implementation's random-token backup speculator
   ar_generate                  ordinary autoregressive decoding (the losslessness reference)
 
 The transformer itself (RMSNorm, rotary embedding with the rotate-half pairing,
@@ -52,6 +54,7 @@ STREAM_ACCEPT = 0      # acceptance uniforms of verification: (seq, position, 0)
 STREAM_BONUS = 1       # Gumbel noise of the bonus token: (seq, position k, token)
 STREAM_DRAFT = 2       # Gumbel noise of branch decoding: (branch row, step, token)
 STREAM_SPEC = 3        # Gumbel noise of just-in-time (non-branch) drafting: (seq, step, token)
+STREAM_BACKUP = 4      # tokens of the random-token backup speculator: (seq, step, 0)
 
 
 # --------------------------------------------------------------------------- draws
@@ -76,15 +79,19 @@ def _mix64_vec(x: np.ndarray) -> np.ndarray:
     return x
 
 
-def draw_u(seed: int, stream: int, a: int, b: int, c) -> np.ndarray:
-    """Uniform draw in the open interval (0,1): (m + 1/2) 2^-23, m = top 23 bits of a
-    four-level hash of (seed, stream, a, b, c).  `c` may be an integer array."""
+def draw_bits(seed: int, stream: int, a: int, b: int, c) -> np.ndarray:
+    """The 64 bits of the four-level hash of (seed, stream, a, b, c).  `c` may be an integer array."""
     h = _mix64(seed ^ ((_GOLD * (stream + 1)) & _MASK64))
     h = _mix64(h + a)
     h = _mix64(h + b)
     with np.errstate(over="ignore"):
-        hc = _mix64_vec(np.uint64(h) + np.asarray(c, dtype=np.uint64))
-    m = (hc >> np.uint64(41)).astype(F64)
+        return _mix64_vec(np.uint64(h) + np.asarray(c, dtype=np.uint64))
+
+
+def draw_u(seed: int, stream: int, a: int, b: int, c) -> np.ndarray:
+    """Uniform draw in the open interval (0,1): (m + 1/2) 2^-23, m = top 23 bits of
+    `draw_bits`."""
+    m = (draw_bits(seed, stream, a, b, c) >> np.uint64(41)).astype(F64)
     return (m + 0.5) * (2.0 ** -23)
 
 
@@ -588,6 +595,16 @@ def speculate(m: Model, trunk: KV, last: int, K: int, T: float, seed: int, seq: 
     return toks, np.array(logs)
 
 
+def random_speculation(seed: int, seq: int, K: int, vocab: int) -> Tuple[List[int], np.ndarray]:
+    """The fast backup speculator of Sec. 4.4: K tokens drawn uniformly from the vocabulary, at
+    no model cost.  Token i is the hash of (seed, backup stream, seq, i, 0) modulo the vocabulary
+    size (all 64 bits, so the draw is uniform to 2^-47).  Returns (tokens, logits): the logits are
+    all zero, i.e. the uniform distribution the tokens were drawn from, which is what lossless
+    verification at temperature > 0 has to be given (Sec. 2.1)."""
+    toks = [int(draw_bits(seed, STREAM_BACKUP, seq, i, 0)) % vocab for i in range(K)]
+    return toks, np.zeros((K, vocab), F64)
+
+
 @dataclass
 class SSDStats:
     rounds: int = 0
@@ -596,11 +613,14 @@ class SSDStats:
     accept_lens: Optional[List[int]] = None
 
 
-def ssd_generate(target: Model, draft: Model, prompt: Sequence[int], n_new: int, K: int, F: int,
-                 T: float = 0.0, seed: int = 0) -> Tuple[List[int], SSDStats]:
+def ssd_generate(target: Model, draft: Model, prompt: Sequence[int], n_new: int, K: int, F,
+                 T: float = 0.0, seed: int = 0, backup: str = "primary") -> Tuple[List[int], SSDStats]:
     """Alg. 1 for one sequence, run sequentially: speculate, then per round
     {verify the pending speculation, pre-speculate for predicted outcomes, look the realised
-    outcome up, fall back to just-in-time drafting with the same draft on a miss}."""
+    outcome up, fall back on a miss}.  The fallback (Sec. 4.4) is just-in-time drafting with the
+    same draft (backup = "primary", the low-batch choice) or K random tokens (backup =
+    "random", the low-latency choice for large batches)."""
+    assert backup in ("primary", "random")
     X = [int(t) for t in prompt]
     n0 = len(X)
     stats = SSDStats(accept_lens=[])
@@ -627,6 +647,8 @@ def ssd_generate(target: Model, draft: Model, prompt: Sequence[int], n_new: int,
         if j >= 0:
             stats.hits += 1
             spec, spec_logits = list(cache.tokens[k, j]), cache.logits[k, j]
-        else:
+        elif backup == "primary":
             spec, spec_logits = speculate(draft, d_trunk, bonus, K, T, rseed)
+        else:
+            spec, spec_logits = random_speculation(rseed, 0, K, draft.vocab)
     return X[n0:n0 + n_new], stats

@@ -214,3 +214,42 @@ def test_verify_zero_probability_token_is_rejected_and_never_bonus():
     for seed in range(50):
         out = O.verify(zt, zd, [4], 1.0, seed)
         assert out.accept_len == 0 and out.bonus != 4
+
+
+# ----------------------------------------------------------------- random-token backup speculator (Sec. 4.4)
+
+def test_random_speculation_is_uniform_reproducible_and_keyed_by_sequence_and_step():
+    V, K = 7, 5
+    counts = np.zeros(V)
+    for seed in range(6000):
+        toks, logits = O.random_speculation(seed, 0, K, V)
+        assert len(toks) == K and all(0 <= t < V for t in toks)
+        assert logits.shape == (K, V) and not logits.any()              # the uniform distribution, as logits
+        counts += np.bincount(toks, minlength=V)
+    n = counts.sum()
+    assert np.all(np.abs(counts / n - 1 / V) < 4.5 * math.sqrt((1 / V) * (1 - 1 / V) / n))
+    # by hand from the generator's definition: token i of sequence b = hash(seed, stream 4, b, i, 0) mod V
+    V = 128256
+    toks, _ = O.random_speculation(99, 3, 4, V)
+    assert toks == [int(O.draw_bits(99, 4, 3, i, 0)) % V for i in range(4)]
+    assert toks == O.random_speculation(99, 3, 4, V)[0]
+    assert toks != O.random_speculation(99, 2, 4, V)[0] and toks != O.random_speculation(98, 3, 4, V)[0]
+    assert len(set(toks)) > 1
+
+
+def test_verifying_random_tokens_against_the_uniform_distribution_is_lossless_monte_carlo():
+    """The random backup's tokens verified with zero draft logits (the uniform q they were drawn from): token 1 of
+    the output follows the target's row 0, and the acceptance frequency is Theorem 1 with q uniform."""
+    g = np.random.default_rng(5)
+    V, T, N = 6, 0.9, 40000
+    zt = g.normal(size=(2, V)) * 1.5
+    p0 = O.softmax_T(zt[0], T)
+    first = np.zeros(V)
+    accepted = 0
+    for n in range(N):
+        toks, zd = O.random_speculation(70000 + n, 0, 1, V)
+        out = O.verify(zt, zd, toks, T, seed=n)
+        first[toks[0] if out.accept_len == 1 else out.bonus] += 1
+        accepted += out.accept_len
+    assert np.all(np.abs(first / N - p0) < 4.5 * np.sqrt(p0 * (1 - p0) / N) + 1e-9)
+    assert abs(accepted / N - O.acceptance_rate(p0, np.full(V, 1 / V))) < 4.5 * math.sqrt(0.25 / N)

@@ -313,3 +313,18 @@ def test_saguaro_sampling_inside_the_round():
         for j in range(F):
             for i in range(K):
                 assert int(zero.tokens[k, j, i]) not in set(int(t) for t in O.top_f_ids(raw0.logits[k, j, i], F))
+
+
+def test_greedy_ssd_with_the_random_token_backup_is_lossless():
+    # Sec. 4.4: after a miss the next speculation is K random tokens; the text is still the target's own
+    shape = I.WORKLOADS["tiny_f32"].draft
+    tw = I.make_weights(shape, 5)
+    target = O.Model.from_weights(shape, tw)
+    draft = O.Model.from_weights(shape, I.make_weights(shape, 55, perturb_of=tw, perturb_std=0.004))
+    prompt = I.make_prompt(shape, 1, 16, 5)[0]
+    n_new = 40
+    got, stats = O.ssd_generate(target, draft, prompt, n_new, K=4, F=2, backup="random")
+    assert got == O.ar_generate(target, prompt, n_new)
+    _, jit = O.ssd_generate(target, draft, prompt, n_new, K=4, F=2, backup="primary")
+    assert 0 < stats.hits < stats.rounds            # misses happened, so random speculations were verified
+    assert stats.rounds >= jit.rounds               # random tokens are (almost) never accepted: more rounds, same text
