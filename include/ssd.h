@@ -207,6 +207,12 @@ int ssd_verify(const float* d_target_logits, const float* d_draft_logits, const 
                int32_t* d_accept_len, int32_t* d_bonus, void* d_workspace, void* stream);
 size_t ssd_verify_workspace_bytes(int32_t B, int32_t K);
 
+/* The low-latency backup speculator of the fallback strategy (Sec. 4.4: after a cache miss at large batch the
+ * next speculation is K random tokens).  out d_tokens int32 [B][K]: token i of sequence b is the 64-bit hash
+ * (seed, stream 4, b, i, 0) of the library's counter-based generator modulo V, uniform over the vocabulary.  Their
+ * verification at temperature > 0 takes the uniform distribution as the draft's, i.e. all-zero draft logits. */
+int ssd_backup_random(uint64_t seed, int32_t B, int32_t K, int32_t V, int32_t* d_tokens, void* stream);
+
 /* The selection kernel on caller-provided logits (Sec. 4.1.1).  d_logits float [rows][V] with row stride
  * `ld` elements; d_exclude int32 [rows] token to skip per row, or -1 (d_exclude may be NULL);
  * out d_ids int32 [rows][F].  EINVAL if F > SSD_MAX_F or F + 1 > V. */

@@ -65,6 +65,7 @@ EXPORTS = {
     "ssd_ctx_create_fanout": (C.c_int, [C.c_void_p, C.POINTER(ssd_round_config), C.POINTER(C.c_int32),
                                         C.POINTER(C.c_void_p)]),
     "ssd_ctx_fanout": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32)]),
+    "ssd_backup_random": (C.c_int, [C.c_uint64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "ssd_geometric_fanout": (C.c_int, [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_int32, C.POINTER(C.c_int32)]),
     "ssd_cache_lookup": (C.c_int, [C.c_void_p] * 8),
     "ssd_ctx_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -250,6 +251,12 @@ def ssd_verify(target_logits, draft_logits, spec_tokens, temperature, seed: int,
     B, K1, V = target_logits.shape
     _check(lib.ssd_verify(_ptr(target_logits), _ptr(draft_logits), _ptr(spec_tokens), _ptr(temperature), B, K1 - 1, V,
                           seed, _ptr(accept_len), _ptr(bonus), _ptr(workspace), _stream(stream)))
+
+
+def ssd_backup_random(seed: int, V: int, tokens: torch.Tensor, stream=None) -> None:
+    nb, K = tokens.shape
+    assert tokens.dtype == torch.int32 and tokens.is_contiguous()
+    _check(lib.ssd_backup_random(seed, nb, K, V, _ptr(tokens), _stream(stream)))
 
 
 def ssd_top_f(logits: torch.Tensor, exclude: Optional[torch.Tensor], F: int, ids: torch.Tensor, stream=None) -> None:

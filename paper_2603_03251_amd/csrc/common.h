@@ -163,6 +163,7 @@ int launch_sample(const float* logits, int64_t ld, const float* temperature, int
 size_t sample_scratch_bytes(int rows);
 int launch_sigma_shift(float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int F,
                        const int32_t* ids, float log_c, hipStream_t s);
+int launch_backup_random(int32_t* tokens, int B, int K, int V, uint64_t seed, hipStream_t s);
 int launch_verify(const float* zt, const float* zd, const int32_t* spec, const float* temperature, int B, int K, int V,
                   uint64_t seed, int32_t* accept_len, int32_t* bonus, void* workspace, hipStream_t s);
 size_t verify_workspace_bytes(int B, int K);

@@ -351,6 +351,22 @@ int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int ro
   return SSD_OK;
 }
 
+// Random-token backup speculator (Sec. 4.4): token i of sequence b is the 64-bit hash of (seed, backup stream, b, i, 0)
+// modulo the vocabulary size.
+__global__ void backup_random_kernel(int32_t* __restrict__ tokens, int B, int K, int V, uint64_t seed) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= B * K) return;
+  const int b = idx / K, i = idx - b * K;
+  tokens[idx] = (int32_t)(mix64(draw_prefix(seed, STREAM_BACKUP, (uint64_t)b, (uint64_t)i)) % (uint64_t)V);
+}
+
+int launch_backup_random(int32_t* tokens, int B, int K, int V, uint64_t seed, hipStream_t s) {
+  if (B * K <= 0) return SSD_OK;
+  backup_random_kernel<<<(B * K + 255) / 256, 256, 0, s>>>(tokens, B, K, V, seed);
+  SSD_HIP(hipGetLastError());
+  return SSD_OK;
+}
+
 int launch_top_f_fan(const float* logits, int64_t ld, const int32_t* exclude, int B, int K, const FanTable& fan, int V,
                      int32_t* ids, hipStream_t s) {
   const int rows = B * (K + 1);

@@ -7,7 +7,7 @@
 
 namespace ssd {
 
-enum { STREAM_ACCEPT = 0, STREAM_BONUS = 1, STREAM_DRAFT = 2 };
+enum { STREAM_ACCEPT = 0, STREAM_BONUS = 1, STREAM_DRAFT = 2, STREAM_BACKUP = 4 };
 
 __host__ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
   x ^= x >> 30;

@@ -862,6 +862,12 @@ int ssd_sample(const float* d_logits, int64_t ld, const float* d_temperature, in
   return launch_sample(d_logits, ld, d_temperature, 1, rows, V, seed, row_base, step, d_out, 1, nullptr, (hipStream_t)stream);
 }
 
+int ssd_backup_random(uint64_t seed, int32_t B, int32_t K, int32_t V, int32_t* d_tokens, void* stream) {
+  SSD_CHECK_ARG(d_tokens, "ssd_backup_random: null argument");
+  SSD_CHECK_ARG(B >= 0 && K >= 0 && V >= 1 && (int64_t)B * K <= (1 << 24), "ssd_backup_random: B, K >= 0, V >= 1 required");
+  return launch_backup_random(d_tokens, B, K, V, seed, (hipStream_t)stream);
+}
+
 int ssd_ctx_views(const ssd_ctx* c, ssd_views* out) {
   SSD_CHECK_ARG(c && out, "ssd_ctx_views: null argument");
   out->d_trunk_len = c->trunk_len; out->d_keys = c->keys; out->d_tokens = c->tokens; out->d_logits = c->logits;

@@ -61,7 +61,7 @@ def jit_speculate(B, draft, last, K, temps):
     return toks
 
 
-def gpu_ssd_generate(B, target, draft, prompt, n_new, K, F):
+def gpu_ssd_generate(B, target, draft, prompt, n_new, K, F, backup="primary", round_seed=lambda rnd: rnd):
     V = target.shape.vocab
     temps = dev_f32(np.zeros(1, np.float32))
     X = [int(t) for t in prompt]
@@ -85,8 +85,8 @@ def gpu_ssd_generate(B, target, draft, prompt, n_new, K, F):
         # the target verifies on one stream while the draft pre-speculates on the other
         zt = torch.empty((1, K + 1, V), dtype=torch.float32, device="cuda")
         B.ssd_ctx_extend(target.ctx, pending, 0, zt, stream=s_target)
-        B.ssd_verify(zt, None, pending[:, 1:].contiguous(), temps, rounds, acc, bonus, ws, stream=s_target)
-        B.ssd_prespeculate(draft.ctx, pending, temps, rounds, stream=s_draft)
+        B.ssd_verify(zt, None, pending[:, 1:].contiguous(), temps, round_seed(rounds), acc, bonus, ws, stream=s_target)
+        B.ssd_prespeculate(draft.ctx, pending, temps, round_seed(rounds), stream=s_draft)
         torch.cuda.synchronize()
         B.ssd_cache_lookup(draft.ctx, acc, bonus, hit, branch, nxt)
         torch.cuda.synchronize()
@@ -99,8 +99,11 @@ def gpu_ssd_generate(B, target, draft, prompt, n_new, K, F):
         if int(hit[0]):
             hits += 1
             spec = [int(x) for x in nxt[0].cpu().numpy()]
-        else:
+        elif backup == "primary":
             spec = jit_speculate(B, draft, t, K, temps)
+        else:
+            B.ssd_backup_random(round_seed(rounds), V, nxt)
+            spec = [int(x) for x in nxt[0].cpu().numpy()]
     return X[n0:n0 + n_new], dict(rounds=rounds, hits=hits, accepted=accepted, accept_lens=accept_lens)
 
 
@@ -170,6 +173,32 @@ def test_greedy_ssd_with_a_geometric_cache_is_lossless_and_decides_like_the_orac
         print(f"[gpu] fan-out {fan}: rounds {gs['rounds']} hits {gs['hits']} accept lengths {gs['accept_lens']}", flush=True)
         assert got == want
         assert gs["accept_lens"] == st.accept_lens and gs["hits"] == st.hits
+    finally:
+        target.close()
+        draft.close()
+
+
+def test_greedy_ssd_with_the_random_token_backup_decides_like_the_oracle(B):
+    """Sec. 4.4: the low-latency backup speculator.  Same random tokens as the oracle's (same generator, same round
+    seeds), so the same accept lengths and hits round by round, and the target's own text."""
+    wl = I.WORKLOADS["tiny_f32"]
+    shape, K, F = wl.draft, wl.round.K, wl.round.F
+    n_new, P = 40, 24
+    wt = I.make_weights(shape, 11)
+    wd = I.make_weights(shape, 12, perturb_of=wt, perturb_std=0.002)
+    prompt = I.make_prompt(shape, 1, P, 21)[0]
+    ot, od = O.Model.from_weights(shape, wt), O.Model.from_weights(shape, wd)
+    want = O.ar_generate(ot, prompt, n_new)
+    _, st = O.ssd_generate(ot, od, prompt, n_new, K, F, seed=0, backup="random")
+    target = Side(B, shape, wt, K, 1, P + 2 * n_new + 4 * K + 8)
+    draft = Side(B, shape, wd, K, F, P + 2 * n_new + 4 * K + 8)
+    try:
+        got, gs = gpu_ssd_generate(B, target, draft, prompt, n_new, K, F, backup="random",
+                                   round_seed=lambda rnd: 1000003 * rnd)          # the oracle's round seeds
+        print(f"[gpu] rounds {gs['rounds']} hits {gs['hits']} accept lengths {gs['accept_lens']}", flush=True)
+        assert got == want
+        assert gs["accept_lens"] == st.accept_lens and gs["hits"] == st.hits
+        assert 0 < gs["hits"] < gs["rounds"]
     finally:
         target.close()
         draft.close()

@@ -146,3 +146,13 @@ def test_verify_identical_models_accept_all(B):
     B.ssd_verify(dev_f32(z), dev_f32(z[:, :K]), dev_i32(spec), dev_f32(temps), 77, k_out, t_out, ws)
     torch.cuda.synchronize()
     assert (k_out.cpu().numpy() == K).all()
+
+
+def test_backup_random_tokens_equal_the_oracles(B):
+    """Sec. 4.4 random-token backup: bit-exact against the oracle's generator, batch of sequences, full vocabulary."""
+    for seed, nb, K, V in [(0, 1, 5, 128256), (12345678901234567, 16, 7, 128256), (7, 3, 15, 97), (1, 5, 1, 1)]:
+        out = torch.full((nb, K), -1, dtype=torch.int32, device="cuda")
+        B.ssd_backup_random(seed, V, out)
+        torch.cuda.synchronize()
+        want = np.array([O.random_speculation(seed, b, K, V)[0] for b in range(nb)], np.int32)
+        assert np.array_equal(out.cpu().numpy(), want), (seed, nb, K, V)
