@@ -215,9 +215,13 @@ int ssd_backup_random(uint64_t seed, int32_t B, int32_t K, int32_t V, int32_t* d
 
 /* The selection kernel on caller-provided logits (Sec. 4.1.1).  d_logits float [rows][V] with row stride
  * `ld` elements; d_exclude int32 [rows] token to skip per row, or -1 (d_exclude may be NULL);
- * out d_ids int32 [rows][F].  EINVAL if F > SSD_MAX_F or F + 1 > V. */
+ * out d_ids int32 [rows][F].  d_workspace: NULL (one workgroup per row), or ssd_top_f_workspace_bytes(rows) of device
+ * memory (8-byte aligned, contents irrelevant, private to the call until `stream` has passed it): few rows of a large
+ * vocabulary are then shared among several workgroups each, with the same result.  EINVAL if F > SSD_MAX_F or
+ * F + 1 > V. */
 int ssd_top_f(const float* d_logits, int64_t ld, const int32_t* d_exclude, int32_t rows, int32_t V, int32_t F,
-              int32_t* d_ids, void* stream);
+              int32_t* d_ids, void* d_workspace, void* stream);
+size_t ssd_top_f_workspace_bytes(int32_t rows);
 
 /* The branch sampler on caller-provided logits: d_out[r] = argmax_t logits[r][t] (T[r] == 0) or
  * argmax_t logits[r][t]/T[r] + g(seed, stream 2, row_base + r, step, t) in fp64.  d_temperature float [rows]. */

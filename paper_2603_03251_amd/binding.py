@@ -72,7 +72,8 @@ EXPORTS = {
     "ssd_verify": (C.c_int, [C.c_void_p] * 4 + [C.c_int32] * 3 + [C.c_uint64] + [C.c_void_p] * 4),
     "ssd_verify_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32]),
     "ssd_top_f": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
-                            C.c_void_p]),
+                            C.c_void_p, C.c_void_p]),
+    "ssd_top_f_workspace_bytes": (C.c_size_t, [C.c_int32]),
     "ssd_sample": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.c_int32,
                              C.c_int32, C.c_void_p, C.c_void_p]),
     "ssd_ctx_extend": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
@@ -259,9 +260,15 @@ def ssd_backup_random(seed: int, V: int, tokens: torch.Tensor, stream=None) -> N
     _check(lib.ssd_backup_random(seed, nb, K, V, _ptr(tokens), _stream(stream)))
 
 
-def ssd_top_f(logits: torch.Tensor, exclude: Optional[torch.Tensor], F: int, ids: torch.Tensor, stream=None) -> None:
+def ssd_top_f_workspace_bytes(rows: int) -> int:
+    return int(lib.ssd_top_f_workspace_bytes(rows))
+
+
+def ssd_top_f(logits: torch.Tensor, exclude: Optional[torch.Tensor], F: int, ids: torch.Tensor,
+              workspace: Optional[torch.Tensor] = None, stream=None) -> None:
     rows, V = logits.shape
-    _check(lib.ssd_top_f(_ptr(logits), V, _ptr(exclude), rows, V, F, _ptr(ids), _stream(stream)))
+    assert workspace is None or workspace.numel() * workspace.element_size() >= ssd_top_f_workspace_bytes(rows)
+    _check(lib.ssd_top_f(_ptr(logits), V, _ptr(exclude), rows, V, F, _ptr(ids), _ptr(workspace), _stream(stream)))
 
 
 def ssd_sample(logits: torch.Tensor, temperature: torch.Tensor, seed: int, row_base: int, step: int,

@@ -153,11 +153,14 @@ int launch_attention(int dtype, const AttnArgs& a, hipStream_t s);
 int64_t attention_partial_floats(int M, int n_q_heads, int head_dim, int max_keys);
 
 // ---------------------------------------------------------------- kernels_select.hip
+// scratch: top_f_scratch_bytes(rows) of device memory lets several blocks share a row (few rows of a large
+// vocabulary would otherwise occupy a handful of compute units); null: one block per row.
 int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int32_t* ids,
-                 hipStream_t s);
+                 void* scratch, hipStream_t s);
 // The fan-out of a round: row (b, k) of logits [B (K+1)] gives its top F_k to ids[b][off[k] ..].
 int launch_top_f_fan(const float* logits, int64_t ld, const int32_t* exclude, int B, int K, const FanTable& fan, int V,
-                     int32_t* ids, hipStream_t s);
+                     int32_t* ids, void* scratch, hipStream_t s);
+size_t top_f_scratch_bytes(int rows);
 int launch_sample(const float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int V,
                   uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, void* scratch, hipStream_t s);
 size_t sample_scratch_bytes(int rows);

@@ -36,19 +36,27 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
 // rounds of a block-wide maximum over the threads' current heads pick the row's top F in order.
 // groups == 0: every row takes F ids, stored at ids[row][F].  groups == K+1 (the fan-out of a round, Sec. 4.1.1 with
 // the cache shape of Sec. 4.2.2): row (b, k) takes F_k ids, stored at ids[b][off[k] ..].
+// gridDim.y > 1: the vocabulary is cut into gridDim.y parts, block (row, part) leaves the sorted keys of its part's
+// top F in part_keys[row][part][FMAX] and top_f_merge_kernel picks the row's top F among them (keys are unique, so
+// the result is the same as that of one block).
+constexpr int kTopFMaxParts = 32;
 template <int FMAX>
 __global__ __launch_bounds__(kSelBlock) void top_f_kernel(const float* __restrict__ logits, int64_t ld,
                                                           const int32_t* __restrict__ exclude, int V, int F, int groups,
-                                                          FanTable fan, int32_t* __restrict__ ids) {
+                                                          FanTable fan, int32_t* __restrict__ ids,
+                                                          uint64_t* __restrict__ part_keys) {
   __shared__ uint64_t wave_best[kSelWaves];
   __shared__ uint64_t round_best;
   const int row = blockIdx.x;
+  const int parts = gridDim.y, part = blockIdx.y;
   int32_t* out = ids + (int64_t)row * F;
   if (groups > 0) {
     const int b = row / groups, k = row - b * groups;
     F = fan.off[k + 1] - fan.off[k];
     out = ids + (int64_t)b * fan.off[groups] + fan.off[k];
   }
+  const int chunk = (V + parts - 1) / parts;
+  const int lo = part * chunk, hi = lo + chunk < V ? lo + chunk : V;
   const float* z = logits + (int64_t)row * ld;
   const int ex = exclude ? exclude[row] : -1;
   uint64_t best[FMAX];
@@ -67,17 +75,17 @@ __global__ __launch_bounds__(kSelBlock) void top_f_kernel(const float* __restric
   };
   // eight loads in flight per thread: one dependent load per iteration would cost a memory latency each
   constexpr int U = 8;
-  for (int t0 = threadIdx.x; t0 < V; t0 += kSelBlock * U) {
+  for (int t0 = lo + threadIdx.x; t0 < hi; t0 += kSelBlock * U) {
     float v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int t = t0 + u * kSelBlock;
-      v[u] = z[t < V ? t : t0];
+      v[u] = z[t < hi ? t : t0];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int t = t0 + u * kSelBlock;
-      if (t < V) offer(v[u], t);
+      if (t < hi) offer(v[u], t);
     }
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -88,7 +96,11 @@ __global__ __launch_bounds__(kSelBlock) void top_f_kernel(const float* __restric
     if (wave == 0) {
       uint64_t v = lane < kSelWaves ? wave_best[lane] : 0ull;
       v = wave_max_u64(v);
-      if (lane == 0) { round_best = v; out[f] = key_id(v); }
+      if (lane == 0) {
+        round_best = v;
+        if (parts == 1) out[f] = key_id(v);
+        else part_keys[((int64_t)row * parts + part) * FMAX + f] = v;     // 0 when the part ran out of tokens
+      }
     }
     __syncthreads();
     if (best[0] == round_best) {                    // keys are unique: exactly one thread pops
@@ -96,6 +108,36 @@ __global__ __launch_bounds__(kSelBlock) void top_f_kernel(const float* __restric
       for (int i = 0; i < FMAX - 1; ++i) best[i] = best[i + 1];
       best[FMAX - 1] = 0ull;
     }
+  }
+}
+
+// One wavefront per row: the top F of the parts' candidates.  Keys are unique and positive, 0 marks "none".
+template <int FMAX>
+__global__ __launch_bounds__(64) void top_f_merge_kernel(const uint64_t* __restrict__ part_keys, int parts, int F, int groups,
+                                                          FanTable fan, int32_t* __restrict__ ids) {
+  const int row = blockIdx.x, lane = threadIdx.x;
+  int32_t* out = ids + (int64_t)row * F;
+  if (groups > 0) {
+    const int b = row / groups, k = row - b * groups;
+    F = fan.off[k + 1] - fan.off[k];
+    out = ids + (int64_t)b * fan.off[groups] + fan.off[k];
+  }
+  constexpr int PER = kTopFMaxParts * FMAX / 64;      // candidates per lane
+  uint64_t mine[PER];
+  const int n = parts * F;                            // part p holds its F best at [p][0..F-1]
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = lane + 64 * i;
+    mine[i] = c < n ? part_keys[((int64_t)row * parts + c / F) * FMAX + c % F] : 0ull;
+  }
+  uint64_t prev = ~0ull;
+  for (int f = 0; f < F; ++f) {
+    uint64_t best = 0ull;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) best = mine[i] < prev && mine[i] > best ? mine[i] : best;
+    best = wave_max_u64(best);
+    if (lane == 0) out[f] = key_id(best);
+    prev = best;
   }
 }
 
@@ -340,15 +382,38 @@ __global__ __launch_bounds__(kSelBlock) void verify_decide_kernel(const float* _
 
 }  // namespace
 
-int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int32_t* ids,
-                 hipStream_t s) {
-  if (rows <= 0) return SSD_OK;
-  const FanTable none = {};
-  if (F <= 4) top_f_kernel<4><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, 0, none, ids);
-  else if (F <= 8) top_f_kernel<8><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, 0, none, ids);
-  else top_f_kernel<16><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, F, 0, none, ids);
+namespace {
+
+// Parts per row: enough blocks to occupy the chip when there are few rows, at least 4096 tokens per part.
+int top_f_parts(int rows, int V, const void* scratch) {
+  if (!scratch) return 1;
+  int parts = 512 / rows;
+  parts = parts > kTopFMaxParts ? kTopFMaxParts : parts;
+  while (parts > 1 && V / parts < 4096) --parts;
+  return parts < 1 ? 1 : parts;
+}
+
+template <int FMAX>
+int run_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int groups, const FanTable& fan,
+              int32_t* ids, void* scratch, hipStream_t s) {
+  const int parts = top_f_parts(rows, V, scratch);
+  top_f_kernel<FMAX><<<dim3(rows, parts), kSelBlock, 0, s>>>(logits, ld, exclude, V, F, groups, fan, ids, (uint64_t*)scratch);
+  if (parts > 1) top_f_merge_kernel<FMAX><<<rows, 64, 0, s>>>((const uint64_t*)scratch, parts, F, groups, fan, ids);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
+}
+
+}  // namespace
+
+size_t top_f_scratch_bytes(int rows) { return (size_t)rows * kTopFMaxParts * SSD_MAX_F * sizeof(uint64_t); }
+
+int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int rows, int V, int F, int32_t* ids,
+                 void* scratch, hipStream_t s) {
+  if (rows <= 0) return SSD_OK;
+  const FanTable none = {};
+  if (F <= 4) return run_top_f<4>(logits, ld, exclude, rows, V, F, 0, none, ids, scratch, s);
+  if (F <= 8) return run_top_f<8>(logits, ld, exclude, rows, V, F, 0, none, ids, scratch, s);
+  return run_top_f<16>(logits, ld, exclude, rows, V, F, 0, none, ids, scratch, s);
 }
 
 // Random-token backup speculator (Sec. 4.4): token i of sequence b is the 64-bit hash of (seed, backup stream, b, i, 0)
@@ -368,16 +433,14 @@ int launch_backup_random(int32_t* tokens, int B, int K, int V, uint64_t seed, hi
 }
 
 int launch_top_f_fan(const float* logits, int64_t ld, const int32_t* exclude, int B, int K, const FanTable& fan, int V,
-                     int32_t* ids, hipStream_t s) {
+                     int32_t* ids, void* scratch, hipStream_t s) {
   const int rows = B * (K + 1);
   if (rows <= 0) return SSD_OK;
   int f_max = 0;
   for (int k = 0; k <= K; ++k) f_max = fan.off[k + 1] - fan.off[k] > f_max ? fan.off[k + 1] - fan.off[k] : f_max;
-  if (f_max <= 4) top_f_kernel<4><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, 0, K + 1, fan, ids);
-  else if (f_max <= 8) top_f_kernel<8><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, 0, K + 1, fan, ids);
-  else top_f_kernel<16><<<rows, kSelBlock, 0, s>>>(logits, ld, exclude, V, 0, K + 1, fan, ids);
-  SSD_HIP(hipGetLastError());
-  return SSD_OK;
+  if (f_max <= 4) return run_top_f<4>(logits, ld, exclude, rows, V, 0, K + 1, fan, ids, scratch, s);
+  if (f_max <= 8) return run_top_f<8>(logits, ld, exclude, rows, V, 0, K + 1, fan, ids, scratch, s);
+  return run_top_f<16>(logits, ld, exclude, rows, V, 0, K + 1, fan, ids, scratch, s);
 }
 
 // Saguaro sampling scheme sigma_{F,C} (Sec. 4.3) on rows of logits, in place: the F tokens in ids[row] (the row's own

@@ -118,6 +118,7 @@ struct ssd_ctx {
   void* act;
   float* attn_partial;
   void* sample_scratch = nullptr;   // per-row partial winners of the multi-block sampler
+  void* top_f_scratch = nullptr;    // per-row, per-part candidates of the multi-block top-F
   float saguaro_c = 1.0f;           // downweighting constant of the sampling scheme sigma_{F,C}; 1 = off
   int32_t* sigma_ids = nullptr;     // [M][F] top-F of the current step's logits (saguaro_c < 1 only)
   int64_t attn_partial_floats = 0;
@@ -537,6 +538,7 @@ static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const
   c->attn_partial_floats = attention_partial_floats(R, d.n_q_heads, d.head_dim, c->max_trunk + c->K);
   A((void**)&c->attn_partial, (size_t)c->attn_partial_floats * sizeof(float));
   A(&c->sample_scratch, sample_scratch_bytes(c->M));
+  A(&c->top_f_scratch, top_f_scratch_bytes(R));
   A((void**)&c->sigma_ids, sizeof(int32_t) * (size_t)c->M * c->F);
   if (st == SSD_OK && c->fused_mode) st = fused_setup(c);
   if (st == SSD_OK) {
@@ -711,7 +713,7 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
   SSD_TRY(mark());
   // a1: fan-out
   SSD_TRY(launch_pending_exclude(c->exclude, d_pending, B, K, s));
-  SSD_TRY(launch_top_f_fan(c->glue_logits, V, c->exclude, B, K, c->fan, V, c->keys, s));
+  SSD_TRY(launch_top_f_fan(c->glue_logits, V, c->exclude, B, K, c->fan, V, c->keys, c->top_f_scratch, s));
   SSD_TRY(mark());
   // a2/a3: K batched branch-decode steps; logits and tokens land in the cache directly
   for (int i = 0; i < K; ++i) {
@@ -724,7 +726,7 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
       // distribution the tokens are drawn from.  The token of depth i is the one whose rejection ends the next round
       // at accept length i, where the cache holds F_i candidates.
       const int F = c->fan.off[i + 1] - c->fan.off[i];
-      SSD_TRY(launch_top_f(c->logits + (size_t)i * V, (int64_t)K * V, nullptr, M, V, F, c->sigma_ids, s));
+      SSD_TRY(launch_top_f(c->logits + (size_t)i * V, (int64_t)K * V, nullptr, M, V, F, c->sigma_ids, c->top_f_scratch, s));
       SSD_TRY(launch_sigma_shift(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, RB, M, F, c->sigma_ids,
                                  c->saguaro_c > 0.f ? logf(c->saguaro_c) : -INFINITY, s));
     }
@@ -847,12 +849,14 @@ int ssd_verify(const float* d_target_logits, const float* d_draft_logits, const 
                        d_workspace, (hipStream_t)stream);
 }
 
+size_t ssd_top_f_workspace_bytes(int32_t rows) { return rows > 0 ? top_f_scratch_bytes(rows) : 0; }
+
 int ssd_top_f(const float* d_logits, int64_t ld, const int32_t* d_exclude, int32_t rows, int32_t V, int32_t F,
-              int32_t* d_ids, void* stream) {
+              int32_t* d_ids, void* d_workspace, void* stream) {
   SSD_CHECK_ARG(d_logits && d_ids, "ssd_top_f: null argument");
   SSD_CHECK_ARG(rows >= 0 && V >= 2 && ld >= V, "ssd_top_f: rows >= 0, V >= 2, ld >= V required");
   SSD_CHECK_ARG(F >= 1 && F <= SSD_MAX_F && F + 1 <= V, "ssd_top_f: F must be in 1..%d and F + 1 <= V", SSD_MAX_F);
-  return launch_top_f(d_logits, ld, d_exclude, rows, V, F, d_ids, (hipStream_t)stream);
+  return launch_top_f(d_logits, ld, d_exclude, rows, V, F, d_ids, d_workspace, (hipStream_t)stream);
 }
 
 int ssd_sample(const float* d_logits, int64_t ld, const float* d_temperature, int32_t rows, int32_t V, uint64_t seed,

@@ -30,7 +30,8 @@ def test_argument_errors_are_reported_without_a_gpu():
     from paper_2603_03251_amd import binding as b
     assert b.lib.ssd_verify(None, None, None, None, 1, 1, 8, 0, None, None, None, None) == b.SSD_EINVAL
     assert b"null" in b.lib.ssd_last_error()
-    assert b.lib.ssd_top_f(None, 8, None, 1, 8, 1, None, None) == b.SSD_EINVAL
+    assert b.lib.ssd_top_f(None, 8, None, 1, 8, 1, None, None, None) == b.SSD_EINVAL
+    assert b.lib.ssd_top_f_workspace_bytes(0) == 0 and b.lib.ssd_top_f_workspace_bytes(6) > 0
     assert b.lib.ssd_ctx_create(None, None, None) == b.SSD_EINVAL
     assert b.lib.ssd_verify_workspace_bytes(0, 3) == 0
     assert b.lib.ssd_verify_workspace_bytes(2, 5) > 0

@@ -19,7 +19,8 @@ def B():
 
 
 @pytest.mark.parametrize("V,rows,F,ties", [(1024, 10, 2, 3), (1000, 7, 5, 40), (128256, 6, 4, 2), (128256, 6, 8, 500),
-                                           (33, 3, 16, 8), (128256, 96, 4, 0)])
+                                           (33, 3, 16, 8), (128256, 96, 4, 0), (128256, 1, 16, 2), (9000, 24, 3, 9),
+                                           (128256, 600, 2, 0)])
 def test_top_f_bit_exact_on_oracle_logits(B, V, rows, F, ties):
     z = I.make_logits(rows, V, seed=V + rows, n_ties=ties)
     g = np.random.default_rng(V)
@@ -33,11 +34,21 @@ def test_top_f_bit_exact_on_oracle_logits(B, V, rows, F, ties):
     B.ssd_top_f(dev_f32(z), dev_i32(exclude), F, ids)
     torch.cuda.synchronize()
     assert np.array_equal(ids.cpu().numpy(), want)
+    # the same with a workspace: several workgroups share a row when the vocabulary is large (the second call finds
+    # the first call's candidates in the workspace and must not be misled by them)
+    ws = torch.full((B.ssd_top_f_workspace_bytes(rows),), 0xff, dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        ids.fill_(-7)
+        B.ssd_top_f(dev_f32(z), dev_i32(exclude), F, ids, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(ids.cpu().numpy(), want)
     # no exclusion list at all
-    B.ssd_top_f(dev_f32(z), None, F, ids)
-    torch.cuda.synchronize()
     want = np.stack([O.top_f_ids(z[r], F) for r in range(rows)])
-    assert np.array_equal(ids.cpu().numpy(), want)
+    for w in (None, ws):
+        ids.fill_(-7)
+        B.ssd_top_f(dev_f32(z), None, F, ids, workspace=w)
+        torch.cuda.synchronize()
+        assert np.array_equal(ids.cpu().numpy(), want)
 
 
 def test_top_f_rejects_bad_sizes(B):
@@ -49,7 +60,7 @@ def test_top_f_rejects_bad_sizes(B):
     with pytest.raises(B.SsdError):
         B.ssd_top_f(z, None, 17, ids)                       # F > SSD_MAX_F
     # zero rows is a no-op
-    assert B.lib.ssd_top_f(z.data_ptr(), 8, None, 0, 8, 2, ids.data_ptr(), None) == B.SSD_OK
+    assert B.lib.ssd_top_f(z.data_ptr(), 8, None, 0, 8, 2, ids.data_ptr(), None, None) == B.SSD_OK
     torch.cuda.synchronize()
 
 
