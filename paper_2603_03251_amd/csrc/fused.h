@@ -76,7 +76,7 @@ struct FusedParams {
   int64_t part_layer_stride;               // in (q-row) entries
   float* logits;   int64_t logits_ld;      // may be null
   float* hidden;   int64_t hidden_ld;      // may be null
-  unsigned* bar;                           // 1024 grid-barrier words, zeroed once; epochs carry over between launches
+  unsigned* bar;                           // 2048 grid-barrier words, zeroed once; epochs carry over between launches
   unsigned* err;                           // set to 1 if a bounded wait expired
   unsigned long long* prof;                // optional [phases][kFusedClockSlots][nwg] real-time-counter ticks, or null
   int nwg;

@@ -131,11 +131,15 @@ union Bf8 {
 };
 
 // ---------------------------------------------------------------------------------------------- grid barrier
-// Two levels: 8 group counters (workgroup g arrives at counter g % 8), the last arrival of a group publishes the
-// epoch in that group's flag, every workgroup polls the 8 flags.  Relaxed agent-scope atomics only: data written
+// Two levels: kBarGroups group counters (workgroup g arrives at counter g % kBarGroups), the last arrival of a group
+// publishes the epoch in that group's flag, every workgroup polls all the flags.  Relaxed agent-scope atomics only: data written
 // before the arrival went out with write-through stores and s_waitcnt 0.  Every wait is bounded; on expiry the
 // error word is set and the workgroup leaves the kernel.
-constexpr int kBarEpochWord = 600;   // barrier words: 8 group counters at 64 g, 8 flags at 512 + g, the epoch here
+constexpr int kBarGroups = 2;        // a power of two that divides the grid; measured per layer of the 1B shape:
+                                     // 1 group 51.7 us, 2 50.5, 4 50.9, 8 51.3, 16 52.2, 32 53.8 (more flags to poll
+                                     // against fewer arrivals queueing at one counter)
+constexpr int kBarFlags = 1024;      // barrier words: group counters at 32 g (a cache line each), flags at 1024 + g,
+constexpr int kBarEpochWord = 1100;  // the epoch here
 struct Grid {
   unsigned* bar;
   unsigned* err;
@@ -151,18 +155,18 @@ __device__ __forceinline__ void grid_arrive(Grid& g) {
   wg_barrier();
   ++g.epoch;
   if (threadIdx.x == 0) {
-    unsigned grp = blockIdx.x & 7u, per = (unsigned)g.nwg >> 3;
-    unsigned old = __hip_atomic_fetch_add(g.bar + 64 * grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned grp = blockIdx.x & (unsigned)(kBarGroups - 1), per = (unsigned)g.nwg / kBarGroups;
+    unsigned old = __hip_atomic_fetch_add(g.bar + 32 * grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1 == g.epoch * per)
-      __hip_atomic_store(g.bar + 512 + grp, g.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(g.bar + kBarFlags + grp, g.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
 __device__ __forceinline__ bool grid_wait(Grid& g) {
   if (!g.persistent) return true;
-  if (threadIdx.x < 8) {
+  if (threadIdx.x < kBarGroups) {
     unsigned spins = 0;
-    while (__hip_atomic_load(g.bar + 512 + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < g.epoch) {
+    while (__hip_atomic_load(g.bar + kBarFlags + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < g.epoch) {
       if (++spins > kSpinLimit) {
         __hip_atomic_store(g.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         *g.dead = 1;

@@ -385,7 +385,7 @@ int fused_setup(ssd_ctx* c) {
                            std::make_pair(&m->fused_layers[l].down, kAtDown)})
       if (ga.first->KS > 1 && (int64_t)ga.first->n_units * ga.second > fix_tiles) fix_tiles = (int64_t)ga.first->n_units * ga.second;
   p.fix_stride = fix_tiles * (kFusedMaxRows / 16) * 256;   // x row tiles x 256 floats
-  c->fused_sync_words = 1024;
+  c->fused_sync_words = 2048;
   A((void**)&p.fix_buf, (size_t)L * 3 * p.fix_stride * 4);
   A((void**)&c->fused_bar, (size_t)(c->fused_sync_words + 64) * 4);
   A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L * c->B);
