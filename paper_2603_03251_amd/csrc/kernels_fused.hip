@@ -172,7 +172,8 @@ __device__ __forceinline__ bool grid_wait(Grid& g) {
         *g.dead = 1;
         break;
       }
-      __builtin_amdgcn_s_sleep(1);   // idle workgroups must not flood the memory fabric with polls
+      // no pause between polls: each one already takes a memory round trip, and only kBarGroups lanes of a
+      // workgroup poll (measured: 0.3 us per layer faster than with a 64-cycle sleep; several polls in flight: no gain)
     }
   }
   wg_barrier();
