@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_STREAM_READ_GBS = 7100.0     # register-ring streaming read of 2 GiB, 256 workgroups x 8 wavefronts
 # HBM bytes per launch of the fused decode kernel from the rocprofv3 counter runs summarised in
 # profiles/fused_decode_kernel_1b_p1024_f4_hbm_traffic.txt (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)
-MEASURED_TRAFFIC_BYTES = 2781659285
+MEASURED_TRAFFIC_BYTES = 2781731406
 WORKLOAD = "1b_p1024_f4"
 WEIGHT_SEED = 2025
 
