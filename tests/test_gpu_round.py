@@ -45,8 +45,9 @@ def _in_row_order(a, fan):
     return np.concatenate([a[k, :f] for k, f in enumerate(fan)])
 
 
-def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=0.0):
-    """F: the uniform fan-out, or F_0..F_K (Sec. 4.2.2)."""
+def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=0.0, lens=None):
+    """F: the uniform fan-out, or F_0..F_K (Sec. 4.2.2).  lens: prompt length per sequence (real prefill only;
+    default P for all)."""
     tol = TOL[shape.dtype]
     w = I.make_weights(shape, seed)
     om = O.Model.from_weights(shape, w)
@@ -64,8 +65,9 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
             trunks = [oracle_trunk_from_arrays(om, k, v, b) for b in range(batch)]
         else:
             prompt = I.make_prompt(shape, batch, P, seed)
-            B.ssd_ctx_prefill(ctx, dev_i32(prompt), [P] * batch)
-            trunks = [O.prefill(om, prompt[b])[1] for b in range(batch)]
+            lens = [P] * batch if lens is None else list(lens)
+            B.ssd_ctx_prefill(ctx, dev_i32(prompt), lens)
+            trunks = [O.prefill(om, prompt[b][:lens[b]])[1] for b in range(batch)]
         pending = I.make_pending(shape, batch, K, seed)
         # make the pending tokens what a greedy draft would have proposed, so that exclusion bites
         for b in range(batch):
@@ -78,7 +80,7 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
         # ---- free run: selection and sampling on the GPU's own logits
         B.ssd_prespeculate(ctx, dev_i32(pending), temps, seed)
         free = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx).items()}
-        assert (free["trunk_len"] == P).all()
+        assert list(free["trunk_len"]) == ([P] * batch if lens is None else lens)
         n_keys_checked = 0
         for b in range(batch):
             assert row_rel_err(free["glue_logits"][b], caches[b].glue_logits) < tol
@@ -193,6 +195,17 @@ def test_fused_pass_phase_by_phase_equals_persistent(B, monkeypatch):
             B.ssd_model_destroy(model)
     for name in ("keys", "tokens", "logits", "hidden", "glue_logits"):
         assert np.array_equal(outs[0][name], outs[1][name]), name
+
+
+def test_small_bf16_ragged_prompt_lengths_in_one_batch(B):
+    # five sequences whose prompts differ in length (one a single token): three fused passes of 2 + 2 + 1 sequences,
+    # every row with its own visible trunk length
+    _run_round_parity(B, SMALL_BF16, batch=5, P=70, K=3, F=2, seed=19, synthetic_kv=False, lens=[70, 33, 1, 64, 17])
+
+
+def test_small_bf16_ragged_prompt_lengths_per_operator_path(B, monkeypatch):
+    monkeypatch.setenv("SSD_FUSED", "off")
+    _run_round_parity(B, SMALL_BF16, batch=3, P=45, K=3, F=2, seed=29, synthetic_kv=False, lens=[45, 2, 31], temperature=0.7)
 
 
 def test_small_bf16_head_dim_128_untied(B):
