@@ -1,26 +1,30 @@
 // The fused decode pass (see fused.h): every phase of the decoder runs on all compute units at once inside one
 // persistent kernel.
 //
-// Linear layers.  A workgroup owns whole output-feature tiles over the full reduction dimension, so no partial
-// sums cross workgroups and the result does not depend on timing.  Its 8 wavefronts split the reduction dimension;
-// each streams its own contiguous run of 1 KiB weight tiles (MFMA 16x16x32 A operands) through a ring of register
-// chunks, several KiB in flight per wavefront, and reads the matching activation tiles (B operands: 16 rows x 32
-// inputs, written by the producing phase as bf16 head/remainder planes in exactly the lane order the MFMA wants).
-// The weight loads of a phase's first chunks are issued BEFORE the workgroup waits at the grid barrier in front of
-// that phase: weights depend on nothing, so HBM keeps streaming while the barrier and the small activation exchange
-// take their latency.
+// Linear layers.  A workgroup owns whole output-feature tiles ("owner computes"): over the full reduction dimension
+// for the qkv, gate/up and LM-head projections, over one of 2 or 4 k-slices of it for the o and down projections,
+// whose slices hand their partial tiles to slice 0 through memory; slice 0 adds them in slice order, so the result
+// does not depend on timing.  The 8 wavefronts of a workgroup split its reduction range; each streams its own
+// contiguous run of 1 KiB weight tiles (MFMA 16x16x32 A operands) and reads the matching activation tiles (B
+// operands: 16 rows x 32 inputs, written by the producing phase as bf16 head/remainder planes in exactly the lane
+// order the MFMA wants).  Two loop shapes: where a workgroup has at most one unit (qkv, o, down) ALL its weight
+// tiles are requested before it waits at the grid barrier in front of the phase; gate/up and the LM head stream
+// weights and activations together through a ring of register chunks whose first chunks go out before the barrier.
+// Weights depend on nothing, so HBM keeps streaming while the barrier and the activation exchange take their latency.
 //
 // RMSNorm is split around the linear layer: the producer of the residual stream writes (h * gain) and the
 // per-feature-tile sums of h^2; the consumer multiplies its accumulators by the row's 1/rms.
 //
 // Attention (App. B: every branch row sees the verified trunk up to its fork point plus its own path).  The trunk
 // keys of one (sequence, KV head) are shared by all rows and all query heads of the group, so they are scored with
-// MFMAs: a unit = (sequence, KV head, group of 8 query tiles, key range); S^T = K Q^T and O^T = V^T P^T keep every
-// query row in a fixed lane, so the probabilities feed the second MFMA without leaving their registers (the two
-// 16-key score tiles take interleaved key rows so that each lane ends up with 8 consecutive keys).  Values are
-// stored transposed in the trunk.  Keys that are private to a row (its own token, its earlier branch tokens, the
-// other tokens of an extend) are a handful and go through one wavefront per (row, head).  A second phase merges
-// the partial softmaxes.  No mask is ever materialised: a row is (visible trunk length, private suffix length).
+// MFMAs: a unit = (sequence, KV head, one 16-row query tile of rows x group heads, key split); S^T = K Q^T and
+// O^T = V^T P^T keep every query row in a fixed lane, so the probabilities feed the second MFMA without leaving their
+// registers (the two 16-key score tiles take interleaved key rows so that each lane ends up with 8 consecutive
+// keys).  Values are stored transposed in the trunk.  The keys computed in this very pass (a branch row's own token
+// and its earlier branch tokens, the other tokens of an extend) are rotated and staged in LDS by the unit and go
+// through the same MFMAs under a per-row visibility test; the unit appends them to the KV store afterwards.  With
+// one key split (up to 2048 visible keys) the unit writes the final output; beyond that a merge phase combines the
+// splits' partial softmaxes.  No mask is ever materialised: a row is (visible trunk length, private suffix length).
 #include <type_traits>
 
 #include "fused.h"
@@ -256,7 +260,7 @@ struct Chunk {
 
 // One linear layer over the workgroup's units.  bsrc: activation planes in B-operand order, `bplane` elements apart.
 // ssq_in: if not null, row scales are computed into r_s after the barrier (SWIGLU and LOGITS need them).
-// AT = 1 serves the qkv, o and down projections (epilogue EPI_QKV / EPI_RESID), AT = 4 the gate/up projection and the
+// AT = 2 serves the qkv, o and down projections (epilogue EPI_QKV / EPI_RESID), AT = 4 the gate/up projection and the
 // LM head (EPI_SWIGLU / EPI_LOGITS).  The epilogue kind is a run-time argument so that each of the two streaming loops
 // exists once in the kernel: its code has to stay resident in the instruction cache across the layers.
 template <int AT, int MT, int NP, int D, bool PRE>
