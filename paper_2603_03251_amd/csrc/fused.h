@@ -104,5 +104,9 @@ bool fused_supported(const Dims& d, int max_rows);
 // persistent = 0: one launch per phase (a debugging aid that needs no co-residency).
 int launch_fused(const FusedParams& p, int first, int last, int persistent, hipStream_t s);
 int fused_grid_size(int* out);
+// Barrier words (kFusedSyncWords of them + the error word behind) as a finished barrier number `epoch0` leaves them;
+// 0 for a new context.  The epoch counts on from launch to launch and wraps after 2^32 barriers.
+constexpr int kFusedSyncWords = 2048;
+int fused_init_barrier(unsigned* bar, unsigned epoch0, int nwg);
 
 }  // namespace ssd

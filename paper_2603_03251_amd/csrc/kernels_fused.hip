@@ -26,6 +26,7 @@
 // one key split (up to 2048 visible keys) the unit writes the final output; beyond that a merge phase combines the
 // splits' partial softmaxes.  No mask is ever materialised: a row is (visible trunk length, private suffix length).
 #include <type_traits>
+#include <vector>
 
 #include "fused.h"
 
@@ -170,7 +171,8 @@ __device__ __forceinline__ bool grid_wait(Grid& g) {
   if (!g.persistent) return true;
   if (threadIdx.x < kBarGroups) {
     unsigned spins = 0;
-    while (__hip_atomic_load(g.bar + kBarFlags + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < g.epoch) {
+    // (compared as a signed difference: the epoch counts on across launches and may wrap)
+    while ((int)(__hip_atomic_load(g.bar + kBarFlags + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - g.epoch) < 0) {
       if (++spins > kSpinLimit) {
         __hip_atomic_store(g.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         *g.dead = 1;
@@ -1245,6 +1247,18 @@ bool fused_supported(const Dims& d, int max_rows) {
   return d.dtype == SSD_BF16 && d.head_dim == 64 && max_rows <= kFusedMaxRows && d.d_model % 512 == 0 &&
          d.q_dim() % 512 == 0 && d.d_ffn % 512 == 0 && d.kv_dim() % 16 == 0 && d.vocab % 16 == 0 &&
          d.n_q_heads % d.n_kv_heads == 0 && 16 % (d.n_q_heads / d.n_kv_heads) == 0;
+}
+
+int fused_init_barrier(unsigned* bar, unsigned epoch0, int nwg) {
+  static_assert(kBarEpochWord < kFusedSyncWords && kBarFlags + kBarGroups <= kFusedSyncWords, "barrier words");
+  std::vector<unsigned> w(kFusedSyncWords + 64, 0u);
+  for (int g = 0; g < kBarGroups; ++g) {
+    w[32 * g] = epoch0 * (unsigned)(nwg / kBarGroups);   // arrivals so far, modulo 2^32 like the counter itself
+    w[kBarFlags + g] = epoch0;
+  }
+  w[kBarEpochWord] = epoch0;
+  SSD_HIP(hipMemcpy(bar, w.data(), w.size() * sizeof(unsigned), hipMemcpyHostToDevice));
+  return SSD_OK;
 }
 
 int fused_grid_size(int* out) {

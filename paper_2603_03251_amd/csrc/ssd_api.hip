@@ -385,7 +385,7 @@ int fused_setup(ssd_ctx* c) {
                            std::make_pair(&m->fused_layers[l].down, kAtDown)})
       if (ga.first->KS > 1 && (int64_t)ga.first->n_units * ga.second > fix_tiles) fix_tiles = (int64_t)ga.first->n_units * ga.second;
   p.fix_stride = fix_tiles * (kFusedMaxRows / 16) * 256;   // x row tiles x 256 floats
-  c->fused_sync_words = 2048;
+  c->fused_sync_words = kFusedSyncWords;
   A((void**)&p.fix_buf, (size_t)L * 3 * p.fix_stride * 4);
   A((void**)&c->fused_bar, (size_t)(c->fused_sync_words + 64) * 4);
   A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L * c->B);
@@ -393,7 +393,11 @@ int fused_setup(ssd_ctx* c) {
   c->fused_err = c->fused_bar + c->fused_sync_words;
   p.bar = c->fused_bar;
   p.err = c->fused_err;
-  SSD_HIP(hipMemset(c->fused_bar, 0, (size_t)(c->fused_sync_words + 64) * 4));
+  {
+    // SSD_FUSED_EPOCH0: start the barrier's epoch count somewhere else than 0 (a test aid: the count wraps after 2^32)
+    const char* env = getenv("SSD_FUSED_EPOCH0");
+    SSD_TRY(fused_init_barrier(c->fused_bar, env ? (unsigned)strtoul(env, nullptr, 0) : 0u, p.nwg));
+  }
   SSD_HIP(hipMemset(p.fix_buf, 0xff, (size_t)L * 3 * p.fix_stride * 4));
   p.deep = 1;   // ring depth of the gate/up and LM-head streaming loops
   for (int l = 0; l < L; ++l)

@@ -208,6 +208,35 @@ def test_small_bf16_ragged_prompt_lengths_per_operator_path(B, monkeypatch):
     _run_round_parity(B, SMALL_BF16, batch=3, P=45, K=3, F=2, seed=29, synthetic_kv=False, lens=[45, 2, 31], temperature=0.7)
 
 
+def test_fused_pass_barrier_epoch_wraps_around(B, monkeypatch):
+    """The grid barrier of the fused pass numbers its barriers on from launch to launch in 32 bits.  A context whose
+    count starts shortly before 2^32 passes the wrap inside its second round and must give bit-identical results."""
+    shape, batch, P, K, F, seed = SMALL_BF16, 2, 40, 3, 2, 5
+    w = I.make_weights(shape, seed)
+    model = B.ssd_model_create(shape, w)
+    k, v = I.make_prefix_kv(shape, batch, P, seed)
+    pending = dev_i32(I.make_pending(shape, batch, K, seed))
+    temps = dev_f32(np.zeros(batch, np.float32))
+    outs = []
+    try:
+        for epoch0 in (0, 2 ** 32 - 40):
+            monkeypatch.setenv("SSD_FUSED_EPOCH0", str(epoch0))
+            ctx = B.ssd_ctx_create(model, batch, K, F, P + 4 * K + 8)
+            try:
+                B.ssd_ctx_load_trunk(ctx, kv_to_device(k, shape.dtype), kv_to_device(v, shape.dtype), P)
+                for rnd in range(3):                       # 4 launches of 11 barriers each per round
+                    B.ssd_prespeculate(ctx, pending, temps, seed)
+                torch.cuda.synchronize()
+                B.ssd_ctx_refresh_bounds(ctx)              # raises if a barrier wait expired
+                outs.append({k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx).items()})
+            finally:
+                B.ssd_ctx_destroy(ctx)
+        for name in ("keys", "tokens", "logits", "hidden"):
+            assert np.array_equal(outs[0][name], outs[1][name]), name
+    finally:
+        B.ssd_model_destroy(model)
+
+
 def test_small_bf16_head_dim_128_untied(B):
     _run_round_parity(B, SMALL_BF16_D128, batch=1, P=70, K=2, F=2, seed=9, synthetic_kv=True)
 
