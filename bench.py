@@ -30,13 +30,14 @@ WORKLOAD = "1b_p1024_f4"
 WEIGHT_SEED = 2025
 
 
-def algorithmic_bytes_per_decode_step(shape, rnd):
+def algorithmic_bytes_per_decode_step(shape, rnd, prefix_lens=None):
     """Bytes one batched branch-decode step must move: every weight once, the shared trunk KV once per
     sequence (not once per branch), the fp32 logits it has to keep, and the branch-private suffix KV."""
     d, f, V, L = shape.d_model, shape.d_ffn, shape.vocab, shape.n_layers
     qd, kvd = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
     weights = (L * ((qd + 2 * kvd) * d + d * qd + 3 * d * f) + V * d) * 2
-    trunk = rnd.batch * L * (rnd.prefix + rnd.K + 1) * 2 * kvd * 2
+    positions = rnd.batch * rnd.prefix if prefix_lens is None else sum(prefix_lens)
+    trunk = L * (positions + rnd.batch * (rnd.K + 1)) * 2 * kvd * 2
     logits = rnd.rows * V * 4
     suffix = rnd.rows * L * rnd.K * 2 * kvd * 2
     return weights + trunk + logits + suffix
@@ -196,6 +197,9 @@ def main():
                     help="default: the workload the headline metric is quoted on; the others print the same kind of line for "
                          "their shape (no CPU baseline, no counter traffic); 70b_verify_1b_draft: the target's verification "
                          "forward beside the draft round")
+    ap.add_argument("--ragged-prefix", action="store_true",
+                    help="give every sequence of the batch its own prefix length (seeded, between a tenth of the workload's "
+                         "prefix and all of it) instead of the same one")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy: the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
@@ -222,7 +226,7 @@ def main():
     import ssd_inputs as I
     from paper_2603_03251_amd import binding as B
 
-    headline = args.workload == WORKLOAD
+    headline = args.workload == WORKLOAD and not args.ragged_prefix
     wl = I.WORKLOADS[args.workload]
     shape, r = wl.draft, wl.round
     K, F, P, nb, V = r.K, r.F, r.prefix, r.batch, shape.vocab
@@ -234,6 +238,10 @@ def main():
     k, v = I.make_prefix_kv(shape, nb, P, wl.seed)
     to_bf16 = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
     B.ssd_ctx_load_trunk(ctx, to_bf16(k), to_bf16(v), P)
+    prefix_lens = None
+    if args.ragged_prefix:
+        prefix_lens = [int(x) for x in np.random.default_rng(wl.seed).integers(P // 10, P + 1, nb)]
+        B.ssd_ctx_truncate_trunk(ctx, prefix_lens)
     pending = dev(I.make_pending(shape, nb, K, wl.seed), np.int32)
     temps = dev(np.full(nb, r.temperature), np.float32)
     pending_spec = pending[:, 1:].contiguous()            # s_1..s_K, what the verifier checks
@@ -283,7 +291,7 @@ def main():
     kernel_ms = float(seg[:, K + 2:].mean()) if fused else step_ms
     if args.phase_clocks and fused:
         print_phase_clocks(B, ctx, one_round, shape)
-    bytes_step = algorithmic_bytes_per_decode_step(shape, r)
+    bytes_step = algorithmic_bytes_per_decode_step(shape, r, prefix_lens)
     achieved = bytes_step / (kernel_ms * 1e-3) / 1e9
 
     tokens_per_round = nb * (K + 1) * F * K
@@ -299,7 +307,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: Llama-3.2-1B-shaped bf16 draft, B={nb}, prefix {P}, K={K}, F={F} "
                                f"({r.rows} branch rows), lookahead {K}, {'greedy' if r.temperature == 0 else 'temperature %g' % r.temperature}"
-                               f"; verify on a second stream; lookup",
+                               f"; verify on a second stream; lookup"
+                               + (f"; prefix lengths {min(prefix_lens)}..{max(prefix_lens)}, mean {sum(prefix_lens) // nb}" if prefix_lens else ""),
                    "branch_rows": r.rows, "tokens_per_round": tokens_per_round},
         "segments_ms": {"glue_extend": float(seg[:, 0].mean()), "fan_out": float(seg[:, 1].mean()),
                         "branch_decode_step": step_ms, "decode_steps_total": float(seg[:, 2:K + 2].sum(axis=1).mean())},

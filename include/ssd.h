@@ -145,6 +145,10 @@ int ssd_ctx_prefill(ssd_ctx* ctx, const int32_t* d_tokens, int32_t stride, const
 /* Trunk := given KV (a synthetic prefix standing in for a prefill).  d_k, d_v:
  * [n_layers][B][len][n_kv_heads][head_dim] in the model dtype; every sequence gets length `len`. */
 int ssd_ctx_load_trunk(ssd_ctx* ctx, const void* d_k, const void* d_v, int32_t len, void* stream);
+/* Trunk of sequence b := its first h_lens[b] positions (1 <= h_lens[b] <= the context's current bound of the trunk
+ * lengths; host int32 [B], read during the call): a batch of different prefix lengths from one loaded or prefilled
+ * block, or a rollback.  EINVAL if a length is out of range.  Synchronises `stream`. */
+int ssd_ctx_truncate_trunk(ssd_ctx* ctx, const int32_t* h_lens, void* stream);
 
 /* ---- hot path --------------------------------------------------------------------------------- */
 

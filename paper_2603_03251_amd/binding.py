@@ -65,6 +65,7 @@ EXPORTS = {
     "ssd_ctx_create_fanout": (C.c_int, [C.c_void_p, C.POINTER(ssd_round_config), C.POINTER(C.c_int32),
                                         C.POINTER(C.c_void_p)]),
     "ssd_ctx_fanout": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32)]),
+    "ssd_ctx_truncate_trunk": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.c_void_p]),
     "ssd_backup_random": (C.c_int, [C.c_uint64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "ssd_geometric_fanout": (C.c_int, [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_int32, C.POINTER(C.c_int32)]),
     "ssd_cache_lookup": (C.c_int, [C.c_void_p] * 8),
@@ -220,6 +221,11 @@ def ssd_ctx_prefill(ctx: int, tokens: torch.Tensor, lens: Sequence[int], stream=
 
 def ssd_ctx_load_trunk(ctx: int, k: torch.Tensor, v: torch.Tensor, length: int, stream=None) -> None:
     _check(lib.ssd_ctx_load_trunk(ctx, _ptr(k), _ptr(v), length, _stream(stream)))
+
+
+def ssd_ctx_truncate_trunk(ctx: int, lens: Sequence[int], stream=None) -> None:
+    h = (C.c_int32 * len(lens))(*[int(x) for x in lens])
+    _check(lib.ssd_ctx_truncate_trunk(ctx, h, _stream(stream)))
 
 
 def ssd_prespeculate(ctx: int, pending: torch.Tensor, temperature: torch.Tensor, round_seed: int, stream=None) -> None:

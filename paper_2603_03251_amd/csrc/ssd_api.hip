@@ -678,6 +678,22 @@ int ssd_ctx_load_trunk(ssd_ctx* c, const void* d_k, const void* d_v, int32_t len
   return SSD_OK;
 }
 
+int ssd_ctx_truncate_trunk(ssd_ctx* c, const int32_t* h_lens, void* stream) {
+  SSD_CHECK_ARG(c && h_lens, "ssd_ctx_truncate_trunk: null argument");
+  int ub = 0;
+  for (int b = 0; b < c->B; ++b) {
+    SSD_CHECK_ARG(h_lens[b] >= 1 && h_lens[b] <= c->trunk_ub, "trunk length %d of sequence %d: must be in 1..%d", h_lens[b], b,
+                  c->trunk_ub);
+    ub = h_lens[b] > ub ? h_lens[b] : ub;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  SSD_HIP(hipMemcpyAsync(c->trunk_len, h_lens, sizeof(int32_t) * c->B, hipMemcpyHostToDevice, s));
+  SSD_HIP(hipStreamSynchronize(s));   // h_lens is caller-owned pageable memory
+  c->trunk_ub = ub;
+  c->have_cache = false;
+  return SSD_OK;
+}
+
 int ssd_ctx_set_forced(ssd_ctx* c, const int32_t* d_keys, const int32_t* d_tokens) {
   SSD_CHECK_ARG(c, "ssd_ctx_set_forced: null context");
   c->forced_keys = d_keys;

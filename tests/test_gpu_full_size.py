@@ -34,12 +34,13 @@ def draft_1b(B):
     B.ssd_model_destroy(model)
 
 
-@pytest.mark.parametrize("name,seqs,rows", [
-    ("1b_p1024_f4", [0], [0, 9, 23]),            # (k=0,j=0), (k=2,j=1), (k=5,j=3)
-    ("1b_p8192_f8_t1", [0], [5, 47]),            # temperature 1.0: Gumbel sampling inside the round
-    ("1b_b16_p2048_f4", [0, 11], [2, 21]),       # 384 branch rows; two of the 16 sequences sampled
+@pytest.mark.parametrize("name,seqs,rows,ragged", [
+    ("1b_p1024_f4", [0], [0, 9, 23], False),            # (k=0,j=0), (k=2,j=1), (k=5,j=3)
+    ("1b_p8192_f8_t1", [0], [5, 47], False),            # temperature 1.0: Gumbel sampling inside the round
+    ("1b_b16_p2048_f4", [0, 11], [2, 21], False),       # 384 branch rows; two of the 16 sequences sampled
+    ("1b_b16_p2048_f4", [3, 12], [7, 20], True),        # the same batch with prefix lengths between 200 and 2048
 ])
-def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows):
+def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows, ragged):
     shape, model, om = draft_1b
     wl = I.WORKLOADS[name]
     r = wl.round
@@ -50,10 +51,16 @@ def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows):
     ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2)
     try:
         B.ssd_ctx_load_trunk(ctx, kv_to_device(k, "bf16"), kv_to_device(v, "bf16"), P)
+        lens = [P] * nb
+        if ragged:
+            lens = [int(x) for x in np.random.default_rng(wl.seed).integers(200, P + 1, nb)]
+            lens[seqs[0]] = 203                                              # a short one among the sampled sequences
+            B.ssd_ctx_truncate_trunk(ctx, lens)
+            print(f"[case] prefix lengths {lens}", flush=True)
         pending = I.make_pending(shape, nb, K, wl.seed)
         caches = {}
         for b in seqs:
-            trunk = oracle_trunk_from_arrays(om, k, v, b)
+            trunk = oracle_trunk_from_arrays(om, k, v, b).slice(lens[b])
             spec, _ = O.speculate(om, trunk, pending[b, 0], K, 0.0, 0)     # a greedy draft's speculation
             pending[b, 1:] = spec
             caches[b] = O.prespeculate(om, trunk, pending[b], F, T, seed=wl.seed, row_base=b * (K + 1) * F,
