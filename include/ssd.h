@@ -204,7 +204,9 @@ int ssd_ctx_commit(ssd_ctx* ctx, const int32_t* d_accept_len, void* stream);
  * the first rejected row (residual distribution), or argmax_t log p_t + g_t at row K, g from stream 1 keyed
  * (seed, b, k, t).  A residual without mass falls back to p.
  *   out: d_accept_len int32 [B], d_bonus int32 [B].
- *   d_workspace: device scratch of ssd_verify_workspace_bytes(B, K) bytes.
+ *   d_workspace: device scratch of ssd_verify_workspace_bytes(B, K) bytes, 16-byte aligned, private to the call until
+ *   `stream` has passed it (every pass over a row of logits is shared among several workgroups, whose partial
+ *   results meet there).
  * EINVAL for B < 1, K < 1 or K > SSD_MAX_K, V < 2, null pointers. */
 int ssd_verify(const float* d_target_logits, const float* d_draft_logits, const int32_t* d_spec_tokens,
                const float* d_temperature, int32_t B, int32_t K, int32_t V, uint64_t seed,

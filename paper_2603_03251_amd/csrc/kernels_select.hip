@@ -261,74 +261,145 @@ struct RowStats {
   int32_t pad;
 };
 
-// Pass 1 of verification: per logit row (K+1 target rows, K draft rows per sequence) the argmax / max and the
-// softmax denominator at the sequence's temperature.
-__global__ __launch_bounds__(kSelBlock) void verify_stats_kernel(const float* __restrict__ zt, const float* __restrict__ zd,
-                                                                 const float* __restrict__ temperature, int K, int V,
-                                                                 RowStats* __restrict__ stats) {
+// ---- lossless verification (Sec. 2.1).  Every pass over a row of logits is shared among `parts` blocks, so that
+// the few rows of one verification occupy the whole chip; partial results meet in the workspace and are merged in a
+// fixed order (the result does not depend on timing).
+constexpr int kVerifyMaxParts = 32;
+struct VerifyWs {
+  RowStats* stats;        // [B (2K+1)]: target rows 0..K, then draft rows 0..K-1 of each sequence
+  ScoreId* part_best;     // [rows][parts]
+  double* part_sum;       // [rows][parts]
+  double* part_mass;      // [B][parts]  residual mass of the bonus position
+  ScoreId* part_bonus;    // [B][parts]
+  int32_t* accept;        // [B]
+};
+__host__ __device__ inline size_t verify_ws_align(size_t x) { return (x + 15) & ~(size_t)15; }
+__host__ inline VerifyWs verify_ws_carve(void* base, int B, int K) {
+  const size_t rows = (size_t)B * (2 * K + 1);
+  char* p = (char*)base;
+  VerifyWs w;
+  w.stats = (RowStats*)p;      p += verify_ws_align(rows * sizeof(RowStats));
+  w.part_best = (ScoreId*)p;   p += verify_ws_align(rows * kVerifyMaxParts * sizeof(ScoreId));
+  w.part_sum = (double*)p;     p += verify_ws_align(rows * kVerifyMaxParts * sizeof(double));
+  w.part_mass = (double*)p;    p += verify_ws_align((size_t)B * kVerifyMaxParts * sizeof(double));
+  w.part_bonus = (ScoreId*)p;  p += verify_ws_align((size_t)B * kVerifyMaxParts * sizeof(ScoreId));
+  w.accept = (int32_t*)p;
+  return w;
+}
+
+// the logit row of workspace row r of sequence b (nullptr: a draft row of a greedy sequence, nothing to do)
+__device__ __forceinline__ const float* verify_row(const float* zt, const float* zd, int b, int r, int K, int V, double T) {
+  if (r <= K) return zt + ((int64_t)b * (K + 1) + r) * V;
+  if (T <= 0.0) return nullptr;
+  return zd + ((int64_t)b * K + (r - K - 1)) * V;
+}
+// this block's share [lo, hi) of a vocabulary of V tokens
+__device__ __forceinline__ void verify_share(int V, int& lo, int& hi) {
+  const int chunk = (V + (int)gridDim.y - 1) / (int)gridDim.y;
+  lo = (int)blockIdx.y * chunk;
+  hi = lo + chunk < V ? lo + chunk : V;
+}
+
+// Pass 1: per logit row and part, the best (logit, token).  grid (B (2K+1), parts).
+__global__ __launch_bounds__(kSelBlock) void verify_max_kernel(const float* __restrict__ zt, const float* __restrict__ zd,
+                                                               const float* __restrict__ temperature, int K, int V,
+                                                               VerifyWs ws) {
   __shared__ ScoreId smem[kSelWaves];
-  __shared__ double dsm[kSelWaves];
   const int b = blockIdx.x / (2 * K + 1), r = blockIdx.x % (2 * K + 1);
   const double T = zd ? (double)temperature[b] : 0.0;   // without draft logits every sequence is greedy
-  const float* z;
-  if (r <= K) z = zt + ((int64_t)b * (K + 1) + r) * V;
-  else {
-    if (T <= 0.0) return;
-    z = zd + ((int64_t)b * K + (r - K - 1)) * V;
-  }
+  const float* z = verify_row(zt, zd, b, r, K, V, T);
+  if (!z) return;
+  int lo, hi;
+  verify_share(V, lo, hi);
   ScoreId best = {-INFINITY, 0x7fffffff};
-  // eight loads in flight per thread in both scans (same visiting order as a plain strided loop)
-  constexpr int U = 8;
-  for (int t0 = threadIdx.x; t0 < V; t0 += kSelBlock * U) {
+  constexpr int U = 8;   // loads in flight per thread
+  for (int t0 = lo + threadIdx.x; t0 < hi; t0 += kSelBlock * U) {
     float v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int t = t0 + u * kSelBlock;
-      v[u] = z[t < V ? t : t0];
+      v[u] = z[t < hi ? t : t0];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int t = t0 + u * kSelBlock;
       ScoreId c = {score_of(v[u]), t};
-      if (t < V && better(c, best)) best = c;
+      if (t < hi && better(c, best)) best = c;
     }
   }
   best = block_argmax(best, smem);
-  double sum = 0.0;
-  if (T > 0.0) {
-    for (int t0 = threadIdx.x; t0 < V; t0 += kSelBlock * U) {
-      float v[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int t = t0 + u * kSelBlock;
-        v[u] = z[t < V ? t : t0];
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (t0 + u * kSelBlock < V) sum += exp((score_of(v[u]) - best.s) / T);
-    }
-    sum = block_sum_f64(sum, dsm);
-  }
-  if (threadIdx.x == 0) {
-    RowStats st;
-    st.max = best.s; st.sum = sum; st.argmax = best.id; st.pad = 0;
-    stats[blockIdx.x] = st;
-  }
+  if (threadIdx.x == 0) ws.part_best[(int64_t)blockIdx.x * gridDim.y + blockIdx.y] = best;
 }
 
-// Pass 2: one block per sequence: sequential acceptance (thread 0), then the bonus token at row k.
-__global__ __launch_bounds__(kSelBlock) void verify_decide_kernel(const float* __restrict__ zt, const float* __restrict__ zd,
+// the row's best over the parts of pass 1 (every thread of the block computes the same)
+__device__ __forceinline__ ScoreId verify_row_best(const VerifyWs& ws, int64_t row, int parts) {
+  ScoreId best = ws.part_best[row * parts];
+  for (int i = 1; i < parts; ++i) {
+    const ScoreId c = ws.part_best[row * parts + i];
+    if (better(c, best)) best = c;
+  }
+  return best;
+}
+
+// Pass 2: per row and part, the partial softmax denominator sum exp((z - max) / T); part 0 also records the row's
+// max and argmax.  grid (B (2K+1), parts).
+__global__ __launch_bounds__(kSelBlock) void verify_sum_kernel(const float* __restrict__ zt, const float* __restrict__ zd,
+                                                               const float* __restrict__ temperature, int K, int V,
+                                                               VerifyWs ws) {
+  __shared__ double dsm[kSelWaves];
+  const int b = blockIdx.x / (2 * K + 1), r = blockIdx.x % (2 * K + 1);
+  const double T = zd ? (double)temperature[b] : 0.0;
+  const float* z = verify_row(zt, zd, b, r, K, V, T);
+  if (!z) return;
+  const ScoreId best = verify_row_best(ws, blockIdx.x, gridDim.y);
+  if (blockIdx.y == 0 && threadIdx.x == 0) {
+    ws.stats[blockIdx.x].max = best.s;
+    ws.stats[blockIdx.x].argmax = best.id;
+    ws.stats[blockIdx.x].pad = 0;
+  }
+  if (T <= 0.0) return;
+  int lo, hi;
+  verify_share(V, lo, hi);
+  double sum = 0.0;
+  constexpr int U = 8;
+  for (int t0 = lo + threadIdx.x; t0 < hi; t0 += kSelBlock * U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * kSelBlock;
+      v[u] = z[t < hi ? t : t0];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (t0 + u * kSelBlock < hi) sum += exp((score_of(v[u]) - best.s) / T);
+  }
+  sum = block_sum_f64(sum, dsm);
+  if (threadIdx.x == 0) ws.part_sum[(int64_t)blockIdx.x * gridDim.y + blockIdx.y] = sum;
+}
+
+// Pass 3: the sequential acceptance (one thread per sequence of work, done by every block of the sequence so that
+// all of them know the bonus position k), then this part's share of the residual mass at position k.  Part 0
+// publishes k, and the bonus token itself if the sequence is greedy.  grid (B, parts).
+__global__ __launch_bounds__(kSelBlock) void verify_accept_kernel(const float* __restrict__ zt, const float* __restrict__ zd,
                                                                   const int32_t* __restrict__ spec,
                                                                   const float* __restrict__ temperature, int K, int V,
-                                                                  uint64_t seed, const RowStats* __restrict__ stats,
-                                                                  int32_t* __restrict__ accept_len,
+                                                                  uint64_t seed, VerifyWs ws, int32_t* __restrict__ accept_len,
                                                                   int32_t* __restrict__ bonus) {
-  __shared__ ScoreId smem[kSelWaves];
   __shared__ double dsm[kSelWaves];
   __shared__ int k_s;
-  const int b = blockIdx.x;
+  const int b = blockIdx.x, parts = gridDim.y;
   const double T = zd ? (double)temperature[b] : 0.0;
-  const RowStats* st = stats + (int64_t)b * (2 * K + 1);
+  RowStats* st = ws.stats + (int64_t)b * (2 * K + 1);
+  // the rows' softmax denominators: the parts' sums in part order (threads 0 .. 2K merge one row each; part 0 keeps them)
+  __shared__ double sums[2 * SSD_MAX_K + 1];
+  if (T > 0.0 && (int)threadIdx.x <= 2 * K) {
+    const int64_t row = (int64_t)b * (2 * K + 1) + threadIdx.x;
+    double sum = 0.0;
+    for (int i = 0; i < parts; ++i) sum += ws.part_sum[row * parts + i];
+    sums[threadIdx.x] = sum;
+    if (blockIdx.y == 0) st[threadIdx.x].sum = sum;
+  }
+  __syncthreads();
   if (threadIdx.x == 0) {
     int k = K;
     for (int i = 0; i < K; ++i) {
@@ -337,8 +408,8 @@ __global__ __launch_bounds__(kSelBlock) void verify_decide_kernel(const float* _
       if (T <= 0.0) ok = st[i].argmax == s;
       else if (s < 0 || s >= V) ok = false;
       else {
-        double p = exp((score_of(zt[((int64_t)b * (K + 1) + i) * V + s]) - st[i].max) / T) / st[i].sum;
-        double q = exp((score_of(zd[((int64_t)b * K + i) * V + s]) - st[K + 1 + i].max) / T) / st[K + 1 + i].sum;
+        double p = exp((score_of(zt[((int64_t)b * (K + 1) + i) * V + s]) - st[i].max) / T) / sums[i];
+        double q = exp((score_of(zd[((int64_t)b * K + i) * V + s]) - st[K + 1 + i].max) / T) / sums[K + 1 + i];
         double u = draw_u(draw_prefix(seed, STREAM_ACCEPT, (uint64_t)b, (uint64_t)i), 0ull);
         ok = u * q < p;
       }
@@ -348,27 +419,52 @@ __global__ __launch_bounds__(kSelBlock) void verify_decide_kernel(const float* _
   }
   __syncthreads();
   const int k = k_s;
-  if (T <= 0.0) {
-    if (threadIdx.x == 0) { accept_len[b] = k; bonus[b] = st[k].argmax; }
-    return;
+  if (blockIdx.y == 0 && threadIdx.x == 0) {
+    ws.accept[b] = k;
+    accept_len[b] = k;
+    if (T <= 0.0) bonus[b] = st[k].argmax;
   }
-  const float* zp = zt + ((int64_t)b * (K + 1) + k) * V;
-  const float* zq = k < K ? zd + ((int64_t)b * K + k) * V : nullptr;
-  const double pmax = st[k].max, psum = st[k].sum;
-  const double qmax = k < K ? st[K + 1 + k].max : 0.0, qsum = k < K ? st[K + 1 + k].sum : 1.0;
-  bool use_residual = false;
-  if (zq) {
-    double mass = 0.0;
-    for (int t = threadIdx.x; t < V; t += kSelBlock) {
+  if (T <= 0.0) return;
+  double mass = 0.0;
+  if (k < K) {
+    const float* zp = zt + ((int64_t)b * (K + 1) + k) * V;
+    const float* zq = zd + ((int64_t)b * K + k) * V;
+    const double pmax = st[k].max, psum = sums[k], qmax = st[K + 1 + k].max, qsum = sums[K + 1 + k];
+    int lo, hi;
+    verify_share(V, lo, hi);
+    for (int t = lo + threadIdx.x; t < hi; t += kSelBlock) {
       double p = exp((score_of(zp[t]) - pmax) / T) / psum;
       double q = exp((score_of(zq[t]) - qmax) / T) / qsum;
       mass += fmax(p - q, 0.0);
     }
-    use_residual = block_sum_f64(mass, dsm) > 0.0;
+    mass = block_sum_f64(mass, dsm);
   }
+  if (threadIdx.x == 0) ws.part_mass[(int64_t)b * parts + blockIdx.y] = mass;
+}
+
+// Pass 4: this part's best Gumbel-max candidate for the bonus token at position k: from the residual max(p - q, 0)
+// if it has mass (k < K), else from p.  grid (B, parts); greedy sequences are done already.
+__global__ __launch_bounds__(kSelBlock) void verify_bonus_kernel(const float* __restrict__ zt, const float* __restrict__ zd,
+                                                                 const float* __restrict__ temperature, int K, int V,
+                                                                 uint64_t seed, VerifyWs ws) {
+  __shared__ ScoreId smem[kSelWaves];
+  const int b = blockIdx.x, parts = gridDim.y;
+  const double T = zd ? (double)temperature[b] : 0.0;
+  if (T <= 0.0) return;
+  const RowStats* st = ws.stats + (int64_t)b * (2 * K + 1);
+  const int k = ws.accept[b];
+  double total = 0.0;
+  for (int i = 0; i < parts; ++i) total += ws.part_mass[(int64_t)b * parts + i];
+  const bool use_residual = k < K && total > 0.0;
+  const float* zp = zt + ((int64_t)b * (K + 1) + k) * V;
+  const float* zq = k < K ? zd + ((int64_t)b * K + k) * V : nullptr;
+  const double pmax = st[k].max, psum = st[k].sum;
+  const double qmax = k < K ? st[K + 1 + k].max : 0.0, qsum = k < K ? st[K + 1 + k].sum : 1.0;
   const uint64_t prefix = draw_prefix(seed, STREAM_BONUS, (uint64_t)b, (uint64_t)k);
+  int lo, hi;
+  verify_share(V, lo, hi);
   ScoreId best = {-INFINITY, 0x7fffffff};
-  for (int t = threadIdx.x; t < V; t += kSelBlock) {
+  for (int t = lo + threadIdx.x; t < hi; t += kSelBlock) {
     double r = exp((score_of(zp[t]) - pmax) / T) / psum;
     if (use_residual) r = fmax(r - exp((score_of(zq[t]) - qmax) / T) / qsum, 0.0);
     ScoreId c;
@@ -377,7 +473,26 @@ __global__ __launch_bounds__(kSelBlock) void verify_decide_kernel(const float* _
     if (better(c, best)) best = c;
   }
   best = block_argmax(best, smem);
-  if (threadIdx.x == 0) { accept_len[b] = k; bonus[b] = best.id; }
+  if (threadIdx.x == 0) ws.part_bonus[(int64_t)b * parts + blockIdx.y] = best;
+}
+
+// Pass 5: the bonus token of every sampled sequence among its parts' candidates.  One wavefront per sequence.
+__global__ __launch_bounds__(64) void verify_bonus_merge_kernel(const float* __restrict__ zd, const float* __restrict__ temperature,
+                                                                int parts, VerifyWs ws, int32_t* __restrict__ bonus) {
+  const int b = blockIdx.x;
+  if (!(zd && temperature[b] > 0.f)) return;
+  ScoreId best = {-INFINITY, 0x7fffffff};
+  for (int i = threadIdx.x; i < parts; i += 64) {
+    const ScoreId c = ws.part_bonus[(int64_t)b * parts + i];
+    if (better(c, best)) best = c;
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    ScoreId t;
+    t.s = __shfl_xor(best.s, o);
+    t.id = __shfl_xor(best.id, o);
+    if (better(t, best)) best = t;
+  }
+  if (threadIdx.x == 0) bonus[b] = best.id;
 }
 
 }  // namespace
@@ -486,16 +601,36 @@ int launch_sample(const float* logits, int64_t ld, const float* temperature, int
   return SSD_OK;
 }
 
-size_t verify_workspace_bytes(int B, int K) { return (size_t)B * (2 * K + 1) * sizeof(RowStats); }
 
 int launch_verify(const float* zt, const float* zd, const int32_t* spec, const float* temperature, int B, int K, int V,
                   uint64_t seed, int32_t* accept_len, int32_t* bonus, void* workspace, hipStream_t s) {
-  RowStats* stats = (RowStats*)workspace;
-  verify_stats_kernel<<<B * (2 * K + 1), kSelBlock, 0, s>>>(zt, zd, temperature, K, V, stats);
-  SSD_HIP(hipGetLastError());
-  verify_decide_kernel<<<B, kSelBlock, 0, s>>>(zt, zd, spec, temperature, K, V, seed, stats, accept_len, bonus);
+  const VerifyWs ws = verify_ws_carve(workspace, B, K);
+  const int rows = B * (2 * K + 1);
+  // enough blocks to occupy the chip, at least 4096 tokens per part
+  int parts = 1024 / rows;
+  parts = parts > kVerifyMaxParts ? kVerifyMaxParts : parts;
+  while (parts > 1 && V / parts < 4096) --parts;
+  parts = parts < 1 ? 1 : parts;
+  int parts_b = 512 / B;
+  parts_b = parts_b > kVerifyMaxParts ? kVerifyMaxParts : parts_b;
+  while (parts_b > 1 && V / parts_b < 4096) --parts_b;
+  parts_b = parts_b < 1 ? 1 : parts_b;
+  verify_max_kernel<<<dim3(rows, parts), kSelBlock, 0, s>>>(zt, zd, temperature, K, V, ws);
+  verify_sum_kernel<<<dim3(rows, parts), kSelBlock, 0, s>>>(zt, zd, temperature, K, V, ws);
+  verify_accept_kernel<<<dim3(B, parts_b), kSelBlock, 0, s>>>(zt, zd, spec, temperature, K, V, seed, ws, accept_len, bonus);
+  if (zd) {   // without draft logits every sequence is greedy and done
+    verify_bonus_kernel<<<dim3(B, parts_b), kSelBlock, 0, s>>>(zt, zd, temperature, K, V, seed, ws);
+    verify_bonus_merge_kernel<<<B, 64, 0, s>>>(zd, temperature, parts_b, ws, bonus);
+  }
   SSD_HIP(hipGetLastError());
   return SSD_OK;
+}
+
+size_t verify_workspace_bytes(int B, int K) {
+  const size_t rows = (size_t)B * (2 * K + 1);
+  return verify_ws_align(rows * sizeof(RowStats)) + verify_ws_align(rows * kVerifyMaxParts * sizeof(ScoreId)) +
+         verify_ws_align(rows * kVerifyMaxParts * sizeof(double)) + verify_ws_align((size_t)B * kVerifyMaxParts * sizeof(double)) +
+         verify_ws_align((size_t)B * kVerifyMaxParts * sizeof(ScoreId)) + verify_ws_align((size_t)B * sizeof(int32_t));
 }
 
 }  // namespace ssd
