@@ -115,14 +115,44 @@ __global__ void rmsnorm_kernel(const float* __restrict__ h, const T* __restrict_
     if (copy_out) copy_out[(int64_t)m * copy_ld + c] = v;
   };
   if (vec) {
+    // four features at a time: one 8-byte gain load, one 8-byte store per bf16 plane (2-byte stores, one per element
+    // and plane, made this kernel several times slower than the memory round trips it consists of)
+    auto put4 = [&](int c, float4 x) {
+      if constexpr (sizeof(T) == 2) {
+        const uint2 gb = *(const uint2*)((const bf16_t*)gain + c);
+        const float g[4] = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
+                            __uint_as_float(gb.y & 0xffff0000u)};
+        const float v[4] = {x.x * scale * g[0], x.y * scale * g[1], x.z * scale * g[2], x.w * scale * g[3]};
+        bf16_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          hi[e] = f32_to_bf16(v[e]);
+          lo[e] = f32_to_bf16(v[e] - bf16_to_f32(hi[e]));
+        }
+        bf16_t* base = (bf16_t*)xn + (int64_t)m * d + c;
+        *(uint2*)base = make_uint2((uint32_t)hi[0] | (uint32_t)hi[1] << 16, (uint32_t)hi[2] | (uint32_t)hi[3] << 16);
+        *(uint2*)(base + xn_plane) = make_uint2((uint32_t)lo[0] | (uint32_t)lo[1] << 16, (uint32_t)lo[2] | (uint32_t)lo[3] << 16);
+        if (copy_out) *(float4*)(copy_out + (int64_t)m * copy_ld + c) = make_float4(v[0], v[1], v[2], v[3]);
+      } else {
+        put(c, x.x);
+        put(c + 1, x.y);
+        put(c + 2, x.z);
+        put(c + 3, x.w);
+      }
+    };
+    const bool aligned = (xn_plane & 3) == 0 && (copy_ld & 3) == 0 && ((uintptr_t)xn & 7) == 0 && ((uintptr_t)gain & 7) == 0 &&
+                         (!copy_out || ((uintptr_t)copy_out & 15) == 0);
 #pragma unroll
     for (int i = 0; i < kHeld; ++i) {
       const int c = threadIdx.x * 4 + i * step;
       if (c < d) {
-        put(c, held[i].x);
-        put(c + 1, held[i].y);
-        put(c + 2, held[i].z);
-        put(c + 3, held[i].w);
+        if (aligned) put4(c, held[i]);
+        else {
+          put(c, held[i].x);
+          put(c + 1, held[i].y);
+          put(c + 2, held[i].z);
+          put(c + 3, held[i].w);
+        }
       }
     }
     for (int c = threadIdx.x + kHeld * step; c < d; c += blockDim.x) put(c, row[c]);
