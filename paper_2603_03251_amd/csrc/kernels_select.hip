@@ -185,7 +185,7 @@ __global__ __launch_bounds__(kSelBlock) void sample_kernel(const float* __restri
                                                            const float* __restrict__ temperature, int rows_per_seq,
                                                            int V, uint64_t seed, int row_base, int step,
                                                            int32_t* __restrict__ out, int64_t out_stride,
-                                                           ScoreId* __restrict__ scratch) {
+                                                           ScoreId* __restrict__ scratch, int exact_scan) {
   __shared__ ScoreId smem[kSelWaves];
   const int row = blockIdx.x, part = blockIdx.y, parts = gridDim.y;
   const float* z = logits + (int64_t)row * ld;
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(kSelBlock) void sample_kernel(const float* __restri
         }
       }
     }
-  } else {
+  } else if (T <= 0.0 || exact_scan) {
     const int t_end = min(V, q_end * 4);
     for (int t = q_begin * 4 + threadIdx.x; t < t_end; t += kSelBlock) {
       ScoreId c;
@@ -228,6 +228,41 @@ __global__ __launch_bounds__(kSelBlock) void sample_kernel(const float* __restri
       c.s = score_of(z[t]);
       if (T > 0.0) c.s = c.s / T + gumbel_from_u(draw_u(prefix, (uint64_t)t));
       if (better(c, best)) best = c;
+    }
+  } else {
+    // Sampled rows.  The decision is the fp64 one (score = z / T + g in double, as specified), but two fp64 logarithms
+    // per token of a 128256-token row cost more than the rest of the sampler together, so the scan runs in fp32 and
+    // only the tokens that can still win are scored in fp64: with |s32 - s64| <= delta for every token near the top,
+    // the fp64 winner t* has s32(t*) >= s64(t*) - delta >= s64(t32) - delta >= max32 - 2 delta.  delta: z / T in
+    // fp32 is within 2^-22 |z / T|; u is exact in fp32 (a 24-bit odd integer times 2^-24); logf is good to 2 ulp, so
+    // g = -log(-log u) (at most 16.7 in magnitude) to 5e-6; near the top |z / T| <= |s| + 17.  The bound used is
+    // twice that.
+    const int t_begin = q_begin * 4, t_end = min(V, q_end * 4);
+    const float inv_t = 1.0f / (float)T;
+    auto s32 = [&](int t) {
+      const float zt = z[t];
+      if (zt != zt) return -INFINITY;
+      const uint64_t m = mix64(prefix + (uint64_t)t) >> 41;
+      const float u = ((float)m + 0.5f) * (1.0f / 8388608.0f);
+      return zt * inv_t - logf(-logf(u));
+    };
+    float mx = -INFINITY;
+    for (int t = t_begin + threadIdx.x; t < t_end; t += kSelBlock) mx = fmaxf(mx, s32(t));
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    __shared__ float fmx[kSelWaves];
+    if ((threadIdx.x & 63) == 0) fmx[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmx[0];
+    for (int i = 1; i < kSelWaves; ++i) mx = fmaxf(mx, fmx[i]);
+    // an infinite or empty maximum: score everything in fp64
+    const float thr = mx > -INFINITY && mx < INFINITY ? mx - 2.0f * (2e-6f * (fabsf(mx) + 40.0f) + 2e-5f) : -INFINITY;
+    for (int t = t_begin + threadIdx.x; t < t_end; t += kSelBlock) {
+      if (s32(t) >= thr) {
+        ScoreId c;
+        c.id = t;
+        c.s = score_of(z[t]) / T + gumbel_from_u(draw_u(prefix, (uint64_t)t));
+        if (better(c, best)) best = c;
+      }
     }
   }
   best = block_argmax(best, smem);
@@ -591,8 +626,12 @@ int launch_sample(const float* logits, int64_t ld, const float* temperature, int
     parts = parts < kSampleMaxParts ? parts : kSampleMaxParts;
     parts = parts < 1 ? 1 : parts;
   }
+  // SSD_SAMPLE_EXACT_SCAN=1: score every token of a sampled row in fp64 instead of pre-selecting in fp32 (a test aid: both
+  // give the same token)
+  const char* env = getenv("SSD_SAMPLE_EXACT_SCAN");
+  const int exact_scan = env && atoi(env) != 0;
   sample_kernel<<<dim3(rows, parts), kSelBlock, 0, s>>>(logits, ld, temperature, rows_per_seq, V, seed, row_base, step, out,
-                                                        out_stride, (ScoreId*)scratch);
+                                                        out_stride, (ScoreId*)scratch, exact_scan);
   SSD_HIP(hipGetLastError());
   if (parts > 1) {
     sample_merge_kernel<<<rows, 64, 0, s>>>((const ScoreId*)scratch, parts, out, out_stride);

@@ -89,6 +89,40 @@ def test_sampler_greedy_and_gumbel(B, V, rows):
     assert (got != greedy).any()
 
 
+@pytest.mark.parametrize("V,rows,scale,temp", [(128256, 24, 1.0, 1.0), (128256, 48, 3.0, 0.3), (4099, 7, 50.0, 0.05),
+                                               (128256, 6, 0.01, 2.0), (1024, 300, 1.0, 0.7)])
+def test_sampler_fp32_preselection_gives_the_fp64_token(B, V, rows, scale, temp, monkeypatch):
+    """Sampled rows are scanned in fp32 and only the tokens within the error bound of the maximum are scored in fp64.
+    The token must be the one a full fp64 scan gives, also with large logits over a small temperature, planted
+    near-ties, infinities and NaN."""
+    z = (I.make_logits(rows, V, seed=7 * V + rows, n_ties=5) * scale).astype(np.float32)
+    g = np.random.default_rng(V + rows)
+    for r in range(rows):
+        top = int(np.argmax(np.nan_to_num(z[r], nan=-np.inf)))
+        z[r, g.integers(0, V, 4)] = np.nextafter(z[r, top], np.float32(-np.inf))     # runners-up one ulp below the top
+    z[0, 5] = np.nan
+    z[min(1, rows - 1), 9] = -np.inf
+    if rows > 3:
+        z[3, 11] = np.inf                                       # an infinite logit wins whatever the noise
+    temps = dev_f32(np.full(rows, temp, np.float32))
+    zd = dev_f32(z)
+    outs = []
+    for exact in ("1", "0"):
+        monkeypatch.setenv("SSD_SAMPLE_EXACT_SCAN", exact)
+        per_step = []
+        for step in range(3):
+            out = torch.full((rows,), -5, dtype=torch.int32, device="cuda")
+            B.ssd_sample(zd, temps, seed=1234, row_base=17, step=step, out=out)
+            torch.cuda.synchronize()
+            per_step.append(out.cpu().numpy())
+        outs.append(np.stack(per_step))
+    assert np.array_equal(outs[0], outs[1])
+    if rows > 3:
+        assert (outs[1][:, 3] == 11).all()
+    # and it is a sample, not the argmax: steps differ somewhere
+    assert (outs[1][0] != outs[1][1]).any() or rows <= 7
+
+
 def _verify_case(B, V, K, nb, seed, temps, close_draft):
     g = np.random.default_rng(seed)
     zt = (g.standard_normal((nb, K + 1, V)) * 2.0).astype(np.float32)
