@@ -69,8 +69,8 @@ __device__ __forceinline__ void st_f32x4(float* p, f32x4 v) {
   st_u64(p + 2, pack_f32x2(v[2], v[3]));
 }
 // Partial tiles of a K-split are their own "ready" flag: a word that holds kFixEmpty (a NaN pattern no sum of
-// products produces) has not been written in this launch.  The reader takes the tile with loads that are served by
-// the L2 (agent scope) and writes kFixEmpty back.
+// products produces) has not been written in this launch.  The reader takes the tile with agent-scope loads (coherent
+// across the XCDs) and writes kFixEmpty back.
 constexpr unsigned kFixEmpty = 0xffffffffu;
 __device__ __forceinline__ f32x4 ld_f32x4_coherent(const float* p) {
   const uint64_t a = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
