@@ -376,6 +376,23 @@ def test_argument_validation(B):
             B.ssd_ctx_prefill(ctx, dev_i32(np.zeros((1, 35))), [35])
         assert e.value.status == B.SSD_EINVAL
         B.ssd_ctx_destroy(ctx)
+        # a fan-out per accept length: K+1 entries, each within 1..SSD_MAX_F
+        for fan in ([2, 2, 2, 2, 0], [2, 2, 2, 2, 17]):
+            with pytest.raises(B.SsdError) as e:
+                B.ssd_ctx_create_fanout(model, 1, 4, fan, 128)
+            assert e.value.status == B.SSD_EINVAL
+        # trunk truncation: lengths within 1 .. what the trunk holds
+        ctx = B.ssd_ctx_create(model, 2, 4, 2, 64)
+        B.ssd_ctx_prefill(ctx, dev_i32(I.make_prompt(shape, 2, 20, 1)), [20, 12])
+        for lens in ([0, 5], [21, 5]):
+            with pytest.raises(B.SsdError) as e:
+                B.ssd_ctx_truncate_trunk(ctx, lens)
+            assert e.value.status == B.SSD_EINVAL
+        B.ssd_ctx_truncate_trunk(ctx, [20, 20])       # within the bound: positions 12..19 of sequence 1 hold padding KV
+        B.ssd_ctx_truncate_trunk(ctx, [7, 3])
+        torch.cuda.synchronize()
+        assert list(B.read_cache(ctx, with_logits=False)["trunk_len"].cpu().numpy()) == [7, 3]
+        B.ssd_ctx_destroy(ctx)
     finally:
         B.ssd_model_destroy(model)
 
