@@ -237,6 +237,29 @@ def test_fused_pass_barrier_epoch_wraps_around(B, monkeypatch):
         B.ssd_model_destroy(model)
 
 
+def _small(**over):
+    return I.ModelShape(**{**SMALL_BF16.__dict__, **over})
+
+
+@pytest.mark.parametrize("name,shape,kw", [
+    ("shortest round", SMALL_BF16, dict(batch=1, P=5, K=1, F=1, seed=1, synthetic_kv=False)),
+    ("longest lookahead", _small(n_layers=1), dict(batch=1, P=40, K=15, F=3, seed=2, synthetic_kv=True)),
+    ("widest fan-out", _small(n_layers=1), dict(batch=1, P=33, K=2, F=16, seed=3, synthetic_kv=True)),
+    ("one KV head for 8 query heads", _small(n_kv_heads=1), dict(batch=2, P=70, K=3, F=2, seed=4, synthetic_kv=True)),
+    ("multi-head attention", _small(n_kv_heads=8), dict(batch=1, P=65, K=3, F=4, seed=5, synthetic_kv=True)),
+    ("one-token prompts", SMALL_BF16, dict(batch=3, P=1, K=2, F=2, seed=6, synthetic_kv=False)),
+    ("two key splits", _small(n_layers=1), dict(batch=1, P=2100, K=2, F=4, seed=7, synthetic_kv=True)),
+    ("wider model", _small(d_model=1024, n_q_heads=16, n_kv_heads=4, d_ffn=1536), dict(batch=1, P=90, K=4, F=4, seed=8, synthetic_kv=True)),
+    ("48 rows, the most of a fused pass", SMALL_BF16, dict(batch=1, P=100, K=5, F=8, seed=10, synthetic_kv=True)),
+    ("56 rows per sequence: per-operator kernels", _small(n_layers=1), dict(batch=1, P=50, K=6, F=8, seed=11, synthetic_kv=True)),
+    ("seven sequences of different lengths", _small(n_layers=1),
+     dict(batch=7, P=12, K=2, F=2, seed=14, synthetic_kv=False, lens=[12, 1, 5, 9, 2, 12, 7])),
+])
+def test_small_bf16_corner_shapes(B, name, shape, kw):
+    print(f"[case] {name}", flush=True)
+    _run_round_parity(B, shape, **kw)
+
+
 def test_small_bf16_head_dim_128_untied(B):
     _run_round_parity(B, SMALL_BF16_D128, batch=1, P=70, K=2, F=2, seed=9, synthetic_kv=True)
 
