@@ -418,11 +418,12 @@ __global__ __launch_bounds__(kSelBlock) void verify_sum_kernel(const float* __re
 __global__ __launch_bounds__(kSelBlock) void verify_accept_kernel(const float* __restrict__ zt, const float* __restrict__ zd,
                                                                   const int32_t* __restrict__ spec,
                                                                   const float* __restrict__ temperature, int K, int V,
-                                                                  uint64_t seed, VerifyWs ws, int32_t* __restrict__ accept_len,
+                                                                  uint64_t seed, VerifyWs ws, int row_parts,
+                                                                  int32_t* __restrict__ accept_len,
                                                                   int32_t* __restrict__ bonus) {
   __shared__ double dsm[kSelWaves];
   __shared__ int k_s;
-  const int b = blockIdx.x, parts = gridDim.y;
+  const int b = blockIdx.x, parts = gridDim.y;   // row_parts: the parts passes 1 and 2 cut a row into (may differ)
   const double T = zd ? (double)temperature[b] : 0.0;
   RowStats* st = ws.stats + (int64_t)b * (2 * K + 1);
   // the rows' softmax denominators: the parts' sums in part order (threads 0 .. 2K merge one row each; part 0 keeps them)
@@ -430,7 +431,7 @@ __global__ __launch_bounds__(kSelBlock) void verify_accept_kernel(const float* _
   if (T > 0.0 && (int)threadIdx.x <= 2 * K) {
     const int64_t row = (int64_t)b * (2 * K + 1) + threadIdx.x;
     double sum = 0.0;
-    for (int i = 0; i < parts; ++i) sum += ws.part_sum[row * parts + i];
+    for (int i = 0; i < row_parts; ++i) sum += ws.part_sum[row * row_parts + i];
     sums[threadIdx.x] = sum;
     if (blockIdx.y == 0) st[threadIdx.x].sum = sum;
   }
@@ -656,7 +657,7 @@ int launch_verify(const float* zt, const float* zd, const int32_t* spec, const f
   parts_b = parts_b < 1 ? 1 : parts_b;
   verify_max_kernel<<<dim3(rows, parts), kSelBlock, 0, s>>>(zt, zd, temperature, K, V, ws);
   verify_sum_kernel<<<dim3(rows, parts), kSelBlock, 0, s>>>(zt, zd, temperature, K, V, ws);
-  verify_accept_kernel<<<dim3(B, parts_b), kSelBlock, 0, s>>>(zt, zd, spec, temperature, K, V, seed, ws, accept_len, bonus);
+  verify_accept_kernel<<<dim3(B, parts_b), kSelBlock, 0, s>>>(zt, zd, spec, temperature, K, V, seed, ws, parts, accept_len, bonus);
   if (zd) {   // without draft logits every sequence is greedy and done
     verify_bonus_kernel<<<dim3(B, parts_b), kSelBlock, 0, s>>>(zt, zd, temperature, K, V, seed, ws);
     verify_bonus_merge_kernel<<<B, 64, 0, s>>>(zd, temperature, parts_b, ws, bonus);

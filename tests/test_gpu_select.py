@@ -147,7 +147,9 @@ def _verify_case(B, V, K, nb, seed, temps, close_draft):
     return zt, zd, spec, k_out.cpu().numpy(), t_out.cpu().numpy()
 
 
-@pytest.mark.parametrize("V,K,nb,close", [(1024, 4, 12, True), (1024, 5, 8, False), (128256, 5, 3, True)])
+@pytest.mark.parametrize("V,K,nb,close", [(1024, 4, 12, True), (1024, 5, 8, False), (128256, 5, 3, True),
+                                          (40000, 2, 40, True),      # rows and sequences are cut into different numbers of parts
+                                          (3, 15, 2, True), (17, 1, 33, False), (128256, 15, 2, True)])
 def test_verify_matches_oracle(B, V, K, nb, close):
     temps = np.array([0.0 if b % 3 == 0 else (1.0 if b % 3 == 1 else 0.6) for b in range(nb)], np.float32)
     seed = 4242 + V + K
@@ -160,7 +162,7 @@ def test_verify_matches_oracle(B, V, K, nb, close):
             assert k_got[b] == want.accept_len, b
             if want.bonus_margin > MARGIN:
                 assert t_got[b] == want.bonus, b
-    assert len(set(ks)) > 1                                   # several accept lengths were exercised
+    assert len(set(ks)) > 1 or nb < 8                         # several accept lengths were exercised
 
 
 def test_verify_greedy_without_draft_logits_and_full_acceptance(B):
