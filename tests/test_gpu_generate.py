@@ -202,3 +202,79 @@ def test_greedy_ssd_with_the_random_token_backup_decides_like_the_oracle(B):
     finally:
         target.close()
         draft.close()
+
+
+def test_greedy_ssd_for_a_batch_whose_sequences_diverge(B):
+    """Alg. 1 for three sequences in one context pair: accept lengths, hits and misses differ per sequence, so the
+    trunk lengths drift apart round by round (the per-sequence rollback of App. B).  Every sequence must still
+    reproduce its own greedy autoregressive text."""
+    wl = I.WORKLOADS["tiny_f32"]
+    shape, K, F = wl.draft, wl.round.K, wl.round.F
+    nb, n_new, P, V = 3, 30, 18, wl.draft.vocab
+    wt = I.make_weights(shape, 41)
+    wd = I.make_weights(shape, 42, perturb_of=wt, perturb_std=0.003)
+    prompts = I.make_prompt(shape, nb, P, 23)
+    lens = [P, P - 5, P - 9]
+    ot = O.Model.from_weights(shape, wt)
+    want = [O.ar_generate(ot, prompts[b][:lens[b]], n_new) for b in range(nb)]
+    cap = P + n_new + 5 * K + 8
+    mt, md = B.ssd_model_create(shape, wt), B.ssd_model_create(shape, wd)
+    ct, cd = B.ssd_ctx_create(mt, nb, K, 1, cap), B.ssd_ctx_create(md, nb, K, F, cap)
+    try:
+        X = [[int(t) for t in prompts[b][:lens[b]]] for b in range(nb)]
+        body = np.zeros((nb, P), np.int32)
+        for b in range(nb):
+            body[b, :lens[b] - 1] = X[b][:-1]
+        for c in (ct, cd):
+            B.ssd_ctx_prefill(c, dev_i32(body), [n - 1 for n in lens])
+        temps = dev_f32(np.zeros(nb, np.float32))
+        out = torch.zeros(nb, dtype=torch.int32, device="cuda")
+
+        def jit(last):                               # K greedy tokens after `last` for every sequence, one extend each
+            toks, cur = [], np.asarray(last, np.int32)
+            for i in range(K):
+                z = torch.empty((nb, 1, V), dtype=torch.float32, device="cuda")
+                B.ssd_ctx_extend(cd, dev_i32(cur[:, None]), i, z)
+                B.ssd_sample(z[:, 0].contiguous(), temps, 0, 0, i, out)
+                cur = out.cpu().numpy().copy()
+                toks.append(cur)
+            return np.stack(toks, axis=1)            # [nb][K]
+
+        spec = jit([x[-1] for x in X])
+        acc = torch.zeros(nb, dtype=torch.int32, device="cuda")
+        bonus = torch.zeros(nb, dtype=torch.int32, device="cuda")
+        hit = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+        branch = torch.zeros(nb, dtype=torch.int32, device="cuda")
+        nxt = torch.zeros((nb, K), dtype=torch.int32, device="cuda")
+        ws = torch.empty(B.ssd_verify_workspace_bytes(nb, K), dtype=torch.uint8, device="cuda")
+        rounds, accept_sets, hits = 0, [set() for _ in range(nb)], np.zeros(nb, int)
+        while min(len(X[b]) - lens[b] for b in range(nb)) < n_new:
+            rounds += 1
+            pending = dev_i32(np.concatenate([np.array([[x[-1]] for x in X], np.int32), spec], axis=1))
+            zt = torch.empty((nb, K + 1, V), dtype=torch.float32, device="cuda")
+            B.ssd_ctx_extend(ct, pending, 0, zt)
+            B.ssd_verify(zt, None, pending[:, 1:].contiguous(), temps, rounds, acc, bonus, ws)
+            B.ssd_prespeculate(cd, pending, temps, rounds)
+            B.ssd_cache_lookup(cd, acc, bonus, hit, branch, nxt)
+            torch.cuda.synchronize()
+            k, t, h = acc.cpu().numpy(), bonus.cpu().numpy(), hit.cpu().numpy()
+            for b in range(nb):
+                X[b] += [int(s) for s in spec[b, :k[b]]] + [int(t[b])]
+                accept_sets[b].add(int(k[b]))
+            hits += h
+            for c in (ct, cd):
+                B.ssd_ctx_commit(c, acc)
+                B.ssd_ctx_refresh_bounds(c)
+            cached = nxt.cpu().numpy()
+            fresh = jit(t) if not h.all() else cached
+            spec = np.where(h[:, None].astype(bool), cached, fresh).astype(np.int32)
+        for b in range(nb):
+            assert X[b][lens[b]:lens[b] + n_new] == want[b], b
+        tl = B.read_cache(cd, with_logits=False)["trunk_len"].cpu().numpy()
+        assert list(tl) == [len(x) - 1 for x in X] and len(set(tl)) > 1          # the sequences have drifted apart
+        assert all(len(s) >= 2 for s in accept_sets) and 0 < hits.sum() < rounds * nb
+    finally:
+        B.ssd_ctx_destroy(ct)
+        B.ssd_ctx_destroy(cd)
+        B.ssd_model_destroy(mt)
+        B.ssd_model_destroy(md)
