@@ -484,3 +484,45 @@ def test_small_bf16_saguaro_sampling_scheme(B):
     finally:
         B.ssd_ctx_destroy(ctx)
         B.ssd_model_destroy(model)
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_small_bf16_rounds_in_sequence_with_rollback(B, fused, monkeypatch):
+    """Several rounds on one context (App. B "Glue & Recurrence"): after each round the trunk keeps the glue positions
+    0..k of the realised accept length and the next glue extend overwrites the rest.  Accept lengths 0, K, 2, 1, K walk
+    the trunk across a 32-position block boundary of the value layout; every round's cache must match the oracle's
+    round on the oracle's own trunk."""
+    if not fused:
+        monkeypatch.setenv("SSD_FUSED", "off")
+    shape, batch, P, K, F, seed = SMALL_BF16, 2, 27, 3, 2, 33
+    tol = TOL[shape.dtype]
+    w = I.make_weights(shape, seed)
+    om = O.Model.from_weights(shape, w)
+    model = B.ssd_model_create(shape, w)
+    ctx = B.ssd_ctx_create(model, batch, K, F, P + 6 * (K + 1) + 2 * K + 4)
+    try:
+        k, v = I.make_prefix_kv(shape, batch, P, seed)
+        B.ssd_ctx_load_trunk(ctx, kv_to_device(k, shape.dtype), kv_to_device(v, shape.dtype), P)
+        trunks = [oracle_trunk_from_arrays(om, k, v, b) for b in range(batch)]
+        temps = dev_f32(np.zeros(batch, np.float32))
+        for rnd, accepts in enumerate([(0, K), (K, 2), (2, 0), (1, 1), (K, K)]):
+            pending = I.make_pending(shape, batch, K, seed + rnd)
+            caches = [O.prespeculate(om, trunks[b], pending[b], F, 0.0, seed=rnd, row_base=b * (K + 1) * F) for b in range(batch)]
+            f_keys = dev_i32(np.stack([c.keys for c in caches]))
+            f_toks = dev_i32(np.stack([c.tokens for c in caches]))
+            d_pending = dev_i32(pending)
+            B.ssd_ctx_set_forced(ctx, f_keys, f_toks)
+            B.ssd_prespeculate(ctx, d_pending, temps, rnd)
+            B.ssd_ctx_set_forced(ctx, None, None)
+            got = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx).items()}
+            assert list(got["trunk_len"]) == [t.length for t in trunks]
+            for b in range(batch):
+                e_g = row_rel_err(got["glue_logits"][b], caches[b].glue_logits)
+                e_l = row_rel_err(got["logits"][b], caches[b].logits)
+                assert e_g < tol and e_l < tol, (rnd, b, e_g, e_l)
+            B.ssd_ctx_commit(ctx, dev_i32(np.array(accepts, np.int32)))
+            B.ssd_ctx_refresh_bounds(ctx)
+            trunks = [caches[b].trunk.slice(trunks[b].length + accepts[b] + 1) for b in range(batch)]
+    finally:
+        B.ssd_ctx_destroy(ctx)
+        B.ssd_model_destroy(model)
