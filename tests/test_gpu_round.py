@@ -420,8 +420,9 @@ def test_argument_validation(B):
         B.ssd_model_destroy(model)
 
 
-def test_small_bf16_saguaro_sampling_scheme(B):
-    """Sec. 4.3: branches drawn from sigma_{F,C}.  Teacher-forced on the oracle's tokens, the cached logits must be the
+@pytest.mark.parametrize("fan", [None, [2, 4, 1, 3]])
+def test_small_bf16_saguaro_sampling_scheme(B, fan):
+    """Sec. 4.3: branches drawn from sigma_{F,C}; with a fan-out per accept length, depth i lowers its top F_i.  Teacher-forced on the oracle's tokens, the cached logits must be the
     oracle's lowered logits wherever the step's top-F set is not a near-tie at this precision (there, lowering a
     different token is equally right: the row is then compared with the shift taken out on both sides)."""
     shape, batch, P, K, F, seed, T, Cw = SMALL_BF16, 2, 61, 3, 3, 17, 1.0, 0.3
@@ -429,19 +430,23 @@ def test_small_bf16_saguaro_sampling_scheme(B):
     w = I.make_weights(shape, seed)
     om = O.Model.from_weights(shape, w)
     model = B.ssd_model_create(shape, w)
-    ctx = B.ssd_ctx_create(model, batch, K, F, P + 4 * K + 8)
+    fans = [F] * (K + 1) if fan is None else fan
+    F = F if fan is None else fan                    # what the oracle's prespeculate takes
+    RB = sum(fans)
+    ctx = B.ssd_ctx_create(model, batch, K, F, P + 4 * K + 8) if fan is None else \
+        B.ssd_ctx_create_fanout(model, batch, K, fans, P + 4 * K + 8)
     try:
         k, v = I.make_prefix_kv(shape, batch, P, seed)
         B.ssd_ctx_load_trunk(ctx, kv_to_device(k, shape.dtype), kv_to_device(v, shape.dtype), P)
         trunks = [oracle_trunk_from_arrays(om, k, v, b) for b in range(batch)]
         pending = I.make_pending(shape, batch, K, seed)
-        rb = lambda b: b * (K + 1) * F
+        rb = lambda b: b * RB
         caches = [O.prespeculate(om, trunks[b], pending[b], F, T, seed=seed, row_base=rb(b), C=Cw) for b in range(batch)]
         raws = [O.prespeculate(om, trunks[b], pending[b], F, T, seed=seed, row_base=rb(b), forced_tokens=caches[b].tokens)
                 for b in range(batch)]
         temps = dev_f32(np.full(batch, T, np.float32))
-        f_keys = dev_i32(np.stack([c.keys for c in caches]))          # kept alive while the context points at them
-        f_toks = dev_i32(np.stack([c.tokens for c in caches]))
+        f_keys = dev_i32(np.stack([_in_row_order(c.keys, fans) for c in caches]))     # kept alive while the context points at them
+        f_toks = dev_i32(np.stack([_in_row_order(c.tokens, fans) for c in caches]))
         B.ssd_ctx_set_saguaro(ctx, Cw)
         B.ssd_ctx_set_forced(ctx, f_keys, f_toks)
         B.ssd_prespeculate(ctx, dev_i32(pending), temps, seed)
@@ -451,10 +456,11 @@ def test_small_bf16_saguaro_sampling_scheme(B):
         n_exact = n_tie = n_tok = 0
         for b in range(batch):
             for kk in range(K + 1):
-                for j in range(F):
+                for j in range(fans[kk]):
                     for i in range(K):
                         z_got, z_want, z_raw = got["logits"][b, kk, j, i], caches[b].logits[kk, j, i], raws[b].logits[kk, j, i]
                         scale = np.abs(z_raw).max()
+                        F = fans[i]                  # depth i is verified at accept length i of the next round
                         top = O.top_f_ids(z_raw, F + 1)
                         # what the GPU lowered: the entries that sit about `shift` below the oracle's raw logits
                         lowered = np.nonzero(z_got - z_raw < shift / 2)[0]
