@@ -197,6 +197,9 @@ def main():
                     help="default: the workload the headline metric is quoted on; the others print the same kind of line for "
                          "their shape (no CPU baseline, no counter traffic); 70b_verify_1b_draft: the target's verification "
                          "forward beside the draft round")
+    ap.add_argument("--geometric-fanout", metavar="A,R", default=None,
+                    help="spread the workload's (K+1) F branch rows over the accept lengths by the geometric cache shape for "
+                         "acceptance rate A and power-law exponent R (e.g. 0.8,0.5) instead of F each")
     ap.add_argument("--ragged-prefix", action="store_true",
                     help="give every sequence of the batch its own prefix length (seeded, between a tenth of the workload's "
                          "prefix and all of it) instead of the same one")
@@ -226,7 +229,7 @@ def main():
     import ssd_inputs as I
     from paper_2603_03251_amd import binding as B
 
-    headline = args.workload == WORKLOAD and not args.ragged_prefix
+    headline = args.workload == WORKLOAD and not args.ragged_prefix and not args.geometric_fanout
     wl = I.WORKLOADS[args.workload]
     shape, r = wl.draft, wl.round
     K, F, P, nb, V = r.K, r.F, r.prefix, r.batch, shape.vocab
@@ -234,7 +237,13 @@ def main():
 
     w = I.make_weights(shape, WEIGHT_SEED)
     model = B.ssd_model_create(shape, w)
-    ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2)
+    fan = None
+    if args.geometric_fanout:
+        a_rate, r_exp = (float(x) for x in args.geometric_fanout.split(","))
+        fan = B.ssd_geometric_fanout((K + 1) * F, K, a_rate, r_exp)
+        ctx = B.ssd_ctx_create_fanout(model, nb, K, fan, P + 2 * K + 2)
+    else:
+        ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2)
     k, v = I.make_prefix_kv(shape, nb, P, wl.seed)
     to_bf16 = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
     B.ssd_ctx_load_trunk(ctx, to_bf16(k), to_bf16(v), P)
@@ -308,7 +317,8 @@ def main():
         "config": {"workload": f"{args.workload}: Llama-3.2-1B-shaped bf16 draft, B={nb}, prefix {P}, K={K}, F={F} "
                                f"({r.rows} branch rows), lookahead {K}, {'greedy' if r.temperature == 0 else 'temperature %g' % r.temperature}"
                                f"; verify on a second stream; lookup"
-                               + (f"; prefix lengths {min(prefix_lens)}..{max(prefix_lens)}, mean {sum(prefix_lens) // nb}" if prefix_lens else ""),
+                               + (f"; prefix lengths {min(prefix_lens)}..{max(prefix_lens)}, mean {sum(prefix_lens) // nb}" if prefix_lens else "")
+                               + (f"; geometric fan-out {fan}" if fan else ""),
                    "branch_rows": r.rows, "tokens_per_round": tokens_per_round},
         "segments_ms": {"glue_extend": float(seg[:, 0].mean()), "fan_out": float(seg[:, 1].mean()),
                         "branch_decode_step": step_ms, "decode_steps_total": float(seg[:, 2:K + 2].sum(axis=1).mean())},
