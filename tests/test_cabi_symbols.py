@@ -58,3 +58,23 @@ def test_geometric_cache_shape_equals_the_oracles_integer_shape():
         with pytest.raises(b.SsdError) as e:
             b.ssd_geometric_fanout(*bad)
         assert e.value.status == b.SSD_EINVAL
+
+
+def test_bench_byte_count_of_the_headline_step_by_hand():
+    """The roofline's numerator for workload 1b_p1024_f4, worked out by hand: every weight once, the trunk KV once per
+    sequence, the fp32 logits kept, the branches' private suffix KV."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    import ssd_inputs as I
+    wl = I.WORKLOADS["1b_p1024_f4"]
+    d, f, V, L, kvd = 2048, 8192, 128256, 16, 512
+    weights = (L * ((2048 + 2 * kvd) * d + d * 2048 + 3 * d * f) + V * d) * 2          # bf16, LM head tied to the embedding
+    trunk = L * (1024 + 6) * 2 * kvd * 2                                             # prefix + glue positions, K and V
+    logits = 24 * V * 4
+    suffix = 24 * L * 5 * 2 * kvd * 2
+    assert weights == 2_471_493_632
+    assert bench.algorithmic_bytes_per_decode_step(wl.draft, wl.round) == weights + trunk + logits + suffix == 2_521_489_408
+    # a prefix length per sequence replaces batch x prefix by the sum of the lengths
+    assert bench.algorithmic_bytes_per_decode_step(wl.draft, wl.round, [500]) == weights + L * (500 + 6) * 2 * kvd * 2 + logits + suffix
