@@ -28,8 +28,8 @@
  *   - Ordering of tokens wherever a maximum or a top-F is taken: larger score first,
  *     equal scores by smaller token id; NaN ranks below every number.
  *   - The library allocates device memory only in *_create; the hot calls
- *     (ssd_prespeculate, ssd_cache_lookup, ssd_ctx_commit, ssd_verify, ssd_top_f,
- *     ssd_sample) allocate nothing.
+ *     (ssd_prespeculate, ssd_cache_lookup, ssd_ctx_commit, ssd_verify, ssd_verify_static,
+ *     ssd_top_f, ssd_sample) allocate nothing.
  */
 #ifndef SSD_H_
 #define SSD_H_
@@ -212,6 +212,19 @@ int ssd_verify(const float* d_target_logits, const float* d_draft_logits, const 
                const float* d_temperature, int32_t B, int32_t K, int32_t V, uint64_t seed,
                int32_t* d_accept_len, int32_t* d_bonus, void* d_workspace, void* stream);
 size_t ssd_verify_workspace_bytes(int32_t B, int32_t K);
+
+/* ssd_verify for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error behaviour as ssd_verify, without
+ * d_workspace: the partial results of the passes meet in a static device array of ssd_verify_static_capacity() bytes
+ * (1 MiB; every GPU the library runs on holds one until the process ends).  The call allocates nothing, neither with
+ * hipMalloc nor through any library.  EINVAL if ssd_verify_workspace_bytes(B, K) exceeds the capacity (B (2K+1) up to
+ * about 1200 rows of logits fit).  All calls on one GPU share that GPU's array: two calls whose work overlaps in time on
+ * one GPU (different streams, or different threads) race; calls on one stream are ordered and safe.  Nothing in the array
+ * has to be cleared between calls. */
+int ssd_verify_static(const float* d_target_logits, const float* d_draft_logits, const int32_t* d_spec_tokens,
+                      const float* d_temperature, int32_t B, int32_t K, int32_t V, uint64_t seed,
+                      int32_t* d_accept_len, int32_t* d_bonus, void* stream);
+size_t ssd_verify_static_capacity(void);
 
 /* The low-latency backup speculator of the fallback strategy (Sec. 4.4: after a cache miss at large batch the
  * next speculation is K random tokens).  out d_tokens int32 [B][K]: token i of sequence b is the 64-bit hash

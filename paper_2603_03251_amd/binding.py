@@ -72,6 +72,8 @@ EXPORTS = {
     "ssd_ctx_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ssd_verify": (C.c_int, [C.c_void_p] * 4 + [C.c_int32] * 3 + [C.c_uint64] + [C.c_void_p] * 4),
     "ssd_verify_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32]),
+    "ssd_verify_static": (C.c_int, [C.c_void_p] * 4 + [C.c_int32] * 3 + [C.c_uint64] + [C.c_void_p] * 3),
+    "ssd_verify_static_capacity": (C.c_size_t, []),
     "ssd_top_f": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                             C.c_void_p, C.c_void_p]),
     "ssd_top_f_workspace_bytes": (C.c_size_t, [C.c_int32]),
@@ -258,6 +260,17 @@ def ssd_verify(target_logits, draft_logits, spec_tokens, temperature, seed: int,
     B, K1, V = target_logits.shape
     _check(lib.ssd_verify(_ptr(target_logits), _ptr(draft_logits), _ptr(spec_tokens), _ptr(temperature), B, K1 - 1, V,
                           seed, _ptr(accept_len), _ptr(bonus), _ptr(workspace), _stream(stream)))
+
+
+def ssd_verify_static(target_logits, draft_logits, spec_tokens, temperature, seed: int, accept_len, bonus,
+                      stream=None) -> None:
+    B, K1, V = target_logits.shape
+    _check(lib.ssd_verify_static(_ptr(target_logits), _ptr(draft_logits), _ptr(spec_tokens), _ptr(temperature), B, K1 - 1,
+                                 V, seed, _ptr(accept_len), _ptr(bonus), _stream(stream)))
+
+
+def ssd_verify_static_capacity() -> int:
+    return int(lib.ssd_verify_static_capacity())
 
 
 def ssd_backup_random(seed: int, V: int, tokens: torch.Tensor, stream=None) -> None:

@@ -170,5 +170,9 @@ int launch_backup_random(int32_t* tokens, int B, int K, int V, uint64_t seed, hi
 int launch_verify(const float* zt, const float* zd, const int32_t* spec, const float* temperature, int B, int K, int V,
                   uint64_t seed, int32_t* accept_len, int32_t* bonus, void* workspace, hipStream_t s);
 size_t verify_workspace_bytes(int B, int K);
+// the same with the workspace in a static device array of verify_static_capacity() bytes (no allocation, ever)
+int launch_verify_static(const float* zt, const float* zd, const int32_t* spec, const float* temperature, int B, int K, int V,
+                         uint64_t seed, int32_t* accept_len, int32_t* bonus, hipStream_t s);
+size_t verify_static_capacity();
 
 }  // namespace ssd

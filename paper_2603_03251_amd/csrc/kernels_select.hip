@@ -1,6 +1,8 @@
 // Selection kernels: top-F bonus-token candidates per accept length (Sec. 4.1.1), the branch sampler
 // (argmax / Gumbel-max), and lossless verification (Sec. 2.1).  All orderings are (score descending,
 // token id ascending); NaN ranks below every number.
+#include <mutex>
+
 #include "common.h"
 #include "rng.h"
 
@@ -664,6 +666,40 @@ int launch_verify(const float* zt, const float* zd, const int32_t* spec, const f
   }
   SSD_HIP(hipGetLastError());
   return SSD_OK;
+}
+
+// ---- verification for callers that cannot allocate: the workspace is a file-scope device array.  Host code never
+// passes the array's name to a kernel (there it is only a host-side stand-in): the device address is looked up once
+// per device with hipGetSymbolAddress and kept.
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+size_t verify_static_capacity() { return kStaticScratchBytes; }
+
+int launch_verify_static(const float* zt, const float* zd, const int32_t* spec, const float* temperature, int B, int K, int V,
+                         uint64_t seed, int32_t* accept_len, int32_t* bonus, hipStream_t s) {
+  const size_t need = verify_workspace_bytes(B, K);
+  SSD_CHECK_ARG(need <= kStaticScratchBytes,
+                "ssd_verify_static: B = %d, K = %d needs %zu bytes of scratch, the static buffer holds %zu (B (2K+1) <= about 1200)",
+                B, K, need, kStaticScratchBytes);
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr_of_device[kMaxDevices] = {};
+  int dev = 0;
+  SSD_HIP(hipGetDevice(&dev));
+  SSD_CHECK_ARG(dev >= 0 && dev < kMaxDevices, "ssd_verify_static: device ordinal %d out of range", dev);
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of_device[dev]) {
+      void* p = nullptr;
+      SSD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));   // this device's copy of the array (the current device)
+      ptr_of_device[dev] = p;
+    }
+    ptr = ptr_of_device[dev];
+  }
+  // nothing in the workspace has to start at zero: every word a pass reads was written by an earlier pass of the same call
+  return launch_verify(zt, zd, spec, temperature, B, K, V, seed, accept_len, bonus, ptr, s);
 }
 
 size_t verify_workspace_bytes(int B, int K) {

@@ -869,6 +869,17 @@ int ssd_verify(const float* d_target_logits, const float* d_draft_logits, const 
                        d_workspace, (hipStream_t)stream);
 }
 
+int ssd_verify_static(const float* d_target_logits, const float* d_draft_logits, const int32_t* d_spec_tokens,
+                      const float* d_temperature, int32_t B, int32_t K, int32_t V, uint64_t seed, int32_t* d_accept_len,
+                      int32_t* d_bonus, void* stream) {
+  SSD_CHECK_ARG(d_target_logits && d_spec_tokens && d_temperature && d_accept_len && d_bonus, "ssd_verify_static: null argument");
+  SSD_CHECK_ARG(B >= 1 && K >= 1 && K <= SSD_MAX_K && V >= 2, "ssd_verify_static: B >= 1, 1 <= K <= %d, V >= 2 required", SSD_MAX_K);
+  return launch_verify_static(d_target_logits, d_draft_logits, d_spec_tokens, d_temperature, B, K, V, seed, d_accept_len,
+                              d_bonus, (hipStream_t)stream);
+}
+
+size_t ssd_verify_static_capacity(void) { return verify_static_capacity(); }
+
 size_t ssd_top_f_workspace_bytes(int32_t rows) { return rows > 0 ? top_f_scratch_bytes(rows) : 0; }
 
 int ssd_top_f(const float* d_logits, int64_t ld, const int32_t* d_exclude, int32_t rows, int32_t V, int32_t F,
