@@ -80,7 +80,7 @@ def algorithmic_bytes_target_forward(shape, prefix, T):
 
 
 def bench_target_verify(args):
-    """Workload 70b_verify_1b_draft (Sec. 4.1, Sec. 5 set-up): the target's verification forward over the K+1 pending
+    """Workload 70b_verify_1b_draft (Sec. 2.1: verification is one target forward over the K+1 positions; Sec. 4 "Setup"): the target's verification forward over the K+1 pending
     positions at the 70B shape, alone and beside the draft's pre-speculation round, both on this one GPU (so the two
     share one HBM: this shows the overlap mechanics and the target forward's own rate, not the paper's two-device
     latency hiding).  80 layers are built from 2 distinct random layers (the host copy stays small); prefix KV is

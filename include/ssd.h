@@ -21,7 +21,7 @@
  *     enqueue work; none synchronises the host unless stated.
  *   - Branch row order (part of the contract): row = b (K+1) F + k F + j, with b the
  *     sequence, k the accept length 0..K and j the candidate rank 0..F-1.  With a fan-out
- *     F_0..F_K that differs per accept length (Sec. 4.2.2; ssd_ctx_create_fanout) rows run
+ *     F_0..F_K that differs per accept length (Sec. 4.1.2; ssd_ctx_create_fanout) rows run
  *     accept length by accept length: row = b R + (F_0 + .. + F_{k-1}) + j, j < F_k,
  *     R = F_0 + .. + F_K rows per sequence; wherever a layout below says [K+1][F], such a
  *     context holds [R] in that order (no padding).
@@ -123,7 +123,7 @@ int ssd_model_destroy(ssd_model* m);
 int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx** out);
 int ssd_ctx_destroy(ssd_ctx* ctx);
 
-/* Cache shape (Sec. 4.2.2, Theorem "Geometric Fan-Out"): a context whose fan-out differs per accept length.
+/* Cache shape (Sec. 4.1.2, Theorem "Geometric Fan-Out"): a context whose fan-out differs per accept length.
  * h_fanout: host int32 [K+1], F_k in 1..SSD_MAX_F (read during the call only); cfg->F is ignored.  Everything else
  * is as for ssd_ctx_create; ssd_views.F reports the largest F_k.  ssd_ctx_fanout copies F_0..F_K of any context
  * to h_fanout [K+1]. */
@@ -173,7 +173,7 @@ int ssd_prespeculate(ssd_ctx* ctx, const int32_t* d_pending, const float* d_temp
  * ssd_prespeculate enqueued meanwhile has run. */
 int ssd_ctx_set_forced(ssd_ctx* ctx, const int32_t* d_keys, const int32_t* d_tokens);
 
-/* Saguaro sampling scheme sigma_{F,C} (Sec. 4.3): with C < 1 every later ssd_prespeculate draws the branch tokens of
+/* Saguaro sampling scheme sigma_{F,C} (Sec. 4.2.1): with C < 1 every later ssd_prespeculate draws the branch tokens of
  * sampled sequences (temperature > 0) from the step's logits with its own top-F entries lowered by T log(1/C), and the
  * cache holds those lowered logits (the distribution a verifier must be given).  The fan-out keys always rank the
  * model's own logits; greedy sequences are unaffected.  C in [0, 1]; 1 (the default) switches the scheme off.
@@ -189,8 +189,9 @@ int ssd_ctx_set_saguaro(ssd_ctx* ctx, float C);
 int ssd_cache_lookup(ssd_ctx* ctx, const int32_t* d_accept_len, const int32_t* d_bonus, uint8_t* d_hit,
                      int32_t* d_branch, int32_t* d_spec_tokens, const float** d_logits_ptr, void* stream);
 
-/* After the outcome (k, t*): trunk_len[b] += k+1 (keeps the glue positions of the last verified token
- * and the k accepted ones, drops the rest).  Values of d_accept_len are clamped to 0..K. */
+/* After the outcome (k, t*) (Alg. 1: the speculator appends the accepted tokens; App. B "Glue & Recurrence" and the
+ * rollback of rejected tokens' cache pages there): trunk_len[b] += k+1, which keeps the glue positions of the last
+ * verified token and the k accepted ones and drops the rest.  Values of d_accept_len are clamped to 0..K. */
 int ssd_ctx_commit(ssd_ctx* ctx, const int32_t* d_accept_len, void* stream);
 
 /* Lossless verification (Sec. 2.1), stateless, meant for a stream of its own.
@@ -226,7 +227,7 @@ int ssd_verify_static(const float* d_target_logits, const float* d_draft_logits,
                       int32_t* d_accept_len, int32_t* d_bonus, void* stream);
 size_t ssd_verify_static_capacity(void);
 
-/* The low-latency backup speculator of the fallback strategy (Sec. 4.4: after a cache miss at large batch the
+/* The low-latency backup speculator of the fallback strategy (Sec. 4.3: after a cache miss at large batch the
  * next speculation is K random tokens).  out d_tokens int32 [B][K]: token i of sequence b is the 64-bit hash
  * (seed, stream 4, b, i, 0) of the library's counter-based generator modulo V, uniform over the vocabulary.  Their
  * verification at temperature > 0 takes the uniform distribution as the draft's, i.e. all-zero draft logits. */

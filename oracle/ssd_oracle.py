@@ -22,18 +22,23 @@ What each function follows (section / equation / algorithm of the paper):
                                Def. "speculation cache"; App. C (token / element counts)
   cache_lookup                 Alg. 1 (lookup of the realised outcome), App. B payload
   cache_hit_rate, geometric_fan_out_real, geometric_fan_out
-                               Sec. 4.2.2, Def. "r power-law cache hit rate" and Theorem
+                               Sec. 4.1.2, Def. "r power-law cache hit rate" and Theorem
                                "Saguaro Cache Shape: Geometric Fan-Out"; closed form of
                                F_0 from its proof in the theory appendix
   ssd_generate                 Alg. 1 (whole loop; backup speculator = primary, just in time, or
-                               random tokens: the two ends of the fallback strategy of Sec. 4.4)
-  random_speculation           Sec. 4.4, the implementation's random-token backup speculator
+                               random tokens: the two ends of the fallback strategy of Sec. 4.3)
+  random_speculation           Sec. 4.3, the implementation's random-token backup speculator
+  sample_token                 Sec. 4.2.1, Def. "sampling scheme": softmax at temperature T,
+                               drawn with the Gumbel-max trick; T = 0 is the argmax
   ar_generate                  ordinary autoregressive decoding (the losslessness reference)
 
 The transformer itself (RMSNorm, rotary embedding with the rotate-half pairing,
 grouped-query softmax attention, SwiGLU) is the Llama-style decoder the paper's
 models are instances of; the paper does not restate it.  "parity unpinned"
-applies to no function here: each has a pin in tests/test_oracle_*.py.
+applies to no function here: each has a pin in tests/test_oracle_*.py (the
+Gumbel-max draw of sample_token at temperature > 0, alone and through
+decode_branch, speculate and the sampled ssd_generate loop, in
+tests/test_oracle_sampling.py).
 
 Draws of the method (acceptance uniforms, Gumbel noise) come from the
 counter-based generator `draw_u`, defined by integer arithmetic only; the HIP
@@ -367,7 +372,7 @@ def fan_out(glue_logits: np.ndarray, pending: Sequence[int], F) -> np.ndarray:
     """keys[k][j], k = 0..K: the F_k most likely bonus tokens if exactly k drafted tokens
     are accepted: top-F_k of the logits s_{k+1} was drawn from, without s_{k+1} itself
     (a rejected token has zero residual mass); for k = K, top-F_K of the logits after s_K.
-    With a fan-out that differs per accept length (Sec. 4.2.2) the array is max F_k wide and
+    With a fan-out that differs per accept length (Sec. 4.1.2) the array is max F_k wide and
     the unused entries hold -1, which no token equals."""
     K = len(pending) - 1
     fan = fan_of(F, K)
@@ -377,7 +382,7 @@ def fan_out(glue_logits: np.ndarray, pending: Sequence[int], F) -> np.ndarray:
     return keys
 
 
-# --------------------------------------------------------------------------- cache shape (Sec. 4.2.2)
+# --------------------------------------------------------------------------- cache shape (Sec. 4.1.2)
 
 def cache_hit_rate(fan: Sequence[float], a: float, r: float) -> float:
     """Chance that the verification outcome of a speculation is in the cache, for a speculator
@@ -462,7 +467,7 @@ def decode_branch(m: Model, trunk_glue: KV, P: int, k: int, first: int, steps: i
     then its own continuation.  With `forced` (teacher forcing) step i > 0 feeds
     forced[i-1] instead of its own sample.  Returns (tokens, logits, hidden, margins).
 
-    `sigma` = (F, C) drafts with the Saguaro sampling scheme sigma_{F,C} (Sec. 4.3): at T > 0
+    `sigma` = (F, C) drafts with the Saguaro sampling scheme sigma_{F,C} (Sec. 4.2.1): at T > 0
     every token is drawn from the model's logits with the top-F entries downweighted by C, and
     those are the logits returned (the distribution a verifier has to be given).  F is one
     number, or one per step."""
@@ -494,13 +499,13 @@ def prespeculate(m: Model, trunk: KV, pending: Sequence[int], F, T: float, seed:
     """One pre-speculation round for one sequence: glue extend, fan-out, then every branch
     (k, j) decoded for K tokens, one branch at a time, each with KV of its own.
 
-    F is the uniform fan-out, or F_0..F_K (Sec. 4.2.2).  Branches are numbered accept length
+    F is the uniform fan-out, or F_0..F_K (Sec. 4.1.2).  Branches are numbered accept length
     by accept length, r = F_0 + .. + F_{k-1} + j (k F + j when uniform); `row_base` is the
     global row index of branch (0,0) (a batch numbers its rows sequence after sequence; the
     index keys the draft Gumbel stream).  `only_rows` restricts the decode to a sample of
     branches (the others are left zero).  `forced_tokens` [K+1][max F_k][K] teacher-forces
     every branch's inputs.  C < 1 decodes the branches with the sampling scheme sigma_{F,C}
-    (Sec. 4.3); the fan-out itself always ranks the model's own logits.  The token drafted at
+    (Sec. 4.2.1); the fan-out itself always ranks the model's own logits.  The token drafted at
     depth i is the one whose rejection ends the next round at accept length i, where the
     cache will hold F_i candidates: that is the F its logits are downweighted with."""
     K = len(pending) - 1
@@ -596,7 +601,7 @@ def speculate(m: Model, trunk: KV, last: int, K: int, T: float, seed: int, seq: 
 
 
 def random_speculation(seed: int, seq: int, K: int, vocab: int) -> Tuple[List[int], np.ndarray]:
-    """The fast backup speculator of Sec. 4.4: K tokens drawn uniformly from the vocabulary, at
+    """The fast backup speculator of Sec. 4.3: K tokens drawn uniformly from the vocabulary, at
     no model cost.  Token i is the hash of (seed, backup stream, seq, i, 0) modulo the vocabulary
     size (all 64 bits, so the draw is uniform to 2^-47).  Returns (tokens, logits): the logits are
     all zero, i.e. the uniform distribution the tokens were drawn from, which is what lossless
@@ -617,7 +622,7 @@ def ssd_generate(target: Model, draft: Model, prompt: Sequence[int], n_new: int,
                  T: float = 0.0, seed: int = 0, backup: str = "primary") -> Tuple[List[int], SSDStats]:
     """Alg. 1 for one sequence, run sequentially: speculate, then per round
     {verify the pending speculation, pre-speculate for predicted outcomes, look the realised
-    outcome up, fall back on a miss}.  The fallback (Sec. 4.4) is just-in-time drafting with the
+    outcome up, fall back on a miss}.  The fallback (Sec. 4.3) is just-in-time drafting with the
     same draft (backup = "primary", the low-batch choice) or K random tokens (backup =
     "random", the low-latency choice for large batches)."""
     assert backup in ("primary", "random")

@@ -92,7 +92,7 @@ struct Dims {
   int qkv_dim() const { return q_dim() + 2 * kv_dim(); }
 };
 
-// Cache shape (Sec. 4.2.2): fan-out per accept length as running offsets.  Accept length k owns the F_k =
+// Cache shape (Sec. 4.1.2): fan-out per accept length as running offsets.  Accept length k owns the F_k =
 // off[k+1] - off[k] consecutive branch rows off[k] .. off[k+1]-1 of its sequence; off[K+1] is the rows per sequence.
 // The uniform shape is off[k] = k F.  Passed to kernels by value.
 struct FanTable {

@@ -196,7 +196,7 @@ __global__ void rope_append_kernel(const float* qkv, const RowDesc* rows, const 
   for (int c = threadIdx.x; c < kvd; c += blockDim.x) Elem<T>::store(vdst + c, src[qd + kvd + c]);
 }
 
-// Input token of every branch row at depth `step`: the cache key (step 0) or the previous step's token.
+// p[0 .. n-1] = v
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

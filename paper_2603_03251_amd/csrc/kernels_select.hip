@@ -37,7 +37,7 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
 // One block per row.  Every thread keeps the best FMAX keys of its strided share in sorted registers; then F
 // rounds of a block-wide maximum over the threads' current heads pick the row's top F in order.
 // groups == 0: every row takes F ids, stored at ids[row][F].  groups == K+1 (the fan-out of a round, Sec. 4.1.1 with
-// the cache shape of Sec. 4.2.2): row (b, k) takes F_k ids, stored at ids[b][off[k] ..].
+// the cache shape of Sec. 4.1.2): row (b, k) takes F_k ids, stored at ids[b][off[k] ..].
 // gridDim.y > 1: the vocabulary is cut into gridDim.y parts, block (row, part) leaves the sorted keys of its part's
 // top F in part_keys[row][part][FMAX] and top_f_merge_kernel picks the row's top F among them (keys are unique, so
 // the result is the same as that of one block).
@@ -569,7 +569,7 @@ int launch_top_f(const float* logits, int64_t ld, const int32_t* exclude, int ro
   return run_top_f<16>(logits, ld, exclude, rows, V, F, 0, none, ids, scratch, s);
 }
 
-// Random-token backup speculator (Sec. 4.4): token i of sequence b is the 64-bit hash of (seed, backup stream, b, i, 0)
+// Random-token backup speculator (Sec. 4.3): token i of sequence b is the 64-bit hash of (seed, backup stream, b, i, 0)
 // modulo the vocabulary size.
 __global__ void backup_random_kernel(int32_t* __restrict__ tokens, int B, int K, int V, uint64_t seed) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
@@ -596,7 +596,7 @@ int launch_top_f_fan(const float* logits, int64_t ld, const int32_t* exclude, in
   return run_top_f<16>(logits, ld, exclude, rows, V, 0, K + 1, fan, ids, scratch, s);
 }
 
-// Saguaro sampling scheme sigma_{F,C} (Sec. 4.3) on rows of logits, in place: the F tokens in ids[row] (the row's own
+// Saguaro sampling scheme sigma_{F,C} (Sec. 4.2.1) on rows of logits, in place: the F tokens in ids[row] (the row's own
 // top-F) get T log C added, which multiplies their weight exp(z/T) by C.  Greedy rows (T == 0) are left alone.
 __global__ void sigma_shift_kernel(float* __restrict__ logits, int64_t ld, const float* __restrict__ temperature,
                                    int rows_per_seq, int rows, int F, const int32_t* __restrict__ ids, float log_c) {

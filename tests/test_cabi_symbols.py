@@ -38,7 +38,7 @@ def test_argument_errors_are_reported_without_a_gpu():
 
 
 def test_geometric_cache_shape_equals_the_oracles_integer_shape():
-    """Sec. 4.2.2 theorem: the library's host-side calculator against the oracle over a grid, and its argument checks."""
+    """Sec. 4.1.2 theorem: the library's host-side calculator against the oracle over a grid, and its argument checks."""
     from oracle import ssd_oracle as O
     from paper_2603_03251_amd import binding as b
     n = 0

@@ -126,7 +126,7 @@ def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows, ragg
 
 
 def test_full_size_round_with_the_geometric_cache_shape(B, draft_1b):
-    """The headline workload's 24 branch rows spread over the accept lengths by the theorem of Sec. 4.2.2 (acceptance
+    """The headline workload's 24 branch rows spread over the accept lengths by the theorem of Sec. 4.1.2 (acceptance
     rate 0.8, power-law exponent 0.5) instead of 4 each: same launch configuration, ragged row order."""
     shape, model, om = draft_1b
     wl = I.WORKLOADS["1b_p1024_f4"]

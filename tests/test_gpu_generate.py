@@ -1,6 +1,6 @@
 """Alg. 1 run for many rounds through the C-ABI on the tiny fp32 pair: every round verifies the pending speculation
 with the target, pre-speculates with the draft, looks the realised outcome up, commits, and on a miss falls back to
-just-in-time drafting with the same draft (Sec. 4.1: backup speculator = primary).  Only the loop is Python; every
+just-in-time drafting with the same draft (Sec. 4.3: backup speculator = primary).  Only the loop is Python; every
 step runs in the library's kernels.
 
 What is fixed independently of any implementation (Sec. 2.1, lossless verification): with greedy decoding the
@@ -154,7 +154,7 @@ def test_identical_draft_has_everything_accepted_and_every_outcome_cached(B):
 
 
 def test_greedy_ssd_with_a_geometric_cache_is_lossless_and_decides_like_the_oracle(B):
-    """Sec. 4.2.2: the cache shape changes which outcomes hit, never the text."""
+    """Sec. 4.1.2: the cache shape changes which outcomes hit, never the text."""
     wl = I.WORKLOADS["tiny_f32"]
     shape, K = wl.draft, wl.round.K
     fan = B.ssd_geometric_fanout((K + 1) * wl.round.F, K, 0.6, 0.5, 8)
@@ -179,7 +179,7 @@ def test_greedy_ssd_with_a_geometric_cache_is_lossless_and_decides_like_the_orac
 
 
 def test_greedy_ssd_with_the_random_token_backup_decides_like_the_oracle(B):
-    """Sec. 4.4: the low-latency backup speculator.  Same random tokens as the oracle's (same generator, same round
+    """Sec. 4.3: the low-latency backup speculator.  Same random tokens as the oracle's (same generator, same round
     seeds), so the same accept lengths and hits round by round, and the target's own text."""
     wl = I.WORKLOADS["tiny_f32"]
     shape, K, F = wl.draft, wl.round.K, wl.round.F

@@ -46,7 +46,7 @@ def _in_row_order(a, fan):
 
 
 def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=0.0, lens=None):
-    """F: the uniform fan-out, or F_0..F_K (Sec. 4.2.2).  lens: prompt length per sequence (real prefill only;
+    """F: the uniform fan-out, or F_0..F_K (Sec. 4.1.2).  lens: prompt length per sequence (real prefill only;
     default P for all)."""
     tol = TOL[shape.dtype]
     w = I.make_weights(shape, seed)
@@ -265,7 +265,7 @@ def test_small_bf16_head_dim_128_untied(B):
 
 
 def test_small_bf16_geometric_cache_shape(B):
-    """Sec. 4.2.2: a round whose fan-out follows the theorem's geometric shape; the library's integer shape equals the
+    """Sec. 4.1.2: a round whose fan-out follows the theorem's geometric shape; the library's integer shape equals the
     oracle's, the rows run accept length by accept length, and the fused pass serves the 13 rows per sequence."""
     K = 3
     fan = B.ssd_geometric_fanout(13, K, 0.7, 0.5, 8)
@@ -422,7 +422,7 @@ def test_argument_validation(B):
 
 @pytest.mark.parametrize("fan", [None, [2, 4, 1, 3]])
 def test_small_bf16_saguaro_sampling_scheme(B, fan):
-    """Sec. 4.3: branches drawn from sigma_{F,C}; with a fan-out per accept length, depth i lowers its top F_i.  Teacher-forced on the oracle's tokens, the cached logits must be the
+    """Sec. 4.2.1: branches drawn from sigma_{F,C}; with a fan-out per accept length, depth i lowers its top F_i.  Teacher-forced on the oracle's tokens, the cached logits must be the
     oracle's lowered logits wherever the step's top-F set is not a near-tie at this precision (there, lowering a
     different token is equally right: the row is then compared with the shift taken out on both sides)."""
     shape, batch, P, K, F, seed, T, Cw = SMALL_BF16, 2, 61, 3, 3, 17, 1.0, 0.3

@@ -196,7 +196,7 @@ def test_verify_identical_models_accept_all(B):
 
 
 def test_backup_random_tokens_equal_the_oracles(B):
-    """Sec. 4.4 random-token backup: bit-exact against the oracle's generator, batch of sequences, full vocabulary."""
+    """Sec. 4.3 random-token backup: bit-exact against the oracle's generator, batch of sequences, full vocabulary."""
     for seed, nb, K, V in [(0, 1, 5, 128256), (12345678901234567, 16, 7, 128256), (7, 3, 15, 97), (1, 5, 1, 1)]:
         out = torch.full((nb, K), -1, dtype=torch.int32, device="cuda")
         B.ssd_backup_random(seed, V, out)

@@ -1,4 +1,4 @@
-"""The target's side of a round at the 70B layer shape (Sec. 4.1: verification of K speculated tokens is one forward
+"""The target's side of a round at the 70B layer shape (Sec. 2.1 and Alg. 1: verification of K speculated tokens is one forward
 of the target over K+1 positions, running while the draft pre-speculates).
 
 The oracle cannot run 80 layers of this shape in seconds, so parity is taken on a model with the 70B per-layer shape

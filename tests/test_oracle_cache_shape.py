@@ -1,4 +1,4 @@
-"""Pins of the oracle's cache shape (Sec. 4.2.2, Theorem "Geometric Fan-Out") and of the round with a fan-out that
+"""Pins of the oracle's cache shape (Sec. 4.1.2, Theorem "Geometric Fan-Out") and of the round with a fan-out that
 differs per accept length (no GPU).
 
 The closed form is checked against what defines it: a numerical constrained maximiser of the hit-rate objective the

@@ -216,7 +216,7 @@ def test_verify_zero_probability_token_is_rejected_and_never_bonus():
         assert out.accept_len == 0 and out.bonus != 4
 
 
-# ----------------------------------------------------------------- random-token backup speculator (Sec. 4.4)
+# ----------------------------------------------------------------- random-token backup speculator (Sec. 4.3)
 
 def test_random_speculation_is_uniform_reproducible_and_keyed_by_sequence_and_step():
     V, K = 7, 5

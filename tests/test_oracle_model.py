@@ -276,7 +276,7 @@ def test_draft_equal_to_target_accepts_all_and_always_hits():
 
 
 def test_saguaro_sampling_inside_the_round():
-    """Sec. 4.3: branches decoded with sigma_{F,C}.  Pinned by consequences of the definition rather than by the
+    """Sec. 4.2.1: branches decoded with sigma_{F,C}.  Pinned by consequences of the definition rather than by the
     formula: C = 1 changes nothing; under teacher forcing the returned logits differ from the model's own by exactly
     T log C on the model's top-F tokens and by nothing elsewhere; with C = 0 a top-F token is never drawn; and the
     fan-out keys (ranked on the model's own logits) do not depend on C."""
@@ -316,7 +316,7 @@ def test_saguaro_sampling_inside_the_round():
 
 
 def test_greedy_ssd_with_the_random_token_backup_is_lossless():
-    # Sec. 4.4: after a miss the next speculation is K random tokens; the text is still the target's own
+    # Sec. 4.3: after a miss the next speculation is K random tokens; the text is still the target's own
     shape = I.WORKLOADS["tiny_f32"].draft
     tw = I.make_weights(shape, 5)
     target = O.Model.from_weights(shape, tw)
