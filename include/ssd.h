@@ -94,7 +94,16 @@ typedef struct {
   int32_t K;         /* 1..SSD_MAX_K drafted tokens per speculation = decode steps per branch */
   int32_t F;         /* 1..SSD_MAX_F bonus-token candidates per accept length */
   int32_t max_trunk; /* capacity of the trunk KV in positions, per sequence */
+  int32_t flags;     /* 0, or SSD_CTX_* bits: which kernels serve the context (results are the same to rounding) */
 } ssd_round_config;
+
+/* ssd_round_config.flags.  By default a context whose model and shape the fused decode pass supports (bf16, head_dim 64)
+ * runs every batched forward as one persistent kernel. */
+enum {
+  SSD_CTX_PER_OPERATOR = 1, /* never the fused pass: one kernel per operator */
+  SSD_CTX_FUSED_PHASES = 2  /* the fused pass as one launch per phase instead of one persistent launch: no grid barrier, so
+                               no need for all its workgroups to be resident at once; same bits as the persistent launch */
+};
 
 /* Read-only device views of the context's state, for tests and for the verifier's payload. */
 typedef struct {
@@ -110,6 +119,7 @@ typedef struct {
                                    rows per pass) keep both head-major with T = max_trunk rounded up to 64: keys
                                    [B][Hkv][T][D], values transposed per 32-position block [B][Hkv][T/32][D][32] */
   int32_t batch, K, F, vocab, d_model, max_trunk;
+  int32_t fused_pass;          /* 0: one kernel per operator; 1: fused pass, one launch per phase; 2: one persistent launch */
 } ssd_views;
 
 const char* ssd_last_error(void);
@@ -247,6 +257,10 @@ size_t ssd_top_f_workspace_bytes(int32_t rows);
  * argmax_t logits[r][t]/T[r] + g(seed, stream 2, row_base + r, step, t) in fp64.  d_temperature float [rows]. */
 int ssd_sample(const float* d_logits, int64_t ld, const float* d_temperature, int32_t rows, int32_t V,
                uint64_t seed, int32_t row_base, int32_t step, int32_t* d_out, void* stream);
+/* Test aid: the same draw with every token of a sampled row scored in fp64 (ssd_sample scans in fp32 and scores in fp64
+ * only the tokens within the fp32 error bound of the maximum; both must give the same token). */
+int ssd_sample_fp64_scan(const float* d_logits, int64_t ld, const float* d_temperature, int32_t rows, int32_t V,
+                         uint64_t seed, int32_t row_base, int32_t step, int32_t* d_out, void* stream);
 
 /* ---- generic extend (the glue step on its own; also how a target model is run) ------------------ */
 
@@ -257,8 +271,34 @@ int ssd_ctx_extend(ssd_ctx* ctx, const int32_t* d_tokens, int32_t T, int32_t off
 
 /* The host keeps only an upper bound of trunk_len (it grows by K+1 per commit, since accept lengths live on the
  * device).  This call SYNCHRONISES `stream`, reads the true lengths back and tightens the bound; use it between
- * rounds of a long generation, never inside the hot path. */
+ * rounds of a long generation, never inside the hot path.  EHIP if a bounded wait of the fused pass has expired
+ * (see ssd_ctx_status). */
 int ssd_ctx_refresh_bounds(ssd_ctx* ctx, void* stream);
+
+/* Health of a context served by the persistent fused pass.  That kernel separates its phases by grid barriers, which
+ * complete only while all its workgroups are resident at once.  The library checks at ssd_ctx_create that they fit the
+ * device and makes every persistent launch of the process wait (on the device) for the previous one wherever that ran on
+ * another stream; a kernel of the caller's own that occupies compute units for seconds could still starve a barrier.
+ * Every wait inside the kernel is bounded: on expiry the kernel sets a word in pinned host memory and ends.  From then
+ * on the context's barrier state and everything computed since are invalid, and ssd_prespeculate, ssd_cache_lookup,
+ * ssd_ctx_commit, ssd_ctx_extend, ssd_ctx_prefill, ssd_ctx_refresh_bounds and ssd_ctx_read_timing return SSD_EHIP as soon
+ * as the host sees the word (calls enqueued before that have returned SSD_OK: check ssd_ctx_status after synchronising
+ * when in doubt).
+ *   ssd_ctx_status   non-blocking, no GPU work: SSD_OK, or SSD_EHIP once a wait has expired.
+ *   ssd_ctx_recover  SYNCHRONISES the device, rebuilds the barrier state, clears the fault and invalidates the
+ *                    speculation cache; trunk_len is kept, the trunk's contents behind it may be partly written
+ *                    (the next glue extend rewrites them). */
+int ssd_ctx_status(const ssd_ctx* ctx);
+int ssd_ctx_recover(ssd_ctx* ctx);
+
+/* Test aids for contexts served by the fused pass (ESTATE elsewhere); never needed in production.
+ *   SSD_DEBUG_BARRIER_EPOCH  the grid barrier numbers its barriers on from launch to launch in 32 bits; restart the
+ *                            count at `value` (SYNCHRONISES the device), e.g. shortly before the wrap.
+ *   SSD_DEBUG_SPIN_LIMIT     polls a bounded wait takes before it gives up (0 = the default, seconds of wall time): a
+ *                            tiny value makes the waits of the next launches expire, which is how the error path is
+ *                            tested without ever hanging a kernel. */
+enum { SSD_DEBUG_BARRIER_EPOCH = 1, SSD_DEBUG_SPIN_LIMIT = 2 };
+int ssd_ctx_debug_set(ssd_ctx* ctx, int32_t what, uint32_t value);
 
 /* Measurement aid.  With timing on, ssd_prespeculate records HIP events on its stream around the glue extend,
  * the fan-out and each of the K branch-decode steps.  ssd_ctx_read_timing waits for the last event of the most

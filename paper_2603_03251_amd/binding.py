@@ -18,6 +18,8 @@ LIB_PATH = os.path.join(HERE, "libssd_hip.so")
 SSD_OK, SSD_EINVAL, SSD_ESTATE, SSD_EHIP, SSD_ENOMEM = 0, -1, -2, -3, -4
 SSD_F32, SSD_BF16 = 0, 1
 SSD_MAX_F, SSD_MAX_K = 16, 15
+SSD_CTX_PER_OPERATOR, SSD_CTX_FUSED_PHASES = 1, 2
+SSD_DEBUG_BARRIER_EPOCH, SSD_DEBUG_SPIN_LIMIT = 1, 2
 
 
 class SsdError(RuntimeError):
@@ -39,7 +41,7 @@ class ssd_model_weights(C.Structure):
 
 
 class ssd_round_config(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("batch", "K", "F", "max_trunk")]
+    _fields_ = [(n, C.c_int32) for n in ("batch", "K", "F", "max_trunk", "flags")]
 
 
 class ssd_views(C.Structure):
@@ -47,7 +49,7 @@ class ssd_views(C.Structure):
                 ("d_logits", C.c_void_p), ("d_hidden", C.c_void_p), ("d_glue_logits", C.c_void_p),
                 ("d_glue_hidden", C.c_void_p), ("h_trunk_k", C.POINTER(C.c_void_p)),
                 ("h_trunk_v", C.POINTER(C.c_void_p))] + \
-               [(n, C.c_int32) for n in ("batch", "K", "F", "vocab", "d_model", "max_trunk")]
+               [(n, C.c_int32) for n in ("batch", "K", "F", "vocab", "d_model", "max_trunk", "fused_pass")]
 
 
 EXPORTS = {
@@ -79,6 +81,11 @@ EXPORTS = {
     "ssd_top_f_workspace_bytes": (C.c_size_t, [C.c_int32]),
     "ssd_sample": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.c_int32,
                              C.c_int32, C.c_void_p, C.c_void_p]),
+    "ssd_sample_fp64_scan": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.c_int32,
+                                       C.c_int32, C.c_void_p, C.c_void_p]),
+    "ssd_ctx_status": (C.c_int, [C.c_void_p]),
+    "ssd_ctx_recover": (C.c_int, [C.c_void_p]),
+    "ssd_ctx_debug_set": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint32]),
     "ssd_ctx_extend": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "ssd_ctx_refresh_bounds": (C.c_int, [C.c_void_p, C.c_void_p]),
     "ssd_ctx_enable_timing": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -183,16 +190,16 @@ def ssd_model_destroy(model: int) -> None:
     _check(lib.ssd_model_destroy(model))
 
 
-def ssd_ctx_create(model: int, batch: int, K: int, F: int, max_trunk: int) -> int:
-    cfg = ssd_round_config(batch, K, F, max_trunk)
+def ssd_ctx_create(model: int, batch: int, K: int, F: int, max_trunk: int, flags: int = 0) -> int:
+    cfg = ssd_round_config(batch, K, F, max_trunk, flags)
     out = C.c_void_p()
     _check(lib.ssd_ctx_create(model, C.byref(cfg), C.byref(out)))
     return out.value
 
 
-def ssd_ctx_create_fanout(model: int, batch: int, K: int, fanout: Sequence[int], max_trunk: int) -> int:
+def ssd_ctx_create_fanout(model: int, batch: int, K: int, fanout: Sequence[int], max_trunk: int, flags: int = 0) -> int:
     assert len(fanout) == K + 1
-    cfg = ssd_round_config(batch, K, 0, max_trunk)
+    cfg = ssd_round_config(batch, K, 0, max_trunk, flags)
     fan = (C.c_int32 * (K + 1))(*[int(f) for f in fanout])
     out = C.c_void_p()
     _check(lib.ssd_ctx_create_fanout(model, C.byref(cfg), fan, C.byref(out)))
@@ -294,6 +301,25 @@ def ssd_sample(logits: torch.Tensor, temperature: torch.Tensor, seed: int, row_b
                out: torch.Tensor, stream=None) -> None:
     rows, V = logits.shape
     _check(lib.ssd_sample(_ptr(logits), V, _ptr(temperature), rows, V, seed, row_base, step, _ptr(out), _stream(stream)))
+
+
+def ssd_sample_fp64_scan(logits: torch.Tensor, temperature: torch.Tensor, seed: int, row_base: int, step: int,
+                         out: torch.Tensor, stream=None) -> None:
+    rows, V = logits.shape
+    _check(lib.ssd_sample_fp64_scan(_ptr(logits), V, _ptr(temperature), rows, V, seed, row_base, step, _ptr(out),
+                                    _stream(stream)))
+
+
+def ssd_ctx_status(ctx: int) -> None:
+    _check(lib.ssd_ctx_status(ctx))
+
+
+def ssd_ctx_recover(ctx: int) -> None:
+    _check(lib.ssd_ctx_recover(ctx))
+
+
+def ssd_ctx_debug_set(ctx: int, what: int, value: int) -> None:
+    _check(lib.ssd_ctx_debug_set(ctx, what, value))
 
 
 def ssd_ctx_extend(ctx: int, tokens: torch.Tensor, offset: int, logits: Optional[torch.Tensor], stream=None) -> None:

@@ -162,7 +162,8 @@ int launch_top_f_fan(const float* logits, int64_t ld, const int32_t* exclude, in
                      int32_t* ids, void* scratch, hipStream_t s);
 size_t top_f_scratch_bytes(int rows);
 int launch_sample(const float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int V,
-                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, void* scratch, hipStream_t s);
+                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, void* scratch, int exact_scan,
+                  hipStream_t s);
 size_t sample_scratch_bytes(int rows);
 int launch_sigma_shift(float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int F,
                        const int32_t* ids, float log_c, hipStream_t s);

@@ -16,6 +16,7 @@ constexpr int kFusedMaxRows = 48;   // rows of one pass (three 16-row MFMA tiles
 constexpr int kFusedActPlanes = 2;   // bf16 planes of the SwiGLU output (1 = rounded to bf16, 2 = head + remainder)
 constexpr int kFusedClockSlots = 8;  // clock probes per phase and workgroup (see stamp())
 constexpr int kFusedMaxSlices = 4;   // most k-slices of a linear layer
+constexpr unsigned kFusedSpinLimit = 4000000u;   // polls of a bounded wait (seconds of wall time) before it gives up
 
 // A linear layer in "stream order".  The [N][Kd] matrix is cut into 1 KiB MFMA tiles (16 features x 32 inputs,
 // stored as the 64 lanes of an MFMA 16x16x32 A operand hold them).  A unit is AT feature tiles over the whole
@@ -77,7 +78,9 @@ struct FusedParams {
   float* logits;   int64_t logits_ld;      // may be null
   float* hidden;   int64_t hidden_ld;      // may be null
   unsigned* bar;                           // 2048 grid-barrier words, zeroed once; epochs carry over between launches
-  unsigned* err;                           // set to 1 if a bounded wait expired
+  unsigned* err;                           // set to 1 if a bounded wait expired (host-pinned memory: the host reads it
+                                           // without synchronising)
+  unsigned spin_limit;                     // polls a bounded wait may take before it gives up
   unsigned long long* prof;                // optional [phases][kFusedClockSlots][nwg] real-time-counter ticks, or null
   int nwg;
   int deep;                                // 1: every linear layer has a multiple of 4 k-tiles per wavefront and unit
@@ -104,6 +107,8 @@ bool fused_supported(const Dims& d, int max_rows);
 // persistent = 0: one launch per phase (a debugging aid that needs no co-residency).
 int launch_fused(const FusedParams& p, int first, int last, int persistent, hipStream_t s);
 int fused_grid_size(int* out);
+// EINVAL unless `nwg` workgroups of every instance of the persistent kernel can be resident at once on the current device
+int fused_check_residency(int nwg);
 // Barrier words (kFusedSyncWords of them + the error word behind) as a finished barrier number `epoch0` leaves them;
 // 0 for a new context.  The epoch counts on from launch to launch and wraps after 2^32 barriers.
 constexpr int kFusedSyncWords = 2048;

@@ -48,7 +48,6 @@ typedef __attribute__((address_space(1))) bf16_t gbf16;
 constexpr int MP = kFusedMaxRows;
 constexpr int NPA = kFusedActPlanes;
 static_assert(kFusedActPlanes == 2, "the down-projection shares the two-plane streaming loop");
-constexpr unsigned kSpinLimit = 4000000u;
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Workgroup barrier that waits for LDS traffic only: global loads issued before it stay in flight.
@@ -152,6 +151,7 @@ struct Grid {
   int persistent;
   int nwg;
   int* dead;   // LDS
+  unsigned spin_limit;   // polls a bounded wait may take before it gives up
 };
 
 __device__ __forceinline__ void grid_arrive(Grid& g) {
@@ -173,8 +173,8 @@ __device__ __forceinline__ bool grid_wait(Grid& g) {
     unsigned spins = 0;
     // (compared as a signed difference: the epoch counts on across launches and may wrap)
     while ((int)(__hip_atomic_load(g.bar + kBarFlags + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - g.epoch) < 0) {
-      if (++spins > kSpinLimit) {
-        __hip_atomic_store(g.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (++spins > g.spin_limit) {
+        __hip_atomic_store(g.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         *g.dead = 1;
         break;
       }
@@ -341,8 +341,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
 #pragma unroll
           for (int q = 0; q < kFusedMaxSlices - 1; ++q)
             if ((pending >> q & 1u) && fix_ready(pv[q])) pending &= ~(1u << q);
-          if (pending && ++spins > kSpinLimit) {
-            __hip_atomic_store(grid.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (pending && ++spins > grid.spin_limit) {
+            __hip_atomic_store(grid.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             *grid.dead = 1;
             break;
           }
@@ -1023,7 +1023,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
   wg_barrier();
   // The barrier counts on from where the previous launch stopped (its last epoch is kept in a word of its own), so
   // the barrier words never have to be cleared between launches.
-  Grid grid{p.bar, p.err, persistent ? p.bar[kBarEpochWord] : 0u, persistent, p.nwg, &dead};
+  Grid grid{p.bar, p.err, persistent ? p.bar[kBarEpochWord] : 0u, persistent, p.nwg, &dead, p.spin_limit};
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t h_stride = (int64_t)MP * p.d;
   const int64_t ssq_stride = (int64_t)(p.d >> 4) * MP;
@@ -1193,9 +1193,22 @@ __global__ void copy_kv_fused_kernel(bf16_t* trunk_k, bf16_t* trunk_vt, const bf
   trunk_vt[head + (int64_t)(pos >> 5) * 2048 + d * 32 + (pos & 31)] = src_v[idx];
 }
 
+constexpr size_t kFusedLdsBytes = 96 * 1024;   // reduction tiles (<= 8 wavefronts x 12 tiles x 1 KiB); also keeps one workgroup per CU
+
+template <int MT, bool DEEP>
+int check_residency_mt(int nwg, int cus) {
+  SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
+  int per_cu = 0;
+  SSD_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fused_kernel<MT, DEEP>, kFusedThreads, kFusedLdsBytes));
+  SSD_CHECK_ARG((int64_t)per_cu * cus >= nwg,
+                "fused pass: %d workgroups cannot be resident at once (%d per compute unit x %d compute units): the grid barrier "
+                "would never complete", nwg, per_cu, cus);
+  return SSD_OK;
+}
+
 template <int MT, bool DEEP>
 int launch_mt(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
-  const size_t lds = 96 * 1024;   // reduction tiles (<= 8 wavefronts x 12 tiles x 1 KiB); also keeps one workgroup per CU
+  const size_t lds = kFusedLdsBytes;
   static bool configured = false;
   if (!configured) {
     SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -1272,6 +1285,19 @@ int fused_grid_size(int* out) {
     return SSD_EINVAL;
   }
   *out = cus;
+  return SSD_OK;
+}
+
+int fused_check_residency(int nwg) {
+  int dev = 0, cus = 0;
+  SSD_HIP(hipGetDevice(&dev));
+  SSD_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  SSD_TRY((check_residency_mt<1, true>(nwg, cus)));
+  SSD_TRY((check_residency_mt<2, true>(nwg, cus)));
+  SSD_TRY((check_residency_mt<3, true>(nwg, cus)));
+  SSD_TRY((check_residency_mt<1, false>(nwg, cus)));
+  SSD_TRY((check_residency_mt<2, false>(nwg, cus)));
+  SSD_TRY((check_residency_mt<3, false>(nwg, cus)));
   return SSD_OK;
 }
 

@@ -619,7 +619,8 @@ size_t sample_scratch_bytes(int rows) { return (size_t)rows * kSampleMaxParts * 
 
 // scratch: sample_scratch_bytes(rows) of device memory, or null (then every row is one block)
 int launch_sample(const float* logits, int64_t ld, const float* temperature, int rows_per_seq, int rows, int V,
-                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, void* scratch, hipStream_t s) {
+                  uint64_t seed, int row_base, int step, int32_t* out, int64_t out_stride, void* scratch, int exact_scan,
+                  hipStream_t s) {
   if (rows <= 0) return SSD_OK;
   int parts = 1;
   if (scratch) {
@@ -629,10 +630,8 @@ int launch_sample(const float* logits, int64_t ld, const float* temperature, int
     parts = parts < kSampleMaxParts ? parts : kSampleMaxParts;
     parts = parts < 1 ? 1 : parts;
   }
-  // SSD_SAMPLE_EXACT_SCAN=1: score every token of a sampled row in fp64 instead of pre-selecting in fp32 (a test aid: both
-  // give the same token)
-  const char* env = getenv("SSD_SAMPLE_EXACT_SCAN");
-  const int exact_scan = env && atoi(env) != 0;
+  // exact_scan: score every token of a sampled row in fp64 instead of pre-selecting in fp32 (a test aid: both give the
+  // same token)
   sample_kernel<<<dim3(rows, parts), kSelBlock, 0, s>>>(logits, ld, temperature, rows_per_seq, V, seed, row_base, step, out,
                                                         out_stride, (ScoreId*)scratch, exact_scan);
   SSD_HIP(hipGetLastError());

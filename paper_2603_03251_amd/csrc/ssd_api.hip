@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -128,7 +129,9 @@ struct ssd_ctx {
   FusedParams fp{};            // everything that does not change between passes
   FusedLayer* fused_layers_dev = nullptr;
   unsigned* fused_bar = nullptr;
-  unsigned* fused_err = nullptr;
+  unsigned* fused_err = nullptr;         // host-pinned word the kernel sets when a bounded wait expires
+  hipEvent_t fused_done = nullptr;       // recorded behind every persistent launch of this context
+  int flags = 0;
   int64_t fused_sync_words = 0; // barrier words, zeroed once (the barrier's epoch carries over from launch to launch)
   int64_t part_entries = 0;    // per-layer capacity of the attention partial buffers, in query rows
   unsigned long long* phase_clocks = nullptr;
@@ -226,6 +229,26 @@ int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
   return SSD_OK;
 }
 
+// Persistent launches spin on grid barriers, so every workgroup of one must be resident at once: two of them running
+// side by side (two contexts, or one context driven from two streams) could each hold part of the compute units and
+// wait for the rest for ever.  Every persistent launch therefore waits, on the device, for the previous one of the
+// process wherever that ran on another stream.
+std::mutex g_fused_mu;
+hipEvent_t g_fused_last_event = nullptr;
+hipStream_t g_fused_last_stream = nullptr;
+const ssd_ctx* g_fused_last_ctx = nullptr;
+
+// Once a bounded wait of the fused pass has expired the context's barrier state and everything computed since are
+// invalid: every later call fails until ssd_ctx_recover.  The word lives in pinned host memory, so this costs one load.
+int ctx_fault(const ssd_ctx* c, const char* who) {
+  if (c->fused_mode && c->fused_err && *(volatile const unsigned*)c->fused_err) {
+    set_error("%s: a bounded wait inside the fused pass expired on this context (were the compute units shared with another "
+              "persistent kernel?); results since then are invalid, call ssd_ctx_recover", who);
+    return SSD_EHIP;
+  }
+  return SSD_OK;
+}
+
 // The same pass through the fused kernel: attention work split for this pass's shape, then one launch per group of
 // whole sequences that fits kFusedMaxRows rows (one launch for the few-row workloads the kernel is built for; a batch
 // with more rows streams the weights once per group).
@@ -267,6 +290,12 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
   }
   const int last = (logits || hidden) ? fused_last_phase(p.L) : fused_last_phase(p.L) - 1;
   const bool timed = c->timing && branch_depth >= 0 && 2 * branch_depth + 1 < (int)c->kernel_events.size();
+  const bool persistent = c->fused_mode == 2;
+  std::unique_lock<std::mutex> serial(g_fused_mu, std::defer_lock);
+  if (persistent) {
+    serial.lock();
+    if (g_fused_last_event && g_fused_last_stream != s) SSD_HIP(hipStreamWaitEvent(s, g_fused_last_event, 0));
+  }
   if (timed) SSD_HIP(hipEventRecord(c->kernel_events[2 * branch_depth], s));
   for (int s0 = 0; s0 < n_seq; s0 += per_pass) {
     const int nb = n_seq - s0 < per_pass ? n_seq - s0 : per_pass;
@@ -287,9 +316,15 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
       set_error("fused pass: attention partial buffer too small (%d splits, %d query tiles)", p.NS, p.QT);
       return SSD_ESTATE;
     }
-    SSD_TRY(launch_fused(p, 0, last, c->fused_mode == 2, s));
+    SSD_TRY(launch_fused(p, 0, last, persistent, s));
   }
   if (timed) SSD_HIP(hipEventRecord(c->kernel_events[2 * branch_depth + 1], s));
+  if (persistent) {
+    SSD_HIP(hipEventRecord(c->fused_done, s));
+    g_fused_last_event = c->fused_done;
+    g_fused_last_stream = s;
+    g_fused_last_ctx = c;
+  }
   return SSD_OK;
 }
 
@@ -390,14 +425,20 @@ int fused_setup(ssd_ctx* c) {
   A((void**)&c->fused_bar, (size_t)(c->fused_sync_words + 64) * 4);
   A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L * c->B);
   SSD_TRY(st);
-  c->fused_err = c->fused_bar + c->fused_sync_words;
+  // every workgroup of a persistent launch has to be resident at once
+  if (c->fused_mode == 2) SSD_TRY(fused_check_residency(p.nwg));
+  {
+    void* host_word = nullptr;
+    hipError_t e = hipHostMalloc(&host_word, 64, hipHostMallocMapped);
+    if (e != hipSuccess) { (void)hipGetLastError(); set_error("hipHostMalloc failed: %s", hipGetErrorString(e)); return SSD_ENOMEM; }
+    c->fused_err = (unsigned*)host_word;
+    *c->fused_err = 0u;
+  }
+  SSD_HIP(hipEventCreateWithFlags(&c->fused_done, hipEventDisableTiming));
   p.bar = c->fused_bar;
   p.err = c->fused_err;
-  {
-    // SSD_FUSED_EPOCH0: start the barrier's epoch count somewhere else than 0 (a test aid: the count wraps after 2^32)
-    const char* env = getenv("SSD_FUSED_EPOCH0");
-    SSD_TRY(fused_init_barrier(c->fused_bar, env ? (unsigned)strtoul(env, nullptr, 0) : 0u, p.nwg));
-  }
+  p.spin_limit = kFusedSpinLimit;
+  SSD_TRY(fused_init_barrier(c->fused_bar, 0u, p.nwg));
   SSD_HIP(hipMemset(p.fix_buf, 0xff, (size_t)L * 3 * p.fix_stride * 4));
   p.deep = 1;   // ring depth of the gate/up and LM-head streaming loops
   for (int l = 0; l < L; ++l)
@@ -482,6 +523,7 @@ static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const
   SSD_CHECK_ARG(cfg->batch >= 1, "batch must be >= 1");
   SSD_CHECK_ARG(cfg->K >= 1 && cfg->K <= SSD_MAX_K, "K must be in 1..%d", SSD_MAX_K);
   SSD_CHECK_ARG(cfg->max_trunk >= 2 * cfg->K + 3, "max_trunk must be at least 2K+3");
+  SSD_CHECK_ARG((cfg->flags & ~(SSD_CTX_PER_OPERATOR | SSD_CTX_FUSED_PHASES)) == 0, "unknown bits in ssd_round_config.flags");
   FanTable fan = {};
   int f_max = 0;
   for (int k = 0; k <= cfg->K; ++k) {
@@ -507,13 +549,12 @@ static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const
   A((void**)&c->trunk_len, sizeof(int32_t) * c->B);
   c->trunk_k.resize(d.n_layers); c->trunk_v.resize(d.n_layers);
   c->suffix_k.resize(d.n_layers); c->suffix_v.resize(d.n_layers);
-  // the fused pass serves every pass of a context it fits (SSD_FUSED=off|phases|persistent overrides, a debugging aid)
+  // the fused pass serves every pass of a context it fits, unless the configuration's flags say otherwise
+  c->flags = cfg->flags;
   c->fused_mode = model->fused_ok && fused_supported(d, c->rows_per_seq) ? 2 : 0;   // rows of one sequence per pass
   if (c->fused_mode && (16 / (d.n_q_heads / d.n_kv_heads)) * (c->K + 1 <= 8 ? 8 : 16) > 64) c->fused_mode = 0;
-  if (const char* env = getenv("SSD_FUSED")) {
-    if (!strcmp(env, "off")) c->fused_mode = 0;
-    else if (!strcmp(env, "phases") && c->fused_mode) c->fused_mode = 1;
-  }
+  if (cfg->flags & SSD_CTX_PER_OPERATOR) c->fused_mode = 0;
+  else if ((cfg->flags & SSD_CTX_FUSED_PHASES) && c->fused_mode) c->fused_mode = 1;
   c->vt_stride = (c->max_trunk + 63) / 64 * 64;
   for (int l = 0; l < d.n_layers; ++l) {
     // fused contexts keep the trunk head-major, with max_trunk rounded up to 64 positions (layouts in fused.h)
@@ -549,7 +590,7 @@ static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const
     hipError_t e = hipMemset(c->trunk_len, 0, sizeof(int32_t) * c->B);
     if (e != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(e)); st = SSD_EHIP; }
   }
-  if (st != SSD_OK) { c->arena.release(); delete c; return st; }
+  if (st != SSD_OK) { ssd_ctx_destroy(c); return st; }
   *out = c;
   return SSD_OK;
 }
@@ -622,6 +663,18 @@ int ssd_geometric_fanout(int32_t budget, int32_t K, double a, double r, int32_t 
 
 int ssd_ctx_destroy(ssd_ctx* c) {
   if (!c) return SSD_OK;
+  {
+    // a later persistent launch must not wait on an event that no longer exists
+    std::lock_guard<std::mutex> lock(g_fused_mu);
+    if (g_fused_last_ctx == c) {
+      (void)hipEventSynchronize(c->fused_done);
+      g_fused_last_event = nullptr;
+      g_fused_last_stream = nullptr;
+      g_fused_last_ctx = nullptr;
+    }
+  }
+  if (c->fused_done) (void)hipEventDestroy(c->fused_done);
+  if (c->fused_err) (void)hipHostFree(c->fused_err);
   for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->kernel_events) (void)hipEventDestroy(e);
   c->arena.release();
@@ -631,6 +684,7 @@ int ssd_ctx_destroy(ssd_ctx* c) {
 
 int ssd_ctx_prefill(ssd_ctx* c, const int32_t* d_tokens, int32_t stride, const int32_t* h_lens, void* stream) {
   SSD_CHECK_ARG(c && d_tokens && h_lens, "ssd_ctx_prefill: null argument");
+  SSD_TRY(ctx_fault(c, "ssd_ctx_prefill"));
   hipStream_t s = (hipStream_t)stream;
   int max_len = 0;
   for (int b = 0; b < c->B; ++b) {
@@ -705,6 +759,7 @@ int ssd_ctx_extend(ssd_ctx* c, const int32_t* d_tokens, int32_t T, int32_t offse
   SSD_CHECK_ARG(c && d_tokens, "ssd_ctx_extend: null argument");
   SSD_CHECK_ARG(T >= 1 && T <= c->K + 1, "extend of %d tokens: must be in 1..K+1", T);
   SSD_CHECK_ARG(offset >= 0, "negative offset");
+  SSD_TRY(ctx_fault(c, "ssd_ctx_extend"));
   if (c->trunk_ub + offset + T > c->max_trunk) {
     set_error("extend would pass max_trunk (%d + %d + %d > %d)", c->trunk_ub, offset, T, c->max_trunk);
     return SSD_ESTATE;
@@ -714,6 +769,7 @@ int ssd_ctx_extend(ssd_ctx* c, const int32_t* d_tokens, int32_t T, int32_t offse
 
 int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temperature, uint64_t round_seed, void* stream) {
   SSD_CHECK_ARG(c && d_pending && d_temperature, "ssd_prespeculate: null argument");
+  SSD_TRY(ctx_fault(c, "ssd_prespeculate"));
   if (c->trunk_ub < 1) { set_error("ssd_prespeculate: the trunk is empty (prefill or load it first)"); return SSD_ESTATE; }
   if (c->trunk_ub + 2 * c->K + 2 > c->max_trunk) {
     set_error("ssd_prespeculate: trunk bound %d + 2K+2 exceeds max_trunk %d", c->trunk_ub, c->max_trunk);
@@ -751,7 +807,7 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
                                  c->saguaro_c > 0.f ? logf(c->saguaro_c) : -INFINITY, s));
     }
     SSD_TRY(launch_sample(c->logits + (size_t)i * V, (int64_t)K * V, d_temperature, RB, M, V, round_seed, 0, i,
-                          c->tokens + i, K, c->sample_scratch, s));
+                          c->tokens + i, K, c->sample_scratch, 0, s));
     SSD_TRY(mark());
   }
   c->have_cache = true;
@@ -761,6 +817,7 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
 int ssd_cache_lookup(ssd_ctx* c, const int32_t* d_accept_len, const int32_t* d_bonus, uint8_t* d_hit, int32_t* d_branch,
                      int32_t* d_spec_tokens, const float** d_logits_ptr, void* stream) {
   SSD_CHECK_ARG(c && d_accept_len && d_bonus && d_hit && d_branch && d_spec_tokens, "ssd_cache_lookup: null argument");
+  SSD_TRY(ctx_fault(c, "ssd_cache_lookup"));
   if (!c->have_cache) { set_error("ssd_cache_lookup before any ssd_prespeculate"); return SSD_ESTATE; }
   return launch_lookup(c->keys, c->tokens, c->logits, d_accept_len, d_bonus, d_hit, d_branch, d_spec_tokens, d_logits_ptr,
                        c->B, c->K, c->fan, c->model->dims.vocab, (hipStream_t)stream);
@@ -768,6 +825,7 @@ int ssd_cache_lookup(ssd_ctx* c, const int32_t* d_accept_len, const int32_t* d_b
 
 int ssd_ctx_commit(ssd_ctx* c, const int32_t* d_accept_len, void* stream) {
   SSD_CHECK_ARG(c && d_accept_len, "ssd_ctx_commit: null argument");
+  SSD_TRY(ctx_fault(c, "ssd_ctx_commit"));
   if (c->trunk_ub < 1) { set_error("ssd_ctx_commit: the trunk is empty"); return SSD_ESTATE; }
   SSD_TRY(launch_commit(c->trunk_len, d_accept_len, c->B, c->K, (hipStream_t)stream));
   c->trunk_ub += c->K + 1;
@@ -789,15 +847,39 @@ int ssd_ctx_refresh_bounds(ssd_ctx* c, void* stream) {
   int ub = 0;
   for (int v : lens) ub = v > ub ? v : ub;
   c->trunk_ub = ub;
+  return ctx_fault(c, "ssd_ctx_refresh_bounds");
+}
+
+int ssd_ctx_status(const ssd_ctx* c) {
+  SSD_CHECK_ARG(c, "ssd_ctx_status: null context");
+  return ctx_fault(c, "ssd_ctx_status");
+}
+
+int ssd_ctx_recover(ssd_ctx* c) {
+  SSD_CHECK_ARG(c, "ssd_ctx_recover: null context");
+  SSD_HIP(hipDeviceSynchronize());
   if (c->fused_mode) {
-    unsigned e = 0;
-    SSD_HIP(hipMemcpy(&e, c->fused_err, sizeof(e), hipMemcpyDeviceToHost));
-    if (e) {
-      set_error("a grid barrier of the fused pass timed out");
-      return SSD_EHIP;
-    }
+    SSD_TRY(fused_init_barrier(c->fused_bar, 0u, c->fp.nwg));
+    SSD_HIP(hipMemset(c->fp.fix_buf, 0xff, (size_t)c->fp.L * 3 * c->fp.fix_stride * 4));
+    *(volatile unsigned*)c->fused_err = 0u;
   }
+  c->have_cache = false;
   return SSD_OK;
+}
+
+int ssd_ctx_debug_set(ssd_ctx* c, int32_t what, uint32_t value) {
+  SSD_CHECK_ARG(c, "ssd_ctx_debug_set: null context");
+  if (!c->fused_mode) { set_error("ssd_ctx_debug_set: the context is not served by the fused pass"); return SSD_ESTATE; }
+  if (what == SSD_DEBUG_BARRIER_EPOCH) {
+    SSD_HIP(hipDeviceSynchronize());
+    return fused_init_barrier(c->fused_bar, value, c->fp.nwg);
+  }
+  if (what == SSD_DEBUG_SPIN_LIMIT) {
+    c->fp.spin_limit = value ? value : kFusedSpinLimit;
+    return SSD_OK;
+  }
+  set_error("ssd_ctx_debug_set: unknown item %d", what);
+  return SSD_EINVAL;
 }
 
 int ssd_ctx_enable_timing(ssd_ctx* c, int32_t on) {
@@ -848,6 +930,7 @@ int ssd_ctx_read_timing(ssd_ctx* c, float* h_ms, int32_t n) {
   SSD_CHECK_ARG(n == c->K + 2 || with_kernels, "ssd_ctx_read_timing: n must be K+2 (or 2K+2 in a context served by the fused pass)");
   if (!c->timing || !c->have_cache) { set_error("ssd_ctx_read_timing: no timed round has run"); return SSD_ESTATE; }
   SSD_HIP(hipEventSynchronize(c->events[c->K + 2]));
+  SSD_TRY(ctx_fault(c, "ssd_ctx_read_timing"));
   for (int i = 0; i < c->K + 2; ++i) SSD_HIP(hipEventElapsedTime(&h_ms[i], c->events[i], c->events[i + 1]));
   for (int i = 0; with_kernels && i < c->K; ++i)
     SSD_HIP(hipEventElapsedTime(&h_ms[c->K + 2 + i], c->kernel_events[2 * i], c->kernel_events[2 * i + 1]));
@@ -894,7 +977,14 @@ int ssd_sample(const float* d_logits, int64_t ld, const float* d_temperature, in
                int32_t row_base, int32_t step, int32_t* d_out, void* stream) {
   SSD_CHECK_ARG(d_logits && d_temperature && d_out, "ssd_sample: null argument");
   SSD_CHECK_ARG(rows >= 0 && V >= 2 && ld >= V, "ssd_sample: rows >= 0, V >= 2, ld >= V required");
-  return launch_sample(d_logits, ld, d_temperature, 1, rows, V, seed, row_base, step, d_out, 1, nullptr, (hipStream_t)stream);
+  return launch_sample(d_logits, ld, d_temperature, 1, rows, V, seed, row_base, step, d_out, 1, nullptr, 0, (hipStream_t)stream);
+}
+
+int ssd_sample_fp64_scan(const float* d_logits, int64_t ld, const float* d_temperature, int32_t rows, int32_t V, uint64_t seed,
+                         int32_t row_base, int32_t step, int32_t* d_out, void* stream) {
+  SSD_CHECK_ARG(d_logits && d_temperature && d_out, "ssd_sample_fp64_scan: null argument");
+  SSD_CHECK_ARG(rows >= 0 && V >= 2 && ld >= V, "ssd_sample_fp64_scan: rows >= 0, V >= 2, ld >= V required");
+  return launch_sample(d_logits, ld, d_temperature, 1, rows, V, seed, row_base, step, d_out, 1, nullptr, 1, (hipStream_t)stream);
 }
 
 int ssd_backup_random(uint64_t seed, int32_t B, int32_t K, int32_t V, int32_t* d_tokens, void* stream) {
@@ -910,6 +1000,7 @@ int ssd_ctx_views(const ssd_ctx* c, ssd_views* out) {
   out->h_trunk_k = (const void* const*)c->trunk_k.data(); out->h_trunk_v = (const void* const*)c->trunk_v.data();
   out->batch = c->B; out->K = c->K; out->F = c->F; out->vocab = c->model->dims.vocab; out->d_model = c->model->dims.d_model;
   out->max_trunk = c->max_trunk;
+  out->fused_pass = c->fused_mode;
   return SSD_OK;
 }
 

@@ -9,6 +9,14 @@ from oracle import ssd_oracle as O
 
 # spec tolerances: relative error of logits / hidden states against the float64 oracle
 TOL = {"bf16": 2e-2, "f32": 1e-4}
+# What the bf16 paths (bf16 weights and KV, fp32 accumulation, activations as head + remainder planes) are measured at
+# against the float64 oracle, with head room of about 2x: a wrongly visible key among thousands, or a lost low-order
+# plane, shows up here long before it reaches the benchmark spec's figure above.  Measured: 1.3e-4 .. 1.8e-3 when both sides
+# start from the same bf16-representable prefix KV (the largest on short prefixes, where the keys the GPU itself rounds
+# to bf16 carry more of the softmax); up to 3.9e-3 when the whole trunk comes from a prefill on the GPU, whose KV is
+# rounded to bf16 while the oracle keeps its own in float64.
+TOL_FUSED_BF16 = 4e-3
+TOL_BF16_OWN_PREFILL = 8e-3
 # decisions that rest on floating point are compared only where the oracle's own margin exceeds this
 MARGIN = 1e-4
 
@@ -20,6 +28,15 @@ def row_rel_err(got: np.ndarray, want: np.ndarray) -> float:
     num = np.abs(got - want).max(axis=1)
     den = np.maximum(np.abs(want).max(axis=1), 1e-30)
     return float((num / den).max())
+
+
+def elem_rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    """The second metric of the parity protocol: max over elements of |got - want| / (|want| + atol) with
+    atol = 1e-2 x the row's RMS, so that entries near zero are held to a fraction of the row's scale."""
+    got = np.asarray(got, np.float64).reshape(-1, got.shape[-1])
+    want = np.asarray(want, np.float64).reshape(-1, want.shape[-1])
+    atol = 1e-2 * np.sqrt((want ** 2).mean(axis=1, keepdims=True))
+    return float((np.abs(got - want) / (np.abs(want) + np.maximum(atol, 1e-30))).max())
 
 
 def rms_rel_err(got: np.ndarray, want: np.ndarray) -> float:

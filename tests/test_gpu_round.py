@@ -11,8 +11,8 @@ import torch
 
 import ssd_inputs as I
 from oracle import ssd_oracle as O
-from tests.gpu_util import (MARGIN, TOL, dev_f32, dev_i32, kv_to_device, oracle_trunk_from_arrays, rms_rel_err,
-                            row_rel_err)
+from tests.gpu_util import (MARGIN, TOL, TOL_BF16_OWN_PREFILL, TOL_FUSED_BF16, dev_f32, dev_i32, elem_rel_err, kv_to_device,
+                            oracle_trunk_from_arrays, rms_rel_err, row_rel_err)
 
 pytestmark = pytest.mark.gpu
 
@@ -45,19 +45,23 @@ def _in_row_order(a, fan):
     return np.concatenate([a[k, :f] for k, f in enumerate(fan)])
 
 
-def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=0.0, lens=None):
+def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=0.0, lens=None, flags=0):
     """F: the uniform fan-out, or F_0..F_K (Sec. 4.1.2).  lens: prompt length per sequence (real prefill only;
-    default P for all)."""
+    default P for all).  flags: ssd_round_config.flags (which kernels serve the context)."""
     tol = TOL[shape.dtype]
     w = I.make_weights(shape, seed)
     om = O.Model.from_weights(shape, w)
     model = B.ssd_model_create(shape, w)
     fan = [F] * (K + 1) if np.ndim(F) == 0 else [int(f) for f in F]
     if np.ndim(F) == 0:
-        ctx = B.ssd_ctx_create(model, batch, K, F, P + 4 * K + 8)
+        ctx = B.ssd_ctx_create(model, batch, K, F, P + 4 * K + 8, flags)
     else:
-        ctx = B.ssd_ctx_create_fanout(model, batch, K, fan, P + 4 * K + 8)
+        ctx = B.ssd_ctx_create_fanout(model, batch, K, fan, P + 4 * K + 8, flags)
     assert B.ssd_ctx_fanout(ctx) == fan
+    if shape.dtype == "bf16":
+        tol = min(tol, TOL_FUSED_BF16 if synthetic_kv else TOL_BF16_OWN_PREFILL)
+    which = B.ssd_ctx_views(ctx).fused_pass
+    assert which == 0 if flags & B.SSD_CTX_PER_OPERATOR else True
     try:
         if synthetic_kv:
             k, v = I.make_prefix_kv(shape, batch, P, seed)
@@ -107,6 +111,9 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
             e_l = row_rel_err(forced["logits"][b], caches[b].logits)
             e_h = row_rel_err(forced["hidden"][b], caches[b].hidden)
             worst = max(worst, e_l, e_h)
+            print(f"[parity] seq {b} ({'fused pass' if which else 'per-operator kernels'}): logits {e_l:.3e}, hidden {e_h:.3e} "
+                  f"(row-max metric); {elem_rel_err(forced['logits'][b], caches[b].logits):.3e}, "
+                  f"{elem_rel_err(forced['hidden'][b], caches[b].hidden):.3e} (elementwise, atol 1e-2 row RMS)", flush=True)
             assert e_l < tol and e_h < tol, (b, e_l, e_h)
             assert rms_rel_err(forced["logits"][b], caches[b].logits) < tol
             # sampled tokens agree wherever the decision is not a near-tie at this precision (at T > 0 the scores are
@@ -166,7 +173,7 @@ def test_small_bf16_fused_pass_group_of_two_and_long_lookahead(B):
     _run_round_parity(B, SMALL_BF16, batch=1, P=45, K=8, F=2, seed=13, synthetic_kv=False)
 
 
-def test_fused_pass_phase_by_phase_equals_persistent(B, monkeypatch):
+def test_fused_pass_phase_by_phase_equals_persistent(B):
     # the same pass as one launch per phase (no grid barrier) and as one persistent launch: identical bits, since
     # every sum is taken in a fixed order
     shape, seed, nb, P, K, F = SMALL_BF16, 21, 2, 50, 3, 3
@@ -176,9 +183,9 @@ def test_fused_pass_phase_by_phase_equals_persistent(B, monkeypatch):
     temps = dev_f32(np.zeros(nb, np.float32))
     outs = []
     for mode in ("phases", "persistent"):
-        monkeypatch.setenv("SSD_FUSED", mode)
         model = B.ssd_model_create(shape, w)
-        ctx = B.ssd_ctx_create(model, nb, K, F, P + 4 * K + 8)
+        ctx = B.ssd_ctx_create(model, nb, K, F, P + 4 * K + 8, B.SSD_CTX_FUSED_PHASES if mode == "phases" else 0)
+        assert B.ssd_ctx_views(ctx).fused_pass == (1 if mode == "phases" else 2)
         try:
             B.ssd_ctx_load_trunk(ctx, kv_to_device(k, "bf16"), kv_to_device(v, "bf16"), P)
             B.ssd_prespeculate(ctx, pending, temps, seed)
@@ -203,12 +210,12 @@ def test_small_bf16_ragged_prompt_lengths_in_one_batch(B):
     _run_round_parity(B, SMALL_BF16, batch=5, P=70, K=3, F=2, seed=19, synthetic_kv=False, lens=[70, 33, 1, 64, 17])
 
 
-def test_small_bf16_ragged_prompt_lengths_per_operator_path(B, monkeypatch):
-    monkeypatch.setenv("SSD_FUSED", "off")
-    _run_round_parity(B, SMALL_BF16, batch=3, P=45, K=3, F=2, seed=29, synthetic_kv=False, lens=[45, 2, 31], temperature=0.7)
+def test_small_bf16_ragged_prompt_lengths_per_operator_path(B):
+    _run_round_parity(B, SMALL_BF16, batch=3, P=45, K=3, F=2, seed=29, synthetic_kv=False, lens=[45, 2, 31], temperature=0.7,
+                      flags=B.SSD_CTX_PER_OPERATOR)
 
 
-def test_fused_pass_barrier_epoch_wraps_around(B, monkeypatch):
+def test_fused_pass_barrier_epoch_wraps_around(B):
     """The grid barrier of the fused pass numbers its barriers on from launch to launch in 32 bits.  A context whose
     count starts shortly before 2^32 passes the wrap inside its second round and must give bit-identical results."""
     shape, batch, P, K, F, seed = SMALL_BF16, 2, 40, 3, 2, 5
@@ -220,8 +227,8 @@ def test_fused_pass_barrier_epoch_wraps_around(B, monkeypatch):
     outs = []
     try:
         for epoch0 in (0, 2 ** 32 - 40):
-            monkeypatch.setenv("SSD_FUSED_EPOCH0", str(epoch0))
             ctx = B.ssd_ctx_create(model, batch, K, F, P + 4 * K + 8)
+            B.ssd_ctx_debug_set(ctx, B.SSD_DEBUG_BARRIER_EPOCH, epoch0)
             try:
                 B.ssd_ctx_load_trunk(ctx, kv_to_device(k, shape.dtype), kv_to_device(v, shape.dtype), P)
                 for rnd in range(3):                       # 4 launches of 11 barriers each per round
@@ -275,11 +282,11 @@ def test_small_bf16_geometric_cache_shape(B):
         assert (free["keys"][:, k, fan[k]:] == -1).all() and (free["keys"][:, k, :fan[k]] >= 0).all()
 
 
-def test_small_bf16_geometric_cache_shape_sampled_per_operator_path(B, monkeypatch):
+def test_small_bf16_geometric_cache_shape_sampled_per_operator_path(B):
     # temperature > 0: the Gumbel noise of a branch is keyed by its row number in the ragged order; kernels launched
     # one by one instead of the fused pass
-    monkeypatch.setenv("SSD_FUSED", "off")
-    _run_round_parity(B, SMALL_BF16, batch=3, P=77, K=4, F=[6, 1, 3, 2, 9], seed=23, synthetic_kv=False, temperature=0.8)
+    _run_round_parity(B, SMALL_BF16, batch=3, P=77, K=4, F=[6, 1, 3, 2, 9], seed=23, synthetic_kv=False, temperature=0.8,
+                      flags=B.SSD_CTX_PER_OPERATOR)
 
 
 def test_tiny_f32_geometric_cache_shape_lookup(B):
@@ -493,19 +500,18 @@ def test_small_bf16_saguaro_sampling_scheme(B, fan):
 
 
 @pytest.mark.parametrize("fused", [True, False])
-def test_small_bf16_rounds_in_sequence_with_rollback(B, fused, monkeypatch):
+def test_small_bf16_rounds_in_sequence_with_rollback(B, fused):
     """Several rounds on one context (App. B "Glue & Recurrence"): after each round the trunk keeps the glue positions
     0..k of the realised accept length and the next glue extend overwrites the rest.  Accept lengths 0, K, 2, 1, K walk
     the trunk across a 32-position block boundary of the value layout; every round's cache must match the oracle's
     round on the oracle's own trunk."""
-    if not fused:
-        monkeypatch.setenv("SSD_FUSED", "off")
     shape, batch, P, K, F, seed = SMALL_BF16, 2, 27, 3, 2, 33
     tol = TOL[shape.dtype]
     w = I.make_weights(shape, seed)
     om = O.Model.from_weights(shape, w)
     model = B.ssd_model_create(shape, w)
-    ctx = B.ssd_ctx_create(model, batch, K, F, P + 6 * (K + 1) + 2 * K + 4)
+    ctx = B.ssd_ctx_create(model, batch, K, F, P + 6 * (K + 1) + 2 * K + 4, 0 if fused else B.SSD_CTX_PER_OPERATOR)
+    assert (B.ssd_ctx_views(ctx).fused_pass == 2) == fused
     try:
         k, v = I.make_prefix_kv(shape, batch, P, seed)
         B.ssd_ctx_load_trunk(ctx, kv_to_device(k, shape.dtype), kv_to_device(v, shape.dtype), P)
@@ -532,3 +538,92 @@ def test_small_bf16_rounds_in_sequence_with_rollback(B, fused, monkeypatch):
     finally:
         B.ssd_ctx_destroy(ctx)
         B.ssd_model_destroy(model)
+
+
+def test_fused_pass_expired_wait_is_reported_and_recovered(B):
+    """Error path of the persistent kernel, forced from the host without hanging anything: with a spin limit of one
+    poll the bounded waits of the next launch expire, every workgroup sets the fault word and leaves the kernel
+    normally.  From then on the hot calls fail with EHIP (instead of handing out a half-written cache), ssd_ctx_status
+    reports the fault without blocking, and after ssd_ctx_recover the context computes the same bits as before."""
+    shape, nb, P, K, F, seed = SMALL_BF16, 2, 50, 3, 2, 41
+    w = I.make_weights(shape, seed)
+    model = B.ssd_model_create(shape, w)
+    ctx = B.ssd_ctx_create(model, nb, K, F, P + 4 * K + 8)
+    try:
+        assert B.ssd_ctx_views(ctx).fused_pass == 2
+        k, v = I.make_prefix_kv(shape, nb, P, seed)
+        kd, vd = kv_to_device(k, "bf16"), kv_to_device(v, "bf16")
+        B.ssd_ctx_load_trunk(ctx, kd, vd, P)
+        pending = dev_i32(I.make_pending(shape, nb, K, seed))
+        temps = dev_f32(np.zeros(nb, np.float32))
+        B.ssd_prespeculate(ctx, pending, temps, seed)
+        good = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx).items()}
+        B.ssd_ctx_status(ctx)                                  # healthy: no exception
+        B.ssd_ctx_debug_set(ctx, B.SSD_DEBUG_SPIN_LIMIT, 1)
+        print("[fault] launching one round whose bounded waits expire after one poll", flush=True)
+        B.ssd_prespeculate(ctx, pending, temps, seed)          # enqueues fine; the kernels give up and end
+        torch.cuda.synchronize()
+        with pytest.raises(B.SsdError) as e:
+            B.ssd_ctx_status(ctx)
+        assert e.value.status == B.SSD_EHIP
+        hit = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+        branch = torch.zeros(nb, dtype=torch.int32, device="cuda")
+        spec = torch.zeros((nb, K), dtype=torch.int32, device="cuda")
+        zero = dev_i32(np.zeros(nb))
+        for call in (lambda: B.ssd_prespeculate(ctx, pending, temps, seed),
+                     lambda: B.ssd_cache_lookup(ctx, zero, zero, hit, branch, spec),
+                     lambda: B.ssd_ctx_commit(ctx, zero),
+                     lambda: B.ssd_ctx_refresh_bounds(ctx)):
+            with pytest.raises(B.SsdError) as e:
+                call()
+            assert e.value.status == B.SSD_EHIP and "ssd_ctx_recover" in str(e.value)
+        B.ssd_ctx_debug_set(ctx, B.SSD_DEBUG_SPIN_LIMIT, 0)    # back to the default
+        B.ssd_ctx_recover(ctx)
+        B.ssd_ctx_status(ctx)
+        with pytest.raises(B.SsdError) as e:                   # the cache was invalidated
+            B.ssd_cache_lookup(ctx, zero, zero, hit, branch, spec)
+        assert e.value.status == B.SSD_ESTATE
+        B.ssd_ctx_load_trunk(ctx, kd, vd, P)                   # the aborted glue extend may have left slots half written
+        B.ssd_prespeculate(ctx, pending, temps, seed)
+        again = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctx).items()}
+        B.ssd_ctx_refresh_bounds(ctx)
+        for name in ("keys", "tokens", "logits", "hidden", "glue_logits"):
+            assert np.array_equal(good[name], again[name]), name
+    finally:
+        B.ssd_ctx_destroy(ctx)
+        B.ssd_model_destroy(model)
+
+
+def test_two_fused_contexts_on_two_streams_take_turns(B):
+    """Two contexts served by the persistent kernel, driven from two streams at once (a draft beside a small target):
+    the library makes each persistent launch wait for the previous one of the process, so neither starves the other's
+    grid barrier, and both give the bits they give alone."""
+    shape, nb, P, K, F = SMALL_BF16, 2, 60, 3, 2
+    models, ctxs, pend, alone = [], [], [], []
+    temps = dev_f32(np.zeros(nb, np.float32))
+    try:
+        for seed in (51, 52):
+            w = I.make_weights(shape, seed)
+            models.append(B.ssd_model_create(shape, w))
+            ctxs.append(B.ssd_ctx_create(models[-1], nb, K, F, P + 4 * K + 8))
+            k, v = I.make_prefix_kv(shape, nb, P, seed)
+            B.ssd_ctx_load_trunk(ctxs[-1], kv_to_device(k, "bf16"), kv_to_device(v, "bf16"), P)
+            pend.append(dev_i32(I.make_pending(shape, nb, K, seed)))
+            B.ssd_prespeculate(ctxs[-1], pend[-1], temps, seed)
+            alone.append({k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctxs[-1]).items()})
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        torch.cuda.synchronize()
+        for rep in range(4):
+            for i in (0, 1):
+                B.ssd_prespeculate(ctxs[i], pend[i], temps, 51 + i, stream=streams[i])
+        torch.cuda.synchronize()
+        for i in (0, 1):
+            B.ssd_ctx_status(ctxs[i])
+            got = {k_: v_.cpu().numpy() for k_, v_ in B.read_cache(ctxs[i]).items()}
+            for name in ("keys", "tokens", "logits", "hidden"):
+                assert np.array_equal(alone[i][name], got[name]), (i, name)
+    finally:
+        for c in ctxs:
+            B.ssd_ctx_destroy(c)
+        for m in models:
+            B.ssd_model_destroy(m)

@@ -91,7 +91,7 @@ def test_sampler_greedy_and_gumbel(B, V, rows):
 
 @pytest.mark.parametrize("V,rows,scale,temp", [(128256, 24, 1.0, 1.0), (128256, 48, 3.0, 0.3), (4099, 7, 50.0, 0.05),
                                                (128256, 6, 0.01, 2.0), (1024, 300, 1.0, 0.7)])
-def test_sampler_fp32_preselection_gives_the_fp64_token(B, V, rows, scale, temp, monkeypatch):
+def test_sampler_fp32_preselection_gives_the_fp64_token(B, V, rows, scale, temp):
     """Sampled rows are scanned in fp32 and only the tokens within the error bound of the maximum are scored in fp64.
     The token must be the one a full fp64 scan gives, also with large logits over a small temperature, planted
     near-ties, infinities and NaN."""
@@ -107,12 +107,11 @@ def test_sampler_fp32_preselection_gives_the_fp64_token(B, V, rows, scale, temp,
     temps = dev_f32(np.full(rows, temp, np.float32))
     zd = dev_f32(z)
     outs = []
-    for exact in ("1", "0"):
-        monkeypatch.setenv("SSD_SAMPLE_EXACT_SCAN", exact)
+    for sample in (B.ssd_sample_fp64_scan, B.ssd_sample):
         per_step = []
         for step in range(3):
             out = torch.full((rows,), -5, dtype=torch.int32, device="cuda")
-            B.ssd_sample(zd, temps, seed=1234, row_base=17, step=step, out=out)
+            sample(zd, temps, seed=1234, row_base=17, step=step, out=out)
             torch.cuda.synchronize()
             per_step.append(out.cpu().numpy())
         outs.append(np.stack(per_step))
