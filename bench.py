@@ -203,6 +203,9 @@ def main():
     ap.add_argument("--ragged-prefix", action="store_true",
                     help="give every sequence of the batch its own prefix length (seeded, between a tenth of the workload's "
                          "prefix and all of it) instead of the same one")
+    ap.add_argument("--one-plane", type=lambda x: int(x, 0), default=None, metavar="MASK",
+                    help="activation tensors the fused pass carries as ONE bf16 plane instead of head + remainder: bits "
+                         "1 xn, 2 att, 4 act, 8 q, 16 p (31 = all; default: the library's default configuration)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy: the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
@@ -238,12 +241,13 @@ def main():
     w = I.make_weights(shape, WEIGHT_SEED)
     model = B.ssd_model_create(shape, w)
     fan = None
+    ctx_flags = 0 if args.one_plane is None else (args.one_plane & 31) << 8
     if args.geometric_fanout:
         a_rate, r_exp = (float(x) for x in args.geometric_fanout.split(","))
         fan = B.ssd_geometric_fanout((K + 1) * F, K, a_rate, r_exp)
-        ctx = B.ssd_ctx_create_fanout(model, nb, K, fan, P + 2 * K + 2)
+        ctx = B.ssd_ctx_create_fanout(model, nb, K, fan, P + 2 * K + 2, ctx_flags)
     else:
-        ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2)
+        ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2, ctx_flags)
     k, v = I.make_prefix_kv(shape, nb, P, wl.seed)
     to_bf16 = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
     B.ssd_ctx_load_trunk(ctx, to_bf16(k), to_bf16(v), P)

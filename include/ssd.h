@@ -101,8 +101,18 @@ typedef struct {
  * runs every batched forward as one persistent kernel. */
 enum {
   SSD_CTX_PER_OPERATOR = 1, /* never the fused pass: one kernel per operator */
-  SSD_CTX_FUSED_PHASES = 2  /* the fused pass as one launch per phase instead of one persistent launch: no grid barrier, so
+  SSD_CTX_FUSED_PHASES = 2, /* the fused pass as one launch per phase instead of one persistent launch: no grid barrier, so
                                no need for all its workgroups to be resident at once; same bits as the persistent launch */
+  SSD_CTX_NARROW_PASSES = 4, /* a context with more than 48 rows in a batched forward runs them as passes of whole sequences
+                                of at most 48 rows (the weights are then streamed once per pass) instead of wide passes of
+                                up to 384 rows; a comparison aid */
+  /* Precision of the activations the fused pass hands from phase to phase.  Default: two bf16 planes, head + remainder
+   * (about 2^-17 relative, so only weights and KV are rounded to bf16).  With a bit set that tensor travels as one bf16
+   * plane, the plain bf16 mixed precision of the paper's system (App. B), at half the operand traffic and MFMAs:
+   * the normalised residual stream, the attention output, the SwiGLU output, the rotated queries, the softmax
+   * probabilities.  EINVAL for a combination that is not compiled in (all five or none are). */
+  SSD_CTX_ONE_PLANE_XN = 0x100, SSD_CTX_ONE_PLANE_ATT = 0x200, SSD_CTX_ONE_PLANE_ACT = 0x400,
+  SSD_CTX_ONE_PLANE_Q = 0x800, SSD_CTX_ONE_PLANE_P = 0x1000, SSD_CTX_ONE_PLANE_ALL = 0x1f00
 };
 
 /* Read-only device views of the context's state, for tests and for the verifier's payload. */
@@ -120,6 +130,8 @@ typedef struct {
                                    [B][Hkv][T][D], values transposed per 32-position block [B][Hkv][T/32][D][32] */
   int32_t batch, K, F, vocab, d_model, max_trunk;
   int32_t fused_pass;          /* 0: one kernel per operator; 1: fused pass, one launch per phase; 2: one persistent launch */
+  int32_t pass_rows;           /* most rows of one fused pass: 48 (narrow passes, activations as two bf16 planes), 384 (wide
+                                  passes, one bf16 plane), 0 without the fused pass */
 } ssd_views;
 
 const char* ssd_last_error(void);

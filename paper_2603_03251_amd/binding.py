@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(HERE, "libssd_hip.so")
 SSD_OK, SSD_EINVAL, SSD_ESTATE, SSD_EHIP, SSD_ENOMEM = 0, -1, -2, -3, -4
 SSD_F32, SSD_BF16 = 0, 1
 SSD_MAX_F, SSD_MAX_K = 16, 15
-SSD_CTX_PER_OPERATOR, SSD_CTX_FUSED_PHASES = 1, 2
+SSD_CTX_PER_OPERATOR, SSD_CTX_FUSED_PHASES, SSD_CTX_NARROW_PASSES = 1, 2, 4
+SSD_CTX_ONE_PLANE_ALL = 0x1f00
 SSD_DEBUG_BARRIER_EPOCH, SSD_DEBUG_SPIN_LIMIT = 1, 2
 
 
@@ -49,7 +50,7 @@ class ssd_views(C.Structure):
                 ("d_logits", C.c_void_p), ("d_hidden", C.c_void_p), ("d_glue_logits", C.c_void_p),
                 ("d_glue_hidden", C.c_void_p), ("h_trunk_k", C.POINTER(C.c_void_p)),
                 ("h_trunk_v", C.POINTER(C.c_void_p))] + \
-               [(n, C.c_int32) for n in ("batch", "K", "F", "vocab", "d_model", "max_trunk", "fused_pass")]
+               [(n, C.c_int32) for n in ("batch", "K", "F", "vocab", "d_model", "max_trunk", "fused_pass", "pass_rows")]
 
 
 EXPORTS = {

@@ -12,8 +12,9 @@ namespace ssd {
 
 constexpr int kFusedThreads = 512;  // 8 wavefronts; they split the reduction dimension of a weight block
 constexpr int kFusedWaves = 8;
-constexpr int kFusedMaxRows = 48;   // rows of one pass (three 16-row MFMA tiles)
-constexpr int kFusedActPlanes = 2;   // bf16 planes of the SwiGLU output (1 = rounded to bf16, 2 = head + remainder)
+constexpr int kFusedMaxRows = 48;   // rows of one narrow pass (three 16-row MFMA tiles)
+constexpr int kFusedWideRows = 384; // rows of one wide pass (24 row tiles): contexts with more than kFusedMaxRows rows
+constexpr int kFusedWideQueryTiles = 3;   // wide passes: query tiles per attention unit (n_attn_units counts such units)
 constexpr int kFusedClockSlots = 8;  // clock probes per phase and workgroup (see stamp())
 constexpr int kFusedMaxSlices = 4;   // most k-slices of a linear layer
 constexpr unsigned kFusedSpinLimit = 4000000u;   // polls of a bounded wait (seconds of wall time) before it gives up
@@ -84,6 +85,8 @@ struct FusedParams {
   unsigned long long* prof;                // optional [phases][kFusedClockSlots][nwg] real-time-counter ticks, or null
   int nwg;
   int deep;                                // 1: every linear layer has a multiple of 4 k-tiles per wavefront and unit
+  int planes;                              // bit i set: tensor i travels as one bf16 plane instead of head + remainder
+                                           // (0 xn, 1 att, 2 act, 3 q, 4 p); see Planes in kernels_fused.hip
 };
 
 // Phase ids: 0 embed; 1 + 6 l + {0 qkv, 1 attention, 2 merge of key splits (NS > 1 only), 3 o-proj, 4 gate/up, 5 down};
@@ -106,9 +109,14 @@ bool fused_supported(const Dims& d, int max_rows);
 // Runs phases [first, last].  persistent = 1: one launch with grid barriers between phases;
 // persistent = 0: one launch per phase (a debugging aid that needs no co-residency).
 int launch_fused(const FusedParams& p, int first, int last, int persistent, hipStream_t s);
+// The same phases for up to kFusedWideRows rows (workspace strides of kFusedWideRows rows, one bf16 plane per tensor),
+// one launch per phase.  layers_host: the layer table p.layers points at, in host memory.
+int launch_fused_wide(const FusedParams& p, const FusedLayer* layers_host, int first, int last, hipStream_t s);
+bool fused_wide_gemm_ok(const FusedGemm& g, int at);
 int fused_grid_size(int* out);
 // EINVAL unless `nwg` workgroups of every instance of the persistent kernel can be resident at once on the current device
-int fused_check_residency(int nwg);
+int fused_check_residency(int nwg, int planes);
+bool fused_planes_supported(int planes);
 // Barrier words (kFusedSyncWords of them + the error word behind) as a finished barrier number `epoch0` leaves them;
 // 0 for a new context.  The epoch counts on from launch to launch and wraps after 2^32 barriers.
 constexpr int kFusedSyncWords = 2048;

