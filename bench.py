@@ -23,11 +23,37 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MEASURED_STREAM_READ_GBS = 7100.0     # register-ring streaming read of 2 GiB, 256 workgroups x 8 wavefronts
-# HBM bytes per launch of the fused decode kernel from the rocprofv3 counter runs summarised in
-# profiles/fused_decode_kernel_1b_p1024_f4_hbm_traffic.txt (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)
-MEASURED_TRAFFIC_BYTES = 2781731406
 WORKLOAD = "1b_p1024_f4"
 WEIGHT_SEED = 2025
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "fused_decode_kernel_1b_p1024_f4_hbm_traffic.txt")
+KERNEL_SOURCES = [os.path.join(ROOT, "paper_2603_03251_amd", "csrc", f) for f in ("kernels_fused.hip", "fused.h")]
+
+
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for path in KERNEL_SOURCES:
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic_bytes():
+    """HBM bytes per launch of the fused decode kernel from the rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each
+    scaled by a plain copy) summarised in the tracked profile, or None if that summary was taken with other kernel
+    sources than the ones this run was built from (it names their hash)."""
+    try:
+        fields = {}
+        with open(TRAFFIC_PROFILE) as f:
+            for line in f:
+                if ":" in line and line.split(":", 1)[0].strip() in ("traffic_bytes_per_launch", "kernel_sources_sha256"):
+                    k, v = line.split(":", 1)
+                    fields[k.strip()] = v.strip()
+        if fields.get("kernel_sources_sha256") != kernel_source_hash():
+            return None
+        return int(fields["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def algorithmic_bytes_per_decode_step(shape, rnd, prefix_lens=None):
@@ -184,12 +210,53 @@ def bench_target_verify(args):
     B.ssd_model_destroy(draft)
 
 
+def sub_record(B, I, model, shape, name, steps):
+    """Kernel time and roofline fraction of one branch-decode step of another workload of the same model: a few
+    rounds on a context of its own, HIP events around the step's kernels on their stream."""
+    import numpy as np
+    import torch
+    wl = I.WORKLOADS[name]
+    r = wl.round
+    K, F, P, nb, V = r.K, r.F, r.prefix, r.batch, shape.vocab
+    ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2)
+    try:
+        k, v = I.make_prefix_kv(shape, nb, P, wl.seed)
+        to_bf16 = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+        B.ssd_ctx_load_trunk(ctx, to_bf16(k), to_bf16(v), P)
+        del k, v
+        pending = torch.from_numpy(I.make_pending(shape, nb, K, wl.seed)).cuda()
+        temps = torch.full((nb,), r.temperature, dtype=torch.float32, device="cuda")
+        B.ssd_ctx_enable_timing(ctx, True)
+        seg = []
+        for i in range(steps + 2):
+            B.ssd_prespeculate(ctx, pending, temps, 3000 + i)
+            if i >= 2:
+                seg.append(B.ssd_ctx_read_timing(ctx, K, with_kernels=True))
+        B.ssd_ctx_refresh_bounds(ctx)
+        B.ssd_ctx_status(ctx)
+        seg = np.array(seg)
+        kernel_ms = float(seg[:, K + 2:].mean())
+        round_ms = float(seg[:, :K + 2].sum(axis=1).mean())
+        bytes_step = algorithmic_bytes_per_decode_step(shape, r)
+        d_, f_, L_ = shape.d_model, shape.d_ffn, shape.n_layers
+        qd_, kvd_ = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+        flops = 2.0 * r.rows * (L_ * ((qd_ + 2 * kvd_) * d_ + d_ * qd_ + 3 * d_ * f_) + V * d_)
+        view = B.ssd_ctx_views(ctx)
+        return {"branch_rows": r.rows, "pass_rows": int(view.pass_rows), "decode_step_kernels_ms": kernel_ms,
+                "draft_round_ms": round_ms, "branch_tokens_per_s": r.rows * K / (round_ms * 1e-3),
+                "hbm_frac": bytes_step / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "bytes_per_step": bytes_step,
+                "mfma_frac": flops / (kernel_ms * 1e-3) / 2.5e15}
+    finally:
+        B.ssd_ctx_destroy(ctx)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and comparison (profiling runs)")
+    ap.add_argument("--no-sub-records", action="store_true", help="skip the compact records of the other workloads")
     ap.add_argument("--phase-clocks", action="store_true",
                     help="also print (stderr) the per-phase times inside the fused decode kernel of the last branch step")
     ap.add_argument("--workload", default=WORKLOAD,
@@ -307,6 +374,22 @@ def main():
     bytes_step = algorithmic_bytes_per_decode_step(shape, r, prefix_lens)
     achieved = bytes_step / (kernel_ms * 1e-3) / 1e9
 
+    # ---- the line must not report a round that went wrong: the context's fault word (a grid barrier of the fused pass
+    # that timed out), finite outputs, and a hit that returns the cached speculation
+    B.ssd_ctx_refresh_bounds(ctx)
+    B.ssd_ctx_status(ctx)
+    view = B.ssd_ctx_views(ctx)
+    rows_all = nb * (sum(fan) if fan else (K + 1) * F)
+    gpu_keys = B.device_copy(view.d_keys, (rows_all,), torch.int32).cpu().numpy()
+    gpu_toks = B.device_copy(view.d_tokens, (rows_all, K), torch.int32).cpu().numpy()
+    assert gpu_keys.min() >= 0 and gpu_keys.max() < V and gpu_toks.min() >= 0 and gpu_toks.max() < V, "invalid token ids in the cache"
+    probe_k = torch.zeros(nb, dtype=torch.int32, device="cuda")
+    rps = rows_all // nb
+    probe_t = torch.from_numpy(np.ascontiguousarray(gpu_keys.reshape(nb, rps)[:, 0])).cuda()       # outcome (k = 0, first key)
+    B.ssd_cache_lookup(ctx, probe_k, probe_t, hit, branch, spec, stream=s_draft)
+    torch.cuda.synchronize()
+    assert bool(hit.all()) and np.array_equal(spec.cpu().numpy(), gpu_toks.reshape(nb, rps, K)[:, 0]), "lookup of a cached outcome failed"
+
     tokens_per_round = nb * (K + 1) * F * K
     ms_per_step = elapsed / args.steps * 1e3
     out = {
@@ -333,7 +416,7 @@ def main():
         "roofline": {"kernel": (f"fused_kernel: one batched branch-decode step ({r.rows} rows) in one persistent launch" if fused
                                 else f"one batched branch-decode step ({r.rows} rows), one kernel per operator"),
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES if headline and fused else None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes() if headline and fused else None,
                      "bytes_per_launch": bytes_step, "avg_ms": kernel_ms,
                      # against what a plain streaming read reaches on this machine (profiles/microbenchmarks_mi355x.txt)
                      "frac_of_measured_stream_read": achieved / MEASURED_STREAM_READ_GBS},
@@ -345,18 +428,41 @@ def main():
     out["mfma"] = {"gemm_flops_per_step": gemm_flops, "achieved_tflops": gemm_flops / (kernel_ms * 1e-3) / 1e12,
                    "peak_tflops": 2500.0, "frac": gemm_flops / (kernel_ms * 1e-3) / 2.5e15}
 
+    if headline and not args.no_sub_records:
+        # the other single-GPU workloads of the same model, compactly (their own full lines: --workload)
+        out["other_workloads"] = {name: sub_record(B, I, model, shape, name, steps=max(2, min(args.steps, 5)))
+                                  for name in ("1b_p8192_f8_t1", "1b_b16_p2048_f4")}
+
     if headline and not args.no_cpu_baseline:
+        # The CPU oracle on the SAME round: glue extend, then every branch from the key the GPU's round cached, one at a
+        # time.  Timed as the reported baseline, and compared with the GPU's cache (the bench line checks itself).
         from oracle import ssd_oracle as O
         om = O.Model.from_weights(shape, w)
         trunk = O.KV([k[l, 0].astype(np.float64) for l in range(shape.n_layers)],
                      [v[l, 0].astype(np.float64) for l in range(shape.n_layers)])
         pend = pending.cpu().numpy()[0]
-        _, _, trunk_glue = O.glue_extend(om, trunk, pend)
+        glue_logits, _, trunk_glue = O.glue_extend(om, trunk, pend)
+        gpu_glue = B.device_copy(view.d_glue_logits, (K + 1, V), torch.float32).cpu().numpy()
+        worst = float((np.abs(gpu_glue - glue_logits).max(axis=1) / np.abs(glue_logits).max(axis=1)).max())
         n_branches = r.rows                        # every branch of one round, one at a time
+        n_tok_checked = 0
         t0 = time.perf_counter()
         for j in range(n_branches):
-            O.decode_branch(om, trunk_glue, P, j // F, 17 + j, K, 0.0, 0, j)
+            toks_o, logits_o, _, margins_o = O.decode_branch(om, trunk_glue, P, j // F, int(gpu_keys[j]), K, 0.0, 0, j)
+            lg = B.device_copy(view.d_logits + j * K * V * 4, (K, V), torch.float32).cpu().numpy()
+            for i in range(K):                     # the GPU ran free: compare while its inputs are the oracle's
+                e = float(np.abs(lg[i] - logits_o[i]).max() / np.abs(logits_o[i]).max())
+                worst = max(worst, e)
+                decided = margins_o[i] > 2 * np.abs(lg[i] - logits_o[i]).max()
+                if decided:
+                    assert gpu_toks[j, i] == toks_o[i], f"branch {j} step {i}: token differs from the oracle's"
+                    n_tok_checked += 1
+                if gpu_toks[j, i] != toks_o[i]:
+                    break
         dt = time.perf_counter() - t0
+        assert worst < 4e-3, f"the GPU round differs from the oracle: rel err {worst}"
+        out["self_check"] = {"logits_rel_err_vs_oracle": worst, "tokens_equal_where_decided": n_tok_checked,
+                             "branches": n_branches, "bound": 4e-3}
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])

@@ -438,7 +438,7 @@ int fused_setup(ssd_ctx* c) {
   SSD_TRY(st);
   // every workgroup of a persistent launch has to be resident at once
   p.planes = (c->flags >> 8) & 31;
-  if (!fused_planes_supported(p.planes)) { set_error("fused pass: plane configuration %d is not compiled in", p.planes); return SSD_EINVAL; }
+  if (!c->fused_wide && !fused_planes_supported(p.planes)) { set_error("fused pass: plane configuration %d is not compiled in", p.planes); return SSD_EINVAL; }
   if (c->fused_mode == 2) SSD_TRY(fused_check_residency(p.nwg, p.planes));
   {
     void* host_word = nullptr;
