@@ -109,8 +109,8 @@ def bench_target_verify(args):
     """Workload 70b_verify_1b_draft (Sec. 2.1: verification is one target forward over the K+1 positions; Sec. 4 "Setup"): the target's verification forward over the K+1 pending
     positions at the 70B shape, alone and beside the draft's pre-speculation round, both on this one GPU (so the two
     share one HBM: this shows the overlap mechanics and the target forward's own rate, not the paper's two-device
-    latency hiding).  80 layers are built from 2 distinct random layers (the host copy stays small); prefix KV is
-    synthetic.  Prints one JSON line; not the default bench line."""
+    latency hiding).  The target's 80 layers of random weights and its prefix KV are generated on the device.  Prints
+    one JSON line; not the default bench line."""
     import numpy as np
     import torch
     import ssd_inputs as I
@@ -123,21 +123,11 @@ def bench_target_verify(args):
     to_bf16 = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
     note = lambda m: (sys.stderr.write(m + "\n"), sys.stderr.flush())
 
-    import dataclasses
-    two = dataclasses.replace(tshape, n_layers=2)
-    w2 = I.make_weights(two, WEIGHT_SEED + 1)
-    wt = {n: a for n, a in w2.items() if "." not in n}          # embedding, final norm, LM head
-    for l in range(tshape.n_layers):
-        for leaf in ("attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "w_gate", "w_up", "w_down"):
-            wt[f"l{l}.{leaf}"] = w2[f"l{l % 2}.{leaf}"]
-    note("target weights generated (2 distinct layers)")
-    target = B.ssd_model_create(tshape, wt)
-    del wt, w2
-    note("target model on the device")
+    # 80 distinct random layers (139 GB of weights) and the synthetic prefix, generated on the device: no host copy
+    target = B.ssd_model_create_random(tshape, WEIGHT_SEED + 1)
+    note("target model generated on the device")
     tctx = B.ssd_ctx_create(target, nb, K, 1, P + 2 * K + 2)
-    kt, vt = I.make_prefix_kv(tshape, nb, P, wl.seed + 7)
-    B.ssd_ctx_load_trunk(tctx, to_bf16(kt), to_bf16(vt), P)
-    del kt, vt
+    B.ssd_ctx_fill_synthetic_kv(tctx, [P] * nb, wl.seed + 7)
     draft = B.ssd_model_create(dshape, I.make_weights(dshape, WEIGHT_SEED))
     dctx = B.ssd_ctx_create(draft, nb, K, F, P + 2 * K + 2)
     kd, vd = I.make_prefix_kv(dshape, nb, P, wl.seed)

@@ -139,6 +139,14 @@ const char* ssd_last_error(void);
 /* ---- set-up (not on the hot path; these allocate) ------------------------------------------ */
 
 int ssd_model_create(const ssd_model_config* cfg, const ssd_model_weights* w, void* stream, ssd_model** out);
+/* A random-init model generated on the device (the synthetic stand-in for trained weights, at any size: no host
+ * copy exists).  Every matrix element is N(0, 0.02)-like, every RMSNorm gain 1, from integer arithmetic alone, so the
+ * host-side generator the tests use gives the same bits: element i (row-major [out][in]) of tensor t is
+ * float(S - 131070) * float(0.02 / 37837.227...), S = the sum of the four 16-bit lanes of
+ * mix64(mix64(seed + 0x9E3779B97F4A7C15 (t + 1)) + i) (mix64 = the SplitMix64 finaliser), rounded to bf16
+ * (nearest even) for bf16 models.  Tensor ids: 0 embedding, 1 LM head (untied models), 16 + 16 l + {0 wq, 1 wk, 2 wv, 3 wo,
+ * 4 w_gate, 5 w_up, 6 w_down} for layer l.  Runs on `stream` and SYNCHRONISES it before returning. */
+int ssd_model_create_random(const ssd_model_config* cfg, uint64_t seed, void* stream, ssd_model** out);
 int ssd_model_destroy(ssd_model* m);
 
 /* The context keeps a pointer to `model`; destroy the context first. */
@@ -167,6 +175,11 @@ int ssd_ctx_prefill(ssd_ctx* ctx, const int32_t* d_tokens, int32_t stride, const
 /* Trunk := given KV (a synthetic prefix standing in for a prefill).  d_k, d_v:
  * [n_layers][B][len][n_kv_heads][head_dim] in the model dtype; every sequence gets length `len`. */
 int ssd_ctx_load_trunk(ssd_ctx* ctx, const void* d_k, const void* d_v, int32_t len, void* stream);
+/* Trunk of sequence b := h_lens[b] positions of synthetic KV (a stand-in for a prefill that is not on the measured path),
+ * generated on the device with the hash of ssd_model_create_random and unit variance: element (position t, KV head h,
+ * dim d) of sequence b has index (b << 40) + (t n_kv_heads + h) head_dim + d in tensor (1 << 20) + 2 l (keys of layer l) or
+ * (1 << 20) + 2 l + 1 (values).  h_lens: host int32 [B], each >= 1 and <= max_trunk - (2K+2).  Synchronises `stream`. */
+int ssd_ctx_fill_synthetic_kv(ssd_ctx* ctx, const int32_t* h_lens, uint64_t seed, void* stream);
 /* Trunk of sequence b := its first h_lens[b] positions (1 <= h_lens[b] <= the context's current bound of the trunk
  * lengths; host int32 [B], read during the call): a batch of different prefix lengths from one loaded or prefilled
  * block, or a rollback.  EINVAL if a length is out of range.  Synchronises `stream`. */

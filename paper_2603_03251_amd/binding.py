@@ -57,10 +57,12 @@ EXPORTS = {
     "ssd_last_error": (C.c_char_p, []),
     "ssd_model_create": (C.c_int, [C.POINTER(ssd_model_config), C.POINTER(ssd_model_weights), C.c_void_p,
                                    C.POINTER(C.c_void_p)]),
+    "ssd_model_create_random": (C.c_int, [C.POINTER(ssd_model_config), C.c_uint64, C.c_void_p, C.POINTER(C.c_void_p)]),
     "ssd_model_destroy": (C.c_int, [C.c_void_p]),
     "ssd_ctx_create": (C.c_int, [C.c_void_p, C.POINTER(ssd_round_config), C.POINTER(C.c_void_p)]),
     "ssd_ctx_destroy": (C.c_int, [C.c_void_p]),
     "ssd_ctx_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p]),
+    "ssd_ctx_fill_synthetic_kv": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.c_uint64, C.c_void_p]),
     "ssd_ctx_load_trunk": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "ssd_prespeculate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "ssd_ctx_set_forced": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -187,6 +189,19 @@ def ssd_model_create(shape, weights: Dict[str, np.ndarray], stream=None) -> int:
     return out.value
 
 
+def _model_config(shape) -> ssd_model_config:
+    return ssd_model_config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                            shape.d_ffn, shape.vocab, SSD_BF16 if shape.dtype == "bf16" else SSD_F32,
+                            shape.rope_theta, shape.rms_eps, 1 if shape.tie_embeddings else 0)
+
+
+def ssd_model_create_random(shape, seed: int, stream=None) -> int:
+    cfg = _model_config(shape)
+    out = C.c_void_p()
+    _check(lib.ssd_model_create_random(C.byref(cfg), seed, _stream(stream), C.byref(out)))
+    return out.value
+
+
 def ssd_model_destroy(model: int) -> None:
     _check(lib.ssd_model_destroy(model))
 
@@ -231,6 +246,11 @@ def ssd_ctx_prefill(ctx: int, tokens: torch.Tensor, lens: Sequence[int], stream=
 
 def ssd_ctx_load_trunk(ctx: int, k: torch.Tensor, v: torch.Tensor, length: int, stream=None) -> None:
     _check(lib.ssd_ctx_load_trunk(ctx, _ptr(k), _ptr(v), length, _stream(stream)))
+
+
+def ssd_ctx_fill_synthetic_kv(ctx: int, lens: Sequence[int], seed: int, stream=None) -> None:
+    h = (C.c_int32 * len(lens))(*[int(x) for x in lens])
+    _check(lib.ssd_ctx_fill_synthetic_kv(ctx, h, seed, _stream(stream)))
 
 
 def ssd_ctx_truncate_trunk(ctx: int, lens: Sequence[int], stream=None) -> None:

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssd_hip.so")
 SOURCES = ["ssd_api.hip", "kernels_misc.hip", "kernels_gemm.hip", "kernels_attn.hip", "kernels_select.hip",
-           "kernels_fused.hip"]
+           "kernels_fused.hip", "kernels_init.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

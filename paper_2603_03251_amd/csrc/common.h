@@ -124,6 +124,15 @@ int launch_lookup(const int32_t* keys, const int32_t* cache_tokens, const float*
 int launch_pending_exclude(int32_t* exclude, const int32_t* pending, int B, int K, hipStream_t s);
 int launch_copy_kv_in(int dtype, void* trunk, const void* src, int B, int len, int max_trunk, int row_elems, hipStream_t s);
 
+// ---------------------------------------------------------------- kernels_init.hip
+// Seeded synthetic tensors generated on the device (bit-identical to the host-side input generators' twin).
+// Tensor ids: 0 embedding, 1 LM head, 16 + 16 l + {0 wq, 1 wk, 2 wv, 3 wo, 4 w_gate, 5 w_up, 6 w_down} for layer l,
+// 1 << 20 + 2 l + {0 keys, 1 values} for the synthetic prefix KV of layer l.
+int launch_fill_hashed(int dtype, void* dst, int64_t n, uint64_t seed, uint64_t tensor_id, double std, hipStream_t s);
+int launch_fill_const(int dtype, void* dst, int64_t n, float v, hipStream_t s);
+int launch_fill_kv(int dtype, void* k, void* v, const int32_t* len, int B, int max_len, int Hkv, int D, int stride, int fused,
+                   uint64_t seed, uint64_t id_k, uint64_t id_v, hipStream_t s);
+
 // ---------------------------------------------------------------- kernels_gemm.hip
 enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL_ADD = 1, EPI_SWIGLU = 2 };
 // Tiled copy of a [N][Kd] bf16 matrix into the MFMA-operand order the bf16 GEMM streams (see kernels_gemm.hip).

@@ -156,87 +156,166 @@ int put_linear(int dtype, const void* src, void* dst, int N, int Kd, hipStream_t
   return SSD_OK;
 }
 
-int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
+// One layer's weights as the caller (or the on-device generator) holds them: row-major [out][in], model dtype.
+struct LayerSrc {
+  const void *attn_norm, *wq, *wk, *wv, *wo, *mlp_norm, *w_gate, *w_up, *w_down;
+};
+
+// A matrix into the stream order of the fused pass.  ks_wanted > 1: split the reduction dimension so that every
+// workgroup of the grid gets a unit, if the shape allows.
+int make_stream_order(ssd_model* m, int grid, FusedGemm* g, const void* s0, int r0, const void* s1, int r1, const void* s2, int r2,
+                      int mode, int at, int ks_wanted, int Kd, hipStream_t s) {
+  const int N = mode == 0 ? r0 + r1 + r2 : 2 * r0;
+  const int NT = (N + 15) / 16, groups = (NT + at - 1) / at;
+  int ks = 1;
+  for (int k = ks_wanted; k > 1; k /= 2)
+    if (groups * k <= grid && (Kd / 256) % (2 * k) == 0) { ks = k; break; }
+  void* dst = nullptr;
+  SSD_TRY(m->arena.alloc(&dst, (size_t)stream_order_elems(N, Kd, at) * 2));
+  SSD_TRY(launch_retile_stream((const bf16_t*)s0, r0, (const bf16_t*)s1, r1, (const bf16_t*)s2, r2, mode, at, ks, Kd,
+                               (bf16_t*)dst, s));
+  g->w = (const bf16_t*)dst;
+  g->KS = ks;
+  g->KTW = Kd / 32 / kFusedWaves / ks;
+  g->NT = NT;
+  g->n_units = groups * ks;
+  return SSD_OK;
+}
+
+// Model building in pieces, so that the source of a layer's weights may be a buffer that is reused for the next layer:
+// build_begin, build_head, build_layer x n_layers, build_end, all on one stream.
+int build_begin(ssd_model* m, int* grid) {
+  const Dims& d = m->dims;
+  m->layers.resize(d.n_layers);
+  m->fused_ok = fused_supported(d, 1);
+  *grid = 0;
+  if (m->fused_ok) {
+    SSD_TRY(fused_grid_size(grid));
+    m->fused_layers.resize(d.n_layers);
+  }
+  return SSD_OK;
+}
+
+int build_head(ssd_model* m, int grid, const void* embed, const void* lm_head, const void* final_norm, hipStream_t s) {
   const Dims& d = m->dims;
   const size_t es = elem_size(d.dtype);
-  const int qd = d.q_dim(), kvd = d.kv_dim();
   SSD_TRY(m->arena.alloc(&m->embed, (size_t)d.vocab * d.d_model * es));
-  SSD_HIP(hipMemcpyAsync(m->embed, w->d_embed, (size_t)d.vocab * d.d_model * es, hipMemcpyDeviceToDevice, s));
+  SSD_HIP(hipMemcpyAsync(m->embed, embed, (size_t)d.vocab * d.d_model * es, hipMemcpyDeviceToDevice, s));
   SSD_TRY(m->arena.alloc(&m->final_norm, (size_t)d.d_model * es));
-  SSD_HIP(hipMemcpyAsync(m->final_norm, w->d_final_norm, (size_t)d.d_model * es, hipMemcpyDeviceToDevice, s));
-  const void* head_src = m->tie ? w->d_embed : w->d_lm_head;
+  SSD_HIP(hipMemcpyAsync(m->final_norm, final_norm, (size_t)d.d_model * es, hipMemcpyDeviceToDevice, s));
+  const void* head_src = m->tie ? embed : lm_head;
   if (d.dtype == SSD_F32 && m->tie) m->lm_head = m->embed;
   else {
     SSD_TRY(m->arena.alloc(&m->lm_head, (size_t)d.vocab * d.d_model * es));
     SSD_TRY(put_linear(d.dtype, head_src, m->lm_head, d.vocab, d.d_model, s));
   }
-  m->layers.resize(d.n_layers);
-  for (int l = 0; l < d.n_layers; ++l) {
-    ssd_model::Layer& L = m->layers[l];
-    SSD_TRY(m->arena.alloc(&L.attn_norm, (size_t)d.d_model * es));
-    SSD_TRY(m->arena.alloc(&L.mlp_norm, (size_t)d.d_model * es));
-    SSD_HIP(hipMemcpyAsync(L.attn_norm, w->h_attn_norm[l], (size_t)d.d_model * es, hipMemcpyDeviceToDevice, s));
-    SSD_HIP(hipMemcpyAsync(L.mlp_norm, w->h_mlp_norm[l], (size_t)d.d_model * es, hipMemcpyDeviceToDevice, s));
-    SSD_TRY(m->arena.alloc(&L.wqkv, (size_t)d.qkv_dim() * d.d_model * es));
-    char* qkv = (char*)L.wqkv;
-    SSD_TRY(put_linear(d.dtype, w->h_wq[l], qkv, qd, d.d_model, s));
-    SSD_TRY(put_linear(d.dtype, w->h_wk[l], qkv + (size_t)qd * d.d_model * es, kvd, d.d_model, s));
-    SSD_TRY(put_linear(d.dtype, w->h_wv[l], qkv + (size_t)(qd + kvd) * d.d_model * es, kvd, d.d_model, s));
-    SSD_TRY(m->arena.alloc(&L.wo, (size_t)d.d_model * qd * es));
-    SSD_TRY(put_linear(d.dtype, w->h_wo[l], L.wo, d.d_model, qd, s));
-    SSD_TRY(m->arena.alloc(&L.w_gate, (size_t)d.d_ffn * d.d_model * es));
-    SSD_TRY(put_linear(d.dtype, w->h_w_gate[l], L.w_gate, d.d_ffn, d.d_model, s));
-    SSD_TRY(m->arena.alloc(&L.w_up, (size_t)d.d_ffn * d.d_model * es));
-    SSD_TRY(put_linear(d.dtype, w->h_w_up[l], L.w_up, d.d_ffn, d.d_model, s));
-    SSD_TRY(m->arena.alloc(&L.w_down, (size_t)d.d_model * d.d_ffn * es));
-    SSD_TRY(put_linear(d.dtype, w->h_w_down[l], L.w_down, d.d_model, d.d_ffn, s));
-  }
-  m->fused_ok = fused_supported(d, 1);
+  if (m->fused_ok)
+    SSD_TRY(make_stream_order(m, grid, &m->fused_lm, head_src, d.vocab, nullptr, 0, nullptr, 0, 0, kAtLm, 1, d.d_model, s));
+  return SSD_OK;
+}
+
+int build_layer(ssd_model* m, int grid, int l, const LayerSrc& w, hipStream_t s) {
+  const Dims& d = m->dims;
+  const size_t es = elem_size(d.dtype);
+  const int qd = d.q_dim(), kvd = d.kv_dim();
+  ssd_model::Layer& L = m->layers[l];
+  SSD_TRY(m->arena.alloc(&L.attn_norm, (size_t)d.d_model * es));
+  SSD_TRY(m->arena.alloc(&L.mlp_norm, (size_t)d.d_model * es));
+  SSD_HIP(hipMemcpyAsync(L.attn_norm, w.attn_norm, (size_t)d.d_model * es, hipMemcpyDeviceToDevice, s));
+  SSD_HIP(hipMemcpyAsync(L.mlp_norm, w.mlp_norm, (size_t)d.d_model * es, hipMemcpyDeviceToDevice, s));
+  SSD_TRY(m->arena.alloc(&L.wqkv, (size_t)d.qkv_dim() * d.d_model * es));
+  char* qkv = (char*)L.wqkv;
+  SSD_TRY(put_linear(d.dtype, w.wq, qkv, qd, d.d_model, s));
+  SSD_TRY(put_linear(d.dtype, w.wk, qkv + (size_t)qd * d.d_model * es, kvd, d.d_model, s));
+  SSD_TRY(put_linear(d.dtype, w.wv, qkv + (size_t)(qd + kvd) * d.d_model * es, kvd, d.d_model, s));
+  SSD_TRY(m->arena.alloc(&L.wo, (size_t)d.d_model * qd * es));
+  SSD_TRY(put_linear(d.dtype, w.wo, L.wo, d.d_model, qd, s));
+  SSD_TRY(m->arena.alloc(&L.w_gate, (size_t)d.d_ffn * d.d_model * es));
+  SSD_TRY(put_linear(d.dtype, w.w_gate, L.w_gate, d.d_ffn, d.d_model, s));
+  SSD_TRY(m->arena.alloc(&L.w_up, (size_t)d.d_ffn * d.d_model * es));
+  SSD_TRY(put_linear(d.dtype, w.w_up, L.w_up, d.d_ffn, d.d_model, s));
+  SSD_TRY(m->arena.alloc(&L.w_down, (size_t)d.d_model * d.d_ffn * es));
+  SSD_TRY(put_linear(d.dtype, w.w_down, L.w_down, d.d_model, d.d_ffn, s));
   if (m->fused_ok) {
-    int grid = 0;
-    SSD_TRY(fused_grid_size(&grid));
-    // ks_wanted > 1: split the reduction dimension so that every workgroup of the grid gets a unit, if the shape allows
-    auto make = [&](FusedGemm* g, const void* s0, int r0, const void* s1, int r1, const void* s2, int r2, int mode, int at,
-                    int ks_wanted, int Kd) -> int {
-      int N = mode == 0 ? r0 + r1 + r2 : 2 * r0;
-      const int NT = (N + 15) / 16, groups = (NT + at - 1) / at;
-      int ks = 1;
-      for (int k = ks_wanted; k > 1; k /= 2)
-        if (groups * k <= grid && (Kd / 256) % (2 * k) == 0) { ks = k; break; }
-      void* dst = nullptr;
-      SSD_TRY(m->arena.alloc(&dst, (size_t)stream_order_elems(N, Kd, at) * 2));
-      SSD_TRY(launch_retile_stream((const bf16_t*)s0, r0, (const bf16_t*)s1, r1, (const bf16_t*)s2, r2, mode, at, ks, Kd,
-                                   (bf16_t*)dst, s));
-      g->w = (const bf16_t*)dst;
-      g->KS = ks;
-      g->KTW = Kd / 32 / kFusedWaves / ks;
-      g->NT = NT;
-      g->n_units = groups * ks;
-      return SSD_OK;
-    };
-    m->fused_layers.resize(d.n_layers);
-    for (int l = 0; l < d.n_layers; ++l) {
-      ssd_model::FusedW& F = m->fused_layers[l];
-      SSD_TRY(make(&F.qkv, w->h_wq[l], qd, w->h_wk[l], kvd, w->h_wv[l], kvd, 0, kAtQkv, 1, d.d_model));
-      SSD_TRY(make(&F.o, w->h_wo[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtO, 2, qd));
-      SSD_TRY(make(&F.gu, w->h_w_gate[l], d.d_ffn, w->h_w_up[l], d.d_ffn, nullptr, 0, 1, kAtGu, 1, d.d_model));
-      SSD_TRY(make(&F.down, w->h_w_down[l], d.d_model, nullptr, 0, nullptr, 0, 0, kAtDown, 4, d.d_ffn));
-    }
-    SSD_TRY(make(&m->fused_lm, head_src, d.vocab, nullptr, 0, nullptr, 0, 0, kAtLm, 1, d.d_model));
-    // the layer phases give every workgroup at most one unit and unroll over the k-tiles of a wavefront
-    auto fits = [&](const FusedGemm& g, int max_ktw) {
-      return g.n_units <= grid && (g.KTW == 2 || g.KTW == 4 || g.KTW == 8) && g.KTW <= max_ktw;
-    };
-    m->wide_ok = fused_wide_gemm_ok(m->fused_lm, kAtLm);
-    for (const ssd_model::FusedW& F : m->fused_layers) {
-      if (!fits(F.qkv, 8) || !fits(F.o, 8) || !fits(F.down, 8)) m->fused_ok = false;
-      if (!fused_wide_gemm_ok(F.qkv, kAtQkv) || !fused_wide_gemm_ok(F.o, kAtO) || !fused_wide_gemm_ok(F.gu, kAtGu) ||
-          !fused_wide_gemm_ok(F.down, kAtDown))
-        m->wide_ok = false;
-    }
-    m->wide_ok = m->wide_ok && m->fused_ok;
+    ssd_model::FusedW& F = m->fused_layers[l];
+    SSD_TRY(make_stream_order(m, grid, &F.qkv, w.wq, qd, w.wk, kvd, w.wv, kvd, 0, kAtQkv, 1, d.d_model, s));
+    SSD_TRY(make_stream_order(m, grid, &F.o, w.wo, d.d_model, nullptr, 0, nullptr, 0, 0, kAtO, 2, qd, s));
+    SSD_TRY(make_stream_order(m, grid, &F.gu, w.w_gate, d.d_ffn, w.w_up, d.d_ffn, nullptr, 0, 1, kAtGu, 1, d.d_model, s));
+    SSD_TRY(make_stream_order(m, grid, &F.down, w.w_down, d.d_model, nullptr, 0, nullptr, 0, 0, kAtDown, 4, d.d_ffn, s));
   }
   return SSD_OK;
+}
+
+int build_end(ssd_model* m, int grid) {
+  if (!m->fused_ok) return SSD_OK;
+  // the layer phases of the narrow pass give every workgroup at most one unit and unroll over the k-tiles of a wavefront
+  auto fits = [&](const FusedGemm& g, int max_ktw) {
+    return g.n_units <= grid && (g.KTW == 2 || g.KTW == 4 || g.KTW == 8) && g.KTW <= max_ktw;
+  };
+  m->wide_ok = fused_wide_gemm_ok(m->fused_lm, kAtLm);
+  for (const ssd_model::FusedW& F : m->fused_layers) {
+    if (!fits(F.qkv, 8) || !fits(F.o, 8) || !fits(F.down, 8)) m->fused_ok = false;
+    if (!fused_wide_gemm_ok(F.qkv, kAtQkv) || !fused_wide_gemm_ok(F.o, kAtO) || !fused_wide_gemm_ok(F.gu, kAtGu) ||
+        !fused_wide_gemm_ok(F.down, kAtDown))
+      m->wide_ok = false;
+  }
+  m->wide_ok = m->wide_ok && m->fused_ok;
+  return SSD_OK;
+}
+
+int build_model(ssd_model* m, const ssd_model_weights* w, hipStream_t s) {
+  int grid = 0;
+  SSD_TRY(build_begin(m, &grid));
+  SSD_TRY(build_head(m, grid, w->d_embed, w->d_lm_head, w->d_final_norm, s));
+  for (int l = 0; l < m->dims.n_layers; ++l) {
+    const LayerSrc src = {w->h_attn_norm[l], w->h_wq[l], w->h_wk[l], w->h_wv[l], w->h_wo[l], w->h_mlp_norm[l],
+                          w->h_w_gate[l], w->h_w_up[l], w->h_w_down[l]};
+    SSD_TRY(build_layer(m, grid, l, src, s));
+  }
+  return build_end(m, grid);
+}
+
+// Random-init weights generated on the device, layer by layer through one set of scratch matrices (every matrix
+// N(0, std)-like from the integer hash of kernels_init.hip, every RMSNorm gain 1).
+int build_model_random(ssd_model* m, uint64_t seed, double std, hipStream_t s) {
+  const Dims& d = m->dims;
+  const size_t es = elem_size(d.dtype);
+  const int64_t qd = d.q_dim(), kvd = d.kv_dim(), dm = d.d_model, ff = d.d_ffn, V = d.vocab;
+  Arena tmp;
+  int grid = 0;
+  int st = build_begin(m, &grid);
+  void *embed = nullptr, *head = nullptr, *ones = nullptr, *wq = nullptr, *wk = nullptr, *wv = nullptr, *wo = nullptr, *wg = nullptr,
+       *wu = nullptr, *wd = nullptr;
+  auto A = [&](void** q, size_t bytes) { if (st == SSD_OK) st = tmp.alloc(q, bytes); };
+  auto T = [&](int r) { if (st == SSD_OK) st = r; };
+  A(&embed, (size_t)V * dm * es);
+  if (!m->tie) A(&head, (size_t)V * dm * es);
+  A(&ones, (size_t)dm * es);
+  if (st == SSD_OK) {
+    T(launch_fill_hashed(d.dtype, embed, V * dm, seed, 0, std, s));
+    if (!m->tie) T(launch_fill_hashed(d.dtype, head, V * dm, seed, 1, std, s));
+    T(launch_fill_const(d.dtype, ones, dm, 1.0f, s));
+    if (st == SSD_OK) st = build_head(m, grid, embed, head, ones, s);
+  }
+  A(&wq, (size_t)qd * dm * es); A(&wk, (size_t)kvd * dm * es); A(&wv, (size_t)kvd * dm * es); A(&wo, (size_t)dm * qd * es);
+  A(&wg, (size_t)ff * dm * es); A(&wu, (size_t)ff * dm * es); A(&wd, (size_t)dm * ff * es);
+  for (int l = 0; l < d.n_layers && st == SSD_OK; ++l) {
+    const uint64_t id = 16 + 16 * (uint64_t)l;
+    T(launch_fill_hashed(d.dtype, wq, qd * dm, seed, id + 0, std, s));
+    T(launch_fill_hashed(d.dtype, wk, kvd * dm, seed, id + 1, std, s));
+    T(launch_fill_hashed(d.dtype, wv, kvd * dm, seed, id + 2, std, s));
+    T(launch_fill_hashed(d.dtype, wo, dm * qd, seed, id + 3, std, s));
+    T(launch_fill_hashed(d.dtype, wg, ff * dm, seed, id + 4, std, s));
+    T(launch_fill_hashed(d.dtype, wu, ff * dm, seed, id + 5, std, s));
+    T(launch_fill_hashed(d.dtype, wd, dm * ff, seed, id + 6, std, s));
+    const LayerSrc src = {ones, wq, wk, wv, wo, ones, wg, wu, wd};
+    if (st == SSD_OK) st = build_layer(m, grid, l, src, s);   // same stream: the next layer's fill follows this layer's re-tiling
+  }
+  if (st == SSD_OK) st = build_end(m, grid);
+  hipError_t e = hipStreamSynchronize(s);
+  tmp.release();
+  if (st == SSD_OK && e != hipSuccess) { set_error("hipStreamSynchronize failed: %s", hipGetErrorString(e)); st = SSD_EHIP; }
+  return st;
 }
 
 // Persistent launches spin on grid barriers, so every workgroup of one must be resident at once: two of them running
@@ -490,9 +569,7 @@ extern "C" {
 
 const char* ssd_last_error(void) { return g_error; }
 
-int ssd_model_create(const ssd_model_config* cfg, const ssd_model_weights* w, void* stream, ssd_model** out) {
-  SSD_CHECK_ARG(cfg && w && out, "ssd_model_create: null argument");
-  *out = nullptr;
+static int check_model_config(const ssd_model_config* cfg) {
   SSD_CHECK_ARG(cfg->dtype == SSD_F32 || cfg->dtype == SSD_BF16, "dtype %d unknown", cfg->dtype);
   SSD_CHECK_ARG(cfg->n_layers >= 1 && cfg->d_model >= 1 && cfg->n_q_heads >= 1 && cfg->n_kv_heads >= 1 &&
                     cfg->d_ffn >= 1 && cfg->vocab >= 2,
@@ -500,6 +577,36 @@ int ssd_model_create(const ssd_model_config* cfg, const ssd_model_weights* w, vo
   SSD_CHECK_ARG(cfg->head_dim == 64 || cfg->head_dim == 128, "head_dim %d not supported (64 or 128)", cfg->head_dim);
   SSD_CHECK_ARG(cfg->n_q_heads % cfg->n_kv_heads == 0, "n_q_heads must be a multiple of n_kv_heads");
   SSD_CHECK_ARG(cfg->d_model % 4 == 0 && cfg->d_ffn % 4 == 0, "d_model and d_ffn must be multiples of 4");
+  return SSD_OK;
+}
+
+static ssd_model* new_model(const ssd_model_config* cfg) {
+  ssd_model* m = new (std::nothrow) ssd_model();
+  if (!m) { set_error("out of host memory"); return nullptr; }
+  m->dims.n_layers = cfg->n_layers; m->dims.d_model = cfg->d_model; m->dims.n_q_heads = cfg->n_q_heads;
+  m->dims.n_kv_heads = cfg->n_kv_heads; m->dims.head_dim = cfg->head_dim; m->dims.d_ffn = cfg->d_ffn;
+  m->dims.vocab = cfg->vocab; m->dims.dtype = cfg->dtype; m->dims.rope_theta = cfg->rope_theta;
+  m->dims.rms_eps = cfg->rms_eps;
+  m->tie = cfg->tie_embeddings ? 1 : 0;
+  return m;
+}
+
+int ssd_model_create_random(const ssd_model_config* cfg, uint64_t seed, void* stream, ssd_model** out) {
+  SSD_CHECK_ARG(cfg && out, "ssd_model_create_random: null argument");
+  *out = nullptr;
+  SSD_TRY(check_model_config(cfg));
+  ssd_model* m = new_model(cfg);
+  if (!m) return SSD_ENOMEM;
+  int st = build_model_random(m, seed, 0.02, (hipStream_t)stream);
+  if (st != SSD_OK) { m->arena.release(); delete m; return st; }
+  *out = m;
+  return SSD_OK;
+}
+
+int ssd_model_create(const ssd_model_config* cfg, const ssd_model_weights* w, void* stream, ssd_model** out) {
+  SSD_CHECK_ARG(cfg && w && out, "ssd_model_create: null argument");
+  *out = nullptr;
+  SSD_TRY(check_model_config(cfg));
   SSD_CHECK_ARG(w->d_embed && w->d_final_norm && (cfg->tie_embeddings || w->d_lm_head), "null weight pointer");
   SSD_CHECK_ARG(w->h_attn_norm && w->h_wq && w->h_wk && w->h_wv && w->h_wo && w->h_mlp_norm && w->h_w_gate &&
                     w->h_w_up && w->h_w_down,
@@ -508,13 +615,8 @@ int ssd_model_create(const ssd_model_config* cfg, const ssd_model_weights* w, vo
     SSD_CHECK_ARG(w->h_attn_norm[l] && w->h_wq[l] && w->h_wk[l] && w->h_wv[l] && w->h_wo[l] && w->h_mlp_norm[l] &&
                       w->h_w_gate[l] && w->h_w_up[l] && w->h_w_down[l],
                   "null weight pointer in layer %d", l);
-  ssd_model* m = new (std::nothrow) ssd_model();
-  if (!m) { set_error("out of host memory"); return SSD_ENOMEM; }
-  m->dims.n_layers = cfg->n_layers; m->dims.d_model = cfg->d_model; m->dims.n_q_heads = cfg->n_q_heads;
-  m->dims.n_kv_heads = cfg->n_kv_heads; m->dims.head_dim = cfg->head_dim; m->dims.d_ffn = cfg->d_ffn;
-  m->dims.vocab = cfg->vocab; m->dims.dtype = cfg->dtype; m->dims.rope_theta = cfg->rope_theta;
-  m->dims.rms_eps = cfg->rms_eps;
-  m->tie = cfg->tie_embeddings ? 1 : 0;
+  ssd_model* m = new_model(cfg);
+  if (!m) return SSD_ENOMEM;
   int st = build_model(m, w, (hipStream_t)stream);
   if (st != SSD_OK) { m->arena.release(); delete m; return st; }
   *out = m;
@@ -758,6 +860,29 @@ int ssd_ctx_load_trunk(ssd_ctx* c, const void* d_k, const void* d_v, int32_t len
   }
   SSD_TRY(launch_fill_i32(c->trunk_len, len, c->B, s));
   c->trunk_ub = len;
+  c->have_cache = false;
+  return SSD_OK;
+}
+
+int ssd_ctx_fill_synthetic_kv(ssd_ctx* c, const int32_t* h_lens, uint64_t seed, void* stream) {
+  SSD_CHECK_ARG(c && h_lens, "ssd_ctx_fill_synthetic_kv: null argument");
+  SSD_TRY(ctx_fault(c, "ssd_ctx_fill_synthetic_kv"));
+  int max_len = 0;
+  for (int b = 0; b < c->B; ++b) {
+    SSD_CHECK_ARG(h_lens[b] >= 1 && h_lens[b] + 2 * c->K + 2 <= c->max_trunk,
+                  "synthetic prefix of %d positions for sequence %d does not fit max_trunk %d with room for a round", h_lens[b], b,
+                  c->max_trunk);
+    max_len = h_lens[b] > max_len ? h_lens[b] : max_len;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  const Dims& d = c->model->dims;
+  SSD_HIP(hipMemcpyAsync(c->trunk_len, h_lens, sizeof(int32_t) * c->B, hipMemcpyHostToDevice, s));
+  SSD_HIP(hipStreamSynchronize(s));   // h_lens is caller-owned pageable memory
+  for (int l = 0; l < d.n_layers; ++l)
+    SSD_TRY(launch_fill_kv(d.dtype, c->trunk_k[l], c->trunk_v[l], c->trunk_len, c->B, max_len, d.n_kv_heads, d.head_dim,
+                           c->fused_mode ? c->vt_stride : c->max_trunk, c->fused_mode ? 1 : 0, seed, (1ull << 20) + 2 * (uint64_t)l,
+                           (1ull << 20) + 2 * (uint64_t)l + 1, s));
+  c->trunk_ub = max_len;
   c->have_cache = false;
   return SSD_OK;
 }

@@ -25,6 +25,7 @@ __all__ = [
     "ModelShape", "RoundShape", "Workload", "WORKLOADS",
     "round_to_bf16", "bf16_bits", "make_weights", "make_prompt",
     "make_pending", "make_prefix_kv", "weight_names",
+    "hashed_normal", "make_hashed_weights", "make_hashed_prefix_kv",
 ]
 
 
@@ -197,3 +198,72 @@ def make_logits(rows: int, vocab: int, seed: int, scale: float = 0.9, n_ties: in
             pos = g.choice(vocab, size=n_ties, replace=False)
             z[r, pos] = z[r].max()
     return z
+
+
+# --------------------------------------------------------------------------- hashed content (the device generates the same)
+# A second family of synthetic inputs, defined by integer arithmetic alone so that the HIP library can generate the very
+# same bits on the device (models too large for a host copy: the 70B-shaped target).  Element i of tensor t:
+#   bits = mix64(mix64(seed + GOLD (t + 1)) + i)        mix64 = the SplitMix64 finaliser
+#   S    = sum of the four 16-bit lanes of bits          (mean 131070, standard deviation sqrt(4 (65536^2 - 1) / 12))
+#   x    = float32(S - 131070) * float32(std / sigma_S)  one exact conversion, one float32 multiplication
+# then rounded to bf16 for bf16 tensors.  Tensor ids: 0 embedding, 1 LM head, 16 + 16 l + {0 wq, 1 wk, 2 wv, 3 wo,
+# 4 w_gate, 5 w_up, 6 w_down} for layer l, (1 << 20) + 2 l + {0 keys, 1 values} for the synthetic prefix KV of layer l.
+
+_GOLD = np.uint64(0x9E3779B97F4A7C15)
+_SIGMA_S = float(np.sqrt(4.0 * (65536.0 ** 2 - 1.0) / 12.0))
+
+
+def _mix64(x: np.ndarray) -> np.ndarray:
+    x = np.asarray(x, dtype=np.uint64).copy()
+    with np.errstate(over="ignore"):
+        x ^= x >> np.uint64(30)
+        x *= np.uint64(0xBF58476D1CE4E5B9)
+        x ^= x >> np.uint64(27)
+        x *= np.uint64(0x94D049BB133111EB)
+        x ^= x >> np.uint64(31)
+    return x
+
+
+def hashed_normal(seed: int, tensor_id: int, index: np.ndarray, std: float, bf16: bool) -> np.ndarray:
+    """The hashed N(0, std)-like value of every element index in `index` (uint64 array) of tensor `tensor_id`."""
+    with np.errstate(over="ignore"):
+        prefix = _mix64(np.array([np.uint64(seed) + _GOLD * np.uint64(tensor_id + 1)], dtype=np.uint64))[0]
+        bits = _mix64(prefix + np.asarray(index, dtype=np.uint64))
+    m = np.uint64(0xFFFF)
+    S = ((bits & m) + ((bits >> np.uint64(16)) & m) + ((bits >> np.uint64(32)) & m) + (bits >> np.uint64(48))).astype(np.int64)
+    x = (S - 131070).astype(np.float32) * np.float32(std / _SIGMA_S)
+    return round_to_bf16(x) if bf16 else x
+
+
+_HASHED_LEAF = {"wq": 0, "wk": 1, "wv": 2, "wo": 3, "w_gate": 4, "w_up": 5, "w_down": 6}
+
+
+def make_hashed_weights(shape: ModelShape, seed: int, std: float = 0.02) -> Dict[str, np.ndarray]:
+    """Random-init weights from the integer hash (what ssd_model_create_random generates on the device)."""
+    out: Dict[str, np.ndarray] = {}
+    for name in weight_names(shape):
+        shp = weight_shape(shape, name)
+        if name.endswith("norm"):
+            out[name] = np.ones(shp, dtype=np.float32)
+            continue
+        if name == "embed":
+            tid = 0
+        elif name == "lm_head":
+            tid = 1
+        else:
+            layer, leaf = name.split(".")
+            tid = 16 + 16 * int(layer[1:]) + _HASHED_LEAF[leaf]
+        n = int(np.prod(shp))
+        out[name] = hashed_normal(seed, tid, np.arange(n, dtype=np.uint64), std, shape.dtype == "bf16").reshape(shp)
+    return out
+
+
+def make_hashed_prefix_kv(shape: ModelShape, batch: int, prefix: int, seed: int):
+    """Synthetic unit-variance trunk KV from the integer hash (what ssd_ctx_fill_synthetic_kv generates on the device):
+    (k, v), float32 [n_layers][batch][prefix][n_kv_heads][head_dim]."""
+    per_seq = prefix * shape.n_kv_heads * shape.head_dim
+    idx = (np.arange(batch, dtype=np.uint64)[:, None] << np.uint64(40)) + np.arange(per_seq, dtype=np.uint64)[None, :]
+    shp = (batch, prefix, shape.n_kv_heads, shape.head_dim)
+    k = np.stack([hashed_normal(seed, (1 << 20) + 2 * l, idx, 1.0, shape.dtype == "bf16").reshape(shp) for l in range(shape.n_layers)])
+    v = np.stack([hashed_normal(seed, (1 << 20) + 2 * l + 1, idx, 1.0, shape.dtype == "bf16").reshape(shp) for l in range(shape.n_layers)])
+    return k, v
