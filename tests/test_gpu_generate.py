@@ -278,3 +278,130 @@ def test_greedy_ssd_for_a_batch_whose_sequences_diverge(B):
         B.ssd_ctx_destroy(cd)
         B.ssd_model_destroy(mt)
         B.ssd_model_destroy(md)
+
+
+SMALL_BF16 = I.ModelShape(n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ffn=1024,
+                          vocab=4112, dtype="bf16", rope_theta=500000.0, tie_embeddings=True)
+
+
+def gpu_ar_generate(B, side, prompt, n_new):
+    """The model's own greedy autoregressive text on the GPU: one single-token extend per token."""
+    X = [int(t) for t in prompt]
+    B.ssd_ctx_prefill(side.ctx, dev_i32(np.asarray(X[:-1], np.int32)[None, :]), [len(X) - 1])
+    temps = dev_f32(np.zeros(1, np.float32))
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    zero = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(n_new):
+        z = side.extend([X[-1]])
+        B.ssd_sample(z[0], temps, 0, 0, 0, out)
+        X.append(int(out[0]))
+        side.commit(zero)                              # accept length 0: the trunk grows by the one token
+    return X[len(prompt):]
+
+
+def test_bf16_pair_on_the_fused_pass_hundreds_of_rounds_greedy(B):
+    """Alg. 1 for more than 200 rounds on a small bf16 pair whose every forward (prefill chunks, verification extends, glue
+    extends, branch steps) runs through the persistent fused pass.  Losslessness (Sec. 2.1): the text equals the same
+    target's own greedy autoregressive text, computed on the same GPU token by token; all accept lengths, hits and
+    misses occur on the way, and the trunk walks across dozens of 32-position blocks of the value layout."""
+    shape, K, F, P, n_new = SMALL_BF16, 4, 3, 19, 1100
+    wt = I.make_weights(shape, 41)
+    wd = I.make_weights(shape, 42, perturb_of=wt, perturb_std=0.006)
+    prompt = I.make_prompt(shape, 1, P, 43)[0]
+    cap = P + n_new + 4 * K + 8
+    ref = Side(B, shape, wt, K, 1, cap)
+    try:
+        assert B.ssd_ctx_views(ref.ctx).fused_pass == 2
+        want = gpu_ar_generate(B, ref, prompt, n_new)
+    finally:
+        ref.close()
+    target, draft = Side(B, shape, wt, K, 1, cap), Side(B, shape, wd, K, F, cap)
+    try:
+        assert B.ssd_ctx_views(draft.ctx).fused_pass == 2 and B.ssd_ctx_views(target.ctx).fused_pass == 2
+        got, gs = gpu_ssd_generate(B, target, draft, prompt, n_new, K, F)
+        hist = np.bincount(gs["accept_lens"], minlength=K + 1)
+        print(f"[gpu bf16] rounds {gs['rounds']} hits {gs['hits']} accepted {gs['accepted']} accept-length histogram {hist.tolist()}",
+              flush=True)
+        assert got == want
+        # (a random-init model soon repeats itself, so accept lengths cluster at 0 and K; the ones between still occur)
+        assert gs["rounds"] >= 200 and (hist > 0).sum() >= 3 and 0 < gs["hits"] < gs["rounds"]
+        B.ssd_ctx_status(draft.ctx)
+        B.ssd_ctx_status(target.ctx)
+    finally:
+        target.close()
+        draft.close()
+
+
+def test_bf16_pair_sampled_rounds_decide_like_the_oracle_on_the_same_logits(B):
+    """Alg. 1 at temperature 0.25 on the bf16 pair: every round's verification outcome (k, t*) equals what the oracle's
+    rejection sampling decides on the very logits the kernels produced (target's verification logits, and the logits the
+    pending speculation was drawn from: the cache's on a hit, the just-in-time ones on a miss), near-ties excepted; hits
+    and misses both occur, and the trunk lengths of both sides stay in step with the text."""
+    shape, K, F, P, T, n_rounds = SMALL_BF16, 3, 8, 23, 0.25, 40
+    wt = I.make_weights(shape, 51)
+    wd = I.make_weights(shape, 52, perturb_of=wt, perturb_std=0.003)
+    prompt = [int(t) for t in I.make_prompt(shape, 1, P, 53)[0]]
+    V = shape.vocab
+    cap = P + n_rounds * (K + 1) + 4 * K + 8
+    target, draft = Side(B, shape, wt, K, 1, cap), Side(B, shape, wd, K, F, cap)
+    temps = dev_f32(np.full(1, T, np.float32))
+    acc = torch.zeros(1, dtype=torch.int32, device="cuda")
+    bonus = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hit = torch.zeros(1, dtype=torch.uint8, device="cuda")
+    branch = torch.zeros(1, dtype=torch.int32, device="cuda")
+    nxt = torch.zeros((1, K), dtype=torch.int32, device="cuda")
+    ptr = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ws = torch.empty(B.ssd_verify_workspace_bytes(1, K), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def jit(last, seed):
+        toks, logits, tok = [], [], int(last)
+        for i in range(K):
+            z = draft.extend([tok], offset=i)
+            B.ssd_sample(z[0], temps, seed, 0, i, out)
+            tok = int(out[0])
+            toks.append(tok)
+            logits.append(z[0, 0].clone())
+        return toks, torch.stack(logits)[None].contiguous()
+
+    try:
+        X = list(prompt)
+        for side in (target, draft):
+            B.ssd_ctx_prefill(side.ctx, dev_i32(np.asarray(X[:-1], np.int32)[None, :]), [len(X) - 1])
+        spec, zd = jit(X[-1], 7)
+        s_draft, s_target = torch.cuda.Stream(), torch.cuda.Stream()
+        hits = n_checked = 0
+        ks = []
+        for rnd in range(1, n_rounds + 1):
+            pending = dev_i32(np.asarray([X[-1]] + spec, np.int32)[None, :])
+            zt = torch.empty((1, K + 1, V), dtype=torch.float32, device="cuda")
+            torch.cuda.synchronize()
+            B.ssd_ctx_extend(target.ctx, pending, 0, zt, stream=s_target)
+            B.ssd_verify(zt, zd, pending[:, 1:].contiguous(), temps, 1000 + rnd, acc, bonus, ws, stream=s_target)
+            B.ssd_prespeculate(draft.ctx, pending, temps, 1000 + rnd, stream=s_draft)
+            torch.cuda.synchronize()
+            k, t = int(acc[0]), int(bonus[0])
+            tr = O.verify(zt[0].cpu().numpy().astype(np.float64), zd[0].cpu().numpy().astype(np.float64), spec, T, 1000 + rnd, 0)
+            if min(tr.accept_margin + [1.0]) > 1e-4 and tr.bonus_margin > 1e-4:
+                assert (k, t) == (tr.accept_len, tr.bonus), (rnd, k, t, tr)
+                n_checked += 1
+            B.ssd_cache_lookup(draft.ctx, acc, bonus, hit, branch, nxt, ptr)
+            torch.cuda.synchronize()
+            X += spec[:k] + [t]
+            ks.append(k)
+            target.commit(acc)
+            draft.commit(acc)
+            tl = [int(B.read_cache(s.ctx, with_logits=False)["trunk_len"][0]) for s in (target, draft)]
+            assert tl == [len(X) - 1, len(X) - 1]
+            if int(hit[0]):
+                hits += 1
+                spec = [int(x) for x in nxt[0].cpu().numpy()]
+                # the hit branch's logits leave the cache before the next round rewrites it (the payload of App. B)
+                zd = B.device_copy(int(ptr[0]), (1, K, V), torch.float32)
+            else:
+                spec, zd = jit(t, 2000 + rnd)
+        print(f"[gpu bf16 sampled] {n_rounds} rounds, {hits} hits, accept lengths {ks}, {n_checked} outcomes compared", flush=True)
+        assert n_checked >= n_rounds - 2 and 0 < hits < n_rounds and len(set(ks)) >= 3
+    finally:
+        target.close()
+        draft.close()
