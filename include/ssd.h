@@ -95,6 +95,11 @@ typedef struct {
   int32_t F;         /* 1..SSD_MAX_F bonus-token candidates per accept length */
   int32_t max_trunk; /* capacity of the trunk KV in positions, per sequence */
   int32_t flags;     /* 0, or SSD_CTX_* bits: which kernels serve the context (results are the same to rounding) */
+  int32_t kv_pages;  /* 0: every sequence owns max_trunk trunk positions.  n >= 2: paged trunk (App. B, the paged attention and
+                        block tables of the paper's system): per layer one pool of n pages of 32 positions, shared by the
+                        sequences, each reaching its positions through its row of a block table; page 0 is the all-zero
+                        page every unmapped block points at and is never handed out.  Fused contexts only, max_trunk <=
+                        16384 (it then only sizes the block table).  Same bits as the contiguous trunk. */
 } ssd_round_config;
 
 /* ssd_round_config.flags.  By default a context whose model and shape the fused decode pass supports (bf16, head_dim 64)
@@ -125,7 +130,7 @@ typedef struct {
   const float* d_glue_logits;  /* [B][K+1][V] logits of the glue extend */
   const float* d_glue_hidden;  /* [B][K+1][d_model] */
   const void* const* h_trunk_k; /* host array [n_layers] of device [B][max_trunk][Hkv][D] (model dtype) */
-  const void* const* h_trunk_v; /* same layout.  Contexts served by the fused decode pass (bf16, head_dim 64, at most 48
+  const void* const* h_trunk_v; /* same layout (both null-free but not meaningful to read in a paged context).  Contexts served by the fused decode pass (bf16, head_dim 64, at most 48
                                    rows per pass) keep both head-major with T = max_trunk rounded up to 64: keys
                                    [B][Hkv][T][D], values transposed per 32-position block [B][Hkv][T/32][D][32] */
   int32_t batch, K, F, vocab, d_model, max_trunk;
@@ -184,6 +189,22 @@ int ssd_ctx_fill_synthetic_kv(ssd_ctx* ctx, const int32_t* h_lens, uint64_t seed
  * lengths; host int32 [B], read during the call): a batch of different prefix lengths from one loaded or prefilled
  * block, or a rollback.  EINVAL if a length is out of range.  Synchronises `stream`. */
 int ssd_ctx_truncate_trunk(ssd_ctx* ctx, const int32_t* h_lens, void* stream);
+
+/* Paged contexts and continuous batching (App. B).  Pages are taken when a call is about to write positions a sequence
+ * has no page for (prefill, load, and the glue extend of a round: up to the host's bound of the trunk length + K+1) and
+ * handed back by the calls that synchronise: ssd_ctx_refresh_bounds (page rollback: pages wholly behind a sequence's
+ * verified text, i.e. rejected positions and bounds that ran ahead), ssd_ctx_truncate_trunk, ssd_ctx_release_sequence.
+ * ENOMEM when the pool is empty: the context is unchanged apart from pages already taken for the same call; release a
+ * sequence or refresh the bounds and call again.
+ *   ssd_ctx_kv_pages          total pages (0 for a contiguous trunk) and pages currently free.
+ *   ssd_ctx_release_sequence  sequence b finished: its pages return to the pool and its trunk is empty; a round must not
+ *                             run before the slot is refilled (ESTATE from ssd_prespeculate: empty trunk).  Synchronises.
+ *   ssd_ctx_prefill_sequence  slot b := KV of d_tokens[0 .. len-1] (device int32), computed by extend passes over that one
+ *                             sequence while the other slots keep their state: the join of a new request.  Works for
+ *                             contiguous contexts too.  The speculation cache is dropped.  Synchronises. */
+int ssd_ctx_kv_pages(const ssd_ctx* ctx, int32_t* total, int32_t* free_pages);
+int ssd_ctx_release_sequence(ssd_ctx* ctx, int32_t b, void* stream);
+int ssd_ctx_prefill_sequence(ssd_ctx* ctx, int32_t b, const int32_t* d_tokens, int32_t len, void* stream);
 
 /* ---- hot path --------------------------------------------------------------------------------- */
 

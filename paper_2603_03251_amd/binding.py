@@ -7,7 +7,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import Dict, List, Optional, Sequence
+from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
 import torch  # imported before the library so that both share one HIP runtime
@@ -42,7 +42,7 @@ class ssd_model_weights(C.Structure):
 
 
 class ssd_round_config(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("batch", "K", "F", "max_trunk", "flags")]
+    _fields_ = [(n, C.c_int32) for n in ("batch", "K", "F", "max_trunk", "flags", "kv_pages")]
 
 
 class ssd_views(C.Structure):
@@ -63,6 +63,9 @@ EXPORTS = {
     "ssd_ctx_destroy": (C.c_int, [C.c_void_p]),
     "ssd_ctx_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p]),
     "ssd_ctx_fill_synthetic_kv": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.c_uint64, C.c_void_p]),
+    "ssd_ctx_kv_pages": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "ssd_ctx_release_sequence": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
+    "ssd_ctx_prefill_sequence": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]),
     "ssd_ctx_load_trunk": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "ssd_prespeculate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "ssd_ctx_set_forced": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -206,16 +209,17 @@ def ssd_model_destroy(model: int) -> None:
     _check(lib.ssd_model_destroy(model))
 
 
-def ssd_ctx_create(model: int, batch: int, K: int, F: int, max_trunk: int, flags: int = 0) -> int:
-    cfg = ssd_round_config(batch, K, F, max_trunk, flags)
+def ssd_ctx_create(model: int, batch: int, K: int, F: int, max_trunk: int, flags: int = 0, kv_pages: int = 0) -> int:
+    cfg = ssd_round_config(batch, K, F, max_trunk, flags, kv_pages)
     out = C.c_void_p()
     _check(lib.ssd_ctx_create(model, C.byref(cfg), C.byref(out)))
     return out.value
 
 
-def ssd_ctx_create_fanout(model: int, batch: int, K: int, fanout: Sequence[int], max_trunk: int, flags: int = 0) -> int:
+def ssd_ctx_create_fanout(model: int, batch: int, K: int, fanout: Sequence[int], max_trunk: int, flags: int = 0,
+                          kv_pages: int = 0) -> int:
     assert len(fanout) == K + 1
-    cfg = ssd_round_config(batch, K, 0, max_trunk, flags)
+    cfg = ssd_round_config(batch, K, 0, max_trunk, flags, kv_pages)
     fan = (C.c_int32 * (K + 1))(*[int(f) for f in fanout])
     out = C.c_void_p()
     _check(lib.ssd_ctx_create_fanout(model, C.byref(cfg), fan, C.byref(out)))
@@ -246,6 +250,23 @@ def ssd_ctx_prefill(ctx: int, tokens: torch.Tensor, lens: Sequence[int], stream=
 
 def ssd_ctx_load_trunk(ctx: int, k: torch.Tensor, v: torch.Tensor, length: int, stream=None) -> None:
     _check(lib.ssd_ctx_load_trunk(ctx, _ptr(k), _ptr(v), length, _stream(stream)))
+
+
+def ssd_ctx_kv_pages(ctx: int) -> Tuple[int, int]:
+    """(pages of the pool, pages free); (0, 0) for a contiguous trunk."""
+    total, free = C.c_int32(), C.c_int32()
+    _check(lib.ssd_ctx_kv_pages(ctx, C.byref(total), C.byref(free)))
+    return total.value, free.value
+
+
+def ssd_ctx_release_sequence(ctx: int, b: int, stream=None) -> None:
+    _check(lib.ssd_ctx_release_sequence(ctx, b, _stream(stream)))
+
+
+def ssd_ctx_prefill_sequence(ctx: int, b: int, tokens: torch.Tensor, stream=None) -> None:
+    """tokens: device int32 [len]"""
+    assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.dim() == 1 and tokens.is_contiguous()
+    _check(lib.ssd_ctx_prefill_sequence(ctx, b, tokens.data_ptr(), tokens.numel(), _stream(stream)))
 
 
 def ssd_ctx_fill_synthetic_kv(ctx: int, lens: Sequence[int], seed: int, stream=None) -> None:

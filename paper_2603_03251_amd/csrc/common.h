@@ -107,7 +107,7 @@ int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk
                              const int32_t* cache_tokens, const int32_t* forced_keys, const int32_t* forced_tokens,
                              hipStream_t s);
 int launch_setup_extend_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int T, int offset,
-                             int half_dim, float theta, hipStream_t s);
+                             int half_dim, float theta, int seq_base, hipStream_t s);
 int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* h, int M, int d, int vocab, hipStream_t s);
 int launch_rmsnorm(int dtype, const float* h, const void* gain, void* xn, int64_t xn_plane, float* copy_out,
                    int64_t copy_ld, int M, int d, float eps, hipStream_t s);
@@ -131,7 +131,7 @@ int launch_copy_kv_in(int dtype, void* trunk, const void* src, int B, int len, i
 int launch_fill_hashed(int dtype, void* dst, int64_t n, uint64_t seed, uint64_t tensor_id, double std, hipStream_t s);
 int launch_fill_const(int dtype, void* dst, int64_t n, float v, hipStream_t s);
 int launch_fill_kv(int dtype, void* k, void* v, const int32_t* len, int B, int max_len, int Hkv, int D, int stride, int fused,
-                   uint64_t seed, uint64_t id_k, uint64_t id_v, hipStream_t s);
+                   const int32_t* pages, int page_stride, uint64_t seed, uint64_t id_k, uint64_t id_v, hipStream_t s);
 
 // ---------------------------------------------------------------- kernels_gemm.hip
 enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL_ADD = 1, EPI_SWIGLU = 2 };

@@ -54,6 +54,11 @@ struct FusedParams {
   const float* cos_sin;                    // [M][32][2]
   const int32_t* tokens;
   int max_trunk, vt_stride, suffix_cap;
+  // paged trunk (null: contiguous): block j (32 positions) of sequence b of this pass is page pages[b * page_stride + j]
+  // of the pool every layer's trunk_k / trunk_vt point at ([page][Hkv][32][64] keys, [page][Hkv][64][32] values);
+  // page 0 is never handed out and holds zeros
+  const int32_t* pages;
+  int page_stride;
   // attention work split: unit = (sequence, KV head, 16-row query tile, key split)
   int KPU;                                 // stored trunk keys per split (multiple of 32)
   int NS;                                  // key splits; 1 = the attention phase writes the final output
@@ -100,7 +105,7 @@ int launch_retile_stream(const bf16_t* src0, int rows0, const bf16_t* src1, int 
 int64_t stream_order_elems(int N, int Kd, int AT);
 // [B][len][Hkv][64] keys and values -> the trunk layouts of FusedLayer
 int launch_copy_kv_fused(bf16_t* trunk_k, bf16_t* trunk_vt, const bf16_t* src_k, const bf16_t* src_v, int B, int len, int Hkv,
-                         int vt_stride, hipStream_t s);
+                         int vt_stride, const int32_t* pages, int page_stride, hipStream_t s);
 
 // feature tiles per unit of each linear layer
 constexpr int kAtQkv = 2, kAtO = 2, kAtGu = 4, kAtDown = 2, kAtLm = 4;
@@ -115,7 +120,7 @@ int launch_fused_wide(const FusedParams& p, const FusedLayer* layers_host, int f
 bool fused_wide_gemm_ok(const FusedGemm& g, int at);
 int fused_grid_size(int* out);
 // EINVAL unless `nwg` workgroups of every instance of the persistent kernel can be resident at once on the current device
-int fused_check_residency(int nwg, int planes);
+int fused_check_residency(int nwg, int planes, int paged);
 bool fused_planes_supported(int planes);
 // Barrier words (kFusedSyncWords of them + the error word behind) as a finished barrier number `epoch0` leaves them;
 // 0 for a new context.  The epoch counts on from launch to launch and wraps after 2^32 barriers.

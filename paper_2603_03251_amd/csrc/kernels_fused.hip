@@ -654,7 +654,7 @@ __device__ __forceinline__ f32x4 score_tile(bf16x8 k0, bf16x8 k1, const Bf8 qh[2
 // fresh-key sources) is issued up front; loop counts come from the host's bound on the visible trunk, the true
 // visibility only masks.  The 8 partial softmaxes meet in LDS; with one split the result goes straight to the
 // o-projection's operand planes, otherwise to the partial buffers of the merge phase.
-template <int MT, int MP, int NPQ, int NPP, int NPT>
+template <int MT, int MP, int NPQ, int NPP, int NPT, bool PG>
 __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
                                           const float* r_s, f32x4* lds, bf16_t* att_out, float* part_o, float* part_ml, int ph,
                                           Grid* wait_on) {
@@ -689,8 +689,15 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
   const int krow = (li >> 2) * 8 + (li & 3);                  // key of this lane's A-operand row in a block (tile 0)
   // trunk K [B][Hkv][vt_stride][64]; trunk V^T [B][Hkv][vt_stride / 32][64 dims][32 keys]: a 32-key block of one head is
   // 4 KiB of contiguous memory in both, so every operand load covers whole cache lines
-  const gbf16* kbase = (const gbf16*)L.trunk_k + ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64 + g4 * 8;
-  const gbf16* vbase = (const gbf16*)L.trunk_vt + ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64 + li * 32 + g4 * 8;
+  // PG (paged trunk, App. B "PagedAttention"): block j of sequence b is page p.pages[b][j] of a pool shared by all
+  // sequences, a page = the same 4 KiB per head and operand as a block of the contiguous layouts.  Lane i of a wavefront
+  // fetches the page of the wavefront's i-th block up front (one load), so the block loop itself stays free of
+  // dependent loads; entries behind a sequence's allocation name page 0, which exists and holds zeros.
+  const int64_t head0 = PG ? 0 : ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64;
+  const gbf16* kbase = (const gbf16*)L.trunk_k + head0 + g4 * 8;
+  const gbf16* vbase = (const gbf16*)L.trunk_vt + head0 + li * 32 + g4 * 8;
+  int pgs = 0;
+  if constexpr (PG) pgs = p.pages[(int64_t)b * p.page_stride + min((kb0 >> 5) + wave + kFusedWaves * lane, p.page_stride - 1)];
   struct TrunkBlock {
     bf16x8 k[2][2];
     bf16x8 vt[4];
@@ -698,16 +705,18 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
   constexpr int RING = 2;
   TrunkBlock ring[RING];
   auto load_trunk = [&](TrunkBlock& tb, int i) {   // i-th block of this wavefront, clamped to its last one
-    const int blk = wave + kFusedWaves * max(min(i, n_mine - 1), 0);
+    const int ic = max(min(i, n_mine - 1), 0);
+    const int blk = wave + kFusedWaves * ic;
     const int kb = min(kb0 + blk * 32, p.vt_stride - 32);
+    const int64_t bo = PG ? ((int64_t)__builtin_amdgcn_readlane(pgs, ic) * p.Hkv + hk) * 2048 : (int64_t)kb * 64;
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
-      const gbf16* kp = kbase + (int64_t)(kb + krow + tile * 4) * 64;
+      const gbf16* kp = kbase + bo + (krow + tile * 4) * 64;
       tb.k[tile][0] = *(const gbf16x8*)kp;
       tb.k[tile][1] = *(const gbf16x8*)(kp + 32);
     }
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) tb.vt[dt] = *(const gbf16x8*)(vbase + (int64_t)kb * 64 + dt * 16 * 32);
+    for (int dt = 0; dt < 4; ++dt) tb.vt[dt] = *(const gbf16x8*)(vbase + bo + dt * 16 * 32);
   };
 #pragma unroll
   for (int i = 0; i < RING; ++i) load_trunk(ring[i], i);   // unconditional (a wavefront without blocks re-reads block 0)
@@ -959,11 +968,12 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
         *(gu32x2*)(L.suffix_k + row + 32 + x.q8 * 4) = k_hi;
         *(gbf16x8*)(L.suffix_v + row + x.q8 * 8) = vv.v;
       } else {
-        const int64_t head = (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64;
-        const int64_t row = head + (int64_t)fresh_slot * 64;
+        const int64_t bb = PG ? ((int64_t)p.pages[(int64_t)b * p.page_stride + (fresh_slot >> 5)] * p.Hkv + hk) * 2048
+                              : (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64 + (int64_t)(fresh_slot >> 5) * 2048;
+        const int64_t row = bb + (int64_t)(fresh_slot & 31) * 64;
         *(gu32x2*)(L.trunk_k + row + x.q8 * 4) = k_lo;
         *(gu32x2*)(L.trunk_k + row + 32 + x.q8 * 4) = k_hi;
-        gbf16* vcol = (gbf16*)L.trunk_vt + head + (int64_t)(fresh_slot >> 5) * 2048 + (x.q8 * 8) * 32 + (fresh_slot & 31);
+        gbf16* vcol = (gbf16*)L.trunk_vt + bb + (x.q8 * 8) * 32 + (fresh_slot & 31);
 #pragma unroll
         for (int e = 0; e < 8; ++e) vcol[e * 32] = vv.u[e];
       }
@@ -979,7 +989,7 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
 // layouts as attn_unit; the qkv projections arrive with the norm's row scale applied.  Fresh keys: those of all the
 // unit's query tiles (branch rows) or the pass's tokens (extend rows), staged once, NFI items per thread.
 constexpr int kMultiFreshKeys = 192;   // LDS room: NQ x (rows per tile x slots per row) for NQ = 3, or the tokens of an extend
-template <int MT, int MP, int NPQ, int NPP, int NQ>
+template <int MT, int MP, int NPQ, int NPP, int NQ, bool PG>
 __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit, f32x4* lds,
                                                 bf16_t* att_out, float* part_o, float* part_ml) {
   const ThreadIds ids = fresh_thread_ids();
@@ -1017,8 +1027,15 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
   const int n_fresh_keys = is_branch ? (NQ * rpt) << sl_log : p.R;
   const int n_fb = s == 0 ? (n_fresh_keys + 31) >> 5 : 0;
   const int krow = (li >> 2) * 8 + (li & 3);                  // key of this lane's A-operand row in a block (tile 0)
-  const gbf16* kbase = (const gbf16*)L.trunk_k + ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64 + g4 * 8;
-  const gbf16* vbase = (const gbf16*)L.trunk_vt + ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64 + li * 32 + g4 * 8;
+  // PG (paged trunk, App. B "PagedAttention"): block j of sequence b is page p.pages[b][j] of a pool shared by all
+  // sequences, a page = the same 4 KiB per head and operand as a block of the contiguous layouts.  Lane i of a wavefront
+  // fetches the page of the wavefront's i-th block up front (one load), so the block loop itself stays free of
+  // dependent loads; entries behind a sequence's allocation name page 0, which exists and holds zeros.
+  const int64_t head0 = PG ? 0 : ((int64_t)(b * p.Hkv + hk) * p.vt_stride) * 64;
+  const gbf16* kbase = (const gbf16*)L.trunk_k + head0 + g4 * 8;
+  const gbf16* vbase = (const gbf16*)L.trunk_vt + head0 + li * 32 + g4 * 8;
+  int pgs = 0;
+  if constexpr (PG) pgs = p.pages[(int64_t)b * p.page_stride + min((kb0 >> 5) + wave + kFusedWaves * lane, p.page_stride - 1)];
   struct TrunkBlock {
     bf16x8 k[2][2];
     bf16x8 vt[4];
@@ -1026,16 +1043,18 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
   constexpr int RING = 2;
   TrunkBlock ring[RING];
   auto load_trunk = [&](TrunkBlock& tb, int i) {   // i-th block of this wavefront, clamped to its last one
-    const int blk = wave + kFusedWaves * max(min(i, n_mine - 1), 0);
+    const int ic = max(min(i, n_mine - 1), 0);
+    const int blk = wave + kFusedWaves * ic;
     const int kb = min(kb0 + blk * 32, p.vt_stride - 32);
+    const int64_t bo = PG ? ((int64_t)__builtin_amdgcn_readlane(pgs, ic) * p.Hkv + hk) * 2048 : (int64_t)kb * 64;
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
-      const gbf16* kp = kbase + (int64_t)(kb + krow + tile * 4) * 64;
+      const gbf16* kp = kbase + bo + (krow + tile * 4) * 64;
       tb.k[tile][0] = *(const gbf16x8*)kp;
       tb.k[tile][1] = *(const gbf16x8*)(kp + 32);
     }
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) tb.vt[dt] = *(const gbf16x8*)(vbase + (int64_t)kb * 64 + dt * 16 * 32);
+    for (int dt = 0; dt < 4; ++dt) tb.vt[dt] = *(const gbf16x8*)(vbase + bo + dt * 16 * 32);
   };
 #pragma unroll
   for (int i = 0; i < RING; ++i) load_trunk(ring[i], i);   // unconditional (a wavefront without blocks re-reads block 0)
@@ -1263,11 +1282,12 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
         *(gbf16x8*)(L.suffix_v + row + q8 * 8) = vv.v;
       } else {
         const int slot = p.rows[m_o].kv_slot;
-        const int64_t head = (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64;
-        const int64_t row = head + (int64_t)slot * 64;
+        const int64_t bb = PG ? ((int64_t)p.pages[(int64_t)b * p.page_stride + (slot >> 5)] * p.Hkv + hk) * 2048
+                              : (int64_t)(b * p.Hkv + hk) * p.vt_stride * 64 + (int64_t)(slot >> 5) * 2048;
+        const int64_t row = bb + (int64_t)(slot & 31) * 64;
         *(gu32x2*)(L.trunk_k + row + q8 * 4) = k_lo;
         *(gu32x2*)(L.trunk_k + row + 32 + q8 * 4) = k_hi;
-        gbf16* vcol = (gbf16*)L.trunk_vt + head + (int64_t)(slot >> 5) * 2048 + (q8 * 8) * 32 + (slot & 31);
+        gbf16* vcol = (gbf16*)L.trunk_vt + bb + (q8 * 8) * 32 + (slot & 31);
 #pragma unroll
         for (int e = 0; e < 8; ++e) vcol[e * 32] = vv.u[e];
       }
@@ -1781,7 +1801,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
 
 // The other phases of a wide pass (embedding, attention, merge of key splits, final hidden states), one launch each:
 // the narrow pass's units over a workspace of kFusedWideRows rows, one bf16 plane per tensor.
-template <class PL>
+template <class PL, bool PG>
 __global__ __launch_bounds__(kFusedThreads) void wide_kernel(FusedParams p, int ph) {
   constexpr int MP = kFusedWideRows, MTOT = kWideTiles;
   extern __shared__ f32x4 red[];
@@ -1833,7 +1853,7 @@ __global__ __launch_bounds__(kFusedThreads) void wide_kernel(FusedParams p, int 
     }
   } else if (sub == 1) {
     for (int u = blockIdx.x; u < p.n_attn_units; u += gridDim.x)
-      attn_unit_multi<MTOT, MP, PL::q, PL::p, kWideQueryTiles>(p, L, qkv, u, red, att, part_o, part_ml);
+      attn_unit_multi<MTOT, MP, PL::q, PL::p, kWideQueryTiles, PG>(p, L, qkv, u, red, att, part_o, part_ml);
   } else if (sub == 2) {
     for (int u = blockIdx.x; u < p.n_pair_units; u += gridDim.x) attn_merge_unit<MTOT, MP, 1>(p, u, part_o, part_ml, att);
   } else if (sub == 6 && p.hidden) {
@@ -1866,7 +1886,7 @@ template <int MT, bool DEEP, int NP> struct Depth {
   static constexpr int a4 = !DEEP ? 2 : (MT * NP > 4 ? 2 : 4);   // four feature tiles per unit
 };
 
-template <int MT, bool DEEP, class PL>
+template <int MT, bool DEEP, class PL, bool PG>
 __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int first, int last, int persistent) {
   constexpr int MP = kFusedMaxRows;
   extern __shared__ f32x4 red[];
@@ -1982,7 +2002,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       // a workgroup with a unit waits for the grid inside its first unit, after requesting that unit's stored keys
       bool waited = !do_wait;
       for (int u = p.nwg - 1 - (int)blockIdx.x; u < p.n_attn_units; u += p.nwg) {
-        if (!attn_unit<MT, MP, PL::q, PL::p, PL::att>(p, L, qkv, u, r_s, red, att, part_o, part_ml, ph, waited ? nullptr : &grid)) return;
+        if (!attn_unit<MT, MP, PL::q, PL::p, PL::att, PG>(p, L, qkv, u, r_s, red, att, part_o, part_ml, ph, waited ? nullptr : &grid)) return;
         waited = true;
       }
       if (!waited) {
@@ -2041,8 +2061,9 @@ __global__ void retile_stream_kernel(const bf16_t* __restrict__ src0, int rows0,
 }
 
 // [B][len][Hkv][64] keys and values -> the head-major trunk layouts of the fused pass
+// pages != null: paged trunk, block j of sequence b in page pages[b * page_stride + j] of the pool
 __global__ void copy_kv_fused_kernel(bf16_t* trunk_k, bf16_t* trunk_vt, const bf16_t* src_k, const bf16_t* src_v, int len,
-                                     int Hkv, int vt_stride, int64_t total) {
+                                     int Hkv, int vt_stride, int64_t total, const int32_t* pages, int page_stride) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // over [B][len][Hkv][64]
   if (idx >= total) return;
   int d = (int)(idx & 63);
@@ -2051,38 +2072,39 @@ __global__ void copy_kv_fused_kernel(bf16_t* trunk_k, bf16_t* trunk_vt, const bf
   r /= Hkv;
   int pos = (int)(r % len);
   int64_t b = r / len;
-  const int64_t head = (b * Hkv + hk) * (int64_t)vt_stride * 64;
-  trunk_k[head + (int64_t)pos * 64 + d] = src_k[idx];
-  trunk_vt[head + (int64_t)(pos >> 5) * 2048 + d * 32 + (pos & 31)] = src_v[idx];
+  const int64_t bb = pages ? ((int64_t)pages[b * page_stride + (pos >> 5)] * Hkv + hk) * 2048
+                           : (b * Hkv + hk) * (int64_t)vt_stride * 64 + (int64_t)(pos >> 5) * 2048;
+  trunk_k[bb + (int64_t)(pos & 31) * 64 + d] = src_k[idx];
+  trunk_vt[bb + d * 32 + (pos & 31)] = src_v[idx];
 }
 
 constexpr size_t kFusedLdsBytes = 96 * 1024;   // reduction tiles (<= 8 wavefronts x 12 tiles x 1 KiB); also keeps one workgroup per CU
 
-template <int MT, bool DEEP, class PL>
+template <int MT, bool DEEP, class PL, bool PG>
 int check_residency_mt(int nwg, int cus) {
-  SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
+  SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL, PG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
   int per_cu = 0;
-  SSD_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fused_kernel<MT, DEEP, PL>, kFusedThreads, kFusedLdsBytes));
+  SSD_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fused_kernel<MT, DEEP, PL, PG>, kFusedThreads, kFusedLdsBytes));
   SSD_CHECK_ARG((int64_t)per_cu * cus >= nwg,
                 "fused pass: %d workgroups cannot be resident at once (%d per compute unit x %d compute units): the grid barrier "
                 "would never complete", nwg, per_cu, cus);
   return SSD_OK;
 }
 
-template <int MT, bool DEEP, class PL>
+template <int MT, bool DEEP, class PL, bool PG>
 int launch_mt(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
   const size_t lds = kFusedLdsBytes;
   static bool configured = false;
   if (!configured) {
-    SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL, PG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     configured = true;
   }
   if (persistent) {
-    fused_kernel<MT, DEEP, PL><<<p.nwg, kFusedThreads, lds, s>>>(p, first, last, 1);
+    fused_kernel<MT, DEEP, PL, PG><<<p.nwg, kFusedThreads, lds, s>>>(p, first, last, 1);
     SSD_HIP(hipGetLastError());
   } else {
     for (int ph = first; ph <= last; ++ph) {
-      fused_kernel<MT, DEEP, PL><<<p.nwg, kFusedThreads, lds, s>>>(p, ph, ph, 0);
+      fused_kernel<MT, DEEP, PL, PG><<<p.nwg, kFusedThreads, lds, s>>>(p, ph, ph, 0);
       SSD_HIP(hipGetLastError());
     }
   }
@@ -2111,10 +2133,10 @@ int launch_retile_stream(const bf16_t* src0, int rows0, const bf16_t* src1, int 
 }
 
 int launch_copy_kv_fused(bf16_t* trunk_k, bf16_t* trunk_vt, const bf16_t* src_k, const bf16_t* src_v, int B, int len, int Hkv,
-                         int vt_stride, hipStream_t s) {
+                         int vt_stride, const int32_t* pages, int page_stride, hipStream_t s) {
   int64_t total = (int64_t)B * len * Hkv * 64;
   if (total == 0) return SSD_OK;
-  copy_kv_fused_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(trunk_k, trunk_vt, src_k, src_v, len, Hkv, vt_stride, total);
+  copy_kv_fused_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(trunk_k, trunk_vt, src_k, src_v, len, Hkv, vt_stride, total, pages, page_stride);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }
@@ -2159,14 +2181,14 @@ int fused_grid_size(int* out) {
 template <int MASK>
 using PlanesOf = Planes<(MASK & 1) ? 1 : 2, (MASK & 2) ? 1 : 2, (MASK & 4) ? 1 : 2, (MASK & 8) ? 1 : 2, (MASK & 16) ? 1 : 2>;
 
-template <class PL>
+template <class PL, bool PG>
 int check_residency_pl(int nwg, int cus) {
-  SSD_TRY((check_residency_mt<1, true, PL>(nwg, cus)));
-  SSD_TRY((check_residency_mt<2, true, PL>(nwg, cus)));
-  SSD_TRY((check_residency_mt<3, true, PL>(nwg, cus)));
-  SSD_TRY((check_residency_mt<1, false, PL>(nwg, cus)));
-  SSD_TRY((check_residency_mt<2, false, PL>(nwg, cus)));
-  SSD_TRY((check_residency_mt<3, false, PL>(nwg, cus)));
+  SSD_TRY((check_residency_mt<1, true, PL, PG>(nwg, cus)));
+  SSD_TRY((check_residency_mt<2, true, PL, PG>(nwg, cus)));
+  SSD_TRY((check_residency_mt<3, true, PL, PG>(nwg, cus)));
+  SSD_TRY((check_residency_mt<1, false, PL, PG>(nwg, cus)));
+  SSD_TRY((check_residency_mt<2, false, PL, PG>(nwg, cus)));
+  SSD_TRY((check_residency_mt<3, false, PL, PG>(nwg, cus)));
   return SSD_OK;
 }
 
@@ -2212,11 +2234,11 @@ int launch_wide_gemm(const FusedParams& p, const FusedGemm& g, const bf16_t* bsr
 }
 
 // One wide pass: phases [first, last] as one launch each.  layers_host: the pass's layer table in host memory.
-template <class PL>
+template <class PL, bool PG>
 int launch_wide_pl(const FusedParams& p, const FusedLayer* layers_host, int first, int last, hipStream_t s) {
   static bool configured = false;
   if (!configured) {
-    SSD_HIP(hipFuncSetAttribute((const void*)wide_kernel<PL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
+    SSD_HIP(hipFuncSetAttribute((const void*)wide_kernel<PL, PG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
     configured = true;
   }
   constexpr int64_t MP = kFusedWideRows;
@@ -2258,24 +2280,24 @@ int launch_wide_pl(const FusedParams& p, const FusedLayer* layers_host, int firs
       if (sub == 1) grid = p.n_attn_units;
       else if (sub == 2) grid = p.n_pair_units;
       else if (sub == 6) grid = p.M;
-      wide_kernel<PL><<<grid, kFusedThreads, kFusedLdsBytes, s>>>(p, ph);
+      wide_kernel<PL, PG><<<grid, kFusedThreads, kFusedLdsBytes, s>>>(p, ph);
       SSD_HIP(hipGetLastError());
     }
   }
   return SSD_OK;
 }
 
-template <class PL>
+template <class PL, bool PG>
 int launch_pl(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
   const int mt = (p.M + 15) / 16;
   if (p.deep != 0) {
-    if (mt == 1) return launch_mt<1, true, PL>(p, first, last, persistent, s);
-    if (mt == 2) return launch_mt<2, true, PL>(p, first, last, persistent, s);
-    return launch_mt<3, true, PL>(p, first, last, persistent, s);
+    if (mt == 1) return launch_mt<1, true, PL, PG>(p, first, last, persistent, s);
+    if (mt == 2) return launch_mt<2, true, PL, PG>(p, first, last, persistent, s);
+    return launch_mt<3, true, PL, PG>(p, first, last, persistent, s);
   }
-  if (mt == 1) return launch_mt<1, false, PL>(p, first, last, persistent, s);
-  if (mt == 2) return launch_mt<2, false, PL>(p, first, last, persistent, s);
-  return launch_mt<3, false, PL>(p, first, last, persistent, s);
+  if (mt == 1) return launch_mt<1, false, PL, PG>(p, first, last, persistent, s);
+  if (mt == 2) return launch_mt<2, false, PL, PG>(p, first, last, persistent, s);
+  return launch_mt<3, false, PL, PG>(p, first, last, persistent, s);
 }
 
 bool fused_planes_supported(int mask) {
@@ -2285,11 +2307,15 @@ bool fused_planes_supported(int mask) {
   return false;
 }
 
-int fused_check_residency(int nwg, int planes) {
+int fused_check_residency(int nwg, int planes, int paged) {
   int dev = 0, cus = 0;
   SSD_HIP(hipGetDevice(&dev));
   SSD_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-#define X(m) if (planes == (m)) return check_residency_pl<PlanesOf<(m)>>(nwg, cus);
+  if (paged) {
+    SSD_CHECK_ARG(planes == 0, "a paged trunk takes the default activation planes only");
+    return check_residency_pl<PlanesOf<0>, true>(nwg, cus);
+  }
+#define X(m) if (planes == (m)) return check_residency_pl<PlanesOf<(m)>, false>(nwg, cus);
   SSD_FUSED_PLANE_MASKS
 #undef X
   set_error("fused pass: plane configuration %d is not compiled in", planes);
@@ -2305,8 +2331,12 @@ int launch_fused_wide(const FusedParams& p, const FusedLayer* layers_host, int f
                     (16 / p.G) * p.SL <= 64,
                 "bad attention split");
   SSD_CHECK_ARG(first >= 0 && last <= fused_last_phase(p.L) && first <= last && layers_host, "bad phase range");
-  if ((p.planes & 24) == 24) return launch_wide_pl<Planes<1, 1, 1, 1, 1>>(p, layers_host, first, last, s);
-  return launch_wide_pl<Planes<1, 1, 1, 2, 2>>(p, layers_host, first, last, s);
+  if (p.pages) {
+    SSD_CHECK_ARG((p.planes & 24) != 24, "a paged trunk takes the default planes of the attention unit only");
+    return launch_wide_pl<Planes<1, 1, 1, 2, 2>, true>(p, layers_host, first, last, s);
+  }
+  if ((p.planes & 24) == 24) return launch_wide_pl<Planes<1, 1, 1, 1, 1>, false>(p, layers_host, first, last, s);
+  return launch_wide_pl<Planes<1, 1, 1, 2, 2>, false>(p, layers_host, first, last, s);
 }
 
 // Shapes the wide pass takes: every layer's stream-order layout must cut into sets of 4 feature tiles over whole
@@ -2324,7 +2354,11 @@ int launch_fused(const FusedParams& p, int first, int last, int persistent, hipS
                     (16 / p.G) * p.SL <= 64,
                 "bad attention split");
   SSD_CHECK_ARG(first >= 0 && last <= fused_last_phase(p.L) && first <= last, "bad phase range");
-#define X(m) if (p.planes == (m)) return launch_pl<PlanesOf<(m)>>(p, first, last, persistent, s);
+  if (p.pages) {
+    SSD_CHECK_ARG(p.planes == 0, "a paged trunk takes the default activation planes only");
+    return launch_pl<PlanesOf<0>, true>(p, first, last, persistent, s);
+  }
+#define X(m) if (p.planes == (m)) return launch_pl<PlanesOf<(m)>, false>(p, first, last, persistent, s);
   SSD_FUSED_PLANE_MASKS
 #undef X
   set_error("fused pass: plane configuration %d is not compiled in", p.planes);

@@ -38,10 +38,12 @@ __global__ void fill_const_kernel(T* __restrict__ dst, int64_t n, float v) {
 
 // Synthetic trunk KV of one layer: element (b, pos, kv head h, dim d), pos < len[b], has index
 // (b << 40) + (pos Hkv + h) D + d in tensor `id_k` / `id_v`.  fused != 0: the head-major layouts of the fused pass (keys
-// [B][Hkv][stride][64], values transposed per 32-position block); else [B][stride][Hkv][D].
+// [B][Hkv][stride][64], values transposed per 32-position block), or with pages != null their paged form (block j of
+// sequence b in page pages[b * page_stride + j] of a pool [page][Hkv][..]); else [B][stride][Hkv][D].
 template <typename T>
 __global__ void fill_kv_kernel(T* __restrict__ k, T* __restrict__ v, const int32_t* __restrict__ len, int B, int max_len, int Hkv,
-                               int D, int stride, int fused, uint64_t prefix_k, uint64_t prefix_v, float scale) {
+                               int D, int stride, int fused, const int32_t* __restrict__ pages, int page_stride,
+                               uint64_t prefix_k, uint64_t prefix_v, float scale) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // over [B][max_len][Hkv][D]
   const int64_t per_seq = (int64_t)max_len * Hkv * D;
   if (i >= per_seq * B) return;
@@ -53,9 +55,10 @@ __global__ void fill_kv_kernel(T* __restrict__ k, T* __restrict__ v, const int32
   const uint64_t index = ((uint64_t)b << 40) + (uint64_t)r;
   const float kv = hashed_value(prefix_k, index, scale), vv = hashed_value(prefix_v, index, scale);
   if (fused) {
-    const int64_t head = ((int64_t)b * Hkv + h) * stride * 64;
-    Elem<T>::store(k + head + (int64_t)pos * 64 + d, kv);
-    Elem<T>::store(v + head + (int64_t)(pos >> 5) * 2048 + d * 32 + (pos & 31), vv);
+    const int64_t bb = pages ? ((int64_t)pages[b * page_stride + (pos >> 5)] * Hkv + h) * 2048
+                             : ((int64_t)b * Hkv + h) * stride * 64 + (int64_t)(pos >> 5) * 2048;
+    Elem<T>::store(k + bb + (int64_t)(pos & 31) * 64 + d, kv);
+    Elem<T>::store(v + bb + d * 32 + (pos & 31), vv);
   } else {
     const int64_t at = (((int64_t)b * stride + pos) * Hkv + h) * D + d;
     Elem<T>::store(k + at, kv);
@@ -86,15 +89,15 @@ int launch_fill_const(int dtype, void* dst, int64_t n, float v, hipStream_t s) {
 }
 
 int launch_fill_kv(int dtype, void* k, void* v, const int32_t* len, int B, int max_len, int Hkv, int D, int stride, int fused,
-                   uint64_t seed, uint64_t id_k, uint64_t id_v, hipStream_t s) {
+                   const int32_t* pages, int page_stride, uint64_t seed, uint64_t id_k, uint64_t id_v, hipStream_t s) {
   const int64_t n = (int64_t)B * max_len * Hkv * D;
   if (n <= 0) return SSD_OK;
   const float scale = (float)(1.0 / kIrwinHallSigma);
   const uint64_t pk = tensor_prefix(seed, id_k), pv = tensor_prefix(seed, id_v);
   if (dtype == SSD_BF16)
-    fill_kv_kernel<bf16_t><<<blocks_for(n), 256, 0, s>>>((bf16_t*)k, (bf16_t*)v, len, B, max_len, Hkv, D, stride, fused, pk, pv, scale);
+    fill_kv_kernel<bf16_t><<<blocks_for(n), 256, 0, s>>>((bf16_t*)k, (bf16_t*)v, len, B, max_len, Hkv, D, stride, fused, pages, page_stride, pk, pv, scale);
   else
-    fill_kv_kernel<float><<<blocks_for(n), 256, 0, s>>>((float*)k, (float*)v, len, B, max_len, Hkv, D, stride, fused, pk, pv, scale);
+    fill_kv_kernel<float><<<blocks_for(n), 256, 0, s>>>((float*)k, (float*)v, len, B, max_len, Hkv, D, stride, fused, pages, page_stride, pk, pv, scale);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }

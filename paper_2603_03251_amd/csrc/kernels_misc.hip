@@ -47,12 +47,13 @@ __global__ void setup_branch_rows_kernel(RowDesc* rows, float* cos_sin, const in
 }
 
 // Extend rows: token t of sequence b at position trunk_len+offset+t, causal (sees itself after the append).
+// rows of sequences seq_base .. seq_base + B - 1 (row m of the pass = token m % T of sequence seq_base + m / T)
 __global__ void setup_extend_rows_kernel(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int T,
-                                         int offset, int half_dim, float theta) {
+                                         int offset, int half_dim, float theta, int seq_base) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= B * T * half_dim) return;
   int m = idx / half_dim, i = idx % half_dim;
-  int b = m / T, t = m % T;
+  int b = seq_base + m / T, t = m % T;
   int pos = trunk_len[b] + offset + t;
   if (i == 0) {
     RowDesc r;
@@ -265,9 +266,9 @@ int launch_setup_branch_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk
 }
 
 int launch_setup_extend_rows(RowDesc* rows, float* cos_sin, const int32_t* trunk_len, int B, int T, int offset,
-                             int half_dim, float theta, hipStream_t s) {
+                             int half_dim, float theta, int seq_base, hipStream_t s) {
   setup_extend_rows_kernel<<<grid_for((int64_t)B * T * half_dim), kBlock, 0, s>>>(rows, cos_sin, trunk_len, B, T,
-                                                                                 offset, half_dim, theta);
+                                                                                 offset, half_dim, theta, seq_base);
   SSD_HIP(hipGetLastError());
   return SSD_OK;
 }

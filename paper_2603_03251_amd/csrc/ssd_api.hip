@@ -125,6 +125,15 @@ struct ssd_ctx {
   int32_t* sigma_ids = nullptr;     // [M][F] top-F of the current step's logits (saguaro_c < 1 only)
   int64_t attn_partial_floats = 0;
   // fused pass (see fused.h): 0 = per-operator kernels, 1 = one launch per phase, 2 = one persistent launch
+  // paged trunk (App. B: block tables, pages of rejected tokens rolled back): the trunk of every layer is a pool of
+  // 32-position pages shared by the sequences; a sequence's block j is page page_table[b][j]; page 0 is never handed out
+  int kv_pages = 0;                      // pages of the pool, page 0 included; 0 = contiguous trunk per sequence
+  int page_stride = 0;                   // blocks per sequence the table has room for
+  int32_t* page_table_dev = nullptr;     // [B][page_stride]
+  int32_t* page_table_host = nullptr;    // pinned mirror, the host's truth
+  std::vector<int32_t> free_pages;       // stack of free page numbers
+  std::vector<int> blocks_of;            // blocks a sequence holds pages for
+  std::vector<int> ub_of;                // host upper bound of trunk_len per sequence (trunk_ub = their maximum)
   int fused_mode = 0;
   bool fused_wide = false;     // passes of up to kFusedWideRows rows through the wide kernel
   int fused_cap = 0;           // rows of one pass: kFusedMaxRows or kFusedWideRows
@@ -338,11 +347,66 @@ int ctx_fault(const ssd_ctx* c, const char* who) {
   return SSD_OK;
 }
 
+// Pages for positions 0 .. positions-1 of sequence b (paged contexts; no-op otherwise).  New entries go to the host
+// mirror; *dirty tells the caller to upload the table before the next kernel.
+int pages_ensure(ssd_ctx* c, int b, int positions, bool* dirty) {
+  if (!c->kv_pages) return SSD_OK;
+  const int need = (positions + 31) / 32;
+  if (need > c->page_stride) { set_error("sequence %d: %d positions exceed the page table", b, positions); return SSD_ESTATE; }
+  while (c->blocks_of[b] < need) {
+    if (c->free_pages.empty()) {
+      set_error("out of KV pages (%d in the pool): sequence %d needs block %d; release a sequence or tighten the bounds "
+                "(ssd_ctx_refresh_bounds)", c->kv_pages, b, c->blocks_of[b]);
+      return SSD_ENOMEM;
+    }
+    c->page_table_host[(size_t)b * c->page_stride + c->blocks_of[b]++] = c->free_pages.back();
+    c->free_pages.pop_back();
+    *dirty = true;
+  }
+  return SSD_OK;
+}
+
+// Page rollback: sequence b keeps the pages of its first `positions` positions, the rest go back to the pool.  The
+// caller has synchronised the streams that may still read them.
+void pages_release_beyond(ssd_ctx* c, int b, int positions, bool* dirty) {
+  if (!c->kv_pages) return;
+  const int keep = (positions + 31) / 32;
+  while (c->blocks_of[b] > keep) {
+    int32_t& e = c->page_table_host[(size_t)b * c->page_stride + --c->blocks_of[b]];
+    c->free_pages.push_back(e);
+    e = 0;
+    *dirty = true;
+  }
+}
+
+int pages_upload(ssd_ctx* c, hipStream_t s) {
+  SSD_HIP(hipMemcpyAsync(c->page_table_dev, c->page_table_host, sizeof(int32_t) * (size_t)c->B * c->page_stride,
+                         hipMemcpyHostToDevice, s));
+  return SSD_OK;
+}
+
+// Before a pass that writes trunk positions up to (bound of sequence b) + extra of sequences [b0, b0 + nb)
+int pages_for_pass(ssd_ctx* c, int b0, int nb, int extra, hipStream_t s) {
+  if (!c->kv_pages) return SSD_OK;
+  bool dirty = false;
+  for (int b = b0; b < b0 + nb; ++b) SSD_TRY(pages_ensure(c, b, c->ub_of[b] + extra, &dirty));
+  return dirty ? pages_upload(c, s) : SSD_OK;
+}
+
+void set_bounds(ssd_ctx* c, const int32_t* lens) {
+  c->trunk_ub = 0;
+  for (int b = 0; b < c->B; ++b) {
+    c->ub_of[b] = lens[b];
+    c->trunk_ub = lens[b] > c->trunk_ub ? lens[b] : c->trunk_ub;
+  }
+}
+
 // The same pass through the fused kernel: attention work split for this pass's shape, then one launch per group of
 // whole sequences that fits kFusedMaxRows rows (one launch for the few-row workloads the kernel is built for; a batch
 // with more rows streams the weights once per group).
+// seq_base: the pass's rows belong to sequences seq_base, seq_base + 1, .. (rows, tokens and outputs are indexed from 0)
 int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int max_vis, int branch_depth, float* logits,
-                  int64_t logits_ld, float* hidden, int64_t hidden_ld, hipStream_t s) {
+                  int64_t logits_ld, float* hidden, int64_t hidden_ld, int seq_base, hipStream_t s) {
   FusedParams p = c->fp;
   p.R = rows_per_seq;
   p.is_branch = branch_depth >= 0;
@@ -391,7 +455,9 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
     const int64_t row0 = (int64_t)s0 * rows_per_seq;
     p.B = nb;
     p.M = nb * rows_per_seq;
-    p.layers = c->fused_layers_dev + (size_t)s0 * p.L;
+    p.layers = c->fused_layers_dev + (size_t)(seq_base + s0) * p.L;
+    p.pages = c->kv_pages ? c->page_table_dev + (size_t)(seq_base + s0) * c->page_stride : nullptr;
+    p.page_stride = c->page_stride;
     p.rows = c->rows + row0;
     p.cos_sin = c->cos_sin + row0 * (c->model->dims.head_dim / 2) * 2;
     p.tokens = tokens + row0;
@@ -405,7 +471,7 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
       set_error("fused pass: attention partial buffer too small (%d splits, %d query tiles)", p.NS, p.QT);
       return SSD_ESTATE;
     }
-    if (c->fused_wide) SSD_TRY(launch_fused_wide(p, c->fused_layers_host.data() + (size_t)s0 * p.L, 0, last, s));
+    if (c->fused_wide) SSD_TRY(launch_fused_wide(p, c->fused_layers_host.data() + (size_t)(seq_base + s0) * p.L, 0, last, s));
     else SSD_TRY(launch_fused(p, 0, last, persistent, s));
   }
   if (timed) SSD_HIP(hipEventRecord(c->kernel_events[2 * branch_depth + 1], s));
@@ -422,10 +488,11 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
 // ctx->cos_sin.  Logits (fp32, row stride logits_ld) and final-norm hidden states are optional.
 // max_vis: host bound of the stored trunk positions any row sees; branch_depth: decode step of branch rows, -1 for an extend.
 int forward_rows(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int max_vis, int branch_depth, float* logits,
-                 int64_t logits_ld, float* hidden, int64_t hidden_ld, hipStream_t s) {
+                 int64_t logits_ld, float* hidden, int64_t hidden_ld, int seq_base, hipStream_t s) {
   const ssd_model* m = c->model;
   const Dims& d = m->dims;
-  if (c->fused_mode) return fused_forward(c, M, tokens, rows_per_seq, max_vis, branch_depth, logits, logits_ld, hidden, hidden_ld, s);
+  if (c->fused_mode)
+    return fused_forward(c, M, tokens, rows_per_seq, max_vis, branch_depth, logits, logits_ld, hidden, hidden_ld, seq_base, s);
   const int dt = d.dtype;
   const int64_t R = c->max_rows;     // plane stride of an activation buffer = R * columns
   SSD_TRY(launch_embed(dt, m->embed, tokens, c->h, M, d.d_model, d.vocab, s));
@@ -460,10 +527,14 @@ int forward_rows(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, int
   return SSD_OK;
 }
 
-int extend_rows(ssd_ctx* c, const int32_t* tokens, int T, int offset, float* logits, float* hidden, hipStream_t s) {
+// Extend of sequences [b0, b0 + nb): tokens [nb][T], outputs [nb][T][..]
+int extend_rows(ssd_ctx* c, const int32_t* tokens, int T, int offset, float* logits, float* hidden, int b0, int nb, hipStream_t s) {
   const Dims& d = c->model->dims;
-  SSD_TRY(launch_setup_extend_rows(c->rows, c->cos_sin, c->trunk_len, c->B, T, offset, d.head_dim / 2, d.rope_theta, s));
-  return forward_rows(c, c->B * T, tokens, T, c->trunk_ub + offset, -1, logits, d.vocab, hidden, d.d_model, s);
+  SSD_TRY(pages_for_pass(c, b0, nb, offset + T, s));
+  SSD_TRY(launch_setup_extend_rows(c->rows, c->cos_sin, c->trunk_len, nb, T, offset, d.head_dim / 2, d.rope_theta, b0, s));
+  int ub = 0;
+  for (int b = b0; b < b0 + nb; ++b) ub = c->ub_of[b] > ub ? c->ub_of[b] : ub;
+  return forward_rows(c, nb * T, tokens, T, ub + offset, -1, logits, d.vocab, hidden, d.d_model, b0, s);
 }
 
 // Workspace and constant parameters of the fused pass.
@@ -518,7 +589,7 @@ int fused_setup(ssd_ctx* c) {
   // every workgroup of a persistent launch has to be resident at once
   p.planes = (c->flags >> 8) & 31;
   if (!c->fused_wide && !fused_planes_supported(p.planes)) { set_error("fused pass: plane configuration %d is not compiled in", p.planes); return SSD_EINVAL; }
-  if (c->fused_mode == 2) SSD_TRY(fused_check_residency(p.nwg, p.planes));
+  if (c->fused_mode == 2) SSD_TRY(fused_check_residency(p.nwg, p.planes, c->kv_pages ? 1 : 0));
   {
     void* host_word = nullptr;
     hipError_t e = hipHostMalloc(&host_word, 64, hipHostMallocMapped);
@@ -545,15 +616,17 @@ int fused_setup(ssd_ctx* c) {
   const size_t branch_rows = (size_t)c->rows_per_seq;
   for (int l = 0; l < L; ++l) {
     // masked keys still feed the value MFMA with weight 0: everything there must be finite
-    SSD_HIP(hipMemset(c->trunk_k[l], 0, (size_t)c->B * kvd * c->vt_stride * 2));
-    SSD_HIP(hipMemset(c->trunk_v[l], 0, (size_t)c->B * kvd * c->vt_stride * 2));
+    const size_t trunk_elems = c->kv_pages ? (size_t)c->kv_pages * 32 * kvd : (size_t)c->B * kvd * c->vt_stride;
+    SSD_HIP(hipMemset(c->trunk_k[l], 0, trunk_elems * 2));
+    SSD_HIP(hipMemset(c->trunk_v[l], 0, trunk_elems * 2));
     for (int sq = 0; sq < c->B; ++sq) {
       FusedLayer& F = host[(size_t)sq * L + l];
       F.qkv = m->fused_layers[l].qkv; F.o = m->fused_layers[l].o; F.gu = m->fused_layers[l].gu; F.down = m->fused_layers[l].down;
       F.attn_norm = (const bf16_t*)m->layers[l].attn_norm;
       F.mlp_norm = (const bf16_t*)m->layers[l].mlp_norm;
-      F.trunk_k = (bf16_t*)c->trunk_k[l] + (size_t)sq * kvd * c->vt_stride;
-      F.trunk_vt = (bf16_t*)c->trunk_v[l] + (size_t)sq * kvd * c->vt_stride;
+      // paged: every sequence addresses the one pool through its row of the page table
+      F.trunk_k = (bf16_t*)c->trunk_k[l] + (c->kv_pages ? 0 : (size_t)sq * kvd * c->vt_stride);
+      F.trunk_vt = (bf16_t*)c->trunk_v[l] + (c->kv_pages ? 0 : (size_t)sq * kvd * c->vt_stride);
       F.suffix_k = (bf16_t*)c->suffix_k[l] + (size_t)sq * branch_rows * c->K * kvd;
       F.suffix_v = (bf16_t*)c->suffix_v[l] + (size_t)sq * branch_rows * c->K * kvd;
     }
@@ -688,11 +761,43 @@ static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const
     }
   }
   c->vt_stride = (c->max_trunk + 63) / 64 * 64;
+  c->ub_of.assign(c->B, 0);
+  c->blocks_of.assign(c->B, 0);
+  if (cfg->kv_pages) {
+    // paged trunk (App. B): a pool of 32-position pages per layer instead of max_trunk positions per sequence
+    if (!c->fused_mode || d.head_dim != 64) {
+      set_error("kv_pages: the paged trunk is served by the fused passes only (bf16 model of a supported shape, no SSD_CTX_PER_OPERATOR)");
+      ssd_ctx_destroy(c);
+      return SSD_EINVAL;
+    }
+    if (cfg->kv_pages < 2 || c->max_trunk > 16384) {
+      set_error("kv_pages must be at least 2 (page 0 is the shared all-zero page) and max_trunk at most 16384 in a paged context");
+      ssd_ctx_destroy(c);
+      return SSD_EINVAL;
+    }
+    c->kv_pages = cfg->kv_pages;
+    c->page_stride = c->vt_stride / 32;
+    // pages are handed out from the back of the list: low ids first
+    for (int pg = c->kv_pages - 1; pg >= 1; --pg) c->free_pages.push_back(pg);
+    A((void**)&c->page_table_dev, sizeof(int32_t) * (size_t)c->B * c->page_stride);
+    if (st == SSD_OK) {
+      void* host = nullptr;
+      hipError_t e = hipHostMalloc(&host, sizeof(int32_t) * (size_t)c->B * c->page_stride, hipHostMallocDefault);
+      if (e != hipSuccess) { (void)hipGetLastError(); set_error("hipHostMalloc failed: %s", hipGetErrorString(e)); st = SSD_ENOMEM; }
+      else {
+        c->page_table_host = (int32_t*)host;
+        memset(host, 0, sizeof(int32_t) * (size_t)c->B * c->page_stride);
+        hipError_t e2 = hipMemset(c->page_table_dev, 0, sizeof(int32_t) * (size_t)c->B * c->page_stride);
+        if (e2 != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(e2)); st = SSD_EHIP; }
+      }
+    }
+  }
   for (int l = 0; l < d.n_layers; ++l) {
     // fused contexts keep the trunk head-major, with max_trunk rounded up to 64 positions (layouts in fused.h)
     const size_t trunk_pos = c->fused_mode ? (size_t)c->vt_stride : (size_t)c->max_trunk;
-    A(&c->trunk_k[l], (size_t)c->B * trunk_pos * kvd * es);
-    A(&c->trunk_v[l], (size_t)c->B * trunk_pos * kvd * es);
+    const size_t trunk_elems = c->kv_pages ? (size_t)c->kv_pages * 32 * kvd : (size_t)c->B * trunk_pos * kvd;
+    A(&c->trunk_k[l], trunk_elems * es);
+    A(&c->trunk_v[l], trunk_elems * es);
     A(&c->suffix_k[l], (size_t)c->M * c->K * kvd * es);
     A(&c->suffix_v[l], (size_t)c->M * c->K * kvd * es);
   }
@@ -807,6 +912,7 @@ int ssd_ctx_destroy(ssd_ctx* c) {
   }
   if (c->fused_done) (void)hipEventDestroy(c->fused_done);
   if (c->fused_err) (void)hipHostFree(c->fused_err);
+  if (c->page_table_host) (void)hipHostFree(c->page_table_host);
   for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->kernel_events) (void)hipEventDestroy(e);
   c->arena.release();
@@ -827,17 +933,88 @@ int ssd_ctx_prefill(ssd_ctx* c, const int32_t* d_tokens, int32_t stride, const i
                 max_len, c->max_trunk);
   SSD_TRY(launch_fill_i32(c->trunk_len, 0, c->B, s));
   const int T = c->K + 1;
-  c->trunk_ub = 0;
+  {
+    std::vector<int32_t> zero(c->B, 0);
+    set_bounds(c, zero.data());
+    if (c->kv_pages) {       // the new text starts from an empty trunk: every page goes back first
+      SSD_HIP(hipStreamSynchronize(s));
+      bool dirty = false;
+      for (int b = 0; b < c->B; ++b) pages_release_beyond(c, b, 0, &dirty);
+    }
+  }
   for (int start = 0; start < max_len; start += T) {
     int n = c->B * T;
     gather_chunk_tokens_kernel<<<(n + 255) / 256, 256, 0, s>>>(c->step_tokens, d_tokens, stride, c->B, T, start);
     SSD_HIP(hipGetLastError());
-    SSD_TRY(extend_rows(c, c->step_tokens, T, start, nullptr, nullptr, s));
+    SSD_TRY(extend_rows(c, c->step_tokens, T, start, nullptr, nullptr, 0, c->B, s));
   }
   SSD_HIP(hipMemcpyAsync(c->trunk_len, h_lens, sizeof(int32_t) * c->B, hipMemcpyHostToDevice, s));
   SSD_HIP(hipStreamSynchronize(s));   // h_lens is caller-owned pageable memory
-  c->trunk_ub = max_len;
+  set_bounds(c, h_lens);
+  if (c->kv_pages) {         // the chunks ran to the longest prompt: shorter ones hand the surplus back
+    bool dirty = false;
+    for (int b = 0; b < c->B; ++b) pages_release_beyond(c, b, h_lens[b], &dirty);
+    if (dirty) SSD_TRY(pages_upload(c, s));
+  }
   c->have_cache = false;
+  return SSD_OK;
+}
+
+int ssd_ctx_prefill_sequence(ssd_ctx* c, int32_t b, const int32_t* d_tokens, int32_t len, void* stream) {
+  SSD_CHECK_ARG(c && d_tokens, "ssd_ctx_prefill_sequence: null argument");
+  SSD_CHECK_ARG(b >= 0 && b < c->B, "ssd_ctx_prefill_sequence: sequence %d out of range", b);
+  SSD_CHECK_ARG(len >= 1 && len + 2 * c->K + 2 <= c->max_trunk, "prefill of %d tokens does not leave room for a round (max_trunk %d)",
+                len, c->max_trunk);
+  SSD_TRY(ctx_fault(c, "ssd_ctx_prefill_sequence"));
+  hipStream_t s = (hipStream_t)stream;
+  SSD_HIP(hipStreamSynchronize(s));
+  {
+    bool dirty = false;
+    pages_release_beyond(c, b, 0, &dirty);
+    if (dirty) SSD_TRY(pages_upload(c, s));
+  }
+  SSD_TRY(launch_fill_i32(c->trunk_len + b, 0, 1, s));
+  c->ub_of[b] = 0;
+  const int T = c->K + 1;
+  for (int start = 0; start < len; start += T) {
+    gather_chunk_tokens_kernel<<<1, 256, 0, s>>>(c->step_tokens, d_tokens, len, 1, T, start);
+    SSD_HIP(hipGetLastError());
+    SSD_TRY(extend_rows(c, c->step_tokens, T, start, nullptr, nullptr, b, 1, s));
+  }
+  SSD_TRY(launch_fill_i32(c->trunk_len + b, len, 1, s));
+  c->ub_of[b] = len;
+  if (c->kv_pages) {
+    SSD_HIP(hipStreamSynchronize(s));
+    bool dirty = false;
+    pages_release_beyond(c, b, len, &dirty);
+    if (dirty) SSD_TRY(pages_upload(c, s));
+  }
+  c->trunk_ub = 0;
+  for (int i = 0; i < c->B; ++i) c->trunk_ub = c->ub_of[i] > c->trunk_ub ? c->ub_of[i] : c->trunk_ub;
+  c->have_cache = false;
+  return SSD_OK;
+}
+
+int ssd_ctx_release_sequence(ssd_ctx* c, int32_t b, void* stream) {
+  SSD_CHECK_ARG(c, "ssd_ctx_release_sequence: null context");
+  SSD_CHECK_ARG(b >= 0 && b < c->B, "ssd_ctx_release_sequence: sequence %d out of range", b);
+  hipStream_t s = (hipStream_t)stream;
+  SSD_HIP(hipStreamSynchronize(s));
+  bool dirty = false;
+  pages_release_beyond(c, b, 0, &dirty);
+  if (dirty) SSD_TRY(pages_upload(c, s));
+  SSD_TRY(launch_fill_i32(c->trunk_len + b, 0, 1, s));
+  c->ub_of[b] = 0;
+  c->trunk_ub = 0;
+  for (int i = 0; i < c->B; ++i) c->trunk_ub = c->ub_of[i] > c->trunk_ub ? c->ub_of[i] : c->trunk_ub;
+  c->have_cache = false;
+  return SSD_OK;
+}
+
+int ssd_ctx_kv_pages(const ssd_ctx* c, int32_t* total, int32_t* free_pages) {
+  SSD_CHECK_ARG(c && total && free_pages, "ssd_ctx_kv_pages: null argument");
+  *total = c->kv_pages;
+  *free_pages = (int32_t)c->free_pages.size();
   return SSD_OK;
 }
 
@@ -849,17 +1026,26 @@ int ssd_ctx_load_trunk(ssd_ctx* c, const void* d_k, const void* d_v, int32_t len
   const Dims& d = c->model->dims;
   const size_t es = elem_size(d.dtype);
   const size_t per_layer = (size_t)c->B * len * d.kv_dim() * es;
+  if (c->kv_pages) {
+    bool dirty = false;
+    for (int b = 0; b < c->B; ++b) SSD_TRY(pages_ensure(c, b, len, &dirty));
+    if (dirty) SSD_TRY(pages_upload(c, s));
+  }
   for (int l = 0; l < d.n_layers; ++l) {
     if (c->fused_mode) {
       SSD_TRY(launch_copy_kv_fused((bf16_t*)c->trunk_k[l], (bf16_t*)c->trunk_v[l], (const bf16_t*)((const char*)d_k + l * per_layer),
-                                   (const bf16_t*)((const char*)d_v + l * per_layer), c->B, len, d.n_kv_heads, c->vt_stride, s));
+                                   (const bf16_t*)((const char*)d_v + l * per_layer), c->B, len, d.n_kv_heads, c->vt_stride,
+                                   c->kv_pages ? c->page_table_dev : nullptr, c->page_stride, s));
     } else {
       SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_k[l], (const char*)d_k + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
       SSD_TRY(launch_copy_kv_in(d.dtype, c->trunk_v[l], (const char*)d_v + l * per_layer, c->B, len, c->max_trunk, d.kv_dim(), s));
     }
   }
   SSD_TRY(launch_fill_i32(c->trunk_len, len, c->B, s));
-  c->trunk_ub = len;
+  {
+    std::vector<int32_t> lens(c->B, len);
+    set_bounds(c, lens.data());
+  }
   c->have_cache = false;
   return SSD_OK;
 }
@@ -878,27 +1064,38 @@ int ssd_ctx_fill_synthetic_kv(ssd_ctx* c, const int32_t* h_lens, uint64_t seed, 
   const Dims& d = c->model->dims;
   SSD_HIP(hipMemcpyAsync(c->trunk_len, h_lens, sizeof(int32_t) * c->B, hipMemcpyHostToDevice, s));
   SSD_HIP(hipStreamSynchronize(s));   // h_lens is caller-owned pageable memory
+  if (c->kv_pages) {
+    bool dirty = false;
+    for (int b = 0; b < c->B; ++b) {
+      pages_release_beyond(c, b, h_lens[b], &dirty);
+      SSD_TRY(pages_ensure(c, b, h_lens[b], &dirty));
+    }
+    if (dirty) SSD_TRY(pages_upload(c, s));
+  }
   for (int l = 0; l < d.n_layers; ++l)
     SSD_TRY(launch_fill_kv(d.dtype, c->trunk_k[l], c->trunk_v[l], c->trunk_len, c->B, max_len, d.n_kv_heads, d.head_dim,
-                           c->fused_mode ? c->vt_stride : c->max_trunk, c->fused_mode ? 1 : 0, seed, (1ull << 20) + 2 * (uint64_t)l,
+                           c->fused_mode ? c->vt_stride : c->max_trunk, c->fused_mode ? 1 : 0,
+                           c->kv_pages ? c->page_table_dev : nullptr, c->page_stride, seed, (1ull << 20) + 2 * (uint64_t)l,
                            (1ull << 20) + 2 * (uint64_t)l + 1, s));
-  c->trunk_ub = max_len;
+  set_bounds(c, h_lens);
   c->have_cache = false;
   return SSD_OK;
 }
 
 int ssd_ctx_truncate_trunk(ssd_ctx* c, const int32_t* h_lens, void* stream) {
   SSD_CHECK_ARG(c && h_lens, "ssd_ctx_truncate_trunk: null argument");
-  int ub = 0;
-  for (int b = 0; b < c->B; ++b) {
-    SSD_CHECK_ARG(h_lens[b] >= 1 && h_lens[b] <= c->trunk_ub, "trunk length %d of sequence %d: must be in 1..%d", h_lens[b], b,
-                  c->trunk_ub);
-    ub = h_lens[b] > ub ? h_lens[b] : ub;
-  }
+  for (int b = 0; b < c->B; ++b)
+    SSD_CHECK_ARG(h_lens[b] >= 1 && h_lens[b] <= c->trunk_ub && (!c->kv_pages || h_lens[b] <= c->ub_of[b]),
+                  "trunk length %d of sequence %d: must be in 1..%d", h_lens[b], b, c->kv_pages ? c->ub_of[b] : c->trunk_ub);
   hipStream_t s = (hipStream_t)stream;
   SSD_HIP(hipMemcpyAsync(c->trunk_len, h_lens, sizeof(int32_t) * c->B, hipMemcpyHostToDevice, s));
   SSD_HIP(hipStreamSynchronize(s));   // h_lens is caller-owned pageable memory
-  c->trunk_ub = ub;
+  set_bounds(c, h_lens);
+  if (c->kv_pages) {
+    bool dirty = false;
+    for (int b = 0; b < c->B; ++b) pages_release_beyond(c, b, h_lens[b], &dirty);
+    if (dirty) SSD_TRY(pages_upload(c, s));
+  }
   c->have_cache = false;
   return SSD_OK;
 }
@@ -919,13 +1116,15 @@ int ssd_ctx_extend(ssd_ctx* c, const int32_t* d_tokens, int32_t T, int32_t offse
     set_error("extend would pass max_trunk (%d + %d + %d > %d)", c->trunk_ub, offset, T, c->max_trunk);
     return SSD_ESTATE;
   }
-  return extend_rows(c, d_tokens, T, offset, d_logits, nullptr, (hipStream_t)stream);
+  return extend_rows(c, d_tokens, T, offset, d_logits, nullptr, 0, c->B, (hipStream_t)stream);
 }
 
 int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temperature, uint64_t round_seed, void* stream) {
   SSD_CHECK_ARG(c && d_pending && d_temperature, "ssd_prespeculate: null argument");
   SSD_TRY(ctx_fault(c, "ssd_prespeculate"));
   if (c->trunk_ub < 1) { set_error("ssd_prespeculate: the trunk is empty (prefill or load it first)"); return SSD_ESTATE; }
+  for (int b = 0; b < c->B; ++b)
+    if (c->ub_of[b] < 1) { set_error("ssd_prespeculate: the trunk of sequence %d is empty (prefill its slot first)", b); return SSD_ESTATE; }
   if (c->trunk_ub + 2 * c->K + 2 > c->max_trunk) {
     set_error("ssd_prespeculate: trunk bound %d + 2K+2 exceeds max_trunk %d", c->trunk_ub, c->max_trunk);
     return SSD_ESTATE;
@@ -940,7 +1139,7 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
   };
   SSD_TRY(mark());
   // a0: glue extend of {last verified token, s_1..s_K}
-  SSD_TRY(extend_rows(c, d_pending, K + 1, 0, c->glue_logits, c->glue_hidden, s));
+  SSD_TRY(extend_rows(c, d_pending, K + 1, 0, c->glue_logits, c->glue_hidden, 0, B, s));
   SSD_TRY(mark());
   // a1: fan-out
   SSD_TRY(launch_pending_exclude(c->exclude, d_pending, B, K, s));
@@ -951,7 +1150,7 @@ int ssd_prespeculate(ssd_ctx* c, const int32_t* d_pending, const float* d_temper
     SSD_TRY(launch_setup_branch_rows(c->rows, c->cos_sin, c->trunk_len, B, K, c->fan, i, d.head_dim / 2, d.rope_theta, c->step_tokens,
                                      c->keys, c->tokens, c->forced_keys, c->forced_tokens, s));
     SSD_TRY(forward_rows(c, M, c->step_tokens, RB, c->trunk_ub + K + 1, i, c->logits + (size_t)i * V, (int64_t)K * V,
-                         c->hidden + (size_t)i * d.d_model, (int64_t)K * d.d_model, s));
+                         c->hidden + (size_t)i * d.d_model, (int64_t)K * d.d_model, 0, s));
     if (c->saguaro_c < 1.0f) {
       // sigma_{F,C}: lower the step's own top-F logits before the draw; the cache keeps the lowered logits, the
       // distribution the tokens are drawn from.  The token of depth i is the one whose rejection ends the next round
@@ -984,6 +1183,7 @@ int ssd_ctx_commit(ssd_ctx* c, const int32_t* d_accept_len, void* stream) {
   if (c->trunk_ub < 1) { set_error("ssd_ctx_commit: the trunk is empty"); return SSD_ESTATE; }
   SSD_TRY(launch_commit(c->trunk_len, d_accept_len, c->B, c->K, (hipStream_t)stream));
   c->trunk_ub += c->K + 1;
+  for (int b = 0; b < c->B; ++b) c->ub_of[b] += c->K + 1;
   return SSD_OK;
 }
 
@@ -999,9 +1199,13 @@ int ssd_ctx_refresh_bounds(ssd_ctx* c, void* stream) {
   std::vector<int32_t> lens(c->B);
   SSD_HIP(hipMemcpyAsync(lens.data(), c->trunk_len, sizeof(int32_t) * c->B, hipMemcpyDeviceToHost, (hipStream_t)stream));
   SSD_HIP(hipStreamSynchronize((hipStream_t)stream));
-  int ub = 0;
-  for (int v : lens) ub = v > ub ? v : ub;
-  c->trunk_ub = ub;
+  set_bounds(c, lens.data());
+  if (c->kv_pages) {
+    // page rollback: the pages behind a sequence's verified text (rejected tokens' positions, old glue) return to the pool
+    bool dirty = false;
+    for (int b = 0; b < c->B; ++b) pages_release_beyond(c, b, lens[b], &dirty);
+    if (dirty) SSD_TRY(pages_upload(c, (hipStream_t)stream));
+  }
   return ctx_fault(c, "ssd_ctx_refresh_bounds");
 }
 
