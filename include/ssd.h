@@ -153,6 +153,12 @@ int ssd_model_create(const ssd_model_config* cfg, const ssd_model_weights* w, vo
  * 4 w_gate, 5 w_up, 6 w_down} for layer l.  Runs on `stream` and SYNCHRONISES it before returning. */
 int ssd_model_create_random(const ssd_model_config* cfg, uint64_t seed, void* stream, ssd_model** out);
 int ssd_model_destroy(ssd_model* m);
+/* A bf16 model whose shape the fused passes take holds every linear layer twice: in the order the fused passes stream
+ * it, and in the tile order of the per-operator kernels (contexts with SSD_CTX_PER_OPERATOR, or round shapes the fused
+ * passes do not take).  A caller that only creates fused contexts gives the second copy back (2.47 GB at the 1B shape):
+ * afterwards a context that would need it fails with ESTATE.  ESTATE also while such a context is alive, and for models
+ * the fused passes do not take (they have no other copy).  Synchronises the device.  Idempotent. */
+int ssd_model_release_operator_weights(ssd_model* m);
 
 /* The context keeps a pointer to `model`; destroy the context first. */
 int ssd_ctx_create(const ssd_model* model, const ssd_round_config* cfg, ssd_ctx** out);

@@ -59,6 +59,7 @@ EXPORTS = {
                                    C.POINTER(C.c_void_p)]),
     "ssd_model_create_random": (C.c_int, [C.POINTER(ssd_model_config), C.c_uint64, C.c_void_p, C.POINTER(C.c_void_p)]),
     "ssd_model_destroy": (C.c_int, [C.c_void_p]),
+    "ssd_model_release_operator_weights": (C.c_int, [C.c_void_p]),
     "ssd_ctx_create": (C.c_int, [C.c_void_p, C.POINTER(ssd_round_config), C.POINTER(C.c_void_p)]),
     "ssd_ctx_destroy": (C.c_int, [C.c_void_p]),
     "ssd_ctx_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p]),
@@ -207,6 +208,10 @@ def ssd_model_create_random(shape, seed: int, stream=None) -> int:
 
 def ssd_model_destroy(model: int) -> None:
     _check(lib.ssd_model_destroy(model))
+
+
+def ssd_model_release_operator_weights(model: int) -> None:
+    _check(lib.ssd_model_release_operator_weights(model))
 
 
 def ssd_ctx_create(model: int, batch: int, K: int, F: int, max_trunk: int, flags: int = 0, kv_pages: int = 0) -> int:

@@ -36,6 +36,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 // pointers into global memory: loads and stores through these are global_*, never flat_* instructions
@@ -1636,6 +1637,10 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_kernel(FusedParams p, 
 // buffered, one workgroup barrier per stage.  Per k-tile a workgroup pulls 16 KiB of weights and 6 KiB of activations
 // for 96 MFMAs (the split-K kernel above: 40 KiB), and nothing has to be reduced across wavefronts: the epilogue runs
 // from the accumulators.  Weights ride a ring of 8 register chunks that is refilled one stage ahead.
+// The MFMAs are 32x32x16: a wavefront that has its SIMD to itself issues one 16x16x32 per 28 clocks (measured: 1.44 of
+// 2.5 PFLOP/s over the chip) but 32x32x16, twice the work per instruction, back to back (2.23).  Both operands stay in
+// their 16x16x32 tile order in memory and LDS: a 32x32x16 operand is the k-half h of two neighbouring tiles, and lane l
+// takes its 16 bytes from lane (l & 15) + 16 (l >> 5) + 32 h of tile (l >> 4) & 1, a fixed offset per lane.
 constexpr int kWideStage = 8;   // k-tiles per LDS stage of the activation operand
 
 template <int EPI>
@@ -1665,11 +1670,18 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
   }
   stamp(p, e.ph, 1);
 
-  f32x4 acc[4][MTG];
+  constexpr int MT32 = MTG / 2;                      // 32-row tiles of a row group
+  static_assert(MTG % 2 == 0, "row tiles pair up into 32-row MFMA operands");
+  const int lsrc = ((lane >> 4) & 1) * 64 + (lane & 15) + ((lane >> 5) << 4);   // operand vector of this lane (k-half 0)
+  auto zero_acc = [](f32x16& a) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
+    for (int i = 0; i < 16; ++i) a[i] = 0.f;
+  };
+  f32x16 acc[2][MT32];                               // [32 features: tiles 0-1 / 2-3 of the unit][32 rows]
 #pragma unroll
-    for (int t = 0; t < MTG; ++t) acc[j][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int f = 0; f < 2; ++f)
+#pragma unroll
+    for (int t = 0; t < MT32; ++t) zero_acc(acc[f][t]);
 
   auto pair_of = [&](int n, int& set, int& rg) {
     const int t = wx + (n < n_my ? n : n_my - 1) * per_xcd;
@@ -1693,6 +1705,12 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
     const int unit = min(set * 4 + wave, g.n_units - 1);
     cu.a = g.w + ((int64_t)unit * NKT + cu.s * KC) * 4 * 512;
     cu.b = bsrc + ((int64_t)(cu.s * KC) * MTOT + rg * MTG) * 512;
+#ifdef WIDE_EXP_SAME_A
+    cu.a = g.w + ((int64_t)unit * NKT) * 4 * 512;
+#endif
+#ifdef WIDE_EXP_SAME_B
+    cu.b = bsrc + ((int64_t)(rg * MTG)) * 512;
+#endif
   };
   auto next_stage = [&](Cursor& cu) {
     if (++cu.s == NST) { cu.s = 0; ++cu.n; }
@@ -1708,18 +1726,24 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
 #pragma unroll
     for (int i = 0; i < BL; ++i) *(bf16x8*)&lds[buf * STAGE + (int)threadIdx.x + kWideThreads * i] = breg[i];
   };
-  auto load_a = [&](const Cursor& cu, int j) {
-    const gbf16x8* ap = (const gbf16x8*)(cu.a + (int64_t)j * 4 * 512) + lane;
+  auto load_a = [&](const Cursor& cu, int j) {       // ring[j][2 f + h]: features 32 f .. 32 f + 31 of the unit, k-half h
+    const gbf16x8* ap = (const gbf16x8*)(cu.a + (int64_t)j * 4 * 512) + lsrc;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) ring[j][jj] = ap[jj * 64];
+    for (int jj = 0; jj < 4; ++jj) ring[j][jj] = ap[(jj >> 1) * 128 + (jj & 1) * 32];
   };
 
   // ---- prologue: stage 0 of the first pair
   Cursor cu{0, 0, nullptr, nullptr};
   place(cu);
   load_b(cu);
+  // the ring is requested in the order the loop refills it: the wait for chunk j inside the loop is computed from BOTH
+  // ways into the loop, and a prologue that had requested chunk 0 last would make every stage wait for the whole ring
 #pragma unroll
-  for (int j = 0; j < KC; ++j) load_a(cu, j);
+  for (int j = 0; j < KC; ++j) {
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(cu, j);
+  }
+  __builtin_amdgcn_sched_barrier(0);
   store_b(0);
   wg_barrier();
   stamp(p, e.ph, 3);
@@ -1732,22 +1756,28 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
       next_stage(cu);                                // the stage after this one (clamped past the end: loaded, never used)
       load_b(cu);
       __builtin_amdgcn_sched_barrier(0);
-      const bf16x8* bs = (const bf16x8*)&lds[buf * STAGE];
+      const bf16x8* bs = (const bf16x8*)&lds[buf * STAGE] + lsrc;
       // the activation tiles of k-tile j + 1 leave LDS while the MFMAs of k-tile j run: one wavefront per SIMD has no
-      // neighbour to hide an LDS round trip behind
+      // neighbour to hide an LDS round trip behind.  bt[..][2 t + h]: rows 32 t .. 32 t + 31 of the group, k-half h
       bf16x8 bt[2][MTG];
 #pragma unroll
-      for (int t = 0; t < MTG; ++t) bt[0][t] = bs[t * 64 + lane];
+      for (int t = 0; t < MTG; ++t) bt[0][t] = bs[(t >> 1) * 128 + (t & 1) * 32];
 #pragma unroll
       for (int j = 0; j < KC; ++j) {
         if (j + 1 < KC) {
 #pragma unroll
-          for (int t = 0; t < MTG; ++t) bt[(j + 1) & 1][t] = bs[((j + 1) * MTG + t) * 64 + lane];
+          for (int t = 0; t < MTG; ++t) bt[(j + 1) & 1][t] = bs[((j + 1) * MTG + (t >> 1) * 2) * 64 + (t & 1) * 32];
         }
+        // (pinned in front of the MFMAs: the scheduler otherwise issues these reads behind them, into the registers the
+        // MFMAs have just released, and every k-tile starts with an LDS round trip)
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-          for (int t = 0; t < MTG; ++t) acc[jj][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[j][jj], bt[j & 1][t], acc[jj][t], 0, 0, 0);
+          for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int t = 0; t < MT32; ++t)
+              acc[f][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[j][2 * f + h], bt[j & 1][2 * t + h], acc[f][t], 0, 0, 0);
         load_a(cu, j);
         // the refill stays here, a whole stage ahead of its use: left alone, the instruction scheduler sinks it to just
         // before that use to save registers, and every k-tile then waits a full memory latency
@@ -1758,42 +1788,46 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
       buf ^= 1;
     }
     if (n == 0) stamp(p, e.ph, 4);
-    // ---- epilogue straight from the accumulators: this wavefront's unit (4 feature tiles) x the row group
+    // ---- epilogue straight from the accumulators: this wavefront's unit (4 feature tiles) x the row group.  Registers
+    // 4 q .. 4 q + 3 of a 32x32 accumulator: features 8 q + 4 (lane >> 5) .. + 3 of the 32, row lane & 31
     const int unit = set * 4 + wave;
-    const int f4 = (lane >> 4) * 4;
+    const int f4 = (lane >> 5) * 4;
     if (unit < g.n_units) {
 #pragma unroll
-      for (int t = 0; t < MTG; ++t) {
-        const int m = (rg * MTG + t) * 16 + (lane & 15);
+      for (int t = 0; t < MT32; ++t) {
+        const int m = (rg * MTG + 2 * t) * 16 + (lane & 31);
         if (m < p.M) {
           const float rs = r_s[m];
           if constexpr (EPI == FE_SWIGLU) {
             // feature tiles 0, 1 of the unit are gate, 2, 3 the matching up tiles
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int q = 0; q < 4; ++q) {
               bf16_t hi[4];
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
-                const float gg = acc[j][t][i] * rs, uu = acc[j + 2][t][i] * rs;
+                const float gg = acc[0][t][4 * q + i] * rs, uu = acc[1][t][4 * q + i] * rs;
                 hi[i] = to_bf16(gg / (1.0f + __expf(-gg)) * uu);
               }
-              const int k = unit * 32 + j * 16 + f4;      // input index of the down-projection
+              const int k = unit * 32 + 8 * q + f4;       // input index of the down-projection
               st_u64_uncounted(e.act_out + b_off<MTOT>(k, m), pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
             }
           } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const int tile = unit * 4 + j;
-              if (tile < g.NT) st_f32x4_uncounted(e.out + (int64_t)m * e.ld + tile * 16 + f4, acc[j][t] * rs);
-            }
+            for (int f = 0; f < 2; ++f)
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const int n0 = unit * 64 + f * 32 + 8 * q + f4;
+                const f32x4 v = (f32x4){acc[f][t][4 * q], acc[f][t][4 * q + 1], acc[f][t][4 * q + 2], acc[f][t][4 * q + 3]};
+                if ((n0 >> 4) < g.NT) st_f32x4_uncounted(e.out + (int64_t)m * e.ld + n0, v * rs);
+              }
           }
         }
       }
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int f = 0; f < 2; ++f)
 #pragma unroll
-      for (int t = 0; t < MTG; ++t) acc[j][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int t = 0; t < MT32; ++t) zero_acc(acc[f][t]);
     if (n == 0) stamp(p, e.ph, 5);
   }
   stamp(p, e.ph, 2);

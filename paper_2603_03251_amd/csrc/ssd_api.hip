@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <new>
 #include <utility>
@@ -49,6 +50,14 @@ struct Arena {
     for (void* p : ptrs) (void)hipFree(p);
     ptrs.clear();
   }
+  void release_one(void* p) {
+    for (size_t i = 0; i < ptrs.size(); ++i)
+      if (ptrs[i] == p) {
+        (void)hipFree(p);
+        ptrs.erase(ptrs.begin() + (long)i);
+        return;
+      }
+  }
 };
 
 __global__ void gather_chunk_tokens_kernel(int32_t* out, const int32_t* tokens, int stride, int B, int T, int start) {
@@ -83,6 +92,9 @@ struct ssd_model {
   };
   std::vector<FusedW> fused_layers;
   FusedGemm fused_lm{};
+  // the per-operator kernels' copies of the linear layers (tile order) can be given up: ssd_model_release_operator_weights
+  bool operator_weights = true;
+  mutable std::atomic<int> operator_contexts{0};   // live contexts that run the per-operator kernels
 };
 
 struct ssd_ctx {
@@ -696,6 +708,27 @@ int ssd_model_create(const ssd_model_config* cfg, const ssd_model_weights* w, vo
   return SSD_OK;
 }
 
+int ssd_model_release_operator_weights(ssd_model* m) {
+  SSD_CHECK_ARG(m, "ssd_model_release_operator_weights: null model");
+  if (!m->operator_weights) return SSD_OK;
+  if (!m->fused_ok) { set_error("this model's shape is served by the per-operator kernels only: their weights stay"); return SSD_ESTATE; }
+  if (m->operator_contexts.load() > 0) {
+    set_error("%d context(s) of this model still run the per-operator kernels: destroy them first", m->operator_contexts.load());
+    return SSD_ESTATE;
+  }
+  SSD_HIP(hipDeviceSynchronize());   // nothing enqueued may still read them
+  for (ssd_model::Layer& L : m->layers) {
+    for (void** w : {&L.wqkv, &L.wo, &L.w_gate, &L.w_up, &L.w_down}) {
+      if (*w) m->arena.release_one(*w);
+      *w = nullptr;
+    }
+  }
+  if (m->lm_head && m->lm_head != m->embed) m->arena.release_one(m->lm_head);
+  m->lm_head = nullptr;
+  m->operator_weights = false;
+  return SSD_OK;
+}
+
 int ssd_model_destroy(ssd_model* m) {
   if (!m) return SSD_OK;
   m->arena.release();
@@ -759,6 +792,16 @@ static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const
     } else if (narrow_ok) {
       c->fused_mode = (cfg->flags & SSD_CTX_FUSED_PHASES) ? 1 : 2;
     }
+  }
+  if (!c->fused_mode) {
+    if (!model->operator_weights) {
+      set_error("this context would run the per-operator kernels (flags, or a shape the fused passes do not take), whose "
+                "weights were released (ssd_model_release_operator_weights)");
+      c->arena.release();
+      delete c;
+      return SSD_ESTATE;
+    }
+    model->operator_contexts.fetch_add(1);
   }
   c->vt_stride = (c->max_trunk + 63) / 64 * 64;
   c->ub_of.assign(c->B, 0);
@@ -910,6 +953,7 @@ int ssd_ctx_destroy(ssd_ctx* c) {
       g_fused_last_ctx = nullptr;
     }
   }
+  if (!c->fused_mode && c->model) c->model->operator_contexts.fetch_sub(1);
   if (c->fused_done) (void)hipEventDestroy(c->fused_done);
   if (c->fused_err) (void)hipHostFree(c->fused_err);
   if (c->page_table_host) (void)hipHostFree(c->page_table_host);

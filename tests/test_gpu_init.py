@@ -76,3 +76,48 @@ def test_fill_synthetic_kv_argument_checks(B):
     finally:
         B.ssd_ctx_destroy(ctx)
         B.ssd_model_destroy(model)
+
+
+def test_model_gives_up_the_per_operator_weight_copies(B):
+    """A model that only serves fused contexts frees the tile-order copies of its linear layers: the fused round is
+    unchanged bit for bit, a context that needs the per-operator kernels is refused, and so is the release while such a
+    context lives or for a shape the fused passes do not take."""
+    shape = I.ModelShape(n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ffn=1024, vocab=4112,
+                         dtype="bf16", rope_theta=500000.0, tie_embeddings=True)
+    nb, K, F = 2, 3, 2
+    model = B.ssd_model_create_random(shape, 5)
+    pending = torch.from_numpy(I.make_pending(shape, nb, K, 5)).cuda()
+    temps = torch.zeros(nb, dtype=torch.float32, device="cuda")
+
+    def round_of(ctx):
+        B.ssd_ctx_fill_synthetic_kv(ctx, [40, 33], 6)
+        B.ssd_prespeculate(ctx, pending, temps, 1)
+        return {k: v.cpu() for k, v in B.read_cache(ctx).items()}
+
+    try:
+        free0 = torch.cuda.mem_get_info()[0]
+        per_op = B.ssd_ctx_create(model, nb, K, F, 64, B.SSD_CTX_PER_OPERATOR)
+        with pytest.raises(B.SsdError):
+            B.ssd_model_release_operator_weights(model)        # a per-operator context is alive
+        B.ssd_ctx_destroy(per_op)
+        fused = B.ssd_ctx_create(model, nb, K, F, 64)
+        before = round_of(fused)
+        B.ssd_model_release_operator_weights(model)
+        B.ssd_model_release_operator_weights(model)            # idempotent
+        assert torch.cuda.mem_get_info()[0] > free0
+        after = round_of(fused)
+        for key in before:
+            assert torch.equal(before[key], after[key]), key
+        B.ssd_ctx_destroy(fused)
+        with pytest.raises(B.SsdError):
+            B.ssd_ctx_create(model, nb, K, F, 64, B.SSD_CTX_PER_OPERATOR)
+    finally:
+        B.ssd_model_destroy(model)
+    d128 = I.ModelShape(n_layers=1, d_model=512, n_q_heads=4, n_kv_heads=1, head_dim=128, d_ffn=512, vocab=4112,
+                        dtype="bf16", rope_theta=500000.0, tie_embeddings=False)
+    m2 = B.ssd_model_create_random(d128, 5)
+    try:
+        with pytest.raises(B.SsdError):
+            B.ssd_model_release_operator_weights(m2)           # its only copy
+    finally:
+        B.ssd_model_destroy(m2)
