@@ -1705,12 +1705,6 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
     const int unit = min(set * 4 + wave, g.n_units - 1);
     cu.a = g.w + ((int64_t)unit * NKT + cu.s * KC) * 4 * 512;
     cu.b = bsrc + ((int64_t)(cu.s * KC) * MTOT + rg * MTG) * 512;
-#ifdef WIDE_EXP_SAME_A
-    cu.a = g.w + ((int64_t)unit * NKT) * 4 * 512;
-#endif
-#ifdef WIDE_EXP_SAME_B
-    cu.b = bsrc + ((int64_t)(rg * MTG)) * 512;
-#endif
   };
   auto next_stage = [&](Cursor& cu) {
     if (++cu.s == NST) { cu.s = 0; ++cu.n; }
