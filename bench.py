@@ -80,7 +80,7 @@ def print_phase_clocks(B, ctx, one_round, shape):
     us = (t - t[0, 0].min()) / 100.0
     entry, after, end = us[:, 0], us[:, 1], us[:, 2]
     L = shape.n_layers
-    names = ["qkv", "attention", "merge (unused: 1 key split)", "o-proj", "gate/up", "down"]
+    names = ["qkv", "attention", "merge of key splits", "o-proj", "gate/up", "down"]
     done = end.max(axis=1)
     w = sys.stderr.write
     w("phase clocks of one fused decode kernel (us; mean over layers; per workgroup: wait = barrier wait, body = work)\n")
@@ -93,7 +93,7 @@ def print_phase_clocks(B, ctx, one_round, shape):
         wait = np.mean([(after[p_] - entry[p_]).mean() for p_ in ph])
         body_mean = np.mean([(end[p_] - after[p_]).mean() for p_ in ph])
         body_max = np.mean([(end[p_] - after[p_]).max() for p_ in ph])
-        w(f"  {names[s_]:10s} wait {wait:6.2f}  body mean {body_mean:6.2f}  body max {body_max:6.2f}\n")
+        w(f"  {names[s_]:19s} wait {wait:6.2f}  body mean {body_mean:6.2f}  body max {body_max:6.2f}\n")
 
 
 def algorithmic_bytes_target_forward(shape, prefix, T):
