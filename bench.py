@@ -77,12 +77,35 @@ def print_phase_clocks(B, ctx, one_round, shape):
     one_round(3000)
     t = B.ssd_ctx_read_phase_clocks(ctx).astype(np.int64)
     B.ssd_ctx_enable_phase_clocks(ctx, False)
+    L = shape.n_layers
+    w = sys.stderr.write
+    if B.ssd_ctx_views(ctx).pass_rows > 48:
+        # wide passes: every phase is a launch of its own; slots 0 entry, 3 operands of the first stage requested,
+        # 4 last MFMA of the first pair, 2 end (the attention kernel records entry and end only)
+        w("phase clocks of one wide decode step (us after the phase's first workgroup entered; mean over layers of the mean / "
+          "slowest workgroup)\n")
+        names = {0: "qkv", 1: "attention", 2: "merge of key splits", 3: "o-proj", 4: "gate/up", 5: "down"}
+        for sub, name in names.items():
+            rows = []
+            for l in range(L):
+                x = t[1 + 6 * l + sub] / 100.0
+                busy = x[2] > 0
+                if not busy.any():
+                    continue
+                t0 = x[0][x[0] > 0].min()
+                rows.append([(x[s_][busy] - t0).mean() if (x[s_][busy] > 0).all() else np.nan for s_ in (3, 4, 2)]
+                            + [(x[2][busy] - t0).max(), busy.sum()])
+            if rows:
+                a_ = np.array(rows, dtype=np.float64)
+                r_ = [a_[:, i][~np.isnan(a_[:, i])].mean() if (~np.isnan(a_[:, i])).any() else None for i in range(5)]
+                f_ = lambda v: "    -" if v is None else f"{v:5.1f}"
+                w(f"  {name:19s} workgroups {int(r_[4]):3d}  first operands requested {f_(r_[0])}  MFMAs done {f_(r_[1])}  "
+                  f"end {f_(r_[2])}  slowest {f_(r_[3])}\n")
+        return
     us = (t - t[0, 0].min()) / 100.0
     entry, after, end = us[:, 0], us[:, 1], us[:, 2]
-    L = shape.n_layers
     names = ["qkv", "attention", "merge of key splits", "o-proj", "gate/up", "down"]
     done = end.max(axis=1)
-    w = sys.stderr.write
     w("phase clocks of one fused decode kernel (us; mean over layers; per workgroup: wait = barrier wait, body = work)\n")
     w(f"kernel span {end[-1].max() - entry[0].min():.1f}; embedding {done[0] - entry[0].min():.1f}; "
       f"per layer {(done[6 * L] - done[0]) / L:.2f}; LM head {done[-1] - done[6 * L]:.1f}\n")
@@ -263,6 +286,8 @@ def main():
     ap.add_argument("--one-plane", type=lambda x: int(x, 0), default=None, metavar="MASK",
                     help="activation tensors the fused pass carries as ONE bf16 plane instead of head + remainder: bits "
                          "1 xn, 2 att, 4 act, 8 q, 16 p (31 = all; default: the library's default configuration)")
+    ap.add_argument("--paged", action="store_true",
+                    help="keep the trunk KV in 32-position pages behind a block table (App. B) instead of one run per sequence")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy: the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
@@ -304,7 +329,8 @@ def main():
         fan = B.ssd_geometric_fanout((K + 1) * F, K, a_rate, r_exp)
         ctx = B.ssd_ctx_create_fanout(model, nb, K, fan, P + 2 * K + 2, ctx_flags)
     else:
-        ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2, ctx_flags)
+        kv_pages = 1 + nb * ((P + 2 * K + 2 + 31) // 32 + 1) if args.paged else 0
+        ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2, ctx_flags, kv_pages)
     k, v = I.make_prefix_kv(shape, nb, P, wl.seed)
     to_bf16 = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
     B.ssd_ctx_load_trunk(ctx, to_bf16(k), to_bf16(v), P)
@@ -351,7 +377,7 @@ def main():
         one_round(2000 + i)
         try:
             seg.append(B.ssd_ctx_read_timing(ctx, K, with_kernels=fused))
-        except B.SsdError:                                # per-operator kernels (SSD_FUSED=off): step times only
+        except B.SsdError:                                # per-operator kernels: step times only
             fused = False
             seg.append(B.ssd_ctx_read_timing(ctx, K))
     torch.cuda.synchronize()
@@ -395,7 +421,8 @@ def main():
                                f"({r.rows} branch rows), lookahead {K}, {'greedy' if r.temperature == 0 else 'temperature %g' % r.temperature}"
                                f"; verify on a second stream; lookup"
                                + (f"; prefix lengths {min(prefix_lens)}..{max(prefix_lens)}, mean {sum(prefix_lens) // nb}" if prefix_lens else "")
-                               + (f"; geometric fan-out {fan}" if fan else ""),
+                               + (f"; geometric fan-out {fan}" if fan else "")
+                               + ("; trunk KV in 32-position pages" if args.paged else ""),
                    "branch_rows": r.rows, "tokens_per_round": tokens_per_round},
         "segments_ms": {"glue_extend": float(seg[:, 0].mean()), "fan_out": float(seg[:, 1].mean()),
                         "branch_decode_step": step_ms, "decode_steps_total": float(seg[:, 2:K + 2].sum(axis=1).mean())},
@@ -403,7 +430,10 @@ def main():
         # the draft stream's own time per round (HIP events: glue extend + fan-out + K steps), over the segment-timing rounds
         "round_ms_percentiles": dict(zip(("p10", "p50", "p90"),
                                          (float(x) for x in np.percentile(seg[:, :K + 2].sum(axis=1), [10, 50, 90])))),
-        "roofline": {"kernel": (f"fused_kernel: one batched branch-decode step ({r.rows} rows) in one persistent launch" if fused
+        "roofline": {"kernel": ((f"fused_kernel: one batched branch-decode step ({r.rows} rows) in one persistent launch"
+                                 if B.ssd_ctx_views(ctx).pass_rows <= 48 else
+                                 f"wide pass: one batched branch-decode step ({r.rows} rows), one launch per phase "
+                                 f"(wide_gemm_kernel, wide_gemm_lds_kernel, wide_kernel)") if fused
                                 else f"one batched branch-decode step ({r.rows} rows), one kernel per operator"),
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes() if headline and fused else None,
