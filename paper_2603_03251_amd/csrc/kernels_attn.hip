@@ -175,7 +175,9 @@ __global__ __launch_bounds__(256) void attention_split_kernel(const float* __res
   for (int g = 0; g < G; ++g) sc[g] = 0.f;
   if (have) {
     const T* kp = j < r.vis ? tk + (int64_t)j * kv_stride : sk + (int64_t)(j - r.vis) * kv_stride;
-#pragma unroll 4
+    // (fully unrolled: the key row's loads all go out before the first product; in groups of 4 a row of 128 bf16
+    // cost four memory round trips)
+#pragma unroll
     for (int d0 = 0; d0 < D; d0 += Vec16<T>::N) {
       float kk[Vec16<T>::N];
       Vec16<T>::load(kp + d0, kk);
@@ -215,18 +217,29 @@ __global__ __launch_bounds__(256) void attention_split_kernel(const float* __res
     for (int e = 0; e < NE; ++e) acc[g][e] = 0.f;
   const int jq0 = wave * (kSplitKeys / 4);
   const int jq1 = min(jq0 + kSplitKeys / 4, j_end - j_begin);
-  for (int jj = jq0; jj < jq1; ++jj) {
-    const int jk = j_begin + jj;
-    const T* vp = (jk < r.vis ? tv + (int64_t)jk * kv_stride : sv + (int64_t)(jk - r.vis) * kv_stride) + lane * NE;
-    float vv[NE];
-    LoadElems<T, NE>::load(vp, vv);
+  // value rows in batches of kPvBatch whose loads go out together (one row per iteration, used at once, made the loop
+  // a chain of memory latencies: 64 of them per wavefront); rows past the quarter's end re-read its last row
+  constexpr int kPvBatch = 8;
+  for (int jj0 = jq0; jj0 < jq1; jj0 += kPvBatch) {
+    float vv[kPvBatch][NE];
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-      if (g < group) {
-        const float pe = p_s[g][jj];
+    for (int u = 0; u < kPvBatch; ++u) {
+      const int jk = j_begin + min(jj0 + u, jq1 - 1);
+      const T* vp = (jk < r.vis ? tv + (int64_t)jk * kv_stride : sv + (int64_t)(jk - r.vis) * kv_stride) + lane * NE;
+      LoadElems<T, NE>::load(vp, vv[u]);
+    }
 #pragma unroll
-        for (int e = 0; e < NE; ++e) acc[g][e] = fmaf(pe, vv[e], acc[g][e]);
+    for (int u = 0; u < kPvBatch; ++u) {
+      if (jj0 + u < jq1) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+          if (g < group) {
+            const float pe = p_s[g][jj0 + u];
+#pragma unroll
+            for (int e = 0; e < NE; ++e) acc[g][e] = fmaf(pe, vv[u][e], acc[g][e]);
+          }
       }
+    }
   }
 #pragma unroll
   for (int g = 0; g < G; ++g)
@@ -252,8 +265,10 @@ __global__ __launch_bounds__(D) void attention_merge_kernel(const float* __restr
   const int d = threadIdx.x;
   const float* pp = partial + pair * n_splits * (D + 2);
   float m_max = -INFINITY;
+#pragma unroll 8
   for (int s = 0; s < n_splits; ++s) m_max = fmaxf(m_max, pp[s * (D + 2)]);
   float l = 0.f, o = 0.f;
+#pragma unroll 8
   for (int s = 0; s < n_splits; ++s) {
     const float ms = pp[s * (D + 2)];
     const float w = ms == -INFINITY ? 0.f : expf(ms - m_max);

@@ -71,13 +71,17 @@ __global__ __launch_bounds__(kWaves * 64) void gemm_bf16_kernel(const bf16_t* __
     xrow[t] = x + (int64_t)m * Kd + (int64_t)kt0 * 32 + (lane >> 4) * 8;
   }
 
-  for (int kt = 0; kt < kt_per_wave; kt += U) {
-    bf16x8 wr[U], wr2[U];
+  // Two register sets of U tiles per stream: the next group's weight loads go out before the current group is
+  // multiplied, so a wavefront always has a group in flight (with one set the wavefront idled for a memory round trip per
+  // group, and the layers with few feature tiles per compute unit had nobody else to fill it).
+  auto load_group = [&](bf16x8* wr, bf16x8* wr2, int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       wr[u] = __builtin_nontemporal_load(wp + (int64_t)(kt + u) * 64);
       if (EPI == EPI_SWIGLU) wr2[u] = __builtin_nontemporal_load(wp2 + (int64_t)(kt + u) * 64);
     }
+  };
+  auto mfma_group = [&](const bf16x8* wr, const bf16x8* wr2, int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -92,7 +96,18 @@ __global__ __launch_bounds__(kWaves * 64) void gemm_bf16_kernel(const bf16_t* __
         }
       }
     }
+  };
+  bf16x8 wa[U], wa2[U], wb[U], wb2[U];
+  const int n_groups = kt_per_wave / U;            // kt_per_wave is a multiple of U (host check)
+  if (n_groups > 0) load_group(wa, wa2, 0);
+  int g = 0;
+  for (; g + 2 <= n_groups; g += 2) {
+    load_group(wb, wb2, (g + 1) * U);
+    mfma_group(wa, wa2, g * U);
+    if (g + 2 < n_groups) load_group(wa, wa2, (g + 2) * U);
+    mfma_group(wb, wb2, (g + 1) * U);
   }
+  if (g < n_groups) mfma_group(wa, wa2, g * U);    // odd number of groups: the last one is already in wa
 
 #pragma unroll
   for (int t = 0; t < MT; ++t) {

@@ -94,13 +94,17 @@ __global__ void rmsnorm_kernel(const float* __restrict__ h, const T* __restrict_
   constexpr int kHeld = 8;                      // float4 per thread kept in registers
   const int step = blockDim.x * 4;
   float4 held[kHeld];
+  uint2 gheld[kHeld];                           // bf16 gains of the held elements, requested with them
   float ss = 0.f;
   const bool vec = (d & 3) == 0;
+  const bool aligned = (xn_plane & 3) == 0 && (copy_ld & 3) == 0 && ((uintptr_t)xn & 7) == 0 && ((uintptr_t)gain & 7) == 0 &&
+                       (!copy_out || ((uintptr_t)copy_out & 15) == 0);
   if (vec) {
 #pragma unroll
     for (int i = 0; i < kHeld; ++i) {
       const int c = threadIdx.x * 4 + i * step;
       held[i] = c < d ? *(const float4*)(row + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      if constexpr (sizeof(T) == 2) gheld[i] = (aligned && c < d) ? *(const uint2*)((const bf16_t*)gain + c) : make_uint2(0u, 0u);
     }
 #pragma unroll
     for (int i = 0; i < kHeld; ++i) ss += held[i].x * held[i].x + held[i].y * held[i].y + held[i].z * held[i].z + held[i].w * held[i].w;
@@ -118,9 +122,8 @@ __global__ void rmsnorm_kernel(const float* __restrict__ h, const T* __restrict_
   if (vec) {
     // four features at a time: one 8-byte gain load, one 8-byte store per bf16 plane (2-byte stores, one per element
     // and plane, made this kernel several times slower than the memory round trips it consists of)
-    auto put4 = [&](int c, float4 x) {
+    auto put4 = [&](int c, float4 x, uint2 gb) {
       if constexpr (sizeof(T) == 2) {
-        const uint2 gb = *(const uint2*)((const bf16_t*)gain + c);
         const float g[4] = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
                             __uint_as_float(gb.y & 0xffff0000u)};
         const float v[4] = {x.x * scale * g[0], x.y * scale * g[1], x.z * scale * g[2], x.w * scale * g[3]};
@@ -141,13 +144,11 @@ __global__ void rmsnorm_kernel(const float* __restrict__ h, const T* __restrict_
         put(c + 3, x.w);
       }
     };
-    const bool aligned = (xn_plane & 3) == 0 && (copy_ld & 3) == 0 && ((uintptr_t)xn & 7) == 0 && ((uintptr_t)gain & 7) == 0 &&
-                         (!copy_out || ((uintptr_t)copy_out & 15) == 0);
 #pragma unroll
     for (int i = 0; i < kHeld; ++i) {
       const int c = threadIdx.x * 4 + i * step;
       if (c < d) {
-        if (aligned) put4(c, held[i]);
+        if (aligned) put4(c, held[i], gheld[i]);
         else {
           put(c, held[i].x);
           put(c + 1, held[i].y);
@@ -165,8 +166,9 @@ __global__ void rmsnorm_kernel(const float* __restrict__ h, const T* __restrict_
 // Rotary embedding (pair (i, i + D/2)) of the q and k heads of one row; q goes out in the activation type,
 // k and v go to the row's KV slot (trunk position or private suffix depth).
 template <typename T>
-__global__ void rope_append_kernel(const float* qkv, const RowDesc* rows, const float* cos_sin, float* q_out, T* trunk_k,
-                                   T* trunk_v, T* suffix_k, T* suffix_v, int n_q_heads, int n_kv_heads, int head_dim,
+__global__ void rope_append_kernel(const float* __restrict__ qkv, const RowDesc* __restrict__ rows, const float* __restrict__ cos_sin,
+                                   float* __restrict__ q_out, T* __restrict__ trunk_k, T* __restrict__ trunk_v,
+                                   T* __restrict__ suffix_k, T* __restrict__ suffix_v, int n_q_heads, int n_kv_heads, int head_dim,
                                    int max_trunk, int suffix_cap) {
   int m = blockIdx.x;
   RowDesc r = rows[m];
@@ -178,20 +180,36 @@ __global__ void rope_append_kernel(const float* qkv, const RowDesc* rows, const 
   T* vdst = (r.is_branch ? suffix_v : trunk_v) + kv_row * kvd;
   const float* cs = cos_sin + (int64_t)m * half * 2;
   int n_rot = (n_q_heads + n_kv_heads) * half;
-  for (int idx = threadIdx.x; idx < n_rot; idx += blockDim.x) {
-    int head = idx / half, i = idx % half;
-    float c = cs[i * 2], s = cs[i * 2 + 1];
-    const float* hsrc = src + head * head_dim;   // q heads then k heads are contiguous in qkv
-    float a = hsrc[i], b = hsrc[i + half];
-    float ra = a * c - b * s, rb = b * c + a * s;
-    if (head < n_q_heads) {
-      float* dst = q_out + (int64_t)m * qd + head * head_dim;
-      dst[i] = ra;
-      dst[i + half] = rb;
-    } else {
-      T* dst = kdst + (head - n_q_heads) * head_dim;
-      Elem<T>::store(dst + i, ra);
-      Elem<T>::store(dst + i + half, rb);
+  // items in batches whose loads go out together (a 70B-shaped row has 18 items per thread: one at a time they were 18
+  // memory round trips); the input and the outputs never overlap, which the qualifiers above tell the compiler
+  constexpr int kBatch = 6;
+  for (int idx0 = threadIdx.x; idx0 < n_rot; idx0 += blockDim.x * kBatch) {
+    float a[kBatch], b[kBatch], c[kBatch], sn[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int idx = min(idx0 + u * (int)blockDim.x, n_rot - 1);
+      const int head = idx / half, i = idx % half;
+      const float* hsrc = src + head * head_dim;   // q heads then k heads are contiguous in qkv
+      c[u] = cs[i * 2];
+      sn[u] = cs[i * 2 + 1];
+      a[u] = hsrc[i];
+      b[u] = hsrc[i + half];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int idx = idx0 + u * (int)blockDim.x;
+      if (idx >= n_rot) break;
+      const int head = idx / half, i = idx % half;
+      const float ra = a[u] * c[u] - b[u] * sn[u], rb = b[u] * c[u] + a[u] * sn[u];
+      if (head < n_q_heads) {
+        float* dst = q_out + (int64_t)m * qd + head * head_dim;
+        dst[i] = ra;
+        dst[i + half] = rb;
+      } else {
+        T* dst = kdst + (head - n_q_heads) * head_dim;
+        Elem<T>::store(dst + i, ra);
+        Elem<T>::store(dst + i + half, rb);
+      }
     }
   }
   for (int c = threadIdx.x; c < kvd; c += blockDim.x) Elem<T>::store(vdst + c, src[qd + kvd + c]);
