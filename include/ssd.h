@@ -202,6 +202,10 @@ int ssd_ctx_truncate_trunk(ssd_ctx* ctx, const int32_t* h_lens, void* stream);
  * verified text, i.e. rejected positions and bounds that ran ahead), ssd_ctx_truncate_trunk, ssd_ctx_release_sequence.
  * ENOMEM when the pool is empty: the context is unchanged apart from pages already taken for the same call; release a
  * sequence or refresh the bounds and call again.
+ * ssd_ctx_prefill runs all sequences in common passes up to the longest prompt, so until it returns every sequence holds
+ * pages for that length (the surplus goes back at its end): a pool sized for the true lengths only is filled slot by slot
+ * with ssd_ctx_prefill_sequence.  The block table lives in pinned host memory and is copied to the device in stream
+ * order whenever it changed; calls on one context are not thread-safe.
  *   ssd_ctx_kv_pages          total pages (0 for a contiguous trunk) and pages currently free.
  *   ssd_ctx_release_sequence  sequence b finished: its pages return to the pool and its trunk is empty; a round must not
  *                             run before the slot is refilled (ESTATE from ssd_prespeculate: empty trunk).  Synchronises.

@@ -135,7 +135,7 @@ def test_paged_round_against_the_oracle(B):
         B.ssd_model_destroy(model)
 
 
-@pytest.mark.parametrize("pages", [0, 14])
+@pytest.mark.parametrize("pages", [0, 14, -1])
 def test_a_sequence_leaves_and_another_joins_its_slot(B, pages):
     """Continuous batching: after a round, sequence 1 finishes and a new request takes its slot while sequences 0 and 2
     keep their trunks.  The next round equals, bit for bit, the round of a context in which the three requests were
@@ -148,8 +148,10 @@ def test_a_sequence_leaves_and_another_joins_its_slot(B, pages):
     joiner = I.make_prompt(shape, 1, new_len, seed + 9)[0]
     temps = dev_f32(np.zeros(batch, np.float32))
     pending = dev_i32(I.make_pending(shape, batch, K, seed))
-    direct = B.ssd_ctx_create(model, batch, K, F, 128)
-    served = B.ssd_ctx_create(model, batch, K, F, 128, 0, pages)
+    flags = B.SSD_CTX_PER_OPERATOR if pages < 0 else 0     # -1: the same on the per-operator kernels (contiguous trunk)
+    pages = max(pages, 0)
+    direct = B.ssd_ctx_create(model, batch, K, F, 128, flags)
+    served = B.ssd_ctx_create(model, batch, K, F, 128, flags, pages)
     try:
         for b, toks in enumerate([prompts[0], joiner, prompts[2]]):
             B.ssd_ctx_prefill_sequence(direct, b, dev_i32(toks))
