@@ -286,6 +286,8 @@ def main():
     ap.add_argument("--one-plane", type=lambda x: int(x, 0), default=None, metavar="MASK",
                     help="activation tensors the fused pass carries as ONE bf16 plane instead of head + remainder: bits "
                          "1 xn, 2 att, 4 act, 8 q, 16 p (31 = all; default: the library's default configuration)")
+    ap.add_argument("--per-operator", action="store_true",
+                    help="one kernel per operator instead of the fused passes (the path of models the fused passes do not take)")
     ap.add_argument("--paged", action="store_true",
                     help="keep the trunk KV in 32-position pages behind a block table (App. B) instead of one run per sequence")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -324,6 +326,8 @@ def main():
     model = B.ssd_model_create(shape, w)
     fan = None
     ctx_flags = 0 if args.one_plane is None else (args.one_plane & 31) << 8
+    if args.per_operator:
+        ctx_flags |= B.SSD_CTX_PER_OPERATOR
     if args.geometric_fanout:
         a_rate, r_exp = (float(x) for x in args.geometric_fanout.split(","))
         fan = B.ssd_geometric_fanout((K + 1) * F, K, a_rate, r_exp)
