@@ -223,15 +223,16 @@ def bench_target_verify(args):
     B.ssd_model_destroy(draft)
 
 
-def sub_record(B, I, model, shape, name, steps):
-    """Kernel time and roofline fraction of one branch-decode step of another workload of the same model: a few
-    rounds on a context of its own, HIP events around the step's kernels on their stream."""
+def sub_record(B, I, model, shape, name, steps, flags=0):
+    """Kernel time and roofline fraction of one branch-decode step of another workload (or another context
+    configuration) of the same model: a few rounds on a context of its own, HIP events around the step's kernels on
+    their stream."""
     import numpy as np
     import torch
     wl = I.WORKLOADS[name]
     r = wl.round
     K, F, P, nb, V = r.K, r.F, r.prefix, r.batch, shape.vocab
-    ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2)
+    ctx = B.ssd_ctx_create(model, nb, K, F, P + 2 * K + 2, flags)
     try:
         k, v = I.make_prefix_kv(shape, nb, P, wl.seed)
         to_bf16 = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()

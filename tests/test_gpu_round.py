@@ -60,8 +60,9 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
     assert B.ssd_ctx_fanout(ctx) == fan
     which = B.ssd_ctx_views(ctx).fused_pass
     wide = B.ssd_ctx_views(ctx).pass_rows > 48
+    one_plane = bool(flags & B.SSD_CTX_ONE_PLANE_ALL)
     if shape.dtype == "bf16":
-        tol = min(tol, TOL_WIDE_BF16 if wide else (TOL_FUSED_BF16 if synthetic_kv else TOL_BF16_OWN_PREFILL))
+        tol = min(tol, TOL_WIDE_BF16 if wide or one_plane else (TOL_FUSED_BF16 if synthetic_kv else TOL_BF16_OWN_PREFILL))
     assert which == 0 if flags & B.SSD_CTX_PER_OPERATOR else True
     try:
         if synthetic_kv:
@@ -98,7 +99,7 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
                     n_keys_checked += 1
                 if k < K:
                     assert pending[b, k + 1] not in free["keys"][b, k]
-        assert n_keys_checked > 0 or wide       # (one bf16 plane: the error can exceed every gap of a small model's top F + 1)
+        assert n_keys_checked > 0 or wide or one_plane       # (one bf16 plane: the error can exceed every gap of a small model's top F + 1)
 
         # ---- teacher-forced run: every row consumes the oracle's tokens
         f_keys = dev_i32(np.stack([_in_row_order(c.keys, fan) for c in caches]))
@@ -172,6 +173,23 @@ def test_small_bf16_fused_pass_group_of_two_and_long_lookahead(B):
                          vocab=4112, dtype="bf16", rope_theta=500000.0, tie_embeddings=True)
     _run_round_parity(B, shape, batch=1, P=70, K=3, F=3, seed=12, synthetic_kv=True)
     _run_round_parity(B, SMALL_BF16, batch=1, P=45, K=8, F=2, seed=13, synthetic_kv=False)
+
+
+def test_small_bf16_narrow_pass_with_one_plane_per_activation(B):
+    """SSD_CTX_ONE_PLANE_ALL: every tensor the narrow pass hands from phase to phase travels as one bf16 plane (the plain
+    bf16 mixed precision of the paper's system, App. B) instead of head + remainder; same round, the bound of that
+    arithmetic.  A combination that is not compiled in is refused at creation."""
+    _, forced, _, worst = _run_round_parity(B, SMALL_BF16, batch=2, P=203, K=3, F=3, seed=7, synthetic_kv=True,
+                                            flags=B.SSD_CTX_ONE_PLANE_ALL)
+    _, _, _, two = _run_round_parity(B, SMALL_BF16, batch=2, P=203, K=3, F=3, seed=7, synthetic_kv=True)
+    print(f"[planes] worst error one plane {worst:.3e}, two planes {two:.3e}", flush=True)
+    assert worst > two                       # the flag did change the arithmetic
+    model = B.ssd_model_create(SMALL_BF16, I.make_weights(SMALL_BF16, 7))
+    try:
+        with pytest.raises(B.SsdError):
+            B.ssd_ctx_create(model, 2, 3, 3, 256, 0x100)          # SSD_CTX_ONE_PLANE_XN alone
+    finally:
+        B.ssd_model_destroy(model)
 
 
 def test_fused_pass_phase_by_phase_equals_persistent(B):
