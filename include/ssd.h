@@ -138,7 +138,7 @@ typedef struct {
   int32_t batch, K, F, vocab, d_model, max_trunk;
   int32_t fused_pass;          /* 0: one kernel per operator; 1: fused pass, one launch per phase; 2: one persistent launch */
   int32_t pass_rows;           /* most rows of one fused pass: 48 (narrow passes, activations as two bf16 planes), 384 (wide
-                                  passes, one bf16 plane), 0 without the fused pass */
+                                  passes, one fp16 plane against fp16 copies of the weights), 0 without the fused pass */
 } ssd_views;
 
 const char* ssd_last_error(void);

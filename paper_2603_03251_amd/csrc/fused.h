@@ -114,10 +114,13 @@ bool fused_supported(const Dims& d, int max_rows);
 // Runs phases [first, last].  persistent = 1: one launch with grid barriers between phases;
 // persistent = 0: one launch per phase (a debugging aid that needs no co-residency).
 int launch_fused(const FusedParams& p, int first, int last, int persistent, hipStream_t s);
-// The same phases for up to kFusedWideRows rows (workspace strides of kFusedWideRows rows, one bf16 plane per tensor),
+// The same phases for up to kFusedWideRows rows (workspace strides of kFusedWideRows rows, one fp16 plane per tensor,
+// the layers' .w and p.lm.w pointing at fp16 copies of the stream-order weights),
 // one launch per phase.  layers_host: the layer table p.layers points at, in host memory.
 int launch_fused_wide(const FusedParams& p, const FusedLayer* layers_host, int first, int last, hipStream_t s);
 bool fused_wide_gemm_ok(const FusedGemm& g, int at);
+// dst[i] = fp16(src[i]) over a stream-order weight buffer (the wide passes multiply in fp16); n a multiple of 8
+int launch_bf16_to_f16(const bf16_t* src, bf16_t* dst, int64_t n, hipStream_t s);
 int fused_grid_size(int* out);
 // EINVAL unless `nwg` workgroups of every instance of the persistent kernel can be resident at once on the current device
 int fused_check_residency(int nwg, int planes, int paged);

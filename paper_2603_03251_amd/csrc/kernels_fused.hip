@@ -37,6 +37,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 // pointers into global memory: loads and stores through these are global_*, never flat_* instructions
@@ -95,8 +96,10 @@ __device__ __forceinline__ f32x4 fix_empty() {
 // for loads degrade to "wait for everything", which would empty the weight pipeline at every unit of the LM head.
 // Hidden, the store only makes a later counted wait err on the safe side: loads complete in order among themselves,
 // so "at most N operations outstanding" still implies that every load older than the N youngest has arrived.
+// (the s_nop: a store of more than 8 bytes must not be followed at once by a VALU write of its data registers, a
+// hazard the compiler covers for its own stores and cannot see inside this one)
 __device__ __forceinline__ void st_f32x4_uncounted(float* p, f32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(p), "v"(v));
+  asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 0" : : "v"(p), "v"(v));
 }
 // Thread coordinates read afresh where they are called: everything derived from them (row and tile indices, LDS and
 // global addresses) is then local to the phase that computes it.  Derived from the kernel-wide threadIdx they would be
@@ -120,6 +123,21 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 // fp32 -> bf16, round to nearest even, on the conversion unit gfx950 has for it (v_cvt_pk_bf16_f32): the softmax and the
 // head/remainder splits convert thousands of values per phase, and the integer sequence costs ~8 VALU instructions each
 __device__ __forceinline__ bf16_t to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// Wide passes multiply in fp16 x fp16 -> fp32: their activations travel as ONE 16-bit plane, and through 16 layers the 8
+// mantissa bits of bf16 put the hidden states 1.4e-2 .. 2.0e-2 from a float64 reference (measured), at the edge of what
+// bf16 paths are held to; fp16 keeps 11.  The weights are converted once (exact for |w| >= 2^-14; smaller ones round to
+// fp16 subnormals, absolute error <= 2^-25); activations saturate at the fp16 range.  Operands keep the 16-byte tile
+// layouts, so loads and staging are the same for both types.
+__device__ __forceinline__ uint16_t to_f16(float x) {
+  const _Float16 h = (_Float16)fminf(fmaxf(x, -65504.0f), 65504.0f);
+  return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ f32x4 mfma16_f16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma32_f16(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
 
 // Optional phase clocks (a measurement aid): [phase][slot][workgroup] ticks of the 100 MHz real-time counter; slot 0
 // phase entry, 1 after the grid barrier, 2 end of the phase's work, 3.. probes inside a phase.
@@ -1252,7 +1270,7 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
           const float inv = 1.0f / lsum;
           bf16_t hi[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) hi[e] = to_bf16(o[e] * inv);
+          for (int e = 0; e < 4; ++e) hi[e] = to_f16(o[e] * inv);      // (this unit serves wide passes only: fp16 activations)
           st_u64(att_out + b_off<MT>(k, mm), pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
         } else {
           const int64_t pb = ((int64_t)(b * p.Hkv + hk) * p.NS + s) * (p.QT * 16) + qrow;
@@ -1299,7 +1317,7 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
 
 // Merge unit (only when the trunk is split over several units): one wavefront per (row, query head), lane = head
 // dimension, merges the NS partial softmaxes and writes the attention output planes.
-template <int MT, int MP, int NPT>
+template <int MT, int MP, int NPT, bool F16 = false>
 __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, const float* part_o, const float* part_ml,
                                                 bf16_t* att_out) {
   const int d = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1323,7 +1341,7 @@ __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, 
     o += wgt * go[pb * 64 + d];
   }
   const float x = o / lsum;
-  const bf16_t hi = to_bf16(x);
+  const bf16_t hi = F16 ? to_f16(x) : to_bf16(x);                  // F16: the one fp16 plane of the wide passes
   const bf16_t lo = to_bf16(x - bf16_to_f32(hi));
   // lanes d, d+1, d+2, d+3 -> one 8-byte store per plane from lane d (d % 4 == 0)
   uint32_t w = (uint32_t)hi | ((uint32_t)lo << 16);
@@ -1351,7 +1369,7 @@ __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, 
 // while one is multiplied: a compute unit has to keep about 200 KiB in flight to pull at L2 rate.  The wavefronts
 // split the reduction dimension; each streams its own weight tiles (A operands, straight from the stream-order
 // layout: two of its eight wavefront runs, and a k-slice of a K-split layer is just another piece of the range) and
-// the matching activation tiles of the row group (B operands, one bf16 plane): 24 MFMAs per 10 KiB pulled.  The row
+// the matching activation tiles of the row group (B operands, one fp16 plane): 24 MFMAs per 10 KiB pulled.  The row
 // groups of one set of feature tiles run on workgroups of ONE XCD (workgroup w runs on XCD w % 8), so the weights
 // leave HBM once and the other row groups find them in that XCD's L2.  The four partial tiles meet in LDS (96 KiB) and
 // are added in wavefront order.
@@ -1512,7 +1530,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_kernel(FusedParams p, 
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int t = 0; t < MTG; ++t) acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ck.a[j], ck.b[t], acc[j][t], 0, 0, 0);
+      for (int t = 0; t < MTG; ++t) acc[j][t] = mfma16_f16(ck.a[j], ck.b[t], acc[j][t]);
   };
 
   // 1/rms of the rows this workgroup's pairs cover: one row group if per_xcd is a multiple of n_rg, else all rows
@@ -1572,7 +1590,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_kernel(FusedParams p, 
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float gg = gv[i] * rs, uu = uv[i] * rs;
-            hi[i] = to_bf16(gg / (1.0f + __expf(-gg)) * uu);
+            hi[i] = to_f16(gg / (1.0f + __expf(-gg)) * uu);
           }
           const int k = q * 32 + j * 16 + f4;      // input index of the down-projection
           st_u64_uncounted(e.act_out + b_off<MTOT>(k, m), pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
@@ -1589,7 +1607,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_kernel(FusedParams p, 
         if constexpr (EPI == FE_QKV || EPI == FE_LOGITS) {
           if (m < p.M) st_f32x4_uncounted(e.out + (int64_t)m * e.ld + nn, v * r_s[m]);
         } else {
-          // residual stream: new h, (h * gain) as one bf16 plane for the next linear layer, this tile's sum of squares
+          // residual stream: new h, (h * gain) as one fp16 plane for the next linear layer, this tile's sum of squares
           f32x4 hn = v;
           float ss = 0.f;
           if (m < p.M) {
@@ -1601,7 +1619,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_kernel(FusedParams p, 
             bf16_t hi[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              hi[i] = to_bf16(hn[i] * gg[i]);
+              hi[i] = to_f16(hn[i] * gg[i]);
               ss += hn[i] * hn[i];
             }
             st_u64_uncounted(e.xn_out + b_off<MTOT>(nn, m), pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
@@ -1771,7 +1789,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
           for (int f = 0; f < 2; ++f)
 #pragma unroll
             for (int t = 0; t < MT32; ++t)
-              acc[f][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[j][2 * f + h], bt[j & 1][2 * t + h], acc[f][t], 0, 0, 0);
+              acc[f][t] = mfma32_f16(ring[j][2 * f + h], bt[j & 1][2 * t + h], acc[f][t]);
         load_a(cu, j);
         // the refill stays here, a whole stage ahead of its use: left alone, the instruction scheduler sinks it to just
         // before that use to save registers, and every k-tile then waits a full memory latency
@@ -1800,7 +1818,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
                 const float gg = acc[0][t][4 * q + i] * rs, uu = acc[1][t][4 * q + i] * rs;
-                hi[i] = to_bf16(gg / (1.0f + __expf(-gg)) * uu);
+                hi[i] = to_f16(gg / (1.0f + __expf(-gg)) * uu);
               }
               const int k = unit * 32 + 8 * q + f4;       // input index of the down-projection
               st_u64_uncounted(e.act_out + b_off<MTOT>(k, m), pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
@@ -1828,7 +1846,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_gemm_lds_kernel(FusedParams
 }
 
 // The other phases of a wide pass (embedding, attention, merge of key splits, final hidden states), one launch each:
-// the narrow pass's units over a workspace of kFusedWideRows rows, one bf16 plane per tensor.
+// the narrow pass's units over a workspace of kFusedWideRows rows, one fp16 plane per tensor.
 template <class PL, bool PG>
 __global__ __launch_bounds__(kFusedThreads) void wide_kernel(FusedParams p, int ph) {
   constexpr int MP = kFusedWideRows, MTOT = kWideTiles;
@@ -1847,7 +1865,7 @@ __global__ __launch_bounds__(kFusedThreads) void wide_kernel(FusedParams p, int 
   float* part_ml = p.part_ml + (int64_t)l * p.part_layer_stride * 2;
   stamp(p, ph, 0);
   if (sub == -1) {
-    // embedding gather: residual stream version 0, (h * gain) as one bf16 plane, sums of squares per 64 features
+    // embedding gather: residual stream version 0, (h * gain) as one fp16 plane, sums of squares per 64 features
     for (int u = blockIdx.x; u < (p.d >> 6); u += gridDim.x) {
       for (int t = wave; t < ((p.M + 15) >> 4); t += kFusedWaves) {
         const int m = t * 16 + (lane & 15);
@@ -1868,7 +1886,7 @@ __global__ __launch_bounds__(kFusedThreads) void wide_kernel(FusedParams p, int 
             bf16_t hi[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              hi[i] = to_bf16(hv[i] * gg[i]);
+              hi[i] = to_f16(hv[i] * gg[i]);
               ss += hv[i] * hv[i];
             }
             *(uint64_t*)(p.xn + b_off<MTOT>(n, m)) = pack_bf16x4(hi[0], hi[1], hi[2], hi[3]);
@@ -1883,7 +1901,7 @@ __global__ __launch_bounds__(kFusedThreads) void wide_kernel(FusedParams p, int 
     for (int u = blockIdx.x; u < p.n_attn_units; u += gridDim.x)
       attn_unit_multi<MTOT, MP, PL::q, PL::p, kWideQueryTiles, PG>(p, L, qkv, u, red, att, part_o, part_ml);
   } else if (sub == 2) {
-    for (int u = blockIdx.x; u < p.n_pair_units; u += gridDim.x) attn_merge_unit<MTOT, MP, 1>(p, u, part_o, part_ml, att);
+    for (int u = blockIdx.x; u < p.n_pair_units; u += gridDim.x) attn_merge_unit<MTOT, MP, 1, true>(p, u, part_o, part_ml, att);
   } else if (sub == 6 && p.hidden) {
     // final-norm hidden states: workgroup per row, the row's scale from the tile sums
     const int v = 2 * p.L;
@@ -2160,6 +2178,25 @@ int launch_retile_stream(const bf16_t* src0, int rows0, const bf16_t* src1, int 
   return SSD_OK;
 }
 
+// The fp16 copy of a stream-order weight buffer for the wide passes: same layout, every element converted (8 per thread)
+__global__ void bf16_to_f16_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int64_t n8) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n8) return;
+  Bf8 v, o;
+  v.w = *(const u32x4*)(src + i * 8);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o.u[e] = to_f16(bf16_to_f32(v.u[e]));
+  *(u32x4*)(dst + i * 8) = o.w;
+}
+
+int launch_bf16_to_f16(const bf16_t* src, bf16_t* dst, int64_t n, hipStream_t s) {
+  SSD_CHECK_ARG(n % 8 == 0, "bf16_to_f16: element count %lld is not a multiple of 8", (long long)n);
+  if (n == 0) return SSD_OK;
+  bf16_to_f16_kernel<<<(unsigned)((n / 8 + 255) / 256), 256, 0, s>>>(src, dst, n / 8);
+  SSD_HIP(hipGetLastError());
+  return SSD_OK;
+}
+
 int launch_copy_kv_fused(bf16_t* trunk_k, bf16_t* trunk_vt, const bf16_t* src_k, const bf16_t* src_v, int B, int len, int Hkv,
                          int vt_stride, const int32_t* pages, int page_stride, hipStream_t s) {
   int64_t total = (int64_t)B * len * Hkv * 64;
@@ -2350,8 +2387,12 @@ int fused_check_residency(int nwg, int planes, int paged) {
   return SSD_EINVAL;
 }
 
-// Wide passes carry xn, att and act as one bf16 plane; the queries and probabilities of the attention unit keep two
-// planes unless both of their bits are set in p.planes.
+// Wide passes carry xn, att and act as ONE plane each, in fp16, and their linear layers multiply fp16 copies of the
+// weights (exact: a bf16 weight of ordinary size is an fp16 number): one bf16 plane rounds every activation to 8
+// significant bits and 16 layers of that put hidden states 1.4e-2 (mean) to 2e-2 (worst row) from the float64 result,
+// fp16's 11 bits put them at 2e-3, for the same bytes and the same MFMA rate.  Values beyond fp16's range saturate
+// at +-65504 (to_f16).  Keys and values stay bf16 in the caches that all passes share, and the attention unit's
+// queries and probabilities keep two bf16 planes unless both of their bits are set in p.planes.
 int launch_fused_wide(const FusedParams& p, const FusedLayer* layers_host, int first, int last, hipStream_t s) {
   SSD_CHECK_ARG(p.M >= 1 && p.M <= kFusedWideRows, "wide fused pass of %d rows (1..%d supported)", p.M, kFusedWideRows);
   SSD_CHECK_ARG(p.nwg >= 8 && p.nwg % 8 == 0, "fused grid of %d workgroups must be a multiple of 8", p.nwg);

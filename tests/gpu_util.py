@@ -17,11 +17,13 @@ TOL = {"bf16": 2e-2, "f32": 1e-4}
 # rounded to bf16 while the oracle keeps its own in float64.
 TOL_FUSED_BF16 = 4e-3
 TOL_BF16_OWN_PREFILL = 8e-3
-# Wide passes (more than 48 rows in one batched forward) carry every activation between phases as ONE bf16 plane, the
-# plain bf16 mixed precision of the paper's system: measured 4e-3 .. 7e-3 on the small shapes (2 layers) and up to
-# 1.7e-2 through the 16 layers of the 1B shape (49 roundings of 2^-9 on the way to the logits), so the bound for them is
-# the benchmark spec's figure itself.
-TOL_WIDE_BF16 = 2e-2
+# Wide passes (more than 48 rows in one batched forward) carry every activation between phases as ONE plane, in fp16,
+# and multiply fp16 copies of the weights: measured 1.8e-3 (mean) and 2.5e-3 (worst row) through the 16 layers of the 1B
+# shape, so they are held to the bound of the narrow pass after its own prefill.
+TOL_WIDE_BF16 = 8e-3
+# The narrow pass with every activation as one bf16 plane (a measurement option): 8 significant bits per activation,
+# 4e-3 .. 7e-3 on the small shapes (2 layers); only those are tested, against the benchmark spec's figure itself.
+TOL_ONE_PLANE_BF16 = 2e-2
 # decisions that rest on floating point are compared only where the oracle's own margin exceeds this
 MARGIN = 1e-4
 

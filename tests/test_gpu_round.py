@@ -11,7 +11,7 @@ import torch
 
 import ssd_inputs as I
 from oracle import ssd_oracle as O
-from tests.gpu_util import (MARGIN, TOL, TOL_BF16_OWN_PREFILL, TOL_FUSED_BF16, TOL_WIDE_BF16, dev_f32, dev_i32, elem_rel_err, kv_to_device,
+from tests.gpu_util import (MARGIN, TOL, TOL_BF16_OWN_PREFILL, TOL_FUSED_BF16, TOL_ONE_PLANE_BF16, TOL_WIDE_BF16, dev_f32, dev_i32, elem_rel_err, kv_to_device,
                             oracle_trunk_from_arrays, rms_rel_err, row_rel_err)
 
 pytestmark = pytest.mark.gpu
@@ -62,7 +62,8 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
     wide = B.ssd_ctx_views(ctx).pass_rows > 48
     one_plane = bool(flags & B.SSD_CTX_ONE_PLANE_ALL)
     if shape.dtype == "bf16":
-        tol = min(tol, TOL_WIDE_BF16 if wide or one_plane else (TOL_FUSED_BF16 if synthetic_kv else TOL_BF16_OWN_PREFILL))
+        tol = min(tol, TOL_ONE_PLANE_BF16 if one_plane and not wide else
+                  TOL_WIDE_BF16 if wide else (TOL_FUSED_BF16 if synthetic_kv else TOL_BF16_OWN_PREFILL))
     assert which == 0 if flags & B.SSD_CTX_PER_OPERATOR else True
     try:
         if synthetic_kv:
