@@ -285,8 +285,9 @@ def main():
                     help="give every sequence of the batch its own prefix length (seeded, between a tenth of the workload's "
                          "prefix and all of it) instead of the same one")
     ap.add_argument("--one-plane", type=lambda x: int(x, 0), default=None, metavar="MASK",
-                    help="activation tensors the fused pass carries as ONE bf16 plane instead of head + remainder: bits "
-                         "1 xn, 2 att, 4 act, 8 q, 16 p (31 = all; default: the library's default configuration)")
+                    help="activation tensors the narrow fused pass carries as ONE 16-bit plane instead of head + remainder: "
+                         "bits 1 xn, 2 att, 4 act, 8 q, 16 p (0 = two planes everywhere, 31 = one everywhere; default: the "
+                         "library's default configuration, 7)")
     ap.add_argument("--per-operator", action="store_true",
                     help="one kernel per operator instead of the fused passes (the path of models the fused passes do not take)")
     ap.add_argument("--paged", action="store_true",
@@ -326,7 +327,7 @@ def main():
     w = I.make_weights(shape, WEIGHT_SEED)
     model = B.ssd_model_create(shape, w)
     fan = None
-    ctx_flags = 0 if args.one_plane is None else (args.one_plane & 31) << 8
+    ctx_flags = 0 if args.one_plane is None else B.SSD_CTX_TWO_PLANES | (args.one_plane & 31) << 8
     if args.per_operator:
         ctx_flags |= B.SSD_CTX_PER_OPERATOR
     if args.geometric_fanout:

@@ -111,15 +111,20 @@ enum {
   SSD_CTX_NARROW_PASSES = 4, /* a context with more than 48 rows in a batched forward runs them as passes of whole sequences
                                 of at most 48 rows (the weights are then streamed once per pass) instead of wide passes of
                                 up to 384 rows; a comparison aid */
-  /* Precision of the activations the narrow fused pass hands from phase to phase.  Default: two bf16 planes, head +
-   * remainder (about 2^-17 relative, so only weights and KV are rounded to bf16).  With a bit set that tensor travels as
-   * one bf16 plane, at half the operand traffic and MFMAs: the normalised residual stream, the attention output, the
-   * SwiGLU output, the rotated queries, the softmax probabilities.  A measurement aid (what the second plane costs: 4 % of
-   * a 24-row step of the 1B shape, 11 % at 48 rows): with all five the error against a float64 reference reaches
-   * 1.7e-2 (logits) / 2.2e-2 (hidden states) through 16 layers, beyond the 2e-2 the parity tests hold bf16 paths to.
-   * EINVAL for a combination that is not compiled in (all five or none are). */
+  /* Precision of the activations the narrow fused pass hands from phase to phase.  The three that meet the weights (the
+   * normalised residual stream xn, the attention output att, the SwiGLU output act) travel in fp16 and the linear
+   * layers multiply them with fp16 copies of the bf16 weights (exact for |w| >= 2^-14, absolute error <= 2^-25 below;
+   * activations beyond +-65504 saturate); the rotated queries q and the softmax probabilities p meet the bf16 KV store
+   * and are bf16.  A tensor is one 16-bit plane or two (head + remainder: about twice the significant bits, twice the
+   * operand traffic and MFMAs).  Default: xn, att, act one fp16 plane (11 bits), q and p two bf16 planes; measured
+   * against a float64 reference through the 16 layers of the 1B shape: 2.6e-3 (worst row).
+   * SSD_CTX_TWO_PLANES: every tensor two planes unless its ONE_PLANE bit is set (alone: 1.1e-3, at +4 % time on a 24-row
+   * step and +11 % on a 48-row step at 8192 keys).  ONE_PLANE_Q / ONE_PLANE_P: that tensor as one bf16 plane too (with
+   * both, = ONE_PLANE_ALL: 1.1e-2, no faster than the default; a measurement aid).  Wide passes always run the default.
+   * EINVAL for a combination that is not compiled in (compiled: the default, TWO_PLANES alone, ONE_PLANE_ALL). */
   SSD_CTX_ONE_PLANE_XN = 0x100, SSD_CTX_ONE_PLANE_ATT = 0x200, SSD_CTX_ONE_PLANE_ACT = 0x400,
-  SSD_CTX_ONE_PLANE_Q = 0x800, SSD_CTX_ONE_PLANE_P = 0x1000, SSD_CTX_ONE_PLANE_ALL = 0x1f00
+  SSD_CTX_ONE_PLANE_Q = 0x800, SSD_CTX_ONE_PLANE_P = 0x1000, SSD_CTX_ONE_PLANE_ALL = 0x1f00,
+  SSD_CTX_TWO_PLANES = 0x2000
 };
 
 /* Read-only device views of the context's state, for tests and for the verifier's payload. */
@@ -137,8 +142,7 @@ typedef struct {
                                    [B][Hkv][T][D], values transposed per 32-position block [B][Hkv][T/32][D][32] */
   int32_t batch, K, F, vocab, d_model, max_trunk;
   int32_t fused_pass;          /* 0: one kernel per operator; 1: fused pass, one launch per phase; 2: one persistent launch */
-  int32_t pass_rows;           /* most rows of one fused pass: 48 (narrow passes, activations as two bf16 planes), 384 (wide
-                                  passes, one fp16 plane against fp16 copies of the weights), 0 without the fused pass */
+  int32_t pass_rows;           /* most rows of one fused pass: 48 (narrow passes), 384 (wide passes), 0 without the fused pass */
 } ssd_views;
 
 const char* ssd_last_error(void);

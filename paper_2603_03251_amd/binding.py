@@ -20,6 +20,7 @@ SSD_F32, SSD_BF16 = 0, 1
 SSD_MAX_F, SSD_MAX_K = 16, 15
 SSD_CTX_PER_OPERATOR, SSD_CTX_FUSED_PHASES, SSD_CTX_NARROW_PASSES = 1, 2, 4
 SSD_CTX_ONE_PLANE_ALL = 0x1f00
+SSD_CTX_TWO_PLANES = 0x2000
 SSD_DEBUG_BARRIER_EPOCH, SSD_DEBUG_SPIN_LIMIT = 1, 2
 
 

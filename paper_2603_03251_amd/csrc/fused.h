@@ -25,7 +25,7 @@ constexpr unsigned kFusedSpinLimit = 4000000u;   // polls of a bounded wait (sec
 // [unit][wavefront][k-tile of the wavefront][feature tile of the unit], so each wavefront streams one contiguous
 // run of memory per unit.  Workgroup g takes units g, g + grid, ...
 struct FusedGemm {
-  const bf16_t* w;
+  const bf16_t* w;  // 16-bit elements holding fp16 (converted from the model's bf16 when the layout is built)
   int KTW;      // k-tiles per wavefront and unit = Kd / 32 / 8 / KS
   int n_units;  // ceil(NT / AT) * KS
   int NT;       // real feature tiles (the last unit may hold zero padding)
@@ -114,12 +114,11 @@ bool fused_supported(const Dims& d, int max_rows);
 // Runs phases [first, last].  persistent = 1: one launch with grid barriers between phases;
 // persistent = 0: one launch per phase (a debugging aid that needs no co-residency).
 int launch_fused(const FusedParams& p, int first, int last, int persistent, hipStream_t s);
-// The same phases for up to kFusedWideRows rows (workspace strides of kFusedWideRows rows, one fp16 plane per tensor,
-// the layers' .w and p.lm.w pointing at fp16 copies of the stream-order weights),
+// The same phases for up to kFusedWideRows rows (workspace strides of kFusedWideRows rows, one fp16 plane per tensor),
 // one launch per phase.  layers_host: the layer table p.layers points at, in host memory.
 int launch_fused_wide(const FusedParams& p, const FusedLayer* layers_host, int first, int last, hipStream_t s);
 bool fused_wide_gemm_ok(const FusedGemm& g, int at);
-// dst[i] = fp16(src[i]) over a stream-order weight buffer (the wide passes multiply in fp16); n a multiple of 8
+// dst[i] = fp16(src[i]) over a stream-order weight buffer (the fused passes multiply in fp16; dst may be src); n a multiple of 8
 int launch_bf16_to_f16(const bf16_t* src, bf16_t* dst, int64_t n, hipStream_t s);
 int fused_grid_size(int* out);
 // EINVAL unless `nwg` workgroups of every instance of the persistent kernel can be resident at once on the current device

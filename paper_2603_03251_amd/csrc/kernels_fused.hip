@@ -5,8 +5,8 @@
 // for the qkv, gate/up and LM-head projections, over one of 2 or 4 k-slices of it for the o and down projections,
 // whose slices hand their partial tiles to slice 0 through memory; slice 0 adds them in slice order, so the result
 // does not depend on timing.  The 8 wavefronts of a workgroup split its reduction range; each streams its own
-// contiguous run of 1 KiB weight tiles (MFMA 16x16x32 A operands) and reads the matching activation tiles (B
-// operands: 16 rows x 32 inputs, written by the producing phase as bf16 head/remainder planes in exactly the lane
+// contiguous run of 1 KiB weight tiles (MFMA 16x16x32 A operands, fp16) and reads the matching activation tiles (B
+// operands: 16 rows x 32 inputs, written by the producing phase as fp16 head/remainder planes in exactly the lane
 // order the MFMA wants).  Two loop shapes: where a workgroup has at most one unit (qkv, o, down) ALL its weight
 // tiles are requested before it waits at the grid barrier in front of the phase; gate/up and the LM head stream
 // weights and activations together through a ring of register chunks whose first chunks go out before the barrier.
@@ -47,10 +47,11 @@ typedef __attribute__((address_space(1))) u32x2 gu32x2;
 typedef __attribute__((address_space(1))) float gfloat;
 typedef __attribute__((address_space(1))) bf16_t gbf16;
 
-// bf16 planes per activation tensor: 2 = head + remainder (x = head + remainder to about 2^-17 relative), 1 = the head
-// alone (x rounded to bf16, the plain mixed-precision arithmetic).  xn: (h * gain) feeding qkv, gate/up and the LM
-// head; att: attention output feeding the o-projection; act: SwiGLU output feeding the down-projection; q, p: the
-// rotated queries and the softmax probabilities inside the attention unit.
+// 16-bit planes per activation tensor: 2 = head + remainder, 1 = the head alone.  xn: (h * gain) feeding qkv, gate/up
+// and the LM head; att: attention output feeding the o-projection; act: SwiGLU output feeding the down-projection:
+// these three meet the weights and are fp16 (head alone: 11 significant bits; with the remainder about 22).  q, p: the
+// rotated queries and the softmax probabilities inside the attention unit, which meet the bf16 keys and values and are
+// bf16 (8 bits, or about 16 with the remainder).
 template <int X, int T, int C, int Q, int P>
 struct Planes {
   static constexpr int xn = X, att = T, act = C, q = Q, p = P;
@@ -123,15 +124,16 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 // fp32 -> bf16, round to nearest even, on the conversion unit gfx950 has for it (v_cvt_pk_bf16_f32): the softmax and the
 // head/remainder splits convert thousands of values per phase, and the integer sequence costs ~8 VALU instructions each
 __device__ __forceinline__ bf16_t to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
-// Wide passes multiply in fp16 x fp16 -> fp32: their activations travel as ONE 16-bit plane, and through 16 layers the 8
-// mantissa bits of bf16 put the hidden states 1.4e-2 .. 2.0e-2 from a float64 reference (measured), at the edge of what
-// bf16 paths are held to; fp16 keeps 11.  The weights are converted once (exact for |w| >= 2^-14; smaller ones round to
-// fp16 subnormals, absolute error <= 2^-25); activations saturate at the fp16 range.  Operands keep the 16-byte tile
-// layouts, so loads and staging are the same for both types.
+// The linear layers multiply in fp16 x fp16 -> fp32.  An activation that travels as ONE 16-bit plane keeps 11 significant
+// bits in fp16 where bf16 keeps 8: through 16 layers that is 2.5e-3 instead of 2e-2 between the hidden states and a
+// float64 reference (measured on 384-row passes), for the same bytes and the same MFMA rate.  The weights are converted
+// once, when the stream-order layout is built (exact for |w| >= 2^-14; smaller ones round to fp16 subnormals, absolute
+// error <= 2^-25); activations saturate at the fp16 range.  Keys, values, queries and probabilities stay bf16.
 __device__ __forceinline__ uint16_t to_f16(float x) {
   const _Float16 h = (_Float16)fminf(fmaxf(x, -65504.0f), 65504.0f);
   return __builtin_bit_cast(uint16_t, h);
 }
+__device__ __forceinline__ float f16_to_f32(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
 __device__ __forceinline__ f32x4 mfma16_f16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
@@ -236,7 +238,7 @@ __device__ __forceinline__ void compute_row_scales(const FusedParams& p, const f
 }
 
 // Residual-stream epilogue shared by the embedding, the o-projection and the down-projection: store the new h
-// (4 consecutive features n..n+3 of row m per lane), (h * gain) as head/remainder planes for the next linear
+// (4 consecutive features n..n+3 of row m per lane), (h * gain) as fp16 head/remainder planes for the next linear
 // layer, and this feature tile's sum of squares per row.
 template <int MT, int MP, int NPX>
 __device__ __forceinline__ void resid_store(const FusedParams& p, f32x4 hn, int m, int n, int lane, u32x2 gb,
@@ -251,8 +253,8 @@ __device__ __forceinline__ void resid_store(const FusedParams& p, f32x4 hn, int 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float x = hn[i] * g[i];
-      hi[i] = to_bf16(x);
-      lo[i] = to_bf16(x - bf16_to_f32(hi[i]));
+      hi[i] = to_f16(x);
+      lo[i] = to_f16(x - f16_to_f32(hi[i]));
       s += hn[i] * hn[i];
     }
     int64_t off = b_off<MT>(n, m);
@@ -401,8 +403,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
           for (int i = 0; i < 4; ++i) {
             float gg = v[i] * rs, uu = u[i] * rs;
             float a = gg / (1.0f + __expf(-gg)) * uu;
-            hi[i] = to_bf16(a);
-            lo[i] = to_bf16(a - bf16_to_f32(hi[i]));
+            hi[i] = to_f16(a);
+            lo[i] = to_f16(a - f16_to_f32(hi[i]));
           }
           const int k = unit * 32 + j * 16 + f4;    // input index of the down-projection
           int64_t off = b_off<MT>(k, m);
@@ -481,7 +483,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
           for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int pl = 0; pl < NP; ++pl)
-              acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[c][j], b[c % DB][t * NP + pl], acc[j][t], 0, 0, 0);
+              acc[j][t] = mfma16_f16(a[c][j], b[c % DB][t * NP + pl], acc[j][t]);
       }
     };
     if (KTW == 2) run(std::integral_constant<int, 2>());
@@ -528,7 +530,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
         for (int t = 0; t < MT; ++t)
 #pragma unroll
           for (int pl = 0; pl < NP; ++pl)
-            acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ck.a[j], ck.b[t * NP + pl], acc[j][t], 0, 0, 0);
+            acc[j][t] = mfma16_f16(ck.a[j], ck.b[t * NP + pl], acc[j][t]);
     };
     // weights of the first chunks go out before the barrier: they depend on nothing
     if (n_chunks > 0) {
@@ -959,8 +961,8 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           float x = o[i] * inv;
-          hi[i] = to_bf16(x);
-          lo[i] = to_bf16(x - bf16_to_f32(hi[i]));
+          hi[i] = to_f16(x);
+          lo[i] = to_f16(x - f16_to_f32(hi[i]));
         }
         const int64_t off = b_off<MT>(k, mm);
         st_u64(att_out + off, pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
@@ -1317,7 +1319,7 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
 
 // Merge unit (only when the trunk is split over several units): one wavefront per (row, query head), lane = head
 // dimension, merges the NS partial softmaxes and writes the attention output planes.
-template <int MT, int MP, int NPT, bool F16 = false>
+template <int MT, int MP, int NPT>
 __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, const float* part_o, const float* part_ml,
                                                 bf16_t* att_out) {
   const int d = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1341,8 +1343,8 @@ __device__ __forceinline__ void attn_merge_unit(const FusedParams& p, int unit, 
     o += wgt * go[pb * 64 + d];
   }
   const float x = o / lsum;
-  const bf16_t hi = F16 ? to_f16(x) : to_bf16(x);                  // F16: the one fp16 plane of the wide passes
-  const bf16_t lo = to_bf16(x - bf16_to_f32(hi));
+  const bf16_t hi = to_f16(x);
+  const bf16_t lo = to_f16(x - f16_to_f32(hi));
   // lanes d, d+1, d+2, d+3 -> one 8-byte store per plane from lane d (d % 4 == 0)
   uint32_t w = (uint32_t)hi | ((uint32_t)lo << 16);
   uint32_t w1 = __shfl_down(w, 1), w2 = __shfl_down(w, 2), w3 = __shfl_down(w, 3);
@@ -1901,7 +1903,7 @@ __global__ __launch_bounds__(kFusedThreads) void wide_kernel(FusedParams p, int 
     for (int u = blockIdx.x; u < p.n_attn_units; u += gridDim.x)
       attn_unit_multi<MTOT, MP, PL::q, PL::p, kWideQueryTiles, PG>(p, L, qkv, u, red, att, part_o, part_ml);
   } else if (sub == 2) {
-    for (int u = blockIdx.x; u < p.n_pair_units; u += gridDim.x) attn_merge_unit<MTOT, MP, 1, true>(p, u, part_o, part_ml, att);
+    for (int u = blockIdx.x; u < p.n_pair_units; u += gridDim.x) attn_merge_unit<MTOT, MP, 1>(p, u, part_o, part_ml, att);
   } else if (sub == 6 && p.hidden) {
     // final-norm hidden states: workgroup per row, the row's scale from the tile sums
     const int v = 2 * p.L;
@@ -2178,8 +2180,8 @@ int launch_retile_stream(const bf16_t* src0, int rows0, const bf16_t* src1, int 
   return SSD_OK;
 }
 
-// The fp16 copy of a stream-order weight buffer for the wide passes: same layout, every element converted (8 per thread)
-__global__ void bf16_to_f16_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int64_t n8) {
+// A stream-order weight buffer from bf16 to fp16: same layout, every element converted (8 per thread)
+__global__ void bf16_to_f16_kernel(const bf16_t* src, bf16_t* dst, int64_t n8) {   // dst may be src
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n8) return;
   Bf8 v, o;
@@ -2238,10 +2240,13 @@ int fused_grid_size(int* out) {
   return SSD_OK;
 }
 
-// The plane configurations that are compiled in: bit i of the mask set = that tensor travels as ONE bf16 plane
-// (bit 0 xn, 1 att, 2 act, 3 q, 4 p).
+// The plane configurations that are compiled in: bit i of the mask set = that tensor travels as ONE plane
+// (bit 0 xn, 1 att, 2 act, 3 q, 4 p).  The default, and the only one with a paged trunk: xn, att, act one fp16 plane,
+// q and p two bf16 planes (what the second plane of the former costs a 24-row step of the 1B shape: 4 %; 11 % at 48 rows
+// and 8192 keys; the error against a float64 reference goes from 1.1e-3 to 2.6e-3).
+constexpr int kFusedDefaultPlanes = 7;
 #ifndef SSD_FUSED_PLANE_MASKS
-#define SSD_FUSED_PLANE_MASKS X(0) X(31)
+#define SSD_FUSED_PLANE_MASKS X(0) X(7) X(31)
 #endif
 template <int MASK>
 using PlanesOf = Planes<(MASK & 1) ? 1 : 2, (MASK & 2) ? 1 : 2, (MASK & 4) ? 1 : 2, (MASK & 8) ? 1 : 2, (MASK & 16) ? 1 : 2>;
@@ -2377,8 +2382,8 @@ int fused_check_residency(int nwg, int planes, int paged) {
   SSD_HIP(hipGetDevice(&dev));
   SSD_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   if (paged) {
-    SSD_CHECK_ARG(planes == 0, "a paged trunk takes the default activation planes only");
-    return check_residency_pl<PlanesOf<0>, true>(nwg, cus);
+    SSD_CHECK_ARG(planes == kFusedDefaultPlanes, "a paged trunk takes the default activation planes only");
+    return check_residency_pl<PlanesOf<kFusedDefaultPlanes>, true>(nwg, cus);
   }
 #define X(m) if (planes == (m)) return check_residency_pl<PlanesOf<(m)>, false>(nwg, cus);
   SSD_FUSED_PLANE_MASKS
@@ -2387,12 +2392,9 @@ int fused_check_residency(int nwg, int planes, int paged) {
   return SSD_EINVAL;
 }
 
-// Wide passes carry xn, att and act as ONE plane each, in fp16, and their linear layers multiply fp16 copies of the
-// weights (exact: a bf16 weight of ordinary size is an fp16 number): one bf16 plane rounds every activation to 8
-// significant bits and 16 layers of that put hidden states 1.4e-2 (mean) to 2e-2 (worst row) from the float64 result,
-// fp16's 11 bits put them at 2e-3, for the same bytes and the same MFMA rate.  Values beyond fp16's range saturate
-// at +-65504 (to_f16).  Keys and values stay bf16 in the caches that all passes share, and the attention unit's
-// queries and probabilities keep two bf16 planes unless both of their bits are set in p.planes.
+// Wide passes carry xn, att and act as ONE fp16 plane each (2.5e-3 between hidden states and a float64 reference through
+// 16 layers, measured); the attention unit's queries and probabilities keep two bf16 planes unless both of their bits
+// are set in p.planes.
 int launch_fused_wide(const FusedParams& p, const FusedLayer* layers_host, int first, int last, hipStream_t s) {
   SSD_CHECK_ARG(p.M >= 1 && p.M <= kFusedWideRows, "wide fused pass of %d rows (1..%d supported)", p.M, kFusedWideRows);
   SSD_CHECK_ARG(p.nwg >= 8 && p.nwg % 8 == 0, "fused grid of %d workgroups must be a multiple of 8", p.nwg);
@@ -2424,8 +2426,8 @@ int launch_fused(const FusedParams& p, int first, int last, int persistent, hipS
                 "bad attention split");
   SSD_CHECK_ARG(first >= 0 && last <= fused_last_phase(p.L) && first <= last, "bad phase range");
   if (p.pages) {
-    SSD_CHECK_ARG(p.planes == 0, "a paged trunk takes the default activation planes only");
-    return launch_pl<PlanesOf<0>, true>(p, first, last, persistent, s);
+    SSD_CHECK_ARG(p.planes == kFusedDefaultPlanes, "a paged trunk takes the default activation planes only");
+    return launch_pl<PlanesOf<kFusedDefaultPlanes>, true>(p, first, last, persistent, s);
   }
 #define X(m) if (p.planes == (m)) return launch_pl<PlanesOf<(m)>, false>(p, first, last, persistent, s);
   SSD_FUSED_PLANE_MASKS

@@ -92,12 +92,6 @@ struct ssd_model {
   };
   std::vector<FusedW> fused_layers;
   FusedGemm fused_lm{};
-  // fp16 copies of the stream-order weights for the wide passes, made when the first wide context is created
-  mutable std::mutex wide_mu;
-  mutable bool wide_f16 = false;
-  mutable std::vector<FusedW> wide_layers;
-  mutable FusedGemm wide_lm{};
-  mutable Arena wide_arena;
   // the per-operator kernels' copies of the linear layers (tile order) can be given up: ssd_model_release_operator_weights
   bool operator_weights = true;
   mutable std::atomic<int> operator_contexts{0};   // live contexts that run the per-operator kernels
@@ -201,6 +195,8 @@ int make_stream_order(ssd_model* m, int grid, FusedGemm* g, const void* s0, int 
   SSD_TRY(m->arena.alloc(&dst, (size_t)stream_order_elems(N, Kd, at) * 2));
   SSD_TRY(launch_retile_stream((const bf16_t*)s0, r0, (const bf16_t*)s1, r1, (const bf16_t*)s2, r2, mode, at, ks, Kd,
                                (bf16_t*)dst, s));
+  // the fused passes multiply in fp16: convert in place (elementwise, same layout)
+  SSD_TRY(launch_bf16_to_f16((const bf16_t*)dst, (bf16_t*)dst, stream_order_elems(N, Kd, at), s));
   g->w = (const bf16_t*)dst;
   g->KS = ks;
   g->KTW = Kd / 32 / kFusedWaves / ks;
@@ -555,40 +551,6 @@ int extend_rows(ssd_ctx* c, const int32_t* tokens, int T, int offset, float* log
   return forward_rows(c, nb * T, tokens, T, ub + offset, -1, logits, d.vocab, hidden, d.d_model, b0, s);
 }
 
-// The wide passes multiply in fp16: their copies of the stream-order weights, made once per model.
-int model_wide_f16(const ssd_model* m) {
-  std::lock_guard<std::mutex> lock(m->wide_mu);
-  if (m->wide_f16) return SSD_OK;
-  auto convert = [&](const FusedGemm& g, int at, FusedGemm* out) -> int {
-    const int64_t elems = (int64_t)(g.n_units / g.KS) * at * ((int64_t)g.KS * kFusedWaves * g.KTW) * 512;
-    void* dst = nullptr;
-    SSD_TRY(m->wide_arena.alloc(&dst, (size_t)elems * 2));
-    SSD_TRY(launch_bf16_to_f16(g.w, (bf16_t*)dst, elems, nullptr));
-    *out = g;
-    out->w = (const bf16_t*)dst;
-    return SSD_OK;
-  };
-  m->wide_layers.resize(m->fused_layers.size());
-  int st = SSD_OK;
-  for (size_t l = 0; l < m->fused_layers.size() && st == SSD_OK; ++l) {
-    const ssd_model::FusedW& F = m->fused_layers[l];
-    ssd_model::FusedW& W = m->wide_layers[l];
-    st = convert(F.qkv, kAtQkv, &W.qkv);
-    if (st == SSD_OK) st = convert(F.o, kAtO, &W.o);
-    if (st == SSD_OK) st = convert(F.gu, kAtGu, &W.gu);
-    if (st == SSD_OK) st = convert(F.down, kAtDown, &W.down);
-  }
-  if (st == SSD_OK) st = convert(m->fused_lm, kAtLm, &m->wide_lm);
-  if (st == SSD_OK && hipDeviceSynchronize() != hipSuccess) { set_error("hipDeviceSynchronize failed"); st = SSD_EHIP; }
-  if (st != SSD_OK) {
-    m->wide_arena.release();
-    m->wide_layers.clear();
-    return st;
-  }
-  m->wide_f16 = true;
-  return SSD_OK;
-}
-
 // Workspace and constant parameters of the fused pass.
 int fused_setup(ssd_ctx* c) {
   const ssd_model* m = c->model;
@@ -639,7 +601,8 @@ int fused_setup(ssd_ctx* c) {
   A((void**)&c->fused_layers_dev, sizeof(FusedLayer) * L * c->B);
   SSD_TRY(st);
   // every workgroup of a persistent launch has to be resident at once
-  p.planes = (c->flags >> 8) & 31;
+  // xn, att, act as one fp16 plane unless two planes are asked for; q, p as asked
+  p.planes = ((c->flags >> 8) & 31) | (c->flags & SSD_CTX_TWO_PLANES ? 0 : 7);
   if (!c->fused_wide && !fused_planes_supported(p.planes)) { set_error("fused pass: plane configuration %d is not compiled in", p.planes); return SSD_EINVAL; }
   if (c->fused_mode == 2) SSD_TRY(fused_check_residency(p.nwg, p.planes, c->kv_pages ? 1 : 0));
   {
@@ -682,16 +645,6 @@ int fused_setup(ssd_ctx* c) {
       F.suffix_k = (bf16_t*)c->suffix_k[l] + (size_t)sq * branch_rows * c->K * kvd;
       F.suffix_v = (bf16_t*)c->suffix_v[l] + (size_t)sq * branch_rows * c->K * kvd;
     }
-  }
-  if (c->fused_wide) {
-    // wide passes take the fp16 copies of the weights (same layout; the launchers read them from this host table)
-    SSD_TRY(model_wide_f16(m));
-    for (int l = 0; l < L; ++l)
-      for (int sq = 0; sq < c->B; ++sq) {
-        FusedLayer& F = host[(size_t)sq * L + l];
-        F.qkv = m->wide_layers[l].qkv; F.o = m->wide_layers[l].o; F.gu = m->wide_layers[l].gu; F.down = m->wide_layers[l].down;
-      }
-    p.lm = m->wide_lm;
   }
   SSD_HIP(hipMemcpy(c->fused_layers_dev, host.data(), sizeof(FusedLayer) * host.size(), hipMemcpyHostToDevice));
   p.layers = c->fused_layers_dev;
@@ -781,7 +734,6 @@ int ssd_model_release_operator_weights(ssd_model* m) {
 
 int ssd_model_destroy(ssd_model* m) {
   if (!m) return SSD_OK;
-  m->wide_arena.release();
   m->arena.release();
   delete m;
   return SSD_OK;
@@ -796,7 +748,7 @@ static int ctx_create(const ssd_model* model, const ssd_round_config* cfg, const
   SSD_CHECK_ARG(cfg->batch >= 1, "batch must be >= 1");
   SSD_CHECK_ARG(cfg->K >= 1 && cfg->K <= SSD_MAX_K, "K must be in 1..%d", SSD_MAX_K);
   SSD_CHECK_ARG(cfg->max_trunk >= 2 * cfg->K + 3, "max_trunk must be at least 2K+3");
-  SSD_CHECK_ARG((cfg->flags & ~(SSD_CTX_PER_OPERATOR | SSD_CTX_FUSED_PHASES | SSD_CTX_NARROW_PASSES | SSD_CTX_ONE_PLANE_ALL)) == 0,
+  SSD_CHECK_ARG((cfg->flags & ~(SSD_CTX_PER_OPERATOR | SSD_CTX_FUSED_PHASES | SSD_CTX_NARROW_PASSES | SSD_CTX_ONE_PLANE_ALL | SSD_CTX_TWO_PLANES)) == 0,
                 "unknown bits in ssd_round_config.flags");
   FanTable fan = {};
   int f_max = 0;

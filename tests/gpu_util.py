@@ -9,20 +9,20 @@ from oracle import ssd_oracle as O
 
 # spec tolerances: relative error of logits / hidden states against the float64 oracle
 TOL = {"bf16": 2e-2, "f32": 1e-4}
-# What the bf16 paths (bf16 weights and KV, fp32 accumulation, activations as head + remainder planes) are measured at
-# against the float64 oracle, with head room of about 2x: a wrongly visible key among thousands, or a lost low-order
-# plane, shows up here long before it reaches the benchmark spec's figure above.  Measured: 1.3e-4 .. 1.8e-3 when both sides
-# start from the same bf16-representable prefix KV (the largest on short prefixes, where the keys the GPU itself rounds
-# to bf16 carry more of the softmax); up to 3.9e-3 when the whole trunk comes from a prefill on the GPU, whose KV is
-# rounded to bf16 while the oracle keeps its own in float64.
-TOL_FUSED_BF16 = 4e-3
+# What the bf16 paths (bf16 weights and KV, fp32 accumulation; between the phases of the fused pass the activations that
+# meet the weights as one fp16 plane, queries and probabilities as two bf16 planes) are measured at against the float64
+# oracle, with head room of about 2x: a wrongly visible key among thousands shows up here long before it reaches the
+# spec figure above.  Measured: up to 2.6e-3 through the 16 layers of the 1B shape when both sides start from the
+# same bf16-representable prefix KV (1.1e-3 with SSD_CTX_TWO_PLANES), less on the 2-layer shapes; up to 3.9e-3 when the
+# whole trunk comes from a prefill on the GPU, whose KV is rounded to bf16 while the oracle keeps its own in float64.
+TOL_FUSED_BF16 = 5e-3
 TOL_BF16_OWN_PREFILL = 8e-3
 # Wide passes (more than 48 rows in one batched forward) carry every activation between phases as ONE plane, in fp16,
 # and multiply fp16 copies of the weights: measured 1.8e-3 (mean) and 2.5e-3 (worst row) through the 16 layers of the 1B
 # shape, so they are held to the bound of the narrow pass after its own prefill.
 TOL_WIDE_BF16 = 8e-3
-# The narrow pass with every activation as one bf16 plane (a measurement option): 8 significant bits per activation,
-# 4e-3 .. 7e-3 on the small shapes (2 layers); only those are tested, against the benchmark spec's figure itself.
+# SSD_CTX_ONE_PLANE_ALL (a measurement option): queries and probabilities as one bf16 plane too, 8 significant bits
+# where the scores and the attention output are formed: 1.1e-2 at the 1B shape.
 TOL_ONE_PLANE_BF16 = 2e-2
 # decisions that rest on floating point are compared only where the oracle's own margin exceeds this
 MARGIN = 1e-4

@@ -60,7 +60,7 @@ def _run_round_parity(B, shape, batch, P, K, F, seed, synthetic_kv, temperature=
     assert B.ssd_ctx_fanout(ctx) == fan
     which = B.ssd_ctx_views(ctx).fused_pass
     wide = B.ssd_ctx_views(ctx).pass_rows > 48
-    one_plane = bool(flags & B.SSD_CTX_ONE_PLANE_ALL)
+    one_plane = (flags & B.SSD_CTX_ONE_PLANE_ALL) == B.SSD_CTX_ONE_PLANE_ALL
     if shape.dtype == "bf16":
         tol = min(tol, TOL_ONE_PLANE_BF16 if one_plane and not wide else
                   TOL_WIDE_BF16 if wide else (TOL_FUSED_BF16 if synthetic_kv else TOL_BF16_OWN_PREFILL))
@@ -176,19 +176,22 @@ def test_small_bf16_fused_pass_group_of_two_and_long_lookahead(B):
     _run_round_parity(B, SMALL_BF16, batch=1, P=45, K=8, F=2, seed=13, synthetic_kv=False)
 
 
-def test_small_bf16_narrow_pass_with_one_plane_per_activation(B):
-    """SSD_CTX_ONE_PLANE_ALL: every tensor the narrow pass hands from phase to phase travels as one bf16 plane (the plain
-    bf16 mixed precision of the paper's system, App. B) instead of head + remainder; same round, the bound of that
-    arithmetic.  A combination that is not compiled in is refused at creation."""
-    _, forced, _, worst = _run_round_parity(B, SMALL_BF16, batch=2, P=203, K=3, F=3, seed=7, synthetic_kv=True,
-                                            flags=B.SSD_CTX_ONE_PLANE_ALL)
-    _, _, _, two = _run_round_parity(B, SMALL_BF16, batch=2, P=203, K=3, F=3, seed=7, synthetic_kv=True)
-    print(f"[planes] worst error one plane {worst:.3e}, two planes {two:.3e}", flush=True)
-    assert worst > two                       # the flag did change the arithmetic
+def test_small_bf16_narrow_pass_plane_configurations(B):
+    """The precision of what the narrow pass hands from phase to phase: default (xn, att, act one fp16 plane; q, p two
+    bf16 planes), SSD_CTX_TWO_PLANES (head + remainder everywhere), SSD_CTX_ONE_PLANE_ALL (q and p one bf16 plane too, the
+    plain bf16 mixed precision of the paper's system, App. B): same round, each within its bound, ordered as their
+    significant bits say.  A combination that is not compiled in is refused at creation."""
+    _, _, _, one = _run_round_parity(B, SMALL_BF16, batch=2, P=203, K=3, F=3, seed=7, synthetic_kv=True,
+                                     flags=B.SSD_CTX_ONE_PLANE_ALL)
+    _, _, _, dflt = _run_round_parity(B, SMALL_BF16, batch=2, P=203, K=3, F=3, seed=7, synthetic_kv=True)
+    _, _, _, two = _run_round_parity(B, SMALL_BF16, batch=2, P=203, K=3, F=3, seed=7, synthetic_kv=True,
+                                     flags=B.SSD_CTX_TWO_PLANES)
+    print(f"[planes] worst error: all one plane {one:.3e}, default {dflt:.3e}, two planes {two:.3e}", flush=True)
+    assert one > dflt > two                  # the flags did change the arithmetic
     model = B.ssd_model_create(SMALL_BF16, I.make_weights(SMALL_BF16, 7))
     try:
         with pytest.raises(B.SsdError):
-            B.ssd_ctx_create(model, 2, 3, 3, 256, 0x100)          # SSD_CTX_ONE_PLANE_XN alone
+            B.ssd_ctx_create(model, 2, 3, 3, 256, B.SSD_CTX_TWO_PLANES | 0x100)      # only xn as one plane
     finally:
         B.ssd_model_destroy(model)
 
@@ -227,7 +230,7 @@ def test_fused_pass_phase_by_phase_equals_persistent(B):
 def test_wide_passes_agree_with_narrow_passes_and_repeat_bit_for_bit(B):
     """75 branch rows (3 sequences of 25): more than a narrow pass holds, so the context is served by wide passes (up to
     384 rows, one stream of the weights per step, one launch per phase).  The same round as narrow passes of whole
-    sequences agrees to rounding (other summation order, two bf16 planes), and a second wide round gives the same bits
+    sequences agrees to rounding (other summation order), and a second wide round gives the same bits
     (every sum is taken in a fixed order)."""
     shape, seed, nb, P, K, F = SMALL_BF16, 23, 3, 50, 4, 5
     w = I.make_weights(shape, seed)
