@@ -120,8 +120,9 @@ enum {
    * against a float64 reference through the 16 layers of the 1B shape: 2.6e-3 (worst row).
    * SSD_CTX_TWO_PLANES: every tensor two planes unless its ONE_PLANE bit is set (alone: 1.1e-3, at +4 % time on a 24-row
    * step and +11 % on a 48-row step at 8192 keys).  ONE_PLANE_Q / ONE_PLANE_P: that tensor as one bf16 plane too (with
-   * both, = ONE_PLANE_ALL: 1.1e-2, no faster than the default; a measurement aid).  Wide passes always run the default.
-   * EINVAL for a combination that is not compiled in (compiled: the default, TWO_PLANES alone, ONE_PLANE_ALL). */
+   * both, = ONE_PLANE_ALL: 1.1e-2 and no faster than the default).  Wide passes always carry xn, att, act as one plane.
+   * EINVAL for a combination the narrow pass is not compiled for: compiled are the default and TWO_PLANES alone; others
+   * are a build option (-DSSD_FUSED_PLANE_MASKS="X(0) X(7) X(31)", bit i of a mask = tensor i as one plane). */
   SSD_CTX_ONE_PLANE_XN = 0x100, SSD_CTX_ONE_PLANE_ATT = 0x200, SSD_CTX_ONE_PLANE_ACT = 0x400,
   SSD_CTX_ONE_PLANE_Q = 0x800, SSD_CTX_ONE_PLANE_P = 0x1000, SSD_CTX_ONE_PLANE_ALL = 0x1f00,
   SSD_CTX_TWO_PLANES = 0x2000

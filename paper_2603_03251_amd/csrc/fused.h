@@ -80,6 +80,8 @@ struct FusedParams {
   int64_t fix_stride;
   float* part_o;   // [L][B][Hkv][NS][QT*16][64]  partial softmaxes of the key splits (NS > 1 only)
   float* part_ml;  // [L][B][Hkv][NS][QT*16][2]
+  unsigned* arrivals;       // [L][arrivals_stride]: per (sequence, KV head, query tile) the key splits that have stored their
+  int64_t arrivals_stride;  // partial softmax in this pass; zero between passes (the last arrival merges and resets)
   int64_t part_layer_stride;               // in (q-row) entries
   float* logits;   int64_t logits_ld;      // may be null
   float* hidden;   int64_t hidden_ld;      // may be null

@@ -675,10 +675,12 @@ __device__ __forceinline__ f32x4 score_tile(bf16x8 k0, bf16x8 k1, const Bf8 qh[2
 // fresh-key sources) is issued up front; loop counts come from the host's bound on the visible trunk, the true
 // visibility only masks.  The 8 partial softmaxes meet in LDS; with one split the result goes straight to the
 // o-projection's operand planes, otherwise to the partial buffers of the merge phase.
-template <int MT, int MP, int NPQ, int NPP, int NPT, bool PG>
+// SM: the unit that arrives last of a tile's key splits merges them (a kernel of its own for passes with several splits:
+// compiled into the one-split kernel, the merge costs its linear layers 1 % through their register allocation).
+template <int MT, int MP, int NPQ, int NPP, int NPT, bool PG, bool SM>
 __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
-                                          const float* r_s, f32x4* lds, bf16_t* att_out, float* part_o, float* part_ml, int ph,
-                                          Grid* wait_on) {
+                                          const float* r_s, f32x4* lds, bf16_t* att_out, float* part_o, float* part_ml,
+                                          unsigned* arrivals, int ph, Grid* wait_on) {
   const ThreadIds ids = fresh_thread_ids();
   const int lane = ids.lane, wave = ids.wave;
   const int li = lane & 15, g4 = lane >> 4;
@@ -928,6 +930,20 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
   st.l_run = sum_over_rows(st.l_run);
   stamp(p, ph, 7);
 
+  // the o-projection's operand planes: dims 4 dq .. 4 dq + 3 of query row qrow of this unit's tile
+  auto write_att = [&](int qrow, int dq, f32x4 x4) {
+    const int mm = b * p.R + qrow / p.G;
+    const int k = (hk * p.G + qrow % p.G) * 64 + dq * 4;
+    bf16_t hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      hi[i] = to_f16(x4[i]);
+      lo[i] = to_f16(x4[i] - f16_to_f32(hi[i]));
+    }
+    const int64_t off = b_off<MT>(k, mm);
+    st_u64(att_out + off, pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
+    if (NPT == 2) st_u64(att_out + (int64_t)MP * p.qd + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
+  };
   // ---- the 8 wavefronts' partial softmaxes meet in LDS: acc [wave][dt][lane], (m, l) [wave][16]
   float* ml = (float*)(lds + kFusedWaves * 4 * 64);
 #pragma unroll
@@ -954,24 +970,27 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
     const int qrow = qt * 16 + q;
     if (qrow < RG) {
       if (p.NS == 1) {
-        const int mm = b * p.R + qrow / p.G;
-        const int k = (hk * p.G + qrow % p.G) * 64 + dq * 4;
         const float inv = 1.0f / lsum;
-        bf16_t hi[4], lo[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float x = o[i] * inv;
-          hi[i] = to_f16(x);
-          lo[i] = to_f16(x - f16_to_f32(hi[i]));
-        }
-        const int64_t off = b_off<MT>(k, mm);
-        st_u64(att_out + off, pack_bf16x4(hi[0], hi[1], hi[2], hi[3]));
-        if (NPT == 2) st_u64(att_out + (int64_t)MP * p.qd + off, pack_bf16x4(lo[0], lo[1], lo[2], lo[3]));
+        write_att(qrow, dq, o * inv);
       } else {
         const int64_t pb = ((int64_t)(b * p.Hkv + hk) * p.NS + s) * (p.QT * 16) + qrow;
         if (dq == 0) st_u64(part_ml + pb * 2, pack_f32x2(mmax, lsum));
         st_f32x4(part_o + pb * 64 + dq * 4, o);
       }
+    }
+  }
+  // ---- several key splits: this unit's arrival is counted once its partial softmax has left (write-through stores,
+  // vmcnt 0); the count comes back while the fresh keys are appended below
+  int* last_s = (int*)(vf_s + 64 * 72);
+  if (SM && p.NS > 1) {
+    __builtin_amdgcn_s_waitcnt(0);
+    wg_barrier();
+    if (threadIdx.x == 0) {
+      unsigned* cnt = arrivals + (b * p.Hkv + hk) * p.QT + qt;
+      const unsigned old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int is_last = old + 1 == (unsigned)p.NS;
+      if (is_last) __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next pass
+      *last_s = is_last;
     }
   }
   // ---- append the keys and values computed in this pass for later passes, from their LDS copies: the row's private
@@ -997,6 +1016,47 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
         gbf16* vcol = (gbf16*)L.trunk_vt + bb + (x.q8 * 8) * 32 + (fresh_slot & 31);
 #pragma unroll
         for (int e = 0; e < 8; ++e) vcol[e * 32] = vv.u[e];
+      }
+    }
+  }
+  // ---- the unit that arrived last of a tile's NS splits merges them, in split order whoever it is: no unit ever waits
+  // for another, and the merge phase with its grid barrier is gone.  Its loads are agent-scope (coherent across the
+  // XCDs); the other splits' stores were complete before their arrivals were counted.
+  if (SM && p.NS > 1) {
+    wg_barrier();
+    if (*last_s != 0 && threadIdx.x < 256) {
+      const int q = threadIdx.x & 15, dq = threadIdx.x >> 4;
+      const int qrow = qt * 16 + q;
+      if (qrow < RG) {
+        constexpr int kMaxSplits = 16;
+        const int64_t pb0 = ((int64_t)(b * p.Hkv + hk) * p.NS) * (p.QT * 16) + qrow, pstep = p.QT * 16;
+        uint64_t mlv[kMaxSplits];
+#pragma unroll
+        for (int t = 0; t < kMaxSplits; ++t)
+          mlv[t] = __hip_atomic_load((const uint64_t*)(part_ml + (pb0 + (t < p.NS ? t : 0) * pstep) * 2), __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT);
+        float mmax = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < kMaxSplits; ++t) mmax = t < p.NS ? fmaxf(mmax, __uint_as_float((unsigned)mlv[t])) : mmax;
+        const float m_use = mmax == -INFINITY ? 0.f : mmax;
+        float lsum = 0.f;
+        f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t0 = 0; t0 < kMaxSplits; t0 += 4) {
+          if (t0 < p.NS) {
+            f32x4 ov[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ov[t] = ld_f32x4_coherent(part_o + (pb0 + (t0 + t < p.NS ? t0 + t : 0) * pstep) * 64 + dq * 4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+              if (t0 + t < p.NS) {
+                const float wgt = exp2_fast(__uint_as_float((unsigned)mlv[t0 + t]) - m_use);
+                lsum += wgt * __uint_as_float((unsigned)(mlv[t0 + t] >> 32));
+                o += ov[t] * wgt;
+              }
+          }
+        }
+        write_att(qrow, dq, o * (1.0f / lsum));
       }
     }
   }
@@ -1934,7 +1994,7 @@ template <int MT, bool DEEP, int NP> struct Depth {
   static constexpr int a4 = !DEEP ? 2 : (MT * NP > 4 ? 2 : 4);   // four feature tiles per unit
 };
 
-template <int MT, bool DEEP, class PL, bool PG>
+template <int MT, bool DEEP, class PL, bool PG, bool SM>
 __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int first, int last, int persistent) {
   constexpr int MP = kFusedMaxRows;
   extern __shared__ f32x4 red[];
@@ -1951,7 +2011,8 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
   const int lm_phase = fused_last_phase(p.L);
 
   for (int ph = first; ph <= last; ++ph) {
-    if (p.NS == 1 && ph > 0 && ph < lm_phase && (ph - 1) % 6 == 2) continue;
+    // the merge phase: none with one key split, and none where the attention units merge their splits themselves
+    if ((SM || p.NS == 1) && ph > 0 && ph < lm_phase && (ph - 1) % 6 == 2) continue;
     const bool do_wait = persistent && ph > first;
     stamp(p, ph, 0);
     if (ph == 0 && p.prof && threadIdx.x == 0) {
@@ -2050,7 +2111,8 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       // a workgroup with a unit waits for the grid inside its first unit, after requesting that unit's stored keys
       bool waited = !do_wait;
       for (int u = p.nwg - 1 - (int)blockIdx.x; u < p.n_attn_units; u += p.nwg) {
-        if (!attn_unit<MT, MP, PL::q, PL::p, PL::att, PG>(p, L, qkv, u, r_s, red, att, part_o, part_ml, ph, waited ? nullptr : &grid)) return;
+        if (!attn_unit<MT, MP, PL::q, PL::p, PL::att, PG, SM>(p, L, qkv, u, r_s, red, att, part_o, part_ml,
+                                                           p.arrivals + (int64_t)l * p.arrivals_stride, ph, waited ? nullptr : &grid)) return;
         waited = true;
       }
       if (!waited) {
@@ -2128,11 +2190,11 @@ __global__ void copy_kv_fused_kernel(bf16_t* trunk_k, bf16_t* trunk_vt, const bf
 
 constexpr size_t kFusedLdsBytes = 96 * 1024;   // reduction tiles (<= 8 wavefronts x 12 tiles x 1 KiB); also keeps one workgroup per CU
 
-template <int MT, bool DEEP, class PL, bool PG>
-int check_residency_mt(int nwg, int cus) {
-  SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL, PG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
+template <int MT, bool DEEP, class PL, bool PG, bool SM>
+int check_residency_sm(int nwg, int cus) {
+  SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL, PG, SM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBytes));
   int per_cu = 0;
-  SSD_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fused_kernel<MT, DEEP, PL, PG>, kFusedThreads, kFusedLdsBytes));
+  SSD_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fused_kernel<MT, DEEP, PL, PG, SM>, kFusedThreads, kFusedLdsBytes));
   SSD_CHECK_ARG((int64_t)per_cu * cus >= nwg,
                 "fused pass: %d workgroups cannot be resident at once (%d per compute unit x %d compute units): the grid barrier "
                 "would never complete", nwg, per_cu, cus);
@@ -2140,23 +2202,38 @@ int check_residency_mt(int nwg, int cus) {
 }
 
 template <int MT, bool DEEP, class PL, bool PG>
-int launch_mt(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
+int check_residency_mt(int nwg, int cus) {
+  SSD_TRY((check_residency_sm<MT, DEEP, PL, PG, false>(nwg, cus)));
+  return check_residency_sm<MT, DEEP, PL, PG, true>(nwg, cus);
+}
+
+template <int MT, bool DEEP, class PL, bool PG, bool SM>
+int launch_sm(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
   const size_t lds = kFusedLdsBytes;
   static bool configured = false;
   if (!configured) {
-    SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL, PG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    SSD_HIP(hipFuncSetAttribute((const void*)fused_kernel<MT, DEEP, PL, PG, SM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     configured = true;
   }
   if (persistent) {
-    fused_kernel<MT, DEEP, PL, PG><<<p.nwg, kFusedThreads, lds, s>>>(p, first, last, 1);
+    fused_kernel<MT, DEEP, PL, PG, SM><<<p.nwg, kFusedThreads, lds, s>>>(p, first, last, 1);
     SSD_HIP(hipGetLastError());
   } else {
+    const int lm_phase = fused_last_phase(p.L);
     for (int ph = first; ph <= last; ++ph) {
-      fused_kernel<MT, DEEP, PL, PG><<<p.nwg, kFusedThreads, lds, s>>>(p, ph, ph, 0);
+      if ((SM || p.NS == 1) && ph > 0 && ph < lm_phase && (ph - 1) % 6 == 2) continue;   // no merge phase
+      fused_kernel<MT, DEEP, PL, PG, SM><<<p.nwg, kFusedThreads, lds, s>>>(p, ph, ph, 0);
       SSD_HIP(hipGetLastError());
     }
   }
   return SSD_OK;
+}
+
+// Passes with several key splits take the kernel whose attention units merge them.
+template <int MT, bool DEEP, class PL, bool PG>
+int launch_mt(const FusedParams& p, int first, int last, int persistent, hipStream_t s) {
+  if (p.NS > 1) return launch_sm<MT, DEEP, PL, PG, true>(p, first, last, persistent, s);
+  return launch_sm<MT, DEEP, PL, PG, false>(p, first, last, persistent, s);
 }
 
 }  // namespace
@@ -2246,7 +2323,7 @@ int fused_grid_size(int* out) {
 // and 8192 keys; the error against a float64 reference goes from 1.1e-3 to 2.6e-3).
 constexpr int kFusedDefaultPlanes = 7;
 #ifndef SSD_FUSED_PLANE_MASKS
-#define SSD_FUSED_PLANE_MASKS X(0) X(7) X(31)
+#define SSD_FUSED_PLANE_MASKS X(0) X(7)
 #endif
 template <int MASK>
 using PlanesOf = Planes<(MASK & 1) ? 1 : 2, (MASK & 2) ? 1 : 2, (MASK & 4) ? 1 : 2, (MASK & 8) ? 1 : 2, (MASK & 16) ? 1 : 2>;
@@ -2425,6 +2502,7 @@ int launch_fused(const FusedParams& p, int first, int last, int persistent, hipS
                     (16 / p.G) * p.SL <= 64,
                 "bad attention split");
   SSD_CHECK_ARG(first >= 0 && last <= fused_last_phase(p.L) && first <= last, "bad phase range");
+  SSD_CHECK_ARG(p.NS <= 16 && (p.NS == 1 || p.arrivals), "fused pass: %d key splits (at most 16, with arrival counters)", p.NS);
   if (p.pages) {
     SSD_CHECK_ARG(p.planes == kFusedDefaultPlanes, "a paged trunk takes the default activation planes only");
     return launch_pl<PlanesOf<kFusedDefaultPlanes>, true>(p, first, last, persistent, s);

@@ -159,6 +159,7 @@ struct ssd_ctx {
   int flags = 0;
   int64_t fused_sync_words = 0; // barrier words, zeroed once (the barrier's epoch carries over from launch to launch)
   int64_t part_entries = 0;    // per-layer capacity of the attention partial buffers, in query rows
+  int part_ns_max = 1;         // key splits they were sized for
   unsigned long long* phase_clocks = nullptr;
   const int32_t* forced_keys = nullptr;
   const int32_t* forced_tokens = nullptr;
@@ -440,12 +441,14 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
     const int pairs = seqs * p.Hkv * (c->fused_wide ? (p.QT + kFusedWideQueryTiles - 1) / kFusedWideQueryTiles : p.QT);
     int best = 1;
     float best_cost = 0.f;
-    const int ns_cap = (c->max_trunk + 2047) / 2048 + 1;   // what the partial-softmax buffers were sized for
+    const int ns_cap = c->part_ns_max;                     // what the partial-softmax buffers were sized for
+    const float merge_cost = c->fused_wide ? 5.0f : 4.0f;  // a phase of its own / the last unit of a tile to arrive (its arrival
+                                                           // count and the other splits' partial results each cost a memory round trip)
     for (int ns = 1; ns <= ns_cap && ns <= 16; ++ns) {
       const int keys = (p_ub + ns - 1) / ns;
       const int blocks = ((keys + 31) / 32 + kFusedWaves - 1) / kFusedWaves;
       const int rounds = (pairs * ns + p.nwg - 1) / p.nwg;
-      const float cost = rounds * (0.9f * blocks + 3.0f) + (ns > 1 ? 5.0f : 0.f);
+      const float cost = rounds * (0.9f * blocks + 3.0f) + (ns > 1 ? merge_cost : 0.f);
       if (ns == 1 || cost < best_cost) { best = ns; best_cost = cost; }
     }
     p.KPU = ((p_ub + best - 1) / best + 31) / 32 * 32;
@@ -582,11 +585,15 @@ int fused_setup(ssd_ctx* c) {
   // attention partials (used only when the trunk is split over several units: more than 2048 visible keys)
   const int r_max = c->rows_per_seq > c->K + 1 ? c->rows_per_seq : c->K + 1;
   const int qt_max = (r_max * p.G + 15) / 16;
-  const int ns_max = (c->max_trunk + 2047) / 2048 + 1;
+  // narrow passes split shorter trunks too (their units merge the splits themselves, at no barrier)
+  const int ns_max = c->fused_wide ? (c->max_trunk + 2047) / 2048 + 1 : std::max((c->max_trunk + 2047) / 2048 + 1, 8);
+  c->part_ns_max = ns_max;
   c->part_entries = (int64_t)p.B * p.Hkv * ns_max * qt_max * 16;
   p.part_layer_stride = c->part_entries;
   A((void**)&p.part_o, (size_t)L * c->part_entries * 64 * 4);
   A((void**)&p.part_ml, (size_t)L * c->part_entries * 2 * 4);
+  p.arrivals_stride = (int64_t)p.B * p.Hkv * qt_max;
+  A((void**)&p.arrivals, (size_t)L * p.arrivals_stride * 4);
   // K-split scratch: per (layer, qkv / o / down) partial tiles.  A word of 0xffffffff means "not written in this
   // launch": filled once here, and the kernel's reader restores it after taking a tile.
   int64_t fix_tiles = 1;   // most (feature tile, slice) pairs of a K-split layer, padding tiles of the last unit included
@@ -618,6 +625,7 @@ int fused_setup(ssd_ctx* c) {
   p.spin_limit = kFusedSpinLimit;
   SSD_TRY(fused_init_barrier(c->fused_bar, 0u, p.nwg));
   SSD_HIP(hipMemset(p.fix_buf, 0xff, (size_t)L * 3 * p.fix_stride * 4));
+  SSD_HIP(hipMemset(p.arrivals, 0, (size_t)L * p.arrivals_stride * 4));
   p.deep = 1;   // ring depth of the gate/up and LM-head streaming loops
   for (int l = 0; l < L; ++l)
     if (m->fused_layers[l].gu.KTW % 4) p.deep = 0;
@@ -1267,6 +1275,7 @@ int ssd_ctx_recover(ssd_ctx* c) {
   if (c->fused_mode) {
     SSD_TRY(fused_init_barrier(c->fused_bar, 0u, c->fp.nwg));
     SSD_HIP(hipMemset(c->fp.fix_buf, 0xff, (size_t)c->fp.L * 3 * c->fp.fix_stride * 4));
+    SSD_HIP(hipMemset(c->fp.arrivals, 0, (size_t)c->fp.L * c->fp.arrivals_stride * 4));
     *(volatile unsigned*)c->fused_err = 0u;
   }
   c->have_cache = false;
