@@ -486,9 +486,9 @@ def main():
                 if gpu_toks[j, i] != toks_o[i]:
                     break
         dt = time.perf_counter() - t0
-        assert worst < 4e-3, f"the GPU round differs from the oracle: rel err {worst}"
+        assert worst < 5e-3, f"the GPU round differs from the oracle: rel err {worst}"
         out["self_check"] = {"logits_rel_err_vs_oracle": worst, "tokens_equal_where_decided": n_tok_checked,
-                             "branches": n_branches, "bound": 4e-3}
+                             "branches": n_branches, "bound": 5e-3}
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])

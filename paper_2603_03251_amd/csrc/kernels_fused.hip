@@ -23,8 +23,9 @@
 // keys).  Values are stored transposed in the trunk.  The keys computed in this very pass (a branch row's own token
 // and its earlier branch tokens, the other tokens of an extend) are rotated and staged in LDS by the unit and go
 // through the same MFMAs under a per-row visibility test; the unit appends them to the KV store afterwards.  With
-// one key split (up to 2048 visible keys) the unit writes the final output; beyond that a merge phase combines the
-// splits' partial softmaxes.  No mask is ever materialised: a row is (visible trunk length, private suffix length).
+// one key split the unit writes the final output; with several, every unit stores its partial softmax and counts its
+// arrival, and the unit that arrives last of a tile's splits merges them in split order (wide passes: a merge phase).
+// No mask is ever materialised: a row is (visible trunk length, private suffix length).
 #include <type_traits>
 #include <vector>
 
@@ -674,7 +675,7 @@ __device__ __forceinline__ f32x4 score_tile(bf16x8 k0, bf16x8 k1, const Bf8 qh[2
 // every load whose address is pure index arithmetic (row descriptors, the query tile, the first trunk blocks, the
 // fresh-key sources) is issued up front; loop counts come from the host's bound on the visible trunk, the true
 // visibility only masks.  The 8 partial softmaxes meet in LDS; with one split the result goes straight to the
-// o-projection's operand planes, otherwise to the partial buffers of the merge phase.
+// o-projection's operand planes, otherwise to the partial buffers that the last unit of the tile to arrive merges.
 // SM: the unit that arrives last of a tile's key splits merges them (a kernel of its own for passes with several splits:
 // compiled into the one-split kernel, the merge costs its linear layers 1 % through their register allocation).
 template <int MT, int MP, int NPQ, int NPP, int NPT, bool PG, bool SM>
