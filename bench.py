@@ -422,7 +422,9 @@ def main():
         "ms_per_step": ms_per_step,
         "us_per_ssd_round": ms_per_step * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        # bf16 model: weights, KV and the attention MFMAs; the linear layers of the fused passes multiply the same weight
+        # values held as fp16 with fp16 activations (11 significant bits instead of 8); fp32 accumulation everywhere
+        "dtype": "bf16", "linear_layer_mfma_dtype": "f16" if fused else "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: Llama-3.2-1B-shaped bf16 draft, B={nb}, prefix {P}, K={K}, F={F} "
                                f"({r.rows} branch rows), lookahead {K}, {'greedy' if r.temperature == 0 else 'temperature %g' % r.temperature}"
                                f"; verify on a second stream; lookup"
@@ -447,7 +449,7 @@ def main():
                      # against what a plain streaming read reaches on this machine (profiles/microbenchmarks_mi355x.txt)
                      "frac_of_measured_stream_read": achieved / MEASURED_STREAM_READ_GBS},
     }
-    # with hundreds of rows the linear layers approach the MFMA ridge: report their share of the dense bf16 peak too
+    # with hundreds of rows the linear layers approach the MFMA ridge: report their share of the dense 16-bit peak too
     d_, f_, L_ = shape.d_model, shape.d_ffn, shape.n_layers
     qd_, kvd_ = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
     gemm_flops = 2.0 * r.rows * (L_ * ((qd_ + 2 * kvd_) * d_ + d_ * qd_ + 3 * d_ * f_) + V * d_)

@@ -67,10 +67,10 @@ struct FusedParams {
   int is_branch;                           // 1: branch rows (private suffix), 0: extend rows (causal among themselves)
   int suffix_len;                          // branch rows: private positions a row sees, its own token included
   int tv_ub;                               // host bound of the stored trunk keys any row sees (loop counts only)
-  int n_attn_units, n_pair_units;          // B Hkv QT NS attention units; ceil(M Hq / 8) merge units
+  int n_attn_units, n_pair_units;          // B Hkv QT NS attention units; ceil(M Hq / 8) merge units (wide passes)
   // workspace, every address written at most once per launch
   float* h;        // [2L+1][48][d]    residual stream after embed / each o-proj / each down-proj
-  bf16_t* xn;      // [2L+1][2][48*d]  (h * gain of the next norm) as head/remainder planes in B-operand order
+  bf16_t* xn;      // [2L+1][2][48*d]  (h * gain of the next norm) as fp16 planes (head, remainder) in B-operand order
   float* ssq;      // [2L+1][d/16][48] per-feature-tile partial sums of h^2
   float* qkv;      // [L][48][qkvd]    raw projections (before the norm's row scale and the rotary embedding)
   bf16_t* att;     // [L][2][48*qd]    attention output planes, B-operand order
@@ -92,7 +92,7 @@ struct FusedParams {
   unsigned long long* prof;                // optional [phases][kFusedClockSlots][nwg] real-time-counter ticks, or null
   int nwg;
   int deep;                                // 1: every linear layer has a multiple of 4 k-tiles per wavefront and unit
-  int planes;                              // bit i set: tensor i travels as one bf16 plane instead of head + remainder
+  int planes;                              // bit i set: tensor i travels as one 16-bit plane instead of head + remainder
                                            // (0 xn, 1 att, 2 act, 3 q, 4 p); see Planes in kernels_fused.hip
 };
 

@@ -434,7 +434,8 @@ int fused_forward(ssd_ctx* c, int M, const int32_t* tokens, int rows_per_seq, in
   const int n_seq = M / rows_per_seq;
   const int per_pass = c->fused_cap / rows_per_seq;
   // Key splits of the stored trunk: the attention phase lasts (rounds of units over the grid) x (a unit's 32-key blocks
-  // per wavefront + its fixed part), and more than one split adds a merge phase.  Costs in microseconds as measured
+  // per wavefront + its fixed part), and more than one split adds a merge (a phase of its own in wide passes, the last
+  // unit of a tile to arrive in narrow ones).  Costs in microseconds as measured
   // on the 1B shape; the choice only affects speed.
   {
     const int seqs = n_seq < per_pass ? n_seq : (per_pass > 0 ? per_pass : 1);

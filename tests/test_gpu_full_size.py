@@ -140,8 +140,8 @@ def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows, ragg
                 ok = c.margins[kk, j] > 2 * err / (T if T > 0 else 1.0) + 1e-12
                 n_decided += int(ok.sum())
                 assert np.array_equal(toks[b, kk, j][ok], c.tokens[kk, j][ok]), (b, row, toks[b, kk, j], c.tokens[kk, j])
-        # near-ties are rare at the narrow pass's accuracy (almost every token is compared); one bf16 plane leaves about a
-        # third of this random-init model's flat top-2 gaps undecided
+        # near-ties are rare at the fused passes' accuracy (almost every token is compared); the bound of the wide passes
+        # dates from their one-bf16-plane arithmetic, which left a third of this random-init model's flat top-2 gaps undecided
         n_all = len(seqs) * len(rows) * K
         assert n_decided >= (n_all - 2 if r.rows <= 48 else n_all // 2)
         # App. C: the round decoded B K (K+1) F branch tokens and every one is a valid token id
@@ -153,7 +153,7 @@ def test_full_size_round_on_sampled_branches(B, draft_1b, name, seqs, rows, ragg
 
 @pytest.mark.parametrize("name,P,nb,F,T,ragged", [
     ("two key splits", 2100, 1, 4, 0.0, False),
-    ("1b_p8192_f8_t1: merge phase, sampled", 8192, 1, 8, 1.0, False),
+    ("1b_p8192_f8_t1: key splits merged by the last unit, sampled", 8192, 1, 8, 1.0, False),
     ("1b_b16_p2048_f4 with ragged prefixes", 2048, 16, 4, 0.0, True),
 ])
 def test_full_size_rows_are_blind_to_what_they_must_not_see(B, draft_1b, name, P, nb, F, T, ragged):
