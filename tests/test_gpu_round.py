@@ -201,6 +201,37 @@ def test_small_bf16_narrow_pass_plane_configurations(B):
         B.ssd_model_destroy(model)
 
 
+@pytest.mark.parametrize("rows_per_seq", ["narrow", "wide"])
+def test_activations_beyond_the_fp16_range_saturate(B, rows_per_seq):
+    """The fused passes hand activations to their linear layers as fp16: with RMSNorm gains of 1e6 the normalised
+    residual stream and the SwiGLU output lie far beyond +-65504.  They saturate there instead of turning into
+    infinities, so every logit and hidden state of the round stays finite (no comparison with the oracle, which has no
+    such limit: this pins the documented behaviour at the edge of the number format, narrow and wide passes)."""
+    shape, seed, nb, P, K = SMALL_BF16, 41, 2, 40, 3
+    F = 3 if rows_per_seq == "narrow" else 16                  # 2 x 4 x 16 = 128 branch rows: wide passes
+    w = I.make_weights(shape, seed)
+    for name in w:
+        if name.endswith("attn_norm") or name.endswith("mlp_norm"):
+            w[name] = I.round_to_bf16(np.full_like(w[name], 1.0e6))
+    model = B.ssd_model_create(shape, w)
+    ctx = B.ssd_ctx_create(model, nb, K, F, P + 4 * K + 8)
+    try:
+        assert (B.ssd_ctx_views(ctx).pass_rows > 48) == (rows_per_seq == "wide")
+        k, v = I.make_prefix_kv(shape, nb, P, seed)
+        B.ssd_ctx_load_trunk(ctx, kv_to_device(k, "bf16"), kv_to_device(v, "bf16"), P)
+        pending = dev_i32(I.make_pending(shape, nb, K, seed))
+        B.ssd_prespeculate(ctx, pending, dev_f32(np.zeros(nb, np.float32)), seed)
+        out = B.read_cache(ctx)
+        B.ssd_ctx_refresh_bounds(ctx)
+        for name in ("logits", "hidden", "glue_logits"):
+            x = out[name].cpu().numpy()
+            assert np.isfinite(x).all(), name
+            assert np.abs(x).max() > 0, name
+    finally:
+        B.ssd_ctx_destroy(ctx)
+        B.ssd_model_destroy(model)
+
+
 @pytest.mark.parametrize("P", [50, 700])
 def test_fused_pass_phase_by_phase_equals_persistent(B, P):
     # the same pass as one launch per phase (no grid barrier) and as one persistent launch: identical bits, since
