@@ -113,9 +113,12 @@ def print_phase_clocks(B, ctx, one_round, shape):
         ph = [1 + 6 * l + s_ for l in range(L)]
         if (t[ph, 2] == 0).all():                         # the merge phase does not exist with one key split
             continue
-        wait = np.mean([(after[p_] - entry[p_]).mean() for p_ in ph])
-        body_mean = np.mean([(end[p_] - after[p_]).mean() for p_ in ph])
-        body_max = np.mean([(end[p_] - after[p_]).max() for p_ in ph])
+        # (a workgroup that does not wait in a phase records no "after": its work starts at entry.  That is the case in
+        # the attention phase, where only workgroups with a unit wait, for the qkv units of their KV head's group)
+        aft = [np.where(t[p_, 1] > 0, after[p_], entry[p_]) for p_ in ph]
+        wait = np.mean([(a_ - entry[p_]).mean() for a_, p_ in zip(aft, ph)])
+        body_mean = np.mean([(end[p_] - a_).mean() for a_, p_ in zip(aft, ph)])
+        body_max = np.mean([(end[p_] - a_).max() for a_, p_ in zip(aft, ph)])
         w(f"  {names[s_]:19s} wait {wait:6.2f}  body mean {body_mean:6.2f}  body max {body_max:6.2f}\n")
 
 

@@ -80,6 +80,8 @@ struct FusedParams {
   int64_t fix_stride;
   float* part_o;   // [L][B][Hkv][NS][QT*16][64]  partial softmaxes of the key splits (NS > 1 only)
   float* part_ml;  // [L][B][Hkv][NS][QT*16][2]
+  unsigned* qkv_flags;      // [L][8][16]: per layer and KV head, the barrier number at which each qkv unit of that head's
+  int qkv_ug;               // group was stored (group sync of the narrow persistent pass); units per group, 0 = off
   unsigned* arrivals;       // [L][arrivals_stride]: per (sequence, KV head, query tile) the key splits that have stored their
   int64_t arrivals_stride;  // partial softmax in this pass; zero between passes (the last arrival merges and resets)
   int64_t part_layer_stride;               // in (q-row) entries
@@ -130,5 +132,7 @@ bool fused_planes_supported(int planes);
 // 0 for a new context.  The epoch counts on from launch to launch and wraps after 2^32 barriers.
 constexpr int kFusedSyncWords = 2048;
 int fused_init_barrier(unsigned* bar, unsigned epoch0, int nwg);
+// the group-sync flags as that barrier number leaves them (no qkv unit of a coming launch carries it)
+int fused_init_group_flags(unsigned* flags, int n_layers, unsigned epoch0);
 
 }  // namespace ssd

@@ -11,6 +11,9 @@
 // tiles are requested before it waits at the grid barrier in front of the phase; gate/up and the LM head stream
 // weights and activations together through a ring of register chunks whose first chunks go out before the barrier.
 // Weights depend on nothing, so HBM keeps streaming while the barrier and the activation exchange take their latency.
+// One exchange needs less than the grid: an attention unit reads the projections of its KV head's group only, so the
+// qkv units of a group announce themselves in a line of flags that the group's attention units poll (group_wait), and
+// no grid barrier stands between a layer's qkv phase and its attention phase.
 //
 // RMSNorm is split around the linear layer: the producer of the residual stream writes (h * gain) and the
 // per-feature-tile sums of h^2; the consumer multiplies its accumulators by the row's 1/rms.
@@ -213,6 +216,28 @@ __device__ __forceinline__ bool grid_wait(Grid& g) {
   return *g.dead == 0;
 }
 
+// Attention needs less than the whole grid behind it: an attention unit of KV head g reads the projections of that
+// head's group only (its query heads, its key head, its value head), which `n` workgroups own in the qkv phase.  Each of
+// them, once its stores have left, writes the current barrier number into its word of the group's line of flags
+// (one 64-byte line per layer and group); the unit polls that one line.  The grid barrier between the qkv and the
+// attention phase is gone with it; workgroups without a unit pass straight on.  The barrier number is the same on
+// both sides (nobody arrives at a grid barrier in between) and differs from launch to launch.
+__device__ __forceinline__ bool group_wait(Grid& g, const unsigned* line, int n) {
+  if (!g.persistent) return true;
+  if ((int)threadIdx.x < n) {
+    unsigned spins = 0;
+    while (__hip_atomic_load(line + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != g.epoch) {
+      if (++spins > g.spin_limit) {
+        __hip_atomic_store(g.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        *g.dead = 1;
+        break;
+      }
+    }
+  }
+  wg_barrier();
+  return *g.dead == 0;
+}
+
 // 1/rms of every row from the per-feature-tile partial sums of squares: r_s[m] (LDS).  MP: row capacity of the workspace.
 template <int MP>
 __device__ __forceinline__ void compute_row_scales(const FusedParams& p, const float* ssq, float* r_s) {
@@ -297,11 +322,12 @@ struct Chunk {
 template <int AT, int MT, int NP, int D, bool PRE, int MP, int NPX, int NPC>
 __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm g, const bf16_t* bsrc, int64_t bplane,
                                            const int EPI, const EpiArgs& e, Grid& grid, bool do_wait, f32x4* red, float* r_s,
-                                           const float* ssq_in, int ph) {
+                                           const float* ssq_in, int ph, int my_unit) {
+  // my_unit: the unit of this workgroup in a phase of at most one unit per workgroup (PRE), or -1
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int KTW = g.KTW;
   // K-split (g.KS > 1, at most one unit per workgroup): unit u = (feature-tile group u / KS, k-slice u % KS)
-  const int KS = g.KS, ks = KS > 1 ? (int)blockIdx.x % KS : 0;
+  const int KS = g.KS, ks = KS > 1 ? (my_unit < 0 ? 0 : my_unit % KS) : 0;
   const gbf16x8* b_first = (const gbf16x8*)(bsrc + ((int64_t)((ks * kFusedWaves + wave) * KTW) * MT * 64 + lane) * 8);
   const int64_t bplane_v = bplane / 8;
 
@@ -436,14 +462,14 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
     // latency, the activation fetch and the row scales; after the barrier only the activation tiles (L2) are loaded,
     // through a short ring.  KTW is a run-time value: one fully unrolled instance per supported value, so that every
     // register index is static and the compiler counts outstanding loads exactly.
-    if ((int)blockIdx.x >= g.n_units) {
+    if (my_unit < 0 || my_unit >= g.n_units) {
       if (do_wait && !grid_wait(grid)) return false;
       stamp(p, ph, 1);
       if (ssq_in) compute_row_scales<MP>(p, ssq_in, r_s);
       return true;
     }
     constexpr int KMAX = 16 / AT;   // most k-tiles per wavefront and unit (the host checks)
-    const gbf16x8* a_base = (const gbf16x8*)(g.w + (((int64_t)blockIdx.x * kFusedWaves + wave) * KTW * AT) * 512 + lane * 8);
+    const gbf16x8* a_base = (const gbf16x8*)(g.w + (((int64_t)my_unit * kFusedWaves + wave) * KTW * AT) * 512 + lane * 8);
     bf16x8 a[KMAX][AT];
 #pragma unroll
     for (int i = 0; i < KMAX; ++i)
@@ -493,7 +519,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedParams& p, const FusedGemm
     stamp(p, ph, 3);
     if (ssq_in) compute_row_scales<MP>(p, ssq_in, r_s);   // for the next phase (qkv -> attention)
     stamp(p, ph, 4);
-    finish_unit((int)blockIdx.x);
+    finish_unit(my_unit);
     stamp(p, ph, 5);
     return true;
   } else {
@@ -681,7 +707,7 @@ __device__ __forceinline__ f32x4 score_tile(bf16x8 k0, bf16x8 k1, const Bf8 qh[2
 template <int MT, int MP, int NPQ, int NPP, int NPT, bool PG, bool SM>
 __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit,
                                           const float* r_s, f32x4* lds, bf16_t* att_out, float* part_o, float* part_ml,
-                                          unsigned* arrivals, int ph, Grid* wait_on) {
+                                          unsigned* arrivals, int ph, Grid* wait_on, const unsigned* group_flags) {
   const ThreadIds ids = fresh_thread_ids();
   const int lane = ids.lane, wave = ids.wave;
   const int li = lane & 15, g4 = lane >> 4;
@@ -747,7 +773,8 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
   // The stored keys do not depend on the phase before: the first unit of a workgroup requests its ring ahead of the
   // grid barrier.
   if (wait_on) {
-    if (!grid_wait(*wait_on)) return false;
+    // the projections of this KV head's group (group_flags: one line of flags per group), or the whole grid
+    if (!(group_flags ? group_wait(*wait_on, group_flags + hk * 16, p.qkv_ug) : grid_wait(*wait_on))) return false;
     stamp(p, ph, 1);
   }
   stamp(p, ph, 3);
@@ -2014,15 +2041,17 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
   for (int ph = first; ph <= last; ++ph) {
     // the merge phase: none with one key split, and none where the attention units merge their splits themselves
     if ((SM || p.NS == 1) && ph > 0 && ph < lm_phase && (ph - 1) % 6 == 2) continue;
-    const bool do_wait = persistent && ph > first;
+    const int l = ph == 0 ? 0 : (ph == lm_phase ? p.L - 1 : (ph - 1) / 6);
+    const int sub = ph == 0 ? -1 : (ph == lm_phase ? 6 : (ph - 1) % 6);
+    // group sync (see group_wait): no grid barrier between a layer's qkv phase and its attention phase
+    const bool gs = persistent && p.qkv_ug > 0;
+    const bool do_wait = persistent && ph > first && !(gs && sub == 1);
     stamp(p, ph, 0);
     if (ph == 0 && p.prof && threadIdx.x == 0) {
       unsigned xcc;
       asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
       p.prof[(int64_t)7 * p.nwg + blockIdx.x] = xcc;   // phase 0, slot 7: the XCD this workgroup runs on
     }
-    const int l = ph == 0 ? 0 : (ph == lm_phase ? p.L - 1 : (ph - 1) / 6);
-    const int sub = ph == 0 ? -1 : (ph == lm_phase ? 6 : (ph - 1) % 6);
     const FusedLayer L = p.layers[l];
     float* qkv = p.qkv + (int64_t)l * MP * p.qkvd;
     bf16_t* att = p.att + (int64_t)l * 2 * MP * p.qd;
@@ -2035,6 +2064,20 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
     int epi = 0;
     EpiArgs e{};
     const float* ssq_in = nullptr;
+    // the unit of this workgroup in the phases of at most one unit per workgroup: the workgroup's index, or, with group
+    // sync, the qkv units of KV head gq's group (2 G for its query heads, 2 for its keys, 2 for its values, 32
+    // features each) on workgroups 7 - gq, 15 - gq, ..: the XCD on which that head's attention units run
+    int my_unit = (int)blockIdx.x;
+    int qkv_flag = -1;    // word of the flags this workgroup sets after its qkv unit
+    if (gs && sub == 0) {
+      const int gq = 7 - ((int)blockIdx.x & 7), jj = (int)blockIdx.x >> 3;
+      my_unit = -1;
+      if (gq < p.Hkv && jj < p.qkv_ug) {
+        const int nq = 2 * p.G;
+        my_unit = jj < nq ? gq * nq + jj : (jj < nq + 2 ? 2 * p.Hq + 2 * gq + (jj - nq) : 2 * p.Hq + 2 * p.Hkv + 2 * gq + (jj - nq - 2));
+        qkv_flag = (l * 8 + gq) * 16 + jj;
+      }
+    }
     // K-split scratch of this phase instance (sub 0, 3, 5 -> slot 0, 1, 2)
     const int fix_slot = l * 3 + (sub == 0 ? 0 : (sub == 3 ? 1 : 2));
     e.fix_buf = p.fix_buf + (int64_t)fix_slot * p.fix_stride;
@@ -2087,15 +2130,18 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       // has to stay resident in the instruction cache across the layers)
       bool ok;
       if constexpr (PL::xn == PL::att && PL::xn == PL::act) {
-        ok = gemm_phase<kAtQkv, MT, PL::xn, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
+        ok = gemm_phase<kAtQkv, MT, PL::xn, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph, my_unit);
       } else {
-        if (sub == 0) ok = gemm_phase<kAtQkv, MT, PL::xn, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
-        else if (sub == 3) ok = gemm_phase<kAtQkv, MT, PL::att, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
-        else ok = gemm_phase<kAtQkv, MT, PL::act, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
+        if (sub == 0) ok = gemm_phase<kAtQkv, MT, PL::xn, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph, my_unit);
+        else if (sub == 3) ok = gemm_phase<kAtQkv, MT, PL::att, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph, my_unit);
+        else ok = gemm_phase<kAtQkv, MT, PL::act, 2, true, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph, my_unit);
       }
       if (!ok) return;
+      // (the unit's stores have left: it ended with a drain and a workgroup barrier)
+      if (qkv_flag >= 0 && threadIdx.x == 0)
+        __hip_atomic_store(p.qkv_flags + qkv_flag, grid.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     } else if (sub == 4 || sub == 6) {
-      const bool ok = gemm_phase<4, MT, PL::xn, Depth<MT, DEEP, PL::xn>::a4, false, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph);
+      const bool ok = gemm_phase<4, MT, PL::xn, Depth<MT, DEEP, PL::xn>::a4, false, MP, PL::xn, PL::act>(p, g, bsrc, bplane, epi, e, grid, do_wait, red, r_s, ssq_in, ph, my_unit);
       if (!ok) return;
       if (sub == 6 && p.hidden) {
         // final-norm hidden states (the row scales are in LDS)
@@ -2110,13 +2156,15 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       // the qkv phase left this layer's row scales in LDS; a launch that starts here computes them itself
       if (ph == first) compute_row_scales<MP>(p, p.ssq + (int64_t)(2 * l) * ssq_stride, r_s);
       // a workgroup with a unit waits for the grid inside its first unit, after requesting that unit's stored keys
-      bool waited = !do_wait;
+      const bool group = gs && ph > first;           // wait for the unit's group instead of the grid
+      bool waited = !(do_wait || group);
       for (int u = p.nwg - 1 - (int)blockIdx.x; u < p.n_attn_units; u += p.nwg) {
         if (!attn_unit<MT, MP, PL::q, PL::p, PL::att, PG, SM>(p, L, qkv, u, r_s, red, att, part_o, part_ml,
-                                                           p.arrivals + (int64_t)l * p.arrivals_stride, ph, waited ? nullptr : &grid)) return;
+                                                           p.arrivals + (int64_t)l * p.arrivals_stride, ph, waited ? nullptr : &grid,
+                                                           group ? p.qkv_flags + l * 128 : nullptr)) return;
         waited = true;
       }
-      if (!waited) {
+      if (!waited && !group) {
         if (!grid_wait(grid)) return;
         stamp(p, ph, 1);
       }
@@ -2130,7 +2178,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(FusedParams p, int
       for (int u = blockIdx.x; u < p.n_pair_units; u += p.nwg) attn_merge_unit<MT, MP, PL::att>(p, u, part_o, part_ml, att);
     }
     stamp(p, ph, 2);
-    if (ph < last) grid_arrive(grid);
+    if (ph < last && !(gs && sub == 0)) grid_arrive(grid);
   }
   // every workgroup read the word before the first barrier of this launch, which workgroup 0 has passed by now
   if (persistent && blockIdx.x == 0 && threadIdx.x == 0) p.bar[kBarEpochWord] = grid.epoch;
@@ -2301,6 +2349,12 @@ int fused_init_barrier(unsigned* bar, unsigned epoch0, int nwg) {
   }
   w[kBarEpochWord] = epoch0;
   SSD_HIP(hipMemcpy(bar, w.data(), w.size() * sizeof(unsigned), hipMemcpyHostToDevice));
+  return SSD_OK;
+}
+
+int fused_init_group_flags(unsigned* flags, int n_layers, unsigned epoch0) {
+  std::vector<unsigned> w((size_t)n_layers * 128, epoch0);
+  SSD_HIP(hipMemcpy(flags, w.data(), w.size() * sizeof(unsigned), hipMemcpyHostToDevice));
   return SSD_OK;
 }
 
@@ -2504,6 +2558,9 @@ int launch_fused(const FusedParams& p, int first, int last, int persistent, hipS
                 "bad attention split");
   SSD_CHECK_ARG(first >= 0 && last <= fused_last_phase(p.L) && first <= last, "bad phase range");
   SSD_CHECK_ARG(p.NS <= 16 && (p.NS == 1 || p.arrivals), "fused pass: %d key splits (at most 16, with arrival counters)", p.NS);
+  SSD_CHECK_ARG(p.qkv_ug == 0 || (p.qkv_flags && p.qkv_ug <= 16 && p.qkv_ug == 2 * p.G + 4 && p.Hkv <= 8 && 8 % p.Hkv == 0 &&
+                                  8 * p.qkv_ug <= p.nwg && (!persistent || first == 0)),
+                "fused pass: group sync does not fit this shape or phase range");
   if (p.pages) {
     SSD_CHECK_ARG(p.planes == kFusedDefaultPlanes, "a paged trunk takes the default activation planes only");
     return launch_pl<PlanesOf<kFusedDefaultPlanes>, true>(p, first, last, persistent, s);

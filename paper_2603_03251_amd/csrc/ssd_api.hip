@@ -595,6 +595,7 @@ int fused_setup(ssd_ctx* c) {
   A((void**)&p.part_ml, (size_t)L * c->part_entries * 2 * 4);
   p.arrivals_stride = (int64_t)p.B * p.Hkv * qt_max;
   A((void**)&p.arrivals, (size_t)L * p.arrivals_stride * 4);
+  A((void**)&p.qkv_flags, (size_t)L * 128 * 4);
   // K-split scratch: per (layer, qkv / o / down) partial tiles.  A word of 0xffffffff means "not written in this
   // launch": filled once here, and the kernel's reader restores it after taking a tile.
   int64_t fix_tiles = 1;   // most (feature tile, slice) pairs of a K-split layer, padding tiles of the last unit included
@@ -625,8 +626,19 @@ int fused_setup(ssd_ctx* c) {
   p.err = c->fused_err;
   p.spin_limit = kFusedSpinLimit;
   SSD_TRY(fused_init_barrier(c->fused_bar, 0u, p.nwg));
+  SSD_TRY(fused_init_group_flags(p.qkv_flags, L, 0u));
   SSD_HIP(hipMemset(p.fix_buf, 0xff, (size_t)L * 3 * p.fix_stride * 4));
   SSD_HIP(hipMemset(p.arrivals, 0, (size_t)L * p.arrivals_stride * 4));
+  // Group sync of the narrow persistent pass (no grid barrier between qkv and attention): the qkv units of a KV head's
+  // group (2 G + 2 + 2 units of 32 features) go to workgroups of the XCD that head's attention units run on
+  p.qkv_ug = 0;
+  {
+    const int ug = 2 * p.G + 4;
+    bool fits = c->fused_mode == 2 && !c->fused_wide && p.Hkv <= 8 && 8 % p.Hkv == 0 && ug <= 16 && 8 * ug <= p.nwg;
+    for (int l = 0; l < L && fits; ++l)
+      fits = m->fused_layers[l].qkv.KS == 1 && m->fused_layers[l].qkv.n_units == 2 * p.Hq + 4 * p.Hkv;
+    if (fits) p.qkv_ug = ug;
+  }
   p.deep = 1;   // ring depth of the gate/up and LM-head streaming loops
   for (int l = 0; l < L; ++l)
     if (m->fused_layers[l].gu.KTW % 4) p.deep = 0;
@@ -1275,6 +1287,7 @@ int ssd_ctx_recover(ssd_ctx* c) {
   SSD_HIP(hipDeviceSynchronize());
   if (c->fused_mode) {
     SSD_TRY(fused_init_barrier(c->fused_bar, 0u, c->fp.nwg));
+    SSD_TRY(fused_init_group_flags(c->fp.qkv_flags, c->fp.L, 0u));
     SSD_HIP(hipMemset(c->fp.fix_buf, 0xff, (size_t)c->fp.L * 3 * c->fp.fix_stride * 4));
     SSD_HIP(hipMemset(c->fp.arrivals, 0, (size_t)c->fp.L * c->fp.arrivals_stride * 4));
     *(volatile unsigned*)c->fused_err = 0u;
@@ -1288,6 +1301,7 @@ int ssd_ctx_debug_set(ssd_ctx* c, int32_t what, uint32_t value) {
   if (!c->fused_mode) { set_error("ssd_ctx_debug_set: the context is not served by the fused pass"); return SSD_ESTATE; }
   if (what == SSD_DEBUG_BARRIER_EPOCH) {
     SSD_HIP(hipDeviceSynchronize());
+    SSD_TRY(fused_init_group_flags(c->fp.qkv_flags, c->fp.L, value));
     return fused_init_barrier(c->fused_bar, value, c->fp.nwg);
   }
   if (what == SSD_DEBUG_SPIN_LIMIT) {
