@@ -148,7 +148,10 @@ __device__ __forceinline__ f32x16 mfma32_f16(bf16x8 a, bf16x8 b, f32x16 c) {
 // Optional phase clocks (a measurement aid): [phase][slot][workgroup] ticks of the 100 MHz real-time counter; slot 0
 // phase entry, 1 after the grid barrier, 2 end of the phase's work, 3.. probes inside a phase.
 __device__ __forceinline__ void stamp(const FusedParams& p, int ph, int which) {
-  if (p.prof && threadIdx.x == 0) p.prof[((int64_t)ph * kFusedClockSlots + which) * p.nwg + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
+  // (launches of more workgroups than the grid of the persistent kernel - the attention, merge and hidden-state launches
+  // of a wide pass - record their first p.nwg workgroups: the table has p.nwg columns)
+  if (p.prof && threadIdx.x == 0 && (int)blockIdx.x < p.nwg)
+    p.prof[((int64_t)ph * kFusedClockSlots + which) * p.nwg + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
 }
 
 // Offset of element (row m, input k) in a B-operand-ordered activation plane with MT row tiles:
