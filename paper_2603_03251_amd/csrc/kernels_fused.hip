@@ -2411,11 +2411,17 @@ int launch_wide_gemm_dm(const FusedParams& p, const FusedGemm& g, const bf16_t* 
 
 template <int ATW, int EPI, int D>
 int launch_wide_gemm_d(const FusedParams& p, const FusedGemm& g, const bf16_t* bsrc, const WideEpi& e, hipStream_t s) {
-  // half-size row groups where the full size would leave half of the grid or more without a pair
+  // Row groups as small as still give every pair a workgroup of its own: what bounds these kernels is what one compute
+  // unit pulls (4 KiB of weights + 1 KiB per row tile of the group, per k-tile), and with few rows or few feature tiles
+  // the full-size groups leave most of the grid without a pair while the busy workgroups pull as much as ever.
   const int nq = ATW == 4 ? g.n_units / g.KS : (g.n_units / g.KS) >> 1;
-  const int n_rg = (((p.M + 15) >> 4) + kWideGroup - 1) / kWideGroup;
-  if (EPI == FE_RESID && 2 * nq * n_rg <= p.nwg && ((p.M + 15) >> 4) > kWideGroup / 2)
-    return launch_wide_gemm_dm<ATW, EPI, D, kWideGroup / 2>(p, g, bsrc, e, s);
+  const int tiles = (p.M + 15) >> 4;
+  auto fits = [&](int mtg) { return nq * ((tiles + mtg - 1) / mtg) <= p.nwg; };
+  if constexpr (ATW == 2) {
+    if (fits(1)) return launch_wide_gemm_dm<ATW, EPI, D, 1>(p, g, bsrc, e, s);
+    if (fits(2)) return launch_wide_gemm_dm<ATW, EPI, D, 2>(p, g, bsrc, e, s);
+    if (fits(kWideGroup / 2)) return launch_wide_gemm_dm<ATW, EPI, D, kWideGroup / 2>(p, g, bsrc, e, s);
+  }
   return launch_wide_gemm_dm<ATW, EPI, D, kWideGroup>(p, g, bsrc, e, s);
 }
 
@@ -2473,7 +2479,13 @@ int launch_wide_pl(const FusedParams& p, const FusedLayer* layers_host, int firs
     } else if (sub == 4) {
       const int v = 2 * l + 1;
       e.act_out = act; e.ssq_in = p.ssq + (int64_t)v * ssq_stride;
-      SSD_TRY((launch_wide_gemm_lds<FE_SWIGLU>(p, L.gu, p.xn + (int64_t)v * 2 * h_stride, e, s)));
+      // one row group (up to 96 rows): a workgroup per unit of 4 feature tiles, the reduction dimension over its
+      // wavefronts, instead of 16 feature tiles per workgroup on a quarter of the grid
+      if (((p.M + 15) >> 4) <= kWideGroup && L.gu.n_units <= p.nwg) {
+        SSD_TRY((launch_wide_gemm<4, FE_SWIGLU>(p, L.gu, p.xn + (int64_t)v * 2 * h_stride, e, s)));
+      } else {
+        SSD_TRY((launch_wide_gemm_lds<FE_SWIGLU>(p, L.gu, p.xn + (int64_t)v * 2 * h_stride, e, s)));
+      }
     } else {
       if (sub == 6 && p.logits) {
         const int v = 2 * p.L;
