@@ -1103,7 +1103,7 @@ __device__ __forceinline__ bool attn_unit(const FusedParams& p, const FusedLayer
 constexpr int kMultiFreshKeys = 192;   // LDS room: NQ x (rows per tile x slots per row) for NQ = 3, or the tokens of an extend
 template <int MT, int MP, int NPQ, int NPP, int NQ, bool PG>
 __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const FusedLayer& L, const float* qkv, int unit, f32x4* lds,
-                                                bf16_t* att_out, float* part_o, float* part_ml) {
+                                                bf16_t* att_out, float* part_o, float* part_ml, int ph) {
   const ThreadIds ids = fresh_thread_ids();
   const int lane = ids.lane, wave = ids.wave;
   const int li = lane & 15, g4 = lane >> 4;
@@ -1170,21 +1170,36 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
   };
 #pragma unroll
   for (int i = 0; i < RING; ++i) load_trunk(ring[i], i);   // unconditional (a wavefront without blocks re-reads block 0)
+  stamp(p, ph, 3);
 
   // ---- Q operands of the NQ tiles: dims g4*8..+7 (k-step 0) and 32+g4*8..+7 (k-step 1) of this lane's query rows,
   // rotated and scaled
+  // (the loads of all NQ tiles go out before the first is used: one memory round trip instead of one per tile; the
+  // scheduling barrier keeps the compiler from sinking them back next to their uses)
   int tv[NQ];
   Bf8 qh[NQ][2], ql[NQ][2];
+  RowDesc rdv[NQ];
+  f32x4 qraw[NQ][4], qcsv[NQ][4];
 #pragma unroll
   for (int i = 0; i < NQ; ++i) {
-    const RowDesc rd = p.rows[m[i]];
+    rdv[i] = p.rows[m[i]];
     const int qrc = vq[i] ? qt[i] * 16 + li : RG - 1;
     const int hq = hk * p.G + (qrc & (p.G - 1));
     const gfloat* qp = gq + (int64_t)m[i] * p.qkvd + hq * 64 + g4 * 8;
-    const f32x4 qa0 = *(const gf32x4*)qp, qa1 = *(const gf32x4*)(qp + 4);
-    const f32x4 qb0 = *(const gf32x4*)(qp + 32), qb1 = *(const gf32x4*)(qp + 36);
+    qraw[i][0] = *(const gf32x4*)qp;
+    qraw[i][1] = *(const gf32x4*)(qp + 4);
+    qraw[i][2] = *(const gf32x4*)(qp + 32);
+    qraw[i][3] = *(const gf32x4*)(qp + 36);
     const gfloat* qcs = gcs + ((int64_t)m[i] * 32 + g4 * 8) * 2;
-    const f32x4 qc0 = *(const gf32x4*)qcs, qc1 = *(const gf32x4*)(qcs + 4), qc2 = *(const gf32x4*)(qcs + 8), qc3 = *(const gf32x4*)(qcs + 12);
+#pragma unroll
+    for (int c4 = 0; c4 < 4; ++c4) qcsv[i][c4] = *(const gf32x4*)(qcs + 4 * c4);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const RowDesc rd = rdv[i];
+    const f32x4 qa0 = qraw[i][0], qa1 = qraw[i][1], qb0 = qraw[i][2], qb1 = qraw[i][3];
+    const f32x4 qc0 = qcsv[i][0], qc1 = qcsv[i][1], qc2 = qcsv[i][2], qc3 = qcsv[i][3];
     tv[i] = vq[i] ? trunk_visible(rd, m[i], p.R) : 0;
     const float a[8] = {qa0[0], qa0[1], qa0[2], qa0[3], qa1[0], qa1[1], qa1[2], qa1[3]};
     const float bb[8] = {qb0[0], qb0[1], qb0[2], qb0[3], qb1[0], qb1[1], qb1[2], qb1[3]};
@@ -1202,6 +1217,7 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
     }
   }
 
+  stamp(p, ph, 4);
   // ---- stage the fresh keys in LDS: K rows [kMultiFreshKeys][72] (row padding against bank conflicts), V^T columns
   // [64][kMultiFreshKeys + 8]; item = (key f, rotary quad / 8-dim group q8), one after the other per thread
   constexpr int VS = kMultiFreshKeys + 8;
@@ -1265,6 +1281,7 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
     }
     wg_barrier();
   }
+  stamp(p, ph, 5);
 
   OnlineSoftmax st[NQ];
 #pragma unroll
@@ -1301,6 +1318,7 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
 #pragma unroll
     for (int r = 0; r < RING; ++r) trunk_block(ring[r], i0 + r);
   }
+  stamp(p, ph, 6);
   // ---- fresh blocks continue the round-robin after the trunk blocks
   for (int blk = n_tb + ((wave - n_tb) & (kFusedWaves - 1)); blk < n_tb + n_fb; blk += kFusedWaves) {
     const int f0 = (blk - n_tb) * 32;
@@ -1328,6 +1346,7 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
     }
   }
 
+  stamp(p, ph, 7);
   // ---- the 8 wavefronts' partial softmaxes meet in LDS, one query tile after the other: acc [wave][dt][lane],
   // (m, l) [wave][16]
   float* ml = (float*)(lds + kFusedWaves * 4 * 64);
@@ -1374,6 +1393,7 @@ __device__ __forceinline__ void attn_unit_multi(const FusedParams& p, const Fuse
     }
     wg_barrier();
   }
+  stamp(p, ph, 1);
   // ---- append the keys and values computed in this pass for later passes, from their LDS copies: the row's private
   // suffix slot (branch) or its trunk position (extend)
   if (n_fb > 0) {
@@ -1992,7 +2012,7 @@ __global__ __launch_bounds__(kFusedThreads) void wide_kernel(FusedParams p, int 
     }
   } else if (sub == 1) {
     for (int u = blockIdx.x; u < p.n_attn_units; u += gridDim.x)
-      attn_unit_multi<MTOT, MP, PL::q, PL::p, kWideQueryTiles, PG>(p, L, qkv, u, red, att, part_o, part_ml);
+      attn_unit_multi<MTOT, MP, PL::q, PL::p, kWideQueryTiles, PG>(p, L, qkv, u, red, att, part_o, part_ml, ph);
   } else if (sub == 2) {
     for (int u = blockIdx.x; u < p.n_pair_units; u += gridDim.x) attn_merge_unit<MTOT, MP, 1>(p, u, part_o, part_ml, att);
   } else if (sub == 6 && p.hidden) {
